@@ -1,0 +1,190 @@
+"""CPU oracle for the augmented causal linear attention path (fp64, plain C).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke``
+and by the ``cpu_baseline`` leg of ``bench.py``.  The product package never
+imports it, and it never imports the product package.
+
+The arithmetic lives in ``linattn_oracle.c`` (see its header for the passages
+of the paper each function follows).  This module only builds that file with
+gcc and marshals numpy float64 arrays through ctypes.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "linattn_oracle.c")
+_LIB = os.path.join(_HERE, "liblinattn_oracle.so")
+_lib = None
+
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int)
+
+
+def build(force: bool = False, src: str = _SRC, out: str = _LIB) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over heads, no fast-math)."""
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(src):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+               "-ffp-contract=off", "-Wall", "-Wextra", src, "-o", out, "-lm"]
+        subprocess.run(cmd, check=True)
+    return out
+
+
+def _load(path: str | None = None):
+    global _lib
+    if path is not None:
+        return _declare(ctypes.CDLL(path))
+    if _lib is None:
+        _lib = _declare(ctypes.CDLL(build()))
+    return _lib
+
+
+def _declare(lib):
+    i, f = ctypes.c_int, ctypes.c_double
+    lib.oracle_phi.restype = f
+    lib.oracle_phi.argtypes = [f]
+    lib.oracle_causal_conv.restype = None
+    lib.oracle_causal_conv.argtypes = [i, i, i, i, i, _dp, _dp, _dp, _dp]
+    for name in ("oracle_prefill_quadratic", "oracle_prefill_recurrent"):
+        fn = getattr(lib, name)
+        fn.restype = i
+        fn.argtypes = [i, i, i, i, i, f] + [_dp] * 11
+    lib.oracle_verify.restype = i
+    lib.oracle_verify.argtypes = [i, i, i, i, i, f] + [_dp] * 7 + [_ip, _dp]
+    lib.oracle_decode.restype = i
+    lib.oracle_decode.argtypes = [i, i, i, i, f] + [_dp] * 8
+    lib.oracle_num_threads.restype = i
+    lib.oracle_set_num_threads.argtypes = [i]
+    return lib
+
+
+def _c(a, shape=None):
+    """float64, C-contiguous copy-if-needed; None passes through."""
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {tuple(a.shape)}")
+    return a
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(_dp)
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    _load().oracle_set_num_threads(int(n))
+
+
+def phi(x, lib=None):
+    lib = lib or _load()
+    return np.vectorize(lambda t: lib.oracle_phi(float(t)), otypes=[np.float64])(np.asarray(x, dtype=np.float64))
+
+
+def causal_conv(v, w, hist=None, lib=None):
+    """U[b,h,t,c] = sum_j w[h,c,j] * vext[b,h,t-j,c]; v [B,H,L,d], w [H,d,Kc]."""
+    lib = lib or _load()
+    v = _c(v)
+    B, H, L, d = v.shape
+    w = _c(w)
+    Kc = w.shape[2]
+    w = _c(w, (H, d, Kc))
+    hist = _c(hist, (B, H, Kc - 1, d)) if hist is not None else None
+    u = np.empty_like(v)
+    lib.oracle_causal_conv(B, H, L, d, Kc, _p(v), _p(w), _p(hist), _p(u))
+    return u
+
+
+def _prefill(fname, q, k, v, w, S0, z0, hist0, eps, lib):
+    lib = lib or _load()
+    q = _c(q)
+    B, H, L, d = q.shape
+    k = _c(k, q.shape)
+    v = _c(v, q.shape)
+    w = _c(w)
+    Kc = w.shape[2]
+    w = _c(w, (H, d, Kc))
+    S0 = _c(S0, (B, H, d, d)) if S0 is not None else None
+    z0 = _c(z0, (B, H, d)) if z0 is not None else None
+    hist0 = _c(hist0, (B, H, Kc - 1, d)) if hist0 is not None else None
+    out = np.empty_like(q)
+    S1 = np.empty((B, H, d, d))
+    z1 = np.empty((B, H, d))
+    h1 = np.empty((B, H, Kc - 1, d))
+    rc = getattr(lib, fname)(B, H, L, d, Kc, float(eps), _p(q), _p(k), _p(v), _p(w),
+                             _p(S0), _p(z0), _p(hist0), _p(out), _p(S1), _p(z1), _p(h1))
+    if rc != 0:
+        raise ValueError(f"{fname} rejected its arguments (code {rc})")
+    return out, S1, z1, h1
+
+
+def prefill_quadratic(q, k, v, w, S0=None, z0=None, hist0=None, eps=0.0, lib=None):
+    """Brute-force masked quadratic form.  Returns (out, S, z, hist)."""
+    return _prefill("oracle_prefill_quadratic", q, k, v, w, S0, z0, hist0, eps, lib)
+
+
+def prefill_recurrent(q, k, v, w, S0=None, z0=None, hist0=None, eps=0.0, lib=None):
+    """Token-by-token recurrence.  Returns (out, S, z, hist)."""
+    return _prefill("oracle_prefill_recurrent", q, k, v, w, S0, z0, hist0, eps, lib)
+
+
+def verify(q, k, v, w, S, z, hist, n_commit=None, eps=0.0, lib=None):
+    """kk sequential steps from one state; returns (out, S', z', hist').
+
+    q, k, v: [B,H,kk,d].  n_commit: None (keep all) or int array [B] in 0..kk.
+    The incoming state arrays are not modified.
+    """
+    lib = lib or _load()
+    q = _c(q)
+    B, H, kk, d = q.shape
+    k = _c(k, q.shape)
+    v = _c(v, q.shape)
+    w = _c(w)
+    Kc = w.shape[2]
+    w = _c(w, (H, d, Kc))
+    S = np.array(_c(S, (B, H, d, d)), copy=True)
+    z = np.array(_c(z, (B, H, d)), copy=True)
+    hist = np.array(_c(hist, (B, H, Kc - 1, d)), copy=True)
+    nc = None
+    if n_commit is not None:
+        nc = np.ascontiguousarray(n_commit, dtype=np.int32)
+        if nc.shape != (B,):
+            raise ValueError("n_commit must have shape [B]")
+    out = np.empty_like(q)
+    rc = lib.oracle_verify(B, H, kk, d, Kc, float(eps), _p(q), _p(k), _p(v), _p(w),
+                           _p(S), _p(z), _p(hist),
+                           None if nc is None else nc.ctypes.data_as(_ip), _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_verify rejected its arguments (code {rc})")
+    return out, S, z, hist
+
+
+def decode(q, k, v, w, S, z, hist, eps=0.0, lib=None):
+    """One generated token per head: q, k, v [B,H,1,d]; the state always advances."""
+    lib = lib or _load()
+    q = _c(q)
+    B, H, one, d = q.shape
+    if one != 1:
+        raise ValueError("decode takes exactly one token per head")
+    k = _c(k, q.shape)
+    v = _c(v, q.shape)
+    w = _c(w)
+    Kc = w.shape[2]
+    w = _c(w, (H, d, Kc))
+    S = np.array(_c(S, (B, H, d, d)), copy=True)
+    z = np.array(_c(z, (B, H, d)), copy=True)
+    hist = np.array(_c(hist, (B, H, Kc - 1, d)), copy=True)
+    out = np.empty_like(q)
+    rc = lib.oracle_decode(B, H, d, Kc, float(eps), _p(q), _p(k), _p(v), _p(w),
+                           _p(S), _p(z), _p(hist), _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_decode rejected its arguments (code {rc})")
+    return out, S, z, hist

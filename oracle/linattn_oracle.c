@@ -1,0 +1,306 @@
+/*
+ * linattn_oracle.c -- plain, slow, obviously-correct CPU oracle (fp64).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing in the product path may call, link or
+ * import this file; it exists so that the GPU library has something
+ * independent to be compared with.  It shares no code with the GPU path.
+ *
+ * What it computes, per (batch, head) independently, for a head of dimension
+ * d and a token sequence of length L:
+ *
+ *   causal kernelised linear attention (Sec. 3 "Linear Attentions": the
+ *   similarity is factored as phi(Q) phi(K)^T, which lets the product be
+ *   re-associated as phi(Q) (phi(K)^T V)), restricted so that token t only
+ *   uses tokens i <= t (Sec. 4.1: the query at step t meets the cumulative
+ *   sum over i = 1..t of the key/value products), row-normalised by the
+ *   matching cumulative sum of phi(K), plus a causally masked depthwise
+ *   convolution over the sequence axis of V (Sec. 4.1, "masked DWConv"),
+ *   added to the attention output.
+ *
+ *   Speculative verification (Sec. 4.2): k draft tokens are scored at once
+ *   from one running state; each draft may see the verified past and the
+ *   drafts before it, never a later one, and the convolution window of draft
+ *   j is the verified history followed by drafts <= j (the paper's example:
+ *   kernel 3 at step t1 must cover {t0, t1}).
+ *
+ * Readings where the paper is silent (all are stated in the design notes of
+ * the repository): phi(x) = elu(x)+1; the row normaliser; eps added to the
+ * denominator; out = Y + U with no mixing weight; conv weights [H, d, Kc]
+ * with tap j multiplying v_{t-j}; zero left padding at sequence start.
+ *
+ * Layouts (all contiguous, host memory, double):
+ *   q, k, v, out : [B, H, L, d]          w    : [H, d, Kc]
+ *   S            : [B, H, d, d]  S[i][c] = sum_t phi(k_t)[i] * v_t[c]
+ *   z            : [B, H, d]     z[i]    = sum_t phi(k_t)[i]
+ *   hist         : [B, H, Kc-1, d]  the last Kc-1 value rows, oldest first
+ * NULL for an incoming S/z/hist means zeros (start of a sequence); NULL for an
+ * outgoing one means "not wanted".
+ *
+ * Two prefill forms are given on purpose: the brute-force masked quadratic
+ * form (the definition) and the token-by-token recurrence.  They are written
+ * separately and the tests require them to agree.
+ *
+ * Pins (tests/test_oracle_pins.py): first-token identity, running mean for
+ * K == 0, weighted running mean for Q == 0 and for d == 1, constant V,
+ * linearity in V, exact rational brute force on a tiny case, conv against a
+ * library grouped convolution, the paper's conv-window example, causality
+ * under perturbation, chunk/split invariance, verify == k decode steps.
+ * No function here is "parity unpinned" with respect to those properties; the
+ * paper prints no numeric output of the operator, so there is no printed
+ * value to compare with.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* phi(x) = elu(x) + 1 : x + 1 for x > 0, exp(x) otherwise (continuous at 0). */
+double oracle_phi(double x) { return x > 0.0 ? x + 1.0 : exp(x); }
+
+static double dot(const double *a, const double *b, int n) {
+  double s = 0.0;
+  for (int i = 0; i < n; ++i) s += a[i] * b[i];
+  return s;
+}
+
+/* Row s of the value sequence extended to the left by the history:
+ * s >= 0 -> v[s];  -(Kc-1) <= s < 0 -> hist[Kc-1+s];  nothing else exists. */
+static const double *vext_row(const double *v, const double *hist, int Kc,
+                              int d, int s) {
+  if (s >= 0) return v + (size_t)s * d;
+  if (hist && s >= -(Kc - 1)) return hist + (size_t)(Kc - 1 + s) * d;
+  return NULL; /* zero padding */
+}
+
+/* One head: u[t][c] = sum_{j<Kc} w[c][j] * vext[t-j][c]   (Sec. 4.1) */
+static void conv_head(int L, int d, int Kc, const double *v, const double *w,
+                      const double *hist, double *u) {
+  for (int t = 0; t < L; ++t)
+    for (int c = 0; c < d; ++c) {
+      double acc = 0.0;
+      for (int j = 0; j < Kc; ++j) {
+        const double *row = vext_row(v, hist, Kc, d, t - j);
+        if (row) acc += w[(size_t)c * Kc + j] * row[c];
+      }
+      u[(size_t)t * d + c] = acc;
+    }
+}
+
+/* New history = last Kc-1 rows of (old history ++ first n rows of v). */
+static void hist_after(int n, int d, int Kc, const double *v,
+                       const double *hist_in, double *hist_out) {
+  int Hn = Kc - 1;
+  double *tmp = (double *)malloc(sizeof(double) * (size_t)(Hn > 0 ? Hn : 1) * d);
+  for (int r = 0; r < Hn; ++r) {
+    int s = n - Hn + r; /* index into the extended sequence */
+    const double *row = vext_row(v, hist_in, Kc, d, s);
+    for (int c = 0; c < d; ++c) tmp[(size_t)r * d + c] = row ? row[c] : 0.0;
+  }
+  memcpy(hist_out, tmp, sizeof(double) * (size_t)Hn * d);
+  free(tmp);
+}
+
+void oracle_causal_conv(int B, int H, int L, int d, int Kc, const double *v,
+                        const double *w, const double *hist, double *u) {
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    int h = bh % H;
+    conv_head(L, d, Kc, v + (size_t)bh * L * d, w + (size_t)h * d * Kc,
+              hist ? hist + (size_t)bh * (Kc - 1) * d : NULL,
+              u + (size_t)bh * L * d);
+  }
+}
+
+/* ---- definition: brute-force masked quadratic form, one head ------------ */
+static void quadratic_head(int L, int d, int Kc, double eps, const double *q,
+                           const double *k, const double *v, const double *w,
+                           const double *S0, const double *z0,
+                           const double *hist0, double *out, double *S1,
+                           double *z1, double *hist1) {
+  double *fq = (double *)malloc(sizeof(double) * (size_t)L * d);
+  double *fk = (double *)malloc(sizeof(double) * (size_t)L * d);
+  double *u = (double *)malloc(sizeof(double) * (size_t)L * d);
+  double *num = (double *)malloc(sizeof(double) * (size_t)d);
+  for (size_t e = 0; e < (size_t)L * d; ++e) {
+    fq[e] = oracle_phi(q[e]);
+    fk[e] = oracle_phi(k[e]);
+  }
+  conv_head(L, d, Kc, v, w, hist0, u);
+  for (int t = 0; t < L; ++t) {
+    const double *fqt = fq + (size_t)t * d;
+    double den = eps;
+    for (int c = 0; c < d; ++c) num[c] = 0.0;
+    /* the part that comes from before this call: phi(q_t)^T S0, phi(q_t).z0 */
+    if (S0)
+      for (int i = 0; i < d; ++i)
+        for (int c = 0; c < d; ++c) num[c] += fqt[i] * S0[(size_t)i * d + c];
+    if (z0) den += dot(fqt, z0, d);
+    /* A[t][i] = phi(q_t).phi(k_i) for i <= t, nothing for i > t */
+    for (int i = 0; i <= t; ++i) {
+      double a = dot(fqt, fk + (size_t)i * d, d);
+      den += a;
+      for (int c = 0; c < d; ++c) num[c] += a * v[(size_t)i * d + c];
+    }
+    for (int c = 0; c < d; ++c)
+      out[(size_t)t * d + c] = num[c] / den + u[(size_t)t * d + c];
+  }
+  if (S1) {
+    for (int i = 0; i < d; ++i)
+      for (int c = 0; c < d; ++c) {
+        double s = S0 ? S0[(size_t)i * d + c] : 0.0;
+        for (int t = 0; t < L; ++t)
+          s += fk[(size_t)t * d + i] * v[(size_t)t * d + c];
+        S1[(size_t)i * d + c] = s;
+      }
+  }
+  if (z1) {
+    for (int i = 0; i < d; ++i) {
+      double s = z0 ? z0[i] : 0.0;
+      for (int t = 0; t < L; ++t) s += fk[(size_t)t * d + i];
+      z1[i] = s;
+    }
+  }
+  if (hist1) hist_after(L, d, Kc, v, hist0, hist1);
+  free(fq); free(fk); free(u); free(num);
+}
+
+/* ---- one recurrent step on a mutable head state (Sec. 4.1 cumulative sum):
+ *   S += phi(k) v^T ; z += phi(k) ; Y = S^T phi(q) / (z.phi(q) + eps)
+ *   U from (hist ++ v) ; out = Y + U ; hist <- shifted by one row           */
+static void step_head(int d, int Kc, double eps, const double *q,
+                      const double *k, const double *v, const double *w,
+                      double *S, double *z, double *hist, double *out) {
+  double *fq = (double *)malloc(sizeof(double) * (size_t)d);
+  for (int i = 0; i < d; ++i) {
+    double fk = oracle_phi(k[i]);
+    fq[i] = oracle_phi(q[i]);
+    z[i] += fk;
+    for (int c = 0; c < d; ++c) S[(size_t)i * d + c] += fk * v[c];
+  }
+  double den = dot(fq, z, d) + eps;
+  for (int c = 0; c < d; ++c) {
+    double num = 0.0;
+    for (int i = 0; i < d; ++i) num += fq[i] * S[(size_t)i * d + c];
+    double u = w[(size_t)c * Kc + 0] * v[c];
+    for (int j = 1; j < Kc; ++j) /* tap j looks j rows back: hist row Kc-1-j */
+      u += w[(size_t)c * Kc + j] * hist[(size_t)(Kc - 1 - j) * d + c];
+    out[c] = num / den + u;
+  }
+  for (int r = 0; r + 1 < Kc - 1; ++r)
+    memcpy(hist + (size_t)r * d, hist + (size_t)(r + 1) * d, sizeof(double) * d);
+  if (Kc > 1) memcpy(hist + (size_t)(Kc - 2) * d, v, sizeof(double) * d);
+  free(fq);
+}
+
+static void load_state(int d, int Kc, const double *S0, const double *z0,
+                       const double *h0, double *S, double *z, double *h) {
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d;
+  if (S0) memcpy(S, S0, sizeof(double) * nS); else memset(S, 0, sizeof(double) * nS);
+  if (z0) memcpy(z, z0, sizeof(double) * d); else memset(z, 0, sizeof(double) * d);
+  if (h0) memcpy(h, h0, sizeof(double) * nh); else memset(h, 0, sizeof(double) * nh);
+}
+
+int oracle_prefill_quadratic(int B, int H, int L, int d, int Kc, double eps,
+                             const double *q, const double *k, const double *v,
+                             const double *w, const double *S0,
+                             const double *z0, const double *hist0,
+                             double *out, double *S1, double *z1,
+                             double *hist1) {
+  if (B < 0 || H < 1 || L < 0 || d < 1 || Kc < 1) return 1;
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d;
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    int h = bh % H;
+    size_t o = (size_t)bh * L * d;
+    quadratic_head(L, d, Kc, eps, q + o, k + o, v + o, w + (size_t)h * d * Kc,
+                   S0 ? S0 + bh * nS : NULL, z0 ? z0 + (size_t)bh * d : NULL,
+                   hist0 ? hist0 + bh * nh : NULL, out + o,
+                   S1 ? S1 + bh * nS : NULL, z1 ? z1 + (size_t)bh * d : NULL,
+                   hist1 ? hist1 + bh * nh : NULL);
+  }
+  return 0;
+}
+
+int oracle_prefill_recurrent(int B, int H, int L, int d, int Kc, double eps,
+                             const double *q, const double *k, const double *v,
+                             const double *w, const double *S0,
+                             const double *z0, const double *hist0,
+                             double *out, double *S1, double *z1,
+                             double *hist1) {
+  if (B < 0 || H < 1 || L < 0 || d < 1 || Kc < 1) return 1;
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d;
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    int h = bh % H;
+    size_t o = (size_t)bh * L * d;
+    double *S = (double *)malloc(sizeof(double) * nS);
+    double *z = (double *)malloc(sizeof(double) * (size_t)d);
+    double *hs = (double *)malloc(sizeof(double) * (nh ? nh : 1));
+    load_state(d, Kc, S0 ? S0 + bh * nS : NULL, z0 ? z0 + (size_t)bh * d : NULL,
+               hist0 ? hist0 + bh * nh : NULL, S, z, hs);
+    for (int t = 0; t < L; ++t)
+      step_head(d, Kc, eps, q + o + (size_t)t * d, k + o + (size_t)t * d,
+                v + o + (size_t)t * d, w + (size_t)h * d * Kc, S, z, hs,
+                out + o + (size_t)t * d);
+    if (S1) memcpy(S1 + bh * nS, S, sizeof(double) * nS);
+    if (z1) memcpy(z1 + (size_t)bh * d, z, sizeof(double) * d);
+    if (hist1) memcpy(hist1 + bh * nh, hs, sizeof(double) * nh);
+    free(S); free(z); free(hs);
+  }
+  return 0;
+}
+
+/* Verification of kk draft tokens (Sec. 4.2): defined as kk recurrent steps
+ * taken one after the other from the SAME incoming state; all kk outputs are
+ * produced; the state handed back is the one reached after the first
+ * n_commit[b] steps (drafts beyond that were rejected).  n_commit == NULL
+ * means every draft is kept.  S, z, hist are updated in place. */
+int oracle_verify(int B, int H, int kk, int d, int Kc, double eps,
+                  const double *q, const double *k, const double *v,
+                  const double *w, double *S, double *z, double *hist,
+                  const int *n_commit, double *out) {
+  if (B < 0 || H < 1 || kk < 0 || d < 1 || Kc < 1) return 1;
+  if (n_commit)
+    for (int b = 0; b < B; ++b)
+      if (n_commit[b] < 0 || n_commit[b] > kk) return 2;
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d;
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    int b = bh / H, h = bh % H;
+    int n = n_commit ? n_commit[b] : kk;
+    size_t o = (size_t)bh * kk * d;
+    double *Sw = (double *)malloc(sizeof(double) * nS);
+    double *zw = (double *)malloc(sizeof(double) * (size_t)d);
+    double *hw = (double *)malloc(sizeof(double) * (nh ? nh : 1));
+    load_state(d, Kc, S + bh * nS, z + (size_t)bh * d,
+               nh ? hist + bh * nh : NULL, Sw, zw, hw);
+    for (int j = 0; j < kk; ++j) {
+      step_head(d, Kc, eps, q + o + (size_t)j * d, k + o + (size_t)j * d,
+                v + o + (size_t)j * d, w + (size_t)h * d * Kc, Sw, zw, hw,
+                out + o + (size_t)j * d);
+      if (j + 1 == n) { /* state after the last accepted draft */
+        memcpy(S + bh * nS, Sw, sizeof(double) * nS);
+        memcpy(z + (size_t)bh * d, zw, sizeof(double) * d);
+        if (nh) memcpy(hist + bh * nh, hw, sizeof(double) * nh);
+      }
+    }
+    free(Sw); free(zw); free(hw);
+  }
+  return 0;
+}
+
+/* One generated token: a verification of a single draft that is always kept. */
+int oracle_decode(int B, int H, int d, int Kc, double eps, const double *q,
+                  const double *k, const double *v, const double *w, double *S,
+                  double *z, double *hist, double *out) {
+  return oracle_verify(B, H, 1, d, Kc, eps, q, k, v, w, S, z, hist, NULL, out);
+}
+
+/* Number of threads the parallel loops above will use (for reporting). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+void oracle_set_num_threads(int n) { if (n > 0) omp_set_num_threads(n); }
+#else
+int oracle_num_threads(void) { return 1; }
+void oracle_set_num_threads(int n) { (void)n; }
+#endif

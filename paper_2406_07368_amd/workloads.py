@@ -1,0 +1,108 @@
+"""Seeded synthetic inputs with the shapes of the five workloads.
+
+This module holds none of the method's arithmetic: it only draws random
+numbers and rounds them to the i/o dtype, so that the very same arrays can be
+handed to the GPU library and to whatever it is checked against.
+
+The workloads stand in for the activations of the models the paper measures
+(LLaMA-2-7B: 32 heads of 128; GPT-2-small: 12 heads of 64; group size 64 for
+LLaMA, Sec. 5 "Settings"); no dataset, prompt or trained weight is used.
+
+Recipe: ``numpy.random.default_rng(seed)``; standard normals drawn in the
+fixed order Q, K, V, conv weights; Q, K, V multiplied by ``scale``; conv
+weights multiplied by ``Kc ** -0.5`` (variance 1/Kc); everything cast to
+float32 and Q, K, V rounded once to the i/o dtype (round-to-nearest-even for
+bf16).  Arrays are returned as float32 numpy arrays holding exactly
+representable values of the i/o dtype.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    mode: str          # "prefill" or "verify"
+    B: int
+    H: int
+    L: int             # prefill length, or prefix length for verify workloads
+    d: int
+    io_dtype: str      # "f32" or "bf16"
+    chunk: int
+    conv_k: int
+    scale: float
+    seed: int
+    draft_k: tuple = ()
+
+    def small(self, **kw) -> "Workload":
+        return replace(self, **kw)
+
+
+CONFIGS = {
+    # config 1: tiny all-fp32 prefill, checked against the brute-force quadratic form
+    "cfg1_fp32_tiny": Workload("cfg1_fp32_tiny", "prefill", 1, 4, 256, 64, "f32", 64, 3, 1.0, 1001),
+    # config 2: GPT-2-small-shaped prefill
+    "cfg2_gpt2_small": Workload("cfg2_gpt2_small", "prefill", 4, 12, 1024, 64, "bf16", 64, 3, 1.0, 1002),
+    # config 3: LLaMA-2-7B-shaped layer prefill (inputs scaled by d**-0.5)
+    "cfg3_llama7b_prefill": Workload("cfg3_llama7b_prefill", "prefill", 8, 32, 4096, 128, "bf16", 64, 3,
+                                     128 ** -0.5, 1003),
+    # config 4: decode + speculative verify on a state built from a 2048-token prefix
+    "cfg4_llama7b_verify": Workload("cfg4_llama7b_verify", "verify", 32, 32, 2048, 128, "bf16", 64, 3, 1.0,
+                                    1004, (1, 4, 8)),
+    # config 5: long-context prefill
+    "cfg5_long_context": Workload("cfg5_long_context", "prefill", 1, 32, 65536, 128, "bf16", 128, 5, 1.0, 1005),
+}
+
+
+def round_to_io(a: np.ndarray, io_dtype: str) -> np.ndarray:
+    """float32 array whose values are exactly representable in ``io_dtype``."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if io_dtype == "f32":
+        return a
+    if io_dtype == "bf16":
+        return torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+    raise ValueError(f"unknown io dtype {io_dtype!r}")
+
+
+def torch_dtype(io_dtype: str):
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[io_dtype]
+
+
+def conv_weights(rng, H: int, d: int, conv_k: int) -> np.ndarray:
+    return (rng.standard_normal((H, d, conv_k)) * conv_k ** -0.5).astype(np.float32)
+
+
+def prefill_inputs(wl: Workload, seed: int | None = None):
+    """Returns q, k, v [B,H,L,d] and conv weights w [H,d,Kc] (float32 numpy)."""
+    rng = np.random.default_rng(wl.seed if seed is None else seed)
+    shape = (wl.B, wl.H, wl.L, wl.d)
+    q, k, v = (round_to_io(rng.standard_normal(shape) * wl.scale, wl.io_dtype) for _ in range(3))
+    w = conv_weights(rng, wl.H, wl.d, wl.conv_k)
+    return q, k, v, w
+
+
+def draft_block(wl: Workload, kk: int, step: int = 0, seed: int | None = None):
+    """q, k, v [B,H,kk,d] for one verify/decode step (seed + 100*(step+1))."""
+    base = wl.seed if seed is None else seed
+    rng = np.random.default_rng(base + 100 * (step + 1))
+    shape = (wl.B, wl.H, kk, wl.d)
+    return tuple(round_to_io(rng.standard_normal(shape) * wl.scale, wl.io_dtype) for _ in range(3))
+
+
+def random_state(wl: Workload, tokens: int, seed: int | None = None):
+    """A plausible running state without running any attention code.
+
+    S, z and hist with the magnitudes a ``tokens``-long prefix of unit-normal
+    inputs would leave behind: S ~ N(0, tokens * 1.6), z ~ tokens * 0.95 +
+    N(0, tokens * 0.5); used only where the *values* of the state do not
+    matter (bandwidth measurements).  float32, hist rounded to the io dtype.
+    """
+    rng = np.random.default_rng((wl.seed if seed is None else seed) + 7)
+    S = (rng.standard_normal((wl.B, wl.H, wl.d, wl.d)) * (1.6 * tokens) ** 0.5).astype(np.float32)
+    z = (0.95 * tokens + rng.standard_normal((wl.B, wl.H, wl.d)) * (0.5 * tokens) ** 0.5).astype(np.float32)
+    hist = round_to_io(rng.standard_normal((wl.B, wl.H, wl.conv_k - 1, wl.d)) * wl.scale, wl.io_dtype)
+    return S, z, hist

@@ -1,0 +1,433 @@
+"""Pins for the CPU oracle: facts fixed by the paper or by mathematics.
+
+Each ``pin_*`` function takes an oracle library handle (``lib``; None = the
+real one) and raises AssertionError if the oracle violates the fact.  They are
+run against the real oracle in ``test_oracle_pins.py`` and against deliberately
+broken copies of it in ``test_oracle_mutants.py`` (every planted mistake must
+trip at least one pin).
+
+None of them re-derives the oracle from its own formula: they use closed
+forms, special cases that reduce to library routines (cumsum, outer, grouped
+conv1d), exact rational arithmetic on a tiny case, invariances and the
+conv-window example the paper gives in Sec. 4.2.
+"""
+from __future__ import annotations
+
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import torch
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _rand(seed, B=2, H=3, L=17, d=5, Kc=3, with_state=False):
+    r = _rng(seed)
+    q, k, v = (r.standard_normal((B, H, L, d)) for _ in range(3))
+    w = r.standard_normal((H, d, Kc))
+    if not with_state:
+        return q, k, v, w
+    S0 = r.standard_normal((B, H, d, d))
+    z0 = np.abs(r.standard_normal((B, H, d))) + 0.5
+    h0 = r.standard_normal((B, H, Kc - 1, d))
+    return q, k, v, w, S0, z0, h0
+
+
+def _close(a, b, tol=1e-12, what=""):
+    a, b = np.asarray(a), np.asarray(b)
+    assert a.shape == b.shape, f"{what}: shape {a.shape} vs {b.shape}"
+    err = np.max(np.abs(a - b)) if a.size else 0.0
+    scale = max(1.0, float(np.max(np.abs(b))) if b.size else 1.0)
+    assert err <= tol * scale, f"{what}: max abs err {err:.3e} (scale {scale:.3e})"
+
+
+FORMS = ("prefill_quadratic", "prefill_recurrent")
+
+
+# --- the feature map ---------------------------------------------------------
+def pin_phi_values(lib=None):
+    """elu(x)+1: 1 at 0, x+1 above, exp(x) below (library exp), positive, increasing."""
+    xs = np.array([-30.0, -3.5, -1.0, -1e-9, 0.0, 1e-9, 0.25, 1.0, 7.5])
+    got = oracle.phi(xs, lib=lib)
+    want = np.array([math.exp(x) if x <= 0 else x + 1.0 for x in xs])
+    _close(got, want, 1e-15, "phi")
+    assert got[4] == 1.0
+    assert np.all(got > 0) and np.all(np.diff(got) > 0)
+
+
+# --- inclusive causal sum and the normaliser -----------------------------------
+def pin_first_token_is_its_own_value(lib=None):
+    """With one visible token the attention weight is 1: Y_1 = v_1 (Sec. 4.1, sum from i=1 to t)."""
+    q, k, v, w = _rand(11)
+    w0 = np.zeros_like(w)
+    for f in FORMS:
+        out = getattr(oracle, f)(q, k, v, w0, lib=lib)[0]
+        _close(out[:, :, 0], v[:, :, 0], 1e-13, f + " first token")
+
+
+def pin_zero_keys_give_running_mean(lib=None):
+    """K == 0 -> phi(K) == 1 -> every visible token weighs the same: cumsum(V)/count."""
+    q, k, v, w = _rand(12, L=23)
+    k = np.zeros_like(k)
+    want = np.cumsum(v, axis=2) / np.arange(1, v.shape[2] + 1)[None, None, :, None]
+    for f in FORMS:
+        out = getattr(oracle, f)(q, k, v, np.zeros_like(w), lib=lib)[0]
+        _close(out, want, 1e-12, f + " running mean")
+
+
+def pin_zero_queries_weigh_by_key_mass(lib=None):
+    """Q == 0 -> phi(q) is all ones -> weight of token i is sum_c phi(k_i)[c]."""
+    q, k, v, w = _rand(13, L=19, d=4)
+    q = np.zeros_like(q)
+    r = np.where(k > 0, k + 1.0, np.exp(k)).sum(-1, keepdims=True)
+    want = np.cumsum(r * v, axis=2) / np.cumsum(r, axis=2)
+    for f in FORMS:
+        out = getattr(oracle, f)(q, k, v, np.zeros_like(w), lib=lib)[0]
+        _close(out, want, 1e-12, f + " key-mass weights")
+
+
+def pin_head_dim_one_ignores_queries(lib=None):
+    """d == 1: phi(q_t) cancels between numerator and normaliser."""
+    q, k, v, w = _rand(14, L=15, d=1)
+    r = np.where(k > 0, k + 1.0, np.exp(k))
+    want = np.cumsum(r * v, axis=2) / np.cumsum(r, axis=2)
+    for f in FORMS:
+        out = getattr(oracle, f)(q, k, v, np.zeros_like(w), lib=lib)[0]
+        _close(out, want, 1e-12, f + " d=1")
+        out2 = getattr(oracle, f)(3.0 * q - 1.0, k, v, np.zeros_like(w), lib=lib)[0]
+        _close(out2, want, 1e-12, f + " d=1, other q")
+
+
+def pin_constant_values_pass_through(lib=None):
+    """All value rows equal c -> Y_t = c for every t (weights are positive and sum to one)."""
+    q, k, v, w = _rand(15)
+    c = _rng(150).standard_normal(v.shape[-1])
+    v = np.broadcast_to(c, v.shape).copy()
+    for f in FORMS:
+        out = getattr(oracle, f)(q, k, v, np.zeros_like(w), lib=lib)[0]
+        _close(out, v, 1e-12, f + " constant V")
+
+
+def pin_query_selects_feature(lib=None):
+    """A query that is (nearly) one-hot in feature i reads column i of the state.
+
+    q = -40 everywhere except +a at feature i: phi(q) = (a+1) e_i + O(e^-40), so
+    Y_t = sum_s phi(k_s)[i] v_s / sum_s phi(k_s)[i] -- a weighted running mean whose
+    weights depend on WHICH feature the query picked.
+    """
+    B, H, L, d = 1, 2, 12, 4
+    r = _rng(16)
+    k, v = r.standard_normal((B, H, L, d)), r.standard_normal((B, H, L, d))
+    fk = np.where(k > 0, k + 1.0, np.exp(k))
+    w = np.zeros((H, d, 3))
+    for i in range(d):
+        q = np.full((B, H, L, d), -40.0)
+        q[..., i] = 1.5
+        want = np.cumsum(fk[..., i:i + 1] * v, axis=2) / np.cumsum(fk[..., i:i + 1], axis=2)
+        for f in FORMS:
+            out = getattr(oracle, f)(q, k, v, w, lib=lib)[0]
+            _close(out, want, 1e-10, f"{f} one-hot query {i}")
+
+
+def pin_linearity_in_values(lib=None):
+    q, k, v, w = _rand(17)
+    v2 = _rng(170).standard_normal(v.shape)
+    a, b = 0.75, -2.5
+    for f in FORMS:
+        fn = getattr(oracle, f)
+        lhs = fn(q, k, a * v + b * v2, w, lib=lib)[0]
+        rhs = a * fn(q, k, v, w, lib=lib)[0] + b * fn(q, k, v2, w, lib=lib)[0]
+        _close(lhs, rhs, 1e-11, f + " linearity")
+
+
+def pin_eps_enters_the_denominator(lib=None):
+    """d=1, one token: out = phi(q)phi(k) v / (phi(q)phi(k) + eps)."""
+    q = np.array([[[[0.5]]]])
+    k = np.array([[[[1.0]]]])
+    v = np.array([[[[3.0]]]])
+    w = np.zeros((1, 1, 1))
+    a = 1.5 * 2.0
+    for f in FORMS:
+        out = getattr(oracle, f)(q, k, v, w, eps=0.25, lib=lib)[0]
+        _close(out, [[[[a * 3.0 / (a + 0.25)]]]], 1e-15, f + " eps")
+
+
+# --- exact arithmetic on a tiny case ----------------------------------------------
+def _phi_frac(x):
+    """Inputs are chosen so that phi is rational: integers >= 0, or log(1/2), log(1/4)."""
+    if x >= 0:
+        return Fraction(x) + 1
+    return {math.log(0.5): Fraction(1, 2), math.log(0.25): Fraction(1, 4)}[x]
+
+
+def pin_exact_rational_brute_force(lib=None):
+    """L=5, d=3, Kc=3, incoming state and history: exact fractions vs the oracle."""
+    L, d, Kc = 5, 3, 3
+    lh, lq = math.log(0.5), math.log(0.25)
+    q = np.array([[0, 1, lh], [2, lq, 0], [lh, lh, 3], [1, 0, 0], [lq, 2, 1]], dtype=float)
+    k = np.array([[1, lh, 0], [0, 0, 2], [lq, 1, lh], [3, lh, lq], [0, 1, 1]], dtype=float)
+    v = np.array([[1, -2, 0.5], [0.25, 3, -1], [-4, 0, 2], [1.5, 1, 1], [0, -0.75, 8]])
+    w = np.array([[0.5, -1, 2], [1, 0.25, -0.5], [-2, 4, 0.125]])          # [d, Kc]
+    S0 = np.array([[1, 0, -1], [2, 0.5, 0], [0, 1, 3]], dtype=float)
+    z0 = np.array([2, 1, 0.5])
+    h0 = np.array([[1, 2, 3], [-1, 0.5, 4]], dtype=float)                   # oldest first
+
+    F = Fraction
+    fq = [[_phi_frac(x) for x in row] for row in q]
+    fk = [[_phi_frac(x) for x in row] for row in k]
+    vf = [[F(x) for x in row] for row in v]
+    ext = [[F(x) for x in row] for row in h0] + vf                         # index s+2
+    want = np.zeros((L, d))
+    for t in range(L):
+        den = sum(fq[t][i] * F(z0[i]) for i in range(d))
+        num = [sum(fq[t][i] * F(S0[i][c]) for i in range(d)) for c in range(d)]
+        for s in range(t + 1):
+            a = sum(fq[t][i] * fk[s][i] for i in range(d))
+            den += a
+            num = [num[c] + a * vf[s][c] for c in range(d)]
+        for c in range(d):
+            u = sum(F(w[c][j]) * ext[t - j + 2][c] for j in range(Kc))
+            want[t, c] = float(num[c] / den + u)
+    S1 = [[F(S0[i][c]) + sum(fk[t][i] * vf[t][c] for t in range(L)) for c in range(d)] for i in range(d)]
+    z1 = [F(z0[i]) + sum(fk[t][i] for t in range(L)) for i in range(d)]
+    for f in FORMS:
+        out, S, z, h = getattr(oracle, f)(q[None, None], k[None, None], v[None, None], w[None],
+                                          S0[None, None], z0[None, None], h0[None, None], lib=lib)
+        _close(out[0, 0], want, 1e-14, f + " exact out")
+        _close(S[0, 0], np.array([[float(x) for x in row] for row in S1]), 1e-14, f + " exact S")
+        _close(z[0, 0], np.array([float(x) for x in z1]), 1e-14, f + " exact z")
+        _close(h[0, 0], v[-2:], 0.0, f + " hist")
+
+
+# --- state layout ----------------------------------------------------------------
+def pin_single_token_state_is_outer_product(lib=None):
+    """After one token S = phi(k) v^T (row = key feature, column = value channel), z = phi(k)."""
+    r = _rng(18)
+    k, v, q = r.standard_normal((1, 1, 1, 4)), r.standard_normal((1, 1, 1, 4)), r.standard_normal((1, 1, 1, 4))
+    fk = np.where(k > 0, k + 1.0, np.exp(k))[0, 0, 0]
+    w = np.zeros((1, 4, 2))
+    for f in FORMS:
+        _, S, z, h = getattr(oracle, f)(q, k, v, w, lib=lib)
+        _close(S[0, 0], np.outer(fk, v[0, 0, 0]), 1e-15, f + " S outer")
+        _close(z[0, 0], fk, 1e-15, f + " z")
+        _close(h[0, 0, 0], v[0, 0, 0], 0.0, f + " hist")
+
+
+def pin_feature_and_channel_permutations(lib=None):
+    """Permuting the q/k feature axis changes nothing; permuting value channels (and the
+    conv weights with them) permutes the output channels."""
+    q, k, v, w = _rand(19, d=6)
+    pf = _rng(190).permutation(6)
+    pc = _rng(191).permutation(6)
+    for f in FORMS:
+        fn = getattr(oracle, f)
+        base = fn(q, k, v, w, lib=lib)[0]
+        _close(fn(q[..., pf], k[..., pf], v, w, lib=lib)[0], base, 1e-12, f + " feature perm")
+        _close(fn(q, k, v[..., pc], w[:, pc], lib=lib)[0], base[..., pc], 1e-12, f + " channel perm")
+
+
+def pin_heads_are_independent(lib=None):
+    """Swapping two heads (inputs and their conv weights) swaps their outputs."""
+    q, k, v, w = _rand(20, B=2, H=3)
+    perm = [2, 0, 1]
+    for f in FORMS:
+        fn = getattr(oracle, f)
+        base = fn(q, k, v, w, lib=lib)[0]
+        got = fn(q[:, perm], k[:, perm], v[:, perm], w[perm], lib=lib)[0]
+        _close(got, base[:, perm], 0.0, f + " head perm")
+
+
+# --- the causal depthwise convolution -----------------------------------------------
+def pin_conv_matches_library_grouped_conv(lib=None):
+    """Left-padded (by the history) grouped conv1d; cross-correlation needs the taps reversed."""
+    B, H, L, d, Kc = 2, 3, 21, 4, 5
+    r = _rng(21)
+    v = r.standard_normal((B, H, L, d))
+    w = r.standard_normal((H, d, Kc))
+    for hist in (None, r.standard_normal((B, H, Kc - 1, d))):
+        left = np.zeros((B, H, Kc - 1, d)) if hist is None else hist
+        x = np.concatenate([left, v], axis=2)                                  # [B,H,L+Kc-1,d]
+        x = torch.from_numpy(x).permute(0, 1, 3, 2).reshape(B, H * d, L + Kc - 1)
+        wt = torch.from_numpy(w[:, :, ::-1].copy()).reshape(H * d, 1, Kc)
+        want = torch.nn.functional.conv1d(x, wt, groups=H * d).reshape(B, H, d, L).permute(0, 1, 3, 2).numpy()
+        _close(oracle.causal_conv(v, w, hist, lib=lib), want, 1e-13, "conv vs conv1d")
+        q, k = r.standard_normal(v.shape), r.standard_normal(v.shape)
+        for f in FORMS:
+            fn = getattr(oracle, f)
+            with_conv = fn(q, k, v, w, hist0=hist, lib=lib)[0]
+            without = fn(q, k, v, np.zeros_like(w), hist0=hist, lib=lib)[0]
+            _close(with_conv - without, want, 1e-12, f + " conv added to attention output")
+
+
+def _window_table(path):
+    table = {}
+    with open(path) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            key, val = line.split(":")
+            table[int(key)] = sorted(int(x) for x in val.split())
+    return table
+
+
+def pin_conv_window_example_from_the_paper(lib=None):
+    """Sec. 4.2: a kernel-3 conv at step t1 must cover {t0, t1}.  An impulse at token s with
+    tap weights 1, 10, 100 tells which tap of which output sees s."""
+    want = _window_table(os.path.join(GOLDEN, "conv_window_k3.txt"))
+    L, Kc = 5, 3
+    w = np.array([[[1.0, 10.0, 100.0]]])
+    seen = {t: [] for t in range(L)}
+    for s in range(L):
+        v = np.zeros((1, 1, L, 1))
+        v[0, 0, s, 0] = 1.0
+        u = oracle.causal_conv(v, w, None, lib=lib)[0, 0, :, 0]
+        for t in range(L):
+            if u[t] != 0.0:
+                seen[t].append(s)
+                assert u[t] == 10.0 ** (t - s), f"tap order: token {s} seen by {t} with weight {u[t]}"
+    assert {t: sorted(x) for t, x in seen.items()} == want
+    # the same windows in a draft block that follows a verified history (t0 = history)
+    S = np.zeros((1, 1, 1, 1)); z = np.ones((1, 1, 1)); hist = np.array([[[[5.0], [7.0]]]])
+    zero = np.zeros((1, 1, 2, 1))
+    drafts = np.array([[[[2.0], [3.0]]]])
+    out = oracle.verify(zero, np.full_like(zero, -745.0), drafts, w, S, z, hist, lib=lib)[0][0, 0, :, 0]
+    # keys ~ -inf -> phi(k) = 0 -> the attention part is 0/1; only the conv remains
+    _close(out, [2.0 + 10 * 7.0 + 100 * 5.0, 3.0 + 10 * 2.0 + 100 * 7.0], 1e-12, "draft windows")
+
+
+# --- no information leakage ---------------------------------------------------------------
+def pin_no_leak_from_later_tokens(lib=None):
+    """Changing any of q, k, v after position t leaves outputs up to t bit-identical (Sec. 4.1)."""
+    q, k, v, w, S0, z0, h0 = _rand(22, L=14, with_state=True)
+    r = _rng(220)
+    for f in FORMS:
+        fn = getattr(oracle, f)
+        base = fn(q, k, v, w, S0, z0, h0, lib=lib)[0]
+        for t in (0, 5, 12):
+            q2, k2, v2 = q.copy(), k.copy(), v.copy()
+            for a in (q2, k2, v2):
+                a[:, :, t + 1:] += 10.0 * r.standard_normal(a[:, :, t + 1:].shape)
+            got = fn(q2, k2, v2, w, S0, z0, h0, lib=lib)[0]
+            assert np.array_equal(got[:, :, :t + 1], base[:, :, :t + 1]), f"{f}: leak into <= {t}"
+            assert not np.array_equal(got[:, :, t + 1:], base[:, :, t + 1:])
+
+
+def pin_every_earlier_token_matters(lib=None):
+    """The converse: output t does change when any token s <= t changes (nothing is dropped)."""
+    q, k, v, w = _rand(23, B=1, H=1, L=9)
+    w = np.zeros_like(w)
+    for f in FORMS:
+        fn = getattr(oracle, f)
+        base = fn(q, k, v, w, lib=lib)[0]
+        for s in range(9):
+            v2 = v.copy()
+            v2[:, :, s] += 1.0
+            got = fn(q, k, v2, w, lib=lib)[0]
+            changed = np.any(got != base, axis=-1)[0, 0]
+            assert list(changed) == [t >= s for t in range(9)], f"{f}: token {s} -> {changed}"
+
+
+# --- re-association, chunking, resuming -------------------------------------------------------
+def pin_recurrent_equals_quadratic(lib=None):
+    """Sec. 3: phi(Q)(phi(K)^T V) is a re-association of (phi(Q)phi(K)^T)V."""
+    for seed, kw in ((30, {}), (31, dict(B=1, H=2, L=32, d=8, Kc=1)), (32, dict(L=9, d=2, Kc=5)),
+                     (33, dict(B=1, H=1, L=1, d=3))):
+        args = _rand(seed, with_state=True, **kw)
+        a = oracle.prefill_quadratic(*args, eps=1e-3, lib=lib)
+        b = oracle.prefill_recurrent(*args, eps=1e-3, lib=lib)
+        for x, y, n in zip(a, b, ("out", "S", "z", "hist")):
+            _close(x, y, 1e-12, f"quadratic vs recurrent {n} (seed {seed})")
+        a = oracle.prefill_quadratic(*args[:4], lib=lib)
+        b = oracle.prefill_recurrent(*args[:4], lib=lib)
+        for x, y, n in zip(a, b, ("out", "S", "z", "hist")):
+            _close(x, y, 1e-12, f"quadratic vs recurrent from zero state {n} (seed {seed})")
+
+
+def pin_split_invariance(lib=None):
+    """prefill(L) == prefill(L1) then prefill(L - L1) from the handed-over state (Sec. 5.3:
+    a shared prefix is computed once)."""
+    q, k, v, w, S0, z0, h0 = _rand(34, L=20, with_state=True)
+    for f in FORMS:
+        fn = getattr(oracle, f)
+        full = fn(q, k, v, w, S0, z0, h0, lib=lib)
+        for L1 in (1, 2, 7, 19):
+            a = fn(q[:, :, :L1], k[:, :, :L1], v[:, :, :L1], w, S0, z0, h0, lib=lib)
+            b = fn(q[:, :, L1:], k[:, :, L1:], v[:, :, L1:], w, a[1], a[2], a[3], lib=lib)
+            _close(np.concatenate([a[0], b[0]], axis=2), full[0], 1e-12, f"{f} split {L1} out")
+            for x, y, n in zip(b[1:], full[1:], ("S", "z", "hist")):
+                _close(x, y, 1e-12, f"{f} split {L1} {n}")
+
+
+def pin_empty_sequence_is_identity(lib=None):
+    q, k, v, w, S0, z0, h0 = _rand(35, L=0, with_state=True)
+    for f in FORMS:
+        out, S, z, h = getattr(oracle, f)(q, k, v, w, S0, z0, h0, lib=lib)
+        assert out.shape[2] == 0
+        assert np.array_equal(S, S0) and np.array_equal(z, z0) and np.array_equal(h, h0)
+
+
+# --- verification of draft tokens -----------------------------------------------------------------
+def pin_verify_equals_sequential_decode(lib=None):
+    """Sec. 4.2: scoring k drafts at once must give what k single steps give."""
+    B, H, d, Kc, kk = 2, 2, 4, 3, 5
+    q, k, v, w, S0, z0, h0 = _rand(40, B=B, H=H, L=kk, d=d, Kc=Kc, with_state=True)
+    out, S, z, h = oracle.verify(q, k, v, w, S0, z0, h0, lib=lib)
+    Ss, zs, hs = S0, z0, h0
+    for j in range(kk):
+        o, Ss, zs, hs = oracle.decode(q[:, :, j:j + 1], k[:, :, j:j + 1], v[:, :, j:j + 1], w, Ss, zs, hs, lib=lib)
+        assert np.array_equal(o[:, :, 0], out[:, :, j]), f"draft {j}"
+    assert np.array_equal(S, Ss) and np.array_equal(z, zs) and np.array_equal(h, hs)
+    # and both equal the last rows of one long prefill over prefix ++ drafts
+    P = 6
+    pq, pk, pv, _ = _rand(41, B=B, H=H, L=P, d=d, Kc=Kc)
+    _, S1, z1, h1 = oracle.prefill_recurrent(pq, pk, pv, w, lib=lib)
+    vo = oracle.verify(q, k, v, w, S1, z1, h1, lib=lib)
+    cat = [np.concatenate([a, b], axis=2) for a, b in ((pq, q), (pk, k), (pv, v))]
+    full = oracle.prefill_quadratic(*cat, w, lib=lib)
+    _close(vo[0], full[0][:, :, P:], 1e-12, "prefill -> verify vs long prefill")
+    for x, y, n in zip(vo[1:], full[1:], ("S", "z", "hist")):
+        _close(x, y, 1e-12, "prefill -> verify " + n)
+
+
+def pin_verify_commit_counts(lib=None):
+    """Rejected drafts leave no trace: n_commit = n gives the state of n single steps,
+    n_commit = 0 hands the state back bit-unchanged; outputs do not depend on n_commit."""
+    B, H, d, Kc, kk = 3, 2, 4, 4, 4
+    q, k, v, w, S0, z0, h0 = _rand(42, B=B, H=H, L=kk, d=d, Kc=Kc, with_state=True)
+    all_out = oracle.verify(q, k, v, w, S0, z0, h0, lib=lib)[0]
+    nc = np.array([0, 2, 4], dtype=np.int32)
+    out, S, z, h = oracle.verify(q, k, v, w, S0, z0, h0, n_commit=nc, lib=lib)
+    assert np.array_equal(out, all_out)
+    assert np.array_equal(S[0], S0[0]) and np.array_equal(z[0], z0[0]) and np.array_equal(h[0], h0[0])
+    for b, n in enumerate(nc):
+        Ss, zs, hs = S0[b:b + 1], z0[b:b + 1], h0[b:b + 1]
+        for j in range(n):
+            _, Ss, zs, hs = oracle.decode(q[b:b + 1, :, j:j + 1], k[b:b + 1, :, j:j + 1], v[b:b + 1, :, j:j + 1],
+                                          w, Ss, zs, hs, lib=lib)
+        assert np.array_equal(S[b:b + 1], Ss) and np.array_equal(z[b:b + 1], zs) and np.array_equal(h[b:b + 1], hs), \
+            f"batch {b} n_commit {n}"
+
+
+def pin_verify_no_leak_between_drafts(lib=None):
+    B, H, d, Kc, kk = 1, 2, 4, 3, 6
+    q, k, v, w, S0, z0, h0 = _rand(43, B=B, H=H, L=kk, d=d, Kc=Kc, with_state=True)
+    base = oracle.verify(q, k, v, w, S0, z0, h0, lib=lib)[0]
+    for j in range(kk - 1):
+        q2, k2, v2 = q.copy(), k.copy(), v.copy()
+        for a in (q2, k2, v2):
+            a[:, :, j + 1:] = -3.0 * a[:, :, j + 1:] + 1.0
+        got = oracle.verify(q2, k2, v2, w, S0, z0, h0, lib=lib)[0]
+        assert np.array_equal(got[:, :, :j + 1], base[:, :, :j + 1]), f"draft {j} saw a later draft"
+        assert not np.array_equal(got[:, :, j + 1:], base[:, :, j + 1:])
+
+
+ALL_PINS = [obj for name, obj in sorted(globals().items()) if name.startswith("pin_") and callable(obj)]

@@ -1,0 +1,80 @@
+"""Every plausible mistake planted in the oracle must trip at least one pin.
+
+The mistakes are planted on the CPU, in a patched copy of the oracle's C source
+compiled to a temporary library; the real oracle is untouched.
+"""
+import os
+
+import pytest
+
+import oracle
+from oracle_pins import ALL_PINS
+
+SRC = open(os.path.join(os.path.dirname(oracle.__file__), "linattn_oracle.c")).read()
+
+# (name, text in the source, replacement)
+MUTANTS = [
+    ("phi_drops_plus_one", "x > 0.0 ? x + 1.0 : exp(x)", "x > 0.0 ? x : exp(x)"),
+    ("phi_branch_flipped", "x > 0.0 ? x + 1.0 : exp(x)", "x < 0.0 ? x + 1.0 : exp(x)"),
+    ("quadratic_excludes_diagonal", "for (int i = 0; i <= t; ++i) {", "for (int i = 0; i < t; ++i) {"),
+    ("quadratic_not_causal", "for (int i = 0; i <= t; ++i) {", "for (int i = 0; i < L; ++i) {"),
+    ("quadratic_den_drops_z0", "if (z0) den += dot(fqt, z0, d);", ""),
+    ("quadratic_S0_transposed", "num[c] += fqt[i] * S0[(size_t)i * d + c];", "num[c] += fqt[i] * S0[(size_t)c * d + i];"),
+    ("quadratic_uses_raw_q", "fq[e] = oracle_phi(q[e]);", "fq[e] = q[e];"),
+    ("quadratic_uses_raw_k", "fk[e] = oracle_phi(k[e]);", "fk[e] = k[e];"),
+    ("quadratic_S_out_transposed", "s += fk[(size_t)t * d + i] * v[(size_t)t * d + c];",
+     "s += fk[(size_t)t * d + c] * v[(size_t)t * d + i];"),
+    ("quadratic_eps_dropped", "double den = eps;", "double den = 0.0;"),
+    ("conv_reads_the_future", "vext_row(v, hist, Kc, d, t - j);\n        if (row) acc", "vext_row(v, hist, Kc, d, t + j < L ? t + j : t);\n        if (row) acc"),
+    ("conv_window_excludes_current", "vext_row(v, hist, Kc, d, t - j);\n        if (row) acc", "vext_row(v, hist, Kc, d, t - j - 1);\n        if (row) acc"),
+    ("conv_hist_reversed", "return hist + (size_t)(Kc - 1 + s) * d;", "return hist + (size_t)(-s - 1) * d;"),
+    ("conv_weights_of_wrong_head", "conv_head(L, d, Kc, v + (size_t)bh * L * d, w + (size_t)h * d * Kc,",
+     "conv_head(L, d, Kc, v + (size_t)bh * L * d, w + (size_t)(bh / H) * d * Kc,"),
+    ("hist_after_off_by_one", "int s = n - Hn + r; /* index into the extended sequence */", "int s = n - Hn + r - 1;"),
+    ("step_state_after_readout", "z[i] += fk;", "z[i] += (i == 0 ? 0.5 : 1.0) * fk;"),
+    ("step_drops_z_update", "z[i] += fk;", ""),
+    ("step_S_transposed_readout", "num += fq[i] * S[(size_t)i * d + c];", "num += fq[i] * S[(size_t)c * d + i];"),
+    ("step_S_transposed_update", "S[(size_t)i * d + c] += fk * v[c];", "S[(size_t)c * d + i] += fk * v[c];"),
+    ("step_eps_dropped", "double den = dot(fq, z, d) + eps;", "double den = dot(fq, z, d);"),
+    ("step_hist_taps_reversed", "hist[(size_t)(Kc - 1 - j) * d + c];", "hist[(size_t)(j - 1) * d + c];"),
+    ("step_hist_not_shifted", "if (Kc > 1) memcpy(hist + (size_t)(Kc - 2) * d, v, sizeof(double) * d);",
+     "if (Kc > 1) memcpy(hist, v, sizeof(double) * d);"),
+    ("step_uses_raw_q", "fq[i] = oracle_phi(q[i]);", "fq[i] = q[i];"),
+    ("verify_commits_one_late", "if (j + 1 == n) {", "if (j == n) {"),
+    ("verify_commits_everything", "int n = n_commit ? n_commit[b] : kk;", "int n = kk; (void)b;"),
+    ("verify_n_commit_per_head", "int n = n_commit ? n_commit[b] : kk;", "int n = n_commit ? n_commit[h % B] : kk; (void)b;"),
+    ("recurrent_ignores_incoming_hist", "hist0 ? hist0 + bh * nh : NULL, S, z, hs);", "NULL, S, z, hs);"),
+    ("recurrent_ignores_incoming_S", "load_state(d, Kc, S0 ? S0 + bh * nS : NULL, z0", "load_state(d, Kc, NULL, z0"),
+]
+
+
+def _run_pins(lib):
+    failed = []
+    for pin in ALL_PINS:
+        try:
+            pin(lib)
+        except AssertionError:
+            failed.append(pin.__name__)
+        except (KeyError, ValueError, FloatingPointError, ZeroDivisionError):
+            failed.append(pin.__name__)
+    return failed
+
+
+def test_mutant_list_still_applies():
+    for name, old, new in MUTANTS:
+        assert SRC.count(old) >= 1, f"mutant {name}: its source text is gone"
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new):
+    src = tmp_path / "mutant.c"
+    src.write_text(SRC.replace(old, new, 1) if SRC.count(old) == 1 else SRC.replace(old, new))
+    so = tmp_path / "libmutant.so"
+    oracle.build(force=True, src=str(src), out=str(so))
+    lib = oracle._load(str(so))
+    failed = _run_pins(lib)
+    assert failed, f"planted mistake {name!r} passed every pin"
+
+
+def test_real_oracle_passes_every_pin():
+    assert _run_pins(None) == []
