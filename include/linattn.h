@@ -1,0 +1,154 @@
+/*
+ * linattn.h -- C ABI of the MI355X (gfx950) library for causal kernelised
+ * linear attention fused with a causal depthwise convolution on V.
+ *
+ * The operation (per batch row b and head h, independently):
+ *
+ *   Phi_q = phi(Q), Phi_k = phi(K), phi(x) = elu(x) + 1, elementwise.
+ *   Y_t   = ( Phi_q[t]^T S_t ) / ( Phi_q[t] . z_t + eps )
+ *   S_t   = S_in + sum_{i<=t} Phi_k[i] V[i]^T      (d x d)
+ *   z_t   = z_in + sum_{i<=t} Phi_k[i]             (d)
+ *   U_t[c]= sum_{j<Kc} conv_w[h][c][j] * Vext[t-j][c]
+ *   out_t = Y_t + U_t
+ *
+ * Sec. 3 ("Linear Attentions") of the paper gives the factorisation
+ * Sim(Q,K) ~ phi(Q) phi(K)^T and its re-association phi(Q)(phi(K)^T V);
+ * Sec. 4.1 gives the causal form (query t meets the cumulative sum over
+ * i <= t of the key/value products), the partition of the sequence into
+ * groups with group-level cumulative sums between them (here: `chunk`), and
+ * the causally masked depthwise convolution on the V branch; Sec. 4.2 gives
+ * speculative verification, where several draft tokens are scored in one call
+ * and each may see the verified past and earlier drafts only, the convolution
+ * window of draft j being the verified history followed by drafts <= j.
+ * The row normaliser z, eps, and out = Y + U are this library's reading where
+ * the paper leaves them open.
+ *
+ * Vext is V extended to the left by `hist` (the last Kc-1 value rows seen so
+ * far, oldest first), or by zeros at the start of a sequence.  Tap j of the
+ * convolution multiplies the value row j positions back (j = 0: the current
+ * token).  No output for token t depends on any token after t.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers, 16-byte aligned.  The descriptor
+ *     and the scalar arguments are host values.  `n_commit` is a device pointer.
+ *   - The caller owns every buffer.  The library allocates no device memory,
+ *     keeps no state between calls and may be called from several host threads.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and the call returns without waiting for it.
+ *   - The return value reports argument validation and launch errors only.
+ *     Validation happens before anything is enqueued: on any error other than
+ *     LINATTN_ERR_HIP nothing has been launched and no buffer was touched.
+ *   - q, k, v, out are addressed as  base + b*stride_b + h*stride_h +
+ *     t*stride_t + c  (element units; the last axis, length d, is contiguous;
+ *     every stride is a multiple of 8 elements).  The same strides apply to all
+ *     four.  State tensors are dense: S [B,H,d,d] float (row = key feature i,
+ *     column = value channel c, c contiguous), z [B,H,d] float,
+ *     hist [B,H,Kc-1,d] in the i/o dtype, conv_w [H,d,Kc] float.
+ *   - Buffers must not overlap except where an alias is explicitly allowed.
+ */
+#ifndef LINATTN_H
+#define LINATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LINATTN_OK = 0,
+  LINATTN_ERR_NULL = 1,        /* a required pointer is NULL                          */
+  LINATTN_ERR_SHAPE = 2,       /* B, H, L, k, d, conv_k, chunk or a stride is invalid  */
+  LINATTN_ERR_DTYPE = 3,       /* unknown io_dtype or phi                              */
+  LINATTN_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned                     */
+  LINATTN_ERR_UNSUPPORTED = 5, /* valid request this build has no kernel for           */
+  LINATTN_ERR_WORKSPACE = 6,   /* workspace missing or smaller than required           */
+  LINATTN_ERR_HIP = 7          /* the HIP runtime refused a launch                     */
+} linattn_status;
+
+typedef enum { LINATTN_F32 = 0, LINATTN_BF16 = 1 } linattn_dtype;
+typedef enum { LINATTN_PHI_ELU1 = 0 } linattn_phi;
+
+#define LINATTN_MAX_CONV_K 8   /* taps t, t-1, ..., t-Kc+1                              */
+#define LINATTN_MAX_DRAFT 16   /* draft tokens per verify call                          */
+
+typedef struct {
+  int32_t B, H;            /* batch rows, heads                                        */
+  int32_t d;               /* head dimension d_k = d_v: 64 or 128                       */
+  int32_t conv_k;          /* Kc, 1..LINATTN_MAX_CONV_K                                 */
+  int32_t chunk;           /* tokens per group in prefill: 64 or 128 (ignored by
+                              verify/decode).  The result does not depend on it.       */
+  int32_t io_dtype;        /* linattn_dtype of q, k, v, out, hist                       */
+  int32_t phi;             /* linattn_phi                                               */
+  float eps;               /* added to every denominator; >= 0                          */
+  int64_t stride_b, stride_h, stride_t; /* element strides of q, k, v, out             */
+} linattn_desc;
+
+/* Bytes of device scratch `linattn_prefill` needs for this descriptor and L
+ * (0 if none).  Depends on B, H, d and on how the sequence axis is split over
+ * workgroups, never on L beyond that split: it is bounded by a constant for
+ * fixed B, H, d.  Returns 0 for an invalid descriptor. */
+size_t linattn_workspace_bytes(const linattn_desc *desc, int32_t L);
+
+/* Prefill (Sec. 4.1): all L tokens of every (b, h) at once, processed in
+ * groups of `chunk` tokens; inside a group the masked phi(Q)phi(K)^T V product,
+ * between groups the running (S, z) carry.
+ *   q, k, v      in   [B,H,L,d] by strides, i/o dtype
+ *   conv_w       in   [H,d,Kc] float
+ *   S_in, z_in, hist_in   in, optional: all three NULL = start of a sequence
+ *                (zeros), or all three given = continue from that state
+ *   out          out  [B,H,L,d] by strides, i/o dtype
+ *   S_out, z_out, hist_out  out, optional (each may be NULL = not wanted);
+ *                each may alias its *_in counterpart
+ *   workspace    device scratch of at least linattn_workspace_bytes(desc, L)
+ *                bytes (may be NULL when that is 0); contents are undefined
+ *                before and after
+ * L >= 0; L need not be a multiple of chunk.  L == 0 copies the state through. */
+linattn_status linattn_prefill(const linattn_desc *desc, int32_t L,
+                               const void *q, const void *k, const void *v,
+                               const float *conv_w,
+                               const float *S_in, const float *z_in, const void *hist_in,
+                               void *out,
+                               float *S_out, float *z_out, void *hist_out,
+                               void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
+
+/* Speculative verification (Sec. 4.2): scores kk draft tokens per (b, h) from
+ * one running state.  Output j equals what kk single decode steps would give
+ * at step j.  Afterwards the state has advanced over the first n_commit[b]
+ * drafts of batch row b (the accepted ones); n_commit == NULL keeps all kk;
+ * n_commit[b] == 0 leaves that row's state bit-unchanged.
+ *   q, k, v      in      [B,H,kk,d] dense, i/o dtype (desc strides are ignored)
+ *   conv_w       in      [H,d,Kc] float
+ *   S, z, hist   in/out  updated in place (hist may be NULL only if Kc == 1)
+ *   n_commit     in      device int32 [B], each in 0..kk, or NULL.  Values
+ *                        outside 0..kk are clamped into that range.
+ *   out          out     [B,H,kk,d] dense, i/o dtype
+ * 1 <= kk <= LINATTN_MAX_DRAFT. */
+linattn_status linattn_verify(const linattn_desc *desc, int32_t kk,
+                              const void *q, const void *k, const void *v,
+                              const float *conv_w,
+                              float *S, float *z, void *hist,
+                              const int32_t *n_commit,
+                              void *out, void *hip_stream);
+
+/* One generated token per (b, h) (Sec. 3, decode phase; Sec. 4.1 recurrence):
+ * linattn_verify with kk = 1 whose draft is always kept.
+ *   q, k, v, out  [B,H,d] dense (equivalently [B,H,1,d]). */
+linattn_status linattn_decode(const linattn_desc *desc,
+                              const void *q, const void *k, const void *v,
+                              const float *conv_w,
+                              float *S, float *z, void *hist,
+                              void *out, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char *linattn_status_string(linattn_status status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t linattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LINATTN_H */

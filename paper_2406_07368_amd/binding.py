@@ -1,0 +1,162 @@
+"""ctypes binding of liblinattn.so: argument marshalling only.
+
+The three calls have the names and argument order of ``include/linattn.h``.
+Tensors are torch tensors on the GPU (torch is used for device memory and
+streams, nothing else); every arithmetic step runs inside the library's
+kernels.  If the library is missing or a call is refused, this module raises;
+there is no other code path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblinattn.so")
+_lib = None
+
+LINATTN_F32, LINATTN_BF16 = 0, 1
+LINATTN_PHI_ELU1 = 0
+MAX_CONV_K, MAX_DRAFT = 8, 16
+SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_verify", "linattn_decode",
+           "linattn_status_string", "linattn_version")
+
+
+class LinattnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("conv_k", ctypes.c_int32), ("chunk", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+                ("phi", ctypes.c_int32), ("eps", ctypes.c_float),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_t", ctypes.c_int64)]
+
+
+def load():
+    """Load the built library (build it first if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    dp = ctypes.POINTER(Desc)
+    lib.linattn_workspace_bytes.restype = sz
+    lib.linattn_workspace_bytes.argtypes = [dp, i32]
+    lib.linattn_prefill.restype = ctypes.c_int
+    lib.linattn_prefill.argtypes = [dp, i32] + [vp] * 11 + [vp, sz, vp]
+    lib.linattn_verify.restype = ctypes.c_int
+    lib.linattn_verify.argtypes = [dp, i32] + [vp] * 9 + [vp]
+    lib.linattn_decode.restype = ctypes.c_int
+    lib.linattn_decode.argtypes = [dp] + [vp] * 8 + [vp]
+    lib.linattn_status_string.restype = ctypes.c_char_p
+    lib.linattn_status_string.argtypes = [ctypes.c_int]
+    lib.linattn_version.restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().linattn_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise LinattnError(status, where)
+
+
+def make_desc(B, H, d, conv_k, chunk=64, io_dtype=torch.bfloat16, eps=0.0, strides=None, L=None) -> Desc:
+    """Descriptor for dense [B,H,L,d] tensors unless ``strides`` (b, h, t) is given."""
+    code = {torch.float32: LINATTN_F32, torch.bfloat16: LINATTN_BF16}[io_dtype]
+    if strides is None:
+        Lx = 0 if L is None else int(L)
+        strides = (H * Lx * d, Lx * d, d)
+    return Desc(B, H, d, conv_k, chunk, code, LINATTN_PHI_ELU1, float(eps), *[int(s) for s in strides])
+
+
+def linattn_workspace_bytes(desc: Desc, L: int) -> int:
+    return int(load().linattn_workspace_bytes(ctypes.byref(desc), int(L)))
+
+
+def linattn_prefill(desc: Desc, L, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out,
+                    workspace=None, workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().linattn_prefill(ctypes.byref(desc), int(L), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
+                                _ptr(S_in), _ptr(z_in), _ptr(hist_in), _ptr(out), _ptr(S_out), _ptr(z_out),
+                                _ptr(hist_out), _ptr(workspace), int(workspace_bytes), _stream(stream))
+    _check(st, "linattn_prefill")
+
+
+def linattn_verify(desc: Desc, kk, q, k, v, conv_w, S, z, hist, n_commit, out, stream=None) -> None:
+    st = load().linattn_verify(ctypes.byref(desc), int(kk), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
+                               _ptr(S), _ptr(z), _ptr(hist), _ptr(n_commit), _ptr(out), _stream(stream))
+    _check(st, "linattn_verify")
+
+
+def linattn_decode(desc: Desc, q, k, v, conv_w, S, z, hist, out, stream=None) -> None:
+    st = load().linattn_decode(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
+                               _ptr(S), _ptr(z), _ptr(hist), _ptr(out), _stream(stream))
+    _check(st, "linattn_decode")
+
+
+# ---- conveniences that only allocate with torch and forward to the calls above ---------------
+def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, stream=None):
+    """q, k, v: dense [B,H,L,d] CUDA tensors (fp32 or bf16).  Returns out, (S, z, hist)."""
+    B, H, L, d = q.shape
+    Kc = conv_w.shape[2]
+    desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, L=L)
+    out = torch.empty_like(q)
+    S_in, z_in, h_in = state if state is not None else (None, None, None)
+    S = z = h = None
+    if want_state:
+        S = torch.empty((B, H, d, d), dtype=torch.float32, device=q.device)
+        z = torch.empty((B, H, d), dtype=torch.float32, device=q.device)
+        h = torch.empty((B, H, max(Kc - 1, 0), d), dtype=q.dtype, device=q.device)
+    nbytes = linattn_workspace_bytes(desc, L)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device) if nbytes else None
+    linattn_prefill(desc, L, q, k, v, conv_w, S_in, z_in, h_in, out, S, z, h, ws, nbytes, stream)
+    return out, (S, z, h)
+
+
+def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None):
+    """q, k, v: dense [B,H,kk,d].  ``state`` = (S, z, hist) is updated in place.  Returns out."""
+    B, H, kk, d = q.shape
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=kk)
+    out = torch.empty_like(q)
+    S, z, h = state
+    linattn_verify(desc, kk, q, k, v, conv_w, S, z, h, n_commit, out, stream)
+    return out
+
+
+def decode(q, k, v, conv_w, state, eps=0.0, stream=None):
+    """q, k, v: dense [B,H,d] (or [B,H,1,d]).  ``state`` is updated in place.  Returns out."""
+    B, H, d = q.shape[0], q.shape[1], q.shape[-1]
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=1)
+    out = torch.empty_like(q)
+    S, z, h = state
+    linattn_decode(desc, q, k, v, conv_w, S, z, h, out, stream)
+    return out

@@ -1,0 +1,147 @@
+// C ABI (include/linattn.h): argument validation, launch planning, dispatch.
+// No device memory is allocated here and nothing is kept between calls.
+#include "../../include/linattn.h"
+
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+using namespace linattn;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+linattn_status check_desc(const linattn_desc* d, bool prefill) {
+  if (!d) return LINATTN_ERR_NULL;
+  if (d->io_dtype != LINATTN_F32 && d->io_dtype != LINATTN_BF16) return LINATTN_ERR_DTYPE;
+  if (d->phi != LINATTN_PHI_ELU1) return LINATTN_ERR_DTYPE;
+  if (d->B < 1 || d->H < 1) return LINATTN_ERR_SHAPE;
+  if ((int64_t)d->B * d->H > (int64_t)1 << 24) return LINATTN_ERR_SHAPE;
+  if (d->d != 64 && d->d != 128) return LINATTN_ERR_SHAPE;
+  if (d->conv_k < 1 || d->conv_k > LINATTN_MAX_CONV_K) return LINATTN_ERR_SHAPE;
+  if (!(d->eps >= 0.f)) return LINATTN_ERR_SHAPE;
+  if (prefill) {
+    if (d->chunk != 64 && d->chunk != 128) return LINATTN_ERR_SHAPE;
+    if (d->stride_t < d->d || d->stride_h < 0 || d->stride_b < 0) return LINATTN_ERR_SHAPE;
+    if ((d->stride_t | d->stride_h | d->stride_b) & 7) return LINATTN_ERR_SHAPE;
+  }
+  return LINATTN_OK;
+}
+
+struct PrefillPlan {
+  bool mfma;
+  int nseg, seg_len;
+  size_t ws_bytes;
+};
+
+// How a prefill call is laid out on the chip.  fp32 inputs go to the vector-ALU
+// kernel (exact fp32 products).  bf16 inputs go to the matrix-core kernel; when
+// B*H alone cannot fill the 256 compute units the sequence axis is cut into
+// segments whose start states come from a first pass over K, V and a scan.
+PrefillPlan plan_prefill(const linattn_desc* d, int32_t L) {
+  PrefillPlan p{};
+  p.mfma = d->io_dtype == LINATTN_BF16;
+  p.nseg = 1;
+  p.seg_len = L;
+  if (p.mfma && L > 0) {
+    p.nseg = prefill_mfma_pick_segments(d->B * d->H, L, d->chunk);
+    const int chunks = (L + d->chunk - 1) / d->chunk;
+    const int cps = (chunks + p.nseg - 1) / p.nseg;
+    p.seg_len = cps * d->chunk;
+    p.nseg = (L + p.seg_len - 1) / p.seg_len;
+  }
+  p.ws_bytes = p.mfma ? prefill_mfma_workspace_bytes(d->B * d->H, d->d, p.nseg) : 0;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* linattn_status_string(linattn_status s) {
+  switch (s) {
+    case LINATTN_OK: return "ok";
+    case LINATTN_ERR_NULL: return "a required pointer is NULL";
+    case LINATTN_ERR_SHAPE: return "invalid shape, size or stride";
+    case LINATTN_ERR_DTYPE: return "unknown dtype or feature map";
+    case LINATTN_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case LINATTN_ERR_UNSUPPORTED: return "no kernel for this request";
+    case LINATTN_ERR_WORKSPACE: return "workspace missing or too small";
+    case LINATTN_ERR_HIP: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+int32_t linattn_version(void) { return 100; }
+
+size_t linattn_workspace_bytes(const linattn_desc* desc, int32_t L) {
+  if (check_desc(desc, true) != LINATTN_OK || L < 0) return 0;
+  return plan_prefill(desc, L).ws_bytes;
+}
+
+linattn_status linattn_prefill(const linattn_desc* desc, int32_t L, const void* q, const void* k, const void* v,
+                               const float* conv_w, const float* S_in, const float* z_in, const void* hist_in,
+                               void* out, float* S_out, float* z_out, void* hist_out, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  linattn_status st = check_desc(desc, true);
+  if (st != LINATTN_OK) return st;
+  if (L < 0) return LINATTN_ERR_SHAPE;
+  if (!conv_w) return LINATTN_ERR_NULL;
+  if (L > 0 && (!q || !k || !v || !out)) return LINATTN_ERR_NULL;
+  const bool has_hist = desc->conv_k > 1;
+  const int given = (S_in != nullptr) + (z_in != nullptr) + ((hist_in != nullptr) || !has_hist);
+  const bool cont = S_in != nullptr || z_in != nullptr || hist_in != nullptr;
+  if (cont && given != 3) return LINATTN_ERR_NULL;   // all of the incoming state, or none of it
+  const void* ptrs[] = {q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, workspace};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LINATTN_ERR_ALIGN;
+  // the last token of the last (b, h) must be addressable with 64-bit offsets
+  if ((double)desc->stride_b * desc->B + (double)desc->stride_h * desc->H + (double)desc->stride_t * L > 9.0e18)
+    return LINATTN_ERR_SHAPE;
+  const PrefillPlan plan = plan_prefill(desc, L);
+  if (plan.ws_bytes > 0 && (!workspace || workspace_bytes < plan.ws_bytes)) return LINATTN_ERR_WORKSPACE;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  PrefillArgs a{};
+  a.q = q; a.k = k; a.v = v; a.conv_w = conv_w;
+  a.S_in = S_in; a.z_in = z_in; a.hist_in = has_hist ? hist_in : nullptr;
+  a.out = out; a.S_out = S_out; a.z_out = z_out; a.hist_out = has_hist ? hist_out : nullptr;
+  a.ws = static_cast<float*>(workspace);
+  a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = desc->conv_k; a.eps = desc->eps;
+  a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
+  a.nseg = plan.nseg; a.seg_len = plan.seg_len;
+  hipError_t e;
+  if (plan.mfma && L > 0) e = launch_prefill_mfma(a, desc->d, desc->chunk, stream);
+  else e = launch_prefill_simt(a, desc->io_dtype == LINATTN_BF16, desc->d, stream);
+  return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
+}
+
+linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* q, const void* k, const void* v,
+                              const float* conv_w, float* S, float* z, void* hist, const int32_t* n_commit,
+                              void* out, void* hip_stream) {
+  linattn_status st = check_desc(desc, false);
+  if (st != LINATTN_OK) return st;
+  if (kk < 1 || kk > LINATTN_MAX_DRAFT) return LINATTN_ERR_SHAPE;
+  if (!q || !k || !v || !conv_w || !S || !z || !out) return LINATTN_ERR_NULL;
+  if (desc->conv_k > 1 && !hist) return LINATTN_ERR_NULL;
+  const void* ptrs[] = {q, k, v, conv_w, S, z, hist, out};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LINATTN_ERR_ALIGN;
+  if (n_commit && (reinterpret_cast<uintptr_t>(n_commit) & 3u)) return LINATTN_ERR_ALIGN;
+
+  VerifyArgs a{};
+  a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;
+  a.n_commit = n_commit; a.out = out;
+  a.B = desc->B; a.H = desc->H; a.kk = kk; a.Kc = desc->conv_k; a.eps = desc->eps;
+  const int nsplit = verify_pick_split(desc->B * desc->H);
+  hipError_t e = launch_verify(a, desc->io_dtype == LINATTN_BF16, desc->d, nsplit, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
+}
+
+linattn_status linattn_decode(const linattn_desc* desc, const void* q, const void* k, const void* v,
+                              const float* conv_w, float* S, float* z, void* hist, void* out, void* hip_stream) {
+  return linattn_verify(desc, 1, q, k, v, conv_w, S, z, hist, nullptr, out, hip_stream);
+}
+
+}  // extern "C"

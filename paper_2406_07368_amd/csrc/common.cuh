@@ -1,0 +1,90 @@
+// Shared device helpers for the gfx950 kernels: vector types, bf16 <-> fp32,
+// the feature map, and typed 8-element global loads/stores.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace linattn {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+// phi(x) = elu(x) + 1 (Sec. 3: kernel embedding of queries and keys; elu+1 is
+// the embedding of the kernelised attention the paper builds on).
+__device__ __forceinline__ float phi_elu1(float x) { return x > 0.f ? x + 1.f : __expf(x); }
+// Same value, branch-free: max(x,0) + min(2^(x*log2 e), 1).
+__device__ __forceinline__ float phi_elu1_fast(float x) {
+  float e = __builtin_amdgcn_exp2f(x * 1.44269504088896340736f);
+  return fmaxf(x, 0.f) + fminf(e, 1.f);
+}
+
+__device__ __forceinline__ float bf16_lo_to_f32(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi_to_f32(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// Two floats -> packed bf16 pair, round-to-nearest-even (v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2 x = {lo, hi};
+  bf16x2 y = __builtin_convertvector(x, bf16x2);
+  return __builtin_bit_cast(uint32_t, y);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  return (uint16_t)(pack_bf16x2(f, 0.f) & 0xffffu);
+}
+
+// ---- typed access to rows of q/k/v/out/hist ------------------------------------
+// IoF32 / IoBf16: load `8 consecutive elements` as floats, store 8 floats.
+struct IoF32 {
+  typedef float elem;
+  static __device__ __forceinline__ void load8(const void* base, int64_t idx, float (&x)[8]) {
+    const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + idx);
+    f32x4 a = p[0], b = p[1];
+    x[0] = a[0]; x[1] = a[1]; x[2] = a[2]; x[3] = a[3];
+    x[4] = b[0]; x[5] = b[1]; x[6] = b[2]; x[7] = b[3];
+  }
+  static __device__ __forceinline__ void store8(void* base, int64_t idx, const float (&x)[8]) {
+    f32x4* p = reinterpret_cast<f32x4*>(static_cast<float*>(base) + idx);
+    p[0] = f32x4{x[0], x[1], x[2], x[3]};
+    p[1] = f32x4{x[4], x[5], x[6], x[7]};
+  }
+  static __device__ __forceinline__ float load1(const void* base, int64_t idx) {
+    return static_cast<const float*>(base)[idx];
+  }
+  static __device__ __forceinline__ void store1(void* base, int64_t idx, float x) {
+    static_cast<float*>(base)[idx] = x;
+  }
+};
+
+struct IoBf16 {
+  typedef uint16_t elem;
+  static __device__ __forceinline__ void load8(const void* base, int64_t idx, float (&x)[8]) {
+    u32x4 r = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + idx);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = bf16_lo_to_f32(r[i]);
+      x[2 * i + 1] = bf16_hi_to_f32(r[i]);
+    }
+  }
+  static __device__ __forceinline__ void store8(void* base, int64_t idx, const float (&x)[8]) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = pack_bf16x2(x[2 * i], x[2 * i + 1]);
+    *reinterpret_cast<u32x4*>(static_cast<uint16_t*>(base) + idx) = r;
+  }
+  static __device__ __forceinline__ float load1(const void* base, int64_t idx) {
+    return bf16_bits_to_f32(static_cast<const uint16_t*>(base)[idx]);
+  }
+  static __device__ __forceinline__ void store1(void* base, int64_t idx, float x) {
+    static_cast<uint16_t*>(base)[idx] = f32_to_bf16_bits(x);
+  }
+};
+
+}  // namespace linattn

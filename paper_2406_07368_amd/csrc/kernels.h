@@ -1,0 +1,55 @@
+// Internal launch interfaces between the C-ABI layer (api.hip) and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace linattn {
+
+struct VerifyArgs {
+  const void* q;
+  const void* k;
+  const void* v;            // [B,H,kk,d] dense, i/o dtype
+  const float* conv_w;      // [H,d,Kc]
+  float* S;                 // [B,H,d,d] in/out
+  float* z;                 // [B,H,d]   in/out
+  void* hist;               // [B,H,Kc-1,d] in/out, i/o dtype
+  const int32_t* n_commit;  // device [B] or null
+  void* out;                // [B,H,kk,d]
+  int B, H, kk, Kc;
+  float eps;
+};
+
+struct PrefillArgs {
+  const void* q;
+  const void* k;
+  const void* v;            // [B,H,L,d] by strides
+  const float* conv_w;      // [H,d,Kc]
+  const float* S_in;        // null = zeros
+  const float* z_in;
+  const void* hist_in;
+  void* out;
+  float* S_out;             // null = not wanted
+  float* z_out;
+  void* hist_out;
+  float* ws;                // [B*H][nseg][d*d + d] floats (segment start states), then staged history rows
+  int B, H, L, Kc;
+  float eps;
+  int64_t sb, sh, st;       // element strides of q, k, v, out
+  int nseg;                 // workgroups along the sequence axis per (b, h)
+  int seg_len;              // tokens per segment (multiple of the chunk size)
+};
+
+// verify.hip
+int verify_pick_split(int BH);
+hipError_t launch_verify(const VerifyArgs& a, bool bf16, int d, int nsplit, hipStream_t st);
+
+// prefill_simt.hip : fp32 arithmetic on the vector ALUs, one workgroup per (b, h)
+hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st);
+
+// prefill_mfma.hip : bf16 operands on the matrix cores, fp32 accumulation
+int prefill_mfma_pick_segments(int BH, int L, int chunk);
+size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg);
+hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, hipStream_t st);
+
+}  // namespace linattn

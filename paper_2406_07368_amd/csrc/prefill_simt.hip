@@ -1,0 +1,162 @@
+// Prefill with fp32 arithmetic on the vector ALUs (Sec. 4.1: groups of tokens,
+// masked in-group product, running (S, z) between groups).  One workgroup of 256
+// threads walks one (b, h) in steps of 32 tokens with the whole d x d state in
+// LDS.  This is the path for fp32 inputs, where every product has to be an exact
+// fp32 multiply-add to meet a 1e-4 bound; it is not tuned for throughput.
+#include "common.cuh"
+#include "kernels.h"
+
+namespace linattn {
+
+namespace {
+constexpr int TC = 32;     // tokens per step (the result does not depend on the grouping)
+constexpr int HMAX = 7;    // history rows kept in LDS: enough for the largest conv kernel (8 taps)
+
+template <int D>
+struct SimtLayout {
+  static constexpr int S = 0;                         // [D][D]
+  static constexpr int FQ = S + D * D;                // [TC][D+1]
+  static constexpr int FK = FQ + TC * (D + 1);        // [TC][D+1]
+  static constexpr int VV = FK + TC * (D + 1);        // [HMAX+TC][D]: history rows, then the step's rows
+  static constexpr int P = VV + (HMAX + TC) * D;      // [TC][TC+1]
+  static constexpr int DEN = P + TC * (TC + 1);       // [TC]
+  static constexpr int ZZ = DEN + TC;                 // [D]
+  static constexpr int TOTAL = ZZ + D;
+};
+}  // namespace
+
+template <typename Io, int D>
+__global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
+  using Lay = SimtLayout<D>;
+  constexpr int NG = 256 / D;
+  extern __shared__ float sm[];
+  float* S = sm + Lay::S;
+  float* fq = sm + Lay::FQ;
+  float* fk = sm + Lay::FK;
+  float* vv = sm + Lay::VV;
+  float* P = sm + Lay::P;
+  float* den = sm + Lay::DEN;
+  float* zz = sm + Lay::ZZ;
+
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
+  const int Kc = a.Kc, L = a.L;
+  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const int c = tid % D, tg = tid / D;
+
+  float wreg[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) wreg[j] = j < Kc ? a.conv_w[((size_t)h * D + c) * Kc + j] : 0.f;
+
+  for (int e = tid; e < D * D; e += 256) S[e] = a.S_in ? a.S_in[(size_t)bh * D * D + e] : 0.f;
+  if (tid < D) zz[tid] = a.z_in ? a.z_in[(size_t)bh * D + tid] : 0.f;
+  for (int e = tid; e < HMAX * D; e += 256) {
+    const int row = e / D, cc = e % D;
+    const int r = row - (HMAX - (Kc - 1));   // row of the incoming history, oldest first
+    vv[e] = (r >= 0 && a.hist_in) ? Io::load1(a.hist_in, ((int64_t)bh * (Kc - 1) + r) * D + cc) : 0.f;
+  }
+  __syncthreads();
+
+  for (int t0 = 0; t0 < L; t0 += TC) {
+    const int nt = (L - t0) < TC ? (L - t0) : TC;
+    // a. rows of this step, feature map applied; rows past the end are zeros
+    for (int c8 = tid; c8 < TC * (D / 8); c8 += 256) {
+      const int t = c8 / (D / 8), i0 = (c8 % (D / 8)) * 8;
+      float xq[8], xk[8], xv[8];
+      if (t < nt) {
+        const int64_t off = base + (int64_t)(t0 + t) * a.st + i0;
+        Io::load8(a.q, off, xq);
+        Io::load8(a.k, off, xk);
+        Io::load8(a.v, off, xv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { xq[e] = phi_elu1(xq[e]); xk[e] = phi_elu1(xk[e]); }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { xq[e] = 0.f; xk[e] = 0.f; xv[e] = 0.f; }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        fq[t * (D + 1) + i0 + e] = xq[e];
+        fk[t * (D + 1) + i0 + e] = xk[e];
+        vv[(HMAX + t) * D + i0 + e] = xv[e];
+      }
+    }
+    __syncthreads();
+    // b. masked in-step scores P[t][s] = phi(q_t).phi(k_s), s <= t
+    for (int p = tid; p < TC * TC; p += 256) {
+      const int t = p / TC, s = p % TC;
+      float acc = 0.f;
+      if (s <= t && t < nt) {
+        const float* x = fq + t * (D + 1);
+        const float* y = fk + s * (D + 1);
+#pragma unroll 8
+        for (int i = 0; i < D; ++i) acc = fmaf(x[i], y[i], acc);
+      }
+      P[t * (TC + 1) + s] = acc;
+    }
+    __syncthreads();
+    if (tid < nt) {
+      float dsum = a.eps;
+      for (int s = 0; s <= tid; ++s) dsum += P[tid * (TC + 1) + s];
+      const float* x = fq + tid * (D + 1);
+      float dz = 0.f;
+      for (int i = 0; i < D; ++i) dz = fmaf(x[i], zz[i], dz);
+      den[tid] = dsum + dz;
+    }
+    __syncthreads();
+    // c. outputs: in-step part + carried state, normalised, plus the causal conv
+    for (int t = tg; t < nt; t += NG) {
+      float num = 0.f;
+      for (int s = 0; s <= t; ++s) num = fmaf(P[t * (TC + 1) + s], vv[(HMAX + s) * D + c], num);
+      const float* x = fq + t * (D + 1);
+#pragma unroll 8
+      for (int i = 0; i < D; ++i) num = fmaf(x[i], S[i * D + c], num);
+      float u = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (j < Kc) u = fmaf(wreg[j], vv[(HMAX + t - j) * D + c], u);
+      Io::store1(a.out, base + (int64_t)(t0 + t) * a.st + c, num / den[t] + u);
+    }
+    __syncthreads();
+    // d. carry: S += phi(K)^T V, z += colsum phi(K); history slides forward by nt rows
+    for (int i = tg; i < D; i += NG) {
+      float acc = S[i * D + c];
+      for (int s = 0; s < nt; ++s) acc = fmaf(fk[s * (D + 1) + i], vv[(HMAX + s) * D + c], acc);
+      S[i * D + c] = acc;
+    }
+    if (tid < D) {
+      float zs = zz[tid];
+      for (int s = 0; s < nt; ++s) zs += fk[s * (D + 1) + tid];
+      zz[tid] = zs;
+      for (int r = 0; r < HMAX; ++r) vv[r * D + tid] = vv[(r + nt) * D + tid];
+    }
+    __syncthreads();
+  }
+
+  if (a.S_out)
+    for (int e = tid; e < D * D; e += 256) a.S_out[(size_t)bh * D * D + e] = S[e];
+  if (a.z_out && tid < D) a.z_out[(size_t)bh * D + tid] = zz[tid];
+  if (a.hist_out)
+    for (int e = tid; e < (Kc - 1) * D; e += 256) {
+      const int r = e / D, cc = e % D;
+      Io::store1(a.hist_out, ((int64_t)bh * (Kc - 1) + r) * D + cc, vv[(HMAX - (Kc - 1) + r) * D + cc]);
+    }
+}
+
+template <typename Io, int D>
+static hipError_t launch_one(const PrefillArgs& a, hipStream_t st) {
+  constexpr size_t bytes = sizeof(float) * SimtLayout<D>::TOTAL;
+  auto kern = prefill_simt_kernel<Io, D>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H)), dim3(256), bytes, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st) {
+  if (bf16) return d == 128 ? launch_one<IoBf16, 128>(a, st) : launch_one<IoBf16, 64>(a, st);
+  return d == 128 ? launch_one<IoF32, 128>(a, st) : launch_one<IoF32, 64>(a, st);
+}
+
+}  // namespace linattn

@@ -1,0 +1,266 @@
+// Speculative verification / decode step (Sec. 4.2; decode = one draft that is
+// always kept).  Memory-bound: every head's fp32 state S (d x d) is read once
+// and, if any draft is accepted, written once; everything else is tiny.
+//
+// One workgroup of 256 threads owns the column slice S[:, c0 : c0+CW] of one
+// (b, h).  All of the slice is pulled into registers with 16-byte loads issued
+// before anything else (rows are contiguous, so a wave reads whole 128..512 B
+// row segments), the kk read-outs phi(q_j)^T S are accumulated from registers,
+// reduced across the threads that share a column group, completed with the
+// causal in-block term, normalised, joined with the convolution over
+// (history ++ drafts <= j), and then the accepted rank-1 updates are folded into
+// the registers and streamed back.
+#include "common.cuh"
+#include "kernels.h"
+
+namespace linattn {
+
+template <int D, int CW, int KP>
+struct VerifySmem {
+  float fq[D][KP];          // phi(q_j)[i], feature-major so one thread reads all drafts of its row
+  float fk[D][KP];          // phi(k_j)[i]
+  float vv[KP][CW];         // v_j[c0 + c]
+  float red[4][KP][CW];     // per-wave partial read-outs
+  float amat[KP][KP];       // phi(q_j).phi(k_j') for j' <= j, else 0
+  float den[KP];            // phi(q_j).z + sum_j' amat + eps
+  float zz[D];
+};
+
+template <typename Io, int D, int CW, int KP>
+__global__ __launch_bounds__(256) void verify_kernel(VerifyArgs a) {
+  constexpr int NSPLIT = D / CW;
+  constexpr int CG = CW / 4;          // float4 column groups per row slice
+  constexpr int RPP = 256 / CG;       // rows covered per pass
+  constexpr int NPASS = D / RPP;
+  static_assert(NPASS >= 1 && RPP * NPASS == D, "tile shape");
+  __shared__ VerifySmem<D, CW, KP> sm;
+
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.x / NSPLIT;
+  const int c0 = (blockIdx.x % NSPLIT) * CW;
+  const int b = bh / a.H, h = bh % a.H;
+  const int kk = a.kk, Kc = a.Kc;
+  const int cg = tid % CG, r0 = tid / CG;
+
+  // ---- 0. the state slice: all loads in flight before anything else -----------
+  float* Sg = a.S + (size_t)bh * D * D + c0 + 4 * cg;
+  f32x4 s[NPASS];
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) s[p] = *reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D);
+
+  // ---- 1. drafts -> LDS (phi applied), normaliser -> LDS -----------------------
+  const int64_t tok0 = (int64_t)bh * kk * D;
+  for (int c8 = tid; c8 < KP * (D / 8); c8 += 256) {
+    const int j = c8 / (D / 8), i0 = (c8 % (D / 8)) * 8;
+    float xq[8], xk[8];
+    if (j < kk) {
+      Io::load8(a.q, tok0 + (int64_t)j * D + i0, xq);
+      Io::load8(a.k, tok0 + (int64_t)j * D + i0, xk);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { xq[e] = phi_elu1(xq[e]); xk[e] = phi_elu1(xk[e]); }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { xq[e] = 0.f; xk[e] = 0.f; }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { sm.fq[i0 + e][j] = xq[e]; sm.fk[i0 + e][j] = xk[e]; }
+  }
+  for (int c8 = tid; c8 < KP * (CW / 8); c8 += 256) {
+    const int j = c8 / (CW / 8), cc = (c8 % (CW / 8)) * 8;
+    float xv[8];
+    if (j < kk) Io::load8(a.v, tok0 + (int64_t)j * D + c0 + cc, xv);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xv[e] = 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sm.vv[j][cc + e] = xv[e];
+  }
+  if (tid < D) sm.zz[tid] = a.z[(size_t)bh * D + tid];
+  int n = kk;
+  if (a.n_commit) { n = a.n_commit[b]; n = n < 0 ? 0 : (n > kk ? kk : n); }
+  __syncthreads();
+
+  // ---- 2. in-block scores and denominators ----------------------------------------
+  {
+    constexpr int NPAIR = KP * KP;
+    constexpr int TPP = (256 / NPAIR) > 64 ? 64 : (256 / NPAIR);   // threads per (j, j') pair
+    if (tid < NPAIR * TPP) {
+      const int pair = tid / TPP, sub = tid % TPP;
+      const int j = pair / KP, jp = pair % KP;
+      float acc = 0.f, dz = 0.f;
+      for (int i = sub; i < D; i += TPP) {
+        const float fqv = sm.fq[i][j];
+        acc += fqv * sm.fk[i][jp];
+        dz += fqv * sm.zz[i];
+      }
+#pragma unroll
+      for (int off = TPP / 2; off >= 1; off >>= 1) {
+        acc += __shfl_xor(acc, off);
+        dz += __shfl_xor(dz, off);
+      }
+      if (sub == 0) {
+        sm.amat[j][jp] = (jp <= j && j < kk) ? acc : 0.f;
+        if (jp == 0) sm.den[j] = dz;     // completed below
+      }
+    }
+  }
+
+  // ---- 3. read-outs phi(q_j)^T S from registers --------------------------------------
+  float acc[KP][4];
+#pragma unroll
+  for (int j = 0; j < KP; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[j][e] = 0.f;
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) {
+    const int i = p * RPP + r0;
+    float f[KP];
+    if constexpr (KP >= 4) {
+#pragma unroll
+      for (int g = 0; g < KP / 4; ++g) {
+        f32x4 t = *reinterpret_cast<const f32x4*>(&sm.fq[i][4 * g]);
+        f[4 * g] = t[0]; f[4 * g + 1] = t[1]; f[4 * g + 2] = t[2]; f[4 * g + 3] = t[3];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < KP; ++j) f[j] = sm.fq[i][j];
+    }
+#pragma unroll
+    for (int j = 0; j < KP; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[j][e] = fmaf(f[j], s[p][e], acc[j][e]);
+  }
+  // threads that share a column group sit CG lanes apart inside a wave
+#pragma unroll
+  for (int off = CG; off < kWave; off <<= 1)
+#pragma unroll
+    for (int j = 0; j < KP; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[j][e] += __shfl_xor(acc[j][e], off);
+  if ((tid % kWave) < CG) {
+    const int wv = tid / kWave;
+#pragma unroll
+    for (int j = 0; j < KP; ++j)
+      *reinterpret_cast<f32x4*>(&sm.red[wv][j][4 * cg]) = f32x4{acc[j][0], acc[j][1], acc[j][2], acc[j][3]};
+  }
+  __syncthreads();
+  if (tid < kk) {
+    float dsum = sm.den[tid] + a.eps;
+    for (int jp = 0; jp <= tid; ++jp) dsum += sm.amat[tid][jp];
+    sm.den[tid] = dsum;
+  }
+  __syncthreads();
+
+  // ---- 4. outputs: normalise, add the causal convolution -------------------------------
+  const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
+  for (int idx = tid; idx < kk * CW; idx += 256) {
+    const int j = idx / CW, c = idx % CW;
+    float num = sm.red[0][j][c] + sm.red[1][j][c] + sm.red[2][j][c] + sm.red[3][j][c];
+    for (int jp = 0; jp <= j; ++jp) num = fmaf(sm.amat[j][jp], sm.vv[jp][c], num);
+    const float* wrow = a.conv_w + ((size_t)h * D + c0 + c) * Kc;
+    float u = 0.f;
+    for (int t = 0; t < Kc; ++t) {
+      const int sidx = j - t;   // position in (history ++ drafts); < 0 reaches into the history
+      const float x = sidx >= 0 ? sm.vv[sidx][c]
+                                : Io::load1(a.hist, hist0 + (int64_t)(Kc - 1 + sidx) * D + c0 + c);
+      u = fmaf(wrow[t], x, u);
+    }
+    Io::store1(a.out, tok0 + (int64_t)j * D + c0 + c, num / sm.den[j] + u);
+  }
+
+  // ---- 5. fold the accepted drafts into the state and stream it back ----------------------
+  if (n == 0) return;   // uniform per workgroup: nothing accepted, state untouched
+  {
+    float vr[KP][4];
+#pragma unroll
+    for (int j = 0; j < KP; ++j) {
+      f32x4 t = *reinterpret_cast<const f32x4*>(&sm.vv[j][4 * cg]);
+      const bool keep = j < n;
+      vr[j][0] = keep ? t[0] : 0.f; vr[j][1] = keep ? t[1] : 0.f;
+      vr[j][2] = keep ? t[2] : 0.f; vr[j][3] = keep ? t[3] : 0.f;
+    }
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+      const int i = p * RPP + r0;
+#pragma unroll
+      for (int j = 0; j < KP; ++j) {
+        const float f = sm.fk[i][j];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[p][e] = fmaf(f, vr[j][e], s[p][e]);
+      }
+      *reinterpret_cast<f32x4*>(Sg + (size_t)i * D) = s[p];
+    }
+  }
+  if (NSPLIT == 1 && tid < D) {   // with several slices per head a separate launch updates z
+    float zs = sm.zz[tid];
+    for (int j = 0; j < n; ++j) zs += sm.fk[tid][j];
+    a.z[(size_t)bh * D + tid] = zs;
+  }
+  if (Kc > 1) {
+    __syncthreads();   // every conv read of the old history is done
+    for (int c = tid; c < CW; c += 256) {
+      for (int r = 0; r < Kc - 1; ++r) {
+        const int sidx = n - (Kc - 1) + r;   // position in (history ++ accepted drafts)
+        const int64_t dst = hist0 + (int64_t)r * D + c0 + c;
+        if (sidx >= 0) Io::store1(a.hist, dst, sm.vv[sidx][c]);
+        else Io::store1(a.hist, dst, Io::load1(a.hist, hist0 + (int64_t)(Kc - 1 + sidx) * D + c0 + c));
+      }
+    }
+  }
+}
+
+// z += sum of the accepted phi(k_j); used when a head's columns are split over
+// several workgroups (they all read the old z, so it cannot be updated by one of them).
+template <typename Io, int D>
+__global__ __launch_bounds__(256) void verify_z_kernel(VerifyArgs a) {
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  if (gid >= a.B * a.H * D) return;
+  const int bh = gid / D, i = gid % D;
+  const int b = bh / a.H;
+  int n = a.kk;
+  if (a.n_commit) { n = a.n_commit[b]; n = n < 0 ? 0 : (n > a.kk ? a.kk : n); }
+  if (n == 0) return;
+  float zs = a.z[gid];
+  for (int j = 0; j < n; ++j) zs += phi_elu1(Io::load1(a.k, ((int64_t)bh * a.kk + j) * D + i));
+  a.z[gid] = zs;
+}
+
+template <typename Io, int D, int CW>
+static hipError_t launch_kp(const VerifyArgs& a, hipStream_t st) {
+  const dim3 grid((unsigned)(a.B * a.H * (D / CW))), block(256);
+  if (a.kk <= 1) hipLaunchKernelGGL((verify_kernel<Io, D, CW, 1>), grid, block, 0, st, a);
+  else if (a.kk <= 4) hipLaunchKernelGGL((verify_kernel<Io, D, CW, 4>), grid, block, 0, st, a);
+  else if (a.kk <= 8) hipLaunchKernelGGL((verify_kernel<Io, D, CW, 8>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((verify_kernel<Io, D, CW, 16>), grid, block, 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (D / CW > 1) {
+    const int total = a.B * a.H * D;
+    hipLaunchKernelGGL((verify_z_kernel<Io, D>), dim3((total + 255) / 256), block, 0, st, a);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+template <typename Io, int D>
+static hipError_t launch_split(const VerifyArgs& a, int nsplit, hipStream_t st) {
+  if (nsplit <= 1) return launch_kp<Io, D, D>(a, st);
+  if (nsplit == 2) return launch_kp<Io, D, D / 2>(a, st);
+  return launch_kp<Io, D, D / 4>(a, st);
+}
+
+// Columns of a head are split over 1, 2 or 4 workgroups so that small B*H still
+// puts enough workgroups on the 256 compute units.
+int verify_pick_split(int BH) {
+  if (BH >= 768) return 1;
+  if (BH >= 384) return 2;
+  return 4;
+}
+
+hipError_t launch_verify(const VerifyArgs& a, bool bf16, int d, int nsplit, hipStream_t st) {
+  if (bf16) return d == 128 ? launch_split<IoBf16, 128>(a, nsplit, st) : launch_split<IoBf16, 64>(a, nsplit, st);
+  return d == 128 ? launch_split<IoF32, 128>(a, nsplit, st) : launch_split<IoF32, 64>(a, nsplit, st);
+}
+
+}  // namespace linattn

@@ -106,3 +106,19 @@ def random_state(wl: Workload, tokens: int, seed: int | None = None):
     z = (0.95 * tokens + rng.standard_normal((wl.B, wl.H, wl.d)) * (0.5 * tokens) ** 0.5).astype(np.float32)
     hist = round_to_io(rng.standard_normal((wl.B, wl.H, wl.conv_k - 1, wl.d)) * wl.scale, wl.io_dtype)
     return S, z, hist
+
+
+def prefill_tensors(wl: Workload, seed: int | None = None):
+    """Full-size variant of ``prefill_inputs``: torch CPU tensors already in the i/o dtype.
+
+    Same distribution and scale, drawn with ``torch.Generator`` (float32 normals, order Q, K, V)
+    because numpy's float64 stream is too slow and too large for the 10^8..10^9-element
+    workloads.  Conv weights come from ``conv_weights(default_rng(seed))`` as above.
+    """
+    s = wl.seed if seed is None else seed
+    g = torch.Generator(device="cpu").manual_seed(s)
+    shape = (wl.B, wl.H, wl.L, wl.d)
+    dt = torch_dtype(wl.io_dtype)
+    q, k, v = ((torch.randn(shape, generator=g, dtype=torch.float32) * wl.scale).to(dt) for _ in range(3))
+    w = torch.from_numpy(conv_weights(np.random.default_rng(s), wl.H, wl.d, wl.conv_k))
+    return q, k, v, w

@@ -1,0 +1,119 @@
+"""The C-ABI library: loads, exports what the header declares, refuses bad arguments.
+
+Runs without a GPU: every call made here is rejected by validation before anything
+could be enqueued.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2406_07368_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = open(os.path.join(ROOT, "include", "linattn.h")).read()
+P = 0x10000  # a 16-byte aligned non-null fake device address; never dereferenced on these paths
+
+
+def declared_symbols():
+    code = re.sub(r"/\*.*?\*/", "", HEADER, flags=re.S)
+    return sorted(set(re.findall(r"\b(linattn_[a-z_0-9]+)\s*\(", code)))
+
+
+def test_header_symbols_are_exported():
+    lib = binding.load()
+    names = declared_symbols()
+    assert set(names) == set(binding.SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert binding.load().linattn_version() >= 100
+    seen = {binding.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and binding.status_string(0) == "ok"
+    assert binding.status_string(99) == "unknown status"
+
+
+def good_desc(**kw):
+    d = binding.make_desc(2, 4, 128, 3, 64, L=256)
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def prefill_status(desc, L=256, **over):
+    lib = binding.load()
+    a = dict(q=P, k=P, v=P, conv_w=P, S_in=None, z_in=None, hist_in=None, out=P, S_out=P, z_out=P, hist_out=P,
+             ws=P, ws_bytes=1 << 40)
+    a.update(over)
+    return lib.linattn_prefill(ctypes.byref(desc) if desc is not None else None, L, a["q"], a["k"], a["v"],
+                               a["conv_w"], a["S_in"], a["z_in"], a["hist_in"], a["out"], a["S_out"], a["z_out"],
+                               a["hist_out"], a["ws"], a["ws_bytes"], None)
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("d", 96, 2), ("d", 0, 2), ("B", 0, 2), ("H", -1, 2), ("conv_k", 0, 2), ("conv_k", 9, 2),
+    ("chunk", 32, 2), ("io_dtype", 7, 3), ("phi", 1, 3), ("eps", -1.0, 2), ("eps", float("nan"), 2),
+    ("stride_t", 64, 2), ("stride_t", 132, 2), ("stride_h", 12, 2),
+])
+def test_prefill_rejects_bad_descriptor(field, value, status):
+    assert prefill_status(good_desc(**{field: value})) == status
+
+
+def test_prefill_rejects_bad_pointers_and_sizes():
+    d = good_desc()
+    assert prefill_status(None) == 1
+    assert prefill_status(d, L=-1) == 2
+    assert prefill_status(d, q=None) == 1
+    assert prefill_status(d, conv_w=None) == 1
+    assert prefill_status(d, out=None) == 1
+    assert prefill_status(d, v=P + 8) == 4
+    assert prefill_status(d, S_out=P + 4) == 4
+    # the incoming state is all-or-nothing
+    assert prefill_status(d, S_in=P) == 1
+    assert prefill_status(d, S_in=P, z_in=P) == 1
+
+
+def test_workspace_is_constant_in_L_and_checked():
+    lib = binding.load()
+    d = binding.make_desc(1, 32, 128, 5, 128, L=65536)
+    sizes = [binding.linattn_workspace_bytes(d, L) for L in (8192, 16384, 32768, 65536)]
+    assert len(set(sizes)) == 1, sizes
+    per_state = (128 * 128 + 128) * 4
+    # at most 64 segment start states per (b, h) plus 8 staged history rows
+    assert 0 < sizes[0] <= 32 * (64 * per_state + 8 * 128 * 2)
+    if sizes[0]:
+        assert prefill_status(d, L=65536, ws=None, ws_bytes=0) == 6
+        assert prefill_status(d, L=65536, ws=P, ws_bytes=sizes[0] - 1) == 6
+    bad = binding.make_desc(1, 32, 96, 5, 128, L=65536)
+    assert lib.linattn_workspace_bytes(ctypes.byref(bad), 65536) == 0
+
+
+def verify_status(desc, kk=4, **over):
+    lib = binding.load()
+    a = dict(q=P, k=P, v=P, conv_w=P, S=P, z=P, hist=P, n_commit=None, out=P)
+    a.update(over)
+    return lib.linattn_verify(ctypes.byref(desc) if desc is not None else None, kk, a["q"], a["k"], a["v"],
+                              a["conv_w"], a["S"], a["z"], a["hist"], a["n_commit"], a["out"], None)
+
+
+def test_verify_rejects_bad_arguments():
+    d = good_desc()
+    assert verify_status(None) == 1
+    assert verify_status(d, kk=0) == 2
+    assert verify_status(d, kk=17) == 2
+    assert verify_status(d, S=None) == 1
+    assert verify_status(d, hist=None) == 1
+    assert verify_status(d, z=P + 4) == 4
+    assert verify_status(d, n_commit=P + 2) == 4
+    assert verify_status(good_desc(d=32)) == 2
+    lib = binding.load()
+    assert lib.linattn_decode(ctypes.byref(d), P, None, P, P, P, P, P, P, None) == 1
+
+
+def test_binding_raises_on_refusal():
+    with pytest.raises(binding.LinattnError) as ei:
+        binding.linattn_verify(good_desc(), 0, P, P, P, P, P, P, P, None, P, stream=0)
+    assert ei.value.status == 2
