@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the linear-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One *step* is one pass over every stage of the path on synthetic, seeded inputs
+already resident in HBM:
+
+    linattn_prefill   LLaMA-2-7B layer shape  B8 H32 L4096 d128 bf16, chunk 64, Kc 3
+    linattn_verify    B32 H32 d128, fp32 state, k = 8 drafts  (state updated in place)
+    linattn_verify    same, k = 4
+    linattn_decode    same, one token
+
+The headline ``value`` is prefill tokens/s (B*L divided by the mean duration of the
+prefill launches, measured with events on the launch stream inside the timed
+region); the verify/decode step times are reported beside it in microseconds with
+their own HBM roofline.  Between steps the verify state rotates over 32 separate
+state sets (2.1 GB) and the prefill inputs over 2 sets (2.1 GB) so that nothing is
+served from the 256 MB last-level cache.
+
+Prints ONE JSON line.  ``roofline`` is for the dominant kernel (prefill):
+algorithmic bytes per launch / measured mean launch duration against 8 TB/s.
+``cpu_baseline`` is the fp64 CPU oracle timed on this machine's host cores on a
+bounded sample of the same prefill workload: a baseline, not a target.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2406_07368_amd import binding, workloads  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix throughput
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--only", choices=["all", "prefill", "verify"], default="all",
+                    help="restrict the step to one stage (for profiling runs)")
+    ap.add_argument("--state-sets", type=int, default=32)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (reference dispatch for counter scaling)")
+    return ap.parse_args()
+
+
+def prefill_bytes(wl):
+    """Algorithmic HBM bytes of one prefill call: read Q, K, V, write out (state and weights are negligible)."""
+    return 4 * wl.B * wl.H * wl.L * wl.d * 2
+
+
+def prefill_flops(wl):
+    """Per head-token: 2(C+1)d + 4d^2 (causal count) and 4Cd + 4d^2 (full tiles)."""
+    ht = wl.B * wl.H * wl.L
+    return ht * (2 * (wl.chunk + 1) * wl.d + 4 * wl.d * wl.d), ht * (4 * wl.chunk * wl.d + 4 * wl.d * wl.d)
+
+
+def verify_bytes(wl, kk):
+    """S and z read and written once, q/k/v read, out written, history read and written."""
+    heads = wl.B * wl.H
+    state = heads * (wl.d * wl.d + wl.d) * 4 * 2
+    io = heads * kk * wl.d * 2 * 4
+    hist = heads * (wl.conv_k - 1) * wl.d * 2 * 2
+    return state + io + hist
+
+
+def read_traffic(name):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary is committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(wl, seconds):
+    """The oracle as it stands, all host threads, on whole heads of the prefill workload."""
+    import oracle
+    threads = oracle.num_threads()
+    rng = np.random.default_rng(wl.seed)
+
+    def run(heads):
+        shp = (1, heads, wl.L, wl.d)
+        q, k, v = (workloads.round_to_io(rng.standard_normal(shp) * wl.scale, wl.io_dtype) for _ in range(3))
+        w = workloads.conv_weights(rng, heads, wl.d, wl.conv_k)
+        t0 = time.perf_counter()
+        oracle.prefill_recurrent(q, k, v, w)
+        return time.perf_counter() - t0
+
+    t_probe = run(threads)                                   # one head per thread
+    heads = int(max(threads, min(wl.B * wl.H, threads * round(seconds / max(t_probe, 1e-3)))))
+    heads -= heads % threads
+    t = run(heads)
+    head_tokens_per_s = heads * wl.L / t
+    return {"value": head_tokens_per_s / wl.H, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"{heads} of {wl.B * wl.H} heads x L={wl.L} (fp64 recurrent form), {t:.1f} s; "
+                      f"scaled to a {wl.H}-head layer"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    binding.load()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.Stream(device=dev)
+
+    pw = workloads.CONFIGS["cfg3_llama7b_prefill"]
+    vw = workloads.CONFIGS["cfg4_llama7b_verify"]
+    do_prefill = args.only in ("all", "prefill")
+    do_verify = args.only in ("all", "verify")
+
+    # ---- inputs, resident in HBM before anything is timed -------------------------------------------
+    g = torch.Generator(device=dev).manual_seed(pw.seed)
+    n_in = 2 if do_prefill else 0
+    pin = []
+    for _ in range(n_in):
+        q, k, v = ((torch.randn((pw.B, pw.H, pw.L, pw.d), generator=g, device=dev) * pw.scale).to(torch.bfloat16)
+                   for _ in range(3))
+        pin.append((q, k, v, torch.empty_like(q)))
+    pwts = torch.from_numpy(workloads.conv_weights(np.random.default_rng(pw.seed), pw.H, pw.d, pw.conv_k)).to(dev)
+    pdesc = binding.make_desc(pw.B, pw.H, pw.d, pw.conv_k, pw.chunk, torch.bfloat16, L=pw.L)
+    ws_bytes = binding.linattn_workspace_bytes(pdesc, pw.L)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    S_out = torch.empty((pw.B, pw.H, pw.d, pw.d), device=dev)
+    z_out = torch.empty((pw.B, pw.H, pw.d), device=dev)
+    h_out = torch.empty((pw.B, pw.H, pw.conv_k - 1, pw.d), device=dev, dtype=torch.bfloat16)
+
+    vwts = torch.from_numpy(workloads.conv_weights(np.random.default_rng(vw.seed), vw.H, vw.d, vw.conv_k)).to(dev)
+    vdesc = binding.make_desc(vw.B, vw.H, vw.d, vw.conv_k, vw.chunk, torch.bfloat16, L=1)
+    states, drafts = [], {}
+    if do_verify:
+        # one real state from the 2048-token prefix, then copies with a small seeded perturbation
+        q, k, v, _ = workloads.prefill_tensors(vw)
+        _, st0 = binding.prefill(q.to(dev), k.to(dev), v.to(dev), vwts, chunk=vw.chunk)
+        del q, k, v
+        for i in range(args.state_sets):
+            S = st0[0] * (1.0 + 0.001 * i)
+            states.append((S, st0[1].clone(), st0[2].clone()))
+        for kk in (8, 4, 1):
+            dq, dk, dv = (torch.from_numpy(a).to(torch.bfloat16).to(dev) for a in workloads.draft_block(vw, kk))
+            drafts[kk] = (dq, dk, dv, torch.empty_like(dq))
+    torch.cuda.synchronize()
+
+    ev = {name: [] for name in ("prefill", "verify8", "verify4", "decode")}
+
+    def timed(name, fn, record):
+        if record:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            ev[name].append((e0, e1))
+        else:
+            fn()
+
+    def step(i, record):
+        if do_prefill:
+            q, k, v, out = pin[i % len(pin)]
+            timed("prefill", lambda: binding.linattn_prefill(pdesc, pw.L, q, k, v, pwts, None, None, None, out,
+                                                             S_out, z_out, h_out, ws, ws_bytes, stream), record)
+        if do_verify:
+            # every call gets a state set of its own, so none finds its state in the last-level cache
+            for j, (name, kk) in enumerate((("verify8", 8), ("verify4", 4))):
+                S, z, h = states[(3 * i + j) % len(states)]
+                dq, dk, dv, o = drafts[kk]
+                timed(name, lambda: binding.linattn_verify(vdesc, kk, dq, dk, dv, vwts, S, z, h, None, o, stream), record)
+            S, z, h = states[(3 * i + 2) % len(states)]
+            dq, dk, dv, o = drafts[1]
+            timed("decode", lambda: binding.linattn_decode(vdesc, dq, dk, dv, vwts, S, z, h, o, stream), record)
+
+    for i in range(args.warmup):
+        step(i, False)
+    if args.copy_calibration:
+        with torch.cuda.stream(stream):
+            a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+            b = torch.empty_like(a)
+            b.copy_(a)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, True)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+
+    mean_ms = {n: (sum(a.elapsed_time(b) for a, b in lst) / len(lst)) for n, lst in ev.items() if lst}
+    min_ms = {n: min(a.elapsed_time(b) for a, b in lst) for n, lst in ev.items() if lst}
+
+    result = {
+        "metric": "linear-attn prefill tokens/s (LLaMA-7B layer shape) + spec-verify step us, % roofline",
+        "value": None, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms / args.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg3_llama7b_prefill B8 H32 L4096 d128 bf16 chunk64 Kc3 (prefill) + "
+                               "cfg4_llama7b_verify B32 H32 d128 fp32-state k=8,4,1 (verify/decode)",
+                   "step": "prefill + verify k=8 + verify k=4 + decode", "only": args.only},
+    }
+    if do_prefill:
+        t = mean_ms["prefill"] * 1e-3
+        nbytes = prefill_bytes(pw)
+        fc, fd = prefill_flops(pw)
+        result["value"] = pw.B * pw.L / t
+        result["prefill_ms"] = {"mean": mean_ms["prefill"], "min": min_ms["prefill"]}
+        result["roofline"] = {"bound": "hbm", "achieved": nbytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": nbytes / t / 1e9 / HBM_PEAK_GBS,
+                              "traffic": read_traffic("prefill_mfma_cfg3_pmc.txt"),
+                              "kernel": "prefill_mfma_kernel<128,64,4,false>", "algorithmic_bytes": nbytes}
+        result["mfma"] = {"tflops_causal": fc / t / 1e12, "tflops_dense_tiles": fd / t / 1e12,
+                          "peak": MFMA_BF16_PEAK_TFLOPS, "frac_causal": fc / t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                          "frac_dense_tiles": fd / t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                          "note": "HBM-bound op: at 1024 B and <= 98304 flop per head-token the HBM roof caps "
+                                  "the MFMA fraction near 0.31"}
+    if do_verify:
+        us = {}
+        roof = {}
+        for name, kk in (("verify8", 8), ("verify4", 4), ("decode", 1)):
+            t = mean_ms[name] * 1e-3
+            nb = verify_bytes(vw, kk)
+            us[f"k{kk}"] = {"mean": mean_ms[name] * 1e3, "min": min_ms[name] * 1e3}
+            roof[f"k{kk}"] = {"bound": "hbm", "achieved": nb / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": nb / t / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": nb,
+                              "traffic": read_traffic(f"verify_cfg4_k{kk}_pmc.txt")}
+        result["verify_us_per_step"] = us
+        result["roofline_verify"] = roof
+        if not do_prefill:
+            result["value"] = us["k8"]["mean"]
+            result["unit"] = "us/step (verify k=8)"
+            result["higher_is_better"] = False
+    if not args.no_cpu_baseline and do_prefill:
+        result["cpu_baseline"] = cpu_baseline(pw, args.cpu_seconds)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,55 @@
+// Helpers shared by the matrix-core prefill kernels: LDS fragment loads (row reads and the
+// gfx950 transpose reads), the 32x32x16 bf16 MFMA, accumulator -> bf16 operand packing.
+#pragma once
+#include "common.cuh"
+
+namespace linattn {
+
+constexpr int HALO = 8;   // value rows kept from the previous group for the conv taps (Kc-1 <= 7)
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+__device__ __forceinline__ bf16x8 lds_row8(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+__device__ __forceinline__ bf16x4 lds_row4(const uint16_t* p) { return *reinterpret_cast<const bf16x4*>(p); }
+
+__device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b) {
+  return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Transpose load: the 16 lanes of a block read a 4 x 16 tile (4 rows, 16 columns,
+// each lane 8 bytes of one row) and lane j receives column j of the 4 rows.
+__device__ __forceinline__ bf16x4 lds_tr4(const uint16_t* p) {
+  s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+  return __builtin_bit_cast(bf16x4, r);
+}
+
+// MFMA operand with lanes <-> 32 consecutive columns (col0 + lane%32) of a row-major
+// bf16 array and registers <-> rows row0 + 8*(lane/32) + 0..7.
+__device__ __forceinline__ bf16x8 tr_operand(const uint16_t* base, int stride, int row0, int col0, int lane) {
+  const int j = lane & 15;
+  const uint16_t* p = base + (row0 + 8 * (lane >> 5) + (j >> 2)) * stride + col0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
+  return cat4(lds_tr4(p), lds_tr4(p + 4 * stride));
+}
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& x, int o) {
+  u32x4 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r[i] = pack_bf16x2(x[o + 2 * i], x[o + 2 * i + 1]);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+
+// phi(x) = elu(x) + 1 as max(x + 1, min(2^(x log2 e), 1)): for x > 0 the clamped exponential is 1 < x + 1,
+// for x <= 0 the exponential is >= x + 1 (convexity), so the maximum picks the right branch without a select.
+__device__ __forceinline__ float phi_elu1_max(float x) {
+  const float e = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(x * 1.44269504088896340736f), 0.f, 1.f);
+  return fmaxf(x + 1.f, e);
+}
+
+}  // namespace linattn

@@ -8,29 +8,28 @@
 //      natural [token][feature] layout (bf16);
 //   2. the causal tiles of P^T = phi(K) phi(Q)^T are computed (32x32x16 MFMA),
 //      masked by select, rounded to bf16 and written to LDS as P[t][s];
-//   3. each wave forms O[:, its channels] = P V + phi(Q) S, where S is fed to the
-//      MFMA straight from the accumulator registers (the accumulator layout of
-//      S[i][c] is, up to a fixed permutation of i that is also applied to the
-//      phi(Q) operand, the B-operand layout), then S += phi(K)^T V;
-//      operands that need the token axis in registers (V, phi(K)^T) are fetched
-//      from the natural layout with the LDS transpose loads of gfx950;
-//   4. O is divided by the row normaliser, the causal convolution over V is added
-//      from LDS, and the result is stored.
+//   3. each wave forms O^T[its channels, :] = V^T P^T + S^T phi(Q)^T, where S^T is fed
+//      to the MFMA straight from the accumulator registers (the accumulator layout
+//      of S[i][c] is, up to a fixed permutation of i that is also applied to the
+//      phi(Q) operand, the A-operand layout), then S += phi(K)^T V; operands that
+//      need the token axis in registers (V, phi(K)^T) are fetched from the natural
+//      layout with the LDS transpose loads of gfx950;
+//   4. in the O^T accumulator a lane holds one token and 16 of the wave's channels,
+//      so the row normaliser is one reciprocal per lane; the causal convolution
+//      over V is added from LDS rows and the result is stored 8 bytes at a time.
 // The state is carried from group to group in registers; between segments of one
 // sequence (used when B*H alone cannot fill the chip) it is carried by a first pass
 // that reduces each segment's K, V to its state increment, a prefix sum over the
 // segments, and a second pass that starts every segment from its prefix.
+#include <type_traits>
+
 #include "common.cuh"
 #include "kernels.h"
+#include "mfma_util.cuh"
 
 namespace linattn {
 
 namespace {
-
-constexpr int HALO = 8;   // value rows kept from the previous group for the conv taps (Kc-1 <= 7)
-
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 
 template <int D, int C>
 struct Cfg {
@@ -41,61 +40,32 @@ struct Cfg {
   static constexpr int KSD = D / 16;         // MFMA K steps over the feature axis
   static constexpr int KSC = C / 16;         // MFMA K steps over the token axis
   static constexpr int NP = C / 16;          // load passes: 16 tokens x (NW*4) column groups per pass
-  static constexpr int QS = D + 8;           // row stride of phi(Q): 16-byte row reads only
-  static constexpr int KS = D + 16;          // row stride of phi(K) and V: mostly transpose reads
-  static constexpr int PS = C + 8;           // row stride of P
+  // LDS row strides in bf16 elements, chosen per array for the way it is read most:
+  static constexpr int QS = D + 4;           // phi(Q): 8-byte row reads, one row per lane
+  static constexpr int KS = D + 16;          // phi(K): transpose reads (4 rows x 32 B per 16 lanes)
+  static constexpr int VS = D + 4;           // V: 8-byte row reads by the conv, some transpose reads
+  static constexpr int PS = C + 8;           // P: 16-byte row reads
+  static constexpr int KCMAX = 8;            // conv weight rows kept in LDS
   static constexpr int NTILE = TB * (TB + 1) / 2;
   static constexpr int MAXT = (NTILE + NW - 1) / NW;
   // byte offsets into dynamic LDS
   static constexpr int OFF_QN = 0;
   static constexpr int OFF_KN = OFF_QN + C * QS * 2;
   static constexpr int OFF_VN = OFF_KN + C * KS * 2;
-  static constexpr int OFF_PN = OFF_VN + (HALO + C) * KS * 2;
+  static constexpr int OFF_PN = (OFF_VN + (HALO + C) * VS * 2 + 15) / 16 * 16;
   static constexpr int OFF_DENQ = OFF_PN + C * PS * 2;       // [NW][C] float: phi(q_t).z over each wave's features
   static constexpr int OFF_DENP = OFF_DENQ + NW * C * 4;     // [TB][C] float: row sums of P per source block
   static constexpr int OFF_ZZ = OFF_DENP + TB * C * 4;       // [2][D] float: normaliser, double-buffered
-  static constexpr int TOTAL = OFF_ZZ + 2 * D * 4;
+  static constexpr int OFF_WL = OFF_ZZ + 2 * D * 4;          // [KCMAX][D] float: conv taps, tap-major
+  static constexpr int TOTAL = OFF_WL + KCMAX * D * 4;
   static_assert(TOTAL <= 160 * 1024, "LDS budget");
 };
-
-__device__ __forceinline__ bf16x8 lds_row8(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
-
-__device__ __forceinline__ bf16x4 lds_row4(const uint16_t* p) { return *reinterpret_cast<const bf16x4*>(p); }
-
-__device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b) {
-  return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-// Transpose load: the 16 lanes of a block read a 4 x 16 tile (4 rows, 16 columns,
-// each lane 8 bytes of one row) and lane j receives column j of the 4 rows.
-__device__ __forceinline__ bf16x4 lds_tr4(const uint16_t* p) {
-  s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
-  return __builtin_bit_cast(bf16x4, r);
-}
-
-// MFMA operand with lanes <-> 32 consecutive columns (col0 + lane%32) of a row-major
-// bf16 array and registers <-> rows row0 + 8*(lane/32) + 0..7.
-__device__ __forceinline__ bf16x8 tr_operand(const uint16_t* base, int stride, int row0, int col0, int lane) {
-  const int j = lane & 15;
-  const uint16_t* p = base + (row0 + 8 * (lane >> 5) + (j >> 2)) * stride + col0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
-  return cat4(lds_tr4(p), lds_tr4(p + 4 * stride));
-}
-
-__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ bf16x8 pack8(const f32x16& x, int o) {
-  u32x4 r;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) r[i] = pack_bf16x2(x[o + 2 * i], x[o + 2 * i + 1]);
-  return __builtin_bit_cast(bf16x8, r);
-}
 
 }  // namespace
 
 // STATE_ONLY: reduce a segment's K, V to its state increment (first pass of the
-// segmented form); otherwise the full path.  KCM: compile-time bound on the conv taps.
+// segmented form); otherwise the full path.  KCM: number of conv taps evaluated
+// (taps >= Kc have zero weight).
 template <int D, int C, int KCM, bool STATE_ONLY>
 __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
   using G = Cfg<D, C>;
@@ -107,13 +77,14 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
   float* denq = reinterpret_cast<float*>(smem + G::OFF_DENQ);
   float* denp = reinterpret_cast<float*>(smem + G::OFF_DENP);
   float* zz = reinterpret_cast<float*>(smem + G::OFF_ZZ);
+  float* wl = reinterpret_cast<float*>(smem + G::OFF_WL);
 
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
   const int r16 = lane & 15;               // token within a 16-token load pass
   const int c0 = 8 * (4 * w + (lane >> 4));  // first of the 8 features/channels this thread loads
-  const int cw = 32 * w + l32;             // the channel this lane owns in phase 3
+  const int cw = 32 * w + l32;             // the channel this lane owns in the state accumulators
 
   const int nseg_grid = STATE_ONLY ? a.nseg - 1 : a.nseg;
   const int bh = blockIdx.x / nseg_grid, seg = blockIdx.x % nseg_grid;
@@ -128,8 +99,11 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
   uint16_t* gout = static_cast<uint16_t*>(a.out) + base;
   constexpr int SLOT = D * D + D;          // floats per stored state (S then z)
   float* ws_bh = a.ws + (size_t)bh * a.nseg * SLOT;
+  const uint16_t* staged_hist =
+      reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
   // ---- start state -------------------------------------------------------------------------
+  // Sacc[ib][r] = S[32ib + 8(r/4) + 4hi + r%4][cw]
   f32x16 Sacc[G::IB];
   {
     const float* Ssrc = nullptr;
@@ -148,25 +122,24 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
     if (tid < D) zz[tid] = zsrc ? zsrc[tid] : 0.f;
   }
 
-  float wreg[KCM];
   if (!STATE_ONLY) {
-#pragma unroll
-    for (int j = 0; j < KCM; ++j) wreg[j] = j < a.Kc ? a.conv_w[((size_t)h * D + cw) * a.Kc + j] : 0.f;
+    for (int e = tid; e < KCM * D; e += G::NT) {
+      const int j = e / D, cc = e % D;
+      wl[e] = j < a.Kc ? a.conv_w[((size_t)h * D + cc) * a.Kc + j] : 0.f;
+    }
     // value rows just before this segment: earlier tokens, else the incoming history, else zeros
-    const uint16_t* hsrc = nullptr;
-    if (a.hist_in) hsrc = a.nseg > 1 ? reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D
-                                     : static_cast<const uint16_t*>(a.hist_in) + (size_t)bh * (a.Kc - 1) * D;
     for (int e = tid; e < HALO * D; e += G::NT) {
       const int r = e / D, cc = e % D;
       const int tok = t_begin - HALO + r;
       uint16_t x = 0;
       if (tok >= 0) x = gv[(int64_t)tok * a.st + cc];
-      else if (hsrc) {
+      else if (a.hist_in) {
         // history rows are oldest first and end right before token 0
-        if (a.nseg > 1) x = hsrc[(size_t)(HALO + tok) * D + cc];            // staged copy: always HALO rows
-        else if (a.Kc - 1 + tok >= 0) x = hsrc[(size_t)(a.Kc - 1 + tok) * D + cc];
+        if (a.nseg > 1) x = staged_hist[(size_t)(HALO + tok) * D + cc];     // staged copy: always HALO rows
+        else if (a.Kc - 1 + tok >= 0)
+          x = static_cast<const uint16_t*>(a.hist_in)[((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + cc];
       }
-      Vn[r * G::KS + cc] = x;
+      Vn[r * G::VS + cc] = x;
     }
   }
 
@@ -188,9 +161,12 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
   if (nchunks > 0) prefetch(0);
   __syncthreads();
 
-  for (int ci = 0; ci < nchunks; ++ci) {
+  // One group of C tokens.  TAIL: the group may be short (rows past the end are zero-filled and
+  // their outputs are not stored); full groups skip those checks.
+  auto group = [&](int ci, auto tail_tag) {
+    constexpr bool TAIL = decltype(tail_tag)::value;
     const int tok0 = t_begin + ci * C;
-    const int nt = (t_end - tok0) < C ? (t_end - tok0) : C;
+    const int nt = TAIL ? (t_end - tok0) : C;
     float* zc = zz + (ci & 1) * D;
     float* zn = zz + ((ci + 1) & 1) * D;
 
@@ -202,27 +178,31 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
         const int t = 16 * p + r16;
-        const bool ok = t < nt;
+        const bool ok = !TAIL || t < nt;
         u32x4 kp, qp;
         float dsum = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           float k0 = phi_elu1_fast(bf16_lo_to_f32(rk[p][i])), k1 = phi_elu1_fast(bf16_hi_to_f32(rk[p][i]));
-          k0 = ok ? k0 : 0.f; k1 = ok ? k1 : 0.f;
+          if (TAIL) { k0 = ok ? k0 : 0.f; k1 = ok ? k1 : 0.f; }
           kp[i] = pack_bf16x2(k0, k1);
           zsum[2 * i] += k0; zsum[2 * i + 1] += k1;
           if (!STATE_ONLY) {
             float q0 = phi_elu1_fast(bf16_lo_to_f32(rq[p][i])), q1 = phi_elu1_fast(bf16_hi_to_f32(rq[p][i]));
-            q0 = ok ? q0 : 0.f; q1 = ok ? q1 : 0.f;
+            if (TAIL) { q0 = ok ? q0 : 0.f; q1 = ok ? q1 : 0.f; }
             qp[i] = pack_bf16x2(q0, q1);
             dsum = fmaf(q0, zcur[2 * i], dsum);
             dsum = fmaf(q1, zcur[2 * i + 1], dsum);
           }
         }
         *reinterpret_cast<u32x4*>(Kn + t * G::KS + c0) = kp;
-        *reinterpret_cast<u32x4*>(Vn + (HALO + t) * G::KS + c0) = rv[p];
+        u32x2* vrow = reinterpret_cast<u32x2*>(Vn + (HALO + t) * G::VS + c0);
+        vrow[0] = u32x2{rv[p][0], rv[p][1]};
+        vrow[1] = u32x2{rv[p][2], rv[p][3]};
         if (!STATE_ONLY) {
-          *reinterpret_cast<u32x4*>(Qn + t * G::QS + c0) = qp;
+          u32x2* qrow = reinterpret_cast<u32x2*>(Qn + t * G::QS + c0);
+          qrow[0] = u32x2{qp[0], qp[1]};
+          qrow[1] = u32x2{qp[2], qp[3]};
           dq[p] = dsum;
         }
       }
@@ -266,7 +246,8 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
           const uint16_t* ka = Kn + (32 * sb + l32) * G::KS + 8 * hi;
           const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 8 * hi;
 #pragma unroll
-          for (int ks = 0; ks < G::KSD; ++ks) acc = mfma(lds_row8(ka + 16 * ks), lds_row8(qb + 16 * ks), acc);
+          for (int ks = 0; ks < G::KSD; ++ks)
+            acc = mfma(lds_row8(ka + 16 * ks), cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4)), acc);
           // acc[r]: source token s = 32sb + 8(r/4) + 4hi + r%4, query token t = 32tb + l32
           float rs = 0.f;
 #pragma unroll
@@ -290,9 +271,10 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
     }
 
     // ---- 3. this wave's channels ---------------------------------------------------------------------
+    // vf[ks]: lanes <-> channels 32w + l32, registers <-> tokens 16ks + 8hi + 0..7
     bf16x8 vf[G::KSC];
 #pragma unroll
-    for (int ks = 0; ks < G::KSC; ++ks) vf[ks] = tr_operand(Vn + HALO * G::KS, G::KS, 16 * ks, 32 * w, lane);
+    for (int ks = 0; ks < G::KSC; ++ks) vf[ks] = tr_operand(Vn + HALO * G::VS, G::VS, 16 * ks, 32 * w, lane);
 
     if (!STATE_ONLY) {
       bf16x8 sbf[G::IB][2];
@@ -300,56 +282,50 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
       for (int ib = 0; ib < G::IB; ++ib) { sbf[ib][0] = pack8(Sacc[ib], 0); sbf[ib][1] = pack8(Sacc[ib], 8); }
 #pragma unroll
       for (int tb = 0; tb < G::TB; ++tb) {
+        // o[r] = O[token 32tb + l32][channel 32w + 8(r/4) + 4hi + r%4]
         f32x16 o;
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[r] = 0.f;
-        const uint16_t* pa = Pn + (32 * tb + l32) * G::PS + 8 * hi;
+        const uint16_t* pb = Pn + (32 * tb + l32) * G::PS + 8 * hi;
 #pragma unroll
-        for (int ks = 0; ks < 2 * (tb + 1); ++ks) o = mfma(lds_row8(pa + 16 * ks), vf[ks], o);
-        // phi(Q) S: register r of S holds feature 32ib + 8(r/4) + 4hi + r%4, so the phi(Q) operand
+        for (int ks = 0; ks < 2 * (tb + 1); ++ks) o = mfma(vf[ks], lds_row8(pb + 16 * ks), o);
+        // S^T phi(Q)^T: register r of S holds feature 32ib + 8(r/4) + 4hi + r%4, so the phi(Q) operand
         // takes features {16h2 + 4hi + 0..3, 16h2 + 8 + 4hi + 0..3} of block ib for MFMA step h2
-        const uint16_t* qa = Qn + (32 * tb + l32) * G::QS + 4 * hi;
+        const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 4 * hi;
 #pragma unroll
         for (int ib = 0; ib < G::IB; ++ib)
 #pragma unroll
           for (int h2 = 0; h2 < 2; ++h2) {
-            const uint16_t* p = qa + 32 * ib + 16 * h2;
-            o = mfma(cat4(lds_row4(p), lds_row4(p + 8)), sbf[ib][h2], o);
+            const uint16_t* p = qb + 32 * ib + 16 * h2;
+            o = mfma(sbf[ib][h2], cat4(lds_row4(p), lds_row4(p + 8)), o);
           }
-        // o[r]: token t = 32tb + 8(r/4) + 4hi + r%4, channel cw
+        // ---- 4. normalise, add the causal conv, store ---------------------------------------------------
+        const int t = 32 * tb + l32;
+        float den = a.eps;
+#pragma unroll
+        for (int ww = 0; ww < G::NW; ++ww) den += denq[ww * C + t];
+#pragma unroll
+        for (int sb = 0; sb <= tb; ++sb) den += denp[sb * C + t];
+        const float inv = __builtin_amdgcn_rcpf(den);
+        const uint16_t* vrow = Vn + (HALO + t) * G::VS + 32 * w + 4 * hi;
+        uint16_t* orow = gout + (int64_t)(tok0 + t) * a.st + 32 * w + 4 * hi;
+        const float* wrow = wl + 32 * w + 4 * hi;
+        const bool live = !TAIL || t < nt;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int t0 = 32 * tb + 8 * g + 4 * hi;
-          f32x4 den = *reinterpret_cast<const f32x4*>(denq + t0);
+          float u[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int ww = 1; ww < G::NW; ++ww) den += *reinterpret_cast<const f32x4*>(denq + ww * C + t0);
-#pragma unroll
-          for (int sb = 0; sb <= tb; ++sb) den += *reinterpret_cast<const f32x4*>(denp + sb * C + t0);
-          // conv window: value rows t0-8 .. t0+3 of channel cw (row -1 is the previous group's last token)
-          float x[12];
-          {
-            const int j = lane & 15;
-            const uint16_t* p = Vn + (HALO + t0 + (j >> 2)) * G::KS + 32 * w + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
-            const bf16x4 cur = lds_tr4(p), prv = lds_tr4(p - 4 * G::KS);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { x[8 + e] = (float)cur[e]; x[4 + e] = (float)prv[e]; }
-            if (KCM > 5) {
-              const bf16x4 pp = lds_tr4(p - 8 * G::KS);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) x[e] = (float)pp[e];
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) x[e] = 0.f;
-            }
+          for (int j = 0; j < KCM; ++j) {
+            const u32x2 xv = *reinterpret_cast<const u32x2*>(vrow - j * G::VS + 8 * g);
+            const f32x4 wv = *reinterpret_cast<const f32x4*>(wrow + j * D + 8 * g);
+            u[0] = fmaf(wv[0], bf16_lo_to_f32(xv[0]), u[0]);
+            u[1] = fmaf(wv[1], bf16_hi_to_f32(xv[0]), u[1]);
+            u[2] = fmaf(wv[2], bf16_lo_to_f32(xv[1]), u[2]);
+            u[3] = fmaf(wv[3], bf16_hi_to_f32(xv[1]), u[3]);
           }
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float u = 0.f;
-#pragma unroll
-            for (int j = 0; j < KCM; ++j) u = fmaf(wreg[j], x[8 + e - j], u);
-            const float y = o[4 * g + e] * __builtin_amdgcn_rcpf(den[e] + a.eps) + u;
-            if (t0 + e < nt) gout[(int64_t)(tok0 + t0 + e) * a.st + cw] = f32_to_bf16_bits(y);
-          }
+          const u32x2 y = {pack_bf16x2(fmaf(o[4 * g], inv, u[0]), fmaf(o[4 * g + 1], inv, u[1])),
+                           pack_bf16x2(fmaf(o[4 * g + 2], inv, u[2]), fmaf(o[4 * g + 3], inv, u[3]))};
+          if (live) *reinterpret_cast<u32x2*>(orow + 8 * g) = y;
         }
       }
     }
@@ -361,13 +337,20 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
       for (int ks = 0; ks < G::KSC; ++ks)
         Sacc[ib] = mfma(tr_operand(Kn, G::KS, 16 * ks, 32 * ib, lane), vf[ks], Sacc[ib]);
 
-    if (!STATE_ONLY && lane < 32) {
-      // keep the last HALO value rows of this wave's channels for the next group's conv taps
-      const int r = lane >> 2, piece = 8 * (lane & 3);
-      const u32x4 t = *reinterpret_cast<const u32x4*>(Vn + (C + r) * G::KS + 32 * w + piece);
-      *reinterpret_cast<u32x4*>(Vn + r * G::KS + 32 * w + piece) = t;
+    __syncthreads();   // C: every read of this group's rows is done
+    if (!STATE_ONLY && tid < HALO * D / 8) {
+      // keep the last HALO value rows for the next group's conv taps
+      const int r = tid / (D / 8), piece = 8 * (tid % (D / 8));
+      const u32x2* src = reinterpret_cast<const u32x2*>(Vn + (C + r) * G::VS + piece);
+      u32x2* dst = reinterpret_cast<u32x2*>(Vn + r * G::VS + piece);
+      const u32x2 t0 = src[0], t1 = src[1];
+      dst[0] = t0; dst[1] = t1;
     }
-    __syncthreads();   // C: LDS rows may be overwritten
+  };
+
+  for (int ci = 0; ci < nchunks; ++ci) {
+    if (t_begin + (ci + 1) * C <= t_end) group(ci, std::false_type{});
+    else group(ci, std::true_type{});
   }
 
   // ---- hand the state over -------------------------------------------------------------------------------
@@ -389,17 +372,16 @@ __global__ __launch_bounds__(D * 2) void prefill_mfma_kernel(PrefillArgs a) {
   if (zdst && tid < D) zdst[tid] = zfin[tid];
   if (!STATE_ONLY && seg == a.nseg - 1 && a.hist_out && tid < D) {
     // last Kc-1 value rows of (history ++ sequence); one thread per channel, rows in ascending
-    // order, so an aliased hist_in is read before it is overwritten
-    // (with segments the copy staged by the scan kernel is read instead of hist_in)
+    // order, so an aliased hist_in is read before it is overwritten (with segments the copy
+    // staged by the scan kernel is read instead of hist_in)
     const uint16_t* hin = static_cast<const uint16_t*>(a.hist_in);
     uint16_t* hout = static_cast<uint16_t*>(a.hist_out) + (size_t)bh * (a.Kc - 1) * D;
-    const uint16_t* staged = reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
     for (int r = 0; r < a.Kc - 1; ++r) {
       const int tok = a.L - (a.Kc - 1) + r;
       uint16_t x = 0;
       if (tok >= 0) x = gv[(int64_t)tok * a.st + tid];
-      else if (a.hist_in) x = a.nseg > 1 ? staged[(size_t)(HALO + tok) * D + tid]
-                                         : hin[((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + tid];
+      else if (hin) x = a.nseg > 1 ? staged_hist[(size_t)(HALO + tok) * D + tid]
+                                   : hin[((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + tid];
       hout[(size_t)r * D + tid] = x;
     }
   }
@@ -465,13 +447,17 @@ static hipError_t launch_dc(const PrefillArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((segment_scan_kernel<D>), dim3((SLOT + 255) / 256, (unsigned)BH), dim3(256), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
+  // full pass: the kernel with specialised loader/compute waves when its two row buffers fit in LDS
+  if (prefill_mfma_ws_available(D, C)) return launch_prefill_mfma_ws(a, D, C, st);
   hipLaunchKernelGGL(full, dim3((unsigned)(BH * a.nseg)), dim3(G::NT), G::TOTAL, st, a);
   return hipGetLastError();
 }
 
 template <int D, int C>
 static hipError_t launch_k(const PrefillArgs& a, hipStream_t st) {
-  return a.Kc <= 4 ? launch_dc<D, C, 4>(a, st) : launch_dc<D, C, 8>(a, st);
+  if (a.Kc <= 3) return launch_dc<D, C, 3>(a, st);
+  if (a.Kc <= 5) return launch_dc<D, C, 5>(a, st);
+  return launch_dc<D, C, 8>(a, st);
 }
 
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, hipStream_t st) {

@@ -10,6 +10,8 @@
 // causal in-block term, normalised, joined with the convolution over
 // (history ++ drafts <= j), and then the accepted rank-1 updates are folded into
 // the registers and streamed back.
+#include <stdlib.h>
+
 #include "common.cuh"
 #include "kernels.h"
 
@@ -25,6 +27,20 @@ struct VerifySmem {
   float den[KP];            // phi(q_j).z + sum_j' amat + eps
   float zz[D];
 };
+
+template <int KP>
+__device__ __forceinline__ void load_row(const float* row, float (&f)[KP]) {
+  if constexpr (KP >= 4) {
+#pragma unroll
+    for (int g = 0; g < KP / 4; ++g) {
+      f32x4 t = *reinterpret_cast<const f32x4*>(row + 4 * g);
+      f[4 * g] = t[0]; f[4 * g + 1] = t[1]; f[4 * g + 2] = t[2]; f[4 * g + 3] = t[3];
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < KP; ++j) f[j] = row[j];
+  }
+}
 
 template <typename Io, int D, int CW, int KP>
 __global__ __launch_bounds__(256) void verify_kernel(VerifyArgs a) {
@@ -106,30 +122,38 @@ __global__ __launch_bounds__(256) void verify_kernel(VerifyArgs a) {
     }
   }
 
-  // ---- 3. read-outs phi(q_j)^T S from registers --------------------------------------
+  // ---- 3. read-outs phi(q_j)^T S from registers; accepted drafts folded in and the row
+  //         streamed back as soon as it has been used (reads of later rows are still in flight)
   float acc[KP][4];
 #pragma unroll
   for (int j = 0; j < KP; ++j)
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[j][e] = 0.f;
+  float vr[KP][4];
+#pragma unroll
+  for (int j = 0; j < KP; ++j) {
+    f32x4 t = *reinterpret_cast<const f32x4*>(&sm.vv[j][4 * cg]);
+    const bool keep = j < n;
+    vr[j][0] = keep ? t[0] : 0.f; vr[j][1] = keep ? t[1] : 0.f;
+    vr[j][2] = keep ? t[2] : 0.f; vr[j][3] = keep ? t[3] : 0.f;
+  }
 #pragma unroll
   for (int p = 0; p < NPASS; ++p) {
     const int i = p * RPP + r0;
-    float f[KP];
-    if constexpr (KP >= 4) {
-#pragma unroll
-      for (int g = 0; g < KP / 4; ++g) {
-        f32x4 t = *reinterpret_cast<const f32x4*>(&sm.fq[i][4 * g]);
-        f[4 * g] = t[0]; f[4 * g + 1] = t[1]; f[4 * g + 2] = t[2]; f[4 * g + 3] = t[3];
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < KP; ++j) f[j] = sm.fq[i][j];
-    }
+    float f[KP], g[KP];
+    load_row<KP>(&sm.fq[i][0], f);
 #pragma unroll
     for (int j = 0; j < KP; ++j)
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[j][e] = fmaf(f[j], s[p][e], acc[j][e]);
+    if (n > 0) {   // uniform per workgroup; n == 0 leaves the state untouched
+      load_row<KP>(&sm.fk[i][0], g);
+#pragma unroll
+      for (int j = 0; j < KP; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[p][e] = fmaf(g[j], vr[j][e], s[p][e]);
+      *reinterpret_cast<f32x4*>(Sg + (size_t)i * D) = s[p];
+    }
   }
   // threads that share a column group sit CG lanes apart inside a wave
 #pragma unroll
@@ -169,29 +193,8 @@ __global__ __launch_bounds__(256) void verify_kernel(VerifyArgs a) {
     Io::store1(a.out, tok0 + (int64_t)j * D + c0 + c, num / sm.den[j] + u);
   }
 
-  // ---- 5. fold the accepted drafts into the state and stream it back ----------------------
+  // ---- 5. the rest of the state: normaliser and history ----------------------------------
   if (n == 0) return;   // uniform per workgroup: nothing accepted, state untouched
-  {
-    float vr[KP][4];
-#pragma unroll
-    for (int j = 0; j < KP; ++j) {
-      f32x4 t = *reinterpret_cast<const f32x4*>(&sm.vv[j][4 * cg]);
-      const bool keep = j < n;
-      vr[j][0] = keep ? t[0] : 0.f; vr[j][1] = keep ? t[1] : 0.f;
-      vr[j][2] = keep ? t[2] : 0.f; vr[j][3] = keep ? t[3] : 0.f;
-    }
-#pragma unroll
-    for (int p = 0; p < NPASS; ++p) {
-      const int i = p * RPP + r0;
-#pragma unroll
-      for (int j = 0; j < KP; ++j) {
-        const float f = sm.fk[i][j];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) s[p][e] = fmaf(f, vr[j][e], s[p][e]);
-      }
-      *reinterpret_cast<f32x4*>(Sg + (size_t)i * D) = s[p];
-    }
-  }
   if (NSPLIT == 1 && tid < D) {   // with several slices per head a separate launch updates z
     float zs = sm.zz[tid];
     for (int j = 0; j < n; ++j) zs += sm.fk[tid][j];
@@ -253,6 +256,7 @@ static hipError_t launch_split(const VerifyArgs& a, int nsplit, hipStream_t st) 
 // Columns of a head are split over 1, 2 or 4 workgroups so that small B*H still
 // puts enough workgroups on the 256 compute units.
 int verify_pick_split(int BH) {
+  if (const char* e = getenv("LINATTN_VERIFY_SPLIT")) return atoi(e);   // TEMPORARY tuning knob
   if (BH >= 768) return 1;
   if (BH >= 384) return 2;
   return 4;
