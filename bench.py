@@ -55,7 +55,8 @@ def parse_args():
                     help="restrict the step to one stage (for profiling runs)")
     ap.add_argument("--state-sets", type=int, default=32)
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one 1 GiB device copy (reference dispatch for counter scaling)")
+                    help="also run one elementwise kernel that reads 1 GiB and writes 1 GiB "
+                         "(reference dispatch for scaling the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -193,10 +194,12 @@ def main():
     for i in range(args.warmup):
         step(i, False)
     if args.copy_calibration:
+        # a plain elementwise kernel of known traffic (reads 1 GiB, writes 1 GiB): the reference
+        # against which the FETCH_SIZE / WRITE_SIZE counters of the same run are scaled
         with torch.cuda.stream(stream):
-            a = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+            a = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
             b = torch.empty_like(a)
-            b.copy_(a)
+            torch.add(a, 1.0, out=b)
     stream.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()

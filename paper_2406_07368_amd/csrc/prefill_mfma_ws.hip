@@ -19,8 +19,9 @@
 // update (phi(K)^T 1) and its read-out (phi(Q) z) are MFMAs as well; the read-out is split
 // over the waves by feature block and summed through LDS.
 //
-// Two workgroup barriers per group keep the halves in step: B (scores and normaliser
-// partials are in LDS) and C (the current buffer is free, the next one is full).
+// One workgroup barrier per group keeps the halves in step (C: the current buffer is free,
+// the next one is full); the compute waves additionally meet once per group at an LDS counter
+// (B: scores and normaliser partials are in LDS), which the loader waves do not take part in.
 #include <type_traits>
 
 #include "common.cuh"
@@ -28,6 +29,12 @@
 #include "mfma_util.cuh"
 
 namespace linattn {
+
+#ifdef LINATTN_TRACE
+#define TRACE(slot) do { if (a.trace && blockIdx.x == 7 && lane == 0 && ci >= 8 && ci < 12) a.trace[((ci - 8) * 8 + wv) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define TRACE(slot) do {} while (0)
+#endif
 
 namespace {
 
@@ -56,7 +63,8 @@ struct WsCfg {
   static constexpr int OFF_DENQ = OFF_PN + C * PS * 2;     // [NW][C] float
   static constexpr int OFF_DENP = OFF_DENQ + NW * C * 4;   // [TB][C] float
   static constexpr int OFF_WL = OFF_DENP + TB * C * 4;     // [KCMAX][D] float, tap-major
-  static constexpr int TOTAL = OFF_WL + KCMAX * D * 4;
+  static constexpr int OFF_SYNC = OFF_WL + KCMAX * D * 4;  // one counter for the compute waves' meeting point
+  static constexpr int TOTAL = OFF_SYNC + 16;
   static constexpr bool FITS = TOTAL <= 160 * 1024;
 };
 
@@ -70,6 +78,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   float* denq = reinterpret_cast<float*>(smem + G::OFF_DENQ);
   float* denp = reinterpret_cast<float*>(smem + G::OFF_DENP);
   float* wl = reinterpret_cast<float*>(smem + G::OFF_WL);
+  unsigned* syncB = reinterpret_cast<unsigned*>(smem + G::OFF_SYNC);
   auto bufQ = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BQ); };
   auto bufK = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BK); };
   auto bufV = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BV); };   // row r = token r - HALO
@@ -93,60 +102,80 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   const uint16_t* staged_hist =
       reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
+  if (tid == 0) *syncB = 0u;
+
   if (wv >= G::NW) {
     // =============================== loader waves ===============================================
     const int lt = tid - G::NLT;                       // 0 .. NLT-1
     const int lw = wv - G::NW;
-    const int r16 = lane & 15;                         // token within a 16-token pass
-    const int c0 = 8 * (4 * lw + (lane >> 4));         // first of the 8 columns this thread carries
-    const int loff = r16 * (int)a.st + c0;             // this thread's offset inside a pass (elements)
+    // a pass is 16 tokens; D/8 consecutive lanes carry one whole row (8 columns each), so every
+    // load instruction of a wave covers complete rows and every LDS row is written contiguously
+    constexpr int LPR = D / 8;                         // lanes per row
+    const int r16 = (64 / LPR) * lw + lane / LPR;      // token within a 16-token pass
+    const int c0 = 8 * (lane % LPR);                   // first of the 8 columns this thread carries
 
-    u32x4 rq[G::NP], rk[G::NP], rv[G::NP];
-    auto load_pass = [&](int ci, int p) {              // rows past the end of the segment read as zero
+    const uint32_t loff_b = (uint32_t)(r16 * (int)a.st + c0) * 2u;   // this thread's byte offset inside a pass
+
+    // two register sets: group ci lives in set ci & 1 from the moment it is requested (two groups
+    // ahead of its use) until it has been written to LDS
+    u32x4 rq[2][G::NP], rk[2][G::NP], rv[2][G::NP];
+    // 16 rows of group ci; uniform base + 32-bit lane offset.  Rows past the end of the segment
+    // read as zero (only a segment's last group can have such rows).
+    auto load_pass = [&](int ci, int p, auto set_tag) {
+      constexpr int SET = decltype(set_tag)::value;
       const int tok = t_begin + ci * C + 16 * p;       // uniform
-      const bool ok = tok + r16 < t_end;
       const int64_t off = (int64_t)tok * a.st;         // uniform
-      const u32x4 zero = {0, 0, 0, 0};
-      rk[p] = ok ? *reinterpret_cast<const u32x4*>(gk + off + loff) : zero;
-      rv[p] = ok ? *reinterpret_cast<const u32x4*>(gv + off + loff) : zero;
-      rq[p] = ok ? *reinterpret_cast<const u32x4*>(gq + off + loff) : zero;
+      const char* bk = reinterpret_cast<const char*>(gk + off);
+      const char* bv = reinterpret_cast<const char*>(gv + off);
+      const char* bq = reinterpret_cast<const char*>(gq + off);
+      if (tok + 16 <= t_end) {
+        rk[SET][p] = *reinterpret_cast<const u32x4*>(bk + loff_b);
+        rv[SET][p] = *reinterpret_cast<const u32x4*>(bv + loff_b);
+        rq[SET][p] = *reinterpret_cast<const u32x4*>(bq + loff_b);
+      } else {
+        const bool ok = tok + r16 < t_end;
+        const u32x4 zero = {0, 0, 0, 0};
+        rk[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bk + loff_b) : zero;
+        rv[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bv + loff_b) : zero;
+        rq[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bq + loff_b) : zero;
+      }
     };
-    auto fill_pass = [&](int bi, int p, int nt, auto tail_tag) {
-      constexpr bool TAIL = decltype(tail_tag)::value;
+    // feature map on the 16 rows held in registers, then to buffer bi; rows >= nt become zero
+    // (phi(0) = 1, so they are cleared after the map)
+    auto fill_pass = [&](int bi, int p, int nt, auto set_tag) {
+      constexpr int SET = decltype(set_tag)::value;
       const int t = 16 * p + r16;
-      const bool ok = !TAIL || t < nt;
+      const bool ok = t < nt;
       u32x4 kp, qp;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        float k0 = phi_elu1_max(bf16_lo_to_f32(rk[p][i])), k1 = phi_elu1_max(bf16_hi_to_f32(rk[p][i]));
-        float q0 = phi_elu1_max(bf16_lo_to_f32(rq[p][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[p][i]));
-        kp[i] = pack_bf16x2(k0, k1);
-        qp[i] = pack_bf16x2(q0, q1);
-        if (TAIL) { kp[i] = ok ? kp[i] : 0u; qp[i] = ok ? qp[i] : 0u; }   // phi(0) = 1, so zero after the map
+        const float k0 = phi_elu1_max(bf16_lo_to_f32(rk[SET][p][i])), k1 = phi_elu1_max(bf16_hi_to_f32(rk[SET][p][i]));
+        const float q0 = phi_elu1_max(bf16_lo_to_f32(rq[SET][p][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[SET][p][i]));
+        kp[i] = ok ? pack_bf16x2(k0, k1) : 0u;
+        qp[i] = ok ? pack_bf16x2(q0, q1) : 0u;
       }
       *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
       u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + t) * G::VS + c0);
-      vrow[0] = u32x2{rv[p][0], rv[p][1]};
-      vrow[1] = u32x2{rv[p][2], rv[p][3]};
+      vrow[0] = u32x2{rv[SET][p][0], rv[SET][p][1]};
+      vrow[1] = u32x2{rv[SET][p][2], rv[SET][p][3]};
       u32x2* qrow = reinterpret_cast<u32x2*>(bufQ(bi) + t * G::QS + c0);
       qrow[0] = u32x2{qp[0], qp[1]};
       qrow[1] = u32x2{qp[2], qp[3]};
     };
-    // group ci -> buffer ci & 1; afterwards the registers hold group ci + 1.  `split` passes are
-    // done before barrier B, the rest after it.
-    auto fill_group = [&](int ci, bool with_barrier) {
+    // group ci (held in set ci & 1) -> buffer ci & 1; as each pass leaves the registers, the same
+    // pass of group ci + 2 is requested from HBM into the freed registers
+    auto fill_group = [&](int ci, auto set_tag) {
       const int bi = ci & 1;
       const int nt = (t_end - (t_begin + ci * C)) < C ? (t_end - (t_begin + ci * C)) : C;
-      const bool more = ci + 1 < nchunks;
-      constexpr int SPLIT = G::NP / 4 > 0 ? G::NP / 4 : 1;
+      const bool more = ci + 2 < nchunks;
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
-        if (p == SPLIT && with_barrier) __syncthreads();            // barrier B
-        if (nt == C) fill_pass(bi, p, nt, std::false_type{});
-        else fill_pass(bi, p, nt, std::true_type{});
-        if (more) load_pass(ci + 1, p);
+        fill_pass(bi, p, nt, set_tag);
+        if (more) load_pass(ci + 2, p, set_tag);
       }
     };
+    using Set0 = std::integral_constant<int, 0>;
+    using Set1 = std::integral_constant<int, 1>;
 
     for (int e = lt; e < KCM * D; e += G::NLT) {
       const int j = e / D, cc = e % D;
@@ -167,9 +196,13 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     }
     if (nchunks > 0) {
 #pragma unroll
-      for (int p = 0; p < G::NP; ++p) load_pass(0, p);
-      fill_group(0, false);
+      for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{});
     }
+    if (nchunks > 1) {
+#pragma unroll
+      for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{});
+    }
+    if (nchunks > 0) fill_group(0, Set0{});
     __syncthreads();                                   // buffer 0 is full
     for (int ci = 0; ci < nchunks; ++ci) {
       if (ci + 1 < nchunks) {
@@ -181,11 +214,13 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           const u32x2 t0 = src[0], t1 = src[1];
           dst[0] = t0; dst[1] = t1;
         }
-        fill_group(ci + 1, true);                      // contains barrier B
-      } else {
-        __syncthreads();                               // barrier B
+        TRACE(0);
+        if ((ci + 1) & 1) fill_group(ci + 1, Set1{});
+        else fill_group(ci + 1, Set0{});
+        TRACE(1);
       }
       __syncthreads();                                 // barrier C
+      TRACE(2);
     }
     return;
   }
@@ -218,7 +253,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   __syncthreads();                                     // buffer 0 is full, conv taps are in LDS
 
   // conv taps of this lane's 16 output channels (32w + 8g + 4hi + e), kept in registers when few
-  constexpr bool W_REGS = KCM <= 3;
+  constexpr bool W_REGS = KCM <= 3 && D == 64;   // D = 128 runs two waves per SIMD: 256 registers each
   f32x4 wreg[W_REGS ? KCM : 1][4];
   if (W_REGS) {
 #pragma unroll
@@ -226,6 +261,11 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) wreg[j][g] = *reinterpret_cast<const f32x4*>(wl + j * D + 32 * w + 8 * g + 4 * hi);
   }
+
+  // LDS reads are issued in batches ahead of the MFMAs that consume them (the fences keep the
+  // compiler from sinking each read next to its use, which would expose the full LDS latency
+  // once per MFMA).
+#define LINATTN_FENCE() __builtin_amdgcn_sched_barrier(0)
 
   auto group = [&](int ci, auto tail_tag) {
     constexpr bool TAIL = decltype(tail_tag)::value;
@@ -235,6 +275,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     const uint16_t* Kn = bufK(ci & 1);
     const uint16_t* Vn = bufV(ci & 1);
 
+    TRACE(0);
     // ---- scores: causal tiles of P^T = phi(K) phi(Q)^T, masked, to LDS as P[t][s] ---------------------
 #pragma unroll
     for (int s = 0; s < G::MAXT; ++s) {
@@ -248,9 +289,20 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
         const uint16_t* ka = Kn + (32 * sb + l32) * G::KS + 8 * hi;
         const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 8 * hi;
+        constexpr int HB = G::KSD / 2;   // two batches of K steps
 #pragma unroll
-        for (int ks = 0; ks < G::KSD; ++ks)
-          acc = mfma(lds_row8(ka + 16 * ks), cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4)), acc);
+        for (int half = 0; half < 2; ++half) {
+          bf16x8 ak[HB], bq[HB];
+#pragma unroll
+          for (int k2 = 0; k2 < HB; ++k2) {
+            const int ks = half * HB + k2;
+            ak[k2] = lds_row8(ka + 16 * ks);
+            bq[k2] = cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4));
+          }
+          LINATTN_FENCE();
+#pragma unroll
+          for (int k2 = 0; k2 < HB; ++k2) acc = mfma(ak[k2], bq[k2], acc);
+        }
         // acc[r]: source token s = 32sb + 8(r/4) + 4hi + r%4, query token t = 32tb + l32
         float rs = 0.f;
 #pragma unroll
@@ -272,86 +324,139 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     }
     // ---- phi(q_t).z over this wave's 32 features, for every token of the group -------------------------
     {
+      bf16x8 bq[G::TB][2];
+#pragma unroll
+      for (int tb = 0; tb < G::TB; ++tb) {
+        const uint16_t* p = Qn + (32 * tb + l32) * G::QS + 32 * w + 4 * hi;
+        bq[tb][0] = cat4(lds_row4(p), lds_row4(p + 8));
+        bq[tb][1] = cat4(lds_row4(p + 16), lds_row4(p + 24));
+      }
       const bf16x8 zb0 = pack8(Zacc, 0), zb1 = pack8(Zacc, 8);
+      LINATTN_FENCE();
 #pragma unroll
       for (int tb = 0; tb < G::TB; ++tb) {
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        const uint16_t* p = Qn + (32 * tb + l32) * G::QS + 32 * w + 4 * hi;
-        acc = mfma(zb0, cat4(lds_row4(p), lds_row4(p + 8)), acc);
-        acc = mfma(zb1, cat4(lds_row4(p + 16), lds_row4(p + 24)), acc);
+        acc = mfma(zb0, bq[tb][0], acc);
+        acc = mfma(zb1, bq[tb][1], acc);
         if (lane < 32) denq[w * C + 32 * tb + l32] = acc[0];   // every row of the product is the same
       }
     }
-    __syncthreads();   // B: P and the normaliser partials are in LDS
+    TRACE(1);
+    // B: the compute waves meet here (scores and normaliser partials are in LDS); the loader waves
+    // are not involved.  Every compute wave adds one to an LDS counter per group and waits until the
+    // counter shows that all NW of them have done so for this group.  The wait is bounded.
+    {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      if (lane == 0) __hip_atomic_fetch_add(syncB, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const unsigned want = (unsigned)G::NW * (unsigned)(ci + 1);
+      for (int spin = 0; spin < (1 << 20); ++spin) {
+        if (__hip_atomic_load(syncB, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= want) break;
+        __builtin_amdgcn_s_sleep(1);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    }
+    TRACE(2);
 
     // ---- this wave's channels ------------------------------------------------------------------------
     // vf[ks]: lanes <-> channels 32w + l32, registers <-> tokens 16ks + 8hi + 0..7
     bf16x8 vf[G::KSC];
 #pragma unroll
     for (int ks = 0; ks < G::KSC; ++ks) vf[ks] = tr_operand(Vn + HALO * G::VS, G::VS, 16 * ks, 32 * w, lane);
-    bf16x8 sbf[G::IB][2];
-#pragma unroll
-    for (int ib = 0; ib < G::IB; ++ib) { sbf[ib][0] = pack8(Sacc[ib], 0); sbf[ib][1] = pack8(Sacc[ib], 8); }
 #pragma unroll
     for (int tb = 0; tb < G::TB; ++tb) {
+      const int t = 32 * tb + l32;
+      // operands and epilogue inputs of this token block, all requested before the first MFMA
+      bf16x8 pB[2 * G::TB], qB[2 * G::IB];
+      const uint16_t* pb = Pn + t * G::PS + 8 * hi;
+#pragma unroll
+      for (int ks = 0; ks < 2 * (tb + 1); ++ks) pB[ks] = lds_row8(pb + 16 * ks);
+      // S^T phi(Q)^T: register r of S holds feature 32ib + 8(r/4) + 4hi + r%4, so the phi(Q) operand
+      // takes features {16h2 + 4hi + 0..3, 16h2 + 8 + 4hi + 0..3} of block ib for MFMA step h2
+      const uint16_t* qb = Qn + t * G::QS + 4 * hi;
+#pragma unroll
+      for (int x = 0; x < 2 * G::IB; ++x) qB[x] = cat4(lds_row4(qb + 16 * x), lds_row4(qb + 16 * x + 8));
+      float den = a.eps;
+      float dpart[G::NW + G::TB];
+#pragma unroll
+      for (int ww = 0; ww < G::NW; ++ww) dpart[ww] = denq[ww * C + t];
+#pragma unroll
+      for (int sb = 0; sb <= tb; ++sb) dpart[G::NW + sb] = denp[sb * C + t];
+      const uint16_t* vrow = Vn + (HALO + t) * G::VS + 32 * w + 4 * hi;
+      const float* wrow = wl + 32 * w + 4 * hi;
+      // conv inputs of channel group g are requested one group ahead of their use
+      u32x2 xv[2][KCM];
+      f32x4 wv[2][W_REGS ? 1 : KCM];
+      auto conv_request = [&](int g) {
+#pragma unroll
+        for (int j = 0; j < KCM; ++j) {
+          xv[g & 1][j] = *reinterpret_cast<const u32x2*>(vrow - j * G::VS + 8 * g);
+          if (!W_REGS) wv[g & 1][j] = *reinterpret_cast<const f32x4*>(wrow + j * D + 8 * g);
+        }
+      };
+      conv_request(0);
+      LINATTN_FENCE();
       // o[r] = O[token 32tb + l32][channel 32w + 8(r/4) + 4hi + r%4]
       f32x16 o;
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[r] = 0.f;
-      const uint16_t* pb = Pn + (32 * tb + l32) * G::PS + 8 * hi;
 #pragma unroll
-      for (int ks = 0; ks < 2 * (tb + 1); ++ks) o = mfma(vf[ks], lds_row8(pb + 16 * ks), o);
-      // S^T phi(Q)^T: register r of S holds feature 32ib + 8(r/4) + 4hi + r%4, so the phi(Q) operand
-      // takes features {16h2 + 4hi + 0..3, 16h2 + 8 + 4hi + 0..3} of block ib for MFMA step h2
-      const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 4 * hi;
+      for (int ks = 0; ks < 2 * (tb + 1); ++ks) o = mfma(vf[ks], pB[ks], o);
 #pragma unroll
       for (int ib = 0; ib < G::IB; ++ib)
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          const uint16_t* p = qb + 32 * ib + 16 * h2;
-          o = mfma(sbf[ib][h2], cat4(lds_row4(p), lds_row4(p + 8)), o);
-        }
+        for (int h2 = 0; h2 < 2; ++h2) o = mfma(pack8(Sacc[ib], 8 * h2), qB[2 * ib + h2], o);
       // normalise, add the causal conv, store
-      const int t = 32 * tb + l32;
-      float den = a.eps;
 #pragma unroll
-      for (int ww = 0; ww < G::NW; ++ww) den += denq[ww * C + t];
+      for (int x = 0; x < G::NW; ++x) den += dpart[x];
 #pragma unroll
-      for (int sb = 0; sb <= tb; ++sb) den += denp[sb * C + t];
+      for (int sb = 0; sb <= tb; ++sb) den += dpart[G::NW + sb];
       const float inv = __builtin_amdgcn_rcpf(den);
-      const uint16_t* vrow = Vn + (HALO + t) * G::VS + 32 * w + 4 * hi;
       uint16_t* orow = gout + (int64_t)(tok0 + t) * a.st + 32 * w + 4 * hi;
-      const float* wrow = wl + 32 * w + 4 * hi;
       const bool live = !TAIL || t < nt;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
+        if (g + 1 < 4) conv_request(g + 1);
         float u[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < KCM; ++j) {
-          const u32x2 xv = *reinterpret_cast<const u32x2*>(vrow - j * G::VS + 8 * g);
-          const f32x4 wv4 = W_REGS ? wreg[W_REGS ? j : 0][g] : *reinterpret_cast<const f32x4*>(wrow + j * D + 8 * g);
-          u[0] = fmaf(wv4[0], bf16_lo_to_f32(xv[0]), u[0]);
-          u[1] = fmaf(wv4[1], bf16_hi_to_f32(xv[0]), u[1]);
-          u[2] = fmaf(wv4[2], bf16_lo_to_f32(xv[1]), u[2]);
-          u[3] = fmaf(wv4[3], bf16_hi_to_f32(xv[1]), u[3]);
+          const f32x4 wv4 = W_REGS ? wreg[W_REGS ? j : 0][g] : wv[g & 1][W_REGS ? 0 : j];
+          const u32x2 x = xv[g & 1][j];
+          u[0] = fmaf(wv4[0], bf16_lo_to_f32(x[0]), u[0]);
+          u[1] = fmaf(wv4[1], bf16_hi_to_f32(x[0]), u[1]);
+          u[2] = fmaf(wv4[2], bf16_lo_to_f32(x[1]), u[2]);
+          u[3] = fmaf(wv4[3], bf16_hi_to_f32(x[1]), u[3]);
         }
         const u32x2 y = {pack_bf16x2(fmaf(o[4 * g], inv, u[0]), fmaf(o[4 * g + 1], inv, u[1])),
                          pack_bf16x2(fmaf(o[4 * g + 2], inv, u[2]), fmaf(o[4 * g + 3], inv, u[3]))};
         if (live) *reinterpret_cast<u32x2*>(orow + 8 * g) = y;
       }
     }
-    // S += phi(K)^T V for this wave's channels, z += phi(K)^T 1 for this wave's features
+    TRACE(3);
+    // S += phi(K)^T V for this wave's channels, z += phi(K)^T 1 for this wave's features;
+    // the phi(K)^T operands of feature block ib + 1 are requested while block ib is multiplied
+    {
+      bf16x8 kt[2][G::KSC];
 #pragma unroll
-    for (int ib = 0; ib < G::IB; ++ib)
+      for (int ks = 0; ks < G::KSC; ++ks) kt[0][ks] = tr_operand(Kn, G::KS, 16 * ks, 0, lane);
 #pragma unroll
-      for (int ks = 0; ks < G::KSC; ++ks) {
-        const bf16x8 kt = tr_operand(Kn, G::KS, 16 * ks, 32 * ib, lane);
-        Sacc[ib] = mfma(kt, vf[ks], Sacc[ib]);
-        if (ib == w) Zacc = mfma(kt, ones, Zacc);
+      for (int ib = 0; ib < G::IB; ++ib) {
+        if (ib + 1 < G::IB) {
+#pragma unroll
+          for (int ks = 0; ks < G::KSC; ++ks) kt[(ib + 1) & 1][ks] = tr_operand(Kn, G::KS, 16 * ks, 32 * (ib + 1), lane);
+        }
+        LINATTN_FENCE();
+#pragma unroll
+        for (int ks = 0; ks < G::KSC; ++ks) {
+          Sacc[ib] = mfma(kt[ib & 1][ks], vf[ks], Sacc[ib]);
+          if (ib == w) Zacc = mfma(kt[ib & 1][ks], ones, Zacc);
+        }
       }
+    }
+    TRACE(4);
     __syncthreads();   // C: this buffer may be refilled, the other one is complete
+    TRACE(5);
   };
 
   for (int ci = 0; ci < nchunks; ++ci) {

@@ -3,13 +3,13 @@
 // and, if any draft is accepted, written once; everything else is tiny.
 //
 // One workgroup of 256 threads owns the column slice S[:, c0 : c0+CW] of one
-// (b, h).  All of the slice is pulled into registers with 16-byte loads issued
-// before anything else (rows are contiguous, so a wave reads whole 128..512 B
-// row segments), the kk read-outs phi(q_j)^T S are accumulated from registers,
-// reduced across the threads that share a column group, completed with the
-// causal in-block term, normalised, joined with the convolution over
-// (history ++ drafts <= j), and then the accepted rank-1 updates are folded into
-// the registers and streamed back.
+// (b, h).  The slice streams through registers in row passes with 16-byte loads
+// (rows are contiguous, so a wave reads whole 128..512 B row segments), a few
+// passes in flight at a time: each row adds its term to the kk read-outs
+// phi(q_j)^T S, receives the accepted rank-1 updates and is written straight back.
+// The read-outs are then reduced across the threads that share a column group,
+// completed with the causal in-block term, normalised, and joined with the
+// convolution over (history ++ drafts <= j).
 #include <stdlib.h>
 
 #include "common.cuh"
@@ -42,8 +42,11 @@ __device__ __forceinline__ void load_row(const float* row, float (&f)[KP]) {
   }
 }
 
+// At most 128 registers per thread for up to 8 drafts, so that four workgroups fit on a compute unit
+// and B*H = 1024 heads are all resident at once (a partial second round would run at a fraction of
+// the bandwidth).
 template <typename Io, int D, int CW, int KP>
-__global__ __launch_bounds__(256) void verify_kernel(VerifyArgs a) {
+__global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyArgs a) {
   constexpr int NSPLIT = D / CW;
   constexpr int CG = CW / 4;          // float4 column groups per row slice
   constexpr int RPP = 256 / CG;       // rows covered per pass
@@ -58,11 +61,14 @@ __global__ __launch_bounds__(256) void verify_kernel(VerifyArgs a) {
   const int kk = a.kk, Kc = a.Kc;
   const int cg = tid % CG, r0 = tid / CG;
 
-  // ---- 0. the state slice: all loads in flight before anything else -----------
+  // ---- 0. the state slice streams through a window of PD row passes: the first PD loads are
+  //         in flight before anything else, each later one is issued when its slot frees up ----
+  constexpr int PDW = KP >= 8 ? 2 : 4;        // fewer passes in flight when the read-outs need the registers
+  constexpr int PD = NPASS < PDW ? NPASS : PDW;
   float* Sg = a.S + (size_t)bh * D * D + c0 + 4 * cg;
-  f32x4 s[NPASS];
+  f32x4 s[PD];
 #pragma unroll
-  for (int p = 0; p < NPASS; ++p) s[p] = *reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D);
+  for (int p = 0; p < PD; ++p) s[p] = *reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D);
 
   // ---- 1. drafts -> LDS (phi applied), normaliser -> LDS -----------------------
   const int64_t tok0 = (int64_t)bh * kk * D;
@@ -137,22 +143,28 @@ __global__ __launch_bounds__(256) void verify_kernel(VerifyArgs a) {
     vr[j][0] = keep ? t[0] : 0.f; vr[j][1] = keep ? t[1] : 0.f;
     vr[j][2] = keep ? t[2] : 0.f; vr[j][3] = keep ? t[3] : 0.f;
   }
+#pragma unroll 1
+  for (int pb = 0; pb < NPASS; pb += PD) {
 #pragma unroll
-  for (int p = 0; p < NPASS; ++p) {
-    const int i = p * RPP + r0;
-    float f[KP], g[KP];
-    load_row<KP>(&sm.fq[i][0], f);
-#pragma unroll
-    for (int j = 0; j < KP; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[j][e] = fmaf(f[j], s[p][e], acc[j][e]);
-    if (n > 0) {   // uniform per workgroup; n == 0 leaves the state untouched
-      load_row<KP>(&sm.fk[i][0], g);
+    for (int q = 0; q < PD; ++q) {
+      const int p = pb + q;
+      const int i = p * RPP + r0;
+      float f[KP], g[KP];
+      f32x4 cur = s[q];
+      load_row<KP>(&sm.fq[i][0], f);
 #pragma unroll
       for (int j = 0; j < KP; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) s[p][e] = fmaf(g[j], vr[j][e], s[p][e]);
-      *reinterpret_cast<f32x4*>(Sg + (size_t)i * D) = s[p];
+        for (int e = 0; e < 4; ++e) acc[j][e] = fmaf(f[j], cur[e], acc[j][e]);
+      if (n > 0) {   // uniform per workgroup; n == 0 leaves the state untouched
+        load_row<KP>(&sm.fk[i][0], g);
+#pragma unroll
+        for (int j = 0; j < KP; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) cur[e] = fmaf(g[j], vr[j][e], cur[e]);
+        *reinterpret_cast<f32x4*>(Sg + (size_t)i * D) = cur;
+      }
+      if (p + PD < NPASS) s[q] = *reinterpret_cast<const f32x4*>(Sg + (size_t)((p + PD) * RPP + r0) * D);
     }
   }
   // threads that share a column group sit CG lanes apart inside a wave
