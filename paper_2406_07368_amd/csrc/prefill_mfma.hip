@@ -460,8 +460,12 @@ static hipError_t launch_k(const PrefillArgs& a, hipStream_t st) {
   return launch_dc<D, C, 8>(a, st);
 }
 
+// The group size only blocks the computation; the result does not depend on it (the in-group
+// part is the exact masked product).  At d = 128 a requested group of 128 tokens is walked as two
+// steps of 64: two 128-token row buffers do not fit in LDS, and larger groups only add in-group
+// MFMA work per token on this design.  Segment boundaries stay multiples of the requested size.
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, hipStream_t st) {
-  if (d == 128) return chunk == 64 ? launch_k<128, 64>(a, st) : launch_k<128, 128>(a, st);
+  if (d == 128) return launch_k<128, 64>(a, st);
   return chunk == 64 ? launch_k<64, 64>(a, st) : launch_k<64, 128>(a, st);
 }
 

@@ -4,14 +4,16 @@
 // A workgroup walks one (b, h) -- or one segment of it -- in groups of C tokens and
 // is split into two halves that run at the same time on every SIMD:
 //
-//   loader waves   bring the next group's Q, K, V rows from HBM (loads issued one whole
-//                  group ahead), apply the feature map on the vector ALUs, and write
-//                  phi(Q), phi(K), V as bf16 rows into the LDS buffer that is not in use;
+//   loader waves   do all HBM traffic with whole 16-byte-per-lane rows: they bring the coming
+//                  groups' Q, K, V rows in (loads issued two groups ahead), apply the feature
+//                  map on the vector ALUs, write phi(Q), phi(K), V as bf16 rows into the LDS
+//                  buffer that is not in use, and write the previous group's finished output
+//                  rows (staged in LDS by the compute waves) back out;
 //   compute waves  run the matrix-core work of the current group from the other buffer:
 //                  the causal tiles of P^T = phi(K) phi(Q)^T (masked by select), then for
 //                  their 32 value channels O^T = V^T P^T + S^T phi(Q)^T, the row
-//                  normaliser, the causal convolution over V, the store, and finally
-//                  S += phi(K)^T V.
+//                  normaliser, the causal convolution over V, the result to an LDS staging
+//                  buffer, and finally S += phi(K)^T V.
 //
 // The state never leaves the compute waves' accumulator registers: wave w holds
 // S[:, 32w:32w+32] and the 32 entries z[32w:32w+32] of the normaliser.  z is carried as
@@ -63,7 +65,10 @@ struct WsCfg {
   static constexpr int OFF_DENQ = OFF_PN + C * PS * 2;     // [NW][C] float
   static constexpr int OFF_DENP = OFF_DENQ + NW * C * 4;   // [TB][C] float
   static constexpr int OFF_WL = OFF_DENP + TB * C * 4;     // [KCMAX][D] float, tap-major
-  static constexpr int OFF_SYNC = OFF_WL + KCMAX * D * 4;  // one counter for the compute waves' meeting point
+  static constexpr int OS = D + 4;           // output staging rows: 8-byte writes, one row per lane
+  static constexpr int OFF_OST = OFF_WL + KCMAX * D * 4;   // [2][C][OS] bf16: finished output rows of a group
+  static constexpr int OST = C * OS * 2;
+  static constexpr int OFF_SYNC = OFF_OST + 2 * OST;       // one counter for the compute waves' meeting point
   static constexpr int TOTAL = OFF_SYNC + 16;
   static constexpr bool FITS = TOTAL <= 160 * 1024;
 };
@@ -82,6 +87,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   auto bufQ = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BQ); };
   auto bufK = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BK); };
   auto bufV = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BV); };   // row r = token r - HALO
+  auto bufO = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + G::OFF_OST + bi * G::OST); };
 
   const int tid = threadIdx.x;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -103,6 +109,9 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
   if (tid == 0) *syncB = 0u;
+#ifdef LINATTN_TRACE
+  if (a.trace && blockIdx.x == 7 && lane == 0) a.trace[4 * 8 * 16 + wv] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);
+#endif
 
   if (wv >= G::NW) {
     // =============================== loader waves ===============================================
@@ -194,6 +203,23 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       }
       bufV(0)[r * G::VS + cc] = x;
     }
+    // finished output rows of group ci (left in LDS by the compute waves) -> HBM, whole rows per
+    // D/8 consecutive lanes, 16 bytes per lane
+    auto store_group = [&](int ci) {
+      const int tok0 = t_begin + ci * C;
+      const int nt = (t_end - tok0) < C ? (t_end - tok0) : C;
+      const uint16_t* ost = bufO(ci & 1);
+      char* bo = reinterpret_cast<char*>(gout + (int64_t)tok0 * a.st);
+#pragma unroll
+      for (int p = 0; p < G::NP; ++p) {
+        const int t = 16 * p + r16;
+        const u32x2* src = reinterpret_cast<const u32x2*>(ost + t * G::OS + c0);
+        const u32x2 lo = src[0], hi2 = src[1];
+        if (t < nt)
+          *reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st * 2u + loff_b) = u32x4{lo[0], lo[1], hi2[0], hi2[1]};
+      }
+    };
+
     if (nchunks > 0) {
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{});
@@ -205,6 +231,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     if (nchunks > 0) fill_group(0, Set0{});
     __syncthreads();                                   // buffer 0 is full
     for (int ci = 0; ci < nchunks; ++ci) {
+      if (ci > 0) store_group(ci - 1);                 // the previous group's outputs are complete
       if (ci + 1 < nchunks) {
         // the last HALO value rows of group ci become the rows before group ci + 1
         if (lt < HALO * D / 8) {
@@ -222,6 +249,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       __syncthreads();                                 // barrier C
       TRACE(2);
     }
+    if (nchunks > 0) store_group(nchunks - 1);
     return;
   }
 
@@ -267,10 +295,9 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   // once per MFMA).
 #define LINATTN_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-  auto group = [&](int ci, auto tail_tag) {
-    constexpr bool TAIL = decltype(tail_tag)::value;
-    const int tok0 = t_begin + ci * C;
-    const int nt = TAIL ? (t_end - tok0) : C;
+  // One group of C tokens.  A short last group needs no special case here: its missing rows are
+  // zero rows in LDS, and the loader waves do not store their outputs.
+  auto group = [&](int ci) {
     const uint16_t* Qn = bufQ(ci & 1);
     const uint16_t* Kn = bufK(ci & 1);
     const uint16_t* Vn = bufV(ci & 1);
@@ -413,8 +440,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
       for (int sb = 0; sb <= tb; ++sb) den += dpart[G::NW + sb];
       const float inv = __builtin_amdgcn_rcpf(den);
-      uint16_t* orow = gout + (int64_t)(tok0 + t) * a.st + 32 * w + 4 * hi;
-      const bool live = !TAIL || t < nt;
+      uint16_t* orow = bufO(ci & 1) + t * G::OS + 32 * w + 4 * hi;   // staged; the loader waves store it
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         if (g + 1 < 4) conv_request(g + 1);
@@ -430,7 +456,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         }
         const u32x2 y = {pack_bf16x2(fmaf(o[4 * g], inv, u[0]), fmaf(o[4 * g + 1], inv, u[1])),
                          pack_bf16x2(fmaf(o[4 * g + 2], inv, u[2]), fmaf(o[4 * g + 3], inv, u[3]))};
-        if (live) *reinterpret_cast<u32x2*>(orow + 8 * g) = y;
+        *reinterpret_cast<u32x2*>(orow + 8 * g) = y;
       }
     }
     TRACE(3);
@@ -459,10 +485,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     TRACE(5);
   };
 
-  for (int ci = 0; ci < nchunks; ++ci) {
-    if (t_begin + (ci + 1) * C <= t_end) group(ci, std::false_type{});
-    else group(ci, std::true_type{});
-  }
+  for (int ci = 0; ci < nchunks; ++ci) group(ci);
 
   // ---- hand the state over ---------------------------------------------------------------------------
   if (seg == a.nseg - 1) {
