@@ -3,9 +3,6 @@
 #include "../../include/linattn.h"
 
 #include <hip/hip_runtime.h>
-#ifdef LINATTN_TRACE
-#include <stdlib.h>
-#endif
 
 #include "kernels.h"
 
@@ -114,9 +111,6 @@ linattn_status linattn_prefill(const linattn_desc* desc, int32_t L, const void* 
   a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = desc->conv_k; a.eps = desc->eps;
   a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
   a.nseg = plan.nseg; a.seg_len = plan.seg_len;
-#ifdef LINATTN_TRACE
-  a.trace = getenv("LINATTN_TRACE_PTR") ? (unsigned long long*)strtoull(getenv("LINATTN_TRACE_PTR"), 0, 0) : nullptr;
-#endif
   hipError_t e;
   if (plan.mfma && L > 0) e = launch_prefill_mfma(a, desc->d, desc->chunk, stream);
   else e = launch_prefill_simt(a, desc->io_dtype == LINATTN_BF16, desc->d, stream);

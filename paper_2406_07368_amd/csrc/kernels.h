@@ -38,9 +38,6 @@ struct PrefillArgs {
   int64_t sb, sh, st;       // element strides of q, k, v, out
   int nseg;                 // workgroups along the sequence axis per (b, h)
   int seg_len;              // tokens per segment (multiple of the chunk size)
-#ifdef LINATTN_TRACE
-  unsigned long long* trace;
-#endif
 };
 
 // verify.hip

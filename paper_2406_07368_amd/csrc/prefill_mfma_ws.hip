@@ -32,12 +32,6 @@
 
 namespace linattn {
 
-#ifdef LINATTN_TRACE
-#define TRACE(slot) do { if (a.trace && blockIdx.x == 7 && lane == 0 && ci >= 8 && ci < 12) a.trace[((ci - 8) * 8 + wv) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); } while (0)
-#else
-#define TRACE(slot) do {} while (0)
-#endif
-
 namespace {
 
 template <int D, int C>
@@ -109,9 +103,6 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
   if (tid == 0) *syncB = 0u;
-#ifdef LINATTN_TRACE
-  if (a.trace && blockIdx.x == 7 && lane == 0) a.trace[4 * 8 * 16 + wv] = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);
-#endif
 
   if (wv >= G::NW) {
     // =============================== loader waves ===============================================
@@ -173,12 +164,32 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     };
     // group ci (held in set ci & 1) -> buffer ci & 1; as each pass leaves the registers, the same
     // pass of group ci + 2 is requested from HBM into the freed registers
-    auto fill_group = [&](int ci, auto set_tag) {
+    // finished output rows of group ci (left in LDS by the compute waves) -> HBM, whole rows per
+    // D/8 consecutive lanes, 16 bytes per lane
+    auto store_group = [&](int ci) {
+      const int tok0 = t_begin + ci * C;
+      const int nt = (t_end - tok0) < C ? (t_end - tok0) : C;
+      const uint16_t* ost = bufO(ci & 1);
+      char* bo = reinterpret_cast<char*>(gout + (int64_t)tok0 * a.st);
+#pragma unroll
+      for (int p = 0; p < G::NP; ++p) {
+        const int t = 16 * p + r16;
+        const u32x2* src = reinterpret_cast<const u32x2*>(ost + t * G::OS + c0);
+        const u32x2 lo = src[0], hi2 = src[1];
+        if (t < nt)
+          *reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st * 2u + loff_b) = u32x4{lo[0], lo[1], hi2[0], hi2[1]};
+      }
+    };
+
+    // `store_ci` >= 0: that group's finished output rows are written out half-way through, so that
+    // no HBM request is younger than half a group when the next fill starts waiting for its rows
+    auto fill_group = [&](int ci, int store_ci, auto set_tag) {
       const int bi = ci & 1;
       const int nt = (t_end - (t_begin + ci * C)) < C ? (t_end - (t_begin + ci * C)) : C;
       const bool more = ci + 2 < nchunks;
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
+        if (p == G::NP / 2 && store_ci >= 0) store_group(store_ci);
         fill_pass(bi, p, nt, set_tag);
         if (more) load_pass(ci + 2, p, set_tag);
       }
@@ -203,23 +214,6 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       }
       bufV(0)[r * G::VS + cc] = x;
     }
-    // finished output rows of group ci (left in LDS by the compute waves) -> HBM, whole rows per
-    // D/8 consecutive lanes, 16 bytes per lane
-    auto store_group = [&](int ci) {
-      const int tok0 = t_begin + ci * C;
-      const int nt = (t_end - tok0) < C ? (t_end - tok0) : C;
-      const uint16_t* ost = bufO(ci & 1);
-      char* bo = reinterpret_cast<char*>(gout + (int64_t)tok0 * a.st);
-#pragma unroll
-      for (int p = 0; p < G::NP; ++p) {
-        const int t = 16 * p + r16;
-        const u32x2* src = reinterpret_cast<const u32x2*>(ost + t * G::OS + c0);
-        const u32x2 lo = src[0], hi2 = src[1];
-        if (t < nt)
-          *reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st * 2u + loff_b) = u32x4{lo[0], lo[1], hi2[0], hi2[1]};
-      }
-    };
-
     if (nchunks > 0) {
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{});
@@ -228,10 +222,9 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{});
     }
-    if (nchunks > 0) fill_group(0, Set0{});
+    if (nchunks > 0) fill_group(0, -1, Set0{});
     __syncthreads();                                   // buffer 0 is full
     for (int ci = 0; ci < nchunks; ++ci) {
-      if (ci > 0) store_group(ci - 1);                 // the previous group's outputs are complete
       if (ci + 1 < nchunks) {
         // the last HALO value rows of group ci become the rows before group ci + 1
         if (lt < HALO * D / 8) {
@@ -241,13 +234,12 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           const u32x2 t0 = src[0], t1 = src[1];
           dst[0] = t0; dst[1] = t1;
         }
-        TRACE(0);
-        if ((ci + 1) & 1) fill_group(ci + 1, Set1{});
-        else fill_group(ci + 1, Set0{});
-        TRACE(1);
+        if ((ci + 1) & 1) fill_group(ci + 1, ci - 1, Set1{});   // ci - 1 = -1 at the first group: nothing to store yet
+        else fill_group(ci + 1, ci - 1, Set0{});
+      } else if (ci > 0) {
+        store_group(ci - 1);
       }
       __syncthreads();                                 // barrier C
-      TRACE(2);
     }
     if (nchunks > 0) store_group(nchunks - 1);
     return;
@@ -301,8 +293,6 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     const uint16_t* Qn = bufQ(ci & 1);
     const uint16_t* Kn = bufK(ci & 1);
     const uint16_t* Vn = bufV(ci & 1);
-
-    TRACE(0);
     // ---- scores: causal tiles of P^T = phi(K) phi(Q)^T, masked, to LDS as P[t][s] ---------------------
 #pragma unroll
     for (int s = 0; s < G::MAXT; ++s) {
@@ -370,7 +360,6 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         if (lane < 32) denq[w * C + 32 * tb + l32] = acc[0];   // every row of the product is the same
       }
     }
-    TRACE(1);
     // B: the compute waves meet here (scores and normaliser partials are in LDS); the loader waves
     // are not involved.  Every compute wave adds one to an LDS counter per group and waits until the
     // counter shows that all NW of them have done so for this group.  The wait is bounded.
@@ -384,7 +373,6 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     }
-    TRACE(2);
 
     // ---- this wave's channels ------------------------------------------------------------------------
     // vf[ks]: lanes <-> channels 32w + l32, registers <-> tokens 16ks + 8hi + 0..7
@@ -459,7 +447,6 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         *reinterpret_cast<u32x2*>(orow + 8 * g) = y;
       }
     }
-    TRACE(3);
     // S += phi(K)^T V for this wave's channels, z += phi(K)^T 1 for this wave's features;
     // the phi(K)^T operands of feature block ib + 1 are requested while block ib is multiplied
     {
@@ -480,9 +467,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         }
       }
     }
-    TRACE(4);
     __syncthreads();   // C: this buffer may be refilled, the other one is complete
-    TRACE(5);
   };
 
   for (int ci = 0; ci < nchunks; ++ci) group(ci);

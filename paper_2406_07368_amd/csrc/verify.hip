@@ -10,8 +10,6 @@
 // The read-outs are then reduced across the threads that share a column group,
 // completed with the causal in-block term, normalised, and joined with the
 // convolution over (history ++ drafts <= j).
-#include <stdlib.h>
-
 #include "common.cuh"
 #include "kernels.h"
 
@@ -268,7 +266,6 @@ static hipError_t launch_split(const VerifyArgs& a, int nsplit, hipStream_t st) 
 // Columns of a head are split over 1, 2 or 4 workgroups so that small B*H still
 // puts enough workgroups on the 256 compute units.
 int verify_pick_split(int BH) {
-  if (const char* e = getenv("LINATTN_VERIFY_SPLIT")) return atoi(e);   // TEMPORARY tuning knob
   if (BH >= 768) return 1;
   if (BH >= 384) return 2;
   return 4;
