@@ -24,6 +24,8 @@ struct VerifySmem {
   float amat[KP][KP];       // phi(q_j).phi(k_j') for j' <= j, else 0
   float den[KP];            // phi(q_j).z + sum_j' amat + eps
   float zz[D];
+  float wt[8][CW];          // conv taps of the slice's channels, tap-major (taps >= Kc are 0)
+  float hh[8][CW];          // hh[t]: the value row t+1 positions before the first draft (t < Kc-1)
 };
 
 template <int KP>
@@ -59,6 +61,49 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
   const int kk = a.kk, Kc = a.Kc;
   const int cg = tid % CG, r0 = tid / CG;
 
+  // ---- 0. the small inputs are requested FIRST: every workgroup of the launch is about to ask for
+  //         its state at the same moment, and anything requested after that waits behind it ------
+  const int64_t tok0 = (int64_t)bh * kk * D;
+  const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
+  constexpr int QK_IT = (KP * (D / 8) + 255) / 256;   // 8-element pieces of q and k per thread
+  constexpr int V_IT = (KP * (CW / 8) + 255) / 256;
+  float xq[QK_IT][8], xk[QK_IT][8], xv[V_IT][8];
+#pragma unroll
+  for (int m = 0; m < QK_IT; ++m) {
+    const int c8 = tid + 256 * m;
+    const int j = c8 / (D / 8), i0 = (c8 % (D / 8)) * 8;
+    if (c8 < KP * (D / 8) && j < kk) {
+      Io::load8(a.q, tok0 + (int64_t)j * D + i0, xq[m]);
+      Io::load8(a.k, tok0 + (int64_t)j * D + i0, xk[m]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { xq[m][e] = -1e30f; xk[m][e] = -1e30f; }   // phi -> 0
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < V_IT; ++m) {
+    const int c8 = tid + 256 * m;
+    const int j = c8 / (CW / 8), cc = (c8 % (CW / 8)) * 8;
+    if (c8 < KP * (CW / 8) && j < kk) Io::load8(a.v, tok0 + (int64_t)j * D + c0 + cc, xv[m]);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) xv[m][e] = 0.f;
+    }
+  }
+  const float zreg = tid < D ? a.z[(size_t)bh * D + tid] : 0.f;
+  float wh[(16 * CW + 255) / 256];
+#pragma unroll
+  for (int m = 0; m < (16 * CW + 255) / 256; ++m) {
+    const int e = tid + 256 * m;          // rows 0..7: taps, rows 8..15: history
+    const int t = (e / CW) & 7, cc = e % CW;
+    float x = 0.f;
+    if (e < 8 * CW) { if (t < Kc) x = a.conv_w[((size_t)h * D + c0 + cc) * Kc + t]; }
+    else if (e < 16 * CW) { if (t < Kc - 1) x = Io::load1(a.hist, hist0 + (int64_t)(Kc - 2 - t) * D + c0 + cc); }
+    wh[m] = x;
+  }
+  int n = kk;
+  if (a.n_commit) { n = a.n_commit[b]; n = n < 0 ? 0 : (n > kk ? kk : n); }
+
   // ---- 0. the state slice streams through a window of PD row passes: the first PD loads are
   //         in flight before anything else, each later one is issued when its slot frees up ----
   constexpr int PDW = KP >= 8 ? 2 : 4;        // fewer passes in flight when the read-outs need the registers
@@ -68,37 +113,35 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
 #pragma unroll
   for (int p = 0; p < PD; ++p) s[p] = *reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D);
 
-  // ---- 1. drafts -> LDS (phi applied), normaliser -> LDS -----------------------
-  const int64_t tok0 = (int64_t)bh * kk * D;
-  for (int c8 = tid; c8 < KP * (D / 8); c8 += 256) {
+  // ---- 1. drafts -> LDS (phi applied), normaliser, taps and history -> LDS -----------------------
+#pragma unroll
+  for (int m = 0; m < QK_IT; ++m) {
+    const int c8 = tid + 256 * m;
     const int j = c8 / (D / 8), i0 = (c8 % (D / 8)) * 8;
-    float xq[8], xk[8];
-    if (j < kk) {
-      Io::load8(a.q, tok0 + (int64_t)j * D + i0, xq);
-      Io::load8(a.k, tok0 + (int64_t)j * D + i0, xk);
+    if (c8 < KP * (D / 8)) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { xq[e] = phi_elu1(xq[e]); xk[e] = phi_elu1(xk[e]); }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { xq[e] = 0.f; xk[e] = 0.f; }
+      for (int e = 0; e < 8; ++e) {
+        sm.fq[i0 + e][j] = j < kk ? phi_elu1(xq[m][e]) : 0.f;
+        sm.fk[i0 + e][j] = j < kk ? phi_elu1(xk[m][e]) : 0.f;
+      }
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { sm.fq[i0 + e][j] = xq[e]; sm.fk[i0 + e][j] = xk[e]; }
   }
-  for (int c8 = tid; c8 < KP * (CW / 8); c8 += 256) {
+#pragma unroll
+  for (int m = 0; m < V_IT; ++m) {
+    const int c8 = tid + 256 * m;
     const int j = c8 / (CW / 8), cc = (c8 % (CW / 8)) * 8;
-    float xv[8];
-    if (j < kk) Io::load8(a.v, tok0 + (int64_t)j * D + c0 + cc, xv);
-    else {
+    if (c8 < KP * (CW / 8)) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) xv[e] = 0.f;
+      for (int e = 0; e < 8; ++e) sm.vv[j][cc + e] = xv[m][e];
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) sm.vv[j][cc + e] = xv[e];
   }
-  if (tid < D) sm.zz[tid] = a.z[(size_t)bh * D + tid];
-  int n = kk;
-  if (a.n_commit) { n = a.n_commit[b]; n = n < 0 ? 0 : (n > kk ? kk : n); }
+  if (tid < D) sm.zz[tid] = zreg;
+#pragma unroll
+  for (int m = 0; m < (16 * CW + 255) / 256; ++m) {
+    const int e = tid + 256 * m;
+    if (e < 8 * CW) sm.wt[e / CW][e % CW] = wh[m];
+    else if (e < 16 * CW) sm.hh[(e / CW) & 7][e % CW] = wh[m];
+  }
   __syncthreads();
 
   // ---- 2. in-block scores and denominators ----------------------------------------
@@ -187,18 +230,15 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
   __syncthreads();
 
   // ---- 4. outputs: normalise, add the causal convolution -------------------------------
-  const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
   for (int idx = tid; idx < kk * CW; idx += 256) {
     const int j = idx / CW, c = idx % CW;
     float num = sm.red[0][j][c] + sm.red[1][j][c] + sm.red[2][j][c] + sm.red[3][j][c];
     for (int jp = 0; jp <= j; ++jp) num = fmaf(sm.amat[j][jp], sm.vv[jp][c], num);
-    const float* wrow = a.conv_w + ((size_t)h * D + c0 + c) * Kc;
     float u = 0.f;
     for (int t = 0; t < Kc; ++t) {
-      const int sidx = j - t;   // position in (history ++ drafts); < 0 reaches into the history
-      const float x = sidx >= 0 ? sm.vv[sidx][c]
-                                : Io::load1(a.hist, hist0 + (int64_t)(Kc - 1 + sidx) * D + c0 + c);
-      u = fmaf(wrow[t], x, u);
+      // tap t looks t rows back from draft j: another draft if t <= j, else history row (t - j) back
+      const float x = t <= j ? sm.vv[j - t][c] : sm.hh[t - j - 1][c];
+      u = fmaf(sm.wt[t][c], x, u);
     }
     Io::store1(a.out, tok0 + (int64_t)j * D + c0 + c, num / sm.den[j] + u);
   }
@@ -217,7 +257,7 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
         const int sidx = n - (Kc - 1) + r;   // position in (history ++ accepted drafts)
         const int64_t dst = hist0 + (int64_t)r * D + c0 + c;
         if (sidx >= 0) Io::store1(a.hist, dst, sm.vv[sidx][c]);
-        else Io::store1(a.hist, dst, Io::load1(a.hist, hist0 + (int64_t)(Kc - 1 + sidx) * D + c0 + c));
+        else Io::store1(a.hist, dst, sm.hh[-sidx - 1][c]);   // an old history row, -sidx positions back
       }
     }
   }
