@@ -54,6 +54,6 @@ hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, hipStream
 
 // prefill_mfma_ws.hip : the same path with loader and compute waves working side by side
 bool prefill_mfma_ws_available(int d, int chunk);
-hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, int chunk, hipStream_t st);
+hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, int chunk, bool state_only, hipStream_t st);
 
 }  // namespace linattn

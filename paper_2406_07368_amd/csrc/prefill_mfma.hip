@@ -434,21 +434,26 @@ template <int D, int C, int KCM>
 static hipError_t launch_dc(const PrefillArgs& a, hipStream_t st) {
   using G = Cfg<D, C>;
   const int BH = a.B * a.H;
-  auto full = prefill_mfma_kernel<D, C, KCM, false>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(full), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
-  if (e != hipSuccess) return e;
+  const bool ws = prefill_mfma_ws_available(D, C);   // specialised loader/compute waves: two row buffers fit in LDS
+  hipError_t e;
   if (a.nseg > 1) {
-    auto first = prefill_mfma_kernel<D, C, KCM, true>;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(first), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(first, dim3((unsigned)(BH * (a.nseg - 1))), dim3(G::NT), G::TOTAL, st, a);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (ws) {
+      if ((e = launch_prefill_mfma_ws(a, D, C, true, st)) != hipSuccess) return e;
+    } else {
+      auto first = prefill_mfma_kernel<D, C, KCM, true>;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(first), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(first, dim3((unsigned)(BH * (a.nseg - 1))), dim3(G::NT), G::TOTAL, st, a);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     constexpr int SLOT = D * D + D;
     hipLaunchKernelGGL((segment_scan_kernel<D>), dim3((SLOT + 255) / 256, (unsigned)BH), dim3(256), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  // full pass: the kernel with specialised loader/compute waves when its two row buffers fit in LDS
-  if (prefill_mfma_ws_available(D, C)) return launch_prefill_mfma_ws(a, D, C, st);
+  if (ws) return launch_prefill_mfma_ws(a, D, C, false, st);
+  auto full = prefill_mfma_kernel<D, C, KCM, false>;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(full), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(full, dim3((unsigned)(BH * a.nseg)), dim3(G::NT), G::TOTAL, st, a);
   return hipGetLastError();
 }

@@ -69,7 +69,9 @@ struct WsCfg {
 
 }  // namespace
 
-template <int D, int C, int KCM>
+// STATE_ONLY: the first pass of the segmented form -- a segment's K, V are reduced to its state
+// increment (S, z) only: no Q, no scores, no output.
+template <int D, int C, int KCM, bool STATE_ONLY>
 __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   using G = WsCfg<D, C>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -87,7 +89,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
 
-  const int bh = blockIdx.x / a.nseg, seg = blockIdx.x % a.nseg;
+  const int nseg_grid = STATE_ONLY ? a.nseg - 1 : a.nseg;
+  const int bh = blockIdx.x / nseg_grid, seg = blockIdx.x % nseg_grid;
   const int b = bh / a.H, h = bh % a.H;
   const int t_begin = seg * a.seg_len;
   const int t_end = (t_begin + a.seg_len) < a.L ? (t_begin + a.seg_len) : a.L;
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   const uint16_t* gv = static_cast<const uint16_t*>(a.v) + base;
   uint16_t* gout = static_cast<uint16_t*>(a.out) + base;
   constexpr int SLOT = D * D + D;
-  const float* ws_bh = a.ws + (size_t)bh * a.nseg * SLOT;
+  float* ws_bh = a.ws + (size_t)bh * a.nseg * SLOT;
   const uint16_t* staged_hist =
       reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
@@ -131,13 +134,13 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       if (tok + 16 <= t_end) {
         rk[SET][p] = *reinterpret_cast<const u32x4*>(bk + loff_b);
         rv[SET][p] = *reinterpret_cast<const u32x4*>(bv + loff_b);
-        rq[SET][p] = *reinterpret_cast<const u32x4*>(bq + loff_b);
+        if (!STATE_ONLY) rq[SET][p] = *reinterpret_cast<const u32x4*>(bq + loff_b);
       } else {
         const bool ok = tok + r16 < t_end;
         const u32x4 zero = {0, 0, 0, 0};
         rk[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bk + loff_b) : zero;
         rv[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bv + loff_b) : zero;
-        rq[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bq + loff_b) : zero;
+        if (!STATE_ONLY) rq[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bq + loff_b) : zero;
       }
     };
     // feature map on the 16 rows held in registers, then to buffer bi; rows >= nt become zero
@@ -150,17 +153,21 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float k0 = phi_elu1_max(bf16_lo_to_f32(rk[SET][p][i])), k1 = phi_elu1_max(bf16_hi_to_f32(rk[SET][p][i]));
-        const float q0 = phi_elu1_max(bf16_lo_to_f32(rq[SET][p][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[SET][p][i]));
         kp[i] = ok ? pack_bf16x2(k0, k1) : 0u;
-        qp[i] = ok ? pack_bf16x2(q0, q1) : 0u;
+        if (!STATE_ONLY) {
+          const float q0 = phi_elu1_max(bf16_lo_to_f32(rq[SET][p][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[SET][p][i]));
+          qp[i] = ok ? pack_bf16x2(q0, q1) : 0u;
+        }
       }
       *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
       u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + t) * G::VS + c0);
       vrow[0] = u32x2{rv[SET][p][0], rv[SET][p][1]};
       vrow[1] = u32x2{rv[SET][p][2], rv[SET][p][3]};
-      u32x2* qrow = reinterpret_cast<u32x2*>(bufQ(bi) + t * G::QS + c0);
-      qrow[0] = u32x2{qp[0], qp[1]};
-      qrow[1] = u32x2{qp[2], qp[3]};
+      if (!STATE_ONLY) {
+        u32x2* qrow = reinterpret_cast<u32x2*>(bufQ(bi) + t * G::QS + c0);
+        qrow[0] = u32x2{qp[0], qp[1]};
+        qrow[1] = u32x2{qp[2], qp[3]};
+      }
     };
     // group ci (held in set ci & 1) -> buffer ci & 1; as each pass leaves the registers, the same
     // pass of group ci + 2 is requested from HBM into the freed registers
@@ -189,7 +196,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       const bool more = ci + 2 < nchunks;
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
-        if (p == G::NP / 2 && store_ci >= 0) store_group(store_ci);
+        if (!STATE_ONLY && p == G::NP / 2 && store_ci >= 0) store_group(store_ci);
         fill_pass(bi, p, nt, set_tag);
         if (more) load_pass(ci + 2, p, set_tag);
       }
@@ -197,12 +204,12 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     using Set0 = std::integral_constant<int, 0>;
     using Set1 = std::integral_constant<int, 1>;
 
-    for (int e = lt; e < KCM * D; e += G::NLT) {
+    for (int e = lt; !STATE_ONLY && e < KCM * D; e += G::NLT) {
       const int j = e / D, cc = e % D;
       wl[e] = j < a.Kc ? a.conv_w[((size_t)h * D + cc) * a.Kc + j] : 0.f;
     }
     // value rows just before this segment: earlier tokens, else the incoming history, else zeros
-    for (int e = lt; e < HALO * D; e += G::NLT) {
+    for (int e = lt; !STATE_ONLY && e < HALO * D; e += G::NLT) {
       const int r = e / D, cc = e % D;
       const int tok = t_begin - HALO + r;
       uint16_t x = 0;
@@ -227,7 +234,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     for (int ci = 0; ci < nchunks; ++ci) {
       if (ci + 1 < nchunks) {
         // the last HALO value rows of group ci become the rows before group ci + 1
-        if (lt < HALO * D / 8) {
+        if (!STATE_ONLY && lt < HALO * D / 8) {
           const int r = lt / (D / 8), piece = 8 * (lt % (D / 8));
           const u32x2* src = reinterpret_cast<const u32x2*>(bufV(ci & 1) + (C + r) * G::VS + piece);
           u32x2* dst = reinterpret_cast<u32x2*>(bufV((ci + 1) & 1) + r * G::VS + piece);
@@ -236,12 +243,12 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         }
         if ((ci + 1) & 1) fill_group(ci + 1, ci - 1, Set1{});   // ci - 1 = -1 at the first group: nothing to store yet
         else fill_group(ci + 1, ci - 1, Set0{});
-      } else if (ci > 0) {
+      } else if (!STATE_ONLY && ci > 0) {
         store_group(ci - 1);
       }
       __syncthreads();                                 // barrier C
     }
-    if (nchunks > 0) store_group(nchunks - 1);
+    if (!STATE_ONLY && nchunks > 0) store_group(nchunks - 1);
     return;
   }
 
@@ -254,7 +261,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   {
     const float* Ssrc = nullptr;
     const float* zsrc = nullptr;
-    if (a.nseg > 1) { Ssrc = ws_bh + (size_t)seg * SLOT; zsrc = Ssrc + D * D; }
+    if (STATE_ONLY) {}
+    else if (a.nseg > 1) { Ssrc = ws_bh + (size_t)seg * SLOT; zsrc = Ssrc + D * D; }
     else if (a.S_in) { Ssrc = a.S_in + (size_t)bh * D * D; zsrc = a.z_in + (size_t)bh * D; }
 #pragma unroll
     for (int ib = 0; ib < G::IB; ++ib)
@@ -293,6 +301,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     const uint16_t* Qn = bufQ(ci & 1);
     const uint16_t* Kn = bufK(ci & 1);
     const uint16_t* Vn = bufV(ci & 1);
+    if constexpr (!STATE_ONLY) {
     // ---- scores: causal tiles of P^T = phi(K) phi(Q)^T, masked, to LDS as P[t][s] ---------------------
 #pragma unroll
     for (int s = 0; s < G::MAXT; ++s) {
@@ -374,11 +383,13 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     }
 
+    }   // !STATE_ONLY
     // ---- this wave's channels ------------------------------------------------------------------------
     // vf[ks]: lanes <-> channels 32w + l32, registers <-> tokens 16ks + 8hi + 0..7
     bf16x8 vf[G::KSC];
 #pragma unroll
     for (int ks = 0; ks < G::KSC; ++ks) vf[ks] = tr_operand(Vn + HALO * G::VS, G::VS, 16 * ks, 32 * w, lane);
+    if constexpr (!STATE_ONLY) {
 #pragma unroll
     for (int tb = 0; tb < G::TB; ++tb) {
       const int t = 32 * tb + l32;
@@ -447,6 +458,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         *reinterpret_cast<u32x2*>(orow + 8 * g) = y;
       }
     }
+    }   // !STATE_ONLY
     // S += phi(K)^T V for this wave's channels, z += phi(K)^T 1 for this wave's features;
     // the phi(K)^T operands of feature block ib + 1 are requested while block ib is multiplied
     {
@@ -473,7 +485,21 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   for (int ci = 0; ci < nchunks; ++ci) group(ci);
 
   // ---- hand the state over ---------------------------------------------------------------------------
-  if (seg == a.nseg - 1) {
+  if (STATE_ONLY) {
+    // this segment's increment goes to the slot that the prefix sum turns into the next segment's start
+    float* Sdst = ws_bh + (size_t)(seg + 1) * SLOT;
+#pragma unroll
+    for (int ib = 0; ib < G::IB; ++ib)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int i = 32 * ib + 8 * (r >> 2) + 4 * hi + (r & 3);
+        Sdst[(size_t)i * D + cw] = Sacc[ib][r];
+      }
+    if (l32 == 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) Sdst[D * D + 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3)] = Zacc[r];
+    }
+  } else if (seg == a.nseg - 1) {
     if (a.S_out) {
       float* Sdst = a.S_out + (size_t)bh * D * D;
 #pragma unroll
@@ -508,25 +534,27 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 template <int D, int C>
 bool ws_fits() { return WsCfg<D, C>::FITS; }
 
-template <int D, int C, int KCM>
+template <int D, int C, int KCM, bool STATE_ONLY>
 static hipError_t launch_ws(const PrefillArgs& a, hipStream_t st) {
   using G = WsCfg<D, C>;
   if constexpr (!G::FITS) {
     return hipErrorInvalidConfiguration;
   } else {
-    auto kern = prefill_mfma_ws_kernel<D, C, KCM>;
+    auto kern = prefill_mfma_ws_kernel<D, C, KCM, STATE_ONLY>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * a.nseg)), dim3(G::NT), G::TOTAL, st, a);
+    const int segs = STATE_ONLY ? a.nseg - 1 : a.nseg;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * segs)), dim3(G::NT), G::TOTAL, st, a);
     return hipGetLastError();
   }
 }
 
 template <int D, int C>
-static hipError_t launch_ws_k(const PrefillArgs& a, hipStream_t st) {
-  if (a.Kc <= 3) return launch_ws<D, C, 3>(a, st);
-  if (a.Kc <= 5) return launch_ws<D, C, 5>(a, st);
-  return launch_ws<D, C, 8>(a, st);
+static hipError_t launch_ws_k(const PrefillArgs& a, bool state_only, hipStream_t st) {
+  if (state_only) return launch_ws<D, C, 3, true>(a, st);   // the conv taps play no part in the state
+  if (a.Kc <= 3) return launch_ws<D, C, 3, false>(a, st);
+  if (a.Kc <= 5) return launch_ws<D, C, 5, false>(a, st);
+  return launch_ws<D, C, 8, false>(a, st);
 }
 
 // True when the specialised kernel exists for this shape (two row buffers fit in 160 KB of LDS).
@@ -535,10 +563,11 @@ bool prefill_mfma_ws_available(int d, int chunk) {
   return chunk == 64 ? ws_fits<64, 64>() : ws_fits<64, 128>();
 }
 
-// The full pass of one prefill call (all segments); segment start states must already be in a.ws.
-hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, int chunk, hipStream_t st) {
-  if (d == 128) return chunk == 64 ? launch_ws_k<128, 64>(a, st) : launch_ws_k<128, 128>(a, st);
-  return chunk == 64 ? launch_ws_k<64, 64>(a, st) : launch_ws_k<64, 128>(a, st);
+// One pass of a prefill call over all its segments.  state_only: the first pass of the segmented
+// form (segment increments into a.ws); otherwise the full pass (segment start states must be in a.ws).
+hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, int chunk, bool state_only, hipStream_t st) {
+  if (d == 128) return chunk == 64 ? launch_ws_k<128, 64>(a, state_only, st) : launch_ws_k<128, 128>(a, state_only, st);
+  return chunk == 64 ? launch_ws_k<64, 64>(a, state_only, st) : launch_ws_k<64, 128>(a, state_only, st);
 }
 
 }  // namespace linattn
