@@ -54,6 +54,10 @@ def parse_args():
     ap.add_argument("--only", choices=["all", "prefill", "verify"], default="all",
                     help="restrict the step to one stage (for profiling runs)")
     ap.add_argument("--state-sets", type=int, default=32)
+    ap.add_argument("--prefill-workload", default="cfg3_llama7b_prefill",
+                    choices=["cfg2_gpt2_small", "cfg3_llama7b_prefill", "cfg5_long_context"],
+                    help="prefill workload of the step (the headline is cfg3; the others are for side measurements)")
+    ap.add_argument("--length", type=int, default=0, help="override L of the prefill workload (length sweeps)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one elementwise kernel that reads 1 GiB and writes 1 GiB "
                          "(reference dispatch for scaling the HBM byte counters)")
@@ -127,7 +131,9 @@ def main():
     torch.cuda.set_device(dev)
     stream = torch.cuda.Stream(device=dev)
 
-    pw = workloads.CONFIGS["cfg3_llama7b_prefill"]
+    pw = workloads.CONFIGS[args.prefill_workload]
+    if args.length > 0:
+        pw = pw.small(L=args.length)
     vw = workloads.CONFIGS["cfg4_llama7b_verify"]
     do_prefill = args.only in ("all", "prefill")
     do_verify = args.only in ("all", "verify")
@@ -217,7 +223,7 @@ def main():
         "value": None, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall_ms / args.steps, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "cfg3_llama7b_prefill B8 H32 L4096 d128 bf16 chunk64 Kc3 (prefill) + "
+        "config": {"workload": f"{pw.name} B{pw.B} H{pw.H} L{pw.L} d{pw.d} bf16 chunk{pw.chunk} Kc{pw.conv_k} (prefill) + "
                                "cfg4_llama7b_verify B32 H32 d128 fp32-state k=8,4,1 (verify/decode)",
                    "step": "prefill + verify k=8 + verify k=4 + decode", "only": args.only},
     }
@@ -229,13 +235,14 @@ def main():
         result["prefill_ms"] = {"mean": mean_ms["prefill"], "min": min_ms["prefill"]}
         result["roofline"] = {"bound": "hbm", "achieved": nbytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": nbytes / t / 1e9 / HBM_PEAK_GBS,
-                              "traffic": read_traffic("prefill_mfma_cfg3_pmc.txt"),
-                              "kernel": "prefill_mfma_kernel<128,64,4,false>", "algorithmic_bytes": nbytes}
+                              "traffic": read_traffic("prefill_mfma_cfg3_pmc.txt") if pw.name.startswith("cfg3") and not args.length else None,
+                              "kernel": "prefill_mfma_ws_kernel (+ state-only pass and scan when the sequence is segmented)",
+                              "algorithmic_bytes": nbytes, "workspace_bytes": ws_bytes}
         result["mfma"] = {"tflops_causal": fc / t / 1e12, "tflops_dense_tiles": fd / t / 1e12,
                           "peak": MFMA_BF16_PEAK_TFLOPS, "frac_causal": fc / t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                           "frac_dense_tiles": fd / t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                          "note": "HBM-bound op: at 1024 B and <= 98304 flop per head-token the HBM roof caps "
-                                  "the MFMA fraction near 0.31"}
+                          "note": "HBM-bound op: at d=128, chunk 64 it moves 1024 B for <= 98304 flop per head-token, so "
+                                  "the HBM roof caps the MFMA fraction near 0.31"}
     if do_verify:
         us = {}
         roof = {}
