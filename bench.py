@@ -6,7 +6,9 @@
 One *step* is one pass over every stage of the path on synthetic, seeded inputs
 already resident in HBM:
 
-    linattn_prefill   LLaMA-2-7B layer shape  B8 H32 L4096 d128 bf16, chunk 64, Kc 3
+    linattn_prefill   LLaMA-2-7B layer shape  B8 H32 L4096 d128 bf16, chunk 64, Kc 3,
+                      q, k, v, out token-major [B,L,H,d] as a projection GEMM writes them
+                      (--layout bhld for head-major; that time is reported beside it anyway)
     linattn_verify    B32 H32 d128, fp32 state, k = 8 drafts  (state updated in place)
     linattn_verify    same, k = 4
     linattn_decode    same, one token
@@ -58,6 +60,9 @@ def parse_args():
                     choices=["cfg2_gpt2_small", "cfg3_llama7b_prefill", "cfg5_long_context"],
                     help="prefill workload of the step (the headline is cfg3; the others are for side measurements)")
     ap.add_argument("--length", type=int, default=0, help="override L of the prefill workload (length sweeps)")
+    ap.add_argument("--layout", choices=["blhd", "bhld"], default="blhd",
+                    help="memory layout of q, k, v, out: blhd = token-major [B,L,H,d], the layout a projection "
+                         "GEMM writes (default); bhld = head-major [B,H,L,d]")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one elementwise kernel that reads 1 GiB and writes 1 GiB "
                          "(reference dispatch for scaling the HBM byte counters)")
@@ -82,6 +87,13 @@ def verify_bytes(wl, kk):
     io = heads * kk * wl.d * 2 * 4
     hist = heads * (wl.conv_k - 1) * wl.d * 2 * 2
     return state + io + hist
+
+
+def layouts(wl):
+    """Tensor shape in memory and (batch, head, token) element strides of the two layouts."""
+    B, H, L, d = wl.B, wl.H, wl.L, wl.d
+    return {"blhd": ((B, L, H, d), (L * H * d, d, H * d)),
+            "bhld": ((B, H, L, d), (H * L * d, L * d, d))}
 
 
 def read_traffic(name):
@@ -142,12 +154,13 @@ def main():
     g = torch.Generator(device=dev).manual_seed(pw.seed)
     n_in = 2 if do_prefill else 0
     pin = []
+    # the values are i.i.d., so drawing them straight into either layout gives the same workload
+    shape, strides = layouts(pw)[args.layout]
     for _ in range(n_in):
-        q, k, v = ((torch.randn((pw.B, pw.H, pw.L, pw.d), generator=g, device=dev) * pw.scale).to(torch.bfloat16)
-                   for _ in range(3))
+        q, k, v = ((torch.randn(shape, generator=g, device=dev) * pw.scale).to(torch.bfloat16) for _ in range(3))
         pin.append((q, k, v, torch.empty_like(q)))
     pwts = torch.from_numpy(workloads.conv_weights(np.random.default_rng(pw.seed), pw.H, pw.d, pw.conv_k)).to(dev)
-    pdesc = binding.make_desc(pw.B, pw.H, pw.d, pw.conv_k, pw.chunk, torch.bfloat16, L=pw.L)
+    pdesc = binding.make_desc(pw.B, pw.H, pw.d, pw.conv_k, pw.chunk, torch.bfloat16, strides=strides)
     ws_bytes = binding.linattn_workspace_bytes(pdesc, pw.L)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
     S_out = torch.empty((pw.B, pw.H, pw.d, pw.d), device=dev)
@@ -215,6 +228,27 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
 
+    other_layout_ms = None
+    if do_prefill and args.only == "all":
+        # the same prefill in the other memory layout, outside the timed region, for the record
+        other = "bhld" if args.layout == "blhd" else "blhd"
+        shape2, strides2 = layouts(pw)[other]
+        desc2 = binding.make_desc(pw.B, pw.H, pw.d, pw.conv_k, pw.chunk, torch.bfloat16, strides=strides2)
+        pin2 = [tuple(t.view(shape2) for t in s4) for s4 in pin]   # same memory, read in the other order
+        ev2 = []
+        for i in range(3 + min(args.steps, 10)):
+            q, k, v, out = pin2[i % len(pin2)]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            binding.linattn_prefill(desc2, pw.L, q, k, v, pwts, None, None, None, out, S_out, z_out, h_out, ws,
+                                    ws_bytes, stream)
+            e1.record(stream)
+            if i >= 3:
+                ev2.append((e0, e1))
+        stream.synchronize()
+        other_layout_ms = {"layout": other, "mean": sum(a.elapsed_time(b) for a, b in ev2) / len(ev2),
+                           "min": min(a.elapsed_time(b) for a, b in ev2)}
+
     mean_ms = {n: (sum(a.elapsed_time(b) for a, b in lst) / len(lst)) for n, lst in ev.items() if lst}
     min_ms = {n: min(a.elapsed_time(b) for a, b in lst) for n, lst in ev.items() if lst}
 
@@ -225,7 +259,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{pw.name} B{pw.B} H{pw.H} L{pw.L} d{pw.d} bf16 chunk{pw.chunk} Kc{pw.conv_k} (prefill) + "
                                "cfg4_llama7b_verify B32 H32 d128 fp32-state k=8,4,1 (verify/decode)",
-                   "step": "prefill + verify k=8 + verify k=4 + decode", "only": args.only},
+                   "step": "prefill + verify k=8 + verify k=4 + decode", "only": args.only,
+                   "layout": {"blhd": "q,k,v,out token-major [B,L,H,d]", "bhld": "q,k,v,out head-major [B,H,L,d]"}[args.layout]},
     }
     if do_prefill:
         t = mean_ms["prefill"] * 1e-3
@@ -233,6 +268,8 @@ def main():
         fc, fd = prefill_flops(pw)
         result["value"] = pw.B * pw.L / t
         result["prefill_ms"] = {"mean": mean_ms["prefill"], "min": min_ms["prefill"]}
+        if other_layout_ms:
+            result["prefill_ms_other_layout"] = other_layout_ms
         result["roofline"] = {"bound": "hbm", "achieved": nbytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": nbytes / t / 1e9 / HBM_PEAK_GBS,
                               "traffic": read_traffic("prefill_mfma_cfg3_pmc.txt") if pw.name.startswith("cfg3") and not args.length else None,

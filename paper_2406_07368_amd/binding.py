@@ -125,11 +125,19 @@ def linattn_decode(desc: Desc, q, k, v, conv_w, S, z, hist, out, stream=None) ->
 
 # ---- conveniences that only allocate with torch and forward to the calls above ---------------
 def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, stream=None):
-    """q, k, v: dense [B,H,L,d] CUDA tensors (fp32 or bf16).  Returns out, (S, z, hist)."""
+    """q, k, v: [B,H,L,d] CUDA tensors (fp32 or bf16), dense or any view with unit stride along d
+    and equal strides for the three (e.g. ``x.transpose(1, 2)`` of a token-major [B,L,H,d] tensor);
+    ``out`` gets the same strides.  Returns out, (S, z, hist)."""
     B, H, L, d = q.shape
     Kc = conv_w.shape[2]
-    desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, L=L)
-    out = torch.empty_like(q)
+    if q.is_contiguous() and k.is_contiguous() and v.is_contiguous():
+        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, L=L)
+        out = torch.empty_like(q)
+    else:
+        if q.stride(3) != 1 or k.stride() != q.stride() or v.stride() != q.stride():
+            raise ValueError("q, k, v must share their strides and be contiguous along d")
+        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, strides=q.stride()[:3])
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     S_in, z_in, h_in = state if state is not None else (None, None, None)
     S = z = h = None
     if want_state:

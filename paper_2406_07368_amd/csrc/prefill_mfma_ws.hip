@@ -124,53 +124,57 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     u32x4 rq[2][G::NP], rk[2][G::NP], rv[2][G::NP];
     // 16 rows of group ci; uniform base + 32-bit lane offset.  Rows past the end of the segment
     // read as zero (only a segment's last group can have such rows).
-    auto load_pass = [&](int ci, int p, auto set_tag) {
+    // PARTIAL (only a segment's last group can be): rows past the end read as zero.
+    auto load_pass = [&](int ci, int p, auto set_tag, auto partial_tag) {
       constexpr int SET = decltype(set_tag)::value;
-      const int tok = t_begin + ci * C + 16 * p;       // uniform
-      const int64_t off = (int64_t)tok * a.st;         // uniform
-      const char* bk = reinterpret_cast<const char*>(gk + off);
-      const char* bv = reinterpret_cast<const char*>(gv + off);
-      const char* bq = reinterpret_cast<const char*>(gq + off);
-      if (tok + 16 <= t_end) {
-        rk[SET][p] = *reinterpret_cast<const u32x4*>(bk + loff_b);
-        rv[SET][p] = *reinterpret_cast<const u32x4*>(bv + loff_b);
-        if (!STATE_ONLY) rq[SET][p] = *reinterpret_cast<const u32x4*>(bq + loff_b);
+      constexpr bool PARTIAL = decltype(partial_tag)::value;
+      const int pk = p, pv = p, pq = p;
+      const int tok = t_begin + ci * C;                // uniform
+      const char* bk = reinterpret_cast<const char*>(gk + (int64_t)(tok + 16 * pk) * a.st);
+      const char* bv = reinterpret_cast<const char*>(gv + (int64_t)(tok + 16 * pv) * a.st);
+      const char* bq = reinterpret_cast<const char*>(gq + (int64_t)(tok + 16 * pq) * a.st);
+      if (!PARTIAL) {
+        rk[SET][pk] = *reinterpret_cast<const u32x4*>(bk + loff_b);
+        rv[SET][pv] = *reinterpret_cast<const u32x4*>(bv + loff_b);
+        if (!STATE_ONLY) rq[SET][pq] = *reinterpret_cast<const u32x4*>(bq + loff_b);
       } else {
-        const bool ok = tok + r16 < t_end;
+        const int rem = t_end - tok - r16;             // rows from this thread's row to the end
         const u32x4 zero = {0, 0, 0, 0};
-        rk[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bk + loff_b) : zero;
-        rv[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bv + loff_b) : zero;
-        if (!STATE_ONLY) rq[SET][p] = ok ? *reinterpret_cast<const u32x4*>(bq + loff_b) : zero;
+        rk[SET][pk] = 16 * pk < rem ? *reinterpret_cast<const u32x4*>(bk + loff_b) : zero;
+        rv[SET][pv] = 16 * pv < rem ? *reinterpret_cast<const u32x4*>(bv + loff_b) : zero;
+        if (!STATE_ONLY) rq[SET][pq] = 16 * pq < rem ? *reinterpret_cast<const u32x4*>(bq + loff_b) : zero;
       }
     };
-    // feature map on the 16 rows held in registers, then to buffer bi; rows >= nt become zero
-    // (phi(0) = 1, so they are cleared after the map)
-    auto fill_pass = [&](int bi, int p, int nt, auto set_tag) {
+    // feature map on the rows held in registers, then to buffer bi.  PARTIAL: rows >= nt become
+    // zero (phi(0) = 1, so they are cleared after the map).
+    auto fill_pass = [&](int bi, int p, int nt, auto set_tag, auto partial_tag) {
       constexpr int SET = decltype(set_tag)::value;
-      const int t = 16 * p + r16;
-      const bool ok = t < nt;
+      constexpr bool PARTIAL = decltype(partial_tag)::value;
+      const int pk = p, pv = p, pq = p;
+      const int tk = 16 * pk + r16, tv = 16 * pv + r16, tq = 16 * pq + r16;
+      const bool okk = !PARTIAL || tk < nt, okq = !PARTIAL || tq < nt;
       u32x4 kp, qp;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float k0 = phi_elu1_max(bf16_lo_to_f32(rk[SET][p][i])), k1 = phi_elu1_max(bf16_hi_to_f32(rk[SET][p][i]));
-        kp[i] = ok ? pack_bf16x2(k0, k1) : 0u;
+        const float k0 = phi_elu1_max(bf16_lo_to_f32(rk[SET][pk][i])), k1 = phi_elu1_max(bf16_hi_to_f32(rk[SET][pk][i]));
+        kp[i] = pack_bf16x2(k0, k1);
+        if (PARTIAL) kp[i] = okk ? kp[i] : 0u;
         if (!STATE_ONLY) {
-          const float q0 = phi_elu1_max(bf16_lo_to_f32(rq[SET][p][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[SET][p][i]));
-          qp[i] = ok ? pack_bf16x2(q0, q1) : 0u;
+          const float q0 = phi_elu1_max(bf16_lo_to_f32(rq[SET][pq][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[SET][pq][i]));
+          qp[i] = pack_bf16x2(q0, q1);
+          if (PARTIAL) qp[i] = okq ? qp[i] : 0u;
         }
       }
-      *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
-      u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + t) * G::VS + c0);
-      vrow[0] = u32x2{rv[SET][p][0], rv[SET][p][1]};
-      vrow[1] = u32x2{rv[SET][p][2], rv[SET][p][3]};
+      *reinterpret_cast<u32x4*>(bufK(bi) + tk * G::KS + c0) = kp;
+      u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + tv) * G::VS + c0);
+      vrow[0] = u32x2{rv[SET][pv][0], rv[SET][pv][1]};
+      vrow[1] = u32x2{rv[SET][pv][2], rv[SET][pv][3]};
       if (!STATE_ONLY) {
-        u32x2* qrow = reinterpret_cast<u32x2*>(bufQ(bi) + t * G::QS + c0);
+        u32x2* qrow = reinterpret_cast<u32x2*>(bufQ(bi) + tq * G::QS + c0);
         qrow[0] = u32x2{qp[0], qp[1]};
         qrow[1] = u32x2{qp[2], qp[3]};
       }
     };
-    // group ci (held in set ci & 1) -> buffer ci & 1; as each pass leaves the registers, the same
-    // pass of group ci + 2 is requested from HBM into the freed registers
     // finished output rows of group ci (left in LDS by the compute waves) -> HBM, whole rows per
     // D/8 consecutive lanes, 16 bytes per lane
     auto store_group = [&](int ci) {
@@ -188,17 +192,29 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       }
     };
 
-    // `store_ci` >= 0: that group's finished output rows are written out half-way through, so that
-    // no HBM request is younger than half a group when the next fill starts waiting for its rows
+    // Only the last group of a segment can be short; everything about it takes the PARTIAL paths.
+    const bool last_partial = (t_end - t_begin) % C != 0;
+    auto is_partial = [&](int ci) { return last_partial && ci == nchunks - 1; };
+    using Full = std::false_type;
+    using Part = std::true_type;
+    // group ci (held in set ci & 1) -> buffer ci & 1; as each pass leaves the registers, the same
+    // pass of group ci + 2 is requested from HBM into the freed registers.  `store_ci` >= 0: that
+    // group's finished output rows are written out half-way through, so that no HBM request is
+    // younger than half a group when the next fill starts waiting for its rows.
     auto fill_group = [&](int ci, int store_ci, auto set_tag) {
       const int bi = ci & 1;
       const int nt = (t_end - (t_begin + ci * C)) < C ? (t_end - (t_begin + ci * C)) : C;
       const bool more = ci + 2 < nchunks;
+      const bool fill_part = is_partial(ci), load_part = is_partial(ci + 2);
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
         if (!STATE_ONLY && p == G::NP / 2 && store_ci >= 0) store_group(store_ci);
-        fill_pass(bi, p, nt, set_tag);
-        if (more) load_pass(ci + 2, p, set_tag);
+        if (!fill_part) fill_pass(bi, p, nt, set_tag, Full{});
+        else fill_pass(bi, p, nt, set_tag, Part{});
+        if (more) {
+          if (!load_part) load_pass(ci + 2, p, set_tag, Full{});
+          else load_pass(ci + 2, p, set_tag, Part{});
+        }
       }
     };
     using Set0 = std::integral_constant<int, 0>;
@@ -223,11 +239,11 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     }
     if (nchunks > 0) {
 #pragma unroll
-      for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{});
+      for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{}, Part{});
     }
     if (nchunks > 1) {
 #pragma unroll
-      for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{});
+      for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{}, Part{});
     }
     if (nchunks > 0) fill_group(0, -1, Set0{});
     __syncthreads();                                   // buffer 0 is full

@@ -105,12 +105,16 @@ def test_config2_full():
     compare(got, want, "bf16", "config 2")
 
 
-def _sampled_full_size(name, sample, L=None):
+def _sampled_full_size(name, sample, L=None, token_major=False):
     wl = workloads.CONFIGS[name]
     if L is not None:
         wl = wl.small(L=L)
     q, k, v, w = workloads.prefill_tensors(wl)
-    out, (S, z, h) = binding.prefill(q.cuda(), k.cuda(), v.cuda(), w.cuda(), None, wl.chunk)
+    gq, gk, gv = q.cuda(), k.cuda(), v.cuda()
+    if token_major:   # [B,L,H,d] in memory, seen as [B,H,L,d]
+        gq, gk, gv = (x.transpose(1, 2).contiguous().transpose(1, 2) for x in (gq, gk, gv))
+    out, (S, z, h) = binding.prefill(gq, gk, gv, w.cuda(), None, wl.chunk)
+    assert out.stride() == gq.stride()
     torch.cuda.synchronize()
     worst = 0.0
     for b, hh in sample:
@@ -124,6 +128,12 @@ def _sampled_full_size(name, sample, L=None):
 def test_config3_full_size_sampled_heads():
     """LLaMA-2-7B layer shape B8 H32 L4096 d128 bf16 run at full size; six heads followed by the oracle."""
     _sampled_full_size("cfg3_llama7b_prefill", [(0, 0), (1, 13), (3, 31), (5, 7), (7, 16), (7, 31)])
+
+
+def test_config3_full_size_token_major_sampled_heads():
+    """The same workload with q, k, v, out laid out [B,L,H,d] (what a projection GEMM writes and
+    what bench.py times); four heads followed by the oracle."""
+    _sampled_full_size("cfg3_llama7b_prefill", [(0, 0), (2, 5), (6, 30), (7, 31)], token_major=True)
 
 
 def test_config5_long_context_sampled_heads():
