@@ -62,7 +62,8 @@ struct WsCfg {
   static constexpr int OS = D + 4;           // output staging rows: 8-byte writes, one row per lane
   static constexpr int OFF_OST = OFF_WL + KCMAX * D * 4;   // [2][C][OS] bf16: finished output rows of a group
   static constexpr int OST = C * OS * 2;
-  static constexpr int OFF_SYNC = OFF_OST + 2 * OST;       // one counter for the compute waves' meeting point
+  static constexpr int OFF_ZOP = OFF_OST + 2 * OST;        // [NW][2][16] bf16: z as the MFMA operand of each feature block
+  static constexpr int OFF_SYNC = OFF_ZOP + NW * 64;       // the counter of the front-end waves' signal
   static constexpr int TOTAL = OFF_SYNC + 16;
   static constexpr bool FITS = TOTAL <= 160 * 1024;
 };
@@ -75,19 +76,36 @@ template <int D, int C, int KCM, bool STATE_ONLY>
 __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   using G = WsCfg<D, C>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+
   uint16_t* Pn = reinterpret_cast<uint16_t*>(smem + G::OFF_PN);
   float* denq = reinterpret_cast<float*>(smem + G::OFF_DENQ);
   float* denp = reinterpret_cast<float*>(smem + G::OFF_DENP);
   float* wl = reinterpret_cast<float*>(smem + G::OFF_WL);
-  unsigned* syncB = reinterpret_cast<unsigned*>(smem + G::OFF_SYNC);
+  uint16_t* zop = reinterpret_cast<uint16_t*>(smem + G::OFF_ZOP);
+  // A counter that only ever grows: every front-end wave adds one per group once its share of the
+  // group's scores, their row sums and phi(q).z is in LDS.
+  unsigned* sync_q = reinterpret_cast<unsigned*>(smem + G::OFF_SYNC);
+  auto signal = [&](unsigned* ctr) __attribute__((always_inline)) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    if (lane == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  };
+  // Bounded wait: the signalling waves never wait for anything that depends on the waiting ones
+  // before they signal, so the count is always reached; the bound only keeps a logic error from
+  // hanging the GPU (the results would then be wrong, not the machine stuck).
+  auto wait_for = [&](unsigned* ctr, unsigned want) __attribute__((always_inline)) {
+    for (int spin = 0; spin < (1 << 20); ++spin) {
+      if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= want) break;
+      __builtin_amdgcn_s_sleep(1);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  };
   auto bufQ = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BQ); };
   auto bufK = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BK); };
   auto bufV = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BV); };   // row r = token r - HALO
   auto bufO = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + G::OFF_OST + bi * G::OST); };
-
-  const int tid = threadIdx.x;
-  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
 
   const int nseg_grid = STATE_ONLY ? a.nseg - 1 : a.nseg;
   const int bh = blockIdx.x / nseg_grid, seg = blockIdx.x % nseg_grid;
@@ -105,7 +123,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   const uint16_t* staged_hist =
       reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
-  if (tid == 0) *syncB = 0u;
+  if (tid == 0) *sync_q = 0u;
+  __syncthreads();                                     // the counters are used before the next barrier
 
   if (wv >= G::NW) {
     // =============================== loader waves ===============================================
@@ -119,106 +138,187 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 
     const uint32_t loff_b = (uint32_t)(r16 * (int)a.st + c0) * 2u;   // this thread's byte offset inside a pass
 
-    // two register sets: group ci lives in set ci & 1 from the moment it is requested (two groups
-    // ahead of its use) until it has been written to LDS
+    // Two register sets: group g lives in set g & 1 from the moment it is requested (two groups
+    // ahead of its use) until it has been written to LDS.
+    //
+    // Every load below is issued unconditionally (groups past the end re-read the last group, rows
+    // past the end re-read the last row; neither is used), and the main loop is unrolled by two so
+    // that the set of each step is fixed at compile time.  The compiler counts outstanding memory
+    // operations statically: only with a fixed sequence of them can it wait for exactly the pass
+    // that is needed while the requests of the following two groups stay in flight.
     u32x4 rq[2][G::NP], rk[2][G::NP], rv[2][G::NP];
-    // 16 rows of group ci; uniform base + 32-bit lane offset.  Rows past the end of the segment
-    // read as zero (only a segment's last group can have such rows).
-    // PARTIAL (only a segment's last group can be): rows past the end read as zero.
-    auto load_pass = [&](int ci, int p, auto set_tag, auto partial_tag) {
+    using Full = std::false_type;
+    using Part = std::true_type;
+    // Only the last group of a segment can be short; everything about it takes the PARTIAL paths.
+    const bool last_partial = (t_end - t_begin) % C != 0;
+    // 16 rows of group g: uniform base + 32-bit lane offset
+    auto load_pass = [&](int g, int p, auto set_tag, auto partial_tag) __attribute__((always_inline)) {
       constexpr int SET = decltype(set_tag)::value;
       constexpr bool PARTIAL = decltype(partial_tag)::value;
-      const int pk = p, pv = p, pq = p;
-      const int tok = t_begin + ci * C;                // uniform
-      const char* bk = reinterpret_cast<const char*>(gk + (int64_t)(tok + 16 * pk) * a.st);
-      const char* bv = reinterpret_cast<const char*>(gv + (int64_t)(tok + 16 * pv) * a.st);
-      const char* bq = reinterpret_cast<const char*>(gq + (int64_t)(tok + 16 * pq) * a.st);
-      if (!PARTIAL) {
-        rk[SET][pk] = *reinterpret_cast<const u32x4*>(bk + loff_b);
-        rv[SET][pv] = *reinterpret_cast<const u32x4*>(bv + loff_b);
-        if (!STATE_ONLY) rq[SET][pq] = *reinterpret_cast<const u32x4*>(bq + loff_b);
+      const int gc = g < nchunks ? g : nchunks - 1;    // uniform
+      const int tok = t_begin + gc * C + 16 * p;       // uniform
+      const int64_t off = (int64_t)tok * a.st;
+      const char* bk = reinterpret_cast<const char*>(gk + off);
+      const char* bv = reinterpret_cast<const char*>(gv + off);
+      const char* bq = reinterpret_cast<const char*>(gq + off);
+      uint32_t lo = loff_b;
+      if (PARTIAL) {
+        const int last = t_end - 1 - tok;              // last row of the segment, relative to this pass
+        const int r = r16 <= last ? r16 : last;        // negative only when the whole pass is past the end
+        lo = (uint32_t)((r < 0 ? last : r) * (int)a.st + c0) * 2u;   // byte offset, may be negative: wraps with the base
+        rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + (int32_t)lo));
+        rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + (int32_t)lo));
+        if (!STATE_ONLY) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + (int32_t)lo));
       } else {
-        const int rem = t_end - tok - r16;             // rows from this thread's row to the end
-        const u32x4 zero = {0, 0, 0, 0};
-        rk[SET][pk] = 16 * pk < rem ? *reinterpret_cast<const u32x4*>(bk + loff_b) : zero;
-        rv[SET][pv] = 16 * pv < rem ? *reinterpret_cast<const u32x4*>(bv + loff_b) : zero;
-        if (!STATE_ONLY) rq[SET][pq] = 16 * pq < rem ? *reinterpret_cast<const u32x4*>(bq + loff_b) : zero;
+        rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + lo));
+        rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + lo));
+        if (!STATE_ONLY) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + lo));
       }
     };
-    // feature map on the rows held in registers, then to buffer bi.  PARTIAL: rows >= nt become
-    // zero (phi(0) = 1, so they are cleared after the map).
-    auto fill_pass = [&](int bi, int p, int nt, auto set_tag, auto partial_tag) {
+    // feature map on the 16 rows held in registers, then to buffer bi.  PARTIAL: rows >= nt become
+    // zero rows (phi(0) = 1, so they are cleared after the map).
+    auto fill_pass = [&](int bi, int p, int nt, auto set_tag, auto partial_tag) __attribute__((always_inline)) {
       constexpr int SET = decltype(set_tag)::value;
       constexpr bool PARTIAL = decltype(partial_tag)::value;
-      const int pk = p, pv = p, pq = p;
-      const int tk = 16 * pk + r16, tv = 16 * pv + r16, tq = 16 * pq + r16;
-      const bool okk = !PARTIAL || tk < nt, okq = !PARTIAL || tq < nt;
-      u32x4 kp, qp;
+      const int t = 16 * p + r16;
+      const bool ok = !PARTIAL || t < nt;
+      u32x4 kp, qp, vp = rv[SET][p];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const float k0 = phi_elu1_max(bf16_lo_to_f32(rk[SET][pk][i])), k1 = phi_elu1_max(bf16_hi_to_f32(rk[SET][pk][i]));
+        const float k0 = phi_elu1_max(bf16_lo_to_f32(rk[SET][p][i])), k1 = phi_elu1_max(bf16_hi_to_f32(rk[SET][p][i]));
         kp[i] = pack_bf16x2(k0, k1);
-        if (PARTIAL) kp[i] = okk ? kp[i] : 0u;
+        if (PARTIAL) { kp[i] = ok ? kp[i] : 0u; vp[i] = ok ? vp[i] : 0u; }
         if (!STATE_ONLY) {
-          const float q0 = phi_elu1_max(bf16_lo_to_f32(rq[SET][pq][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[SET][pq][i]));
+          const float q0 = phi_elu1_max(bf16_lo_to_f32(rq[SET][p][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[SET][p][i]));
           qp[i] = pack_bf16x2(q0, q1);
-          if (PARTIAL) qp[i] = okq ? qp[i] : 0u;
+          if (PARTIAL) qp[i] = ok ? qp[i] : 0u;
         }
       }
-      *reinterpret_cast<u32x4*>(bufK(bi) + tk * G::KS + c0) = kp;
-      u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + tv) * G::VS + c0);
-      vrow[0] = u32x2{rv[SET][pv][0], rv[SET][pv][1]};
-      vrow[1] = u32x2{rv[SET][pv][2], rv[SET][pv][3]};
+      *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
+      u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + t) * G::VS + c0);
+      vrow[0] = u32x2{vp[0], vp[1]};
+      vrow[1] = u32x2{vp[2], vp[3]};
       if (!STATE_ONLY) {
-        u32x2* qrow = reinterpret_cast<u32x2*>(bufQ(bi) + tq * G::QS + c0);
+        u32x2* qrow = reinterpret_cast<u32x2*>(bufQ(bi) + t * G::QS + c0);
         qrow[0] = u32x2{qp[0], qp[1]};
         qrow[1] = u32x2{qp[2], qp[3]};
       }
     };
-    // finished output rows of group ci (left in LDS by the compute waves) -> HBM, whole rows per
-    // D/8 consecutive lanes, 16 bytes per lane
-    auto store_group = [&](int ci) {
-      const int tok0 = t_begin + ci * C;
+    // finished output rows of group g (left in LDS by the state waves) -> HBM, whole rows per
+    // D/8 consecutive lanes, 16 bytes per lane.  PARTIAL: only the rows that exist.
+    auto store_group = [&](int g, auto partial_tag) __attribute__((always_inline)) {
+      constexpr bool PARTIAL = decltype(partial_tag)::value;
+      const int tok0 = t_begin + g * C;
       const int nt = (t_end - tok0) < C ? (t_end - tok0) : C;
-      const uint16_t* ost = bufO(ci & 1);
+      const uint16_t* ost = bufO(g & 1);
       char* bo = reinterpret_cast<char*>(gout + (int64_t)tok0 * a.st);
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
         const int t = 16 * p + r16;
         const u32x2* src = reinterpret_cast<const u32x2*>(ost + t * G::OS + c0);
         const u32x2 lo = src[0], hi2 = src[1];
-        if (t < nt)
-          *reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st * 2u + loff_b) = u32x4{lo[0], lo[1], hi2[0], hi2[1]};
+        if (!PARTIAL || t < nt)
+          __builtin_nontemporal_store(u32x4{lo[0], lo[1], hi2[0], hi2[1]}, reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st * 2u + loff_b));
       }
     };
-
-    // Only the last group of a segment can be short; everything about it takes the PARTIAL paths.
-    const bool last_partial = (t_end - t_begin) % C != 0;
-    auto is_partial = [&](int ci) { return last_partial && ci == nchunks - 1; };
-    using Full = std::false_type;
-    using Part = std::true_type;
-    // group ci (held in set ci & 1) -> buffer ci & 1; as each pass leaves the registers, the same
-    // pass of group ci + 2 is requested from HBM into the freed registers.  `store_ci` >= 0: that
-    // group's finished output rows are written out half-way through, so that no HBM request is
-    // younger than half a group when the next fill starts waiting for its rows.
-    auto fill_group = [&](int ci, int store_ci, auto set_tag) {
-      const int bi = ci & 1;
-      const int nt = (t_end - (t_begin + ci * C)) < C ? (t_end - (t_begin + ci * C)) : C;
-      const bool more = ci + 2 < nchunks;
-      const bool fill_part = is_partial(ci), load_part = is_partial(ci + 2);
+    // Group g (held in set g & 1) -> buffer g & 1; as each pass leaves the registers, the same pass
+    // of group g + 2 is requested from HBM into the freed registers.  STORE: the finished output
+    // rows of group g - 2 (always a full group) are written out half-way through, so that no HBM
+    // request is younger than half a group when the next fill starts waiting for its rows.
+    auto fill_group = [&](int g, auto set_tag, auto store_tag) __attribute__((always_inline)) {
+      constexpr bool STORE = decltype(store_tag)::value;
+      const int bi = g & 1;
+      const int nt = (t_end - (t_begin + g * C)) < C ? (t_end - (t_begin + g * C)) : C;
+      const bool fill_part = last_partial && g == nchunks - 1;
+      const bool load_part = last_partial && g + 2 >= nchunks - 1;
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
-        if (!STATE_ONLY && p == G::NP / 2 && store_ci >= 0) store_group(store_ci);
+        if (!STATE_ONLY && STORE && p == G::NP / 2) store_group(g - 2, Full{});
         if (!fill_part) fill_pass(bi, p, nt, set_tag, Full{});
         else fill_pass(bi, p, nt, set_tag, Part{});
-        if (more) {
-          if (!load_part) load_pass(ci + 2, p, set_tag, Full{});
-          else load_pass(ci + 2, p, set_tag, Part{});
-        }
+        if (!load_part) load_pass(g + 2, p, set_tag, Full{});
+        else load_pass(g + 2, p, set_tag, Part{});
       }
     };
     using Set0 = std::integral_constant<int, 0>;
     using Set1 = std::integral_constant<int, 1>;
+
+    // Scores of group ci from its rows in LDS: the causal 32 x 32 tiles of P^T = phi(K) phi(Q)^T,
+    // masked by select, to LDS as P[t][s] in bf16, and the row sums of each tile (of the fp32
+    // values) as the scores' part of the normaliser.  Tiles are dealt out over the waves.
+    auto scores = [&](int ci) __attribute__((always_inline)) {
+      const uint16_t* Qn = bufQ(ci & 1);
+      const uint16_t* Kn = bufK(ci & 1);
+#pragma unroll
+      for (int s = 0; s < G::MAXT; ++s) {
+        const int idx = lw + s * G::NW;
+        if (idx < G::NTILE) {
+          int tb = 0;
+          while ((tb + 1) * (tb + 2) / 2 <= idx) ++tb;
+          const int sb = idx - tb * (tb + 1) / 2;
+          f32x16 acc;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+          const uint16_t* ka = Kn + (32 * sb + l32) * G::KS + 8 * hi;
+          const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 8 * hi;
+          constexpr int HB = G::KSD / 2;   // two batches of K steps
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            bf16x8 ak[HB], bq[HB];
+#pragma unroll
+            for (int k2 = 0; k2 < HB; ++k2) {
+              const int ks = half * HB + k2;
+              ak[k2] = lds_row8(ka + 16 * ks);
+              bq[k2] = cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k2 = 0; k2 < HB; ++k2) acc = mfma(ak[k2], bq[k2], acc);
+          }
+          // acc[r]: source token s = 32sb + 8(r/4) + 4hi + r%4, query token t = 32tb + l32
+          float rs = 0.f;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            float x[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int sl = 8 * g + 4 * hi + e;
+              const float v0 = acc[4 * g + e];
+              x[e] = (sb < tb || sl <= l32) ? v0 : 0.f;   // select, never multiply: later tokens cannot leak
+              rs += x[e];
+            }
+            u32x2 pk = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
+            *reinterpret_cast<u32x2*>(Pn + (32 * tb + l32) * G::PS + 32 * sb + 8 * g + 4 * hi) = pk;
+          }
+          rs += __shfl_xor(rs, 32);
+          if (lane < 32) denp[sb * C + 32 * tb + l32] = rs;
+        }
+      }
+    };
+    // phi(q_t).z over feature block lw, for every token of group ci; z (the state before the group)
+    // is read from LDS in operand form, where the state waves left it
+    auto q_dot_z = [&](int ci) __attribute__((always_inline)) {
+      const uint16_t* Qn = bufQ(ci & 1);
+      bf16x8 bq[G::TB][2];
+#pragma unroll
+      for (int tb = 0; tb < G::TB; ++tb) {
+        const uint16_t* p = Qn + (32 * tb + l32) * G::QS + 32 * lw + 4 * hi;
+        bq[tb][0] = cat4(lds_row4(p), lds_row4(p + 8));
+        bq[tb][1] = cat4(lds_row4(p + 16), lds_row4(p + 24));
+      }
+      const uint16_t* zp = zop + (2 * lw + hi) * 16;
+      const bf16x8 zb0 = lds_row8(zp), zb1 = lds_row8(zp + 8);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int tb = 0; tb < G::TB; ++tb) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        acc = mfma(zb0, bq[tb][0], acc);
+        acc = mfma(zb1, bq[tb][1], acc);
+        if (lane < 32) denq[lw * C + 32 * tb + l32] = acc[0];   // every row of the product is the same
+      }
+    };
 
     for (int e = lt; !STATE_ONLY && e < KCM * D; e += G::NLT) {
       const int j = e / D, cc = e % D;
@@ -240,31 +340,53 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     if (nchunks > 0) {
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{}, Part{});
-    }
-    if (nchunks > 1) {
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{}, Part{});
+      fill_group(0, Set0{}, std::false_type{});
     }
-    if (nchunks > 0) fill_group(0, -1, Set0{});
-    __syncthreads();                                   // buffer 0 is full
-    for (int ci = 0; ci < nchunks; ++ci) {
-      if (ci + 1 < nchunks) {
+    __syncthreads();                                   // buffer 0 is full, z is in LDS
+
+    // One step of the front end.  First the scores and phi(q).z of group ci, which the state waves
+    // need a little later (they start with the products that involve the state only); then, while
+    // the state waves work on group ci, group ci + 1 is filled, group ci + 3 requested and group
+    // ci - 1 stored.
+    auto step = [&](int ci, auto set_tag, auto store_tag) __attribute__((always_inline)) {
+      if (!STATE_ONLY) {
+        scores(ci);
+        q_dot_z(ci);
+        signal(sync_q);
         // the last HALO value rows of group ci become the rows before group ci + 1
-        if (!STATE_ONLY && lt < HALO * D / 8) {
+        if (lt < HALO * D / 8) {
           const int r = lt / (D / 8), piece = 8 * (lt % (D / 8));
           const u32x2* src = reinterpret_cast<const u32x2*>(bufV(ci & 1) + (C + r) * G::VS + piece);
           u32x2* dst = reinterpret_cast<u32x2*>(bufV((ci + 1) & 1) + r * G::VS + piece);
           const u32x2 t0 = src[0], t1 = src[1];
           dst[0] = t0; dst[1] = t1;
         }
-        if ((ci + 1) & 1) fill_group(ci + 1, ci - 1, Set1{});   // ci - 1 = -1 at the first group: nothing to store yet
-        else fill_group(ci + 1, ci - 1, Set0{});
-      } else if (!STATE_ONLY && ci > 0) {
-        store_group(ci - 1);
+      }
+      fill_group(ci + 1, set_tag, store_tag);
+      __syncthreads();                                 // barrier C
+    };
+    int ci = 0;
+    if (nchunks > 1) { step(0, Set1{}, std::false_type{}); ci = 1; }
+    for (; ci + 2 < nchunks; ci += 2) {                // ci is odd here: group ci + 1 is even
+      step(ci, Set0{}, std::true_type{});
+      step(ci + 1, Set1{}, std::true_type{});
+    }
+    if (ci >= 1 && ci + 1 < nchunks) { step(ci, Set0{}, std::true_type{}); ++ci; }
+    if (nchunks > 0) {                                 // ci == nchunks - 1: nothing left to fill
+      if (!STATE_ONLY) {
+        scores(ci);
+        q_dot_z(ci);
+        signal(sync_q);
+        if (ci > 0) store_group(ci - 1, Full{});
       }
       __syncthreads();                                 // barrier C
     }
-    if (!STATE_ONLY && nchunks > 0) store_group(nchunks - 1);
+    if (!STATE_ONLY && nchunks > 0) {
+      if (last_partial) store_group(nchunks - 1, Part{});
+      else store_group(nchunks - 1, Full{});
+    }
     return;
   }
 
@@ -294,7 +416,18 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
 
-  __syncthreads();                                     // buffer 0 is full, conv taps are in LDS
+  // z of the state as it stands, as the bf16 MFMA operand of this wave's feature block, for the
+  // front-end waves' phi(q).z of the next group
+  auto publish_z = [&]() __attribute__((always_inline)) {
+    if (l32 == 0) {
+      uint16_t* zp = zop + (2 * w + hi) * 16;
+      *reinterpret_cast<bf16x8*>(zp) = pack8(Zacc, 0);
+      *reinterpret_cast<bf16x8*>(zp + 8) = pack8(Zacc, 8);
+    }
+  };
+  if (!STATE_ONLY) publish_z();
+
+  __syncthreads();                                     // buffer 0 is full, its scores and the conv taps are in LDS
 
   // conv taps of this lane's 16 output channels (32w + 8g + 4hi + e), kept in registers when few
   constexpr bool W_REGS = KCM <= 3 && D == 64;   // D = 128 runs two waves per SIMD: 256 registers each
@@ -312,114 +445,46 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #define LINATTN_FENCE() __builtin_amdgcn_sched_barrier(0)
 
   // One group of C tokens.  A short last group needs no special case here: its missing rows are
-  // zero rows in LDS, and the loader waves do not store their outputs.
-  auto group = [&](int ci) {
+  // zero rows in LDS, and the front-end waves do not store their outputs.
+  auto group = [&](int ci) __attribute__((always_inline)) {
     const uint16_t* Qn = bufQ(ci & 1);
     const uint16_t* Kn = bufK(ci & 1);
     const uint16_t* Vn = bufV(ci & 1);
-    if constexpr (!STATE_ONLY) {
-    // ---- scores: causal tiles of P^T = phi(K) phi(Q)^T, masked, to LDS as P[t][s] ---------------------
-#pragma unroll
-    for (int s = 0; s < G::MAXT; ++s) {
-      const int idx = w + s * G::NW;
-      if (idx < G::NTILE) {
-        int tb = 0;
-        while ((tb + 1) * (tb + 2) / 2 <= idx) ++tb;
-        const int sb = idx - tb * (tb + 1) / 2;
-        f32x16 acc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        const uint16_t* ka = Kn + (32 * sb + l32) * G::KS + 8 * hi;
-        const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 8 * hi;
-        constexpr int HB = G::KSD / 2;   // two batches of K steps
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          bf16x8 ak[HB], bq[HB];
-#pragma unroll
-          for (int k2 = 0; k2 < HB; ++k2) {
-            const int ks = half * HB + k2;
-            ak[k2] = lds_row8(ka + 16 * ks);
-            bq[k2] = cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4));
-          }
-          LINATTN_FENCE();
-#pragma unroll
-          for (int k2 = 0; k2 < HB; ++k2) acc = mfma(ak[k2], bq[k2], acc);
-        }
-        // acc[r]: source token s = 32sb + 8(r/4) + 4hi + r%4, query token t = 32tb + l32
-        float rs = 0.f;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float x[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int sl = 8 * g + 4 * hi + e;
-            const float v0 = acc[4 * g + e];
-            x[e] = (sb < tb || sl <= l32) ? v0 : 0.f;   // select, never multiply: later tokens cannot leak
-            rs += x[e];
-          }
-          u32x2 pk = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
-          *reinterpret_cast<u32x2*>(Pn + (32 * tb + l32) * G::PS + 32 * sb + 8 * g + 4 * hi) = pk;
-        }
-        rs += __shfl_xor(rs, 32);
-        if (lane < 32) denp[sb * C + 32 * tb + l32] = rs;
-      }
-    }
-    // ---- phi(q_t).z over this wave's 32 features, for every token of the group -------------------------
-    {
-      bf16x8 bq[G::TB][2];
-#pragma unroll
-      for (int tb = 0; tb < G::TB; ++tb) {
-        const uint16_t* p = Qn + (32 * tb + l32) * G::QS + 32 * w + 4 * hi;
-        bq[tb][0] = cat4(lds_row4(p), lds_row4(p + 8));
-        bq[tb][1] = cat4(lds_row4(p + 16), lds_row4(p + 24));
-      }
-      const bf16x8 zb0 = pack8(Zacc, 0), zb1 = pack8(Zacc, 8);
-      LINATTN_FENCE();
-#pragma unroll
-      for (int tb = 0; tb < G::TB; ++tb) {
-        f32x16 acc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        acc = mfma(zb0, bq[tb][0], acc);
-        acc = mfma(zb1, bq[tb][1], acc);
-        if (lane < 32) denq[w * C + 32 * tb + l32] = acc[0];   // every row of the product is the same
-      }
-    }
-    // B: the compute waves meet here (scores and normaliser partials are in LDS); the loader waves
-    // are not involved.  Every compute wave adds one to an LDS counter per group and waits until the
-    // counter shows that all NW of them have done so for this group.  The wait is bounded.
-    {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-      if (lane == 0) __hip_atomic_fetch_add(syncB, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      const unsigned want = (unsigned)G::NW * (unsigned)(ci + 1);
-      for (int spin = 0; spin < (1 << 20); ++spin) {
-        if (__hip_atomic_load(syncB, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= want) break;
-        __builtin_amdgcn_s_sleep(1);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    }
-
-    }   // !STATE_ONLY
     // ---- this wave's channels ------------------------------------------------------------------------
     // vf[ks]: lanes <-> channels 32w + l32, registers <-> tokens 16ks + 8hi + 0..7
     bf16x8 vf[G::KSC];
 #pragma unroll
     for (int ks = 0; ks < G::KSC; ++ks) vf[ks] = tr_operand(Vn + HALO * G::VS, G::VS, 16 * ks, 32 * w, lane);
     if constexpr (!STATE_ONLY) {
+    // First the part that needs the state only, S^T phi(Q)^T, for every token block; the front-end
+    // waves compute the scores of this group meanwhile.
+    // o[tb][r] = O[token 32tb + l32][channel 32w + 8(r/4) + 4hi + r%4]
+    f32x16 o[G::TB];
+#pragma unroll
+    for (int tb = 0; tb < G::TB; ++tb) {
+      // register r of S holds feature 32ib + 8(r/4) + 4hi + r%4, so the phi(Q) operand takes
+      // features {16h2 + 4hi + 0..3, 16h2 + 8 + 4hi + 0..3} of block ib for MFMA step h2
+      bf16x8 qB[2 * G::IB];
+      const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 4 * hi;
+#pragma unroll
+      for (int x = 0; x < 2 * G::IB; ++x) qB[x] = cat4(lds_row4(qb + 16 * x), lds_row4(qb + 16 * x + 8));
+      LINATTN_FENCE();
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[tb][r] = 0.f;
+#pragma unroll
+      for (int ib = 0; ib < G::IB; ++ib)
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) o[tb] = mfma(pack8(Sacc[ib], 8 * h2), qB[2 * ib + h2], o[tb]);
+    }
+    wait_for(sync_q, (unsigned)G::NW * (unsigned)(ci + 1));   // scores, their row sums and phi(q).z are in LDS
 #pragma unroll
     for (int tb = 0; tb < G::TB; ++tb) {
       const int t = 32 * tb + l32;
-      // operands and epilogue inputs of this token block, all requested before the first MFMA
-      bf16x8 pB[2 * G::TB], qB[2 * G::IB];
+      // the scores of this token block (lane <-> query token) and the parts of the normaliser
+      bf16x8 pB[2 * G::TB];
       const uint16_t* pb = Pn + t * G::PS + 8 * hi;
 #pragma unroll
       for (int ks = 0; ks < 2 * (tb + 1); ++ks) pB[ks] = lds_row8(pb + 16 * ks);
-      // S^T phi(Q)^T: register r of S holds feature 32ib + 8(r/4) + 4hi + r%4, so the phi(Q) operand
-      // takes features {16h2 + 4hi + 0..3, 16h2 + 8 + 4hi + 0..3} of block ib for MFMA step h2
-      const uint16_t* qb = Qn + t * G::QS + 4 * hi;
-#pragma unroll
-      for (int x = 0; x < 2 * G::IB; ++x) qB[x] = cat4(lds_row4(qb + 16 * x), lds_row4(qb + 16 * x + 8));
-      float den = a.eps;
       float dpart[G::NW + G::TB];
 #pragma unroll
       for (int ww = 0; ww < G::NW; ++ww) dpart[ww] = denq[ww * C + t];
@@ -430,7 +495,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       // conv inputs of channel group g are requested one group ahead of their use
       u32x2 xv[2][KCM];
       f32x4 wv[2][W_REGS ? 1 : KCM];
-      auto conv_request = [&](int g) {
+      auto conv_request = [&](int g) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < KCM; ++j) {
           xv[g & 1][j] = *reinterpret_cast<const u32x2*>(vrow - j * G::VS + 8 * g);
@@ -439,23 +504,17 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       };
       conv_request(0);
       LINATTN_FENCE();
-      // o[r] = O[token 32tb + l32][channel 32w + 8(r/4) + 4hi + r%4]
-      f32x16 o;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 2 * (tb + 1); ++ks) o = mfma(vf[ks], pB[ks], o);
-#pragma unroll
-      for (int ib = 0; ib < G::IB; ++ib)
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) o = mfma(pack8(Sacc[ib], 8 * h2), qB[2 * ib + h2], o);
-      // normalise, add the causal conv, store
+      for (int ks = 0; ks < 2 * (tb + 1); ++ks) o[tb] = mfma(vf[ks], pB[ks], o[tb]);
+      // the normaliser: eps + phi(q).z (one part per feature block) + the scores' row sums
+      float den = a.eps;
 #pragma unroll
       for (int x = 0; x < G::NW; ++x) den += dpart[x];
 #pragma unroll
       for (int sb = 0; sb <= tb; ++sb) den += dpart[G::NW + sb];
       const float inv = __builtin_amdgcn_rcpf(den);
-      uint16_t* orow = bufO(ci & 1) + t * G::OS + 32 * w + 4 * hi;   // staged; the loader waves store it
+      // normalise, add the causal conv, stage the row for the front-end waves to store
+      uint16_t* orow = bufO(ci & 1) + t * G::OS + 32 * w + 4 * hi;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         if (g + 1 < 4) conv_request(g + 1);
@@ -469,8 +528,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           u[2] = fmaf(wv4[2], bf16_lo_to_f32(x[1]), u[2]);
           u[3] = fmaf(wv4[3], bf16_hi_to_f32(x[1]), u[3]);
         }
-        const u32x2 y = {pack_bf16x2(fmaf(o[4 * g], inv, u[0]), fmaf(o[4 * g + 1], inv, u[1])),
-                         pack_bf16x2(fmaf(o[4 * g + 2], inv, u[2]), fmaf(o[4 * g + 3], inv, u[3]))};
+        const u32x2 y = {pack_bf16x2(fmaf(o[tb][4 * g], inv, u[0]), fmaf(o[tb][4 * g + 1], inv, u[1])),
+                         pack_bf16x2(fmaf(o[tb][4 * g + 2], inv, u[2]), fmaf(o[tb][4 * g + 3], inv, u[3]))};
         *reinterpret_cast<u32x2*>(orow + 8 * g) = y;
       }
     }
@@ -495,6 +554,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         }
       }
     }
+    if (!STATE_ONLY) publish_z();
     __syncthreads();   // C: this buffer may be refilled, the other one is complete
   };
 
