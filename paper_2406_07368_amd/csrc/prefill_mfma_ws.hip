@@ -56,7 +56,7 @@ struct WsCfg {
   static constexpr int BV = BK + C * KS * 2;
   static constexpr int BUF = (BV + (HALO + C) * VS * 2 + 15) / 16 * 16;   // bytes of one row buffer
   static constexpr int OFF_PN = 2 * BUF;
-  static constexpr int OFF_DENQ = OFF_PN + C * PS * 2;     // [NW][C] float
+  static constexpr int OFF_DENQ = OFF_PN + C * PS * 2;     // [C] float (room for [NW][C])
   static constexpr int OFF_DENP = OFF_DENQ + NW * C * 4;   // [TB][C] float
   static constexpr int OFF_WL = OFF_DENP + TB * C * 4;     // [KCMAX][D] float, tap-major
   static constexpr int OS = D + 4;           // output staging rows: 8-byte writes, one row per lane
@@ -295,29 +295,37 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         }
       }
     };
-    // phi(q_t).z over feature block lw, for every token of group ci; z (the state before the group)
-    // is read from LDS in operand form, where the state waves left it
+    // phi(q_t).z for every token of group ci, by the last front-end wave alone (it has the fewest
+    // score tiles); z (the state before the group) is read from LDS in operand form, where the
+    // state waves left it
     auto q_dot_z = [&](int ci) __attribute__((always_inline)) {
+      if (lw != G::NW - 1) return;
       const uint16_t* Qn = bufQ(ci & 1);
-      bf16x8 bq[G::TB][2];
+      f32x16 acc[G::TB];
 #pragma unroll
-      for (int tb = 0; tb < G::TB; ++tb) {
-        const uint16_t* p = Qn + (32 * tb + l32) * G::QS + 32 * lw + 4 * hi;
-        bq[tb][0] = cat4(lds_row4(p), lds_row4(p + 8));
-        bq[tb][1] = cat4(lds_row4(p + 16), lds_row4(p + 24));
+      for (int tb = 0; tb < G::TB; ++tb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
+#pragma unroll
+      for (int ib = 0; ib < G::IB; ++ib) {
+        bf16x8 bq[G::TB][2];
+#pragma unroll
+        for (int tb = 0; tb < G::TB; ++tb) {
+          const uint16_t* p = Qn + (32 * tb + l32) * G::QS + 32 * ib + 4 * hi;
+          bq[tb][0] = cat4(lds_row4(p), lds_row4(p + 8));
+          bq[tb][1] = cat4(lds_row4(p + 16), lds_row4(p + 24));
+        }
+        const uint16_t* zp = zop + (2 * ib + hi) * 16;
+        const bf16x8 zb0 = lds_row8(zp), zb1 = lds_row8(zp + 8);
+#pragma unroll
+        for (int tb = 0; tb < G::TB; ++tb) {
+          acc[tb] = mfma(zb0, bq[tb][0], acc[tb]);
+          acc[tb] = mfma(zb1, bq[tb][1], acc[tb]);
+        }
       }
-      const uint16_t* zp = zop + (2 * lw + hi) * 16;
-      const bf16x8 zb0 = lds_row8(zp), zb1 = lds_row8(zp + 8);
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int tb = 0; tb < G::TB; ++tb) {
-        f32x16 acc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        acc = mfma(zb0, bq[tb][0], acc);
-        acc = mfma(zb1, bq[tb][1], acc);
-        if (lane < 32) denq[lw * C + 32 * tb + l32] = acc[0];   // every row of the product is the same
-      }
+      for (int tb = 0; tb < G::TB; ++tb)
+        if (lane < 32) denq[32 * tb + l32] = acc[tb][0];   // every row of the product is the same
     };
 
     for (int e = lt; !STATE_ONLY && e < KCM * D; e += G::NLT) {
@@ -430,7 +438,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   __syncthreads();                                     // buffer 0 is full, its scores and the conv taps are in LDS
 
   // conv taps of this lane's 16 output channels (32w + 8g + 4hi + e), kept in registers when few
-  constexpr bool W_REGS = KCM <= 3 && D == 64;   // D = 128 runs two waves per SIMD: 256 registers each
+  constexpr bool W_REGS = KCM <= 3 && D == 64;   // D = 128: the registers do not suffice
   f32x4 wreg[W_REGS ? KCM : 1][4];
   if (W_REGS) {
 #pragma unroll
@@ -485,44 +493,44 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       const uint16_t* pb = Pn + t * G::PS + 8 * hi;
 #pragma unroll
       for (int ks = 0; ks < 2 * (tb + 1); ++ks) pB[ks] = lds_row8(pb + 16 * ks);
-      float dpart[G::NW + G::TB];
+      float dpart[1 + G::TB];
+      dpart[0] = denq[t];
 #pragma unroll
-      for (int ww = 0; ww < G::NW; ++ww) dpart[ww] = denq[ww * C + t];
-#pragma unroll
-      for (int sb = 0; sb <= tb; ++sb) dpart[G::NW + sb] = denp[sb * C + t];
+      for (int sb = 0; sb <= tb; ++sb) dpart[1 + sb] = denp[sb * C + t];
       const uint16_t* vrow = Vn + (HALO + t) * G::VS + 32 * w + 4 * hi;
       const float* wrow = wl + 32 * w + 4 * hi;
-      // conv inputs of channel group g are requested one group ahead of their use
-      u32x2 xv[2][KCM];
-      f32x4 wv[2][W_REGS ? 1 : KCM];
+      // conv inputs of channel group g are requested one group ahead of their use (with many
+      // taps the registers for that do not suffice: then just before)
+      constexpr int CB = KCM > 5 ? 1 : 2;
+      u32x2 xv[CB][KCM];
+      f32x4 wv[CB][W_REGS ? 1 : KCM];
       auto conv_request = [&](int g) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < KCM; ++j) {
-          xv[g & 1][j] = *reinterpret_cast<const u32x2*>(vrow - j * G::VS + 8 * g);
-          if (!W_REGS) wv[g & 1][j] = *reinterpret_cast<const f32x4*>(wrow + j * D + 8 * g);
+          xv[g % CB][j] = *reinterpret_cast<const u32x2*>(vrow - j * G::VS + 8 * g);
+          if (!W_REGS) wv[g % CB][j] = *reinterpret_cast<const f32x4*>(wrow + j * D + 8 * g);
         }
       };
       conv_request(0);
       LINATTN_FENCE();
 #pragma unroll
       for (int ks = 0; ks < 2 * (tb + 1); ++ks) o[tb] = mfma(vf[ks], pB[ks], o[tb]);
-      // the normaliser: eps + phi(q).z (one part per feature block) + the scores' row sums
-      float den = a.eps;
+      // the normaliser: eps + phi(q).z + the scores' row sums
+      float den = a.eps + dpart[0];
 #pragma unroll
-      for (int x = 0; x < G::NW; ++x) den += dpart[x];
-#pragma unroll
-      for (int sb = 0; sb <= tb; ++sb) den += dpart[G::NW + sb];
+      for (int sb = 0; sb <= tb; ++sb) den += dpart[1 + sb];
       const float inv = __builtin_amdgcn_rcpf(den);
       // normalise, add the causal conv, stage the row for the front-end waves to store
       uint16_t* orow = bufO(ci & 1) + t * G::OS + 32 * w + 4 * hi;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        if (g + 1 < 4) conv_request(g + 1);
+        if (CB == 2 && g + 1 < 4) conv_request(g + 1);
+        if (CB == 1 && g > 0) conv_request(g);
         float u[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < KCM; ++j) {
-          const f32x4 wv4 = W_REGS ? wreg[W_REGS ? j : 0][g] : wv[g & 1][W_REGS ? 0 : j];
-          const u32x2 x = xv[g & 1][j];
+          const f32x4 wv4 = W_REGS ? wreg[W_REGS ? j : 0][g] : wv[g % CB][W_REGS ? 0 : j];
+          const u32x2 x = xv[g % CB][j];
           u[0] = fmaf(wv4[0], bf16_lo_to_f32(x[0]), u[0]);
           u[1] = fmaf(wv4[1], bf16_hi_to_f32(x[0]), u[1]);
           u[2] = fmaf(wv4[2], bf16_lo_to_f32(x[1]), u[2]);
