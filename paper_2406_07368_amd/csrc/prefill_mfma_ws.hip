@@ -45,7 +45,12 @@ struct WsCfg {
   static constexpr int KSC = C / 16;
   static constexpr int NP = C / 16;          // loader passes: 16 tokens x all columns per pass
   static constexpr int QS = D + 4;           // phi(Q): 8-byte row reads, one row per lane
-  static constexpr int KS = D + 16;          // phi(K): transpose reads and 16-byte row reads
+  // phi(K) is read two ways: 16-byte row reads (one row per lane) for the scores and transpose
+  // reads (4 rows x 32 columns per half wave) for the state update.  The row stride of D + 32
+  // (16 banks more than a multiple of 64) spreads the four rows of a transpose read over the
+  // banks; rotating row t by 8 * (t / 4) columns does the same for 16 consecutive rows of a
+  // row read.  Both readers and the writer apply the rotation (krot).
+  static constexpr int KS = D + 32;
   static constexpr int VS = D + 4;           // V: 8-byte row reads by the conv, some transpose reads
   static constexpr int PS = C + 8;           // P: 16-byte row reads
   static constexpr int NTILE = TB * (TB + 1) / 2;
@@ -67,6 +72,20 @@ struct WsCfg {
   static constexpr int TOTAL = OFF_SYNC + 16;
   static constexpr bool FITS = TOTAL <= 160 * 1024;
 };
+
+// column of feature c in row t of the phi(K) rows
+template <int D>
+__device__ __forceinline__ int krot(int t, int c) { return (c + 8 * (t >> 2)) & (D - 1); }
+
+// tr_operand for the rotated phi(K) rows: lanes <-> 32 consecutive features col0 + lane%32,
+// registers <-> rows row0 + 8*(lane/32) + 0..7 (row0 a multiple of 16)
+template <int D>
+__device__ __forceinline__ bf16x8 tr_operand_krot(const uint16_t* base, int stride, int row0, int col0, int lane) {
+  const int j = lane & 15;
+  const int r = row0 + 8 * (lane >> 5) + (j >> 2);
+  const int c = col0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
+  return cat4(lds_tr4(base + r * stride + krot<D>(r, c)), lds_tr4(base + (r + 4) * stride + krot<D>(r + 4, c)));
+}
 
 }  // namespace
 
@@ -194,7 +213,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           if (PARTIAL) qp[i] = ok ? qp[i] : 0u;
         }
       }
-      *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
+      *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + krot<D>(t, c0)) = kp;
       u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + t) * G::VS + c0);
       vrow[0] = u32x2{vp[0], vp[1]};
       vrow[1] = u32x2{vp[2], vp[3]};
@@ -259,7 +278,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           f32x16 acc;
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-          const uint16_t* ka = Kn + (32 * sb + l32) * G::KS + 8 * hi;
+          const uint16_t* ka = Kn + (32 * sb + l32) * G::KS;
+          const int kc = 8 * hi + 8 * ((32 * sb + l32) >> 2);   // rotated column of this lane's first feature
           const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 8 * hi;
           constexpr int HB = G::KSD / 2;   // two batches of K steps
 #pragma unroll
@@ -268,7 +288,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
             for (int k2 = 0; k2 < HB; ++k2) {
               const int ks = half * HB + k2;
-              ak[k2] = lds_row8(ka + 16 * ks);
+              ak[k2] = lds_row8(ka + ((kc + 16 * ks) & (D - 1)));
               bq[k2] = cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4));
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -463,6 +483,28 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     bf16x8 vf[G::KSC];
 #pragma unroll
     for (int ks = 0; ks < G::KSC; ++ks) vf[ks] = tr_operand(Vn + HALO * G::VS, G::VS, 16 * ks, 32 * w, lane);
+    auto update_state = [&]() __attribute__((always_inline)) {
+    // S += phi(K)^T V for this wave's channels, z += phi(K)^T 1 for this wave's features;
+    // the phi(K)^T operands of feature block ib + 1 are requested while block ib is multiplied
+    {
+      bf16x8 kt[2][G::KSC];
+#pragma unroll
+      for (int ks = 0; ks < G::KSC; ++ks) kt[0][ks] = tr_operand_krot<D>(Kn, G::KS, 16 * ks, 0, lane);
+#pragma unroll
+      for (int ib = 0; ib < G::IB; ++ib) {
+        if (ib + 1 < G::IB) {
+#pragma unroll
+          for (int ks = 0; ks < G::KSC; ++ks) kt[(ib + 1) & 1][ks] = tr_operand_krot<D>(Kn, G::KS, 16 * ks, 32 * (ib + 1), lane);
+        }
+        LINATTN_FENCE();
+#pragma unroll
+        for (int ks = 0; ks < G::KSC; ++ks) {
+          Sacc[ib] = mfma(kt[ib & 1][ks], vf[ks], Sacc[ib]);
+          if (ib == w) Zacc = mfma(kt[ib & 1][ks], ones, Zacc);
+        }
+      }
+    }
+    };
     if constexpr (!STATE_ONLY) {
     // First the part that needs the state only, S^T phi(Q)^T, for every token block; the front-end
     // waves compute the scores of this group meanwhile.
@@ -484,7 +526,10 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) o[tb] = mfma(pack8(Sacc[ib], 8 * h2), qB[2 * ib + h2], o[tb]);
     }
+    // the state update needs nothing from the front end either: it goes before the wait for the scores
+    update_state();
     wait_for(sync_q, (unsigned)G::NW * (unsigned)(ci + 1));   // scores, their row sums and phi(q).z are in LDS
+    publish_z();   // only now: the front end has read the previous z by the time it signals
 #pragma unroll
     for (int tb = 0; tb < G::TB; ++tb) {
       const int t = 32 * tb + l32;
@@ -541,28 +586,9 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         *reinterpret_cast<u32x2*>(orow + 8 * g) = y;
       }
     }
-    }   // !STATE_ONLY
-    // S += phi(K)^T V for this wave's channels, z += phi(K)^T 1 for this wave's features;
-    // the phi(K)^T operands of feature block ib + 1 are requested while block ib is multiplied
-    {
-      bf16x8 kt[2][G::KSC];
-#pragma unroll
-      for (int ks = 0; ks < G::KSC; ++ks) kt[0][ks] = tr_operand(Kn, G::KS, 16 * ks, 0, lane);
-#pragma unroll
-      for (int ib = 0; ib < G::IB; ++ib) {
-        if (ib + 1 < G::IB) {
-#pragma unroll
-          for (int ks = 0; ks < G::KSC; ++ks) kt[(ib + 1) & 1][ks] = tr_operand(Kn, G::KS, 16 * ks, 32 * (ib + 1), lane);
-        }
-        LINATTN_FENCE();
-#pragma unroll
-        for (int ks = 0; ks < G::KSC; ++ks) {
-          Sacc[ib] = mfma(kt[ib & 1][ks], vf[ks], Sacc[ib]);
-          if (ib == w) Zacc = mfma(kt[ib & 1][ks], ones, Zacc);
-        }
-      }
+    } else {
+      update_state();
     }
-    if (!STATE_ONLY) publish_z();
     __syncthreads();   // C: this buffer may be refilled, the other one is complete
   };
 
