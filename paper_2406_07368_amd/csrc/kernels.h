@@ -52,7 +52,8 @@ int prefill_mfma_pick_segments(int BH, int L, int chunk);
 size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg);
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, hipStream_t st);
 
-// prefill_mfma_ws.hip : the same path with loader and compute waves working side by side
+// prefill_mfma_ws.hip : the same path with front-end waves (HBM traffic, feature map, scores) and
+// state waves (everything that touches S and z) working side by side
 bool prefill_mfma_ws_available(int d, int chunk);
 hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, int chunk, bool state_only, hipStream_t st);
 

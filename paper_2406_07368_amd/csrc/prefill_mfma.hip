@@ -434,7 +434,7 @@ template <int D, int C, int KCM>
 static hipError_t launch_dc(const PrefillArgs& a, hipStream_t st) {
   using G = Cfg<D, C>;
   const int BH = a.B * a.H;
-  const bool ws = prefill_mfma_ws_available(D, C);   // specialised loader/compute waves: two row buffers fit in LDS
+  const bool ws = prefill_mfma_ws_available(D, C);   // specialised front-end/state waves: two row buffers fit in LDS
   hipError_t e;
   if (a.nseg > 1) {
     if (ws) {

@@ -2,28 +2,28 @@
 // whenever two copies of a group's rows fit in LDS.
 //
 // A workgroup walks one (b, h) -- or one segment of it -- in groups of C tokens and
-// is split into two halves that run at the same time on every SIMD:
+// is split into two halves that run at the same time, one wave of each on every SIMD:
 //
-//   loader waves   do all HBM traffic with whole 16-byte-per-lane rows: they bring the coming
-//                  groups' Q, K, V rows in (loads issued two groups ahead), apply the feature
-//                  map on the vector ALUs, write phi(Q), phi(K), V as bf16 rows into the LDS
-//                  buffer that is not in use, and write the previous group's finished output
-//                  rows (staged in LDS by the compute waves) back out;
-//   compute waves  run the matrix-core work of the current group from the other buffer:
-//                  the causal tiles of P^T = phi(K) phi(Q)^T (masked by select), then for
-//                  their 32 value channels O^T = V^T P^T + S^T phi(Q)^T, the row
-//                  normaliser, the causal convolution over V, the result to an LDS staging
-//                  buffer, and finally S += phi(K)^T V.
+//   front-end waves  do all HBM traffic with whole 16-byte-per-lane rows and everything that
+//                    needs no state.  Per step: the causal tiles of P^T = phi(K) phi(Q)^T of the
+//                    current group (masked by select) with their row sums, and phi(q).z, from
+//                    the rows in LDS; then the next group's rows (requested two groups ahead,
+//                    the requests in a fixed sequence so that the hardware counter can be waited
+//                    on pass by pass) get the feature map on the vector ALUs and go to the LDS
+//                    buffer that is not in use; half-way through, the previous group's finished
+//                    output rows (staged in LDS by the state waves) are written back out.
+//   state waves      hold the state in accumulator registers for the whole sequence: wave w owns
+//                    S[:, 32w:32w+32] and z[32w:32w+32].  Per group, for their 32 value channels:
+//                    O^T = S^T phi(Q)^T, then S += phi(K)^T V (neither needs the front end), then
+//                    O^T += V^T P^T once the scores are there, the row normaliser, the causal
+//                    convolution over V, and the result to the LDS staging buffer.
 //
-// The state never leaves the compute waves' accumulator registers: wave w holds
-// S[:, 32w:32w+32] and the 32 entries z[32w:32w+32] of the normaliser.  z is carried as
-// the state column of a virtual value channel that is constantly one, so that both its
-// update (phi(K)^T 1) and its read-out (phi(Q) z) are MFMAs as well; the read-out is split
-// over the waves by feature block and summed through LDS.
+// z is carried as the state column of a virtual value channel that is constantly one, so that its
+// update (phi(K)^T 1) and its read-out (phi(Q) z) are MFMAs as well; after each update the state
+// waves leave z in LDS in operand form for the front end.
 //
-// One workgroup barrier per group keeps the halves in step (C: the current buffer is free,
-// the next one is full); the compute waves additionally meet once per group at an LDS counter
-// (B: scores and normaliser partials are in LDS), which the loader waves do not take part in.
+// Synchronisation per group: one workgroup barrier (C: the current buffer is free, the next one is
+// full) and one LDS counter on which the state waves wait for the front end's scores.
 #include <type_traits>
 
 #include "common.cuh"
@@ -36,14 +36,14 @@ namespace {
 
 template <int D, int C>
 struct WsCfg {
-  static constexpr int NW = D / 32;          // compute waves (and as many loader waves)
+  static constexpr int NW = D / 32;          // state waves (and as many front-end waves)
   static constexpr int NT = 2 * NW * 64;
-  static constexpr int NLT = NW * 64;        // loader threads
+  static constexpr int NLT = NW * 64;        // front-end threads (the upper half of the workgroup)
   static constexpr int TB = C / 32;
   static constexpr int IB = D / 32;
   static constexpr int KSD = D / 16;
   static constexpr int KSC = C / 16;
-  static constexpr int NP = C / 16;          // loader passes: 16 tokens x all columns per pass
+  static constexpr int NP = C / 16;          // front-end passes: 16 tokens x all columns per pass
   static constexpr int QS = D + 4;           // phi(Q): 8-byte row reads, one row per lane
   // phi(K) is read two ways: 16-byte row reads (one row per lane) for the scores and transpose
   // reads (4 rows x 32 columns per half wave) for the state update.  The row stride of D + 32
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   __syncthreads();                                     // the counters are used before the next barrier
 
   if (wv >= G::NW) {
-    // =============================== loader waves ===============================================
+    // =============================== front-end waves ============================================
     const int lt = tid - G::NLT;                       // 0 .. NLT-1
     const int lw = wv - G::NW;
     // a pass is 16 tokens; D/8 consecutive lanes carry one whole row (8 columns each), so every
@@ -160,8 +160,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     // Two register sets: group g lives in set g & 1 from the moment it is requested (two groups
     // ahead of its use) until it has been written to LDS.
     //
-    // Every load below is issued unconditionally (groups past the end re-read the last group, rows
-    // past the end re-read the last row; neither is used), and the main loop is unrolled by two so
+    // Every load below is issued unconditionally (requests for groups or rows past the end re-read
+    // one row that exists; the data is not used), and the main loop is unrolled by two so
     // that the set of each step is fixed at compile time.  The compiler counts outstanding memory
     // operations statically: only with a fixed sequence of them can it wait for exactly the pass
     // that is needed while the requests of the following two groups stay in flight.
@@ -180,11 +180,13 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       const char* bk = reinterpret_cast<const char*>(gk + off);
       const char* bv = reinterpret_cast<const char*>(gv + off);
       const char* bq = reinterpret_cast<const char*>(gq + off);
-      uint32_t lo = loff_b;
+      // past the last group every lane of a row group re-reads row 0 of the last group: one cache line
+      // per request instead of 16 fresh rows
+      uint32_t lo = g < nchunks ? loff_b : (uint32_t)c0 * 2u;
       if (PARTIAL) {
         const int last = t_end - 1 - tok;              // last row of the segment, relative to this pass
-        const int r = r16 <= last ? r16 : last;        // negative only when the whole pass is past the end
-        lo = (uint32_t)((r < 0 ? last : r) * (int)a.st + c0) * 2u;   // byte offset, may be negative: wraps with the base
+        const int r = (g < nchunks && r16 <= last) ? r16 : (last < 0 ? last : 0);   // a row that exists
+        lo = (uint32_t)(r * (int)a.st + c0) * 2u;      // byte offset, may be negative: wraps with the base
         rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + (int32_t)lo));
         rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + (int32_t)lo));
         if (!STATE_ONLY) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + (int32_t)lo));
@@ -418,7 +420,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     return;
   }
 
-  // ================================= compute waves =================================================
+  // ================================= state waves ===================================================
   const int w = wv;
   const int cw = 32 * w + l32;             // the channel this lane owns in the state accumulators
 
