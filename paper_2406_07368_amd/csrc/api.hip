@@ -135,7 +135,10 @@ linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* 
   a.n_commit = n_commit; a.out = out;
   a.B = desc->B; a.H = desc->H; a.kk = kk; a.Kc = desc->conv_k; a.eps = desc->eps;
   const int nsplit = verify_pick_split(desc->B * desc->H);
-  hipError_t e = launch_verify(a, desc->io_dtype == LINATTN_BF16, desc->d, nsplit, static_cast<hipStream_t>(hip_stream));
+  const bool bf16 = desc->io_dtype == LINATTN_BF16;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = verify_mfma_available(bf16, desc->d, nsplit, kk) ? launch_verify_mfma(a, desc->d, stream)
+                                                                        : launch_verify(a, bf16, desc->d, nsplit, stream);
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 

@@ -44,6 +44,10 @@ struct PrefillArgs {
 int verify_pick_split(int BH);
 hipError_t launch_verify(const VerifyArgs& a, bool bf16, int d, int nsplit, hipStream_t st);
 
+// verify_mfma.hip : the same step as one 16-token group on the matrix cores (bf16 drafts, whole heads)
+bool verify_mfma_available(bool bf16, int d, int nsplit, int kk);
+hipError_t launch_verify_mfma(const VerifyArgs& a, int d, hipStream_t st);
+
 // prefill_simt.hip : fp32 arithmetic on the vector ALUs, one workgroup per (b, h)
 hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st);
 

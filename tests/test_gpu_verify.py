@@ -60,9 +60,60 @@ def test_verify_every_column_split(BH, expect_split):
     want = oracle.verify(q, k, v, w, S, z, hist, n_commit)
     got = run_gpu(q, k, v, w, S, z, hist, io, n_commit)
     check(got[0], want[0], TOL[io], "out")
-    check(got[1], want[1], 1e-5, "S")
-    check(got[2], want[2], 1e-5, "z")
+    # whole heads of bf16 drafts take the matrix-core kernel, which rounds phi(k) to bf16 for the
+    # state update as the prefill does; the column-split kernel updates with fp32 products
+    state_tol = TOL[io] if expect_split == 1 else 1e-5
+    check(got[1], want[1], state_tol, "S")
+    check(got[2], want[2], state_tol, "z")
     assert np.array_equal(got[3], workloads.round_to_io(want[3], io).astype(np.float64))
+
+
+# ---- the matrix-core kernel: bf16 drafts, B*H >= 768 (whole heads per workgroup) -------------------
+MB, MH = 24, 32
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("kk,Kc", [(1, 3), (2, 1), (4, 3), (5, 5), (8, 3), (13, 8), (16, 2)])
+def test_verify_whole_heads_on_the_matrix_cores(d, kk, Kc):
+    io = "bf16"
+    q, k, v, w, S, z, hist = make_case(300 + kk + d, MB, MH, d, Kc, kk, io, prefix=12)
+    n_commit = (np.arange(MB) * 5 % (kk + 1)).astype(np.int32)
+    want = oracle.verify(q, k, v, w, S, z, hist, n_commit, eps=1e-3)
+    got = run_gpu(q, k, v, w, S, z, hist, io, n_commit, eps=1e-3)
+    check(got[0], want[0], TOL[io], "out")
+    check(got[1], want[1], TOL[io], "S")
+    check(got[2], want[2], TOL[io], "z")
+    assert np.array_equal(got[3], workloads.round_to_io(want[3], io).astype(np.float64)), "hist"
+    for b in np.nonzero(n_commit == 0)[0]:       # nothing accepted: the state comes back bit-unchanged
+        assert np.array_equal(got[1][b], S[b].astype(np.float64))
+        assert np.array_equal(got[2][b], z[b].astype(np.float64))
+        assert np.array_equal(got[3][b], hist[b].astype(np.float64))
+
+
+def test_matrix_core_verify_equals_sequential_decode_and_leaks_nothing():
+    """Sec. 4.2 on the matrix-core kernel: one call over kk drafts == kk decode calls, and changing
+    later drafts leaves the outputs of earlier ones bit-identical."""
+    io, d, Kc, kk = "bf16", 128, 3, 6
+    dt = IO[io]
+    q, k, v, w, S, z, hist = make_case(17, MB, MH, d, Kc, kk, io, prefix=12)
+    got = run_gpu(q, k, v, w, S, z, hist, io)
+    state = (dev(S), dev(z), dev(hist, dt))
+    outs = []
+    for j in range(kk):
+        outs.append(host(binding.decode(dev(q[:, :, j], dt), dev(k[:, :, j], dt), dev(v[:, :, j], dt), dev(w), state)))
+    torch.cuda.synchronize()
+    seq = np.stack(outs, axis=2)
+    # the same terms, grouped differently (bf16-rounded S for the read-out in both): output rounding apart
+    check(seq, got[0], 1.2e-2, "decode chain out")
+    check(host(state[0]), got[1], 1e-5, "decode chain S")
+    check(host(state[1]), got[2], 1e-5, "decode chain z")
+    assert np.array_equal(host(state[2]), got[3])
+    for j in (0, 3):
+        q2, k2, v2 = q.copy(), k.copy(), v.copy()
+        for a in (q2, k2, v2):
+            a[:, :, j + 1:] = workloads.round_to_io(-2.0 * a[:, :, j + 1:] + 1.0, io)
+        other = run_gpu(q2, k2, v2, w, S, z, hist, io)[0]
+        assert np.array_equal(other[:, :, :j + 1], got[0][:, :, :j + 1]), f"draft {j} saw a later draft"
 
 
 def test_rejected_drafts_leave_no_trace():
