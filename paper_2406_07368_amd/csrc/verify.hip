@@ -4,7 +4,8 @@
 //
 // One workgroup of 256 threads owns the column slice S[:, c0 : c0+CW] of one
 // (b, h).  The slice streams through registers in row passes with 16-byte loads
-// (rows are contiguous, so a wave reads whole 128..512 B row segments), a few
+// (rows are contiguous, so a wave reads whole 128..512 B row segments; nontemporal:
+// the state is touched once per step), a few
 // passes in flight at a time: each row adds its term to the kk read-outs
 // phi(q_j)^T S, receives the accepted rank-1 updates and is written straight back.
 // The read-outs are then reduced across the threads that share a column group,
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
   float* Sg = a.S + (size_t)bh * D * D + c0 + 4 * cg;
   f32x4 s[PD];
 #pragma unroll
-  for (int p = 0; p < PD; ++p) s[p] = *reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D);
+  for (int p = 0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D));
 
   // ---- 1. drafts -> LDS (phi applied), normaliser, taps and history -> LDS -----------------------
 #pragma unroll
@@ -203,9 +204,9 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
         for (int j = 0; j < KP; ++j)
 #pragma unroll
           for (int e = 0; e < 4; ++e) cur[e] = fmaf(g[j], vr[j][e], cur[e]);
-        *reinterpret_cast<f32x4*>(Sg + (size_t)i * D) = cur;
+        __builtin_nontemporal_store(cur, reinterpret_cast<f32x4*>(Sg + (size_t)i * D));
       }
-      if (p + PD < NPASS) s[q] = *reinterpret_cast<const f32x4*>(Sg + (size_t)((p + PD) * RPP + r0) * D);
+      if (p + PD < NPASS) s[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)((p + PD) * RPP + r0) * D));
     }
   }
   // threads that share a column group sit CG lanes apart inside a wave
