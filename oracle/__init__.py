@@ -55,6 +55,8 @@ def _declare(lib):
         fn.argtypes = [i, i, i, i, i, f] + [_dp] * 11
     lib.oracle_verify.restype = i
     lib.oracle_verify.argtypes = [i, i, i, i, i, f] + [_dp] * 7 + [_ip, _dp]
+    lib.oracle_verify_tree.restype = i
+    lib.oracle_verify_tree.argtypes = [i, i, i, i, i, f] + [_dp] * 3 + [_ip] + [_dp] * 4 + [_ip, _dp]
     lib.oracle_decode.restype = i
     lib.oracle_decode.argtypes = [i, i, i, i, f] + [_dp] * 8
     lib.oracle_num_threads.restype = i
@@ -164,6 +166,39 @@ def verify(q, k, v, w, S, z, hist, n_commit=None, eps=0.0, lib=None):
                            None if nc is None else nc.ctypes.data_as(_ip), _p(out))
     if rc != 0:
         raise ValueError(f"oracle_verify rejected its arguments (code {rc})")
+    return out, S, z, hist
+
+
+def verify_tree(q, k, v, parent, w, S, z, hist, accept=None, eps=0.0, lib=None):
+    """Tree-structured verification (Sec. 4.2): n candidates, parent[i] < i (or -1 for a candidate that
+    follows the verified sequence directly), every candidate scored from the verified state and its own
+    root path only.  accept: None (nothing is committed) or int array [B], the candidate whose root path is
+    committed (-1: none).  Returns (out, S', z', hist'); the incoming state arrays are not modified.
+    """
+    lib = lib or _load()
+    q = _c(q)
+    B, H, n, d = q.shape
+    k = _c(k, q.shape)
+    v = _c(v, q.shape)
+    w = _c(w)
+    Kc = w.shape[2]
+    w = _c(w, (H, d, Kc))
+    par = np.ascontiguousarray(parent, dtype=np.int32)
+    if par.shape != (n,):
+        raise ValueError("parent must have shape [n]")
+    S = np.array(_c(S, (B, H, d, d)), copy=True)
+    z = np.array(_c(z, (B, H, d)), copy=True)
+    hist = np.array(_c(hist, (B, H, Kc - 1, d)), copy=True)
+    acc = None
+    if accept is not None:
+        acc = np.ascontiguousarray(accept, dtype=np.int32)
+        if acc.shape != (B,):
+            raise ValueError("accept must have shape [B]")
+    out = np.empty_like(q)
+    rc = lib.oracle_verify_tree(B, H, n, d, Kc, float(eps), _p(q), _p(k), _p(v), par.ctypes.data_as(_ip), _p(w),
+                                _p(S), _p(z), _p(hist), None if acc is None else acc.ctypes.data_as(_ip), _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_verify_tree rejected its arguments (code {rc})")
     return out, S, z, hist
 
 

@@ -289,6 +289,109 @@ int oracle_verify(int B, int H, int kk, int d, int Kc, double eps,
 }
 
 /* One generated token: a verification of a single draft that is always kept. */
+/*
+ * Tree-structured verification (Sec. 4.2, "Proposed Solution").  The n candidate
+ * tokens of one speculation step form a tree that hangs off the verified
+ * sequence: parent[i] < i is the candidate that precedes candidate i in time,
+ * -1 if candidate i directly follows the verified sequence.  Candidates of the
+ * same time step are siblings; they do not see each other.  Candidate i may
+ * use the verified state and the candidates on its own root path (its
+ * ancestors and itself), and its convolution window is that path read
+ * backwards in time, continuing into the verified history (the paper's
+ * example: with kernel 3 the candidate at step t1 covers {t0, t1}, not the
+ * unchosen candidate of step t1 that happens to be stored next to it).
+ *
+ * Written out from that definition: for every candidate the visible tokens
+ * are listed (path[0] = the candidate itself, path[1] = its parent, ...) and
+ * every sum is taken over that list.  accept[b] names the candidate whose root
+ * path becomes part of the verified sequence of batch row b (-1: none); the
+ * state is advanced by exactly the tokens of that path, oldest first.
+ * parent is shared by all batch rows and heads (the tree shape of a
+ * speculation step is fixed in advance).
+ */
+int oracle_verify_tree(int B, int H, int n, int d, int Kc, double eps,
+                       const double *q, const double *k, const double *v,
+                       const int *parent, const double *w, double *S, double *z,
+                       double *hist, const int *accept, double *out) {
+  if (B < 0 || H < 1 || n < 0 || d < 1 || Kc < 1) return 1;
+  for (int i = 0; i < n; ++i)
+    if (parent[i] < -1 || parent[i] >= i) return 2;
+  if (accept)
+    for (int b = 0; b < B; ++b)
+      if (accept[b] < -1 || accept[b] >= n) return 2;
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d;
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    int b = bh / H, h = bh % H;
+    size_t o = (size_t)bh * n * d;
+    const double *qh = q + o, *kh = k + o, *vh = v + o, *wh = w + (size_t)h * d * Kc;
+    double *Sh = S + bh * nS, *zh = z + (size_t)bh * d;
+    double *hh = nh ? hist + bh * nh : NULL;
+    double *fq = (double *)malloc(sizeof(double) * (size_t)(n ? n : 1) * d);
+    double *fk = (double *)malloc(sizeof(double) * (size_t)(n ? n : 1) * d);
+    int *path = (int *)malloc(sizeof(int) * (size_t)(n ? n : 1));
+    for (size_t e = 0; e < (size_t)n * d; ++e) {
+      fq[e] = oracle_phi(qh[e]);
+      fk[e] = oracle_phi(kh[e]);
+    }
+    for (int i = 0; i < n; ++i) {
+      int len = 0;
+      for (int a = i; a >= 0; a = parent[a]) path[len++] = a;
+      const double *fqi = fq + (size_t)i * d;
+      double den = eps;
+      for (int f = 0; f < d; ++f) den += fqi[f] * zh[f];
+      for (int c = 0; c < d; ++c) {
+        double acc = 0.0;
+        for (int f = 0; f < d; ++f) acc += fqi[f] * Sh[(size_t)f * d + c];
+        out[o + (size_t)i * d + c] = acc; /* numerator so far: the verified state */
+      }
+      for (int m = 0; m < len; ++m) {
+        int a = path[m];
+        double sim = 0.0;
+        for (int f = 0; f < d; ++f) sim += fqi[f] * fk[(size_t)a * d + f];
+        den += sim;
+        for (int c = 0; c < d; ++c) out[o + (size_t)i * d + c] += sim * vh[(size_t)a * d + c];
+      }
+      for (int c = 0; c < d; ++c) {
+        double u = 0.0;
+        for (int t = 0; t < Kc; ++t) {
+          /* t steps back in time from candidate i: on the path, else (t - len + 1) rows into the history */
+          double x = t < len ? vh[(size_t)path[t] * d + c]
+                             : hh[(size_t)(Kc - 1 - (t - len + 1)) * d + c];
+          u += wh[(size_t)c * Kc + t] * x;
+        }
+        out[o + (size_t)i * d + c] = out[o + (size_t)i * d + c] / den + u;
+      }
+    }
+    int acc_node = accept ? accept[b] : -1;
+    if (acc_node >= 0) {
+      int len = 0;
+      for (int a = acc_node; a >= 0; a = parent[a]) path[len++] = a;
+      for (int m = len - 1; m >= 0; --m) { /* oldest first */
+        int a = path[m];
+        for (int f = 0; f < d; ++f) {
+          double x = fk[(size_t)a * d + f];
+          zh[f] += x;
+          for (int c = 0; c < d; ++c) Sh[(size_t)f * d + c] += x * vh[(size_t)a * d + c];
+        }
+      }
+      if (nh) { /* last Kc-1 rows of (history ++ accepted path) */
+        double *nw = (double *)malloc(sizeof(double) * nh);
+        for (int r = 0; r < Kc - 1; ++r) {
+          int back = Kc - 1 - r; /* 1 = newest */
+          const double *src = back <= len ? vh + (size_t)path[back - 1] * d
+                                          : hh + (size_t)(Kc - 1 - (back - len)) * d;
+          memcpy(nw + (size_t)r * d, src, sizeof(double) * d);
+        }
+        memcpy(hh, nw, sizeof(double) * nh);
+        free(nw);
+      }
+    }
+    free(fq); free(fk); free(path);
+  }
+  return 0;
+}
+
 int oracle_decode(int B, int H, int d, int Kc, double eps, const double *q,
                   const double *k, const double *v, const double *w, double *S,
                   double *z, double *hist, double *out) {

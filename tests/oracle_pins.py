@@ -430,4 +430,101 @@ def pin_verify_no_leak_between_drafts(lib=None):
         assert not np.array_equal(got[:, :, j + 1:], base[:, :, j + 1:])
 
 
+# --- tree-structured verification (Sec. 4.2, "Proposed Solution") -------------------------------
+def _tree_case(seed, n=11, B=2, H=2, d=4, Kc=4):
+    r = _rng(seed)
+    parent = np.array([-1] + [int(r.integers(-1, i)) for i in range(1, n)], dtype=np.int32)
+    q, k, v = (r.standard_normal((B, H, n, d)) for _ in range(3))
+    w = r.standard_normal((H, d, Kc))
+    S = r.standard_normal((B, H, d, d))
+    z = np.abs(r.standard_normal((B, H, d))) + 0.5
+    hist = r.standard_normal((B, H, Kc - 1, d))
+    return parent, q, k, v, w, S, z, hist
+
+
+def _root_path(parent, i):
+    path = []
+    while i >= 0:
+        path.append(i)
+        i = int(parent[i])
+    return path[::-1]          # oldest first
+
+
+def pin_tree_example_from_the_paper(lib=None):
+    """Two candidates for the same step stored side by side: the second one's window is {t0, t1b}."""
+    rows = {}
+    for line in open(os.path.join(GOLDEN, "tree_verify_example.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            node, rest = line.split(":")
+            tok = rest.split()
+            rows[int(node)] = (int(tok[1]), float(tok[-1]))
+    parent = np.array([rows[i][0] for i in sorted(rows)], dtype=np.int32)
+    v = np.array([2.0, 3.0, 11.0]).reshape(1, 1, 3, 1)
+    zero = np.zeros_like(v)
+    w = np.array([[[1.0, 10.0, 100.0]]])
+    hist = np.array([5.0, 7.0]).reshape(1, 1, 2, 1)
+    out = oracle.verify_tree(zero, zero, v, parent, w, np.zeros((1, 1, 1, 1)), np.zeros((1, 1, 1)), hist, lib=lib)[0]
+    _close(out[0, 0, :, 0], [rows[i][1] for i in sorted(rows)], 1e-12, "paper's tree example")
+
+
+def pin_tree_that_is_a_chain_is_plain_verify(lib=None):
+    """parent[i] = i - 1 is the chain of drafts; accepting candidate n - 1 is n_commit = n."""
+    parent, q, k, v, w, S, z, hist = _tree_case(31)
+    n = q.shape[2]
+    chain = np.arange(n, dtype=np.int32) - 1
+    n_commit = np.array([4, 0], dtype=np.int32)
+    got = oracle.verify_tree(q, k, v, chain, w, S, z, hist, n_commit - 1, eps=0.25, lib=lib)
+    want = oracle.verify(q, k, v, w, S, z, hist, n_commit, eps=0.25, lib=lib)
+    for g, x, what in zip(got, want, ("out", "S", "z", "hist")):
+        _close(g, x, 1e-12, "chain tree " + what)
+
+
+def pin_tree_candidate_equals_chain_over_its_root_path(lib=None):
+    """Every candidate's output, and the state after accepting it, are those of plain verification of the
+    tokens on its root path in time order (the same prefix is computed once, Sec. 5.3)."""
+    parent, q, k, v, w, S, z, hist = _tree_case(32)
+    n = q.shape[2]
+    out = oracle.verify_tree(q, k, v, parent, w, S, z, hist, lib=lib)[0]
+    for i in range(n):
+        path = _root_path(parent, i)
+        want = oracle.verify(q[:, :, path], k[:, :, path], v[:, :, path], w, S, z, hist, lib=lib)
+        _close(out[:, :, i], want[0][:, :, -1], 1e-12, f"candidate {i}")
+        got = oracle.verify_tree(q, k, v, parent, w, S, z, hist, np.array([i, -1], dtype=np.int32), lib=lib)
+        for b in (0, 1):
+            ref = want if b == 0 else (None, S, z, hist)
+            _close(got[1][b], ref[1][b], 1e-12, f"S after accepting {i}, row {b}")
+            _close(got[2][b], ref[2][b], 1e-12, f"z after accepting {i}, row {b}")
+            _close(got[3][b], ref[3][b], 1e-12, f"hist after accepting {i}, row {b}")
+
+
+def pin_tree_candidates_off_the_path_are_invisible(lib=None):
+    """Changing any candidate that is not on the root path of candidate i leaves out[i] bit-identical."""
+    parent, q, k, v, w, S, z, hist = _tree_case(33)
+    n = q.shape[2]
+    base = oracle.verify_tree(q, k, v, parent, w, S, z, hist, lib=lib)[0]
+    for i in range(n):
+        on = set(_root_path(parent, i))
+        off = [a for a in range(n) if a not in on]
+        if not off:
+            continue
+        q2, k2, v2 = q.copy(), k.copy(), v.copy()
+        for a in (q2, k2, v2):
+            a[:, :, off] = -3.0 * a[:, :, off] + 1.0
+        other = oracle.verify_tree(q2, k2, v2, parent, w, S, z, hist, lib=lib)[0]
+        assert np.array_equal(other[:, :, i], base[:, :, i]), f"candidate {i} saw a candidate off its path"
+        for a in on:                                   # ... and every candidate on the path does matter
+            v3 = v.copy()
+            v3[:, :, a] += 1.0
+            moved = oracle.verify_tree(q, k, v3, parent, w, S, z, hist, lib=lib)[0]
+            assert not np.array_equal(moved[:, :, i], base[:, :, i]), f"candidate {i} ignores {a} on its path"
+
+
+def pin_tree_without_acceptance_leaves_the_state(lib=None):
+    parent, q, k, v, w, S, z, hist = _tree_case(34)
+    for accept in (None, np.array([-1, -1], dtype=np.int32)):
+        got = oracle.verify_tree(q, k, v, parent, w, S, z, hist, accept, lib=lib)
+        assert np.array_equal(got[1], S) and np.array_equal(got[2], z) and np.array_equal(got[3], hist)
+
+
 ALL_PINS = [obj for name, obj in sorted(globals().items()) if name.startswith("pin_") and callable(obj)]

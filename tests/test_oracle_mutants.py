@@ -44,6 +44,19 @@ MUTANTS = [
     ("verify_commits_everything", "int n = n_commit ? n_commit[b] : kk;", "int n = kk; (void)b;"),
     ("verify_n_commit_per_head", "int n = n_commit ? n_commit[b] : kk;", "int n = n_commit ? n_commit[h % B] : kk; (void)b;"),
     ("recurrent_ignores_incoming_hist", "hist0 ? hist0 + bh * nh : NULL, S, z, hs);", "NULL, S, z, hs);"),
+    ("tree_sees_the_stored_neighbour", "for (int a = i; a >= 0; a = parent[a]) path[len++] = a;\n      const double *fqi",
+     "for (int a = i; a >= 0; a = a - 1) path[len++] = a;\n      const double *fqi"),
+    ("tree_excludes_the_candidate_itself", "for (int a = i; a >= 0; a = parent[a]) path[len++] = a;\n      const double *fqi",
+     "for (int a = parent[i]; a >= 0; a = parent[a]) path[len++] = a;\n      const double *fqi"),
+    ("tree_den_drops_z", "for (int f = 0; f < d; ++f) den += fqi[f] * zh[f];", ""),
+    ("tree_S_transposed", "acc += fqi[f] * Sh[(size_t)f * d + c];", "acc += fqi[f] * Sh[(size_t)c * d + f];"),
+    ("tree_window_runs_forward", "double x = t < len ? vh[(size_t)path[t] * d + c]", "double x = t < len ? vh[(size_t)path[len - 1 - t] * d + c]"),
+    ("tree_history_off_by_one", ": hh[(size_t)(Kc - 1 - (t - len + 1)) * d + c];", ": hh[(size_t)(Kc - 1 - (t - len + 1) > 0 ? Kc - 2 - (t - len + 1) : 0) * d + c];"),
+    ("tree_commits_newest_first_hist", "const double *src = back <= len ? vh + (size_t)path[back - 1] * d",
+     "const double *src = back <= len ? vh + (size_t)path[len - back] * d"),
+    ("tree_commit_skips_the_root", "for (int m = len - 1; m >= 0; --m) { /* oldest first */", "for (int m = len - 2; m >= 0; --m) {"),
+    ("tree_accept_per_head", "int acc_node = accept ? accept[b] : -1;", "int acc_node = accept ? accept[h % B] : -1; (void)b;"),
+    ("tree_uses_raw_k", "fk[e] = oracle_phi(kh[e]);", "fk[e] = kh[e];"),
     ("recurrent_ignores_incoming_S", "load_state(d, Kc, S0 ? S0 + bh * nS : NULL, z0", "load_state(d, Kc, NULL, z0"),
 ]
 
