@@ -72,6 +72,7 @@ typedef enum { LINATTN_PHI_ELU1 = 0 } linattn_phi;
 
 #define LINATTN_MAX_CONV_K 8   /* taps t, t-1, ..., t-Kc+1                              */
 #define LINATTN_MAX_DRAFT 16   /* draft tokens per verify call                          */
+#define LINATTN_MAX_TREE 64    /* candidate tokens per tree-verify call                 */
 
 typedef struct {
   int32_t B, H;            /* batch rows, heads                                        */
@@ -132,6 +133,38 @@ linattn_status linattn_verify(const linattn_desc *desc, int32_t kk,
                               float *S, float *z, void *hist,
                               const int32_t *n_commit,
                               void *out, void *hip_stream);
+
+/* Tree-structured speculative verification (Sec. 4.2, "Proposed Solution": the
+ * candidates of a speculation step follow Medusa's tree-based attention
+ * pattern; Sec. 5.3 / Tab. 9 use 64 speculated tokens).  n candidate tokens per
+ * (b, h) hang off the verified sequence as a tree: parent[i] < i is the
+ * candidate that precedes candidate i in time, -1 if candidate i follows the
+ * verified sequence directly.  Candidate i is scored from the verified state
+ * and the candidates on its own root path (its ancestors and itself), never
+ * from a sibling or another branch, and its convolution window is that path
+ * read backwards, continuing into the verified history; output i is what
+ * linattn_verify would give for the last token of that path.  A common prefix
+ * of several candidates is computed once and the state is read once for all
+ * of them.  Afterwards the state of batch row b has advanced over the root
+ * path of candidate accept[b], oldest token first.
+ *   q, k, v      in      [B,H,n,d] dense, bf16 (desc strides are ignored)
+ *   parent       in      device int32 [n], shared by all (b, h); an entry outside
+ *                        -1..i-1 is read as -1
+ *   conv_w       in      [H,d,Kc] float
+ *   S, z, hist   in/out  updated in place (hist may be NULL only if Kc == 1)
+ *   accept       in      device int32 [B] or NULL; -1, NULL or an entry outside
+ *                        0..n-1 accepts nothing and leaves that row's state
+ *                        bit-unchanged
+ *   out          out     [B,H,n,d] dense, bf16
+ * 1 <= n <= LINATTN_MAX_TREE.  io_dtype must be LINATTN_BF16
+ * (LINATTN_ERR_UNSUPPORTED otherwise). */
+linattn_status linattn_verify_tree(const linattn_desc *desc, int32_t n,
+                                   const void *q, const void *k, const void *v,
+                                   const int32_t *parent,
+                                   const float *conv_w,
+                                   float *S, float *z, void *hist,
+                                   const int32_t *accept,
+                                   void *out, void *hip_stream);
 
 /* One generated token per (b, h) (Sec. 3, decode phase; Sec. 4.1 recurrence):
  * linattn_verify with kk = 1 whose draft is always kept.

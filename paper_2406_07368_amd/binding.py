@@ -19,8 +19,8 @@ _lib = None
 
 LINATTN_F32, LINATTN_BF16 = 0, 1
 LINATTN_PHI_ELU1 = 0
-MAX_CONV_K, MAX_DRAFT = 8, 16
-SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_verify", "linattn_decode",
+MAX_CONV_K, MAX_DRAFT, MAX_TREE = 8, 16, 64
+SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_verify", "linattn_verify_tree", "linattn_decode",
            "linattn_status_string", "linattn_version")
 
 
@@ -54,6 +54,8 @@ def load():
     lib.linattn_prefill.argtypes = [dp, i32] + [vp] * 11 + [vp, sz, vp]
     lib.linattn_verify.restype = ctypes.c_int
     lib.linattn_verify.argtypes = [dp, i32] + [vp] * 9 + [vp]
+    lib.linattn_verify_tree.restype = ctypes.c_int
+    lib.linattn_verify_tree.argtypes = [dp, i32] + [vp] * 10 + [vp]
     lib.linattn_decode.restype = ctypes.c_int
     lib.linattn_decode.argtypes = [dp] + [vp] * 8 + [vp]
     lib.linattn_status_string.restype = ctypes.c_char_p
@@ -117,6 +119,12 @@ def linattn_verify(desc: Desc, kk, q, k, v, conv_w, S, z, hist, n_commit, out, s
     _check(st, "linattn_verify")
 
 
+def linattn_verify_tree(desc: Desc, n, q, k, v, parent, conv_w, S, z, hist, accept, out, stream=None) -> None:
+    st = load().linattn_verify_tree(ctypes.byref(desc), int(n), _ptr(q), _ptr(k), _ptr(v), _ptr(parent), _ptr(conv_w),
+                                    _ptr(S), _ptr(z), _ptr(hist), _ptr(accept), _ptr(out), _stream(stream))
+    _check(st, "linattn_verify_tree")
+
+
 def linattn_decode(desc: Desc, q, k, v, conv_w, S, z, hist, out, stream=None) -> None:
     st = load().linattn_decode(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
                                _ptr(S), _ptr(z), _ptr(hist), _ptr(out), _stream(stream))
@@ -157,6 +165,17 @@ def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None):
     out = torch.empty_like(q)
     S, z, h = state
     linattn_verify(desc, kk, q, k, v, conv_w, S, z, h, n_commit, out, stream)
+    return out
+
+
+def verify_tree(q, k, v, parent, conv_w, state, accept=None, eps=0.0, stream=None):
+    """q, k, v: dense bf16 [B,H,n,d]; parent: int32 [n] on the GPU.  ``state`` is updated in place along the
+    root path of candidate ``accept[b]`` (int32 [B] on the GPU; None accepts nothing).  Returns out."""
+    B, H, n, d = q.shape
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=n)
+    out = torch.empty_like(q)
+    S, z, h = state
+    linattn_verify_tree(desc, n, q, k, v, parent, conv_w, S, z, h, accept, out, stream)
     return out
 
 

@@ -142,6 +142,28 @@ linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* 
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 
+linattn_status linattn_verify_tree(const linattn_desc* desc, int32_t n, const void* q, const void* k, const void* v,
+                                   const int32_t* parent, const float* conv_w, float* S, float* z, void* hist,
+                                   const int32_t* accept, void* out, void* hip_stream) {
+  linattn_status st = check_desc(desc, false);
+  if (st != LINATTN_OK) return st;
+  if (n < 1 || n > LINATTN_MAX_TREE) return LINATTN_ERR_SHAPE;
+  if (!q || !k || !v || !parent || !conv_w || !S || !z || !out) return LINATTN_ERR_NULL;
+  if (desc->conv_k > 1 && !hist) return LINATTN_ERR_NULL;
+  const void* ptrs[] = {q, k, v, conv_w, S, z, hist, out};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LINATTN_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(parent) & 3u) || (reinterpret_cast<uintptr_t>(accept) & 3u)) return LINATTN_ERR_ALIGN;
+  if (desc->io_dtype != LINATTN_BF16) return LINATTN_ERR_UNSUPPORTED;   // the tree kernel exists for bf16 candidates only
+
+  VerifyTreeArgs a{};
+  a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;
+  a.parent = parent; a.accept = accept; a.out = out;
+  a.B = desc->B; a.H = desc->H; a.n = n; a.Kc = desc->conv_k; a.eps = desc->eps;
+  const hipError_t e = launch_verify_tree(a, desc->d, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
+}
+
 linattn_status linattn_decode(const linattn_desc* desc, const void* q, const void* k, const void* v,
                               const float* conv_w, float* S, float* z, void* hist, void* out, void* hip_stream) {
   return linattn_verify(desc, 1, q, k, v, conv_w, S, z, hist, nullptr, out, hip_stream);

@@ -20,6 +20,21 @@ struct VerifyArgs {
   float eps;
 };
 
+struct VerifyTreeArgs {
+  const void* q;
+  const void* k;
+  const void* v;            // [B,H,n,d] dense, bf16
+  const float* conv_w;      // [H,d,Kc]
+  float* S;                 // [B,H,d,d] in/out
+  float* z;                 // [B,H,d]   in/out
+  void* hist;               // [B,H,Kc-1,d] in/out, bf16
+  const int32_t* parent;    // device [n]
+  const int32_t* accept;    // device [B] or null
+  void* out;                // [B,H,n,d]
+  int B, H, n, Kc;
+  float eps;
+};
+
 struct PrefillArgs {
   const void* q;
   const void* k;
@@ -47,6 +62,9 @@ hipError_t launch_verify(const VerifyArgs& a, bool bf16, int d, int nsplit, hipS
 // verify_mfma.hip : the same step as one 16-token group on the matrix cores (bf16 drafts, whole heads)
 bool verify_mfma_available(bool bf16, int d, int nsplit, int kk);
 hipError_t launch_verify_mfma(const VerifyArgs& a, int d, hipStream_t st);
+
+// verify_tree.hip : candidates arranged as a tree, scored from one read of the state
+hipError_t launch_verify_tree(const VerifyTreeArgs& a, int d, hipStream_t st);
 
 // prefill_simt.hip : fp32 arithmetic on the vector ALUs, one workgroup per (b, h)
 hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st);

@@ -26,7 +26,7 @@ import torch
 @dataclass(frozen=True)
 class Workload:
     name: str
-    mode: str          # "prefill" or "verify"
+    mode: str          # "prefill", "verify" or "verify_tree"
     B: int
     H: int
     L: int             # prefill length, or prefix length for verify workloads
@@ -53,6 +53,10 @@ CONFIGS = {
     # config 4: decode + speculative verify on a state built from a 2048-token prefix
     "cfg4_llama7b_verify": Workload("cfg4_llama7b_verify", "verify", 32, 32, 2048, 128, "bf16", 64, 3, 1.0,
                                     1004, (1, 4, 8)),
+    # tree-structured verify on the state of config 4: 64 speculated tokens, 42 sequence candidates
+    # (root-to-leaf paths), the shape of the paper's single-batch comparison (Sec. 5.3, Tab. 9)
+    "tree_verify_64x42": Workload("tree_verify_64x42", "verify_tree", 32, 32, 2048, 128, "bf16", 64, 3, 1.0,
+                                  1006, (64, 42)),
     # config 5: long-context prefill
     "cfg5_long_context": Workload("cfg5_long_context", "prefill", 1, 32, 65536, 128, "bf16", 128, 5, 1.0, 1005),
 }
@@ -91,6 +95,34 @@ def draft_block(wl: Workload, kk: int, step: int = 0, seed: int | None = None):
     rng = np.random.default_rng(base + 100 * (step + 1))
     shape = (wl.B, wl.H, kk, wl.d)
     return tuple(round_to_io(rng.standard_normal(shape) * wl.scale, wl.io_dtype) for _ in range(3))
+
+
+def candidate_tree(n: int, leaves: int, seed: int) -> np.ndarray:
+    """parent[n] (int32) of a seeded tree with ``n`` candidates of which exactly ``leaves`` have no child,
+    i.e. ``leaves`` root-to-leaf sequence candidates.  parent[i] < i; -1 marks a candidate that follows the
+    verified sequence directly.  The n - leaves inner candidates come first (each hangs under an earlier inner
+    candidate or under the verified sequence, so the tree is a few steps deep and bushy near the root, like
+    the hand-made trees of tree-based speculative decoders); every inner candidate without a child
+    then gets a leaf, and the remaining leaves pick an inner candidate at random.  Only the shape is modelled: no decoder's
+    actual tree is reproduced.
+    """
+    inner = n - leaves
+    if not (0 <= inner <= leaves and n >= 1):
+        raise ValueError("need n >= 1 and at most as many inner candidates as leaves")
+    rng = np.random.default_rng(seed)
+    parent = np.full(n, -1, dtype=np.int32)
+    has_child = np.zeros(max(inner, 1), dtype=bool)
+    for i in range(1, inner):
+        parent[i] = int(rng.integers(-1, i))
+        if parent[i] >= 0:
+            has_child[parent[i]] = True
+    childless = [i for i in range(inner) if not has_child[i]]
+    for j in range(inner, n):
+        if childless:
+            parent[j] = childless.pop(0)
+        elif inner:
+            parent[j] = int(rng.integers(0, inner))
+    return parent
 
 
 def random_state(wl: Workload, tokens: int, seed: int | None = None):

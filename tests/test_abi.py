@@ -113,6 +113,28 @@ def test_verify_rejects_bad_arguments():
     assert lib.linattn_decode(ctypes.byref(d), P, None, P, P, P, P, P, P, None) == 1
 
 
+def tree_status(desc, n=8, **over):
+    lib = binding.load()
+    a = dict(q=P, k=P, v=P, parent=P, conv_w=P, S=P, z=P, hist=P, accept=None, out=P)
+    a.update(over)
+    return lib.linattn_verify_tree(ctypes.byref(desc) if desc is not None else None, n, a["q"], a["k"], a["v"],
+                                   a["parent"], a["conv_w"], a["S"], a["z"], a["hist"], a["accept"], a["out"], None)
+
+
+def test_verify_tree_rejects_bad_arguments():
+    d = good_desc()
+    assert tree_status(None) == 1
+    assert tree_status(d, n=0) == 2
+    assert tree_status(d, n=65) == 2
+    assert tree_status(d, parent=None) == 1
+    assert tree_status(d, hist=None) == 1
+    assert tree_status(d, S=P + 8) == 4
+    assert tree_status(d, parent=P + 2) == 4
+    assert tree_status(d, accept=P + 1) == 4
+    assert tree_status(good_desc(io_dtype=binding.LINATTN_F32)) == 5      # bf16 candidates only
+    assert tree_status(good_desc(d=96)) == 2
+
+
 def test_binding_raises_on_refusal():
     with pytest.raises(binding.LinattnError) as ei:
         binding.linattn_verify(good_desc(), 0, P, P, P, P, P, P, P, None, P, stream=0)
