@@ -16,7 +16,8 @@ already resident in HBM:
 The headline ``value`` is prefill tokens/s (B*L divided by the mean duration of the
 prefill launches, measured with events on the launch stream inside the timed
 region); the verify/decode step times are reported beside it in microseconds with
-their own HBM roofline.  Between steps the verify state rotates over 32 separate
+their own HBM roofline; the tree-structured verify (64 candidates) is timed after the
+steps and reported as ``tree_verify``.  Between steps the verify state rotates over 32 separate
 state sets (2.1 GB) and the prefill inputs over 2 sets (2.1 GB) so that nothing is
 served from the 256 MB last-level cache.
 
@@ -250,6 +251,38 @@ def main():
         other_layout_ms = {"layout": other, "mean": sum(a.elapsed_time(b) for a, b in ev2) / len(ev2),
                            "min": min(a.elapsed_time(b) for a, b in ev2)}
 
+    tree = None
+    if do_verify and args.only == "all":
+        # next row of the scope (not part of the step): tree-structured verify, 64 speculated tokens / 42
+        # sequence candidates on the same 1024 heads; each call takes a state set of its own and every batch row
+        # accepts one root path, so the whole state is written back as in the chain case
+        tw = workloads.CONFIGS["tree_verify_64x42"]
+        n_nodes, n_leaves = tw.draft_k
+        parent = torch.from_numpy(workloads.candidate_tree(n_nodes, n_leaves, tw.seed)).to(dev)
+        tq, tk, tv = (torch.from_numpy(a).to(torch.bfloat16).to(dev) for a in workloads.draft_block(tw, n_nodes))
+        tout = torch.empty_like(tq)
+        accept = torch.from_numpy(((np.arange(tw.B) * 7) % n_nodes).astype(np.int32)).to(dev)
+        ev3 = []
+        for i in range(10 + min(args.steps, 50)):
+            S, z, h = states[i % len(states)]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            binding.linattn_verify_tree(vdesc, n_nodes, tq, tk, tv, parent, vwts, S, z, h, accept, tout, stream)
+            e1.record(stream)
+            if i >= 10:
+                ev3.append((e0, e1))
+        stream.synchronize()
+        t_us = [a.elapsed_time(b) * 1e3 for a, b in ev3]
+        heads = tw.B * tw.H
+        nb = heads * ((tw.d * tw.d + tw.d) * 8 + n_nodes * tw.d * 8 + (tw.conv_k - 1) * tw.d * 4)
+        t_mean = sum(t_us) / len(t_us)
+        tree = {"workload": f"{tw.name}: B{tw.B} H{tw.H} d{tw.d}, {n_nodes} candidates, {n_leaves} root-to-leaf paths, "
+                            "every row accepts one path",
+                "us": {"mean": t_mean, "min": min(t_us)},
+                "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": nb / t_mean / 1e3 / HBM_PEAK_GBS, "algorithmic_bytes": nb,
+                             "traffic": read_traffic("tree_verify_64x42_pmc.txt")}}
+
     mean_ms = {n: (sum(a.elapsed_time(b) for a, b in lst) / len(lst)) for n, lst in ev.items() if lst}
     min_ms = {n: min(a.elapsed_time(b) for a, b in lst) for n, lst in ev.items() if lst}
 
@@ -293,6 +326,8 @@ def main():
                               "traffic": read_traffic(f"verify_cfg4_k{kk}_pmc.txt")}
         result["verify_us_per_step"] = us
         result["roofline_verify"] = roof
+        if tree:
+            result["tree_verify"] = tree
         if not do_prefill:
             result["value"] = us["k8"]["mean"]
             result["unit"] = "us/step (verify k=8)"

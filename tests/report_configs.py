@@ -132,6 +132,45 @@ def verify_rows():
         t1, tn = oracle_time(run_heads, threads)
         rows.append(f"| cfg4 verify k={kk} | {t * 1e6:.1f} µs | {wl.B * kk / t / 1e6:.2f} M draft tokens/s | {100 * nbytes / t / HBM:.1f} | - | "
                     f"{t1 * heads * 1e3:.1f} ms | {tn * heads * 1e3:.1f} ms ({threads}) | {worst:.1e} ({len(sample)} heads) |")
+    # tree-structured verify on the same state: 64 candidates, 42 root-to-leaf paths
+    tw = workloads.CONFIGS["tree_verify_64x42"]
+    n, leaves = tw.draft_k
+    parent = workloads.candidate_tree(n, leaves, tw.seed)
+    dq, dk, dv = (torch.from_numpy(a).to(torch.bfloat16) for a in workloads.draft_block(tw, n))
+    gq, gk, gv, gp = dq.cuda(), dk.cuda(), dv.cuda(), torch.from_numpy(parent).cuda()
+    accept = torch.from_numpy(((np.arange(tw.B) * 7) % n).astype(np.int32))
+    state = tuple(t.clone() for t in state0)
+    out = binding.verify_tree(gq, gk, gv, gp, gw, state, accept.cuda())
+    torch.cuda.synchronize()
+    worst = 0.0
+    for b, h in sample:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        S1, z1, h1 = pre[(b, h)]
+        want = oracle.verify_tree(host(dq[sl]), host(dk[sl]), host(dv[sl]), parent, w[h:h + 1].numpy(), S1, z1, h1,
+                                  accept[b:b + 1].numpy())
+        worst = max(worst, rel_err(host(out[sl]), want[0]), rel_err(host(state[0][sl]), want[1]))
+    desc = binding.make_desc(tw.B, tw.H, tw.d, tw.conv_k, tw.chunk, torch.bfloat16, L=1)
+    o = torch.empty_like(gq)
+    ga = accept.cuda()
+    i = [0]
+
+    def call_tree():
+        S, z, h = sets[i[0] % len(sets)]
+        i[0] += 1
+        binding.linattn_verify_tree(desc, n, gq, gk, gv, gp, gw, S, z, h, ga, o)
+    t = gpu_time(call_tree)
+    heads = tw.B * tw.H
+    nbytes = heads * ((tw.d * tw.d + tw.d) * 8 + n * tw.d * 8 + (tw.conv_k - 1) * tw.d * 4)
+    S1, z1, h1 = pre[sample[0]]
+
+    def run_tree_heads(m):
+        a = np.repeat(host(dq[:1, :1]), m, axis=1)
+        oracle.verify_tree(a, a, a, parent, np.repeat(w[:1].numpy(), m, axis=0), np.repeat(S1, m, axis=1),
+                           np.repeat(z1, m, axis=1), np.repeat(h1, m, axis=1))
+    t1, tn = oracle_time(run_tree_heads, threads)
+    rows.append(f"| tree verify, {n} candidates / {leaves} paths | {t * 1e6:.1f} µs | {tw.B * n / t / 1e6:.2f} M candidate tokens/s | "
+                f"{100 * nbytes / t / HBM:.1f} | - | {t1 * heads * 1e3:.1f} ms | {tn * heads * 1e3:.1f} ms ({threads}) | "
+                f"{worst:.1e} ({len(sample)} heads) |")
     return rows
 
 
