@@ -122,12 +122,16 @@ def cpu_baseline(wl, seconds):
         oracle.prefill_recurrent(q, k, v, w)
         return time.perf_counter() - t0
 
+    oracle.set_num_threads(1)
+    t_one = run(1)                                           # one head on one thread
+    oracle.set_num_threads(threads)
     t_probe = run(threads)                                   # one head per thread
     heads = int(max(threads, min(wl.B * wl.H, threads * round(seconds / max(t_probe, 1e-3)))))
     heads -= heads % threads
     t = run(heads)
     head_tokens_per_s = heads * wl.L / t
     return {"value": head_tokens_per_s / wl.H, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "value_one_thread": wl.L / t_one / wl.H,
             "sample": f"{heads} of {wl.B * wl.H} heads x L={wl.L} (fp64 recurrent form), {t:.1f} s; "
                       f"scaled to a {wl.H}-head layer"}
 
@@ -285,6 +289,7 @@ def main():
 
     mean_ms = {n: (sum(a.elapsed_time(b) for a, b in lst) / len(lst)) for n, lst in ev.items() if lst}
     min_ms = {n: min(a.elapsed_time(b) for a, b in lst) for n, lst in ev.items() if lst}
+    med_ms = {n: float(np.median([a.elapsed_time(b) for a, b in lst])) for n, lst in ev.items() if lst}
 
     result = {
         "metric": "linear-attn prefill tokens/s (LLaMA-7B layer shape) + spec-verify step us, % roofline",
@@ -301,7 +306,7 @@ def main():
         nbytes = prefill_bytes(pw)
         fc, fd = prefill_flops(pw)
         result["value"] = pw.B * pw.L / t
-        result["prefill_ms"] = {"mean": mean_ms["prefill"], "min": min_ms["prefill"]}
+        result["prefill_ms"] = {"mean": mean_ms["prefill"], "median": med_ms["prefill"], "min": min_ms["prefill"]}
         if other_layout_ms:
             result["prefill_ms_other_layout"] = other_layout_ms
         result["roofline"] = {"bound": "hbm", "achieved": nbytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -320,7 +325,7 @@ def main():
         for name, kk in (("verify8", 8), ("verify4", 4), ("decode", 1)):
             t = mean_ms[name] * 1e-3
             nb = verify_bytes(vw, kk)
-            us[f"k{kk}"] = {"mean": mean_ms[name] * 1e3, "min": min_ms[name] * 1e3}
+            us[f"k{kk}"] = {"mean": mean_ms[name] * 1e3, "median": med_ms[name] * 1e3, "min": min_ms[name] * 1e3}
             roof[f"k{kk}"] = {"bound": "hbm", "achieved": nb / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": nb / t / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": nb,
                               "traffic": read_traffic(f"verify_cfg4_k{kk}_pmc.txt")}

@@ -27,6 +27,17 @@ def rel_err(got, want) -> float:
     return float(np.max(np.abs(got - want) / den))
 
 
+def err_stats(got, want):
+    """(rel_err as above, plain max abs error, 99.9th percentile of the un-floored relative error)."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return 0.0, 0.0, 0.0
+    diff = np.abs(got - want)
+    unfloored = diff / np.maximum(np.abs(want), 1e-30)
+    return rel_err(got, want), float(diff.max()), float(np.percentile(unfloored, 99.9))
+
+
 def check(got, want, tol, what):
     e = rel_err(got, want)
     assert e <= tol, f"{what}: rel err {e:.3e} > {tol:.1e} (max abs {np.max(np.abs(np.asarray(got, dtype=np.float64) - want)):.3e})"
