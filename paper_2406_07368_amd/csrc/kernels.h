@@ -69,14 +69,13 @@ hipError_t launch_verify_tree(const VerifyTreeArgs& a, int d, hipStream_t st);
 // prefill_simt.hip : fp32 arithmetic on the vector ALUs, one workgroup per (b, h)
 hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st);
 
-// prefill_mfma.hip : bf16 operands on the matrix cores, fp32 accumulation
+// prefill_mfma.hip : launch plan of the bf16 prefill (segments, prefix sum over segment states)
 int prefill_mfma_pick_segments(int BH, int L, int chunk);
 size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg);
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, hipStream_t st);
 
-// prefill_mfma_ws.hip : the same path with front-end waves (HBM traffic, feature map, scores) and
-// state waves (everything that touches S and z) working side by side
-bool prefill_mfma_ws_available(int d, int chunk);
-hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, int chunk, bool state_only, hipStream_t st);
+// prefill_mfma_ws.hip : the matrix-core kernel, with front-end waves (HBM traffic, feature map, scores)
+// and state waves (everything that touches S and z) working side by side
+hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, bool state_only, hipStream_t st);
 
 }  // namespace linattn

@@ -1,5 +1,5 @@
-// Prefill on the matrix cores with specialised waves (Sec. 4.1), the kernel used
-// whenever two copies of a group's rows fit in LDS.
+// Prefill on the matrix cores with specialised waves (Sec. 4.1): the kernel of every bf16
+// prefill (bf16 operands, fp32 accumulation).
 //
 // A workgroup walks one (b, h) -- or one segment of it -- in groups of C tokens and
 // is split into two halves that run at the same time, one wave of each on every SIMD:
@@ -643,43 +643,31 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   }
 }
 
-template <int D, int C>
-bool ws_fits() { return WsCfg<D, C>::FITS; }
-
 template <int D, int C, int KCM, bool STATE_ONLY>
 static hipError_t launch_ws(const PrefillArgs& a, hipStream_t st) {
   using G = WsCfg<D, C>;
-  if constexpr (!G::FITS) {
-    return hipErrorInvalidConfiguration;
-  } else {
-    auto kern = prefill_mfma_ws_kernel<D, C, KCM, STATE_ONLY>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
-    if (e != hipSuccess) return e;
-    const int segs = STATE_ONLY ? a.nseg - 1 : a.nseg;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * segs)), dim3(G::NT), G::TOTAL, st, a);
-    return hipGetLastError();
-  }
+  static_assert(G::FITS, "two row buffers must fit in the 160 KB of LDS");
+  auto kern = prefill_mfma_ws_kernel<D, C, KCM, STATE_ONLY>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
+  if (e != hipSuccess) return e;
+  const int segs = STATE_ONLY ? a.nseg - 1 : a.nseg;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * segs)), dim3(G::NT), G::TOTAL, st, a);
+  return hipGetLastError();
 }
 
-template <int D, int C>
+template <int D>
 static hipError_t launch_ws_k(const PrefillArgs& a, bool state_only, hipStream_t st) {
+  constexpr int C = 64;   // tokens per group
   if (state_only) return launch_ws<D, C, 3, true>(a, st);   // the conv taps play no part in the state
   if (a.Kc <= 3) return launch_ws<D, C, 3, false>(a, st);
   if (a.Kc <= 5) return launch_ws<D, C, 5, false>(a, st);
   return launch_ws<D, C, 8, false>(a, st);
 }
 
-// True when the specialised kernel exists for this shape (two row buffers fit in 160 KB of LDS).
-bool prefill_mfma_ws_available(int d, int chunk) {
-  if (d == 128) return chunk == 64 ? ws_fits<128, 64>() : ws_fits<128, 128>();
-  return chunk == 64 ? ws_fits<64, 64>() : ws_fits<64, 128>();
-}
-
 // One pass of a prefill call over all its segments.  state_only: the first pass of the segmented
 // form (segment increments into a.ws); otherwise the full pass (segment start states must be in a.ws).
-hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, int chunk, bool state_only, hipStream_t st) {
-  if (d == 128) return chunk == 64 ? launch_ws_k<128, 64>(a, state_only, st) : launch_ws_k<128, 128>(a, state_only, st);
-  return chunk == 64 ? launch_ws_k<64, 64>(a, state_only, st) : launch_ws_k<64, 128>(a, state_only, st);
+hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, bool state_only, hipStream_t st) {
+  return d == 128 ? launch_ws_k<128>(a, state_only, st) : launch_ws_k<64>(a, state_only, st);
 }
 
 }  // namespace linattn

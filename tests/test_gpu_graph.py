@@ -1,0 +1,95 @@
+"""The entry points under HIP graph capture: a serving loop replays decode / verify steps as a graph.
+
+The library allocates nothing and keeps no state between calls, so a captured sequence of calls must give,
+on every replay, what the same calls give when issued eagerly."""
+import numpy as np
+import pytest
+import torch
+
+from parity import dev, host
+from paper_2406_07368_amd import binding, workloads
+from test_gpu_verify import make_case
+
+pytestmark = pytest.mark.gpu
+BF = torch.bfloat16
+
+
+def test_decode_verify_and_tree_steps_replay_as_a_graph():
+    B, H, d, Kc = 24, 32, 128, 3                       # whole heads: the matrix-core kernels
+    q, k, v, w, S, z, hist = make_case(71, B, H, d, Kc, 8, "bf16", prefix=12)
+    gw = dev(w)
+    dq, dk, dv = dev(q, BF), dev(k, BF), dev(v, BF)
+    parent = torch.from_numpy(workloads.candidate_tree(8, 5, 3)).cuda()
+    accept = torch.from_numpy((np.arange(B) % 8).astype(np.int32)).cuda()
+    n_commit = torch.from_numpy((np.arange(B) % 5).astype(np.int32)).cuda()
+    desc = binding.make_desc(B, H, d, Kc, 64, BF, L=1)
+
+    def new_state():
+        return dev(S), dev(z), dev(hist, BF)
+
+    outs = [torch.empty((B, H, 1, d), dtype=BF, device="cuda"), torch.empty((B, H, 4, d), dtype=BF, device="cuda"),
+            torch.empty((B, H, 8, d), dtype=BF, device="cuda")]
+
+    # the inputs of the captured calls must outlive the capture: slice once, outside
+    d1 = tuple(x[:, :, :1].contiguous() for x in (dq, dk, dv))
+    d4 = tuple(x[:, :, 1:5].contiguous() for x in (dq, dk, dv))
+
+    def steps_fixed(state, o):
+        Ss, zs, hs = state
+        binding.linattn_decode(desc, d1[0], d1[1], d1[2], gw, Ss, zs, hs, o[0])
+        binding.linattn_verify(desc, 4, d4[0], d4[1], d4[2], gw, Ss, zs, hs, n_commit, o[1])
+        binding.linattn_verify_tree(desc, 8, dq, dk, dv, parent, gw, Ss, zs, hs, accept, o[2])
+
+    graph_state, eager_state = new_state(), new_state()
+    eager_outs = [torch.empty_like(o) for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream, then restore the state
+        steps_fixed(graph_state, outs)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for t, s0 in zip(graph_state, (S, z, hist)):
+        t.copy_(dev(s0, t.dtype))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        steps_fixed(graph_state, outs)
+    torch.cuda.synchronize()
+    for t, s0 in zip(graph_state, (S, z, hist)):       # capture does not execute: still the initial state
+        assert torch.equal(t, dev(s0, t.dtype))
+    for replay in range(4):
+        g.replay()
+        steps_fixed(eager_state, eager_outs)           # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        for a, b in zip(outs, eager_outs):
+            assert torch.equal(a, b), f"replay {replay}: outputs differ from the eager calls"
+        for a, b in zip(graph_state, eager_state):
+            assert torch.equal(a, b), f"replay {replay}: state differs from the eager calls"
+    assert not np.array_equal(host(graph_state[0]), S.astype(np.float64))   # the state did move
+
+
+def test_prefill_replays_as_a_graph():
+    wl = workloads.CONFIGS["cfg2_gpt2_small"]        # segmented: three kernels and a workspace per call
+    q, k, v, w = workloads.prefill_tensors(wl)
+    gq, gk, gv, gw = q.cuda(), k.cuda(), v.cuda(), w.cuda()
+    desc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, BF, L=wl.L)
+    nb = binding.linattn_workspace_bytes(desc, wl.L)
+    assert nb > 0
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    mk = lambda: (torch.empty_like(gq), torch.empty((wl.B, wl.H, wl.d, wl.d), device="cuda"),
+                  torch.empty((wl.B, wl.H, wl.d), device="cuda"),
+                  torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d), dtype=BF, device="cuda"))
+    want, got = mk(), mk()
+    binding.linattn_prefill(desc, wl.L, gq, gk, gv, gw, None, None, None, *want, ws, nb)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        binding.linattn_prefill(desc, wl.L, gq, gk, gv, gw, None, None, None, *got, ws, nb)
+    for replay in range(3):
+        for t in got:
+            t.zero_()
+        ws.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"replay {replay} differs from the eager call"
