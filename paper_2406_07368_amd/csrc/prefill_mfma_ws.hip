@@ -45,12 +45,7 @@ struct WsCfg {
   static constexpr int KSC = C / 16;
   static constexpr int NP = C / 16;          // front-end passes: 16 tokens x all columns per pass
   static constexpr int QS = D + 4;           // phi(Q): 8-byte row reads, one row per lane
-  // phi(K) is read two ways: 16-byte row reads (one row per lane) for the scores and transpose
-  // reads (4 rows x 32 columns per half wave) for the state update.  The row stride of D + 32
-  // (16 banks more than a multiple of 64) spreads the four rows of a transpose read over the
-  // banks; rotating row t by 8 * (t / 4) columns does the same for 16 consecutive rows of a
-  // row read.  Both readers and the writer apply the rotation (krot).
-  static constexpr int KS = D + 32;
+  static constexpr int KS = D + 16;          // phi(K): transpose reads and 16-byte row reads
   static constexpr int VS = D + 4;           // V: 8-byte row reads by the conv, some transpose reads
   static constexpr int PS = C + 8;           // P: 16-byte row reads
   static constexpr int NTILE = TB * (TB + 1) / 2;
@@ -72,20 +67,6 @@ struct WsCfg {
   static constexpr int TOTAL = OFF_SYNC + 16;
   static constexpr bool FITS = TOTAL <= 160 * 1024;
 };
-
-// column of feature c in row t of the phi(K) rows
-template <int D>
-__device__ __forceinline__ int krot(int t, int c) { return (c + 8 * (t >> 2)) & (D - 1); }
-
-// tr_operand for the rotated phi(K) rows: lanes <-> 32 consecutive features col0 + lane%32,
-// registers <-> rows row0 + 8*(lane/32) + 0..7 (row0 a multiple of 16)
-template <int D>
-__device__ __forceinline__ bf16x8 tr_operand_krot(const uint16_t* base, int stride, int row0, int col0, int lane) {
-  const int j = lane & 15;
-  const int r = row0 + 8 * (lane >> 5) + (j >> 2);
-  const int c = col0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
-  return cat4(lds_tr4(base + r * stride + krot<D>(r, c)), lds_tr4(base + (r + 4) * stride + krot<D>(r + 4, c)));
-}
 
 }  // namespace
 
@@ -215,7 +196,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           if (PARTIAL) qp[i] = ok ? qp[i] : 0u;
         }
       }
-      *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + krot<D>(t, c0)) = kp;
+      *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
       u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + t) * G::VS + c0);
       vrow[0] = u32x2{vp[0], vp[1]};
       vrow[1] = u32x2{vp[2], vp[3]};
@@ -280,8 +261,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           f32x16 acc;
 #pragma unroll
           for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-          const uint16_t* ka = Kn + (32 * sb + l32) * G::KS;
-          const int kc = 8 * hi + 8 * ((32 * sb + l32) >> 2);   // rotated column of this lane's first feature
+          const uint16_t* ka = Kn + (32 * sb + l32) * G::KS + 8 * hi;
           const uint16_t* qb = Qn + (32 * tb + l32) * G::QS + 8 * hi;
           constexpr int HB = G::KSD / 2;   // two batches of K steps
 #pragma unroll
@@ -290,7 +270,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
             for (int k2 = 0; k2 < HB; ++k2) {
               const int ks = half * HB + k2;
-              ak[k2] = lds_row8(ka + ((kc + 16 * ks) & (D - 1)));
+              ak[k2] = lds_row8(ka + 16 * ks);
               bq[k2] = cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4));
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -491,12 +471,12 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     {
       bf16x8 kt[2][G::KSC];
 #pragma unroll
-      for (int ks = 0; ks < G::KSC; ++ks) kt[0][ks] = tr_operand_krot<D>(Kn, G::KS, 16 * ks, 0, lane);
+      for (int ks = 0; ks < G::KSC; ++ks) kt[0][ks] = tr_operand(Kn, G::KS, 16 * ks, 0, lane);
 #pragma unroll
       for (int ib = 0; ib < G::IB; ++ib) {
         if (ib + 1 < G::IB) {
 #pragma unroll
-          for (int ks = 0; ks < G::KSC; ++ks) kt[(ib + 1) & 1][ks] = tr_operand_krot<D>(Kn, G::KS, 16 * ks, 32 * (ib + 1), lane);
+          for (int ks = 0; ks < G::KSC; ++ks) kt[(ib + 1) & 1][ks] = tr_operand(Kn, G::KS, 16 * ks, 32 * (ib + 1), lane);
         }
         LINATTN_FENCE();
 #pragma unroll
