@@ -45,6 +45,8 @@ def _load(path: str | None = None):
 
 def _declare(lib):
     i, f = ctypes.c_int, ctypes.c_double
+    lib.oracle_set_feature_map.restype = None
+    lib.oracle_set_feature_map.argtypes = [i]
     lib.oracle_phi.restype = f
     lib.oracle_phi.argtypes = [f]
     lib.oracle_causal_conv.restype = None
@@ -84,6 +86,26 @@ def num_threads() -> int:
 
 def set_num_threads(n: int) -> None:
     _load().oracle_set_num_threads(int(n))
+
+
+FEATURE_MAPS = {"elu1": 0, "relu": 1}
+
+
+class feature_map:
+    """``with oracle.feature_map("relu"): ...`` -- every oracle call inside uses phi(x) = max(x, 0)
+    instead of elu(x) + 1 (a setting of the loaded library, restored on exit)."""
+
+    def __init__(self, kind: str, lib=None):
+        self.code = FEATURE_MAPS[kind]
+        self.lib = lib or _load()
+
+    def __enter__(self):
+        self.lib.oracle_set_feature_map(self.code)
+        return self
+
+    def __exit__(self, *exc):
+        self.lib.oracle_set_feature_map(0)
+        return False
 
 
 def phi(x, lib=None):

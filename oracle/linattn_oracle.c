@@ -54,7 +54,17 @@
 #include <string.h>
 
 /* phi(x) = elu(x) + 1 : x + 1 for x > 0, exp(x) otherwise (continuous at 0). */
-double oracle_phi(double x) { return x > 0.0 ? x + 1.0 : exp(x); }
+/* The feature map.  0: elu(x) + 1 (the default of this build).  1: max(x, 0), the
+ * "ReLU" linear attention that the paper lists among the existing linear
+ * attentions it evaluates (Sec. 3, "Comprehensive Evaluation"); with it the
+ * denominator can vanish, so callers pass eps > 0.  The choice is a property of
+ * the loaded library (one setting for all calls that follow). */
+static int g_feature_map = 0;
+void oracle_set_feature_map(int kind) { g_feature_map = kind; }
+double oracle_phi(double x) {
+  if (g_feature_map == 1) return x > 0.0 ? x : 0.0;
+  return x > 0.0 ? x + 1.0 : exp(x);
+}
 
 static double dot(const double *a, const double *b, int n) {
   double s = 0.0;

@@ -430,6 +430,58 @@ def pin_verify_no_leak_between_drafts(lib=None):
         assert not np.array_equal(got[:, :, j + 1:], base[:, :, j + 1:])
 
 
+# --- the other feature map: phi(x) = max(x, 0) (the "ReLU" linear attention of Sec. 3) ------------------
+def pin_relu_feature_map_values(lib=None):
+    xs = np.array([-30.0, -1.0, -1e-9, 0.0, 1e-9, 0.25, 7.5])
+    with oracle.feature_map("relu", lib):
+        got = oracle.phi(xs, lib=lib)
+    assert np.array_equal(got, np.maximum(xs, 0.0))
+    assert oracle.phi(np.array([0.0]), lib=lib)[0] == 1.0      # and the default is back afterwards
+
+
+def pin_relu_on_inputs_above_one_is_the_default_map_shifted(lib=None):
+    """For x > 1: max(x, 0) = x = elu(x - 1) + 1, so on such inputs the two maps must give the same
+    results when the default map is fed q - 1 and k - 1 (every form, incoming state included)."""
+    r = _rng(61)
+    B, H, L, d, Kc = 2, 2, 9, 4, 3
+    q, k = (1.0 + np.abs(r.standard_normal((B, H, L, d))) + 0.125 for _ in range(2))
+    v = r.standard_normal((B, H, L, d))
+    w = r.standard_normal((H, d, Kc))
+    S0 = r.standard_normal((B, H, d, d)); z0 = np.abs(r.standard_normal((B, H, d))) + 0.5
+    h0 = r.standard_normal((B, H, Kc - 1, d))
+    for form in FORMS:
+        want = getattr(oracle, form)(q - 1.0, k - 1.0, v, w, S0, z0, h0, eps=0.5, lib=lib)
+        with oracle.feature_map("relu", lib):
+            got = getattr(oracle, form)(q, k, v, w, S0, z0, h0, eps=0.5, lib=lib)
+        for g, x, what in zip(got, want, ("out", "S", "z", "hist")):
+            _close(g, x, 1e-12, f"relu {form} {what}")
+    n_commit = np.array([4, 0], dtype=np.int32)
+    want = oracle.verify(q - 1.0, k - 1.0, v, w, S0, z0, h0, n_commit, eps=0.5, lib=lib)
+    parent = np.array([-1, 0, 0, 2, 1, 4, -1, 6, 3], dtype=np.int32)
+    want_t = oracle.verify_tree(q - 1.0, k - 1.0, v, parent, w, S0, z0, h0, n_commit - 1, eps=0.5, lib=lib)
+    with oracle.feature_map("relu", lib):
+        got = oracle.verify(q, k, v, w, S0, z0, h0, n_commit, eps=0.5, lib=lib)
+        got_t = oracle.verify_tree(q, k, v, parent, w, S0, z0, h0, n_commit - 1, eps=0.5, lib=lib)
+    for g, x in zip(got + got_t, want + want_t):
+        _close(g, x, 1e-12, "relu verify")
+
+
+def pin_relu_drops_negative_entries(lib=None):
+    """Negative entries of q and k do not exist for this map; with every key negative only eps and the
+    convolution are left."""
+    q, k, v, w = _rand(62, L=11)
+    with oracle.feature_map("relu", lib):
+        a = oracle.prefill_recurrent(q, k, v, w, eps=0.25, lib=lib)
+        b = oracle.prefill_recurrent(np.maximum(q, 0.0), np.maximum(k, 0.0), v, w, eps=0.25, lib=lib)
+        dead = oracle.prefill_quadratic(q, -np.abs(k) - 0.5, v, w, eps=0.25, lib=lib)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    _close(dead[0], oracle.causal_conv(v, w, None, lib=lib), 1e-12, "all keys dead: out = conv")
+    assert np.all(dead[1] == 0.0) and np.all(dead[2] == 0.0)
+    default = oracle.prefill_recurrent(q, k, v, w, eps=0.25, lib=lib)
+    assert not np.allclose(a[0], default[0])
+
+
 # --- tree-structured verification (Sec. 4.2, "Proposed Solution") -------------------------------
 def _tree_case(seed, n=11, B=2, H=2, d=4, Kc=4):
     r = _rng(seed)

@@ -116,6 +116,19 @@ def test_matrix_core_verify_equals_sequential_decode_and_leaks_nothing():
         assert np.array_equal(other[:, :, :j + 1], got[0][:, :, :j + 1]), f"draft {j} saw a later draft"
 
 
+def test_fp32_drafts_on_whole_heads_keep_the_exact_update():
+    """fp32 drafts never take the matrix-core kernel: B*H >= 768 runs the streaming kernel unsplit (fp32 products)."""
+    B, H, d, Kc, kk, io = MB, MH, 64, 3, 5, "f32"
+    q, k, v, w, S, z, hist = make_case(19, B, H, d, Kc, kk, io, prefix=8)
+    n_commit = (np.arange(B) % (kk + 1)).astype(np.int32)
+    want = oracle.verify(q, k, v, w, S, z, hist, n_commit)
+    got = run_gpu(q, k, v, w, S, z, hist, io, n_commit)
+    check(got[0], want[0], TOL[io], "out")
+    check(got[1], want[1], 1e-5, "S")
+    check(got[2], want[2], 1e-5, "z")
+    assert np.array_equal(got[3], want[3])
+
+
 def test_rejected_drafts_leave_no_trace():
     """n_commit = 0 hands the state back bit-unchanged; outputs are still produced."""
     B, H, d, Kc, kk, io = 3, 4, 128, 3, 8, "bf16"

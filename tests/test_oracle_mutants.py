@@ -44,6 +44,9 @@ MUTANTS = [
     ("verify_commits_everything", "int n = n_commit ? n_commit[b] : kk;", "int n = kk; (void)b;"),
     ("verify_n_commit_per_head", "int n = n_commit ? n_commit[b] : kk;", "int n = n_commit ? n_commit[h % B] : kk; (void)b;"),
     ("recurrent_ignores_incoming_hist", "hist0 ? hist0 + bh * nh : NULL, S, z, hs);", "NULL, S, z, hs);"),
+    ("relu_keeps_negatives", "if (g_feature_map == 1) return x > 0.0 ? x : 0.0;", "if (g_feature_map == 1) return x;"),
+    ("relu_adds_one", "if (g_feature_map == 1) return x > 0.0 ? x : 0.0;", "if (g_feature_map == 1) return x > 0.0 ? x + 1.0 : 0.0;"),
+    ("relu_setting_ignored", "void oracle_set_feature_map(int kind) { g_feature_map = kind; }", "void oracle_set_feature_map(int kind) { (void)kind; }"),
     ("tree_sees_the_stored_neighbour", "for (int a = i; a >= 0; a = parent[a]) path[len++] = a;\n      const double *fqi",
      "for (int a = i; a >= 0; a = a - 1) path[len++] = a;\n      const double *fqi"),
     ("tree_excludes_the_candidate_itself", "for (int a = i; a >= 0; a = parent[a]) path[len++] = a;\n      const double *fqi",
