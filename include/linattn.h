@@ -4,7 +4,7 @@
  *
  * The operation (per batch row b and head h, independently):
  *
- *   Phi_q = phi(Q), Phi_k = phi(K), phi(x) = elu(x) + 1, elementwise.
+ *   Phi_q = phi(Q), Phi_k = phi(K), phi(x) = elu(x) + 1 (or max(x, 0), see linattn_phi), elementwise.
  *   Y_t   = ( Phi_q[t]^T S_t ) / ( Phi_q[t] . z_t + eps )
  *   S_t   = S_in + sum_{i<=t} Phi_k[i] V[i]^T      (d x d)
  *   z_t   = z_in + sum_{i<=t} Phi_k[i]             (d)
@@ -68,7 +68,10 @@ typedef enum {
 } linattn_status;
 
 typedef enum { LINATTN_F32 = 0, LINATTN_BF16 = 1 } linattn_dtype;
-typedef enum { LINATTN_PHI_ELU1 = 0 } linattn_phi;
+/* Feature map on Q and K (Sec. 3: "kernel embeddings").  ELU1: phi(x) = elu(x) + 1, the default of
+ * every workload here.  RELU: phi(x) = max(x, 0), the ReLU linear attention the paper lists among the
+ * existing ones (Sec. 3, "Comprehensive Evaluation"); its denominator can vanish, so pass eps > 0. */
+typedef enum { LINATTN_PHI_ELU1 = 0, LINATTN_PHI_RELU = 1 } linattn_phi;
 
 #define LINATTN_MAX_CONV_K 8   /* taps t, t-1, ..., t-Kc+1                              */
 #define LINATTN_MAX_DRAFT 16   /* draft tokens per verify call                          */

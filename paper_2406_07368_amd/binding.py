@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "liblinattn.so")
 _lib = None
 
 LINATTN_F32, LINATTN_BF16 = 0, 1
-LINATTN_PHI_ELU1 = 0
+LINATTN_PHI_ELU1, LINATTN_PHI_RELU = 0, 1
+PHI = {"elu1": LINATTN_PHI_ELU1, "relu": LINATTN_PHI_RELU}
 MAX_CONV_K, MAX_DRAFT, MAX_TREE = 8, 16, 64
 SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_verify", "linattn_verify_tree", "linattn_decode",
            "linattn_status_string", "linattn_version")
@@ -90,13 +91,13 @@ def _check(status: int, where: str):
         raise LinattnError(status, where)
 
 
-def make_desc(B, H, d, conv_k, chunk=64, io_dtype=torch.bfloat16, eps=0.0, strides=None, L=None) -> Desc:
-    """Descriptor for dense [B,H,L,d] tensors unless ``strides`` (b, h, t) is given."""
+def make_desc(B, H, d, conv_k, chunk=64, io_dtype=torch.bfloat16, eps=0.0, strides=None, L=None, phi="elu1") -> Desc:
+    """Descriptor for dense [B,H,L,d] tensors unless ``strides`` (b, h, t) is given.  phi: "elu1" or "relu"."""
     code = {torch.float32: LINATTN_F32, torch.bfloat16: LINATTN_BF16}[io_dtype]
     if strides is None:
         Lx = 0 if L is None else int(L)
         strides = (H * Lx * d, Lx * d, d)
-    return Desc(B, H, d, conv_k, chunk, code, LINATTN_PHI_ELU1, float(eps), *[int(s) for s in strides])
+    return Desc(B, H, d, conv_k, chunk, code, PHI[phi], float(eps), *[int(s) for s in strides])
 
 
 def linattn_workspace_bytes(desc: Desc, L: int) -> int:
@@ -132,19 +133,19 @@ def linattn_decode(desc: Desc, q, k, v, conv_w, S, z, hist, out, stream=None) ->
 
 
 # ---- conveniences that only allocate with torch and forward to the calls above ---------------
-def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, stream=None):
+def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, stream=None, phi="elu1"):
     """q, k, v: [B,H,L,d] CUDA tensors (fp32 or bf16), dense or any view with unit stride along d
     and equal strides for the three (e.g. ``x.transpose(1, 2)`` of a token-major [B,L,H,d] tensor);
     ``out`` gets the same strides.  Returns out, (S, z, hist)."""
     B, H, L, d = q.shape
     Kc = conv_w.shape[2]
     if q.is_contiguous() and k.is_contiguous() and v.is_contiguous():
-        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, L=L)
+        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, L=L, phi=phi)
         out = torch.empty_like(q)
     else:
         if q.stride(3) != 1 or k.stride() != q.stride() or v.stride() != q.stride():
             raise ValueError("q, k, v must share their strides and be contiguous along d")
-        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, strides=q.stride()[:3])
+        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, strides=q.stride()[:3], phi=phi)
         out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     S_in, z_in, h_in = state if state is not None else (None, None, None)
     S = z = h = None
@@ -158,31 +159,31 @@ def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, str
     return out, (S, z, h)
 
 
-def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None):
+def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None, phi="elu1"):
     """q, k, v: dense [B,H,kk,d].  ``state`` = (S, z, hist) is updated in place.  Returns out."""
     B, H, kk, d = q.shape
-    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=kk)
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=kk, phi=phi)
     out = torch.empty_like(q)
     S, z, h = state
     linattn_verify(desc, kk, q, k, v, conv_w, S, z, h, n_commit, out, stream)
     return out
 
 
-def verify_tree(q, k, v, parent, conv_w, state, accept=None, eps=0.0, stream=None):
+def verify_tree(q, k, v, parent, conv_w, state, accept=None, eps=0.0, stream=None, phi="elu1"):
     """q, k, v: dense bf16 [B,H,n,d]; parent: int32 [n] on the GPU.  ``state`` is updated in place along the
     root path of candidate ``accept[b]`` (int32 [B] on the GPU; None accepts nothing).  Returns out."""
     B, H, n, d = q.shape
-    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=n)
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=n, phi=phi)
     out = torch.empty_like(q)
     S, z, h = state
     linattn_verify_tree(desc, n, q, k, v, parent, conv_w, S, z, h, accept, out, stream)
     return out
 
 
-def decode(q, k, v, conv_w, state, eps=0.0, stream=None):
+def decode(q, k, v, conv_w, state, eps=0.0, stream=None, phi="elu1"):
     """q, k, v: dense [B,H,d] (or [B,H,1,d]).  ``state`` is updated in place.  Returns out."""
     B, H, d = q.shape[0], q.shape[1], q.shape[-1]
-    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=1)
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=1, phi=phi)
     out = torch.empty_like(q)
     S, z, h = state
     linattn_decode(desc, q, k, v, conv_w, S, z, h, out, stream)

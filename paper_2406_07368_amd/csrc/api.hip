@@ -15,7 +15,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 linattn_status check_desc(const linattn_desc* d, bool prefill) {
   if (!d) return LINATTN_ERR_NULL;
   if (d->io_dtype != LINATTN_F32 && d->io_dtype != LINATTN_BF16) return LINATTN_ERR_DTYPE;
-  if (d->phi != LINATTN_PHI_ELU1) return LINATTN_ERR_DTYPE;
+  if (d->phi != LINATTN_PHI_ELU1 && d->phi != LINATTN_PHI_RELU) return LINATTN_ERR_DTYPE;
   if (d->B < 1 || d->H < 1) return LINATTN_ERR_SHAPE;
   if ((int64_t)d->B * d->H > (int64_t)1 << 24) return LINATTN_ERR_SHAPE;
   if (d->d != 64 && d->d != 128) return LINATTN_ERR_SHAPE;
@@ -108,7 +108,7 @@ linattn_status linattn_prefill(const linattn_desc* desc, int32_t L, const void* 
   a.S_in = S_in; a.z_in = z_in; a.hist_in = has_hist ? hist_in : nullptr;
   a.out = out; a.S_out = S_out; a.z_out = z_out; a.hist_out = has_hist ? hist_out : nullptr;
   a.ws = static_cast<float*>(workspace);
-  a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = desc->conv_k; a.eps = desc->eps;
+  a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
   a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
   a.nseg = plan.nseg; a.seg_len = plan.seg_len;
   hipError_t e;
@@ -133,7 +133,7 @@ linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* 
   VerifyArgs a{};
   a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;
   a.n_commit = n_commit; a.out = out;
-  a.B = desc->B; a.H = desc->H; a.kk = kk; a.Kc = desc->conv_k; a.eps = desc->eps;
+  a.B = desc->B; a.H = desc->H; a.kk = kk; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
   const int nsplit = verify_pick_split(desc->B * desc->H);
   const bool bf16 = desc->io_dtype == LINATTN_BF16;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -159,7 +159,7 @@ linattn_status linattn_verify_tree(const linattn_desc* desc, int32_t n, const vo
   VerifyTreeArgs a{};
   a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;
   a.parent = parent; a.accept = accept; a.out = out;
-  a.B = desc->B; a.H = desc->H; a.n = n; a.Kc = desc->conv_k; a.eps = desc->eps;
+  a.B = desc->B; a.H = desc->H; a.n = n; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
   const hipError_t e = launch_verify_tree(a, desc->d, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }

@@ -26,6 +26,9 @@ __device__ __forceinline__ float phi_elu1_fast(float x) {
   return fmaxf(x, 0.f) + fminf(e, 1.f);
 }
 
+// Either feature map; `relu` is uniform over a launch.
+__device__ __forceinline__ float phi_any(float x, int relu) { return relu ? fmaxf(x, 0.f) : phi_elu1(x); }
+
 __device__ __forceinline__ float bf16_lo_to_f32(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi_to_f32(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }

@@ -18,6 +18,7 @@ struct VerifyArgs {
   void* out;                // [B,H,kk,d]
   int B, H, kk, Kc;
   float eps;
+  int relu;                 // feature map: 0 = elu + 1, 1 = max(x, 0)
 };
 
 struct VerifyTreeArgs {
@@ -33,6 +34,7 @@ struct VerifyTreeArgs {
   void* out;                // [B,H,n,d]
   int B, H, n, Kc;
   float eps;
+  int relu;
 };
 
 struct PrefillArgs {
@@ -50,6 +52,7 @@ struct PrefillArgs {
   float* ws;                // [B*H][nseg][d*d + d] floats (segment start states), then staged history rows
   int B, H, L, Kc;
   float eps;
+  int relu;                 // feature map: 0 = elu + 1, 1 = max(x, 0)
   int64_t sb, sh, st;       // element strides of q, k, v, out
   int nseg;                 // workgroups along the sequence axis per (b, h)
   int seg_len;              // tokens per segment (multiple of the chunk size)

@@ -52,4 +52,7 @@ __device__ __forceinline__ float phi_elu1_max(float x) {
   return fmaxf(x + 1.f, e);
 }
 
+// Either feature map for the matrix-core kernels' LDS fill; `relu` is uniform over a launch.
+__device__ __forceinline__ float phi_any_max(float x, int relu) { return relu ? fmaxf(x, 0.f) : phi_elu1_max(x); }
+
 }  // namespace linattn

@@ -179,21 +179,33 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     };
     // feature map on the 16 rows held in registers, then to buffer bi.  PARTIAL: rows >= nt become
     // zero rows (phi(0) = 1, so they are cleared after the map).
-    auto fill_pass = [&](int bi, int p, int nt, auto set_tag, auto partial_tag) __attribute__((always_inline)) {
+    auto fill_pass = [&](int bi, int p, int nt, auto set_tag, auto partial_tag, auto relu_tag) __attribute__((always_inline)) {
       constexpr int SET = decltype(set_tag)::value;
       constexpr bool PARTIAL = decltype(partial_tag)::value;
       const int t = 16 * p + r16;
       const bool ok = !PARTIAL || t < nt;
       u32x4 kp, qp, vp = rv[SET][p];
+      if (!decltype(relu_tag)::value) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float k0 = phi_elu1_max(bf16_lo_to_f32(rk[SET][p][i])), k1 = phi_elu1_max(bf16_hi_to_f32(rk[SET][p][i]));
-        kp[i] = pack_bf16x2(k0, k1);
-        if (PARTIAL) { kp[i] = ok ? kp[i] : 0u; vp[i] = ok ? vp[i] : 0u; }
-        if (!STATE_ONLY) {
-          const float q0 = phi_elu1_max(bf16_lo_to_f32(rq[SET][p][i])), q1 = phi_elu1_max(bf16_hi_to_f32(rq[SET][p][i]));
-          qp[i] = pack_bf16x2(q0, q1);
-          if (PARTIAL) qp[i] = ok ? qp[i] : 0u;
+        for (int i = 0; i < 4; ++i) {
+          kp[i] = pack_bf16x2(phi_elu1_max(bf16_lo_to_f32(rk[SET][p][i])), phi_elu1_max(bf16_hi_to_f32(rk[SET][p][i])));
+          if (!STATE_ONLY)
+            qp[i] = pack_bf16x2(phi_elu1_max(bf16_lo_to_f32(rq[SET][p][i])), phi_elu1_max(bf16_hi_to_f32(rq[SET][p][i])));
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          kp[i] = pack_bf16x2(fmaxf(bf16_lo_to_f32(rk[SET][p][i]), 0.f), fmaxf(bf16_hi_to_f32(rk[SET][p][i]), 0.f));
+          if (!STATE_ONLY)
+            qp[i] = pack_bf16x2(fmaxf(bf16_lo_to_f32(rq[SET][p][i]), 0.f), fmaxf(bf16_hi_to_f32(rq[SET][p][i]), 0.f));
+        }
+      }
+      if (PARTIAL) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          kp[i] = ok ? kp[i] : 0u;
+          vp[i] = ok ? vp[i] : 0u;
+          if (!STATE_ONLY) qp[i] = ok ? qp[i] : 0u;
         }
       }
       *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
@@ -227,7 +239,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     // of group g + 2 is requested from HBM into the freed registers.  STORE: the finished output
     // rows of group g - 2 (always a full group) are written out half-way through, so that no HBM
     // request is younger than half a group when the next fill starts waiting for its rows.
-    auto fill_group = [&](int g, auto set_tag, auto store_tag) __attribute__((always_inline)) {
+    auto fill_group = [&](int g, auto set_tag, auto store_tag, auto relu_tag) __attribute__((always_inline)) {
       constexpr bool STORE = decltype(store_tag)::value;
       const int bi = g & 1;
       const int nt = (t_end - (t_begin + g * C)) < C ? (t_end - (t_begin + g * C)) : C;
@@ -236,8 +248,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
         if (!STATE_ONLY && STORE && p == G::NP / 2) store_group(g - 2, Full{});
-        if (!fill_part) fill_pass(bi, p, nt, set_tag, Full{});
-        else fill_pass(bi, p, nt, set_tag, Part{});
+        if (!fill_part) fill_pass(bi, p, nt, set_tag, Full{}, relu_tag);
+        else fill_pass(bi, p, nt, set_tag, Part{}, relu_tag);
         if (!load_part) load_pass(g + 2, p, set_tag, Full{});
         else load_pass(g + 2, p, set_tag, Part{});
       }
@@ -347,56 +359,62 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       }
       bufV(0)[r * G::VS + cc] = x;
     }
-    if (nchunks > 0) {
-#pragma unroll
-      for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{}, Part{});
-#pragma unroll
-      for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{}, Part{});
-      fill_group(0, Set0{}, std::false_type{});
-    }
-    __syncthreads();                                   // buffer 0 is full, z is in LDS
+    // The whole walk, once per feature map: the map is a property of the launch, and choosing it out here
+    // keeps the loop of either map free of selects and branches on it.
+    auto walk = [&](auto relu_tag) __attribute__((always_inline)) {
+      if (nchunks > 0) {
+  #pragma unroll
+        for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{}, Part{});
+  #pragma unroll
+        for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{}, Part{});
+        fill_group(0, Set0{}, std::false_type{}, relu_tag);
+      }
+      __syncthreads();                                   // buffer 0 is full, z is in LDS
 
-    // One step of the front end.  First the scores and phi(q).z of group ci, which the state waves
-    // need a little later (they start with the products that involve the state only); then, while
-    // the state waves work on group ci, group ci + 1 is filled, group ci + 3 requested and group
-    // ci - 1 stored.
-    auto step = [&](int ci, auto set_tag, auto store_tag) __attribute__((always_inline)) {
-      if (!STATE_ONLY) {
-        scores(ci);
-        q_dot_z(ci);
-        signal(sync_q);
-        // the last HALO value rows of group ci become the rows before group ci + 1
-        if (lt < HALO * D / 8) {
-          const int r = lt / (D / 8), piece = 8 * (lt % (D / 8));
-          const u32x2* src = reinterpret_cast<const u32x2*>(bufV(ci & 1) + (C + r) * G::VS + piece);
-          u32x2* dst = reinterpret_cast<u32x2*>(bufV((ci + 1) & 1) + r * G::VS + piece);
-          const u32x2 t0 = src[0], t1 = src[1];
-          dst[0] = t0; dst[1] = t1;
+      // One step of the front end.  First the scores and phi(q).z of group ci, which the state waves
+      // need a little later (they start with the products that involve the state only); then, while
+      // the state waves work on group ci, group ci + 1 is filled, group ci + 3 requested and group
+      // ci - 1 stored.
+      auto step = [&](int ci, auto set_tag, auto store_tag) __attribute__((always_inline)) {
+        if (!STATE_ONLY) {
+          scores(ci);
+          q_dot_z(ci);
+          signal(sync_q);
+          // the last HALO value rows of group ci become the rows before group ci + 1
+          if (lt < HALO * D / 8) {
+            const int r = lt / (D / 8), piece = 8 * (lt % (D / 8));
+            const u32x2* src = reinterpret_cast<const u32x2*>(bufV(ci & 1) + (C + r) * G::VS + piece);
+            u32x2* dst = reinterpret_cast<u32x2*>(bufV((ci + 1) & 1) + r * G::VS + piece);
+            const u32x2 t0 = src[0], t1 = src[1];
+            dst[0] = t0; dst[1] = t1;
+          }
         }
+        fill_group(ci + 1, set_tag, store_tag, relu_tag);
+        __syncthreads();                                 // barrier C
+      };
+      int ci = 0;
+      if (nchunks > 1) { step(0, Set1{}, std::false_type{}); ci = 1; }
+      for (; ci + 2 < nchunks; ci += 2) {                // ci is odd here: group ci + 1 is even
+        step(ci, Set0{}, std::true_type{});
+        step(ci + 1, Set1{}, std::true_type{});
       }
-      fill_group(ci + 1, set_tag, store_tag);
-      __syncthreads();                                 // barrier C
+      if (ci >= 1 && ci + 1 < nchunks) { step(ci, Set0{}, std::true_type{}); ++ci; }
+      if (nchunks > 0) {                                 // ci == nchunks - 1: nothing left to fill
+        if (!STATE_ONLY) {
+          scores(ci);
+          q_dot_z(ci);
+          signal(sync_q);
+          if (ci > 0) store_group(ci - 1, Full{});
+        }
+        __syncthreads();                                 // barrier C
+      }
+      if (!STATE_ONLY && nchunks > 0) {
+        if (last_partial) store_group(nchunks - 1, Part{});
+        else store_group(nchunks - 1, Full{});
+      }
     };
-    int ci = 0;
-    if (nchunks > 1) { step(0, Set1{}, std::false_type{}); ci = 1; }
-    for (; ci + 2 < nchunks; ci += 2) {                // ci is odd here: group ci + 1 is even
-      step(ci, Set0{}, std::true_type{});
-      step(ci + 1, Set1{}, std::true_type{});
-    }
-    if (ci >= 1 && ci + 1 < nchunks) { step(ci, Set0{}, std::true_type{}); ++ci; }
-    if (nchunks > 0) {                                 // ci == nchunks - 1: nothing left to fill
-      if (!STATE_ONLY) {
-        scores(ci);
-        q_dot_z(ci);
-        signal(sync_q);
-        if (ci > 0) store_group(ci - 1, Full{});
-      }
-      __syncthreads();                                 // barrier C
-    }
-    if (!STATE_ONLY && nchunks > 0) {
-      if (last_partial) store_group(nchunks - 1, Part{});
-      else store_group(nchunks - 1, Full{});
-    }
+    if (a.relu) walk(std::true_type{});
+    else walk(std::false_type{});
     return;
   }
 

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
         Io::load8(a.k, off, xk);
         Io::load8(a.v, off, xv);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { xq[e] = phi_elu1(xq[e]); xk[e] = phi_elu1(xk[e]); }
+        for (int e = 0; e < 8; ++e) { xq[e] = phi_any(xq[e], a.relu); xk[e] = phi_any(xk[e], a.relu); }
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) { xq[e] = 0.f; xk[e] = 0.f; xv[e] = 0.f; }

@@ -122,8 +122,8 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
     if (c8 < KP * (D / 8)) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        sm.fq[i0 + e][j] = j < kk ? phi_elu1(xq[m][e]) : 0.f;
-        sm.fk[i0 + e][j] = j < kk ? phi_elu1(xk[m][e]) : 0.f;
+        sm.fq[i0 + e][j] = j < kk ? phi_any(xq[m][e], a.relu) : 0.f;
+        sm.fk[i0 + e][j] = j < kk ? phi_any(xk[m][e], a.relu) : 0.f;
       }
     }
   }
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256) void verify_z_kernel(VerifyArgs a) {
   if (a.n_commit) { n = a.n_commit[b]; n = n < 0 ? 0 : (n > a.kk ? a.kk : n); }
   if (n == 0) return;
   float zs = a.z[gid];
-  for (int j = 0; j < n; ++j) zs += phi_elu1(Io::load1(a.k, ((int64_t)bh * a.kk + j) * D + i));
+  for (int j = 0; j < n; ++j) zs += phi_any(Io::load1(a.k, ((int64_t)bh * a.kk + j) * D + i), a.relu);
   a.z[gid] = zs;
 }
 

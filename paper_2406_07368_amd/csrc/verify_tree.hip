@@ -130,8 +130,8 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
     u32x4 qp, kp;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      qp[i] = pack_bf16x2(phi_elu1_max(bf16_lo_to_f32(rq[m][i])), phi_elu1_max(bf16_hi_to_f32(rq[m][i])));
-      kp[i] = pack_bf16x2(phi_elu1_max(bf16_lo_to_f32(rk[m][i])), phi_elu1_max(bf16_hi_to_f32(rk[m][i])));
+      qp[i] = pack_bf16x2(phi_any_max(bf16_lo_to_f32(rq[m][i]), a.relu), phi_any_max(bf16_hi_to_f32(rq[m][i]), a.relu));
+      kp[i] = pack_bf16x2(phi_any_max(bf16_lo_to_f32(rk[m][i]), a.relu), phi_any_max(bf16_hi_to_f32(rk[m][i]), a.relu));
       if (dj >= n) { qp[i] = 0u; kp[i] = 0u; }
     }
     u32x2* qrow = reinterpret_cast<u32x2*>(sm.q + dj * G::QS + di0);
