@@ -52,7 +52,18 @@ __device__ __forceinline__ float phi_elu1_max(float x) {
   return fmaxf(x + 1.f, e);
 }
 
-// Either feature map for the matrix-core kernels' LDS fill; `relu` is uniform over a launch.
-__device__ __forceinline__ float phi_any_max(float x, int relu) { return relu ? fmaxf(x, 0.f) : phi_elu1_max(x); }
+// phi on four packed bf16 pairs -> four packed bf16 pairs.  `relu` is uniform over a launch: one branch
+// per call, no select per element.
+__device__ __forceinline__ u32x4 phi_pack8(u32x4 x, int relu) {
+  u32x4 y;
+  if (!relu) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) y[i] = pack_bf16x2(phi_elu1_max(bf16_lo_to_f32(x[i])), phi_elu1_max(bf16_hi_to_f32(x[i])));
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) y[i] = pack_bf16x2(fmaxf(bf16_lo_to_f32(x[i]), 0.f), fmaxf(bf16_hi_to_f32(x[i]), 0.f));
+  }
+  return y;
+}
 
 }  // namespace linattn

@@ -109,13 +109,8 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
 
   // ---- drafts -> LDS: phi(Q), phi(K) as bf16 rows (rows >= kk are zero rows), V, history, z, taps --
   {
-    u32x4 qp, kp;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      qp[i] = pack_bf16x2(phi_any_max(bf16_lo_to_f32(rq[i]), a.relu), phi_any_max(bf16_hi_to_f32(rq[i]), a.relu));
-      kp[i] = pack_bf16x2(phi_any_max(bf16_lo_to_f32(rk[i]), a.relu), phi_any_max(bf16_hi_to_f32(rk[i]), a.relu));
-      if (dj >= kk) { qp[i] = 0u; kp[i] = 0u; }
-    }
+    u32x4 qp = phi_pack8(rq, a.relu), kp = phi_pack8(rk, a.relu);
+    if (dj >= kk) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; }
     u32x2* qrow = reinterpret_cast<u32x2*>(sm.q + dj * G::QS + di0);
     qrow[0] = u32x2{qp[0], qp[1]};
     qrow[1] = u32x2{qp[2], qp[3]};

@@ -127,13 +127,8 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   for (int m = 0; m < G::QP; ++m) {
     const int piece = tid + G::NT * m;
     const int dj = piece / (D / 8), di0 = 8 * (piece % (D / 8));
-    u32x4 qp, kp;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      qp[i] = pack_bf16x2(phi_any_max(bf16_lo_to_f32(rq[m][i]), a.relu), phi_any_max(bf16_hi_to_f32(rq[m][i]), a.relu));
-      kp[i] = pack_bf16x2(phi_any_max(bf16_lo_to_f32(rk[m][i]), a.relu), phi_any_max(bf16_hi_to_f32(rk[m][i]), a.relu));
-      if (dj >= n) { qp[i] = 0u; kp[i] = 0u; }
-    }
+    u32x4 qp = phi_pack8(rq[m], a.relu), kp = phi_pack8(rk[m], a.relu);
+    if (dj >= n) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; }
     u32x2* qrow = reinterpret_cast<u32x2*>(sm.q + dj * G::QS + di0);
     qrow[0] = u32x2{qp[0], qp[1]};
     qrow[1] = u32x2{qp[2], qp[3]};
