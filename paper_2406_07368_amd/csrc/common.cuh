@@ -20,12 +20,6 @@ constexpr int kWave = 64;
 // phi(x) = elu(x) + 1 (Sec. 3: kernel embedding of queries and keys; elu+1 is
 // the embedding of the kernelised attention the paper builds on).
 __device__ __forceinline__ float phi_elu1(float x) { return x > 0.f ? x + 1.f : __expf(x); }
-// Same value, branch-free: max(x,0) + min(2^(x*log2 e), 1).
-__device__ __forceinline__ float phi_elu1_fast(float x) {
-  float e = __builtin_amdgcn_exp2f(x * 1.44269504088896340736f);
-  return fmaxf(x, 0.f) + fminf(e, 1.f);
-}
-
 // Either feature map; `relu` is uniform over a launch.
 __device__ __forceinline__ float phi_any(float x, int relu) { return relu ? fmaxf(x, 0.f) : phi_elu1(x); }
 
