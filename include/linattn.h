@@ -87,7 +87,7 @@ typedef struct {
   int32_t phi;             /* linattn_phi                                               */
   float eps;               /* added to every denominator; >= 0                          */
   int64_t stride_b, stride_h, stride_t; /* element strides of q, k, v, out: multiples of
-                              8, stride_t >= d and <= 2^24                           */
+                              8, stride_t >= d and <= 2^22                           */
 } linattn_desc;
 
 /* Bytes of device scratch `linattn_prefill` needs for this descriptor and L

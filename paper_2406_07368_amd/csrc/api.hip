@@ -25,7 +25,7 @@ linattn_status check_desc(const linattn_desc* d, bool prefill) {
     if (d->chunk != 64 && d->chunk != 128) return LINATTN_ERR_SHAPE;
     if (d->stride_t < d->d || d->stride_h < 0 || d->stride_b < 0) return LINATTN_ERR_SHAPE;
     if ((d->stride_t | d->stride_h | d->stride_b) & 7) return LINATTN_ERR_SHAPE;
-    if (d->stride_t > (int64_t)1 << 24) return LINATTN_ERR_SHAPE;   // the kernels index inside a group with 32 bits
+    if (d->stride_t > (int64_t)1 << 22) return LINATTN_ERR_SHAPE;   // the kernels index inside a group with 32 bits
   }
   return LINATTN_OK;
 }

@@ -55,7 +55,7 @@ def prefill_status(desc, L=256, **over):
 
 @pytest.mark.parametrize("field,value,status", [
     ("d", 96, 2), ("d", 0, 2), ("B", 0, 2), ("H", -1, 2), ("conv_k", 0, 2), ("conv_k", 9, 2),
-    ("chunk", 32, 2), ("stride_t", (1 << 24) + 8, 2), ("io_dtype", 7, 3), ("phi", 2, 3), ("eps", -1.0, 2), ("eps", float("nan"), 2),
+    ("chunk", 32, 2), ("stride_t", (1 << 22) + 8, 2), ("io_dtype", 7, 3), ("phi", 2, 3), ("eps", -1.0, 2), ("eps", float("nan"), 2),
     ("stride_t", 64, 2), ("stride_t", 132, 2), ("stride_h", 12, 2),
 ])
 def test_prefill_rejects_bad_descriptor(field, value, status):
