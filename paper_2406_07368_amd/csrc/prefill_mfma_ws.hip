@@ -363,9 +363,9 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     // keeps the loop of either map free of selects and branches on it.
     auto walk = [&](auto relu_tag) __attribute__((always_inline)) {
       if (nchunks > 0) {
-  #pragma unroll
+#pragma unroll
         for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{}, Part{});
-  #pragma unroll
+#pragma unroll
         for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{}, Part{});
         fill_group(0, Set0{}, std::false_type{}, relu_tag);
       }
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   };
   if (!STATE_ONLY) publish_z();
 
-  __syncthreads();                                     // buffer 0 is full, its scores and the conv taps are in LDS
+  __syncthreads();                                     // buffer 0 is full, the conv taps and z are in LDS
 
   // conv taps of this lane's 16 output channels (32w + 8g + 4hi + e), kept in registers when few
   constexpr bool W_REGS = KCM <= 3 && D == 64;   // D = 128: the registers do not suffice
