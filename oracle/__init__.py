@@ -55,6 +55,8 @@ def _declare(lib):
         fn = getattr(lib, name)
         fn.restype = i
         fn.argtypes = [i, i, i, i, i, f] + [_dp] * 11
+    lib.oracle_prefill_grouped.restype = i
+    lib.oracle_prefill_grouped.argtypes = [i, i, i, i, i, i, f, f] + [_dp] * 11
     lib.oracle_verify.restype = i
     lib.oracle_verify.argtypes = [i, i, i, i, i, f] + [_dp] * 7 + [_ip, _dp]
     lib.oracle_verify_tree.restype = i
@@ -158,6 +160,32 @@ def prefill_quadratic(q, k, v, w, S0=None, z0=None, hist0=None, eps=0.0, lib=Non
 def prefill_recurrent(q, k, v, w, S0=None, z0=None, hist0=None, eps=0.0, lib=None):
     """Token-by-token recurrence.  Returns (out, S, z, hist)."""
     return _prefill("oracle_prefill_recurrent", q, k, v, w, S0, z0, hist0, eps, lib)
+
+
+def prefill_grouped(q, k, v, w, group, alpha=1.0, S0=None, z0=None, hist0=None, eps=0.0, lib=None):
+    """The three-branch form of Sec. 4.1: grouped linear attention over the groups before a token's own
+    (weight alpha) + causal softmax attention inside its group + masked conv.  group: tokens per group.
+    Returns (out, S, z, hist); the state is the same running sum as in the other forms."""
+    lib = lib or _load()
+    q = _c(q)
+    B, H, L, d = q.shape
+    k = _c(k, q.shape)
+    v = _c(v, q.shape)
+    w = _c(w)
+    Kc = w.shape[2]
+    w = _c(w, (H, d, Kc))
+    S0 = _c(S0, (B, H, d, d)) if S0 is not None else None
+    z0 = _c(z0, (B, H, d)) if z0 is not None else None
+    hist0 = _c(hist0, (B, H, Kc - 1, d)) if hist0 is not None else None
+    out = np.empty_like(q)
+    S1 = np.empty((B, H, d, d))
+    z1 = np.empty((B, H, d))
+    h1 = np.empty((B, H, Kc - 1, d))
+    rc = lib.oracle_prefill_grouped(B, H, L, d, Kc, int(group), float(eps), float(alpha), _p(q), _p(k), _p(v), _p(w),
+                                    _p(S0), _p(z0), _p(hist0), _p(out), _p(S1), _p(z1), _p(h1))
+    if rc != 0:
+        raise ValueError(f"oracle_prefill_grouped rejected its arguments (code {rc})")
+    return out, S1, z1, h1
 
 
 def verify(q, k, v, w, S, z, hist, n_commit=None, eps=0.0, lib=None):

@@ -44,7 +44,10 @@
  * K == 0, weighted running mean for Q == 0 and for d == 1, constant V,
  * linearity in V, exact rational brute force on a tiny case, conv against a
  * library grouped convolution, the paper's conv-window example, causality
- * under perturbation, chunk/split invariance, verify == k decode steps.
+ * under perturbation, chunk/split invariance, verify == k decode steps; for the
+ * grouped form of Sec. 4.1: one group = a library softmax attention, one-token groups =
+ * the token-level form shifted by one token, a closed-form example, shift invariance
+ * of the logits, the weight alpha, splits at group boundaries, causality.
  * No function here is "parity unpinned" with respect to those properties; the
  * paper prints no numeric output of the operator, so there is no printed
  * value to compare with.
@@ -255,6 +258,97 @@ int oracle_prefill_recurrent(int B, int H, int L, int d, int Kc, double eps,
     if (z1) memcpy(z1 + (size_t)bh * d, z, sizeof(double) * d);
     if (hist1) memcpy(hist1 + bh * nh, hs, sizeof(double) * nh);
     free(S); free(z); free(hs);
+  }
+  return 0;
+}
+
+/* ---- the augmented attention of Sec. 4.1 as the text states it, one head ----
+ * The sequence is cut into consecutive groups of C tokens (the last one may be
+ * short).  Three branches are summed for every token t of a group:
+ *   grouped linear attention: the query meets the key/value sums of the groups
+ *     BEFORE its own (plus whatever state came in); nothing of its own group --
+ *     the sums advance once per group, not once per token:
+ *         G_t = phi(q_t)^T S / (phi(q_t).z + eps),   S, z as they stood before the group;
+ *   local attention: softmax attention (Sec. 3, Eq. 1: logits q.k / sqrt(d)) over
+ *     the tokens of its own group that are not later than t (the model is
+ *     autoregressive; a token never sees a later one):
+ *         A_t = sum_i softmax_i(q_t.k_i / sqrt(d)) v_i,  i in the group, i <= t;
+ *   masked depthwise convolution of V, as in the other forms:  U_t.
+ *   out_t = alpha * G_t + A_t + U_t   (alpha weighs the grouped against the local branch).
+ * A grouped branch whose denominator is exactly zero (no token and no state before
+ * the group, eps = 0) contributes nothing.  The state handed back is the same running
+ * sum over all L tokens as in the other forms. */
+static void grouped_head(int L, int d, int Kc, int C, double eps, double alpha,
+                         const double *q, const double *k, const double *v,
+                         const double *w, const double *S0, const double *z0,
+                         const double *hist0, double *out, double *S1,
+                         double *z1, double *hist1) {
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d;
+  double *S = (double *)malloc(sizeof(double) * nS);
+  double *z = (double *)malloc(sizeof(double) * (size_t)d);
+  double *hs = (double *)malloc(sizeof(double) * (nh ? nh : 1));
+  double *u = (double *)malloc(sizeof(double) * ((size_t)L * d + 1));
+  double *fq = (double *)malloc(sizeof(double) * (size_t)d);
+  double *logit = (double *)malloc(sizeof(double) * (size_t)(C > 0 ? C : 1));
+  load_state(d, Kc, S0, z0, hist0, S, z, hs);
+  conv_head(L, d, Kc, v, w, hist0, u);
+  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  for (int g0 = 0; g0 < L; g0 += C) {
+    int g1 = g0 + C < L ? g0 + C : L;
+    for (int t = g0; t < g1; ++t) {
+      const double *qt = q + (size_t)t * d;
+      for (int i = 0; i < d; ++i) fq[i] = oracle_phi(qt[i]);
+      /* grouped branch: S and z have not seen any token of this group */
+      double gden = dot(fq, z, d) + eps;
+      /* local branch: logits of the group's tokens up to t, largest one taken out first */
+      double top = -INFINITY;
+      for (int i = g0; i <= t; ++i) {
+        logit[i - g0] = dot(qt, k + (size_t)i * d, d) * inv_sqrt_d;
+        if (logit[i - g0] > top) top = logit[i - g0];
+      }
+      double mass = 0.0;
+      for (int i = g0; i <= t; ++i) {
+        logit[i - g0] = exp(logit[i - g0] - top);
+        mass += logit[i - g0];
+      }
+      for (int c = 0; c < d; ++c) {
+        double gnum = 0.0, loc = 0.0;
+        for (int i = 0; i < d; ++i) gnum += fq[i] * S[(size_t)i * d + c];
+        for (int i = g0; i <= t; ++i) loc += logit[i - g0] * v[(size_t)i * d + c];
+        double glob = gden != 0.0 ? gnum / gden : 0.0;
+        out[(size_t)t * d + c] = alpha * glob + loc / mass + u[(size_t)t * d + c];
+      }
+    }
+    /* only now do the group's keys and values enter the sums */
+    for (int t = g0; t < g1; ++t)
+      for (int i = 0; i < d; ++i) {
+        double fk = oracle_phi(k[(size_t)t * d + i]);
+        z[i] += fk;
+        for (int c = 0; c < d; ++c) S[(size_t)i * d + c] += fk * v[(size_t)t * d + c];
+      }
+  }
+  if (S1) memcpy(S1, S, sizeof(double) * nS);
+  if (z1) memcpy(z1, z, sizeof(double) * (size_t)d);
+  if (hist1) hist_after(L, d, Kc, v, hist0, hist1);
+  free(S); free(z); free(hs); free(u); free(fq); free(logit);
+}
+
+int oracle_prefill_grouped(int B, int H, int L, int d, int Kc, int C, double eps,
+                           double alpha, const double *q, const double *k,
+                           const double *v, const double *w, const double *S0,
+                           const double *z0, const double *hist0, double *out,
+                           double *S1, double *z1, double *hist1) {
+  if (B < 0 || H < 1 || L < 0 || d < 1 || Kc < 1 || C < 1) return 1;
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d;
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    int h = bh % H;
+    size_t o = (size_t)bh * L * d;
+    grouped_head(L, d, Kc, C, eps, alpha, q + o, k + o, v + o,
+                 w + (size_t)h * d * Kc, S0 ? S0 + bh * nS : NULL,
+                 z0 ? z0 + (size_t)bh * d : NULL, hist0 ? hist0 + bh * nh : NULL,
+                 out + o, S1 ? S1 + bh * nS : NULL, z1 ? z1 + (size_t)bh * d : NULL,
+                 hist1 ? hist1 + bh * nh : NULL);
   }
   return 0;
 }

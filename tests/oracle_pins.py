@@ -579,4 +579,139 @@ def pin_tree_without_acceptance_leaves_the_state(lib=None):
         assert np.array_equal(got[1], S) and np.array_equal(got[2], z) and np.array_equal(got[3], hist)
 
 
+# --- the grouped (three-branch) form of Sec. 4.1 -------------------------------
+def pin_grouped_single_group_is_library_softmax_attention(lib=None):
+    """One group covering the sequence, no state: nothing precedes the group, so what is left is causal
+    softmax attention with logits q.k/sqrt(d) (Eq. 1) -- a library routine -- plus the conv."""
+    q, k, v, w = _rand(401, B=2, H=2, L=13, d=5, Kc=3)
+    for group in (13, 64):
+        got = oracle.prefill_grouped(q, k, v, w, group, alpha=0.7, lib=lib)[0]
+        tq, tk, tv = (torch.from_numpy(a) for a in (q, k, v))
+        want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True).numpy()
+        _close(got, want + oracle.causal_conv(v, w), 1e-12, "one group vs library softmax attention")
+
+
+def pin_grouped_one_token_groups_are_the_token_level_form_shifted(lib=None):
+    """Groups of one token: the local branch is the token's own value (a softmax over one logit) and the
+    grouped branch is linear attention over the strictly earlier tokens.  The latter is the token-level
+    oracle run on keys and values moved one step later, the vacated first slot cancelled through the
+    incoming normaliser (phi(0) = 1 per feature, value 0)."""
+    q, k, v, w = _rand(402, B=1, H=2, L=9, d=4, Kc=3)
+    eps = 0.3
+    ks, vs = np.zeros_like(k), np.zeros_like(v)
+    ks[:, :, 1:], vs[:, :, 1:] = k[:, :, :-1], v[:, :, :-1]
+    B, H, L, d = q.shape
+    w0 = np.zeros_like(w)
+    earlier = oracle.prefill_recurrent(q, ks, vs, w0, S0=np.zeros((B, H, d, d)), z0=-np.ones((B, H, d)),
+                                       hist0=np.zeros((B, H, 2, d)), eps=eps)[0]
+    got = oracle.prefill_grouped(q, k, v, w, 1, alpha=1.0, eps=eps, lib=lib)[0]
+    _close(got, earlier + v + oracle.causal_conv(v, w), 1e-12, "one-token groups")
+
+
+def pin_grouped_closed_form_example(lib=None):
+    """d = 1, Q = K = 0: every logit is 0 (uniform local weights) and phi = 1 (uniform linear weights), so
+    the local branch is the mean of the group's values so far and the grouped branch the mean over all
+    earlier groups.  Groups of 2, alpha = 2, taps (current, one back) = (1, 10), history 1:
+        v      =  2   4   6  10   20
+        local  =  2   3   6   8   20
+        grouped=  -   -   3   3   5.5      (x alpha)
+        conv   = 12  24  46  70  120
+    """
+    v = np.array([2.0, 4.0, 6.0, 10.0, 20.0]).reshape(1, 1, 5, 1)
+    zero = np.zeros_like(v)
+    w = np.array([1.0, 10.0]).reshape(1, 1, 2)
+    got = oracle.prefill_grouped(zero, zero, v, w, 2, alpha=2.0, hist0=np.ones((1, 1, 1, 1)), lib=lib)
+    _close(got[0].ravel(), [14.0, 27.0, 58.0, 84.0, 151.0], 1e-13, "closed-form example")
+    _close(got[1].ravel(), [42.0], 1e-13, "S = sum of values (phi = 1)")
+    _close(got[2].ravel(), [5.0], 1e-13, "z = number of tokens")
+
+
+def pin_grouped_logit_scale(lib=None):
+    """d = 4, two tokens, q_1.k_1 = 2 ln 3 and q_1.k_0 = 0: with logits divided by sqrt(d) = 2 the local
+    weights of token 1 are (1/4, 3/4)."""
+    q = np.zeros((1, 1, 2, 4)); k = np.zeros((1, 1, 2, 4))
+    q[0, 0, 1, 0] = 2.0
+    k[0, 0, 1, 0] = math.log(3.0)
+    v = _rng(403).standard_normal((1, 1, 2, 4))
+    got = oracle.prefill_grouped(q, k, v, np.zeros((1, 4, 1)), 2, alpha=0.0, lib=lib)[0]
+    _close(got[0, 0, 0], v[0, 0, 0], 1e-14, "first token")
+    _close(got[0, 0, 1], 0.25 * v[0, 0, 0] + 0.75 * v[0, 0, 1], 1e-14, "second token")
+
+
+def pin_grouped_local_weights_ignore_a_common_logit_shift(lib=None):
+    """Adding one vector to every key moves all logits of a query by the same amount: the local branch
+    (alpha = 0 isolates it) does not change, however large the shift."""
+    q, k, v, w = _rand(404, B=1, H=2, L=11, d=4, Kc=2)
+    base = oracle.prefill_grouped(q, k, v, w, 4, alpha=0.0, lib=lib)[0]
+    for shift in (0.5, 400.0):
+        moved = oracle.prefill_grouped(q, k + shift * np.array([1.0, -2.0, 0.5, 3.0]), v, w, 4, alpha=0.0, lib=lib)[0]
+        assert np.all(np.isfinite(moved)), "overflow in the local weights"
+        _close(moved, base, 1e-9, f"shift {shift}")
+
+
+def pin_grouped_alpha_weighs_the_grouped_branch_only(lib=None):
+    """out is affine in alpha; the alpha-part is absent in the first group (nothing before it) and, in
+    any group, does not depend on keys and values of that group."""
+    q, k, v, w = _rand(405, B=1, H=2, L=12, d=3, Kc=3)
+    o0, o1, o25 = (oracle.prefill_grouped(q, k, v, w, 4, alpha=a, lib=lib)[0] for a in (0.0, 1.0, 2.5))
+    g = o1 - o0
+    _close(o25 - o0, 2.5 * g, 1e-12, "affine in alpha")
+    assert np.array_equal(o1[:, :, :4], o0[:, :, :4]), "first group has a grouped part"
+    assert np.max(np.abs(g[:, :, 4:])) > 1e-3, "no grouped part after the first group"
+    k2, v2 = k.copy(), v.copy()
+    k2[:, :, 8:10] += 1.0
+    v2[:, :, 8:10] -= 2.0
+    p0, p1 = (oracle.prefill_grouped(q, k2, v2, w, 4, alpha=a, lib=lib)[0] for a in (0.0, 1.0))
+    _close((p1 - p0)[:, :, 8:], g[:, :, 8:], 1e-12, "grouped part sees its own group")
+    assert np.max(np.abs(p0[:, :, 9:] - o0[:, :, 9:])) > 1e-3, "local part does not see its own group"
+
+
+def pin_grouped_split_at_a_group_boundary(lib=None):
+    """Everything before a group boundary reaches later tokens through (S, z, hist) alone."""
+    q, k, v, w, S0, z0, h0 = _rand(406, B=2, H=2, L=14, d=4, Kc=3, with_state=True)
+    whole = oracle.prefill_grouped(q, k, v, w, 3, alpha=1.3, S0=S0, z0=z0, hist0=h0, eps=1e-3, lib=lib)
+    cut = 6
+    a = oracle.prefill_grouped(q[:, :, :cut], k[:, :, :cut], v[:, :, :cut], w, 3, alpha=1.3, S0=S0, z0=z0, hist0=h0, eps=1e-3, lib=lib)
+    b = oracle.prefill_grouped(q[:, :, cut:], k[:, :, cut:], v[:, :, cut:], w, 3, alpha=1.3, S0=a[1], z0=a[2], hist0=a[3], eps=1e-3, lib=lib)
+    _close(np.concatenate([a[0], b[0]], axis=2), whole[0], 1e-12, "outputs")
+    for i, name in ((1, "S"), (2, "z"), (3, "hist")):
+        _close(b[i], whole[i], 1e-12, name)
+
+
+def pin_grouped_no_leak_and_long_memory(lib=None):
+    """A later token never changes an earlier output (bit for bit); a token of the first group still
+    reaches the last one (through the grouped branch)."""
+    q, k, v, w = _rand(407, B=1, H=1, L=10, d=3, Kc=2)
+    base = oracle.prefill_grouped(q, k, v, w, 4, alpha=1.0, lib=lib)[0]
+    for j in (1, 4, 7, 9):
+        q2, k2, v2 = q.copy(), k.copy(), v.copy()
+        q2[:, :, j] += 1.0; k2[:, :, j] -= 1.0; v2[:, :, j] += 3.0
+        o = oracle.prefill_grouped(q2, k2, v2, w, 4, alpha=1.0, lib=lib)[0]
+        assert np.array_equal(o[:, :, :j], base[:, :, :j]), f"token {j} leaked backwards"
+    v2 = v.copy(); v2[:, :, 0] += 5.0
+    o = oracle.prefill_grouped(q, k, v2, w, 4, alpha=1.0, lib=lib)[0]
+    assert np.max(np.abs(o[:, :, 9] - base[:, :, 9])) > 1e-3, "the first token is forgotten"
+
+
+def pin_grouped_state_is_the_same_running_sum(lib=None):
+    """The state handed back does not depend on the grouping: it is the token-level form's."""
+    q, k, v, w, S0, z0, h0 = _rand(408, B=1, H=2, L=11, d=4, Kc=4, with_state=True)
+    want = oracle.prefill_recurrent(q, k, v, w, S0=S0, z0=z0, hist0=h0)
+    for group in (1, 4, 64):
+        got = oracle.prefill_grouped(q, k, v, w, group, S0=S0, z0=z0, hist0=h0, lib=lib)
+        for i, name in ((1, "S"), (2, "z"), (3, "hist")):
+            _close(got[i], want[i], 1e-12, f"{name}, groups of {group}")
+
+
+def pin_grouped_feature_map_touches_the_linear_branch_only(lib=None):
+    """The feature map belongs to the linear branch: with alpha = 0 the output is the same under either
+    map, while the state follows the map."""
+    q, k, v, w = _rand(409, B=1, H=1, L=9, d=3, Kc=2)
+    base = oracle.prefill_grouped(q, k, v, w, 4, alpha=0.0, lib=lib)
+    with oracle.feature_map("relu", lib=lib):
+        other = oracle.prefill_grouped(q, k, v, w, 4, alpha=0.0, lib=lib)
+    _close(other[0], base[0], 1e-13, "local + conv under the other map")
+    _close(other[1], np.einsum("bhti,bhtc->bhic", np.maximum(k, 0.0), v), 1e-12, "state under max(x, 0)")
+
+
 ALL_PINS = [obj for name, obj in sorted(globals().items()) if name.startswith("pin_") and callable(obj)]

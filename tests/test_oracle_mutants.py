@@ -60,6 +60,23 @@ MUTANTS = [
     ("tree_commit_skips_the_root", "for (int m = len - 1; m >= 0; --m) { /* oldest first */", "for (int m = len - 2; m >= 0; --m) {"),
     ("tree_accept_per_head", "int acc_node = accept ? accept[b] : -1;", "int acc_node = accept ? accept[h % B] : -1; (void)b;"),
     ("tree_uses_raw_k", "fk[e] = oracle_phi(kh[e]);", "fk[e] = kh[e];"),
+    ("grouped_local_not_causal", "for (int i = g0; i <= t; ++i)", "for (int i = g0; i < g1; ++i)"),
+    ("grouped_logit_scale_dropped", "dot(qt, k + (size_t)i * d, d) * inv_sqrt_d;", "dot(qt, k + (size_t)i * d, d);"),
+    ("grouped_logit_scale_is_1_over_d", "const double inv_sqrt_d = 1.0 / sqrt((double)d);", "const double inv_sqrt_d = 1.0 / (double)d;"),
+    ("grouped_largest_logit_not_taken_out", "logit[i - g0] = exp(logit[i - g0] - top);", "logit[i - g0] = exp(logit[i - g0]);"),
+    ("grouped_alpha_on_the_local_branch", "alpha * glob + loc / mass", "glob + alpha * loc / mass"),
+    ("grouped_local_not_normalised", "alpha * glob + loc / mass", "alpha * glob + loc"),
+    ("grouped_sums_skip_a_groups_first_token", "for (int t = g0; t < g1; ++t)\n      for (int i = 0; i < d; ++i) {\n        double fk = oracle_phi(k[",
+     "for (int t = g0 + 1; t < g1; ++t)\n      for (int i = 0; i < d; ++i) {\n        double fk = oracle_phi(k["),
+    ("grouped_normaliser_counts_own_group", "double gden = dot(fq, z, d) + eps;",
+     "double gden = dot(fq, z, d) + eps; for (int i2 = g0; i2 < t; ++i2) for (int f = 0; f < d; ++f) gden += fq[f] * oracle_phi(k[(size_t)i2 * d + f]);"),
+    ("grouped_linear_branch_uses_raw_q", "fq[i] = oracle_phi(qt[i]);", "fq[i] = qt[i];"),
+    ("grouped_local_branch_uses_phi_q", "logit[i - g0] = dot(qt, k + (size_t)i * d, d) * inv_sqrt_d;", "logit[i - g0] = dot(fq, k + (size_t)i * d, d) * inv_sqrt_d;"),
+    ("grouped_eps_dropped", "double gden = dot(fq, z, d) + eps;", "double gden = dot(fq, z, d);"),
+    ("grouped_S_transposed", "gnum += fq[i] * S[(size_t)i * d + c];", "gnum += fq[i] * S[(size_t)c * d + i];"),
+    ("grouped_ignores_incoming_state", "load_state(d, Kc, S0, z0, hist0, S, z, hs);", "load_state(d, Kc, NULL, NULL, hist0, S, z, hs);"),
+    ("grouped_conv_dropped", "alpha * glob + loc / mass + u[(size_t)t * d + c];", "alpha * glob + loc / mass;"),
+    ("grouped_state_uses_raw_k", "double fk = oracle_phi(k[(size_t)t * d + i]);", "double fk = k[(size_t)t * d + i];"),
     ("recurrent_ignores_incoming_S", "load_state(d, Kc, S0 ? S0 + bh * nS : NULL, z0", "load_state(d, Kc, NULL, z0"),
 ]
 
