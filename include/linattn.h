@@ -119,6 +119,31 @@ linattn_status linattn_prefill(const linattn_desc *desc, int32_t L,
                                void *workspace, size_t workspace_bytes,
                                void *hip_stream);
 
+/* Prefill in the three-branch form of Sec. 4.1 (the text around the figure of the
+ * augmented attention): the sequence is cut into consecutive groups of `chunk`
+ * tokens, counted from the first token of the call, and every token gets
+ *   alpha * phi(q)^T S / (phi(q).z + eps)    with S, z as they stood BEFORE the
+ *                                            token's group (grouped linear attention:
+ *                                            the sums advance once per group; a
+ *                                            denominator of exactly 0 gives 0)
+ * + causal softmax attention over the tokens of its own group, logits
+ *   q.k / sqrt(d) on the raw rows (local attention)
+ * + the masked depthwise convolution of V, as in linattn_prefill.
+ * Unlike linattn_prefill the result depends on the group size.  Arguments,
+ * layouts, state handling, workspace and L as for linattn_prefill (same
+ * linattn_workspace_bytes); the state handed back is the same running sum.  To
+ * continue a sequence with the same grouping, cut it at multiples of `chunk`.
+ *   alpha        finite (LINATTN_ERR_SHAPE otherwise)
+ * io_dtype must be LINATTN_BF16 and chunk 64 (LINATTN_ERR_UNSUPPORTED otherwise). */
+linattn_status linattn_prefill_grouped(const linattn_desc *desc, int32_t L, float alpha,
+                                       const void *q, const void *k, const void *v,
+                                       const float *conv_w,
+                                       const float *S_in, const float *z_in, const void *hist_in,
+                                       void *out,
+                                       float *S_out, float *z_out, void *hist_out,
+                                       void *workspace, size_t workspace_bytes,
+                                       void *hip_stream);
+
 /* Speculative verification (Sec. 4.2): scores kk draft tokens per (b, h) from
  * one running state.  Output j equals what kk single decode steps would give
  * at step j.  Afterwards the state has advanced over the first n_commit[b]

@@ -21,7 +21,7 @@ LINATTN_F32, LINATTN_BF16 = 0, 1
 LINATTN_PHI_ELU1, LINATTN_PHI_RELU = 0, 1
 PHI = {"elu1": LINATTN_PHI_ELU1, "relu": LINATTN_PHI_RELU}
 MAX_CONV_K, MAX_DRAFT, MAX_TREE = 8, 16, 64
-SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_verify", "linattn_verify_tree", "linattn_decode",
+SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_grouped", "linattn_verify", "linattn_verify_tree", "linattn_decode",
            "linattn_status_string", "linattn_version")
 
 
@@ -53,6 +53,8 @@ def load():
     lib.linattn_workspace_bytes.argtypes = [dp, i32]
     lib.linattn_prefill.restype = ctypes.c_int
     lib.linattn_prefill.argtypes = [dp, i32] + [vp] * 11 + [vp, sz, vp]
+    lib.linattn_prefill_grouped.restype = ctypes.c_int
+    lib.linattn_prefill_grouped.argtypes = [dp, i32, ctypes.c_float] + [vp] * 11 + [vp, sz, vp]
     lib.linattn_verify.restype = ctypes.c_int
     lib.linattn_verify.argtypes = [dp, i32] + [vp] * 9 + [vp]
     lib.linattn_verify_tree.restype = ctypes.c_int
@@ -114,6 +116,16 @@ def linattn_prefill(desc: Desc, L, q, k, v, conv_w, S_in, z_in, hist_in, out, S_
     _check(st, "linattn_prefill")
 
 
+def linattn_prefill_grouped(desc: Desc, L, alpha, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out,
+                            workspace=None, workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().linattn_prefill_grouped(ctypes.byref(desc), int(L), float(alpha), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
+                                        _ptr(S_in), _ptr(z_in), _ptr(hist_in), _ptr(out), _ptr(S_out), _ptr(z_out),
+                                        _ptr(hist_out), _ptr(workspace), int(workspace_bytes), _stream(stream))
+    _check(st, "linattn_prefill_grouped")
+
+
 def linattn_verify(desc: Desc, kk, q, k, v, conv_w, S, z, hist, n_commit, out, stream=None) -> None:
     st = load().linattn_verify(ctypes.byref(desc), int(kk), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
                                _ptr(S), _ptr(z), _ptr(hist), _ptr(n_commit), _ptr(out), _stream(stream))
@@ -133,10 +145,11 @@ def linattn_decode(desc: Desc, q, k, v, conv_w, S, z, hist, out, stream=None) ->
 
 
 # ---- conveniences that only allocate with torch and forward to the calls above ---------------
-def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, stream=None, phi="elu1"):
+def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, stream=None, phi="elu1", grouped_alpha=None):
     """q, k, v: [B,H,L,d] CUDA tensors (fp32 or bf16), dense or any view with unit stride along d
     and equal strides for the three (e.g. ``x.transpose(1, 2)`` of a token-major [B,L,H,d] tensor);
-    ``out`` gets the same strides.  Returns out, (S, z, hist)."""
+    ``out`` gets the same strides.  Returns out, (S, z, hist).  grouped_alpha: None, or the weight of the
+    grouped branch of the three-branch form (``linattn_prefill_grouped``; bf16, groups of 64)."""
     B, H, L, d = q.shape
     Kc = conv_w.shape[2]
     if q.is_contiguous() and k.is_contiguous() and v.is_contiguous():
@@ -155,8 +168,17 @@ def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, str
         h = torch.empty((B, H, max(Kc - 1, 0), d), dtype=q.dtype, device=q.device)
     nbytes = linattn_workspace_bytes(desc, L)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device) if nbytes else None
-    linattn_prefill(desc, L, q, k, v, conv_w, S_in, z_in, h_in, out, S, z, h, ws, nbytes, stream)
+    if grouped_alpha is None:
+        linattn_prefill(desc, L, q, k, v, conv_w, S_in, z_in, h_in, out, S, z, h, ws, nbytes, stream)
+    else:
+        linattn_prefill_grouped(desc, L, grouped_alpha, q, k, v, conv_w, S_in, z_in, h_in, out, S, z, h, ws, nbytes, stream)
     return out, (S, z, h)
+
+
+def prefill_grouped(q, k, v, conv_w, alpha=1.0, state=None, eps=0.0, want_state=True, stream=None, phi="elu1"):
+    """The three-branch form (grouped linear attention, weight alpha + local softmax attention + masked conv)
+    with groups of 64 tokens; arguments as for ``prefill``."""
+    return prefill(q, k, v, conv_w, state, 64, eps, want_state, stream, phi, grouped_alpha=alpha)
 
 
 def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None, phi="elu1"):

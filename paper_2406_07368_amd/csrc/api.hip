@@ -56,6 +56,49 @@ PrefillPlan plan_prefill(const linattn_desc* d, int32_t L) {
   return p;
 }
 
+linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, float alpha, const void* q, const void* k,
+                           const void* v, const float* conv_w, const float* S_in, const float* z_in, const void* hist_in,
+                           void* out, float* S_out, float* z_out, void* hist_out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  linattn_status st = check_desc(desc, true);
+  if (st != LINATTN_OK) return st;
+  if (L < 0) return LINATTN_ERR_SHAPE;
+  if (grouped) {
+    if (!(alpha == alpha) || alpha - alpha != 0.f) return LINATTN_ERR_SHAPE;   // NaN, infinity
+    // the groups are part of the result here: only the kernel's own group of 64 tokens, bf16 rows
+    if (desc->io_dtype != LINATTN_BF16 || desc->chunk != 64) return LINATTN_ERR_UNSUPPORTED;
+  }
+  if (!conv_w) return LINATTN_ERR_NULL;
+  if (L > 0 && (!q || !k || !v || !out)) return LINATTN_ERR_NULL;
+  const bool has_hist = desc->conv_k > 1;
+  const int given = (S_in != nullptr) + (z_in != nullptr) + ((hist_in != nullptr) || !has_hist);
+  const bool cont = S_in != nullptr || z_in != nullptr || hist_in != nullptr;
+  if (cont && given != 3) return LINATTN_ERR_NULL;   // all of the incoming state, or none of it
+  const void* ptrs[] = {q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, workspace};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LINATTN_ERR_ALIGN;
+  // the last token of the last (b, h) must be addressable with 64-bit offsets
+  if ((double)desc->stride_b * desc->B + (double)desc->stride_h * desc->H + (double)desc->stride_t * L > 9.0e18)
+    return LINATTN_ERR_SHAPE;
+  const PrefillPlan plan = plan_prefill(desc, L);
+  if (plan.ws_bytes > 0 && (!workspace || workspace_bytes < plan.ws_bytes)) return LINATTN_ERR_WORKSPACE;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  PrefillArgs a{};
+  a.q = q; a.k = k; a.v = v; a.conv_w = conv_w;
+  a.S_in = S_in; a.z_in = z_in; a.hist_in = has_hist ? hist_in : nullptr;
+  a.out = out; a.S_out = S_out; a.z_out = z_out; a.hist_out = has_hist ? hist_out : nullptr;
+  a.ws = static_cast<float*>(workspace);
+  a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
+  a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
+  a.nseg = plan.nseg; a.seg_len = plan.seg_len;
+  a.alpha = alpha;
+  hipError_t e;
+  if (plan.mfma && L > 0) e = launch_prefill_mfma(a, desc->d, desc->chunk, grouped, stream);
+  else e = launch_prefill_simt(a, desc->io_dtype == LINATTN_BF16, desc->d, stream);   // L = 0: the state is handed through
+  return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -85,37 +128,16 @@ linattn_status linattn_prefill(const linattn_desc* desc, int32_t L, const void* 
                                const float* conv_w, const float* S_in, const float* z_in, const void* hist_in,
                                void* out, float* S_out, float* z_out, void* hist_out, void* workspace,
                                size_t workspace_bytes, void* hip_stream) {
-  linattn_status st = check_desc(desc, true);
-  if (st != LINATTN_OK) return st;
-  if (L < 0) return LINATTN_ERR_SHAPE;
-  if (!conv_w) return LINATTN_ERR_NULL;
-  if (L > 0 && (!q || !k || !v || !out)) return LINATTN_ERR_NULL;
-  const bool has_hist = desc->conv_k > 1;
-  const int given = (S_in != nullptr) + (z_in != nullptr) + ((hist_in != nullptr) || !has_hist);
-  const bool cont = S_in != nullptr || z_in != nullptr || hist_in != nullptr;
-  if (cont && given != 3) return LINATTN_ERR_NULL;   // all of the incoming state, or none of it
-  const void* ptrs[] = {q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, workspace};
-  for (const void* p : ptrs)
-    if (!aligned16(p)) return LINATTN_ERR_ALIGN;
-  // the last token of the last (b, h) must be addressable with 64-bit offsets
-  if ((double)desc->stride_b * desc->B + (double)desc->stride_h * desc->H + (double)desc->stride_t * L > 9.0e18)
-    return LINATTN_ERR_SHAPE;
-  const PrefillPlan plan = plan_prefill(desc, L);
-  if (plan.ws_bytes > 0 && (!workspace || workspace_bytes < plan.ws_bytes)) return LINATTN_ERR_WORKSPACE;
+  return prefill_any(desc, L, false, 0.f, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, workspace,
+                     workspace_bytes, hip_stream);
+}
 
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  PrefillArgs a{};
-  a.q = q; a.k = k; a.v = v; a.conv_w = conv_w;
-  a.S_in = S_in; a.z_in = z_in; a.hist_in = has_hist ? hist_in : nullptr;
-  a.out = out; a.S_out = S_out; a.z_out = z_out; a.hist_out = has_hist ? hist_out : nullptr;
-  a.ws = static_cast<float*>(workspace);
-  a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
-  a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
-  a.nseg = plan.nseg; a.seg_len = plan.seg_len;
-  hipError_t e;
-  if (plan.mfma && L > 0) e = launch_prefill_mfma(a, desc->d, desc->chunk, stream);
-  else e = launch_prefill_simt(a, desc->io_dtype == LINATTN_BF16, desc->d, stream);
-  return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
+linattn_status linattn_prefill_grouped(const linattn_desc* desc, int32_t L, float alpha, const void* q, const void* k,
+                                       const void* v, const float* conv_w, const float* S_in, const float* z_in,
+                                       const void* hist_in, void* out, float* S_out, float* z_out, void* hist_out,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return prefill_any(desc, L, true, alpha, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, workspace,
+                     workspace_bytes, hip_stream);
 }
 
 linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* q, const void* k, const void* v,

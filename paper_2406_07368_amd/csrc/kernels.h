@@ -53,6 +53,7 @@ struct PrefillArgs {
   int B, H, L, Kc;
   float eps;
   int relu;                 // feature map: 0 = elu + 1, 1 = max(x, 0)
+  float alpha;              // three-branch form only: weight of the grouped linear branch
   int64_t sb, sh, st;       // element strides of q, k, v, out
   int nseg;                 // workgroups along the sequence axis per (b, h)
   int seg_len;              // tokens per segment (multiple of the chunk size)
@@ -75,10 +76,10 @@ hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream
 // prefill_mfma.hip : launch plan of the bf16 prefill (segments, prefix sum over segment states)
 int prefill_mfma_pick_segments(int BH, int L, int chunk);
 size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg);
-hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, hipStream_t st);
+hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st);
 
 // prefill_mfma_ws.hip : the matrix-core kernel, with front-end waves (HBM traffic, feature map, scores)
 // and state waves (everything that touches S and z) working side by side
-hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, bool state_only, hipStream_t st);
+hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, bool state_only, bool grouped, hipStream_t st);
 
 }  // namespace linattn

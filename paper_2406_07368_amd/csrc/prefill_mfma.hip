@@ -59,19 +59,21 @@ size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg) {
 // part is the exact masked product).  A requested group of 128 tokens is walked as two steps of
 // 64: two 128-token row buffers do not fit in LDS, and larger groups only add in-group MFMA work
 // per token on this design.  Segment boundaries stay multiples of the requested size.
-hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, hipStream_t st) {
+// grouped: the three-branch form, whose groups are exactly 64 tokens (segments start on group
+// boundaries, so the first pass and the prefix sum are the same for both forms).
+hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st) {
   (void)chunk;
   const int BH = a.B * a.H;
   hipError_t e;
   if (a.nseg > 1) {
-    if ((e = launch_prefill_mfma_ws(a, d, true, st)) != hipSuccess) return e;
+    if ((e = launch_prefill_mfma_ws(a, d, true, false, st)) != hipSuccess) return e;
     const int slot = d * d + d;
     const dim3 grid((unsigned)((slot + 255) / 256), (unsigned)BH);
     if (d == 128) hipLaunchKernelGGL((segment_scan_kernel<128>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((segment_scan_kernel<64>), grid, dim3(256), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  return launch_prefill_mfma_ws(a, d, false, st);
+  return launch_prefill_mfma_ws(a, d, false, grouped, st);
 }
 
 }  // namespace linattn

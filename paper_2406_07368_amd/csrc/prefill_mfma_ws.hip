@@ -24,6 +24,14 @@
 //
 // Synchronisation per group: one workgroup barrier (C: the current buffer is free, the next one is
 // full) and one LDS counter on which the state waves wait for the front end's scores.
+//
+// GROUPED: the three-branch form of Sec. 4.1 on the same machinery.  The linear branch of a token
+// only meets the state as it stood before the token's group (S^T phi(Q)^T over its own normaliser
+// phi(q).z + eps, weighted by alpha); inside the group the scores are causal softmax attention on
+// the raw rows (logits q.k / sqrt(d)).  The front end therefore also keeps the raw Q and K rows of
+// the current group in LDS; to make room, everything that is only read at the start of a group
+// (phi(Q), raw Q, raw K) and the output staging exist once instead of twice, and a second LDS
+// counter tells the front end when the state waves are done with phi(Q).
 #include <type_traits>
 
 #include "common.cuh"
@@ -34,7 +42,7 @@ namespace linattn {
 
 namespace {
 
-template <int D, int C>
+template <int D, int C, bool GROUPED = false>
 struct WsCfg {
   static constexpr int NW = D / 32;          // state waves (and as many front-end waves)
   static constexpr int NT = 2 * NW * 64;
@@ -51,19 +59,24 @@ struct WsCfg {
   static constexpr int NTILE = TB * (TB + 1) / 2;
   static constexpr int MAXT = (NTILE + NW - 1) / NW;
   static constexpr int KCMAX = 8;
-  static constexpr int BQ = 0;
-  static constexpr int BK = BQ + C * QS * 2;
-  static constexpr int BV = BK + C * KS * 2;
+  static constexpr int SZQ = C * QS * 2, SZK = C * KS * 2;
+  static constexpr int BQ = 0;                               // GROUPED: phi(Q) is not part of the row buffers
+  static constexpr int BK = GROUPED ? 0 : BQ + SZQ;
+  static constexpr int BV = BK + SZK;
   static constexpr int BUF = (BV + (HALO + C) * VS * 2 + 15) / 16 * 16;   // bytes of one row buffer
-  static constexpr int OFF_PN = 2 * BUF;
+  static constexpr int OFF_FQ = 2 * BUF;                     // GROUPED: phi(Q), raw Q, raw K of the current group
+  static constexpr int OFF_RQ = OFF_FQ + (GROUPED ? SZQ : 0);
+  static constexpr int OFF_RK = OFF_RQ + (GROUPED ? SZQ : 0);
+  static constexpr int OFF_PN = OFF_RK + (GROUPED ? SZK : 0);
   static constexpr int OFF_DENQ = OFF_PN + C * PS * 2;     // [C] float (room for [NW][C])
   static constexpr int OFF_DENP = OFF_DENQ + NW * C * 4;   // [TB][C] float
   static constexpr int OFF_WL = OFF_DENP + TB * C * 4;     // [KCMAX][D] float, tap-major
   static constexpr int OS = D + 4;           // output staging rows: 8-byte writes, one row per lane
   static constexpr int OFF_OST = OFF_WL + KCMAX * D * 4;   // [2][C][OS] bf16: finished output rows of a group
   static constexpr int OST = C * OS * 2;
-  static constexpr int OFF_ZOP = OFF_OST + 2 * OST;        // [NW][2][16] bf16: z as the MFMA operand of each feature block
-  static constexpr int OFF_SYNC = OFF_ZOP + NW * 64;       // the counter of the front-end waves' signal
+  static constexpr int NOST = GROUPED ? 1 : 2;             // staging buffers
+  static constexpr int OFF_ZOP = OFF_OST + NOST * OST;     // [NW][2][16] bf16: z as the MFMA operand of each feature block
+  static constexpr int OFF_SYNC = OFF_ZOP + NW * 64;       // the counters of the front-end waves' and the state waves' signals
   static constexpr int TOTAL = OFF_SYNC + 16;
   static constexpr bool FITS = TOTAL <= 160 * 1024;
 };
@@ -72,9 +85,10 @@ struct WsCfg {
 
 // STATE_ONLY: the first pass of the segmented form -- a segment's K, V are reduced to its state
 // increment (S, z) only: no Q, no scores, no output.
-template <int D, int C, int KCM, bool STATE_ONLY>
+template <int D, int C, int KCM, bool STATE_ONLY, bool GROUPED = false>
 __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
-  using G = WsCfg<D, C>;
+  static_assert(!(STATE_ONLY && GROUPED), "the state does not depend on the form");
+  using G = WsCfg<D, C, GROUPED>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -88,6 +102,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   // A counter that only ever grows: every front-end wave adds one per group once its share of the
   // group's scores, their row sums and phi(q).z is in LDS.
   unsigned* sync_q = reinterpret_cast<unsigned*>(smem + G::OFF_SYNC);
+  // GROUPED only: every state wave adds one per group once it has read phi(Q) for the last time.
+  unsigned* sync_s = sync_q + 1;
   auto signal = [&](unsigned* ctr) __attribute__((always_inline)) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     if (lane == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -102,10 +118,12 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   };
-  auto bufQ = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BQ); };
+  auto bufQ = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + (GROUPED ? G::OFF_FQ : bi * G::BUF + G::BQ)); };
+  uint16_t* rawQ = reinterpret_cast<uint16_t*>(smem + G::OFF_RQ);   // GROUPED: the current group's rows as they came
+  uint16_t* rawK = reinterpret_cast<uint16_t*>(smem + G::OFF_RK);
   auto bufK = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BK); };
   auto bufV = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BV); };   // row r = token r - HALO
-  auto bufO = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + G::OFF_OST + bi * G::OST); };
+  auto bufO = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + G::OFF_OST + (GROUPED ? 0 : bi) * G::OST); };
 
   const int nseg_grid = STATE_ONLY ? a.nseg - 1 : a.nseg;
   const int bh = blockIdx.x / nseg_grid, seg = blockIdx.x % nseg_grid;
@@ -123,7 +141,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   const uint16_t* staged_hist =
       reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
-  if (tid == 0) *sync_q = 0u;
+  if (tid == 0) { *sync_q = 0u; *sync_s = 0u; }
   __syncthreads();                                     // the counters are used before the next barrier
 
   if (wv >= G::NW) {
@@ -217,6 +235,20 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         qrow[0] = u32x2{qp[0], qp[1]};
         qrow[1] = u32x2{qp[2], qp[3]};
       }
+      if constexpr (GROUPED) {
+        u32x4 rq0 = rq[SET][p], rk0 = rk[SET][p];
+        if (PARTIAL) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            rq0[i] = ok ? rq0[i] : 0u;
+            rk0[i] = ok ? rk0[i] : 0u;
+          }
+        }
+        u32x2* rqrow = reinterpret_cast<u32x2*>(rawQ + t * G::QS + c0);
+        rqrow[0] = u32x2{rq0[0], rq0[1]};
+        rqrow[1] = u32x2{rq0[2], rq0[3]};
+        *reinterpret_cast<u32x4*>(rawK + t * G::KS + c0) = rk0;
+      }
     };
     // finished output rows of group g (left in LDS by the state waves) -> HBM, whole rows per
     // D/8 consecutive lanes, 16 bytes per lane.  PARTIAL: only the rows that exist.
@@ -309,6 +341,73 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         }
       }
     };
+    // GROUPED: the local branch.  Causal softmax weights of the group's raw rows, logits q.k / sqrt(d)
+    // (Sec. 3, Eq. 1), in base 2.  One wave takes a block of 32 queries with all of its key tiles, so
+    // that the largest logit of a query is found inside the wave: lanes l and l + 32 hold the same
+    // query.  Left in LDS like the other form's scores: unnormalised weights exp2(x - top) as
+    // P[t][s] in bf16 and their sums (of the fp32 values) per key tile.
+    auto scores_local = [&](int) __attribute__((always_inline)) {
+      static_assert(!GROUPED || G::TB == 2, "two query blocks per group");
+      const int tb = lw == 0 ? 1 : (lw == 1 ? 0 : -1);   // the two-tile block goes to the wave that does not do phi(q).z
+      if (tb < 0) return;
+      static_assert(D == 64 || D == 128, "1 / sqrt(d) below");
+      constexpr float to_log2 = 1.44269504088896340736f * (D == 64 ? 0.125f : 0.08838834764831845f);
+      f32x16 acc[G::TB];
+#pragma unroll
+      for (int sb = 0; sb < G::TB; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[sb][r] = 0.f;
+      const uint16_t* qb = rawQ + (32 * tb + l32) * G::QS + 8 * hi;
+      constexpr int HB = G::KSD / 2;   // two batches of K steps
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        bf16x8 ak[G::TB][HB], bq[HB];
+#pragma unroll
+        for (int k2 = 0; k2 < HB; ++k2) {
+          const int ks = half * HB + k2;
+          bq[k2] = cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4));
+#pragma unroll
+          for (int sb = 0; sb < G::TB; ++sb)
+            if (sb <= tb) ak[sb][k2] = lds_row8(rawK + (32 * sb + l32) * G::KS + 8 * hi + 16 * ks);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k2 = 0; k2 < HB; ++k2)
+#pragma unroll
+          for (int sb = 0; sb < G::TB; ++sb)
+            if (sb <= tb) acc[sb] = mfma(ak[sb][k2], bq[k2], acc[sb]);
+      }
+      // acc[sb][r]: key token s = 32sb + 8(r/4) + 4hi + r%4, query token t = 32tb + l32
+      float top = -INFINITY;
+#pragma unroll
+      for (int sb = 0; sb < G::TB; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int sl = 8 * (r >> 2) + 4 * hi + (r & 3);
+          const bool seen = sb < tb || (sb == tb && sl <= l32);
+          acc[sb][r] = seen ? acc[sb][r] * to_log2 : -INFINITY;
+          top = fmaxf(top, acc[sb][r]);
+        }
+      top = fmaxf(top, __shfl_xor(top, 32));             // the diagonal is always seen: top is finite
+#pragma unroll
+      for (int sb = 0; sb < G::TB; ++sb) {
+        if (sb > tb) continue;
+        float rs = 0.f;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float x[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            x[e] = __builtin_amdgcn_exp2f(acc[sb][4 * g + e] - top);   // exp2(-inf) = 0: later tokens cannot leak
+            rs += x[e];
+          }
+          u32x2 pk = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
+          *reinterpret_cast<u32x2*>(Pn + (32 * tb + l32) * G::PS + 32 * sb + 8 * g + 4 * hi) = pk;
+        }
+        rs += __shfl_xor(rs, 32);
+        if (lane < 32) denp[sb * C + 32 * tb + l32] = rs;
+      }
+    };
     // phi(q_t).z for every token of group ci, by the last front-end wave alone (it has the fewest
     // score tiles); z (the state before the group) is read from LDS in operand form, where the
     // state waves left it
@@ -377,7 +476,14 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       // ci - 1 stored.
       auto step = [&](int ci, auto set_tag, auto store_tag) __attribute__((always_inline)) {
         if (!STATE_ONLY) {
-          scores(ci);
+          if constexpr (GROUPED) {
+            // the one staging buffer: group ci - 1 leaves before the state waves may write group ci
+            // (they wait for this step's signal first)
+            if (decltype(store_tag)::value) store_group(ci - 1, Full{});
+            scores_local(ci);
+          } else {
+            scores(ci);
+          }
           q_dot_z(ci);
           signal(sync_q);
           // the last HALO value rows of group ci become the rows before group ci + 1
@@ -389,9 +495,19 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
             dst[0] = t0; dst[1] = t1;
           }
         }
-        fill_group(ci + 1, set_tag, store_tag, relu_tag);
+        if constexpr (GROUPED) {
+          // phi(Q), raw Q and raw K exist once: group ci + 1 may replace them when every front-end wave
+          // has its scores of group ci and every state wave its products with phi(Q)
+          wait_for(sync_q, (unsigned)G::NW * (unsigned)(ci + 1));
+          wait_for(sync_s, (unsigned)G::NW * (unsigned)(ci + 1));
+          fill_group(ci + 1, set_tag, std::false_type{}, relu_tag);
+        } else {
+          fill_group(ci + 1, set_tag, store_tag, relu_tag);
+        }
         __syncthreads();                                 // barrier C
       };
+      // store_tag of a step: GROUPED, group ci - 1 exists (ci > 0); otherwise, group ci - 1 exists and
+      // is stored half-way through the fill (ci > 0, too)
       int ci = 0;
       if (nchunks > 1) { step(0, Set1{}, std::false_type{}); ci = 1; }
       for (; ci + 2 < nchunks; ci += 2) {                // ci is odd here: group ci + 1 is even
@@ -401,10 +517,15 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       if (ci >= 1 && ci + 1 < nchunks) { step(ci, Set0{}, std::true_type{}); ++ci; }
       if (nchunks > 0) {                                 // ci == nchunks - 1: nothing left to fill
         if (!STATE_ONLY) {
-          scores(ci);
+          if constexpr (GROUPED) {
+            if (ci > 0) store_group(ci - 1, Full{});
+            scores_local(ci);
+          } else {
+            scores(ci);
+          }
           q_dot_z(ci);
           signal(sync_q);
-          if (ci > 0) store_group(ci - 1, Full{});
+          if (!GROUPED && ci > 0) store_group(ci - 1, Full{});
         }
         __syncthreads();                                 // barrier C
       }
@@ -526,6 +647,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) o[tb] = mfma(pack8(Sacc[ib], 8 * h2), qB[2 * ib + h2], o[tb]);
     }
+    if constexpr (GROUPED) signal(sync_s);   // phi(Q) of this group has been read for the last time
     // the state update needs nothing from the front end either: it goes before the wait for the scores
     update_state();
     wait_for(sync_q, (unsigned)G::NW * (unsigned)(ci + 1));   // scores, their row sums and phi(q).z are in LDS
@@ -558,12 +680,28 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       };
       conv_request(0);
       LINATTN_FENCE();
+      float den;
+      if constexpr (GROUPED) {
+        // two normalisers: the linear branch (so far alone in o) over eps + phi(q).z, the local branch
+        // over the sum of its weights.  The first is applied here, times the second, so that one
+        // division by the second at the end serves both.  A linear branch with nothing before it
+        // (denominator exactly zero) contributes nothing.
+        den = 0.f;
+#pragma unroll
+        for (int sb = 0; sb <= tb; ++sb) den += dpart[1 + sb];
+        const float gden = a.eps + dpart[0];
+        const float f = gden != 0.f ? a.alpha * den * __builtin_amdgcn_rcpf(gden) : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[tb][r] = gden != 0.f ? o[tb][r] * f : 0.f;
+      }
 #pragma unroll
       for (int ks = 0; ks < 2 * (tb + 1); ++ks) o[tb] = mfma(vf[ks], pB[ks], o[tb]);
-      // the normaliser: eps + phi(q).z + the scores' row sums
-      float den = a.eps + dpart[0];
+      if constexpr (!GROUPED) {
+        // the normaliser: eps + phi(q).z + the scores' row sums
+        den = a.eps + dpart[0];
 #pragma unroll
-      for (int sb = 0; sb <= tb; ++sb) den += dpart[1 + sb];
+        for (int sb = 0; sb <= tb; ++sb) den += dpart[1 + sb];
+      }
       const float inv = __builtin_amdgcn_rcpf(den);
       // normalise, add the causal conv, stage the row for the front-end waves to store
       uint16_t* orow = bufO(ci & 1) + t * G::OS + 32 * w + 4 * hi;
@@ -641,11 +779,11 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   }
 }
 
-template <int D, int C, int KCM, bool STATE_ONLY>
+template <int D, int C, int KCM, bool STATE_ONLY, bool GROUPED = false>
 static hipError_t launch_ws(const PrefillArgs& a, hipStream_t st) {
-  using G = WsCfg<D, C>;
+  using G = WsCfg<D, C, GROUPED>;
   static_assert(G::FITS, "two row buffers must fit in the 160 KB of LDS");
-  auto kern = prefill_mfma_ws_kernel<D, C, KCM, STATE_ONLY>;
+  auto kern = prefill_mfma_ws_kernel<D, C, KCM, STATE_ONLY, GROUPED>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
   if (e != hipSuccess) return e;
   const int segs = STATE_ONLY ? a.nseg - 1 : a.nseg;
@@ -654,9 +792,14 @@ static hipError_t launch_ws(const PrefillArgs& a, hipStream_t st) {
 }
 
 template <int D>
-static hipError_t launch_ws_k(const PrefillArgs& a, bool state_only, hipStream_t st) {
+static hipError_t launch_ws_k(const PrefillArgs& a, bool state_only, bool grouped, hipStream_t st) {
   constexpr int C = 64;   // tokens per group
   if (state_only) return launch_ws<D, C, 3, true>(a, st);   // the conv taps play no part in the state
+  if (grouped) {
+    if (a.Kc <= 3) return launch_ws<D, C, 3, false, true>(a, st);
+    if (a.Kc <= 5) return launch_ws<D, C, 5, false, true>(a, st);
+    return launch_ws<D, C, 8, false, true>(a, st);
+  }
   if (a.Kc <= 3) return launch_ws<D, C, 3, false>(a, st);
   if (a.Kc <= 5) return launch_ws<D, C, 5, false>(a, st);
   return launch_ws<D, C, 8, false>(a, st);
@@ -664,8 +807,9 @@ static hipError_t launch_ws_k(const PrefillArgs& a, bool state_only, hipStream_t
 
 // One pass of a prefill call over all its segments.  state_only: the first pass of the segmented
 // form (segment increments into a.ws); otherwise the full pass (segment start states must be in a.ws).
-hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, bool state_only, hipStream_t st) {
-  return d == 128 ? launch_ws_k<128>(a, state_only, st) : launch_ws_k<64>(a, state_only, st);
+// grouped: the three-branch form with 64-token groups (a.alpha weighs its linear branch).
+hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, bool state_only, bool grouped, hipStream_t st) {
+  return d == 128 ? launch_ws_k<128>(a, state_only, grouped, st) : launch_ws_k<64>(a, state_only, grouped, st);
 }
 
 }  // namespace linattn

@@ -91,6 +91,33 @@ def test_workspace_is_constant_in_L_and_checked():
     assert lib.linattn_workspace_bytes(ctypes.byref(bad), 65536) == 0
 
 
+def grouped_status(desc, L=256, alpha=1.0, **over):
+    lib = binding.load()
+    a = dict(q=P, k=P, v=P, conv_w=P, S_in=None, z_in=None, hist_in=None, out=P, S_out=P, z_out=P, hist_out=P,
+             ws=P, ws_bytes=1 << 40)
+    a.update(over)
+    return lib.linattn_prefill_grouped(ctypes.byref(desc) if desc is not None else None, L, alpha, a["q"], a["k"], a["v"],
+                                       a["conv_w"], a["S_in"], a["z_in"], a["hist_in"], a["out"], a["S_out"], a["z_out"],
+                                       a["hist_out"], a["ws"], a["ws_bytes"], None)
+
+
+def test_prefill_grouped_rejects_bad_arguments():
+    d = good_desc()
+    assert grouped_status(None) == 1
+    assert grouped_status(d, L=-1) == 2
+    assert grouped_status(d, alpha=float("nan")) == 2
+    assert grouped_status(d, alpha=float("inf")) == 2
+    assert grouped_status(d, k=None) == 1
+    assert grouped_status(d, out=P + 8) == 4
+    assert grouped_status(d, S_in=P) == 1
+    assert grouped_status(good_desc(io_dtype=binding.LINATTN_F32)) == 5     # bf16 rows only
+    assert grouped_status(good_desc(chunk=128)) == 5                        # the group is part of the result: 64 only
+    assert grouped_status(good_desc(chunk=32)) == 2
+    few = binding.make_desc(1, 2, 128, 3, 64, L=4096)                       # segmented: needs the workspace
+    assert binding.linattn_workspace_bytes(few, 4096) > 0
+    assert grouped_status(few, L=4096, ws=None, ws_bytes=0) == 6
+
+
 def verify_status(desc, kk=4, **over):
     lib = binding.load()
     a = dict(q=P, k=P, v=P, conv_w=P, S=P, z=P, hist=P, n_commit=None, out=P)
