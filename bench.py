@@ -16,8 +16,8 @@ already resident in HBM:
 The headline ``value`` is prefill tokens/s (B*L divided by the mean duration of the
 prefill launches, measured with events on the launch stream inside the timed
 region); the verify/decode step times are reported beside it in microseconds with
-their own HBM roofline; the tree-structured verify (64 candidates) is timed after the
-steps and reported as ``tree_verify``.  Between steps the verify state rotates over 32 separate
+their own HBM roofline; the tree-structured verify (64 candidates) and the three-branch form of
+the prefill are timed after the steps and reported as ``tree_verify`` and ``prefill_grouped``.  Between steps the verify state rotates over 32 separate
 state sets (2.1 GB) and the prefill inputs over 2 sets (2.1 GB) so that nothing is
 served from the 256 MB last-level cache.
 
@@ -255,6 +255,32 @@ def main():
         other_layout_ms = {"layout": other, "mean": sum(a.elapsed_time(b) for a, b in ev2) / len(ev2),
                            "min": min(a.elapsed_time(b) for a, b in ev2)}
 
+    grouped = None
+    if do_prefill and args.only == "all" and pw.chunk == 64:
+        # next row of the scope (not part of the step): the three-branch form of the same prefill (grouped linear
+        # attention + local softmax attention + masked conv), same inputs, same layout, same algorithmic bytes
+        ev4 = []
+        for i in range(20 + min(args.steps, 50)):
+            q, k, v, out = pin[i % len(pin)]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            binding.linattn_prefill_grouped(pdesc, pw.L, 1.0, q, k, v, pwts, None, None, None, out, S_out, z_out, h_out,
+                                            ws, ws_bytes, stream)
+            e1.record(stream)
+            if i >= 20:
+                ev4.append((e0, e1))
+        stream.synchronize()
+        t_ms = [a.elapsed_time(b) for a, b in ev4]
+        t_mean = sum(t_ms) / len(t_ms)
+        nb = prefill_bytes(pw)
+        grouped = {"workload": f"{pw.name} B{pw.B} H{pw.H} L{pw.L} d{pw.d} bf16, groups of 64, Kc{pw.conv_k}, alpha 1, same tensors "
+                               "and layout as the prefill of the step",
+                   "ms": {"mean": t_mean, "median": float(np.median(t_ms)), "min": min(t_ms)},
+                   "tokens_per_s": pw.B * pw.L / (t_mean * 1e-3),
+                   "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb,
+                                "traffic": read_traffic("prefill_grouped_cfg3_pmc.txt") if pw.name.startswith("cfg3") and not args.length else None}}
+
     tree = None
     if do_verify and args.only == "all":
         # next row of the scope (not part of the step): tree-structured verify, 64 speculated tokens / 42
@@ -309,6 +335,8 @@ def main():
         result["prefill_ms"] = {"mean": mean_ms["prefill"], "median": med_ms["prefill"], "min": min_ms["prefill"]}
         if other_layout_ms:
             result["prefill_ms_other_layout"] = other_layout_ms
+        if grouped:
+            result["prefill_grouped"] = grouped
         result["roofline"] = {"bound": "hbm", "achieved": nbytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": nbytes / t / 1e9 / HBM_PEAK_GBS,
                               "traffic": read_traffic("prefill_mfma_cfg3_pmc.txt") if pw.name.startswith("cfg3") and not args.length else None,

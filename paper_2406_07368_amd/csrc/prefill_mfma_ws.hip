@@ -104,6 +104,9 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   unsigned* sync_q = reinterpret_cast<unsigned*>(smem + G::OFF_SYNC);
   // GROUPED only: every state wave adds one per group once it has read phi(Q) for the last time.
   unsigned* sync_s = sync_q + 1;
+  // GROUPED with eight waves: the two waves that share a query block add one each per group once their
+  // largest logits are in LDS.
+  unsigned* sync_m = sync_q + 2;
   auto signal = [&](unsigned* ctr) __attribute__((always_inline)) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     if (lane == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -141,7 +144,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   const uint16_t* staged_hist =
       reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
-  if (tid == 0) { *sync_q = 0u; *sync_s = 0u; }
+  if (tid == 0) { *sync_q = 0u; *sync_s = 0u; *sync_m = 0u; }
   __syncthreads();                                     // the counters are used before the next barrier
 
   if (wv >= G::NW) {
@@ -170,9 +173,12 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     // Only the last group of a segment can be short; everything about it takes the PARTIAL paths.
     const bool last_partial = (t_end - t_begin) % C != 0;
     // 16 rows of group g: uniform base + 32-bit lane offset
-    auto load_pass = [&](int g, int p, auto set_tag, auto partial_tag) __attribute__((always_inline)) {
+    // part_tag: 0 = K, V and Q; GROUPED fills in two parts and requests with them: 1 = V only, 2 = K and Q
+    auto load_pass = [&](int g, int p, auto set_tag, auto partial_tag, auto part_tag) __attribute__((always_inline)) {
       constexpr int SET = decltype(set_tag)::value;
       constexpr bool PARTIAL = decltype(partial_tag)::value;
+      constexpr int PART = decltype(part_tag)::value;
+      constexpr bool LK = PART != 1, LV = PART != 2, LQ = PART != 1 && !STATE_ONLY;
       const int gc = g < nchunks ? g : nchunks - 1;    // uniform
       const int tok = t_begin + gc * C + 16 * p;       // uniform
       const int64_t off = (int64_t)tok * a.st;
@@ -186,56 +192,58 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         const int last = t_end - 1 - tok;              // last row of the segment, relative to this pass
         const int r = (g < nchunks && r16 <= last) ? r16 : (last < 0 ? last : 0);   // a row that exists
         lo = (uint32_t)(r * (int)a.st + c0) * 2u;      // byte offset, may be negative: wraps with the base
-        rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + (int32_t)lo));
-        rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + (int32_t)lo));
-        if (!STATE_ONLY) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + (int32_t)lo));
+        if (LK) rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + (int32_t)lo));
+        if (LV) rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + (int32_t)lo));
+        if (LQ) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + (int32_t)lo));
       } else {
-        rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + lo));
-        rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + lo));
-        if (!STATE_ONLY) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + lo));
+        if (LK) rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + lo));
+        if (LV) rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + lo));
+        if (LQ) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + lo));
       }
     };
     // feature map on the 16 rows held in registers, then to buffer bi.  PARTIAL: rows >= nt become
     // zero rows (phi(0) = 1, so they are cleared after the map).
-    auto fill_pass = [&](int bi, int p, int nt, auto set_tag, auto partial_tag, auto relu_tag) __attribute__((always_inline)) {
+    auto fill_pass = [&](int bi, int p, int nt, auto set_tag, auto partial_tag, auto relu_tag, auto part_tag) __attribute__((always_inline)) {
       constexpr int SET = decltype(set_tag)::value;
       constexpr bool PARTIAL = decltype(partial_tag)::value;
+      constexpr bool RELU = decltype(relu_tag)::value;
+      constexpr int PART = decltype(part_tag)::value;    // 0: everything; GROUPED: 1 = phi(K) and V, 2 = the rest
+      constexpr bool DO_KV = PART != 2, DO_Q = PART != 1 && !STATE_ONLY, DO_RAW = GROUPED && PART != 1;
       const int t = 16 * p + r16;
       const bool ok = !PARTIAL || t < nt;
-      u32x4 kp, qp, vp = rv[SET][p];
-      if (!decltype(relu_tag)::value) {
+      auto phi2 = [&](uint32_t x) __attribute__((always_inline)) {
+        return RELU ? pack_bf16x2(fmaxf(bf16_lo_to_f32(x), 0.f), fmaxf(bf16_hi_to_f32(x), 0.f))
+                    : pack_bf16x2(phi_elu1_max(bf16_lo_to_f32(x)), phi_elu1_max(bf16_hi_to_f32(x)));
+      };
+      if constexpr (DO_KV) {
+        u32x4 kp, vp = rv[SET][p];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          kp[i] = pack_bf16x2(phi_elu1_max(bf16_lo_to_f32(rk[SET][p][i])), phi_elu1_max(bf16_hi_to_f32(rk[SET][p][i])));
-          if (!STATE_ONLY)
-            qp[i] = pack_bf16x2(phi_elu1_max(bf16_lo_to_f32(rq[SET][p][i])), phi_elu1_max(bf16_hi_to_f32(rq[SET][p][i])));
-        }
-      } else {
+        for (int i = 0; i < 4; ++i) kp[i] = phi2(rk[SET][p][i]);
+        if (PARTIAL) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          kp[i] = pack_bf16x2(fmaxf(bf16_lo_to_f32(rk[SET][p][i]), 0.f), fmaxf(bf16_hi_to_f32(rk[SET][p][i]), 0.f));
-          if (!STATE_ONLY)
-            qp[i] = pack_bf16x2(fmaxf(bf16_lo_to_f32(rq[SET][p][i]), 0.f), fmaxf(bf16_hi_to_f32(rq[SET][p][i]), 0.f));
+          for (int i = 0; i < 4; ++i) {
+            kp[i] = ok ? kp[i] : 0u;
+            vp[i] = ok ? vp[i] : 0u;
+          }
         }
+        *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
+        u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + t) * G::VS + c0);
+        vrow[0] = u32x2{vp[0], vp[1]};
+        vrow[1] = u32x2{vp[2], vp[3]};
       }
-      if (PARTIAL) {
+      if constexpr (DO_Q) {
+        u32x4 qp;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          kp[i] = ok ? kp[i] : 0u;
-          vp[i] = ok ? vp[i] : 0u;
-          if (!STATE_ONLY) qp[i] = ok ? qp[i] : 0u;
+        for (int i = 0; i < 4; ++i) qp[i] = phi2(rq[SET][p][i]);
+        if (PARTIAL) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) qp[i] = ok ? qp[i] : 0u;
         }
-      }
-      *reinterpret_cast<u32x4*>(bufK(bi) + t * G::KS + c0) = kp;
-      u32x2* vrow = reinterpret_cast<u32x2*>(bufV(bi) + (HALO + t) * G::VS + c0);
-      vrow[0] = u32x2{vp[0], vp[1]};
-      vrow[1] = u32x2{vp[2], vp[3]};
-      if (!STATE_ONLY) {
         u32x2* qrow = reinterpret_cast<u32x2*>(bufQ(bi) + t * G::QS + c0);
         qrow[0] = u32x2{qp[0], qp[1]};
         qrow[1] = u32x2{qp[2], qp[3]};
       }
-      if constexpr (GROUPED) {
+      if constexpr (DO_RAW) {
         u32x4 rq0 = rq[SET][p], rk0 = rk[SET][p];
         if (PARTIAL) {
 #pragma unroll
@@ -271,19 +279,47 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     // of group g + 2 is requested from HBM into the freed registers.  STORE: the finished output
     // rows of group g - 2 (always a full group) are written out half-way through, so that no HBM
     // request is younger than half a group when the next fill starts waiting for its rows.
+    //
+    // GROUPED (STORE means something else there: "wait"): first everything that goes to the row buffer not in
+    // use (phi(K), V); then, once every front-end wave has its scores of group g - 1 and every state wave its
+    // products with phi(Q) -- normally long since --, the arrays that exist once (phi(Q), raw Q, raw K).
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
     auto fill_group = [&](int g, auto set_tag, auto store_tag, auto relu_tag) __attribute__((always_inline)) {
       constexpr bool STORE = decltype(store_tag)::value;
       const int bi = g & 1;
       const int nt = (t_end - (t_begin + g * C)) < C ? (t_end - (t_begin + g * C)) : C;
       const bool fill_part = last_partial && g == nchunks - 1;
       const bool load_part = last_partial && g + 2 >= nchunks - 1;
+      if constexpr (GROUPED) {
 #pragma unroll
-      for (int p = 0; p < G::NP; ++p) {
-        if (!STATE_ONLY && STORE && p == G::NP / 2) store_group(g - 2, Full{});
-        if (!fill_part) fill_pass(bi, p, nt, set_tag, Full{}, relu_tag);
-        else fill_pass(bi, p, nt, set_tag, Part{}, relu_tag);
-        if (!load_part) load_pass(g + 2, p, set_tag, Full{});
-        else load_pass(g + 2, p, set_tag, Part{});
+        for (int p = 0; p < G::NP; ++p) {
+          if (!fill_part) fill_pass(bi, p, nt, set_tag, Full{}, relu_tag, P1{});
+          else fill_pass(bi, p, nt, set_tag, Part{}, relu_tag, P1{});
+          if (!load_part) load_pass(g + 2, p, set_tag, Full{}, P1{});
+          else load_pass(g + 2, p, set_tag, Part{}, P1{});
+        }
+        if (STORE) {
+          wait_for(sync_q, (unsigned)G::NW * (unsigned)g);
+          wait_for(sync_s, (unsigned)G::NW * (unsigned)g);
+        }
+#pragma unroll
+        for (int p = 0; p < G::NP; ++p) {
+          if (!fill_part) fill_pass(bi, p, nt, set_tag, Full{}, relu_tag, P2{});
+          else fill_pass(bi, p, nt, set_tag, Part{}, relu_tag, P2{});
+          if (!load_part) load_pass(g + 2, p, set_tag, Full{}, P2{});
+          else load_pass(g + 2, p, set_tag, Part{}, P2{});
+        }
+      } else {
+#pragma unroll
+        for (int p = 0; p < G::NP; ++p) {
+          if (!STATE_ONLY && STORE && p == G::NP / 2) store_group(g - 2, Full{});
+          if (!fill_part) fill_pass(bi, p, nt, set_tag, Full{}, relu_tag, P0{});
+          else fill_pass(bi, p, nt, set_tag, Part{}, relu_tag, P0{});
+          if (!load_part) load_pass(g + 2, p, set_tag, Full{}, P0{});
+          else load_pass(g + 2, p, set_tag, Part{}, P0{});
+        }
       }
     };
     using Set0 = std::integral_constant<int, 0>;
@@ -342,63 +378,84 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       }
     };
     // GROUPED: the local branch.  Causal softmax weights of the group's raw rows, logits q.k / sqrt(d)
-    // (Sec. 3, Eq. 1), in base 2.  One wave takes a block of 32 queries with all of its key tiles, so
-    // that the largest logit of a query is found inside the wave: lanes l and l + 32 hold the same
-    // query.  Left in LDS like the other form's scores: unnormalised weights exp2(x - top) as
-    // P[t][s] in bf16 and their sums (of the fp32 values) per key tile.
-    auto scores_local = [&](int) __attribute__((always_inline)) {
+    // (Sec. 3, Eq. 1), in base 2, left in LDS like the other form's scores: unnormalised weights
+    // exp2(x - top) as P[t][s] in bf16 and their sums (of the fp32 values) per key tile.  top is the
+    // largest logit of the query: lanes l and l + 32 of a tile hold the same query; with eight waves
+    // the two key tiles of the second query block are on two waves, which pass each other their
+    // largest logits through LDS (a counter of their own tells when both are there), with four waves
+    // one wave has both tiles.
+    auto scores_local = [&](int ci) __attribute__((always_inline)) {
       static_assert(!GROUPED || G::TB == 2, "two query blocks per group");
-      const int tb = lw == 0 ? 1 : (lw == 1 ? 0 : -1);   // the two-tile block goes to the wave that does not do phi(q).z
-      if (tb < 0) return;
+      constexpr bool SPLIT = G::NW >= 4;
+      constexpr int NA = SPLIT ? 1 : 2;                  // tiles per wave at most
+      // SPLIT: wave 0 -> tile (1, 0), wave 1 -> (1, 1), wave 2 -> (0, 0); the last wave has phi(q).z.
+      // otherwise: wave 0 -> (1, 0) and (1, 1), wave 1 -> (0, 0) (and phi(q).z)
+      const int tb = SPLIT ? (lw <= 1 ? 1 : 0) : (lw == 0 ? 1 : 0);
+      const int sb0 = SPLIT && lw == 1 ? 1 : 0;
+      const int nsb = SPLIT ? (lw <= 2 ? 1 : 0) : (lw == 0 ? 2 : 1);
+      if (nsb == 0) return;
       static_assert(D == 64 || D == 128, "1 / sqrt(d) below");
       constexpr float to_log2 = 1.44269504088896340736f * (D == 64 ? 0.125f : 0.08838834764831845f);
-      f32x16 acc[G::TB];
+      f32x16 acc[NA];
 #pragma unroll
-      for (int sb = 0; sb < G::TB; ++sb)
+      for (int j = 0; j < NA; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[sb][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
       const uint16_t* qb = rawQ + (32 * tb + l32) * G::QS + 8 * hi;
       constexpr int HB = G::KSD / 2;   // two batches of K steps
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
-        bf16x8 ak[G::TB][HB], bq[HB];
+        bf16x8 ak[NA][HB], bq[HB];
 #pragma unroll
         for (int k2 = 0; k2 < HB; ++k2) {
           const int ks = half * HB + k2;
           bq[k2] = cat4(lds_row4(qb + 16 * ks), lds_row4(qb + 16 * ks + 4));
 #pragma unroll
-          for (int sb = 0; sb < G::TB; ++sb)
-            if (sb <= tb) ak[sb][k2] = lds_row8(rawK + (32 * sb + l32) * G::KS + 8 * hi + 16 * ks);
+          for (int j = 0; j < NA; ++j)
+            if (j < nsb) ak[j][k2] = lds_row8(rawK + (32 * (sb0 + j) + l32) * G::KS + 8 * hi + 16 * ks);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k2 = 0; k2 < HB; ++k2)
 #pragma unroll
-          for (int sb = 0; sb < G::TB; ++sb)
-            if (sb <= tb) acc[sb] = mfma(ak[sb][k2], bq[k2], acc[sb]);
+          for (int j = 0; j < NA; ++j)
+            if (j < nsb) acc[j] = mfma(ak[j][k2], bq[k2], acc[j]);
       }
-      // acc[sb][r]: key token s = 32sb + 8(r/4) + 4hi + r%4, query token t = 32tb + l32
+      // acc[j][r]: key token s = 32(sb0 + j) + 8(r/4) + 4hi + r%4, query token t = 32tb + l32.
+      // Only the diagonal tile has keys later than the query: they become -inf, exp2 of which is 0
+      // (later tokens cannot leak).  The scale is positive, so the largest raw product is the largest logit.
       float top = -INFINITY;
 #pragma unroll
-      for (int sb = 0; sb < G::TB; ++sb)
+      for (int j = 0; j < NA; ++j) {
+        if (j >= nsb) continue;
+        const bool diag = sb0 + j == tb;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int sl = 8 * (r >> 2) + 4 * hi + (r & 3);
-          const bool seen = sb < tb || (sb == tb && sl <= l32);
-          acc[sb][r] = seen ? acc[sb][r] * to_log2 : -INFINITY;
-          top = fmaxf(top, acc[sb][r]);
+          acc[j][r] = (!diag || sl <= l32) ? acc[j][r] : -INFINITY;
+          top = fmaxf(top, acc[j][r]);
         }
-      top = fmaxf(top, __shfl_xor(top, 32));             // the diagonal is always seen: top is finite
+      }
+      top = fmaxf(top, __shfl_xor(top, 32));
+      if (SPLIT && tb == 1) {
+        float* mx = denq + C;                            // [2][32], behind phi(q).z
+        if (lane < 32) mx[32 * sb0 + l32] = top;
+        signal(sync_m);
+        wait_for(sync_m, 2u * (unsigned)(ci + 1));
+        top = fmaxf(top, mx[32 * (1 - sb0) + l32]);
+      }
+      const float shift = -top * to_log2;                // the diagonal is always seen: top is finite
 #pragma unroll
-      for (int sb = 0; sb < G::TB; ++sb) {
-        if (sb > tb) continue;
+      for (int j = 0; j < NA; ++j) {
+        if (j >= nsb) continue;
+        const int sb = sb0 + j;
         float rs = 0.f;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           float x[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            x[e] = __builtin_amdgcn_exp2f(acc[sb][4 * g + e] - top);   // exp2(-inf) = 0: later tokens cannot leak
+            x[e] = __builtin_amdgcn_exp2f(fmaf(acc[j][4 * g + e], to_log2, shift));
             rs += x[e];
           }
           u32x2 pk = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3])};
@@ -463,9 +520,9 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     auto walk = [&](auto relu_tag) __attribute__((always_inline)) {
       if (nchunks > 0) {
 #pragma unroll
-        for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{}, Part{});
+        for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{}, Part{}, P0{});
 #pragma unroll
-        for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{}, Part{});
+        for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{}, Part{}, P0{});
         fill_group(0, Set0{}, std::false_type{}, relu_tag);
       }
       __syncthreads();                                   // buffer 0 is full, z is in LDS
@@ -497,10 +554,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         }
         if constexpr (GROUPED) {
           // phi(Q), raw Q and raw K exist once: group ci + 1 may replace them when every front-end wave
-          // has its scores of group ci and every state wave its products with phi(Q)
-          wait_for(sync_q, (unsigned)G::NW * (unsigned)(ci + 1));
-          wait_for(sync_s, (unsigned)G::NW * (unsigned)(ci + 1));
-          fill_group(ci + 1, set_tag, std::false_type{}, relu_tag);
+          // has its scores of group ci and every state wave its products with phi(Q) (the fill waits)
+          fill_group(ci + 1, set_tag, std::true_type{}, relu_tag);
         } else {
           fill_group(ci + 1, set_tag, store_tag, relu_tag);
         }

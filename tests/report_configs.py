@@ -50,16 +50,20 @@ def oracle_time(fn_heads, threads_all):
     return t1, tn
 
 
-def prefill_row(name, sample):
+def prefill_row(name, sample, grouped=False):
+    """grouped: the three-branch form (groups of 64, alpha 1) on the same tensors."""
     wl = workloads.CONFIGS[name]
     io = torch.float32 if wl.io_dtype == "f32" else torch.bfloat16
     q, k, v, w = workloads.prefill_tensors(wl)
     gq, gk, gv, gw = q.cuda(), k.cuda(), v.cuda(), w.cuda()
-    out, (S, z, h) = binding.prefill(gq, gk, gv, gw, None, wl.chunk)
+    out, (S, z, h) = binding.prefill(gq, gk, gv, gw, None, wl.chunk, grouped_alpha=1.0 if grouped else None)
     torch.cuda.synchronize()
     heads = sample if sample is not None else [(b, hh) for b in range(wl.B) for hh in range(wl.H)]
     worst, extra = 0.0, (0.0, 0.0)
     ref = oracle.prefill_quadratic if name.startswith("cfg1") else oracle.prefill_recurrent
+    if grouped:
+        def ref(q_, k_, v_, w_):
+            return oracle.prefill_grouped(q_, k_, v_, w_, 64, alpha=1.0)
     for b, hh in heads:
         sl = (slice(b, b + 1), slice(hh, hh + 1))
         want = ref(host(q[sl]), host(k[sl]), host(v[sl]), w[hh:hh + 1].numpy())
@@ -69,7 +73,10 @@ def prefill_row(name, sample):
     desc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, io, L=wl.L)
     nb = binding.linattn_workspace_bytes(desc, wl.L)
     ws = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda")
-    t = gpu_time(lambda: binding.linattn_prefill(desc, wl.L, gq, gk, gv, gw, None, None, None, out, S, z, h, ws, nb))
+    if grouped:
+        t = gpu_time(lambda: binding.linattn_prefill_grouped(desc, wl.L, 1.0, gq, gk, gv, gw, None, None, None, out, S, z, h, ws, nb))
+    else:
+        t = gpu_time(lambda: binding.linattn_prefill(desc, wl.L, gq, gk, gv, gw, None, None, None, out, S, z, h, ws, nb))
     esz = 4 if wl.io_dtype == "f32" else 2
     nbytes = 4 * wl.B * wl.H * wl.L * wl.d * esz
     ht = wl.B * wl.H * wl.L
@@ -84,6 +91,9 @@ def prefill_row(name, sample):
     t1, tn = oracle_time(run_heads, threads)
     nh = wl.B * wl.H
     mf = "-" if wl.io_dtype == "f32" else f"{100 * fc / t / MFMA:.1f} / {100 * fd / t / MFMA:.1f}"
+    if grouped:
+        name += ", three-branch form"
+        fc = fd = ht * (4 * wl.chunk * wl.d + 4 * wl.d * wl.d)
     return (f"| {name} | {t * 1e6:.1f} µs | {wl.B * wl.L / t / 1e6:.2f} M tokens/s | {100 * nbytes / t / HBM:.1f} | {mf} | "
             f"{t1 * nh:.2f} s | {tn * nh:.2f} s ({threads}) | {worst:.1e} ({'all' if sample is None else len(sample)} heads); "
             f"out: max abs {extra[0]:.1e}, p99.9 rel {extra[1]:.1e} |")
@@ -192,6 +202,7 @@ def main():
     for r in verify_rows():
         print(r, flush=True)
     print(prefill_row("cfg5_long_context", [(0, 0), (0, 31)]), flush=True)
+    print(prefill_row("cfg3_llama7b_prefill", [(0, 0), (3, 31), (7, 16)], grouped=True), flush=True)
 
 
 if __name__ == "__main__":

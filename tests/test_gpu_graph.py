@@ -67,7 +67,9 @@ def test_decode_verify_and_tree_steps_replay_as_a_graph():
     assert not np.array_equal(host(graph_state[0]), S.astype(np.float64))   # the state did move
 
 
-def test_prefill_replays_as_a_graph():
+@pytest.mark.parametrize("grouped", [False, True])
+def test_prefill_replays_as_a_graph(grouped):
+    """grouped: the three-branch form (same launch plan, its own kernel for the full pass)."""
     wl = workloads.CONFIGS["cfg2_gpt2_small"]        # segmented: three kernels and a workspace per call
     q, k, v, w = workloads.prefill_tensors(wl)
     gq, gk, gv, gw = q.cuda(), k.cuda(), v.cuda(), w.cuda()
@@ -79,12 +81,18 @@ def test_prefill_replays_as_a_graph():
                   torch.empty((wl.B, wl.H, wl.d), device="cuda"),
                   torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d), dtype=BF, device="cuda"))
     want, got = mk(), mk()
-    binding.linattn_prefill(desc, wl.L, gq, gk, gv, gw, None, None, None, *want, ws, nb)
+
+    def call(dst):
+        if grouped:
+            binding.linattn_prefill_grouped(desc, wl.L, 0.75, gq, gk, gv, gw, None, None, None, *dst, ws, nb)
+        else:
+            binding.linattn_prefill(desc, wl.L, gq, gk, gv, gw, None, None, None, *dst, ws, nb)
+    call(want)
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=side):
-        binding.linattn_prefill(desc, wl.L, gq, gk, gv, gw, None, None, None, *got, ws, nb)
+        call(got)
     for replay in range(3):
         for t in got:
             t.zero_()
