@@ -57,6 +57,8 @@ def _declare(lib):
         fn.argtypes = [i, i, i, i, i, f] + [_dp] * 11
     lib.oracle_prefill_grouped.restype = i
     lib.oracle_prefill_grouped.argtypes = [i, i, i, i, i, i, f, f] + [_dp] * 11
+    lib.oracle_verify_grouped.restype = i
+    lib.oracle_verify_grouped.argtypes = [i, i, i, i, i, i, f, f] + [_dp] * 9 + [_ip, _ip, _dp]
     lib.oracle_verify.restype = i
     lib.oracle_verify.argtypes = [i, i, i, i, i, f] + [_dp] * 7 + [_ip, _dp]
     lib.oracle_verify_tree.restype = i
@@ -217,6 +219,42 @@ def verify(q, k, v, w, S, z, hist, n_commit=None, eps=0.0, lib=None):
     if rc != 0:
         raise ValueError(f"oracle_verify rejected its arguments (code {rc})")
     return out, S, z, hist
+
+
+def verify_grouped(q, k, v, w, group, S, z, hist, kwin, vwin, fill, n_commit=None, alpha=1.0, eps=0.0, lib=None):
+    """kk token steps of the three-branch form from one state.  S, z: sums over the completed groups;
+    kwin, vwin [B,H,group,d]: raw key / value rows of the current group, rows 0..fill[b]-1 in use; fill int [B].
+    Returns (out, S', z', hist', kwin', vwin', fill') after the first n_commit[b] steps (None: all); the
+    incoming arrays are not modified."""
+    lib = lib or _load()
+    q = _c(q)
+    B, H, kk, d = q.shape
+    k = _c(k, q.shape)
+    v = _c(v, q.shape)
+    w = _c(w)
+    Kc = w.shape[2]
+    w = _c(w, (H, d, Kc))
+    C = int(group)
+    S = np.array(_c(S, (B, H, d, d)), copy=True)
+    z = np.array(_c(z, (B, H, d)), copy=True)
+    hist = np.array(_c(hist, (B, H, Kc - 1, d)), copy=True)
+    kwin = np.array(_c(kwin, (B, H, C, d)), copy=True)
+    vwin = np.array(_c(vwin, (B, H, C, d)), copy=True)
+    fill = np.array(np.ascontiguousarray(fill, dtype=np.int32), copy=True)
+    if fill.shape != (B,):
+        raise ValueError("fill must have shape [B]")
+    nc = None
+    if n_commit is not None:
+        nc = np.ascontiguousarray(n_commit, dtype=np.int32)
+        if nc.shape != (B,):
+            raise ValueError("n_commit must have shape [B]")
+    out = np.empty_like(q)
+    rc = lib.oracle_verify_grouped(B, H, kk, d, Kc, C, float(eps), float(alpha), _p(q), _p(k), _p(v), _p(w),
+                                   _p(S), _p(z), _p(hist), _p(kwin), _p(vwin), fill.ctypes.data_as(_ip),
+                                   None if nc is None else nc.ctypes.data_as(_ip), _p(out))
+    if rc != 0:
+        raise ValueError(f"oracle_verify_grouped rejected its arguments (code {rc})")
+    return out, S, z, hist, kwin, vwin, fill
 
 
 def verify_tree(q, k, v, parent, w, S, z, hist, accept=None, eps=0.0, lib=None):

@@ -392,6 +392,117 @@ int oracle_verify(int B, int H, int kk, int d, int Kc, double eps,
   return 0;
 }
 
+/* ---- generation with the three-branch form (Sec. 4.1 block, Sec. 3 decode phase) ----
+ * One token at a time, per head.  What is carried between tokens: S and z over the
+ * COMPLETED groups only, the conv history, and the raw key and value rows of the
+ * current, still incomplete group (kwin, vwin: [C][d], rows 0..fill-1 in use;
+ * fill is a property of the batch row).  A step with (q, k, v):
+ *   the token joins its group (row fill of the window);
+ *   grouped branch from S, z (none of the current group is in them);
+ *   local branch: softmax over the window rows 0..fill (the token itself included);
+ *   conv over (hist ++ v);  out = alpha * grouped + local + conv;
+ *   if the group is now complete (C rows) its keys and values enter S and z and the
+ *   window starts again from row 0.
+ * This is the same function of the token sequence as grouped_head: a sequence fed
+ * token by token from an empty state gives grouped_head's outputs. */
+static void grouped_step_head(int d, int Kc, int C, double eps, double alpha,
+                              const double *q, const double *k, const double *v,
+                              const double *w, double *S, double *z, double *hist,
+                              double *kwin, double *vwin, int *fill, double *out) {
+  double *fq = (double *)malloc(sizeof(double) * (size_t)d);
+  double *wt = (double *)malloc(sizeof(double) * (size_t)C);
+  int n = *fill;
+  memcpy(kwin + (size_t)n * d, k, sizeof(double) * (size_t)d);
+  memcpy(vwin + (size_t)n * d, v, sizeof(double) * (size_t)d);
+  for (int i = 0; i < d; ++i) fq[i] = oracle_phi(q[i]);
+  double gden = dot(fq, z, d) + eps;
+  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  double top = -INFINITY, mass = 0.0;
+  for (int r = 0; r <= n; ++r) {
+    wt[r] = dot(q, kwin + (size_t)r * d, d) * inv_sqrt_d;
+    if (wt[r] > top) top = wt[r];
+  }
+  for (int r = 0; r <= n; ++r) {
+    wt[r] = exp(wt[r] - top);
+    mass += wt[r];
+  }
+  for (int c = 0; c < d; ++c) {
+    double gnum = 0.0, loc = 0.0;
+    for (int i = 0; i < d; ++i) gnum += fq[i] * S[(size_t)i * d + c];
+    for (int r = 0; r <= n; ++r) loc += wt[r] * vwin[(size_t)r * d + c];
+    double u = w[(size_t)c * Kc + 0] * v[c];
+    for (int j = 1; j < Kc; ++j) u += w[(size_t)c * Kc + j] * hist[(size_t)(Kc - 1 - j) * d + c];
+    out[c] = alpha * (gden != 0.0 ? gnum / gden : 0.0) + loc / mass + u;
+  }
+  for (int r = 0; r + 1 < Kc - 1; ++r)
+    memcpy(hist + (size_t)r * d, hist + (size_t)(r + 1) * d, sizeof(double) * d);
+  if (Kc > 1) memcpy(hist + (size_t)(Kc - 2) * d, v, sizeof(double) * d);
+  n += 1;
+  if (n == C) { /* the group is complete: it becomes part of the sums */
+    for (int r = 0; r < C; ++r)
+      for (int i = 0; i < d; ++i) {
+        double fk = oracle_phi(kwin[(size_t)r * d + i]);
+        z[i] += fk;
+        for (int c = 0; c < d; ++c) S[(size_t)i * d + c] += fk * vwin[(size_t)r * d + c];
+      }
+    n = 0;
+  }
+  *fill = n;
+  free(fq); free(wt);
+}
+
+/* kk draft tokens per head with the three-branch form: kk steps as above from the
+ * same incoming state; all kk outputs are produced; the state handed back (S, z,
+ * hist, kwin, vwin, fill, all updated in place) is the one reached after the first
+ * n_commit[b] steps (NULL: all kk).  fill: [B], each in 0..C-1.  Window rows at or
+ * beyond fill are not read and, unless a kept draft lands on them, not written. */
+int oracle_verify_grouped(int B, int H, int kk, int d, int Kc, int C, double eps,
+                          double alpha, const double *q, const double *k,
+                          const double *v, const double *w, double *S, double *z,
+                          double *hist, double *kwin, double *vwin, int *fill,
+                          const int *n_commit, double *out) {
+  if (B < 0 || H < 1 || kk < 0 || d < 1 || Kc < 1 || C < 1) return 1;
+  for (int b = 0; b < B; ++b) {
+    if (n_commit && (n_commit[b] < 0 || n_commit[b] > kk)) return 2;
+    if (fill[b] < 0 || fill[b] >= C) return 3;
+  }
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d, nw = (size_t)C * d;
+  int *fill_after = (int *)malloc(sizeof(int) * (size_t)(B > 0 ? B : 1));
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    int b = bh / H, h = bh % H;
+    int n = n_commit ? n_commit[b] : kk;
+    size_t o = (size_t)bh * kk * d;
+    double *Sw = (double *)malloc(sizeof(double) * nS);
+    double *zw = (double *)malloc(sizeof(double) * (size_t)d);
+    double *hw = (double *)malloc(sizeof(double) * (nh ? nh : 1));
+    double *kw = (double *)malloc(sizeof(double) * nw);
+    double *vw = (double *)malloc(sizeof(double) * nw);
+    int fw = fill[b];
+    load_state(d, Kc, S + bh * nS, z + (size_t)bh * d, nh ? hist + bh * nh : NULL, Sw, zw, hw);
+    memcpy(kw, kwin + bh * nw, sizeof(double) * nw);
+    memcpy(vw, vwin + bh * nw, sizeof(double) * nw);
+    for (int j = 0; j < kk; ++j) {
+      grouped_step_head(d, Kc, C, eps, alpha, q + o + (size_t)j * d, k + o + (size_t)j * d,
+                        v + o + (size_t)j * d, w + (size_t)h * d * Kc, Sw, zw, hw, kw, vw, &fw,
+                        out + o + (size_t)j * d);
+      if (j + 1 == n) { /* state after the last accepted draft */
+        memcpy(S + bh * nS, Sw, sizeof(double) * nS);
+        memcpy(z + (size_t)bh * d, zw, sizeof(double) * d);
+        if (nh) memcpy(hist + bh * nh, hw, sizeof(double) * nh);
+        memcpy(kwin + bh * nw, kw, sizeof(double) * nw);
+        memcpy(vwin + bh * nw, vw, sizeof(double) * nw);
+        if (h == 0) fill_after[b] = fw;
+      }
+    }
+    if (n == 0 && h == 0) fill_after[b] = fill[b];
+    free(Sw); free(zw); free(hw); free(kw); free(vw);
+  }
+  for (int b = 0; b < B; ++b) fill[b] = fill_after[b];
+  free(fill_after);
+  return 0;
+}
+
 /* One generated token: a verification of a single draft that is always kept. */
 /*
  * Tree-structured verification (Sec. 4.2, "Proposed Solution").  The n candidate

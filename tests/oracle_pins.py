@@ -714,4 +714,94 @@ def pin_grouped_feature_map_touches_the_linear_branch_only(lib=None):
     _close(other[1], np.einsum("bhti,bhtc->bhic", np.maximum(k, 0.0), v), 1e-12, "state under max(x, 0)")
 
 
+# --- generation with the three-branch form ---------------------------------------
+def _empty_grouped_state(B, H, d, Kc, C):
+    return (np.zeros((B, H, d, d)), np.zeros((B, H, d)), np.zeros((B, H, Kc - 1, d)),
+            np.zeros((B, H, C, d)), np.zeros((B, H, C, d)), np.zeros(B, dtype=np.int32))
+
+
+def _window_sums(kwin, vwin, fill, lib=None):
+    """sum of phi(k) v^T and of phi(k) over the window rows in use, per (b, h)"""
+    B, H, C, d = kwin.shape
+    S = np.zeros((B, H, d, d)); z = np.zeros((B, H, d))
+    for b in range(B):
+        fk = oracle.phi(kwin[b, :, :fill[b]], lib=lib) if fill[b] else np.zeros((H, 0, d))
+        S[b] = np.einsum("hti,htc->hic", fk, vwin[b, :, :fill[b]])
+        z[b] = fk.sum(axis=1)
+    return S, z
+
+
+def pin_grouped_steps_reproduce_the_grouped_prefill(lib=None):
+    """Fed token by token, or in blocks of drafts that are all kept, a sequence gives the outputs of the
+    whole-sequence form; what is carried is the state of the completed groups plus the open group's rows."""
+    C = 4
+    q, k, v, w, S0, z0, h0 = _rand(501, B=2, H=2, L=14, d=3, Kc=3, with_state=True)
+    want = oracle.prefill_grouped(q, k, v, w, C, alpha=0.6, S0=S0, z0=z0, hist0=h0, eps=1e-3, lib=lib)
+    for block in (1, 3, 5):
+        st = (S0, z0, h0) + _empty_grouped_state(2, 2, 3, 3, C)[3:]
+        outs = []
+        for t0 in range(0, 14, block):
+            sl = slice(t0, min(t0 + block, 14))
+            r = oracle.verify_grouped(q[:, :, sl], k[:, :, sl], v[:, :, sl], w, C, *st, alpha=0.6, eps=1e-3, lib=lib)
+            outs.append(r[0]); st = r[1:]
+        _close(np.concatenate(outs, axis=2), want[0], 1e-12, f"outputs, blocks of {block}")
+        assert st[5].tolist() == [14 % C] * 2, "rows in the open group"
+        Sw, zw = _window_sums(st[3], st[4], st[5], lib=lib)
+        _close(st[0] + Sw, want[1], 1e-12, "completed groups + open group = running sum (S)")
+        _close(st[1] + zw, want[2], 1e-12, "completed groups + open group = running sum (z)")
+        _close(st[2], want[3], 1e-12, "conv history")
+        _close(st[3][:, :, :2], k[:, :, 12:14], 0, "open group's key rows")
+        _close(st[4][:, :, :2], v[:, :, 12:14], 0, "open group's value rows")
+
+
+def pin_grouped_verify_commit_counts(lib=None):
+    """All outputs are produced whatever is kept; the state is the one after exactly n_commit[b] steps
+    (crossing a group boundary or not); nothing kept = nothing changed, bit for bit."""
+    C, kk = 4, 6
+    r = _rng(502)
+    B, H, d, Kc = 3, 2, 3, 3
+    q, k, v = (r.standard_normal((B, H, kk, d)) for _ in range(3))
+    w = r.standard_normal((H, d, Kc))
+    st = (r.standard_normal((B, H, d, d)), np.abs(r.standard_normal((B, H, d))) + 0.5, r.standard_normal((B, H, Kc - 1, d)),
+          r.standard_normal((B, H, C, d)), r.standard_normal((B, H, C, d)), np.array([1, 3, 0], dtype=np.int32))
+    every = oracle.verify_grouped(q, k, v, w, C, *st, alpha=1.2, eps=1e-3, lib=lib)
+    n_commit = np.array([0, 2, 5], dtype=np.int32)          # row 1 crosses the boundary (3 + 2 > 4), row 2 too (0 + 5)
+    some = oracle.verify_grouped(q, k, v, w, C, *st, n_commit=n_commit, alpha=1.2, eps=1e-3, lib=lib)
+    assert np.array_equal(some[0], every[0]), "outputs depend on what is kept"
+    for b, n in enumerate(n_commit):
+        sb = tuple(a[b:b + 1] for a in st)
+        if n == 0:
+            for got, was in zip(some[1:], st):
+                assert np.array_equal(got[b], was[b]), "nothing kept, yet the state moved"
+            continue
+        ref = oracle.verify_grouped(q[b:b + 1, :, :n], k[b:b + 1, :, :n], v[b:b + 1, :, :n], w, C, *sb, alpha=1.2, eps=1e-3, lib=lib)
+        for i in range(1, 7):
+            _close(some[i][b], ref[i][0], 1e-13, f"row {b}, state item {i}")
+    assert some[6].tolist() == [1, (3 + 2) % C, (0 + 5) % C]
+
+
+def pin_grouped_verify_ignores_rows_beyond_fill_and_later_drafts(lib=None):
+    """Window rows at or beyond fill are not part of the state; a later draft never changes an earlier output."""
+    C, kk = 5, 4
+    r = _rng(503)
+    B, H, d, Kc = 2, 2, 3, 2
+    q, k, v = (r.standard_normal((B, H, kk, d)) for _ in range(3))
+    w = r.standard_normal((H, d, Kc))
+    fill = np.array([2, 4], dtype=np.int32)
+    st = [r.standard_normal((B, H, d, d)), np.abs(r.standard_normal((B, H, d))) + 0.5, r.standard_normal((B, H, Kc - 1, d)),
+          r.standard_normal((B, H, C, d)), r.standard_normal((B, H, C, d)), fill]
+    base = oracle.verify_grouped(q, k, v, w, C, *st, lib=lib)
+    junk = [a.copy() for a in st]
+    for b in range(B):
+        junk[3][b, :, fill[b]:] = 77.0
+        junk[4][b, :, fill[b]:] = -55.0
+    other = oracle.verify_grouped(q, k, v, w, C, *junk, lib=lib)
+    assert np.array_equal(other[0], base[0]), "rows beyond fill were read"
+    q2, k2, v2 = q.copy(), k.copy(), v.copy()
+    q2[:, :, 2:] += 1.0; k2[:, :, 2:] -= 1.0; v2[:, :, 2:] += 2.0
+    later = oracle.verify_grouped(q2, k2, v2, w, C, *st, lib=lib)
+    assert np.array_equal(later[0][:, :, :2], base[0][:, :, :2]), "a later draft leaked backwards"
+    assert np.max(np.abs(later[0][:, :, 3] - base[0][:, :, 3])) > 1e-3
+
+
 ALL_PINS = [obj for name, obj in sorted(globals().items()) if name.startswith("pin_") and callable(obj)]

@@ -68,8 +68,8 @@ MUTANTS = [
     ("grouped_local_not_normalised", "alpha * glob + loc / mass", "alpha * glob + loc"),
     ("grouped_sums_skip_a_groups_first_token", "for (int t = g0; t < g1; ++t)\n      for (int i = 0; i < d; ++i) {\n        double fk = oracle_phi(k[",
      "for (int t = g0 + 1; t < g1; ++t)\n      for (int i = 0; i < d; ++i) {\n        double fk = oracle_phi(k["),
-    ("grouped_normaliser_counts_own_group", "double gden = dot(fq, z, d) + eps;",
-     "double gden = dot(fq, z, d) + eps; for (int i2 = g0; i2 < t; ++i2) for (int f = 0; f < d; ++f) gden += fq[f] * oracle_phi(k[(size_t)i2 * d + f]);"),
+    ("grouped_normaliser_counts_own_group", "any token of this group */\n      double gden = dot(fq, z, d) + eps;",
+     "any token of this group */\n      double gden = dot(fq, z, d) + eps; for (int i2 = g0; i2 < t; ++i2) for (int f = 0; f < d; ++f) gden += fq[f] * oracle_phi(k[(size_t)i2 * d + f]);"),
     ("grouped_linear_branch_uses_raw_q", "fq[i] = oracle_phi(qt[i]);", "fq[i] = qt[i];"),
     ("grouped_local_branch_uses_phi_q", "logit[i - g0] = dot(qt, k + (size_t)i * d, d) * inv_sqrt_d;", "logit[i - g0] = dot(fq, k + (size_t)i * d, d) * inv_sqrt_d;"),
     ("grouped_eps_dropped", "double gden = dot(fq, z, d) + eps;", "double gden = dot(fq, z, d);"),
@@ -77,6 +77,20 @@ MUTANTS = [
     ("grouped_ignores_incoming_state", "load_state(d, Kc, S0, z0, hist0, S, z, hs);", "load_state(d, Kc, NULL, NULL, hist0, S, z, hs);"),
     ("grouped_conv_dropped", "alpha * glob + loc / mass + u[(size_t)t * d + c];", "alpha * glob + loc / mass;"),
     ("grouped_state_uses_raw_k", "double fk = oracle_phi(k[(size_t)t * d + i]);", "double fk = k[(size_t)t * d + i];"),
+    ("gstep_token_not_in_its_own_window", "for (int r = 0; r <= n; ++r)", "for (int r = 0; r < n; ++r)"),
+    ("gstep_closed_group_misses_its_last_token", "for (int r = 0; r < C; ++r)\n      for (int i = 0; i < d; ++i) {\n        double fk = oracle_phi(kwin",
+     "for (int r = 0; r < C - 1; ++r)\n      for (int i = 0; i < d; ++i) {\n        double fk = oracle_phi(kwin"),
+    ("gstep_closed_group_missing_from_z", "double fk = oracle_phi(kwin[(size_t)r * d + i]);\n        z[i] += fk;", "double fk = oracle_phi(kwin[(size_t)r * d + i]);"),
+    ("gstep_closed_group_uses_raw_k", "double fk = oracle_phi(kwin[(size_t)r * d + i]);", "double fk = kwin[(size_t)r * d + i];"),
+    ("gstep_window_not_restarted", "    n = 0;\n  }\n  *fill = n;", "    n = 1;\n  }\n  *fill = n;"),
+    ("gstep_local_branch_uses_phi_q", "wt[r] = dot(q, kwin + (size_t)r * d, d) * inv_sqrt_d;", "wt[r] = dot(fq, kwin + (size_t)r * d, d) * inv_sqrt_d;"),
+    ("gstep_alpha_on_the_local_branch", "alpha * (gden != 0.0 ? gnum / gden : 0.0) + loc / mass + u", "(gden != 0.0 ? gnum / gden : 0.0) + alpha * loc / mass + u"),
+    ("gstep_S_transposed", "for (int i = 0; i < d; ++i) gnum += fq[i] * S[(size_t)i * d + c];\n    for (int r = 0; r <= n; ++r) loc",
+     "for (int i = 0; i < d; ++i) gnum += fq[i] * S[(size_t)c * d + i];\n    for (int r = 0; r <= n; ++r) loc"),
+    ("gverify_fill_not_advanced", "if (h == 0) fill_after[b] = fw;", "if (h == 0) fill_after[b] = fill[b];"),
+    ("gverify_window_not_written_back", "memcpy(kwin + bh * nw, kw, sizeof(double) * nw);", ""),
+    ("gverify_commits_everything", "int n = n_commit ? n_commit[b] : kk;\n    size_t o = (size_t)bh * kk * d;\n    double *Sw = (double *)malloc(sizeof(double) * nS);\n    double *zw = (double *)malloc(sizeof(double) * (size_t)d);\n    double *hw = (double *)malloc(sizeof(double) * (nh ? nh : 1));\n    double *kw",
+     "int n = kk;\n    size_t o = (size_t)bh * kk * d;\n    double *Sw = (double *)malloc(sizeof(double) * nS);\n    double *zw = (double *)malloc(sizeof(double) * (size_t)d);\n    double *hw = (double *)malloc(sizeof(double) * (nh ? nh : 1));\n    double *kw"),
     ("recurrent_ignores_incoming_S", "load_state(d, Kc, S0 ? S0 + bh * nS : NULL, z0", "load_state(d, Kc, NULL, z0"),
 ]
 
