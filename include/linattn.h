@@ -163,6 +163,35 @@ linattn_status linattn_verify(const linattn_desc *desc, int32_t kk,
                               const int32_t *n_commit,
                               void *out, void *hip_stream);
 
+/* Generation with the three-branch form (the block of linattn_prefill_grouped in the
+ * decode phase of Sec. 3; kk > 1: the verification step of Sec. 4.2): kk draft
+ * tokens per (b, h), each scored as linattn_prefill_grouped would score it at
+ * the end of the sequence so far.  The state between calls is
+ *   S, z         in/out  sums over the COMPLETED groups of `chunk` tokens only
+ *   hist         in/out  last Kc-1 value rows (may be NULL only if Kc == 1)
+ *   kwin, vwin   in/out  [B,H,chunk,d] dense, i/o dtype: raw key / value rows of
+ *                        the open group; rows 0 .. fill[b]-1 are in use, the
+ *                        rest is neither read nor (unless a kept draft lands
+ *                        there) written
+ *   fill         in/out  device int32 [B], rows of the open group in use,
+ *                        0 .. chunk-1 (values outside are clamped into it)
+ * A new sequence starts from zeros with fill = 0; after linattn_prefill_grouped
+ * over a multiple of `chunk` tokens its S, z, hist are this state with fill = 0
+ * (a remainder of the prompt goes through this call).  Afterwards the state has
+ * advanced over the first n_commit[b] drafts (NULL: all kk; 0: bit-unchanged);
+ * when they fill the group, its rows enter S and z and the next group opens.
+ *   q, k, v, out [B,H,kk,d] dense, i/o dtype; conv_w [H,d,Kc] float
+ *   n_commit     device int32 [B] or NULL, clamped into 0..kk
+ * 1 <= kk <= LINATTN_MAX_DRAFT; chunk must be 64 (LINATTN_ERR_UNSUPPORTED
+ * otherwise); fp32 and bf16 rows.  Arithmetic is fp32 throughout. */
+linattn_status linattn_verify_grouped(const linattn_desc *desc, int32_t kk, float alpha,
+                                      const void *q, const void *k, const void *v,
+                                      const float *conv_w,
+                                      float *S, float *z, void *hist,
+                                      void *kwin, void *vwin, int32_t *fill,
+                                      const int32_t *n_commit,
+                                      void *out, void *hip_stream);
+
 /* Tree-structured speculative verification (Sec. 4.2, "Proposed Solution": the
  * candidates of a speculation step follow Medusa's tree-based attention
  * pattern; Sec. 5.3 / Tab. 9 use 64 speculated tokens).  n candidate tokens per

@@ -21,7 +21,7 @@ LINATTN_F32, LINATTN_BF16 = 0, 1
 LINATTN_PHI_ELU1, LINATTN_PHI_RELU = 0, 1
 PHI = {"elu1": LINATTN_PHI_ELU1, "relu": LINATTN_PHI_RELU}
 MAX_CONV_K, MAX_DRAFT, MAX_TREE = 8, 16, 64
-SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_grouped", "linattn_verify", "linattn_verify_tree", "linattn_decode",
+SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_grouped", "linattn_verify", "linattn_verify_grouped", "linattn_verify_tree", "linattn_decode",
            "linattn_status_string", "linattn_version")
 
 
@@ -57,6 +57,8 @@ def load():
     lib.linattn_prefill_grouped.argtypes = [dp, i32, ctypes.c_float] + [vp] * 11 + [vp, sz, vp]
     lib.linattn_verify.restype = ctypes.c_int
     lib.linattn_verify.argtypes = [dp, i32] + [vp] * 9 + [vp]
+    lib.linattn_verify_grouped.restype = ctypes.c_int
+    lib.linattn_verify_grouped.argtypes = [dp, i32, ctypes.c_float] + [vp] * 12 + [vp]
     lib.linattn_verify_tree.restype = ctypes.c_int
     lib.linattn_verify_tree.argtypes = [dp, i32] + [vp] * 10 + [vp]
     lib.linattn_decode.restype = ctypes.c_int
@@ -132,6 +134,13 @@ def linattn_verify(desc: Desc, kk, q, k, v, conv_w, S, z, hist, n_commit, out, s
     _check(st, "linattn_verify")
 
 
+def linattn_verify_grouped(desc: Desc, kk, alpha, q, k, v, conv_w, S, z, hist, kwin, vwin, fill, n_commit, out, stream=None) -> None:
+    st = load().linattn_verify_grouped(ctypes.byref(desc), int(kk), float(alpha), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
+                                       _ptr(S), _ptr(z), _ptr(hist), _ptr(kwin), _ptr(vwin), _ptr(fill), _ptr(n_commit),
+                                       _ptr(out), _stream(stream))
+    _check(st, "linattn_verify_grouped")
+
+
 def linattn_verify_tree(desc: Desc, n, q, k, v, parent, conv_w, S, z, hist, accept, out, stream=None) -> None:
     st = load().linattn_verify_tree(ctypes.byref(desc), int(n), _ptr(q), _ptr(k), _ptr(v), _ptr(parent), _ptr(conv_w),
                                     _ptr(S), _ptr(z), _ptr(hist), _ptr(accept), _ptr(out), _stream(stream))
@@ -188,6 +197,32 @@ def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None, phi="elu
     out = torch.empty_like(q)
     S, z, h = state
     linattn_verify(desc, kk, q, k, v, conv_w, S, z, h, n_commit, out, stream)
+    return out
+
+
+def grouped_state(B, H, d, conv_k, dtype=torch.bfloat16, device="cuda", prefill_state=None):
+    """State of the three-branch form for ``verify_grouped``: (S, z, hist, kwin, vwin, fill).  Zeros (start of a
+    sequence), or the (S, z, hist) that ``prefill_grouped`` returned for a multiple of 64 tokens, with an empty
+    open group."""
+    if prefill_state is None:
+        S = torch.zeros((B, H, d, d), dtype=torch.float32, device=device)
+        z = torch.zeros((B, H, d), dtype=torch.float32, device=device)
+        h = torch.zeros((B, H, max(conv_k - 1, 0), d), dtype=dtype, device=device)
+    else:
+        S, z, h = prefill_state
+    kwin = torch.zeros((B, H, 64, d), dtype=dtype, device=device)
+    vwin = torch.zeros((B, H, 64, d), dtype=dtype, device=device)
+    fill = torch.zeros((B,), dtype=torch.int32, device=device)
+    return S, z, h, kwin, vwin, fill
+
+
+def verify_grouped(q, k, v, conv_w, state, alpha=1.0, n_commit=None, eps=0.0, stream=None, phi="elu1"):
+    """q, k, v: dense [B,H,kk,d].  ``state`` = (S, z, hist, kwin, vwin, fill) is updated in place.  Returns out."""
+    B, H, kk, d = q.shape
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=kk, phi=phi)
+    out = torch.empty_like(q)
+    S, z, h, kwin, vwin, fill = state
+    linattn_verify_grouped(desc, kk, alpha, q, k, v, conv_w, S, z, h, kwin, vwin, fill, n_commit, out, stream)
     return out
 
 

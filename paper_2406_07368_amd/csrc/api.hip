@@ -165,6 +165,30 @@ linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* 
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 
+linattn_status linattn_verify_grouped(const linattn_desc* desc, int32_t kk, float alpha, const void* q, const void* k,
+                                      const void* v, const float* conv_w, float* S, float* z, void* hist, void* kwin,
+                                      void* vwin, int32_t* fill, const int32_t* n_commit, void* out, void* hip_stream) {
+  linattn_status st = check_desc(desc, true);     // the group size is part of the result: chunk is checked
+  if (st != LINATTN_OK) return st;
+  if (kk < 1 || kk > LINATTN_MAX_DRAFT) return LINATTN_ERR_SHAPE;
+  if (!(alpha == alpha) || alpha - alpha != 0.f) return LINATTN_ERR_SHAPE;   // NaN, infinity
+  if (!q || !k || !v || !conv_w || !S || !z || !kwin || !vwin || !fill || !out) return LINATTN_ERR_NULL;
+  if (desc->conv_k > 1 && !hist) return LINATTN_ERR_NULL;
+  const void* ptrs[] = {q, k, v, conv_w, S, z, hist, kwin, vwin, out};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LINATTN_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(fill) & 3u) || (reinterpret_cast<uintptr_t>(n_commit) & 3u)) return LINATTN_ERR_ALIGN;
+  if (desc->chunk != 64) return LINATTN_ERR_UNSUPPORTED;
+
+  VerifyGroupedArgs a{};
+  a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;
+  a.kwin = kwin; a.vwin = vwin; a.fill = fill; a.n_commit = n_commit; a.out = out;
+  a.B = desc->B; a.H = desc->H; a.kk = kk; a.Kc = desc->conv_k; a.eps = desc->eps; a.alpha = alpha;
+  a.relu = desc->phi == LINATTN_PHI_RELU;
+  const hipError_t e = launch_verify_grouped(a, desc->io_dtype == LINATTN_BF16, desc->d, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
+}
+
 linattn_status linattn_verify_tree(const linattn_desc* desc, int32_t n, const void* q, const void* k, const void* v,
                                    const int32_t* parent, const float* conv_w, float* S, float* z, void* hist,
                                    const int32_t* accept, void* out, void* hip_stream) {

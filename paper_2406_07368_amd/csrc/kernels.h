@@ -37,6 +37,24 @@ struct VerifyTreeArgs {
   int relu;
 };
 
+struct VerifyGroupedArgs {
+  const void* q;
+  const void* k;
+  const void* v;            // [B,H,kk,d] dense, i/o dtype
+  const float* conv_w;      // [H,d,Kc]
+  float* S;                 // [B,H,d,d] in/out: completed groups only
+  float* z;                 // [B,H,d]   in/out
+  void* hist;               // [B,H,Kc-1,d] in/out, i/o dtype
+  void* kwin;               // [B,H,64,d] in/out, i/o dtype: raw key rows of the open group
+  void* vwin;               // [B,H,64,d] in/out: its value rows
+  int32_t* fill;            // device [B] in/out: rows of the open group in use, 0..63
+  const int32_t* n_commit;  // device [B] or null
+  void* out;                // [B,H,kk,d]
+  int B, H, kk, Kc;
+  float eps, alpha;
+  int relu;
+};
+
 struct PrefillArgs {
   const void* q;
   const void* k;
@@ -66,6 +84,9 @@ hipError_t launch_verify(const VerifyArgs& a, bool bf16, int d, int nsplit, hipS
 // verify_mfma.hip : the same step as one 16-token group on the matrix cores (bf16 drafts, whole heads)
 bool verify_mfma_available(bool bf16, int d, int nsplit, int kk);
 hipError_t launch_verify_mfma(const VerifyArgs& a, int d, hipStream_t st);
+
+// verify_grouped.hip : generation with the three-branch form (state of the completed groups + the open group's rows)
+hipError_t launch_verify_grouped(const VerifyGroupedArgs& a, bool bf16, int d, hipStream_t st);
 
 // verify_tree.hip : candidates arranged as a tree, scored from one read of the state
 hipError_t launch_verify_tree(const VerifyTreeArgs& a, int d, hipStream_t st);

@@ -1,0 +1,380 @@
+// Generation with the three-branch form (Sec. 4.1 block in the decode phase of Sec. 3; with k > 1 the
+// verification step of Sec. 4.2): k draft tokens of one (b, h) are scored from one state, which is
+//   S, z        sums of phi(k) v^T and phi(k) over the COMPLETED groups of 64 tokens (fp32),
+//   hist        the last Kc-1 value rows (conv),
+//   kwin, vwin  the raw key / value rows of the open group, rows 0 .. fill[b]-1 in use.
+// Draft j sits at position P = fill + j of the open group.  Its output is
+//   alpha * phi(q)^T S / (phi(q).z + eps)  +  softmax over the group's rows 0..P of q.k/sqrt(d), times V  +  conv.
+// A draft beyond the end of the group (P >= 64) belongs to the next group: its local branch starts at
+// row 64 and its linear branch sees the group that has just been completed, which is added in the
+// quadratic form (weights phi(q).phi(k_r) on the value rows r < 64) instead of forming S + that group.
+// Memory-bound on the read of S (64 KB per head at d = 128); S is only written when the kept drafts
+// complete the group (once in 64 tokens), so a step moves about half the bytes of the token-level form.
+//
+// One workgroup of 256 threads per (b, h), fp32 arithmetic on the vector ALUs throughout:
+//   1. logits: one wave per row of (window ++ drafts), lanes over features, wave reduction;
+//   2. per draft: softmax over its rows, the linear normaliser, one weight per row in LDS;
+//   3. the state streams through registers once (16-byte nontemporal loads, a few row passes in
+//      flight) for the read-outs phi(q_j)^T S; the value rows are combined with the weights;
+//   4. outputs; 5. the kept drafts join the window, or complete the group and enter S and z.
+// fill[b] is shared by the heads of a batch row, so it is advanced by a second, tiny kernel.
+#include "common.cuh"
+#include "kernels.h"
+
+namespace linattn {
+
+namespace {
+
+constexpr int GC = 64;         // tokens per group
+constexpr int GROWS = GC + 16; // rows of (window ++ drafts) at most (63 + 16), rounded up
+
+template <int D, int KP>
+struct VgScore {
+  float rq[KP][D];            // q_j as it came
+  float fq[D][KP];            // phi(q_j), feature-major: one thread reads all drafts of its state row
+  float red[KP][D];           // phi(q_j)^T S
+  float loc[KP][D];           // sum_r W[j][r] v_r
+};
+template <int D>
+struct VgStage {              // completion of a group: 16 rows of phi(k) and of v at a time
+  float k[16][D];
+  float v[16][D];
+};
+template <int D, int KP>
+struct VgSmem {
+  union {                     // the completion runs when the outputs are done
+    VgScore<D, KP> sc;
+    VgStage<D> st;
+  };
+  float W[KP][GROWS];         // first the logits, then the weight of value row r in the output of draft j
+  float lin[KP][GC];          // phi(q_j).phi(k_r) for the rows of the group being completed
+  float vv[KP][D];            // v_j (conv)
+  float fscale[KP];           // alpha / (phi(q_j).z [+ completed group] + eps), 0 if that denominator is 0
+  float zz[D];
+  float wt[8][D];             // conv taps, tap-major (taps >= Kc are 0)
+  float hh[8][D];             // hh[t]: the value row t+1 positions before the first draft
+};
+
+template <typename Io>
+__device__ __forceinline__ const void* row_of(const void* win, const void* drafts, int64_t win0, int64_t tok0, int D, int n, int r,
+                                              int64_t* idx) {
+  // virtual row r of (window ++ drafts): which array, and the element index of its first element
+  if (r < n) { *idx = win0 + (int64_t)r * D; return win; }
+  *idx = tok0 + (int64_t)(r - n) * D;
+  return drafts;
+}
+
+}  // namespace
+
+// At most 128 registers per thread for up to 8 drafts: four workgroups per compute unit, so that 1024 heads
+// are all resident at once.
+template <typename Io, int D, int KP>
+__global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_grouped_kernel(VerifyGroupedArgs a) {
+  constexpr int CG = D / 4;          // float4 column groups per state row
+  constexpr int RPP = 256 / CG;      // state rows per pass
+  constexpr int NPASS = D / RPP;
+  constexpr int EPL = D / 64;        // features per lane in the logits phase
+  constexpr int NH = 256 / D;        // row partitions in the value phase
+  __shared__ VgSmem<D, KP> sm;
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int bh = blockIdx.x;
+  const int b = bh / a.H, h = bh % a.H;
+  const int kk = a.kk, Kc = a.Kc;
+  const int cg = tid % CG, r0 = tid / CG;
+
+  int n = a.fill[b];
+  n = n < 0 ? 0 : (n > GC - 1 ? GC - 1 : n);                       // rows of the open group
+  int m = kk;
+  if (a.n_commit) { m = a.n_commit[b]; m = m < 0 ? 0 : (m > kk ? kk : m); }
+  const int rows = n + kk;                                          // rows of (window ++ drafts)
+  const bool crossing = rows > GC;                                  // some draft belongs to the next group
+  const int64_t tok0 = (int64_t)bh * kk * D;
+  const int64_t win0 = (int64_t)bh * GC * D;
+  const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
+
+  // ---- 0. the first passes of the state are requested before anything else -----------------------
+  constexpr int PD = NPASS < 4 ? NPASS : 4;
+  const float* Sg = a.S + (size_t)bh * D * D + 4 * cg;
+  f32x4 s[PD];
+#pragma unroll
+  for (int p = 0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D));
+
+  for (int e = tid; e < KP * D; e += 256) {
+    const int j = e / D, i = e % D;
+    float xq = 0.f, xv = 0.f;
+    if (j < kk) { xq = Io::load1(a.q, tok0 + e); xv = Io::load1(a.v, tok0 + e); }
+    sm.sc.rq[j][i] = xq;
+    sm.sc.fq[i][j] = j < kk ? phi_any(xq, a.relu) : 0.f;
+    sm.vv[j][i] = xv;
+    sm.sc.red[j][i] = 0.f;
+    sm.sc.loc[j][i] = 0.f;
+  }
+  if (tid < D) sm.zz[tid] = a.z[(size_t)bh * D + tid];
+  for (int e = tid; e < 16 * D; e += 256) {
+    const int t = (e / D) & 7, cc = e % D;
+    float x = 0.f;
+    if (e < 8 * D) { if (t < Kc) x = a.conv_w[((size_t)h * D + cc) * Kc + t]; }
+    else if (t < Kc - 1) x = Io::load1(a.hist, hist0 + (int64_t)(Kc - 2 - t) * D + cc);
+    if (e < 8 * D) sm.wt[t][cc] = x; else sm.hh[t][cc] = x;
+  }
+  __syncthreads();
+
+  // ---- 1. logits q_j.k_r (raw rows), and phi(q_j).phi(k_r) for the rows of a group being completed ----
+  for (int r = wv; r < rows; r += 4) {
+    int64_t idx;
+    const void* src = row_of<Io>(a.kwin, a.k, win0, tok0, D, n, r, &idx);
+    float x[EPL], fx[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      x[e] = Io::load1(src, idx + lane + 64 * e);
+      fx[e] = phi_any(x[e], a.relu);
+    }
+    const bool need_lin = crossing && r < GC;
+#pragma unroll
+    for (int j = 0; j < KP; ++j) {
+      if (j >= kk) continue;                                        // uniform
+      float dotv = 0.f, lin = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        dotv = fmaf(sm.sc.rq[j][lane + 64 * e], x[e], dotv);
+        lin = fmaf(sm.sc.fq[lane + 64 * e][j], fx[e], lin);
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) dotv += __shfl_xor(dotv, off);
+      if (need_lin) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) lin += __shfl_xor(lin, off);
+      }
+      if (lane == 0) {
+        sm.W[j][r] = dotv;
+        if (need_lin) sm.lin[j][r] = lin;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- 2. per draft: softmax over its rows, the linear normaliser, the weights of the value rows ----
+  static_assert(D == 64 || D == 128, "1 / sqrt(d) below");
+  constexpr float to_log2 = 1.44269504088896340736f * (D == 64 ? 0.125f : 0.08838834764831845f);
+  for (int j = wv; j < kk; j += 4) {
+    const int P = n + j;                                            // position of the draft
+    const int g0 = P < GC ? 0 : GC;                                 // first row of its group
+    float xr[2];                                                    // rows lane and lane + 64
+    float top = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int r = lane + 64 * t;
+      const bool seen = r >= g0 && r <= P;
+      xr[t] = seen ? sm.W[j][r < GROWS ? r : GROWS - 1] : -INFINITY;
+      top = fmaxf(top, xr[t]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) top = fmaxf(top, __shfl_xor(top, off));
+    float mass = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      xr[t] = __builtin_amdgcn_exp2f((xr[t] - top) * to_log2);      // exp2(-inf) = 0: rows that are not seen
+      mass += xr[t];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mass += __shfl_xor(mass, off);
+    // phi(q_j).z, plus the completed group for a draft of the next group
+    float dz = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) dz = fmaf(sm.sc.fq[lane + 64 * e][j], sm.zz[lane + 64 * e], dz);
+    if (g0 > 0) dz += sm.lin[j][lane];                              // GC == 64 rows, one per lane
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) dz += __shfl_xor(dz, off);
+    const float gden = dz + a.eps;
+    const float f = gden != 0.f ? a.alpha / gden : 0.f;
+    const float inv_mass = 1.f / mass;                              // the draft itself is always seen: mass >= 1
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int r = lane + 64 * t;
+      float wgt = xr[t] * inv_mass;
+      if (g0 > 0 && r < GC) wgt = f * sm.lin[j][r];                 // the completed group, through the linear branch
+      if (r < GROWS) sm.W[j][r] = wgt;
+    }
+    if (lane == 0) sm.fscale[j] = f;
+  }
+  __syncthreads();
+
+  // ---- 3a. read-outs phi(q_j)^T S: the state streams through registers once ---------------------
+  {
+    float acc[KP][4];
+#pragma unroll
+    for (int j = 0; j < KP; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[j][e] = 0.f;
+#pragma unroll 1
+    for (int pb = 0; pb < NPASS; pb += PD) {
+#pragma unroll
+      for (int q = 0; q < PD; ++q) {
+        const int p = pb + q;
+        const int i = p * RPP + r0;
+        const f32x4 cur = s[q];
+#pragma unroll
+        for (int j = 0; j < KP; ++j) {
+          const float f = sm.sc.fq[i][j];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[j][e] = fmaf(f, cur[e], acc[j][e]);
+        }
+        if (p + PD < NPASS) s[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)((p + PD) * RPP + r0) * D));
+      }
+    }
+    // threads that share a column group sit CG lanes apart inside a wave; the four waves add up in LDS,
+#pragma unroll
+    for (int off = CG; off < kWave; off <<= 1)
+#pragma unroll
+      for (int j = 0; j < KP; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[j][e] += __shfl_xor(acc[j][e], off);
+    // ... one after the other, so that the sum does not depend on which wave arrives first
+    for (int turn = 0; turn < 4; ++turn) {
+      if (wv == turn && lane < CG) {
+#pragma unroll
+        for (int j = 0; j < KP; ++j) {
+          if (j < kk) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sm.sc.red[j][4 * cg + e] += acc[j][e];
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  // ---- 3b. value rows times their weights: thread = (channel, every NH-th row) ----------------------
+  {
+    const int c = tid % D, part = tid / D;
+    float accl[KP];
+#pragma unroll
+    for (int j = 0; j < KP; ++j) accl[j] = 0.f;
+    for (int r = part; r < rows; r += NH) {
+      int64_t idx;
+      const void* src = row_of<Io>(a.vwin, a.v, win0, tok0, D, n, r, &idx);
+      const float x = Io::load1(src, idx + c);
+#pragma unroll
+      for (int j = 0; j < KP; ++j) accl[j] = fmaf(sm.W[j][r], x, accl[j]);
+    }
+    for (int turn = 0; turn < NH; ++turn) {
+      if (part == turn) {
+#pragma unroll
+        for (int j = 0; j < KP; ++j)
+          if (j < kk) sm.sc.loc[j][c] += accl[j];
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- 4. outputs ---------------------------------------------------------------------------------
+  for (int idx = tid; idx < kk * D; idx += 256) {
+    const int j = idx / D, c = idx % D;
+    float u = 0.f;
+    for (int t = 0; t < Kc; ++t) {
+      // tap t looks t rows back from draft j: another draft if t <= j, else history row (t - j) back
+      const float x = t <= j ? sm.vv[j - t][c] : sm.hh[t - j - 1][c];
+      u = fmaf(sm.wt[t][c], x, u);
+    }
+    Io::store1(a.out, tok0 + idx, fmaf(sm.fscale[j], sm.sc.red[j][c], sm.sc.loc[j][c]) + u);
+  }
+
+  // ---- 5. the kept drafts join the state ----------------------------------------------------------
+  if (m == 0) return;                                               // uniform: nothing kept, nothing changes
+  if (Kc > 1) {
+    for (int c = tid; c < D; c += 256) {
+      for (int r = 0; r < Kc - 1; ++r) {
+        const int sidx = m - (Kc - 1) + r;                          // position in (history ++ kept drafts)
+        const int64_t dst = hist0 + (int64_t)r * D + c;
+        if (sidx >= 0) Io::store1(a.hist, dst, sm.vv[sidx][c]);
+        else Io::store1(a.hist, dst, sm.hh[-sidx - 1][c]);
+      }
+    }
+  }
+  typedef typename Io::elem elem_t;
+  const elem_t* dk = static_cast<const elem_t*>(a.k) + tok0;
+  const elem_t* dv = static_cast<const elem_t*>(a.v) + tok0;
+  elem_t* wk = static_cast<elem_t*>(a.kwin) + win0;
+  elem_t* wvp = static_cast<elem_t*>(a.vwin) + win0;
+  if (n + m < GC) {
+    // the group stays open: drafts 0..m-1 become rows n..n+m-1
+    for (int e = tid; e < m * D; e += 256) {
+      wk[(size_t)n * D + e] = dk[e];
+      wvp[(size_t)n * D + e] = dv[e];
+    }
+    return;
+  }
+  // the group is complete: rows 0..63 of (window ++ drafts) enter S and z, 16 rows at a time through LDS.
+  // Once in 64 tokens: the state slice is walked once per 16 rows (through the cache) rather than held in
+  // registers, which would cost the common path its occupancy.
+  float* Sw = a.S + (size_t)bh * D * D + 4 * cg;
+  float zsum = tid < D ? sm.zz[tid] : 0.f;
+  for (int rb = 0; rb < GC; rb += 16) {
+    __syncthreads();                                                // the previous 16 rows have been used (first turn: the outputs are done)
+    for (int e = tid; e < 16 * D; e += 256) {
+      const int r = rb + e / D, i = e % D;
+      int64_t ik, iv;
+      const void* ksrc = row_of<Io>(a.kwin, a.k, win0, tok0, D, n, r, &ik);
+      const void* vsrc = row_of<Io>(a.vwin, a.v, win0, tok0, D, n, r, &iv);
+      sm.st.k[e / D][i] = phi_any(Io::load1(ksrc, ik + i), a.relu);
+      sm.st.v[e / D][i] = Io::load1(vsrc, iv + i);
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int p = 0; p < NPASS; ++p) {
+      const int i = p * RPP + r0;
+      f32x4 cur = *reinterpret_cast<const f32x4*>(Sw + (size_t)i * D);
+#pragma unroll 4
+      for (int r = 0; r < 16; ++r) {
+        const f32x4 v4 = *reinterpret_cast<const f32x4*>(&sm.st.v[r][4 * cg]);
+        const float kf = sm.st.k[r][i];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cur[e] = fmaf(kf, v4[e], cur[e]);
+      }
+      *reinterpret_cast<f32x4*>(Sw + (size_t)i * D) = cur;
+    }
+    if (tid < D) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) zsum += sm.st.k[r][tid];
+    }
+  }
+  if (tid < D) a.z[(size_t)bh * D + tid] = zsum;
+  __syncthreads();                                                  // every read of the old window rows is done
+  // the next group opens with the kept drafts beyond the completed one: drafts 64-n .. m-1 -> rows 0 ..
+  const int first = GC - n;
+  for (int e = tid; e < (m - first) * D; e += 256) {
+    wk[e] = dk[(size_t)first * D + e];
+    wvp[e] = dv[(size_t)first * D + e];
+  }
+}
+
+// fill[b] <- (fill[b] + kept drafts) mod 64, after every head of the launch has read the old value
+__global__ __launch_bounds__(256) void verify_grouped_fill_kernel(VerifyGroupedArgs a) {
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b >= a.B) return;
+  int n = a.fill[b];
+  n = n < 0 ? 0 : (n > GC - 1 ? GC - 1 : n);
+  int m = a.kk;
+  if (a.n_commit) { m = a.n_commit[b]; m = m < 0 ? 0 : (m > a.kk ? a.kk : m); }
+  if (m > 0) a.fill[b] = (n + m) % GC;
+}
+
+template <typename Io, int D>
+static hipError_t launch_kp(const VerifyGroupedArgs& a, hipStream_t st) {
+  const dim3 grid((unsigned)(a.B * a.H)), block(256);
+  if (a.kk <= 1) hipLaunchKernelGGL((verify_grouped_kernel<Io, D, 1>), grid, block, 0, st, a);
+  else if (a.kk <= 4) hipLaunchKernelGGL((verify_grouped_kernel<Io, D, 4>), grid, block, 0, st, a);
+  else if (a.kk <= 8) hipLaunchKernelGGL((verify_grouped_kernel<Io, D, 8>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((verify_grouped_kernel<Io, D, 16>), grid, block, 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(verify_grouped_fill_kernel, dim3((unsigned)((a.B + 255) / 256)), block, 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_verify_grouped(const VerifyGroupedArgs& a, bool bf16, int d, hipStream_t st) {
+  if (bf16) return d == 128 ? launch_kp<IoBf16, 128>(a, st) : launch_kp<IoBf16, 64>(a, st);
+  return d == 128 ? launch_kp<IoF32, 128>(a, st) : launch_kp<IoF32, 64>(a, st);
+}
+
+}  // namespace linattn

@@ -118,6 +118,31 @@ def test_prefill_grouped_rejects_bad_arguments():
     assert grouped_status(few, L=4096, ws=None, ws_bytes=0) == 6
 
 
+def vgrouped_status(desc, kk=4, alpha=1.0, **over):
+    lib = binding.load()
+    a = dict(q=P, k=P, v=P, conv_w=P, S=P, z=P, hist=P, kwin=P, vwin=P, fill=P, n_commit=None, out=P)
+    a.update(over)
+    return lib.linattn_verify_grouped(ctypes.byref(desc) if desc is not None else None, kk, alpha, a["q"], a["k"], a["v"],
+                                      a["conv_w"], a["S"], a["z"], a["hist"], a["kwin"], a["vwin"], a["fill"],
+                                      a["n_commit"], a["out"], None)
+
+
+def test_verify_grouped_rejects_bad_arguments():
+    d = good_desc()
+    assert vgrouped_status(None) == 1
+    assert vgrouped_status(d, kk=0) == 2
+    assert vgrouped_status(d, kk=17) == 2
+    assert vgrouped_status(d, alpha=float("nan")) == 2
+    assert vgrouped_status(d, kwin=None) == 1
+    assert vgrouped_status(d, fill=None) == 1
+    assert vgrouped_status(d, hist=None) == 1
+    assert vgrouped_status(d, vwin=P + 8) == 4
+    assert vgrouped_status(d, fill=P + 2) == 4
+    assert vgrouped_status(d, n_commit=P + 1) == 4
+    assert vgrouped_status(good_desc(chunk=128)) == 5           # the window is one group of 64 rows
+    assert vgrouped_status(good_desc(d=96)) == 2
+
+
 def verify_status(desc, kk=4, **over):
     lib = binding.load()
     a = dict(q=P, k=P, v=P, conv_w=P, S=P, z=P, hist=P, n_commit=None, out=P)
