@@ -170,11 +170,13 @@ linattn_status linattn_verify(const linattn_desc *desc, int32_t kk,
  *   S, z         in/out  sums over the COMPLETED groups of `chunk` tokens only
  *   hist         in/out  last Kc-1 value rows (may be NULL only if Kc == 1)
  *   kwin, vwin   in/out  [B,H,chunk,d] dense, i/o dtype: raw key / value rows of
- *                        the open group; rows 0 .. fill[b]-1 are in use, the
+ *                        the open group; rows 0 .. fill[b][h]-1 are in use, the
  *                        rest is neither read nor (unless a kept draft lands
  *                        there) written
- *   fill         in/out  device int32 [B], rows of the open group in use,
- *                        0 .. chunk-1 (values outside are clamped into it)
+ *   fill         in/out  device int32 [B,H], rows of the open group in use,
+ *                        0 .. chunk-1 (values outside are clamped into it); the
+ *                        heads of a batch row carry equal values -- one count per
+ *                        head so that each is read and advanced by one owner
  * A new sequence starts from zeros with fill = 0; after linattn_prefill_grouped
  * over a multiple of `chunk` tokens its S, z, hist are this state with fill = 0
  * (a remainder of the prompt goes through this call).  Afterwards the state has

@@ -212,7 +212,7 @@ def grouped_state(B, H, d, conv_k, dtype=torch.bfloat16, device="cuda", prefill_
         S, z, h = prefill_state
     kwin = torch.zeros((B, H, 64, d), dtype=dtype, device=device)
     vwin = torch.zeros((B, H, 64, d), dtype=dtype, device=device)
-    fill = torch.zeros((B,), dtype=torch.int32, device=device)
+    fill = torch.zeros((B, H), dtype=torch.int32, device=device)
     return S, z, h, kwin, vwin, fill
 
 

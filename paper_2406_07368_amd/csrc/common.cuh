@@ -39,8 +39,19 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
 
 // ---- typed access to rows of q/k/v/out/hist ------------------------------------
 // IoF32 / IoBf16: load `8 consecutive elements` as floats, store 8 floats.
+struct F32Raw8 { f32x4 lo, hi; };
+
 struct IoF32 {
   typedef float elem;
+  typedef F32Raw8 raw8;     // 8 elements as they lie in memory: requested early, converted where they are used
+  static __device__ __forceinline__ raw8 load_raw8(const void* base, int64_t idx) {
+    const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + idx);
+    return raw8{p[0], p[1]};
+  }
+  static __device__ __forceinline__ void unpack8(const raw8& r, float (&x)[8]) {
+    x[0] = r.lo[0]; x[1] = r.lo[1]; x[2] = r.lo[2]; x[3] = r.lo[3];
+    x[4] = r.hi[0]; x[5] = r.hi[1]; x[6] = r.hi[2]; x[7] = r.hi[3];
+  }
   static __device__ __forceinline__ void load8(const void* base, int64_t idx, float (&x)[8]) {
     const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + idx);
     f32x4 a = p[0], b = p[1];
@@ -62,6 +73,17 @@ struct IoF32 {
 
 struct IoBf16 {
   typedef uint16_t elem;
+  typedef u32x4 raw8;
+  static __device__ __forceinline__ raw8 load_raw8(const void* base, int64_t idx) {
+    return *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + idx);
+  }
+  static __device__ __forceinline__ void unpack8(const raw8& r, float (&x)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = bf16_lo_to_f32(r[i]);
+      x[2 * i + 1] = bf16_hi_to_f32(r[i]);
+    }
+  }
   static __device__ __forceinline__ void load8(const void* base, int64_t idx, float (&x)[8]) {
     u32x4 r = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + idx);
 #pragma unroll

@@ -47,7 +47,7 @@ struct VerifyGroupedArgs {
   void* hist;               // [B,H,Kc-1,d] in/out, i/o dtype
   void* kwin;               // [B,H,64,d] in/out, i/o dtype: raw key rows of the open group
   void* vwin;               // [B,H,64,d] in/out: its value rows
-  int32_t* fill;            // device [B] in/out: rows of the open group in use, 0..63
+  int32_t* fill;            // device [B,H] in/out: rows of the open group in use, 0..63 (equal over the heads of a row)
   const int32_t* n_commit;  // device [B] or null
   void* out;                // [B,H,kk,d]
   int B, H, kk, Kc;

@@ -2,7 +2,7 @@
 // verification step of Sec. 4.2): k draft tokens of one (b, h) are scored from one state, which is
 //   S, z        sums of phi(k) v^T and phi(k) over the COMPLETED groups of 64 tokens (fp32),
 //   hist        the last Kc-1 value rows (conv),
-//   kwin, vwin  the raw key / value rows of the open group, rows 0 .. fill[b]-1 in use.
+//   kwin, vwin  the raw key / value rows of the open group, rows 0 .. fill[b][h]-1 in use.
 // Draft j sits at position P = fill + j of the open group.  Its output is
 //   alpha * phi(q)^T S / (phi(q).z + eps)  +  softmax over the group's rows 0..P of q.k/sqrt(d), times V  +  conv.
 // A draft beyond the end of the group (P >= 64) belongs to the next group: its local branch starts at
@@ -17,7 +17,8 @@
 //   3. the state streams through registers once (16-byte nontemporal loads, a few row passes in
 //      flight) for the read-outs phi(q_j)^T S; the value rows are combined with the weights;
 //   4. outputs; 5. the kept drafts join the window, or complete the group and enter S and z.
-// fill[b] is shared by the heads of a batch row, so it is advanced by a second, tiny kernel.
+// The count of rows in use is kept per head ([B,H], equal over the heads of a batch row), so that every
+// workgroup owns the one it reads and advances.
 #include "common.cuh"
 #include "kernels.h"
 
@@ -55,6 +56,42 @@ struct VgSmem {
   float hh[8][D];             // hh[t]: the value row t+1 positions before the first draft
 };
 
+// Sums across lanes without the LDS crossbar (hundreds of them per step: as ds_bpermute they were the
+// bottleneck).  Within a row of 16 lanes: DPP modifiers on the add; across rows: the lane-swap instructions.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, false));
+}
+// every lane gets the sum over its group of N consecutive lanes (N = 8 or 16, groups aligned)
+template <int N>
+__device__ __forceinline__ float sum_lanes(float x) {
+  x = dpp_add<0xB1>(x);                 // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                 // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);                // row_half_mirror: the other quad of each 8
+  if (N == 16) x = dpp_add<0x140>(x);   // row_mirror: the other half of each 16
+  return x;
+}
+// x[l] + x[l ^ 8] (rotation by 8 inside a row of 16)
+__device__ __forceinline__ float add_xor8(float x) { return dpp_add<0x128>(x); }
+// x[l] + x[l ^ 16]: rows 0,1 and rows 2,3 of the wave are swapped against each other
+__device__ __forceinline__ float add_xor16(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// x[l] + x[l ^ 32]
+__device__ __forceinline__ float add_xor32(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// x[l] + x[l ^ off] for the strides that occur here
+template <int OFF>
+__device__ __forceinline__ float add_xor(float x) {
+  static_assert(OFF == 8 || OFF == 16 || OFF == 32, "stride");
+  return OFF == 8 ? add_xor8(x) : OFF == 16 ? add_xor16(x) : add_xor32(x);
+}
+
 template <typename Io>
 __device__ __forceinline__ const void* row_of(const void* win, const void* drafts, int64_t win0, int64_t tok0, int D, int n, int r,
                                               int64_t* idx) {
@@ -66,15 +103,14 @@ __device__ __forceinline__ const void* row_of(const void* win, const void* draft
 
 }  // namespace
 
-// At most 128 registers per thread for up to 8 drafts: four workgroups per compute unit, so that 1024 heads
-// are all resident at once.
+// At most 128 registers per thread for up to 8 bf16 drafts: four workgroups per compute unit, so that 1024
+// heads are all resident at once.
 template <typename Io, int D, int KP>
-__global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_grouped_kernel(VerifyGroupedArgs a) {
+__global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 ? 4 : 2)) void verify_grouped_kernel(VerifyGroupedArgs a) {
   constexpr int CG = D / 4;          // float4 column groups per state row
   constexpr int RPP = 256 / CG;      // state rows per pass
   constexpr int NPASS = D / RPP;
-  constexpr int EPL = D / 64;        // features per lane in the logits phase
-  constexpr int NH = 256 / D;        // row partitions in the value phase
+  constexpr int EPL = D / 64;        // features per lane where a wave walks a feature vector
   __shared__ VgSmem<D, KP> sm;
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -83,7 +119,7 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_grouped_kernel(
   const int kk = a.kk, Kc = a.Kc;
   const int cg = tid % CG, r0 = tid / CG;
 
-  int n = a.fill[b];
+  int n = a.fill[bh];                                               // every head carries its own copy of the count
   n = n < 0 ? 0 : (n > GC - 1 ? GC - 1 : n);                       // rows of the open group
   int m = kk;
   if (a.n_commit) { m = a.n_commit[b]; m = m < 0 ? 0 : (m > kk ? kk : m); }
@@ -93,68 +129,123 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_grouped_kernel(
   const int64_t win0 = (int64_t)bh * GC * D;
   const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
 
-  // ---- 0. the first passes of the state are requested before anything else -----------------------
-  constexpr int PD = NPASS < 4 ? NPASS : 4;
+  // ---- 0. every request of the step is issued before anything waits: the small inputs first (they are
+  //         needed first), then this thread's rows of the open group and of the drafts, then the first passes
+  //         of the state.  All of them unconditional (indices past the end are clamped, the data not used),
+  //         so that nothing serialises on a round trip to memory. ----
+  constexpr int CG8 = D / 8;                       // 8-feature pieces per row
+  constexpr int NPART = 256 / CG8;                 // row partitions
+  constexpr int RT = (GROWS + NPART - 1) / NPART;  // rows per thread
+  const int c8 = tid % CG8, part = tid / CG8;
+  // drafts: at most one 8-element piece of q and of v per thread (KP * D / 8 <= 256 pieces)
+  const int pj = tid / CG8;                        // draft of this thread's piece (== part)
+  const int64_t piece = tok0 + (int64_t)(pj < kk ? pj : kk - 1) * D + 8 * c8;
+  const typename Io::raw8 q_raw = Io::load_raw8(a.q, piece);
+  const typename Io::raw8 v_raw = Io::load_raw8(a.v, piece);
+  const float z_reg = a.z[(size_t)bh * D + (tid < D ? tid : 0)];
+  constexpr int TAP_IT = 8 * D / 256;
+  float tap_reg[TAP_IT], hist_reg[TAP_IT];
+#pragma unroll
+  for (int mth = 0; mth < TAP_IT; ++mth) {
+    const int e = tid + 256 * mth;
+    const int t = e / D, cc = e % D;
+    tap_reg[mth] = a.conv_w[((size_t)h * D + cc) * Kc + (t < Kc ? t : 0)];
+    hist_reg[mth] = Kc > 1 ? Io::load1(a.hist, hist0 + (int64_t)(t < Kc - 1 ? Kc - 2 - t : 0) * D + cc) : 0.f;
+  }
+  typename Io::raw8 rk[RT], rv[RT];
+#pragma unroll
+  for (int t = 0; t < RT; ++t) {
+    const int r = part + NPART * t;
+    int64_t idx;
+    const void* src = row_of<Io>(a.kwin, a.k, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
+    rk[t] = Io::load_raw8(src, idx + 8 * c8);
+  }
+#pragma unroll
+  for (int t = 0; t < RT; ++t) {
+    const int r = part + NPART * t;
+    int64_t idx;
+    const void* src = row_of<Io>(a.vwin, a.v, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
+    rv[t] = Io::load_raw8(src, idx + 8 * c8);
+  }
+  constexpr int PDW = KP <= 1 ? 8 : 4;             // row passes in flight (more when the read-outs leave registers free)
+  constexpr int PD = NPASS < PDW ? NPASS : PDW;
   const float* Sg = a.S + (size_t)bh * D * D + 4 * cg;
   f32x4 s[PD];
 #pragma unroll
   for (int p = 0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D));
 
-  for (int e = tid; e < KP * D; e += 256) {
-    const int j = e / D, i = e % D;
-    float xq = 0.f, xv = 0.f;
-    if (j < kk) { xq = Io::load1(a.q, tok0 + e); xv = Io::load1(a.v, tok0 + e); }
-    sm.sc.rq[j][i] = xq;
-    sm.sc.fq[i][j] = j < kk ? phi_any(xq, a.relu) : 0.f;
-    sm.vv[j][i] = xv;
-    sm.sc.red[j][i] = 0.f;
-    sm.sc.loc[j][i] = 0.f;
+  if (pj < KP) {
+    float xq[8], xv[8];
+    Io::unpack8(q_raw, xq);
+    Io::unpack8(v_raw, xv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i = 8 * c8 + e;
+      const bool live = pj < kk;
+      sm.sc.rq[pj][i] = live ? xq[e] : 0.f;
+      sm.sc.fq[i][pj] = live ? phi_any(xq[e], a.relu) : 0.f;
+      sm.vv[pj][i] = live ? xv[e] : 0.f;
+      sm.sc.red[pj][i] = 0.f;
+      sm.sc.loc[pj][i] = live ? phi_any(xq[e], a.relu) : 0.f;   // phi(q_j) once more, draft-major, until step 2 clears it
+    }
   }
-  if (tid < D) sm.zz[tid] = a.z[(size_t)bh * D + tid];
-  for (int e = tid; e < 16 * D; e += 256) {
-    const int t = (e / D) & 7, cc = e % D;
-    float x = 0.f;
-    if (e < 8 * D) { if (t < Kc) x = a.conv_w[((size_t)h * D + cc) * Kc + t]; }
-    else if (t < Kc - 1) x = Io::load1(a.hist, hist0 + (int64_t)(Kc - 2 - t) * D + cc);
-    if (e < 8 * D) sm.wt[t][cc] = x; else sm.hh[t][cc] = x;
+  if (tid < D) sm.zz[tid] = z_reg;
+#pragma unroll
+  for (int mth = 0; mth < TAP_IT; ++mth) {
+    const int e = tid + 256 * mth;
+    const int t = e / D, cc = e % D;
+    sm.wt[t][cc] = t < Kc ? tap_reg[mth] : 0.f;
+    sm.hh[t][cc] = t < Kc - 1 ? hist_reg[mth] : 0.f;
   }
   __syncthreads();
 
-  // ---- 1. logits q_j.k_r (raw rows), and phi(q_j).phi(k_r) for the rows of a group being completed ----
-  for (int r = wv; r < rows; r += 4) {
-    int64_t idx;
-    const void* src = row_of<Io>(a.kwin, a.k, win0, tok0, D, n, r, &idx);
-    float x[EPL], fx[EPL];
+  // ---- 1. logits q_j.k_r (raw rows), and phi(q_j).phi(k_r) for the rows of a group being completed.
+  //         Thread = (8 consecutive features, every NPART-th row) ----
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      x[e] = Io::load1(src, idx + lane + 64 * e);
-      fx[e] = phi_any(x[e], a.relu);
+  for (int jj = 0; jj < KP; ++jj) {
+    if (jj >= kk) continue;                                         // uniform
+    float q8[8];
+    {
+      const f32x4 q0 = *reinterpret_cast<const f32x4*>(&sm.sc.rq[jj][8 * c8]);
+      const f32x4 q1 = *reinterpret_cast<const f32x4*>(&sm.sc.rq[jj][8 * c8 + 4]);
+      q8[0] = q0[0]; q8[1] = q0[1]; q8[2] = q0[2]; q8[3] = q0[3];
+      q8[4] = q1[0]; q8[5] = q1[1]; q8[6] = q1[2]; q8[7] = q1[3];
     }
-    const bool need_lin = crossing && r < GC;
 #pragma unroll
-    for (int j = 0; j < KP; ++j) {
-      if (j >= kk) continue;                                        // uniform
-      float dotv = 0.f, lin = 0.f;
+    for (int t = 0; t < RT; ++t) {
+      const int r = part + NPART * t;
+      float xk[8];
+      Io::unpack8(rk[t], xk);
+      float dotv = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        dotv = fmaf(sm.sc.rq[j][lane + 64 * e], x[e], dotv);
-        lin = fmaf(sm.sc.fq[lane + 64 * e][j], fx[e], lin);
+      for (int e = 0; e < 8; ++e) dotv = fmaf(q8[e], xk[e], dotv);
+      dotv = sum_lanes<CG8>(dotv);
+      if (c8 == 0 && r < rows) sm.W[jj][r] = dotv;
+    }
+    if (crossing) {                                                 // uniform
+      {
+        const f32x4 q0 = *reinterpret_cast<const f32x4*>(&sm.sc.loc[jj][8 * c8]);
+        const f32x4 q1 = *reinterpret_cast<const f32x4*>(&sm.sc.loc[jj][8 * c8 + 4]);
+        q8[0] = q0[0]; q8[1] = q0[1]; q8[2] = q0[2]; q8[3] = q0[3];
+        q8[4] = q1[0]; q8[5] = q1[1]; q8[6] = q1[2]; q8[7] = q1[3];
       }
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) dotv += __shfl_xor(dotv, off);
-      if (need_lin) {
+      for (int t = 0; t < RT; ++t) {
+        const int r = part + NPART * t;
+        float xk[8];
+        Io::unpack8(rk[t], xk);
+        float lin = 0.f;
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) lin += __shfl_xor(lin, off);
-      }
-      if (lane == 0) {
-        sm.W[j][r] = dotv;
-        if (need_lin) sm.lin[j][r] = lin;
+        for (int e = 0; e < 8; ++e) lin = fmaf(q8[e], phi_any(xk[e], a.relu), lin);
+        lin = sum_lanes<CG8>(lin);
+        if (c8 == 0 && r < GC) sm.lin[jj][r] = lin;
       }
     }
   }
   __syncthreads();
 
   // ---- 2. per draft: softmax over its rows, the linear normaliser, the weights of the value rows ----
+  for (int e = tid; e < KP * D; e += 256) sm.sc.loc[e / D][e % D] = 0.f;   // step 1 is done with its copy of phi(q)
   static_assert(D == 64 || D == 128, "1 / sqrt(d) below");
   constexpr float to_log2 = 1.44269504088896340736f * (D == 64 ? 0.125f : 0.08838834764831845f);
   for (int j = wv; j < kk; j += 4) {
@@ -225,11 +316,12 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_grouped_kernel(
     }
     // threads that share a column group sit CG lanes apart inside a wave; the four waves add up in LDS,
 #pragma unroll
-    for (int off = CG; off < kWave; off <<= 1)
+    for (int j = 0; j < KP; ++j)
 #pragma unroll
-      for (int j = 0; j < KP; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[j][e] += __shfl_xor(acc[j][e], off);
+      for (int e = 0; e < 4; ++e) {
+        if (CG <= 16) acc[j][e] = add_xor<16>(acc[j][e]);
+        acc[j][e] = add_xor<32>(acc[j][e]);
+      }
     // ... one after the other, so that the sum does not depend on which wave arrives first
     for (int turn = 0; turn < 4; ++turn) {
       if (wv == turn && lane < CG) {
@@ -244,26 +336,48 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_grouped_kernel(
       __syncthreads();
     }
   }
-  // ---- 3b. value rows times their weights: thread = (channel, every NH-th row) ----------------------
+  // ---- 3b. value rows times their weights, in the arrangement of step 1 (a row past the end has weight 0);
+  //          the partitions of a wave are CG8 lanes apart, the waves add up in LDS in turn ----------------
   {
-    const int c = tid % D, part = tid / D;
-    float accl[KP];
+    constexpr int JB = KP < 4 ? KP : 4;            // drafts at a time
 #pragma unroll
-    for (int j = 0; j < KP; ++j) accl[j] = 0.f;
-    for (int r = part; r < rows; r += NH) {
-      int64_t idx;
-      const void* src = row_of<Io>(a.vwin, a.v, win0, tok0, D, n, r, &idx);
-      const float x = Io::load1(src, idx + c);
+    for (int jb = 0; jb < KP; jb += JB) {
+      float accl[JB][8];
 #pragma unroll
-      for (int j = 0; j < KP; ++j) accl[j] = fmaf(sm.W[j][r], x, accl[j]);
-    }
-    for (int turn = 0; turn < NH; ++turn) {
-      if (part == turn) {
+      for (int j = 0; j < JB; ++j)
 #pragma unroll
-        for (int j = 0; j < KP; ++j)
-          if (j < kk) sm.sc.loc[j][c] += accl[j];
+        for (int e = 0; e < 8; ++e) accl[j][e] = 0.f;
+#pragma unroll
+      for (int t = 0; t < RT; ++t) {
+        const int r = part + NPART * t;
+        float xv[8];
+        Io::unpack8(rv[t], xv);
+#pragma unroll
+        for (int j = 0; j < JB; ++j) {
+          const float wgt = r < GROWS ? sm.W[jb + j][r < GROWS ? r : GROWS - 1] : 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) accl[j][e] = fmaf(wgt, xv[e], accl[j][e]);
+        }
       }
-      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < JB; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (CG8 <= 8) accl[j][e] = add_xor<8>(accl[j][e]);
+          accl[j][e] = add_xor<16>(accl[j][e]);
+          accl[j][e] = add_xor<32>(accl[j][e]);
+        }
+      for (int turn = 0; turn < 4; ++turn) {
+        if (wv == turn && lane < CG8) {
+#pragma unroll
+          for (int j = 0; j < JB; ++j)
+            if (jb + j < kk) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) sm.sc.loc[jb + j][8 * c8 + e] += accl[j][e];
+            }
+        }
+        __syncthreads();
+      }
     }
   }
 
@@ -281,6 +395,7 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_grouped_kernel(
 
   // ---- 5. the kept drafts join the state ----------------------------------------------------------
   if (m == 0) return;                                               // uniform: nothing kept, nothing changes
+  if (tid == 0) a.fill[bh] = (n + m) % GC;                          // read at the top by this workgroup only
   if (Kc > 1) {
     for (int c = tid; c < D; c += 256) {
       for (int r = 0; r < Kc - 1; ++r) {
@@ -348,17 +463,6 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_grouped_kernel(
   }
 }
 
-// fill[b] <- (fill[b] + kept drafts) mod 64, after every head of the launch has read the old value
-__global__ __launch_bounds__(256) void verify_grouped_fill_kernel(VerifyGroupedArgs a) {
-  const int b = blockIdx.x * 256 + threadIdx.x;
-  if (b >= a.B) return;
-  int n = a.fill[b];
-  n = n < 0 ? 0 : (n > GC - 1 ? GC - 1 : n);
-  int m = a.kk;
-  if (a.n_commit) { m = a.n_commit[b]; m = m < 0 ? 0 : (m > a.kk ? a.kk : m); }
-  if (m > 0) a.fill[b] = (n + m) % GC;
-}
-
 template <typename Io, int D>
 static hipError_t launch_kp(const VerifyGroupedArgs& a, hipStream_t st) {
   const dim3 grid((unsigned)(a.B * a.H)), block(256);
@@ -366,9 +470,6 @@ static hipError_t launch_kp(const VerifyGroupedArgs& a, hipStream_t st) {
   else if (a.kk <= 4) hipLaunchKernelGGL((verify_grouped_kernel<Io, D, 4>), grid, block, 0, st, a);
   else if (a.kk <= 8) hipLaunchKernelGGL((verify_grouped_kernel<Io, D, 8>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((verify_grouped_kernel<Io, D, 16>), grid, block, 0, st, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(verify_grouped_fill_kernel, dim3((unsigned)((a.B + 255) / 256)), block, 0, st, a);
   return hipGetLastError();
 }
 
