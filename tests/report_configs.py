@@ -189,6 +189,53 @@ def verify_rows():
     rows.append(f"| tree verify, {n} candidates / {leaves} paths | {t * 1e6:.1f} µs | {tw.B * n / t / 1e6:.2f} M candidate tokens/s | "
                 f"{100 * nbytes / t / HBM:.1f} | - | {t1 * heads * 1e3:.1f} ms | {tn * heads * 1e3:.1f} ms ({threads}) | "
                 f"{worst:.1e} ({len(sample)} heads); out: max abs {extra[0]:.1e}, p99.9 rel {extra[1]:.1e} |")
+    # generation with the three-branch form: one token per head, open groups of 32 rows, on the same completed-group state
+    rng = np.random.default_rng(77)
+    C = 64
+    fill = np.full(wl.B, 32, dtype=np.int32)
+    kwin, vwin = (torch.from_numpy(workloads.round_to_io(rng.standard_normal((wl.B, wl.H, C, wl.d)), "bf16")).to(torch.bfloat16) for _ in range(2))
+    dq, dk, dv = (torch.from_numpy(a).to(torch.bfloat16) for a in workloads.draft_block(wl, 1))
+    gq, gk, gv = dq.cuda(), dk.cuda(), dv.cuda()
+
+    def gstate(st):
+        return (st[0].clone(), st[1].clone(), st[2].clone(), kwin.cuda(), vwin.cuda(),
+                torch.from_numpy(np.repeat(fill[:, None], wl.H, axis=1)).cuda())
+    gs = gstate(state0)
+    out = binding.verify_grouped(gq, gk, gv, gw, gs)
+    torch.cuda.synchronize()
+    worst, extra = 0.0, (0.0, 0.0)
+    for b, h in sample:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        S1, z1, h1 = pre[(b, h)]
+        want = oracle.verify_grouped(host(dq[sl]), host(dk[sl]), host(dv[sl]), w[h:h + 1].numpy(), C, S1, z1, h1,
+                                     host(kwin[sl]), host(vwin[sl]), fill[b:b + 1])
+        worst = max(worst, rel_err(host(out[sl]), want[0]))
+        _, ma, p999 = err_stats(host(out[sl]), want[0])
+        extra = (max(extra[0], ma), max(extra[1], p999))
+    gsets = [gstate(st) for st in sets]
+    desc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, 64, torch.bfloat16, L=1)
+    o = torch.empty_like(gq)
+    nothing = torch.zeros(wl.B, dtype=torch.int32, device="cuda")     # nothing kept: every call sees the same 32 rows
+    i = [0]
+
+    def call_g():
+        S, z, h, kw, vwn, fl = gsets[i[0] % len(gsets)]
+        i[0] += 1
+        binding.linattn_verify_grouped(desc, 1, 1.0, gq, gk, gv, gw, S, z, h, kw, vwn, fl, nothing, o)
+    t = gpu_time(call_g)
+    heads = wl.B * wl.H
+    nbytes = heads * ((wl.d * wl.d + wl.d) * 4 + 2 * 32 * wl.d * 2 + 4 * wl.d * 2 + (wl.conv_k - 1) * wl.d * 2)
+    S1, z1, h1 = pre[sample[0]]
+
+    def run_g_heads(m):
+        a = np.repeat(host(dq[:1, :1]), m, axis=1)
+        kw1 = np.repeat(host(kwin[:1, :1]), m, axis=1)
+        oracle.verify_grouped(a, a, a, np.repeat(w[:1].numpy(), m, axis=0), C, np.repeat(S1, m, axis=1), np.repeat(z1, m, axis=1),
+                              np.repeat(h1, m, axis=1), kw1, kw1, fill[:1])
+    t1, tn = oracle_time(run_g_heads, threads)
+    rows.append(f"| cfg4 shape, three-branch generation step (1 token, 32 rows open, nothing kept) | {t * 1e6:.1f} µs | {wl.B / t / 1e6:.2f} M tokens/s | "
+                f"{100 * nbytes / t / HBM:.1f} | - | {t1 * heads * 1e3:.1f} ms | {tn * heads * 1e3:.1f} ms ({threads}) | "
+                f"{worst:.1e} ({len(sample)} heads; out only); out: max abs {extra[0]:.1e}, p99.9 rel {extra[1]:.1e} |")
     return rows
 
 
