@@ -131,3 +131,39 @@ def test_verify_tree_random_case(seed):
     check(host(state[0]), want[1], TOL["bf16"], what + " S")
     check(host(state[1]), want[2], TOL["bf16"], what + " z")
     assert np.array_equal(host(state[2]), workloads.round_to_io(want[3], "bf16").astype(np.float64)), what + " hist"
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_verify_grouped_random_case(seed):
+    """Generation with the three-branch form: random open-group lengths per batch row (so some rows complete their
+    group and some drafts fall into the next one), random commit counts."""
+    rng = np.random.default_rng(9300 + seed)
+    io = "bf16" if rng.random() < 0.7 else "f32"
+    d, Kc, kk = int(rng.choice([64, 128])), int(rng.integers(1, 9)), int(rng.integers(1, 17))
+    B, H = int(rng.integers(1, 5)), int(rng.integers(1, 6))
+    phi = "relu" if rng.random() < 0.25 else "elu1"
+    eps = 0.05 if phi == "relu" else 1e-3
+    alpha = float(rng.choice([1.0, 0.5, 2.0]))
+    fill = rng.choice([0, 1, 31, 47, 48, 55, 60, 62, 63], size=B).astype(np.int32)
+    n_commit = None if rng.random() < 0.3 else rng.integers(0, kk + 1, size=B).astype(np.int32)
+    what = f"seed {seed}: {io} d{d} Kc{Kc} k{kk} B{B} H{H} {phi} fill={fill.tolist()} keep={'all' if n_commit is None else n_commit.tolist()}"
+    print(what, flush=True)
+    S, z, hist = random_state(rng, B, H, d, Kc, io)
+    kwin, vwin = (workloads.round_to_io(rng.standard_normal((B, H, 64, d)), io) for _ in range(2))
+    q, k, v = (workloads.round_to_io(rng.standard_normal((B, H, kk, d)), io) for _ in range(3))
+    w = workloads.conv_weights(rng, H, d, Kc)
+    with oracle.feature_map(phi):
+        want = oracle.verify_grouped(q, k, v, w, 64, S, z, hist, kwin, vwin, fill, n_commit, alpha=alpha, eps=eps)
+    dt = IO[io]
+    gs = (dev(S), dev(z), dev(hist, dt), dev(kwin, dt), dev(vwin, dt), torch.from_numpy(np.repeat(fill[:, None], H, axis=1)).cuda())
+    nc = None if n_commit is None else torch.from_numpy(n_commit).cuda()
+    out = binding.verify_grouped(dev(q, dt), dev(k, dt), dev(v, dt), dev(w), gs, alpha, nc, eps, phi=phi)
+    torch.cuda.synchronize()
+    check(host(out), want[0], TOL[io], what + " out")
+    check(host(gs[0]), want[1], TOL[io], what + " S")
+    check(host(gs[1]), want[2], TOL[io], what + " z")
+    assert np.array_equal(host(gs[2]), workloads.round_to_io(want[3], io).astype(np.float64)), what + " hist"
+    assert np.array_equal(gs[5].cpu().numpy(), np.repeat(want[6][:, None], H, axis=1)), what + " rows in use"
+    for b, n in enumerate(want[6]):
+        assert np.array_equal(host(gs[3])[b, :, :n], want[4][b, :, :n]), what + " kwin"
+        assert np.array_equal(host(gs[4])[b, :, :n], want[5][b, :, :n]), what + " vwin"
