@@ -185,7 +185,10 @@ linattn_status linattn_verify_grouped(const linattn_desc* desc, int32_t kk, floa
   a.kwin = kwin; a.vwin = vwin; a.fill = fill; a.n_commit = n_commit; a.out = out;
   a.B = desc->B; a.H = desc->H; a.kk = kk; a.Kc = desc->conv_k; a.eps = desc->eps; a.alpha = alpha;
   a.relu = desc->phi == LINATTN_PHI_RELU;
-  const hipError_t e = launch_verify_grouped(a, desc->io_dtype == LINATTN_BF16, desc->d, static_cast<hipStream_t>(hip_stream));
+  const bool bf16 = desc->io_dtype == LINATTN_BF16;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = verify_grouped_mfma_available(bf16, desc->d, kk) ? launch_verify_grouped_mfma(a, desc->d, stream)
+                                                                        : launch_verify_grouped(a, bf16, desc->d, stream);
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 

@@ -152,20 +152,13 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
     tap_reg[mth] = a.conv_w[((size_t)h * D + cc) * Kc + (t < Kc ? t : 0)];
     hist_reg[mth] = Kc > 1 ? Io::load1(a.hist, hist0 + (int64_t)(t < Kc - 1 ? Kc - 2 - t : 0) * D + cc) : 0.f;
   }
-  typename Io::raw8 rk[RT], rv[RT];
+  typename Io::raw8 rk[RT];
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
     const int r = part + NPART * t;
     int64_t idx;
     const void* src = row_of<Io>(a.kwin, a.k, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
     rk[t] = Io::load_raw8(src, idx + 8 * c8);
-  }
-#pragma unroll
-  for (int t = 0; t < RT; ++t) {
-    const int r = part + NPART * t;
-    int64_t idx;
-    const void* src = row_of<Io>(a.vwin, a.v, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
-    rv[t] = Io::load_raw8(src, idx + 8 * c8);
   }
   constexpr int PDW = KP <= 1 ? 8 : 4;             // row passes in flight (more when the read-outs leave registers free)
   constexpr int PD = NPASS < PDW ? NPASS : PDW;
@@ -241,6 +234,16 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
         if (c8 == 0 && r < GC) sm.lin[jj][r] = lin;
       }
     }
+  }
+  // the value rows, in the arrangement of step 1, are needed after the state has streamed: requested now, into the
+  // registers that the key rows leave
+  typename Io::raw8 rv[RT];
+#pragma unroll
+  for (int t = 0; t < RT; ++t) {
+    const int r = part + NPART * t;
+    int64_t idx;
+    const void* src = row_of<Io>(a.vwin, a.v, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
+    rv[t] = Io::load_raw8(src, idx + 8 * c8);
   }
   __syncthreads();
 
