@@ -18,7 +18,7 @@ prefill launches, measured with events on the launch stream inside the timed
 region); the verify/decode step times are reported beside it in microseconds with
 their own HBM roofline; the tree-structured verify (64 candidates) and the three-branch form of
 the prefill with its one-token generation step are timed after the steps and reported as ``tree_verify``,
-``prefill_grouped`` and ``decode_grouped``.  Between steps the verify state rotates over 32 separate
+``prefill_grouped`` and ``verify_grouped`` (one token = decode, and eight drafts).  Between steps the verify state rotates over 32 separate
 state sets (2.1 GB) and the prefill inputs over 2 sets (2.1 GB) so that nothing is
 served from the 256 MB last-level cache.
 
@@ -316,40 +316,45 @@ def main():
 
     gdecode = None
     if do_verify and args.only == "all":
-        # generation with the three-branch form (not part of the step): one token per head on the same 1024 heads,
-        # every open group half full (32 of 64 rows) when the measurement starts; each call takes a state set of
-        # its own and keeps its token, so the groups grow by one row each time a set comes round again
+        # generation with the three-branch form (not part of the step): one token, then eight drafts, per head on the
+        # same 1024 heads, every open group half full (32 of 64 rows) when a measurement starts; each call takes a
+        # state set of its own and keeps its tokens, so the groups grow each time a set comes round again
         fill0 = 32
         wins = [(torch.randn((vw.B, vw.H, 64, vw.d), generator=g, device=dev).to(torch.bfloat16),
                  torch.randn((vw.B, vw.H, 64, vw.d), generator=g, device=dev).to(torch.bfloat16),
                  torch.full((vw.B, vw.H), fill0, dtype=torch.int32, device=dev)) for _ in states]
         gdesc = binding.make_desc(vw.B, vw.H, vw.d, vw.conv_k, 64, torch.bfloat16, L=1)
-        dq, dk, dv, o = drafts[1]
-        ev5, nb_total = [], 0
-        n_warm, n_timed = 10, min(args.steps, 50)
-        for i in range(n_warm + n_timed):
-            S, z, h = states[i % len(states)]
-            kw, vwn, fl = wins[i % len(states)]
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            binding.linattn_verify_grouped(gdesc, 1, 1.0, dq, dk, dv, vwts, S, z, h, kw, vwn, fl, None, o, stream)
-            e1.record(stream)
-            if i >= n_warm:
-                ev5.append((e0, e1))
-                rows_in_use = fill0 + i // len(states)
-                # read: S, z, the rows in use of both windows, q k v, history, taps, count; write: out, the new rows, history, count
-                nb_total += vw.B * vw.H * ((vw.d * vw.d + vw.d) * 4 + 2 * rows_in_use * vw.d * 2 + 3 * vw.d * 2 + vw.d * 2
-                                         + 2 * vw.d * 2 + 2 * (vw.conv_k - 1) * vw.d * 2 + vw.conv_k * vw.d * 4 + 8)
-        stream.synchronize()
-        t_us = [a.elapsed_time(b) * 1e3 for a, b in ev5]
-        t_mean = sum(t_us) / len(t_us)
-        nb = nb_total / len(t_us)
-        gdecode = {"workload": f"B{vw.B} H{vw.H} d{vw.d} bf16, one token per head, open groups {fill0}+ of 64 rows, completed-group "
-                               "state from the 2048-token prefix of cfg4, alpha 1",
-                   "us": {"mean": t_mean, "median": float(np.median(t_us)), "min": min(t_us)},
-                   "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                "frac": nb / t_mean / 1e3 / HBM_PEAK_GBS, "algorithmic_bytes": nb,
-                                "traffic": read_traffic("decode_grouped_cfg4_pmc.txt")}}
+        gdecode = {}
+        for key, kk in (("k1", 1), ("k8", 8)):
+            for _, _, fl in wins:
+                fl.fill_(fill0)
+            dq, dk, dv, o = drafts[kk]
+            ev5, nb_total = [], 0
+            n_warm, n_timed = 10, min(args.steps, 50)
+            for i in range(n_warm + n_timed):
+                S, z, h = states[i % len(states)]
+                kw, vwn, fl = wins[i % len(states)]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                binding.linattn_verify_grouped(gdesc, kk, 1.0, dq, dk, dv, vwts, S, z, h, kw, vwn, fl, None, o, stream)
+                e1.record(stream)
+                if i >= n_warm:
+                    ev5.append((e0, e1))
+                    rows_in_use = fill0 + kk * (i // len(states))
+                    # read: S, z, the rows in use of both windows, q k v, history, taps, count; write: out, the new rows, history, count
+                    nb_total += vw.B * vw.H * ((vw.d * vw.d + vw.d) * 4 + 2 * rows_in_use * vw.d * 2 + 3 * kk * vw.d * 2 + kk * vw.d * 2
+                                             + 2 * kk * vw.d * 2 + 2 * (vw.conv_k - 1) * vw.d * 2 + vw.conv_k * vw.d * 4 + 8)
+            stream.synchronize()
+            t_us = [a.elapsed_time(b) * 1e3 for a, b in ev5]
+            t_mean = sum(t_us) / len(t_us)
+            nb = nb_total / len(t_us)
+            gdecode[key] = {"workload": f"B{vw.B} H{vw.H} d{vw.d} bf16, {kk} token(s) per head, all kept, open groups {fill0}+ of 64 rows, "
+                                        "completed-group state from the 2048-token prefix of cfg4, alpha 1",
+                            "kernel": "verify_grouped_kernel (vector ALUs)" if kk < 4 else "verify_grouped_mfma_kernel",
+                            "us": {"mean": t_mean, "median": float(np.median(t_us)), "min": min(t_us)},
+                            "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": nb / t_mean / 1e3 / HBM_PEAK_GBS, "algorithmic_bytes": nb,
+                                         "traffic": read_traffic(f"verify_grouped_cfg4_{key}_pmc.txt")}}
 
     mean_ms = {n: (sum(a.elapsed_time(b) for a, b in lst) / len(lst)) for n, lst in ev.items() if lst}
     min_ms = {n: min(a.elapsed_time(b) for a, b in lst) for n, lst in ev.items() if lst}
@@ -400,7 +405,7 @@ def main():
         if tree:
             result["tree_verify"] = tree
         if gdecode:
-            result["decode_grouped"] = gdecode
+            result["verify_grouped"] = gdecode
         if not do_prefill:
             result["value"] = us["k8"]["mean"]
             result["unit"] = "us/step (verify k=8)"

@@ -88,7 +88,7 @@ hipError_t launch_verify_mfma(const VerifyArgs& a, int d, hipStream_t st);
 // verify_grouped.hip : generation with the three-branch form (state of the completed groups + the open group's rows)
 hipError_t launch_verify_grouped(const VerifyGroupedArgs& a, bool bf16, int d, hipStream_t st);
 
-// verify_grouped_mfma.hip : the same step on the matrix cores (bf16 drafts, two or more of them)
+// verify_grouped_mfma.hip : the same step on the matrix cores (bf16 drafts, four or more of them)
 bool verify_grouped_mfma_available(bool bf16, int d, int kk);
 hipError_t launch_verify_grouped_mfma(const VerifyGroupedArgs& a, int d, hipStream_t st);
 

@@ -1,4 +1,4 @@
-// Generation with the three-branch form on the matrix cores: k >= 2 bf16 drafts per head (Sec. 4.1 block,
+// Generation with the three-branch form on the matrix cores: k >= 4 bf16 drafts per head (Sec. 4.1 block,
 // Sec. 4.2 verification).  Same function as verify_grouped.hip, whose vector-ALU arithmetic is the bound
 // from a few drafts on; here the three contractions are MFMAs:
 //
@@ -380,8 +380,9 @@ static hipError_t launch_vgm(const VerifyGroupedArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-// bf16 drafts, from two of them on; one draft is faster on the vector ALUs (fewer fixed steps, four workgroups per CU).
-bool verify_grouped_mfma_available(bool bf16, int d, int kk) { return bf16 && kk >= 2 && kk <= 16 && (d == 64 || d == 128); }
+// bf16 drafts, from four of them on; below that the vector-ALU kernel is as fast or faster (fewer fixed steps, four
+// workgroups per CU instead of two).
+bool verify_grouped_mfma_available(bool bf16, int d, int kk) { return bf16 && kk >= 4 && kk <= 16 && (d == 64 || d == 128); }
 
 hipError_t launch_verify_grouped_mfma(const VerifyGroupedArgs& a, int d, hipStream_t st) {
   return d == 128 ? launch_vgm<128>(a, st) : launch_vgm<64>(a, st);
