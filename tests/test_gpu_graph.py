@@ -101,3 +101,47 @@ def test_prefill_replays_as_a_graph(grouped):
         torch.cuda.synchronize()
         for a, b in zip(got, want):
             assert torch.equal(a, b), f"replay {replay} differs from the eager call"
+
+
+def test_three_branch_generation_replays_as_a_graph():
+    """A decode step and an eight-draft step of the three-branch form (vector-ALU and matrix-core kernels) captured
+    once and replayed: the open groups grow, and on the later replays they are completed and re-opened."""
+    B, H, d, Kc = 8, 32, 128, 3
+    rng = np.random.default_rng(72)
+    gw = dev(workloads.conv_weights(rng, H, d, Kc))
+    q1, k1, v1 = (dev(workloads.round_to_io(rng.standard_normal((B, H, 1, d)), "bf16"), BF) for _ in range(3))
+    q8, k8, v8 = (dev(workloads.round_to_io(rng.standard_normal((B, H, 8, d)), "bf16"), BF) for _ in range(3))
+    n_commit = torch.from_numpy((np.arange(B) % 9).astype(np.int32)).cuda()
+    desc = binding.make_desc(B, H, d, Kc, 64, BF, L=1)
+
+    def new_state():
+        st = list(binding.grouped_state(B, H, d, Kc, BF))
+        st[5].fill_(40)                                   # 40 rows in use: the third replay completes some groups
+        torch.manual_seed(5)
+        st[3].copy_(torch.randn(st[3].shape, device="cuda").to(BF))
+        st[4].copy_(torch.randn(st[4].shape, device="cuda").to(BF))
+        st[1].fill_(3.0)
+        return st
+
+    def steps(st, o):
+        binding.linattn_verify_grouped(desc, 1, 1.0, q1, k1, v1, gw, *st, None, o[0])
+        binding.linattn_verify_grouped(desc, 8, 1.0, q8, k8, v8, gw, *st, n_commit, o[1])
+
+    graph_state, eager_state = new_state(), new_state()
+    outs = [torch.empty_like(q1), torch.empty_like(q8)]
+    eager_outs = [torch.empty_like(o) for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        steps(graph_state, outs)
+    torch.cuda.synchronize()
+    for replay in range(5):
+        g.replay()
+        steps(eager_state, eager_outs)
+        torch.cuda.synchronize()
+        for a, b in zip(outs, eager_outs):
+            assert torch.equal(a, b), f"replay {replay}: outputs differ from the eager calls"
+        for a, b in zip(graph_state, eager_state):
+            assert torch.equal(a, b), f"replay {replay}: state differs from the eager calls"
+    assert int(graph_state[5].min()) < 40                 # some groups were completed and re-opened
