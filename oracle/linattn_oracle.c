@@ -23,6 +23,12 @@
  *   j is the verified history followed by drafts <= j (the paper's example:
  *   kernel 3 at step t1 must cover {t0, t1}).
  *
+ *   The three-branch form of Sec. 4.1 as its text states it (grouped linear
+ *   attention over the groups before a token's own, softmax attention inside the
+ *   group, masked DWConv, weight alpha), for a whole sequence
+ *   (oracle_prefill_grouped) and token by token with the state that generation
+ *   carries (oracle_verify_grouped).
+ *
  * Readings where the paper is silent (all are stated in the design notes of
  * the repository): phi(x) = elu(x)+1; the row normaliser; eps added to the
  * denominator; out = Y + U with no mixing weight; conv weights [H, d, Kc]
@@ -47,7 +53,9 @@
  * under perturbation, chunk/split invariance, verify == k decode steps; for the
  * grouped form of Sec. 4.1: one group = a library softmax attention, one-token groups =
  * the token-level form shifted by one token, a closed-form example, shift invariance
- * of the logits, the weight alpha, splits at group boundaries, causality.
+ * of the logits, the weight alpha, splits at group boundaries, causality; token steps
+ * of that form reproduce the whole-sequence form, commit counts across group
+ * boundaries, blindness to rows beyond the count.
  * No function here is "parity unpinned" with respect to those properties; the
  * paper prints no numeric output of the operator, so there is no printed
  * value to compare with.
