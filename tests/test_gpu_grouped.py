@@ -107,7 +107,7 @@ def test_continuation_at_a_group_boundary():
 
 
 def test_full_size_llama_shape_on_sampled_heads():
-    """B8 H32 L8192 d128 token-major, the launch the bench times: three heads against the oracle."""
+    """B8 H32 L4096 d128 token-major, the launch the bench times: three heads against the oracle."""
     wl = workloads.CONFIGS["cfg3_llama7b_prefill"]
     q, k, v, w = workloads.prefill_tensors(wl)
     tm = [t.transpose(1, 2).contiguous().cuda().transpose(1, 2) for t in (q, k, v)]
