@@ -786,6 +786,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   };
 
   for (int ci = 0; ci < nchunks; ++ci) group(ci);
+#undef LINATTN_FENCE
 
   // ---- hand the state over ---------------------------------------------------------------------------
   if (STATE_ONLY) {

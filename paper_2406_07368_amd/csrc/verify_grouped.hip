@@ -92,7 +92,6 @@ __device__ __forceinline__ float add_xor(float x) {
   return OFF == 8 ? add_xor8(x) : OFF == 16 ? add_xor16(x) : add_xor32(x);
 }
 
-template <typename Io>
 __device__ __forceinline__ const void* row_of(const void* win, const void* drafts, int64_t win0, int64_t tok0, int D, int n, int r,
                                               int64_t* idx) {
   // virtual row r of (window ++ drafts): which array, and the element index of its first element
@@ -157,7 +156,7 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
   for (int t = 0; t < RT; ++t) {
     const int r = part + NPART * t;
     int64_t idx;
-    const void* src = row_of<Io>(a.kwin, a.k, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
+    const void* src = row_of(a.kwin, a.k, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
     rk[t] = Io::load_raw8(src, idx + 8 * c8);
   }
   constexpr int PDW = KP <= 1 ? 8 : 4;             // row passes in flight (more when the read-outs leave registers free)
@@ -242,7 +241,7 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
   for (int t = 0; t < RT; ++t) {
     const int r = part + NPART * t;
     int64_t idx;
-    const void* src = row_of<Io>(a.vwin, a.v, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
+    const void* src = row_of(a.vwin, a.v, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
     rv[t] = Io::load_raw8(src, idx + 8 * c8);
   }
   __syncthreads();
@@ -432,8 +431,8 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
     for (int e = tid; e < 16 * D; e += 256) {
       const int r = rb + e / D, i = e % D;
       int64_t ik, iv;
-      const void* ksrc = row_of<Io>(a.kwin, a.k, win0, tok0, D, n, r, &ik);
-      const void* vsrc = row_of<Io>(a.vwin, a.v, win0, tok0, D, n, r, &iv);
+      const void* ksrc = row_of(a.kwin, a.k, win0, tok0, D, n, r, &ik);
+      const void* vsrc = row_of(a.vwin, a.v, win0, tok0, D, n, r, &iv);
       sm.st.k[e / D][i] = phi_any(Io::load1(ksrc, ik + i), a.relu);
       sm.st.v[e / D][i] = Io::load1(vsrc, iv + i);
     }
