@@ -134,7 +134,9 @@ linattn_status linattn_prefill(const linattn_desc *desc, int32_t L,
  * linattn_workspace_bytes); the state handed back is the same running sum.  To
  * continue a sequence with the same grouping, cut it at multiples of `chunk`.
  *   alpha        finite (LINATTN_ERR_SHAPE otherwise)
- * io_dtype must be LINATTN_BF16 and chunk 64 (LINATTN_ERR_UNSUPPORTED otherwise). */
+ * chunk must be 64 (LINATTN_ERR_UNSUPPORTED otherwise).  bf16 rows run on the
+ * matrix cores; fp32 rows on a plain fp32 kernel that is exact to fp32 rounding
+ * but not built for speed. */
 linattn_status linattn_prefill_grouped(const linattn_desc *desc, int32_t L, float alpha,
                                        const void *q, const void *k, const void *v,
                                        const float *conv_w,

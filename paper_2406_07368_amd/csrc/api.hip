@@ -65,8 +65,8 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
   if (L < 0) return LINATTN_ERR_SHAPE;
   if (grouped) {
     if (!(alpha == alpha) || alpha - alpha != 0.f) return LINATTN_ERR_SHAPE;   // NaN, infinity
-    // the groups are part of the result here: only the kernel's own group of 64 tokens, bf16 rows
-    if (desc->io_dtype != LINATTN_BF16 || desc->chunk != 64) return LINATTN_ERR_UNSUPPORTED;
+    // the groups are part of the result here: only the kernels' own group of 64 tokens
+    if (desc->chunk != 64) return LINATTN_ERR_UNSUPPORTED;
   }
   if (!conv_w) return LINATTN_ERR_NULL;
   if (L > 0 && (!q || !k || !v || !out)) return LINATTN_ERR_NULL;
@@ -95,6 +95,7 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
   a.alpha = alpha;
   hipError_t e;
   if (plan.mfma && L > 0) e = launch_prefill_mfma(a, desc->d, desc->chunk, grouped, stream);
+  else if (grouped && L > 0) e = launch_prefill_grouped_simt(a, desc->d, stream);      // fp32 rows
   else e = launch_prefill_simt(a, desc->io_dtype == LINATTN_BF16, desc->d, stream);   // L = 0: the state is handed through
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }

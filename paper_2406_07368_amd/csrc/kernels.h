@@ -97,6 +97,8 @@ hipError_t launch_verify_tree(const VerifyTreeArgs& a, int d, hipStream_t st);
 
 // prefill_simt.hip : fp32 arithmetic on the vector ALUs, one workgroup per (b, h)
 hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st);
+// ... and the three-branch form for fp32 rows (groups of 64 tokens, a.alpha)
+hipError_t launch_prefill_grouped_simt(const PrefillArgs& a, int d, hipStream_t st);
 
 // prefill_mfma.hip : launch plan of the bf16 prefill (segments, prefix sum over segment states)
 int prefill_mfma_pick_segments(int BH, int L, int chunk);

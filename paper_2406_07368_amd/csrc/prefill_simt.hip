@@ -143,6 +143,187 @@ __global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
     }
 }
 
+// The three-branch form (grouped linear attention over the groups before a token's own, weight alpha + causal
+// softmax attention inside its group of 64 + masked conv) with fp32 arithmetic: the path for fp32 rows.  One
+// workgroup walks one (b, h) group by group and, inside a group, token by token; S and z are only advanced at
+// the end of a group, which is exactly what the linear branch is defined on.  Not tuned for throughput.
+namespace {
+constexpr int GC = 64;     // tokens per group
+template <int D>
+struct GroupedSimtLayout {
+  static constexpr int S = 0;                         // [D][D]
+  static constexpr int KR = S + D * D;                // [GC][D+1] raw key rows of the group
+  static constexpr int VV = KR + GC * (D + 1);        // [HMAX+GC][D]: history rows, then the group's value rows
+  static constexpr int QR = VV + (HMAX + GC) * D;     // [D] raw q_t
+  static constexpr int FQ = QR + D;                   // [D] phi(q_t)
+  static constexpr int LG = FQ + D;                   // [GC] logits, then weights
+  static constexpr int PART = LG + GC;                // [256 / D][D] partial outputs
+  static constexpr int ZZ = PART + 256;               // [D]
+  static constexpr int SCAL = ZZ + D;                 // [4]
+  static constexpr int TOTAL = SCAL + 4;
+};
+}  // namespace
+
+template <typename Io, int D>
+__global__ __launch_bounds__(256) void prefill_grouped_simt_kernel(PrefillArgs a) {
+  using Lay = GroupedSimtLayout<D>;
+  constexpr int NG = 256 / D;
+  extern __shared__ float sm[];
+  float* S = sm + Lay::S;
+  float* kr = sm + Lay::KR;
+  float* vv = sm + Lay::VV;
+  float* qr = sm + Lay::QR;
+  float* fq = sm + Lay::FQ;
+  float* lg = sm + Lay::LG;
+  float* part = sm + Lay::PART;
+  float* zz = sm + Lay::ZZ;
+  float* scal = sm + Lay::SCAL;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
+  const int Kc = a.Kc, L = a.L;
+  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const int c = tid % D, tg = tid / D;
+  static_assert(D == 64 || D == 128, "1 / sqrt(d) below");
+  constexpr float inv_sqrt_d = D == 64 ? 0.125f : 0.08838834764831845f;
+
+  float wreg[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) wreg[j] = j < Kc ? a.conv_w[((size_t)h * D + c) * Kc + j] : 0.f;
+  for (int e = tid; e < D * D; e += 256) S[e] = a.S_in ? a.S_in[(size_t)bh * D * D + e] : 0.f;
+  if (tid < D) zz[tid] = a.z_in ? a.z_in[(size_t)bh * D + tid] : 0.f;
+  for (int e = tid; e < HMAX * D; e += 256) {
+    const int row = e / D, cc = e % D;
+    const int r = row - (HMAX - (Kc - 1));   // row of the incoming history, oldest first
+    vv[e] = (r >= 0 && a.hist_in) ? Io::load1(a.hist_in, ((int64_t)bh * (Kc - 1) + r) * D + cc) : 0.f;
+  }
+  __syncthreads();
+
+  for (int t0 = 0; t0 < L; t0 += GC) {
+    const int nt = (L - t0) < GC ? (L - t0) : GC;
+    // a. the group's raw key and value rows
+    for (int c8 = tid; c8 < nt * (D / 8); c8 += 256) {
+      const int t = c8 / (D / 8), i0 = (c8 % (D / 8)) * 8;
+      float xk[8], xv[8];
+      const int64_t off = base + (int64_t)(t0 + t) * a.st + i0;
+      Io::load8(a.k, off, xk);
+      Io::load8(a.v, off, xv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        kr[t * (D + 1) + i0 + e] = xk[e];
+        vv[(HMAX + t) * D + i0 + e] = xv[e];
+      }
+    }
+    __syncthreads();
+    for (int t = 0; t < nt; ++t) {
+      // b. the token's query, raw and under the feature map
+      if (tid < D) {
+        const float x = Io::load1(a.q, base + (int64_t)(t0 + t) * a.st + tid);
+        qr[tid] = x;
+        fq[tid] = phi_any(x, a.relu);
+      }
+      __syncthreads();
+      // c. logits against the group's rows up to the token (four lanes per row); the linear normaliser
+      {
+        const int i = tid / 4, sub = tid % 4;
+        float acc = 0.f;
+        if (i <= t) {
+          const float* y = kr + i * (D + 1) + sub * (D / 4);
+          const float* x = qr + sub * (D / 4);
+#pragma unroll 8
+          for (int f = 0; f < D / 4; ++f) acc = fmaf(x[f], y[f], acc);
+        }
+        acc += __shfl_xor(acc, 1);
+        acc += __shfl_xor(acc, 2);
+        if (sub == 0) lg[i] = acc * inv_sqrt_d;
+        if (tid >= 192) {                       // the last wave: phi(q_t).z
+          float dz = 0.f;
+          for (int f = lane; f < D; f += 64) dz = fmaf(fq[f], zz[f], dz);
+#pragma unroll
+          for (int off = 32; off >= 1; off >>= 1) dz += __shfl_xor(dz, off);
+          if (lane == 0) {
+            const float gden = dz + a.eps;
+            scal[0] = gden != 0.f ? a.alpha / gden : 0.f;
+          }
+        }
+      }
+      __syncthreads();
+      // d. softmax over rows 0..t (one wave, one row per lane)
+      if (tid < 64) {
+        const float x = tid <= t ? lg[tid] : -INFINITY;
+        float top = x;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) top = fmaxf(top, __shfl_xor(top, off));
+        const float p = tid <= t ? __expf(x - top) : 0.f;
+        float mass = p;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mass += __shfl_xor(mass, off);
+        lg[tid] = p / mass;
+      }
+      __syncthreads();
+      // e. both branches for channel c, the features / rows dealt out over the NG thread groups
+      {
+        float lin = 0.f, loc = 0.f;
+        for (int i = tg; i < D; i += NG) lin = fmaf(fq[i], S[i * D + c], lin);
+        for (int s2 = tg; s2 <= t; s2 += NG) loc = fmaf(lg[s2], vv[(HMAX + s2) * D + c], loc);
+        part[tg * D + c] = fmaf(scal[0], lin, loc);
+      }
+      __syncthreads();
+      if (tid < D) {
+        float y = 0.f;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) y += part[g * D + tid];
+        float u = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (j < Kc) u = fmaf(wreg[j], vv[(HMAX + t - j) * D + tid], u);
+        Io::store1(a.out, base + (int64_t)(t0 + t) * a.st + tid, y + u);
+      }
+      // the next token's step b writes qr, fq (read in c, e: both behind barriers by then) -- no barrier needed here
+      // except for lg and part, which the next token's c and e write after their own barriers
+    }
+    __syncthreads();
+    // f. the group enters the sums: S += phi(K)^T V, z += colsum phi(K); the history slides forward by nt rows
+    for (int i = tg; i < D; i += NG) {
+      float acc = S[i * D + c];
+      for (int s2 = 0; s2 < nt; ++s2) acc = fmaf(phi_any(kr[s2 * (D + 1) + i], a.relu), vv[(HMAX + s2) * D + c], acc);
+      S[i * D + c] = acc;
+    }
+    if (tid < D) {
+      float zs = zz[tid];
+      for (int s2 = 0; s2 < nt; ++s2) zs += phi_any(kr[s2 * (D + 1) + tid], a.relu);
+      zz[tid] = zs;
+      for (int r = 0; r < HMAX; ++r) vv[r * D + tid] = vv[(r + nt) * D + tid];
+    }
+    __syncthreads();
+  }
+
+  if (a.S_out)
+    for (int e = tid; e < D * D; e += 256) a.S_out[(size_t)bh * D * D + e] = S[e];
+  if (a.z_out && tid < D) a.z_out[(size_t)bh * D + tid] = zz[tid];
+  if (a.hist_out)
+    for (int e = tid; e < (Kc - 1) * D; e += 256) {
+      const int r = e / D, cc = e % D;
+      Io::store1(a.hist_out, ((int64_t)bh * (Kc - 1) + r) * D + cc, vv[(HMAX - (Kc - 1) + r) * D + cc]);
+    }
+}
+
+template <typename Io, int D>
+static hipError_t launch_grouped_one(const PrefillArgs& a, hipStream_t st) {
+  constexpr size_t bytes = sizeof(float) * GroupedSimtLayout<D>::TOTAL;
+  static_assert(bytes <= 160 * 1024, "LDS");
+  auto kern = prefill_grouped_simt_kernel<Io, D>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H)), dim3(256), bytes, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill_grouped_simt(const PrefillArgs& a, int d, hipStream_t st) {
+  return d == 128 ? launch_grouped_one<IoF32, 128>(a, st) : launch_grouped_one<IoF32, 64>(a, st);
+}
+
 template <typename Io, int D>
 static hipError_t launch_one(const PrefillArgs& a, hipStream_t st) {
   constexpr size_t bytes = sizeof(float) * SimtLayout<D>::TOTAL;

@@ -110,7 +110,6 @@ def test_prefill_grouped_rejects_bad_arguments():
     assert grouped_status(d, k=None) == 1
     assert grouped_status(d, out=P + 8) == 4
     assert grouped_status(d, S_in=P) == 1
-    assert grouped_status(good_desc(io_dtype=binding.LINATTN_F32)) == 5     # bf16 rows only
     assert grouped_status(good_desc(chunk=128)) == 5                        # the group is part of the result: 64 only
     assert grouped_status(good_desc(chunk=32)) == 2
     few = binding.make_desc(1, 2, 128, 3, 64, L=4096)                       # segmented: needs the workspace

@@ -13,15 +13,15 @@ pytestmark = pytest.mark.gpu
 BF = torch.bfloat16
 
 
-def run_gpu(q, k, v, w, state, alpha, eps=0.0, phi="elu1"):
-    st = None if state is None else (dev(state[0]), dev(state[1]), dev(state[2], BF))
-    out, (S, z, h) = binding.prefill_grouped(dev(q, BF), dev(k, BF), dev(v, BF), dev(w), alpha, st, eps, phi=phi)
+def run_gpu(q, k, v, w, state, alpha, eps=0.0, phi="elu1", dt=BF):
+    st = None if state is None else (dev(state[0]), dev(state[1]), dev(state[2], dt))
+    out, (S, z, h) = binding.prefill_grouped(dev(q, dt), dev(k, dt), dev(v, dt), dev(w), alpha, st, eps, phi=phi)
     torch.cuda.synchronize()
     return host(out), host(S), host(z), host(h)
 
 
-def compare(got, want, what=""):
-    tol = TOL["bf16"]
+def compare(got, want, what="", io="bf16"):
+    tol = TOL[io]
     e = check(got[0], want[0], tol, what + " out")
     check(got[1], want[1], tol, what + " S")
     check(got[2], want[2], tol, what + " z")
@@ -41,6 +41,20 @@ def test_grouped_matches_oracle_small(d, alpha, L, Kc, with_state):
     want = oracle.prefill_grouped(q, k, v, w, 64, alpha=alpha, eps=1e-3, **args)
     got = run_gpu(q, k, v, w, state, alpha, eps=1e-3)
     compare(got, want, f"L={L} d={d} alpha={alpha}")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("L,Kc,with_state,phi", [(1, 3, False, "elu1"), (64, 1, True, "elu1"), (65, 5, True, "relu"), (200, 8, False, "elu1"),
+                                                 (130, 3, True, "elu1")])
+def test_grouped_fp32_rows_match_the_oracle_to_1e4(d, L, Kc, with_state, phi):
+    """fp32 rows take a plain fp32 kernel: the three-branch form against the oracle at the fp32 bar."""
+    B, H = 2, 2
+    q, k, v, w, state = small_case(5050 + L + d + Kc, B, H, L, d, Kc, "f32", with_state)
+    args = {} if state is None else dict(S0=state[0], z0=state[1], hist0=state[2])
+    with oracle.feature_map(phi):
+        want = oracle.prefill_grouped(q, k, v, w, 64, alpha=0.7, eps=1e-2, **args)
+    got = run_gpu(q, k, v, w, state, 0.7, eps=1e-2, phi=phi, dt=torch.float32)
+    compare(got, want, f"fp32 L={L} d={d}", io="f32")
 
 
 @pytest.mark.parametrize("d", [64, 128])
