@@ -35,7 +35,7 @@ def in_layout(a, dt, layout, pad=24):
 
 @pytest.mark.parametrize("seed", range(24))
 def test_prefill_random_case(seed):
-    """Both prefill forms on the same random case (the three-branch form where it exists: bf16, groups of 64)."""
+    """Both prefill forms on the same random case (the three-branch form with groups of 64)."""
     rng = np.random.default_rng(9000 + seed)
     io = "bf16" if rng.random() < 0.8 else "f32"
     d, chunk, Kc = int(rng.choice([64, 128])), int(rng.choice([64, 128])), int(rng.integers(1, 9))
@@ -56,7 +56,7 @@ def test_prefill_random_case(seed):
     args = (None, None, None) if state is None else state
     with oracle.feature_map(phi):
         want = oracle.prefill_recurrent(q, k, v, w, *args, eps=eps)
-        want_g = oracle.prefill_grouped(q, k, v, w, 64, alpha, *args, eps=eps) if io == "bf16" else None
+        want_g = oracle.prefill_grouped(q, k, v, w, 64, alpha, *args, eps=eps)
     gq, gk, gv, gw = in_layout(q, dt, layout), in_layout(k, dt, layout), in_layout(v, dt, layout), dev(w)
 
     def gpu_state():
@@ -71,8 +71,7 @@ def test_prefill_random_case(seed):
         assert np.array_equal(host(h), workloads.round_to_io(ref[3], io).astype(np.float64)), f"{what} {tag} hist"
 
     compare(binding.prefill(gq, gk, gv, gw, gpu_state(), chunk, eps, phi=phi), want, "token-level")
-    if want_g is not None:
-        compare(binding.prefill_grouped(gq, gk, gv, gw, alpha, gpu_state(), eps, phi=phi), want_g, "three-branch")
+    compare(binding.prefill_grouped(gq, gk, gv, gw, alpha, gpu_state(), eps, phi=phi), want_g, "three-branch")
 
 
 @pytest.mark.parametrize("seed", range(16))
