@@ -38,13 +38,13 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(PrefillArgs a) {
   }
 }
 
-// Segments per (b, h): enough workgroups to cover the 256 compute units about once,
-// but at least 4 groups per segment so the first pass stays a small fraction.
+// Segments per (b, h): as many as keep all workgroups of the second pass resident at once (one per compute unit:
+// a workgroup takes most of a unit's LDS, so the 257th would wait for a whole segment), with at least 2 groups per
+// segment, and no segments at all for sequences of fewer than 8 groups, where a second launch costs more than it saves.
 int prefill_mfma_pick_segments(int BH, int L, int chunk) {
   const int chunks = (L + chunk - 1) / chunk;
-  int want = (256 + BH - 1) / BH;
-  int most = chunks / 4;
-  if (most < 1) most = 1;
+  int want = 256 / BH;
+  int most = chunks >= 8 ? chunks / 2 : 1;
   if (want > most) want = most;
   if (want > 64) want = 64;
   return want < 1 ? 1 : want;
