@@ -498,31 +498,61 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         if (lane < 32) denq[32 * tb + l32] = acc[tb][0];   // every row of the product is the same
     };
 
-    for (int e = lt; !STATE_ONLY && e < KCM * D; e += G::NLT) {
-      const int j = e / D, cc = e % D;
-      wl[e] = j < a.Kc ? a.conv_w[((size_t)h * D + cc) * a.Kc + j] : 0.f;
-    }
-    // value rows just before this segment: earlier tokens, else the incoming history, else zeros
-    for (int e = lt; !STATE_ONLY && e < HALO * D; e += G::NLT) {
-      const int r = e / D, cc = e % D;
-      const int tok = t_begin - HALO + r;
-      uint16_t x = 0;
-      if (tok >= 0) x = gv[(int64_t)tok * a.st + cc];
-      else if (a.hist_in) {
-        if (a.nseg > 1) x = staged_hist[(size_t)(HALO + tok) * D + cc];
-        else if (a.Kc - 1 + tok >= 0)
-          x = static_cast<const uint16_t*>(a.hist_in)[((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + cc];
+    // The conv taps and the value rows just before this segment (earlier tokens, else the incoming history, else
+    // zeros) are requested ahead of the first two groups and stored behind those requests: unconditional loads
+    // (an address that exists where there is nothing to read), so that a short sequence does not pay one round
+    // trip to memory per loop iteration before its first group is even asked for.
+    constexpr int TAP_IT = (KCM * D + G::NLT - 1) / G::NLT;
+    constexpr int HALO_IT = HALO * D / G::NLT;
+    float tap_reg[TAP_IT];
+    uint16_t halo_reg[HALO_IT];
+    bool halo_ok[HALO_IT];
+    auto small_inputs_request = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int mth = 0; mth < TAP_IT; ++mth) {
+        const int e = lt + G::NLT * mth;
+        const int j = e / D, cc = e % D;
+        tap_reg[mth] = a.conv_w[((size_t)h * D + cc) * a.Kc + (j < a.Kc ? j : 0)];
       }
-      bufV(0)[r * G::VS + cc] = x;
-    }
+#pragma unroll
+      for (int mth = 0; mth < HALO_IT; ++mth) {
+        const int e = lt + G::NLT * mth;
+        const int r = e / D, cc = e % D;
+        const int tok = t_begin - HALO + r;
+        const uint16_t* src = gv + (int64_t)t_begin * a.st + cc;   // exists: the segment is not empty
+        bool ok = false;
+        if (tok >= 0) { src = gv + (int64_t)tok * a.st + cc; ok = true; }
+        else if (a.hist_in && a.nseg > 1) { src = staged_hist + (size_t)(HALO + tok) * D + cc; ok = true; }
+        else if (a.hist_in && a.Kc - 1 + tok >= 0) {
+          src = static_cast<const uint16_t*>(a.hist_in) + ((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + cc;
+          ok = true;
+        }
+        halo_reg[mth] = *src;
+        halo_ok[mth] = ok;
+      }
+    };
+    auto small_inputs_store = [&]() __attribute__((always_inline)) {
+#pragma unroll
+      for (int mth = 0; mth < TAP_IT; ++mth) {
+        const int e = lt + G::NLT * mth;
+        if (e < KCM * D) wl[e] = e / D < a.Kc ? tap_reg[mth] : 0.f;
+      }
+#pragma unroll
+      for (int mth = 0; mth < HALO_IT; ++mth) {
+        const int e = lt + G::NLT * mth;
+        bufV(0)[(e / D) * G::VS + e % D] = halo_ok[mth] ? halo_reg[mth] : (uint16_t)0;
+      }
+    };
     // The whole walk, once per feature map: the map is a property of the launch, and choosing it out here
     // keeps the loop of either map free of selects and branches on it.
     auto walk = [&](auto relu_tag) __attribute__((always_inline)) {
       if (nchunks > 0) {
+        if (!STATE_ONLY) small_inputs_request();
 #pragma unroll
         for (int p = 0; p < G::NP; ++p) load_pass(0, p, Set0{}, Part{}, P0{});
 #pragma unroll
         for (int p = 0; p < G::NP; ++p) load_pass(1, p, Set1{}, Part{}, P0{});
+        if (!STATE_ONLY) small_inputs_store();
         fill_group(0, Set0{}, std::false_type{}, relu_tag);
       }
       __syncthreads();                                   // buffer 0 is full, z is in LDS
