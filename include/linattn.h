@@ -23,6 +23,11 @@
  * The row normaliser z, eps, and out = Y + U are this library's reading where
  * the paper leaves them open.
  *
+ * linattn_prefill_grouped / linattn_verify_grouped compute the block in the
+ * other form that Sec. 4.1 describes (group-level sums only in the linear
+ * branch, softmax attention inside each group, the same convolution); see
+ * their declarations.
+ *
  * Vext is V extended to the left by `hist` (the last Kc-1 value rows seen so
  * far, oldest first), or by zeros at the start of a sequence.  Tap j of the
  * convolution multiplies the value row j positions back (j = 0: the current
