@@ -37,7 +37,8 @@
  *   - All data pointers are DEVICE pointers, 16-byte aligned.  The descriptor
  *     and the scalar arguments are host values.  `n_commit` is a device pointer.
  *   - The caller owns every buffer.  The library allocates no device memory,
- *     keeps no state between calls and may be called from several host threads.
+ *     keeps no state between calls (linattn_set_wait_limit apart) and may be
+ *     called from several host threads.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and the call returns without waiting for it.
  *   - The return value reports argument validation and launch errors only.
@@ -241,6 +242,18 @@ linattn_status linattn_decode(const linattn_desc *desc,
                               const float *conv_w,
                               float *S, float *z, void *hist,
                               void *out, void *hip_stream);
+
+/* What happens when the kernels' own synchronisation fails.  The waves of a bf16 prefill workgroup hand each
+ * other data through LDS and wait for one another with bounded polling, so that a logic error or an extreme
+ * slowdown cannot hang the GPU.  A wait that gives up does not go unnoticed: from then on every output row
+ * that workgroup stores, and the S_out and z_out it hands back, are NaN (never finite numbers computed from
+ * operands that were not ready).  The call itself still returns LINATTN_OK, since it returned before the
+ * kernel ran; callers that must know check their outputs for NaN.
+ * linattn_set_wait_limit sets the number of polls (about 64 clock cycles each) after which a wait gives up,
+ * for all later prefill calls of this process, and returns the previous value.  spins == 0 restores the
+ * default (2^20); spins < 0 makes every wait give up without looking, which is how the tests reach the NaN
+ * path with kernels that still run to their end.  The only setting the library keeps; thread-safe. */
+int32_t linattn_set_wait_limit(int32_t spins);
 
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char *linattn_status_string(linattn_status status);

@@ -1,6 +1,6 @@
 """ctypes binding of liblinattn.so: argument marshalling only.
 
-The three calls have the names and argument order of ``include/linattn.h``.
+Every call has the name and argument order of its declaration in ``include/linattn.h``.
 Tensors are torch tensors on the GPU (torch is used for device memory and
 streams, nothing else); every arithmetic step runs inside the library's
 kernels.  If the library is missing or a call is refused, this module raises;
@@ -22,7 +22,7 @@ LINATTN_PHI_ELU1, LINATTN_PHI_RELU = 0, 1
 PHI = {"elu1": LINATTN_PHI_ELU1, "relu": LINATTN_PHI_RELU}
 MAX_CONV_K, MAX_DRAFT, MAX_TREE = 8, 16, 64
 SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_grouped", "linattn_verify", "linattn_verify_grouped", "linattn_verify_tree", "linattn_decode",
-           "linattn_status_string", "linattn_version")
+           "linattn_set_wait_limit", "linattn_status_string", "linattn_version")
 
 
 class LinattnError(RuntimeError):
@@ -66,6 +66,8 @@ def load():
     lib.linattn_status_string.restype = ctypes.c_char_p
     lib.linattn_status_string.argtypes = [ctypes.c_int]
     lib.linattn_version.restype = i32
+    lib.linattn_set_wait_limit.restype = i32
+    lib.linattn_set_wait_limit.argtypes = [i32]
     _lib = lib
     return lib
 
@@ -102,6 +104,10 @@ def make_desc(B, H, d, conv_k, chunk=64, io_dtype=torch.bfloat16, eps=0.0, strid
         Lx = 0 if L is None else int(L)
         strides = (H * Lx * d, Lx * d, d)
     return Desc(B, H, d, conv_k, chunk, code, PHI[phi], float(eps), *[int(s) for s in strides])
+
+
+def linattn_set_wait_limit(spins: int) -> int:
+    return int(load().linattn_set_wait_limit(int(spins)))
 
 
 def linattn_workspace_bytes(desc: Desc, L: int) -> int:
@@ -177,6 +183,8 @@ def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, str
         h = torch.empty((B, H, max(Kc - 1, 0), d), dtype=q.dtype, device=q.device)
     nbytes = linattn_workspace_bytes(desc, L)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device) if nbytes else None
+    if ws is not None and stream is not None and not isinstance(stream, int):
+        ws.record_stream(stream)     # the allocator must not hand this memory out again before the launch stream is done with it
     if grouped_alpha is None:
         linattn_prefill(desc, L, q, k, v, conv_w, S_in, z_in, h_in, out, S, z, h, ws, nbytes, stream)
     else:

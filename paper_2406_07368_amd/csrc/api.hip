@@ -1,8 +1,11 @@
 // C ABI (include/linattn.h): argument validation, launch planning, dispatch.
-// No device memory is allocated here and nothing is kept between calls.
+// No device memory is allocated here and nothing is kept between calls (one setting apart:
+// linattn_set_wait_limit).
 #include "../../include/linattn.h"
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 
 #include "kernels.h"
 
@@ -10,9 +13,15 @@ using namespace linattn;
 
 namespace {
 
+// Polls before a wait between the waves of a prefill workgroup gives up (linattn_set_wait_limit).
+constexpr int32_t kDefaultWaitSpins = 1 << 20;
+std::atomic<int32_t> g_wait_spins{kDefaultWaitSpins};
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-linattn_status check_desc(const linattn_desc* d, bool prefill) {
+// chunk: the group size takes part in the call; strides: q, k, v, out are addressed by the descriptor's strides
+// (the verify entry points take dense tensors and ignore them).
+linattn_status check_desc(const linattn_desc* d, bool chunk, bool strides) {
   if (!d) return LINATTN_ERR_NULL;
   if (d->io_dtype != LINATTN_F32 && d->io_dtype != LINATTN_BF16) return LINATTN_ERR_DTYPE;
   if (d->phi != LINATTN_PHI_ELU1 && d->phi != LINATTN_PHI_RELU) return LINATTN_ERR_DTYPE;
@@ -21,8 +30,8 @@ linattn_status check_desc(const linattn_desc* d, bool prefill) {
   if (d->d != 64 && d->d != 128) return LINATTN_ERR_SHAPE;
   if (d->conv_k < 1 || d->conv_k > LINATTN_MAX_CONV_K) return LINATTN_ERR_SHAPE;
   if (!(d->eps >= 0.f)) return LINATTN_ERR_SHAPE;
-  if (prefill) {
-    if (d->chunk != 64 && d->chunk != 128) return LINATTN_ERR_SHAPE;
+  if (chunk && d->chunk != 64 && d->chunk != 128) return LINATTN_ERR_SHAPE;
+  if (strides) {
     if (d->stride_t < d->d || d->stride_h < 0 || d->stride_b < 0) return LINATTN_ERR_SHAPE;
     if ((d->stride_t | d->stride_h | d->stride_b) & 7) return LINATTN_ERR_SHAPE;
     if (d->stride_t > (int64_t)1 << 22) return LINATTN_ERR_SHAPE;   // the kernels index inside a group with 32 bits
@@ -60,7 +69,7 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
                            const void* v, const float* conv_w, const float* S_in, const float* z_in, const void* hist_in,
                            void* out, float* S_out, float* z_out, void* hist_out, void* workspace,
                            size_t workspace_bytes, void* hip_stream) {
-  linattn_status st = check_desc(desc, true);
+  linattn_status st = check_desc(desc, true, true);
   if (st != LINATTN_OK) return st;
   if (L < 0) return LINATTN_ERR_SHAPE;
   if (grouped) {
@@ -93,6 +102,7 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
   a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
   a.nseg = plan.nseg; a.seg_len = plan.seg_len;
   a.alpha = alpha;
+  a.wait_spins = g_wait_spins.load(std::memory_order_relaxed);
   hipError_t e;
   if (plan.mfma && L > 0) e = launch_prefill_mfma(a, desc->d, desc->chunk, grouped, stream);
   else if (grouped && L > 0) e = launch_prefill_grouped_simt(a, desc->d, stream);      // fp32 rows
@@ -118,10 +128,14 @@ const char* linattn_status_string(linattn_status s) {
   return "unknown status";
 }
 
-int32_t linattn_version(void) { return 100; }
+int32_t linattn_version(void) { return 200; }
+
+int32_t linattn_set_wait_limit(int32_t spins) {
+  return g_wait_spins.exchange(spins == 0 ? kDefaultWaitSpins : spins, std::memory_order_relaxed);
+}
 
 size_t linattn_workspace_bytes(const linattn_desc* desc, int32_t L) {
-  if (check_desc(desc, true) != LINATTN_OK || L < 0) return 0;
+  if (check_desc(desc, true, true) != LINATTN_OK || L < 0) return 0;
   return plan_prefill(desc, L).ws_bytes;
 }
 
@@ -144,7 +158,7 @@ linattn_status linattn_prefill_grouped(const linattn_desc* desc, int32_t L, floa
 linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* q, const void* k, const void* v,
                               const float* conv_w, float* S, float* z, void* hist, const int32_t* n_commit,
                               void* out, void* hip_stream) {
-  linattn_status st = check_desc(desc, false);
+  linattn_status st = check_desc(desc, false, false);
   if (st != LINATTN_OK) return st;
   if (kk < 1 || kk > LINATTN_MAX_DRAFT) return LINATTN_ERR_SHAPE;
   if (!q || !k || !v || !conv_w || !S || !z || !out) return LINATTN_ERR_NULL;
@@ -169,7 +183,7 @@ linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* 
 linattn_status linattn_verify_grouped(const linattn_desc* desc, int32_t kk, float alpha, const void* q, const void* k,
                                       const void* v, const float* conv_w, float* S, float* z, void* hist, void* kwin,
                                       void* vwin, int32_t* fill, const int32_t* n_commit, void* out, void* hip_stream) {
-  linattn_status st = check_desc(desc, true);     // the group size is part of the result: chunk is checked
+  linattn_status st = check_desc(desc, true, false);     // the group size is part of the result; the tensors are dense
   if (st != LINATTN_OK) return st;
   if (kk < 1 || kk > LINATTN_MAX_DRAFT) return LINATTN_ERR_SHAPE;
   if (!(alpha == alpha) || alpha - alpha != 0.f) return LINATTN_ERR_SHAPE;   // NaN, infinity
@@ -196,7 +210,7 @@ linattn_status linattn_verify_grouped(const linattn_desc* desc, int32_t kk, floa
 linattn_status linattn_verify_tree(const linattn_desc* desc, int32_t n, const void* q, const void* k, const void* v,
                                    const int32_t* parent, const float* conv_w, float* S, float* z, void* hist,
                                    const int32_t* accept, void* out, void* hip_stream) {
-  linattn_status st = check_desc(desc, false);
+  linattn_status st = check_desc(desc, false, false);
   if (st != LINATTN_OK) return st;
   if (n < 1 || n > LINATTN_MAX_TREE) return LINATTN_ERR_SHAPE;
   if (!q || !k || !v || !parent || !conv_w || !S || !z || !out) return LINATTN_ERR_NULL;

@@ -75,6 +75,7 @@ struct PrefillArgs {
   int64_t sb, sh, st;       // element strides of q, k, v, out
   int nseg;                 // workgroups along the sequence axis per (b, h)
   int seg_len;              // tokens per segment (multiple of the chunk size)
+  int wait_spins;           // polls before a wait between the waves of a workgroup gives up; < 0: give up at once
 };
 
 // verify.hip

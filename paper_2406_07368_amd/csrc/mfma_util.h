@@ -1,7 +1,7 @@
-// Helpers shared by the matrix-core prefill kernels: LDS fragment loads (row reads and the
+// Helpers shared by the matrix-core kernels: LDS fragment loads (row reads and the
 // gfx950 transpose reads), the 32x32x16 bf16 MFMA, accumulator -> bf16 operand packing.
 #pragma once
-#include "common.cuh"
+#include "common.h"
 
 namespace linattn {
 
@@ -64,6 +64,27 @@ __device__ __forceinline__ u32x4 phi_pack8(u32x4 x, int relu) {
     for (int i = 0; i < 4; ++i) y[i] = pack_bf16x2(fmaxf(bf16_lo_to_f32(x[i]), 0.f), fmaxf(bf16_hi_to_f32(x[i]), 0.f));
   }
   return y;
+}
+
+// phi on four packed bf16 pairs as the sum of two bf16 terms: hi = bf16(phi(x)), lo = bf16(phi(x) - hi).
+// phi(x) = x + 1 of a bf16 x needs more significant bits than one bf16 has; hi + lo carries sixteen, so a
+// product (hi + lo) * v that enters the fp32 state is off by 2^-17 of itself instead of 2^-9.  max(x, 0)
+// of a bf16 x is a bf16: lo = 0.
+__device__ __forceinline__ void phi_split8(u32x4 x, int relu, u32x4& hi, u32x4& lo) {
+  if (!relu) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float f0 = phi_elu1_max(bf16_lo_to_f32(x[i])), f1 = phi_elu1_max(bf16_hi_to_f32(x[i]));
+      hi[i] = pack_bf16x2(f0, f1);
+      lo[i] = pack_bf16x2(f0 - bf16_lo_to_f32(hi[i]), f1 - bf16_hi_to_f32(hi[i]));
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      hi[i] = pack_bf16x2(fmaxf(bf16_lo_to_f32(x[i]), 0.f), fmaxf(bf16_hi_to_f32(x[i]), 0.f));
+      lo[i] = 0u;
+    }
+  }
 }
 
 }  // namespace linattn

@@ -6,9 +6,9 @@
 // K, V to its state increment, a prefix sum over the segments (here) turns the
 // increments into segment start states, and the full pass starts every segment from its
 // prefix.
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
-#include "mfma_util.cuh"
+#include "mfma_util.h"
 
 namespace linattn {
 

@@ -34,9 +34,9 @@
 // counter tells the front end when the state waves are done with phi(Q).
 #include <type_traits>
 
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
-#include "mfma_util.cuh"
+#include "mfma_util.h"
 
 namespace linattn {
 
@@ -113,12 +113,18 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   };
   // Bounded wait: the signalling waves never wait for anything that depends on the waiting ones
   // before they signal, so the count is always reached; the bound only keeps a logic error from
-  // hanging the GPU (the results would then be wrong, not the machine stuck).
+  // hanging the GPU.  A wait that gives up raises the workgroup's `gave_up` word, and from then on
+  // everything the workgroup hands back -- output rows, S, z -- is NaN instead of numbers computed
+  // from operands that were not ready: an error shows as such, never as a finite wrong result.
+  // a.wait_spins < 0 gives up without looking (the host's way to exercise this path).
+  unsigned* gave_up = sync_q + 3;
   auto wait_for = [&](unsigned* ctr, unsigned want) __attribute__((always_inline)) {
-    for (int spin = 0; spin < (1 << 20); ++spin) {
-      if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= want) break;
+    bool reached = false;
+    for (int spin = 0; spin <= a.wait_spins; ++spin) {
+      if (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= want) { reached = true; break; }
       __builtin_amdgcn_s_sleep(1);
     }
+    if (!reached && lane == 0) __hip_atomic_store(gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   };
   auto bufQ = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + (GROUPED ? G::OFF_FQ : bi * G::BUF + G::BQ)); };
@@ -144,7 +150,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   const uint16_t* staged_hist =
       reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
 
-  if (tid == 0) { *sync_q = 0u; *sync_s = 0u; *sync_m = 0u; }
+  if (tid == 0) { *sync_q = 0u; *sync_s = 0u; *sync_m = 0u; *gave_up = 0u; }
   __syncthreads();                                     // the counters are used before the next barrier
 
   if (wv >= G::NW) {
@@ -266,6 +272,18 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       const int nt = (t_end - tok0) < C ? (t_end - tok0) : C;
       const uint16_t* ost = bufO(g & 1);
       char* bo = reinterpret_cast<char*>(gout + (int64_t)tok0 * a.st);
+      // a wait of this workgroup gave up (the word was written before the barrier that precedes this store):
+      // the rows become NaN.  One uniform branch per group; the path is never taken in a correct run.
+      if (__builtin_amdgcn_readfirstlane(*gave_up)) {
+#pragma unroll
+        for (int p = 0; p < G::NP; ++p) {
+          const int t = 16 * p + r16;
+          if (!PARTIAL || t < nt)
+            __builtin_nontemporal_store(u32x4{0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u},
+                                        reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st * 2u + loff_b));
+        }
+        return;
+      }
 #pragma unroll
       for (int p = 0; p < G::NP; ++p) {
         const int t = 16 * p + r16;
@@ -834,6 +852,14 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       for (int r = 0; r < 16; ++r) Sdst[D * D + 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3)] = Zacc[r];
     }
   } else if (seg == a.nseg - 1) {
+    if (__builtin_amdgcn_readfirstlane(*gave_up)) {      // a wait gave up (written before the last barrier): no numbers
+#pragma unroll
+      for (int ib = 0; ib < G::IB; ++ib)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) Sacc[ib][r] = __builtin_nanf("");
+#pragma unroll
+      for (int r = 0; r < 16; ++r) Zacc[r] = __builtin_nanf("");
+    }
     if (a.S_out) {
       float* Sdst = a.S_out + (size_t)bh * D * D;
 #pragma unroll

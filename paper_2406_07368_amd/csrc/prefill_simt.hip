@@ -3,7 +3,7 @@
 // threads walks one (b, h) in steps of 32 tokens with the whole d x d state in
 // LDS.  This is the path for fp32 inputs, where every product has to be an exact
 // fp32 multiply-add to meet a 1e-4 bound; it is not tuned for throughput.
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
 
 namespace linattn {

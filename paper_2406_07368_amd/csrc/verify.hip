@@ -11,7 +11,7 @@
 // The read-outs are then reduced across the threads that share a column group,
 // completed with the causal in-block term, normalised, and joined with the
 // convolution over (history ++ drafts <= j).
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
 
 namespace linattn {

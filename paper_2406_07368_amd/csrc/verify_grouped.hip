@@ -19,7 +19,7 @@
 //   4. outputs; 5. the kept drafts join the window, or complete the group and enter S and z.
 // The count of rows in use is kept per head ([B,H], equal over the heads of a batch row), so that every
 // workgroup owns the one it reads and advances.
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
 
 namespace linattn {

@@ -11,11 +11,12 @@
 // S[:, 32w:32w+32] as D/32 accumulator tiles, requested first thing (nontemporal buffer loads) and only
 // written when the kept drafts complete the group: then S += phi(K)^T V over the 64 rows, again by MFMA.
 // Up to 96 rows (63 of the open group + 16 drafts, padded with zero rows) and 16 query rows live in LDS.
-// Arithmetic as in the prefill: bf16 operands (the logits are exact products of bf16 inputs), fp32
-// accumulation, S rounded to bf16 for the read-out only; the stored state stays fp32.
-#include "common.cuh"
+// Arithmetic: bf16 operands (the logits are exact products of bf16 inputs), fp32 accumulation, S rounded
+// to bf16 for the read-out only; the stored state stays fp32, and when a group enters it phi(k) is taken as
+// the sum of two bf16 terms (two MFMAs per tile: sixteen significant bits of phi(k) in every product).
+#include "common.h"
 #include "kernels.h"
-#include "mfma_util.cuh"
+#include "mfma_util.h"
 
 namespace linattn {
 
@@ -52,7 +53,13 @@ struct VgmSmem {
   __attribute__((aligned(16))) float w[8 * D];                        // conv taps, tap-major
   __attribute__((aligned(16))) float z[D];
   float fscale[G::NQ];                                                 // alpha / (phi(q_j).z [+ completed group] + eps), 0 if that is 0
+  // qr .. lin are dead once the outputs are complete; when the group is then completed their memory holds
+  // the low-order term of phi(k) of its 64 rows
+  __device__ uint16_t* klo() { return qr; }                            // [GC][KS]
 };
+static_assert(offsetof(VgmSmem<128>, w) - offsetof(VgmSmem<128>, qr) >= VgmCfg<128>::GC * VgmCfg<128>::KS * 2 &&
+              offsetof(VgmSmem<64>, w) - offsetof(VgmSmem<64>, qr) >= VgmCfg<64>::GC * VgmCfg<64>::KS * 2,
+              "the low-order term of phi(K) takes the place of qr, q, p, W and lin");
 
 }  // namespace
 
@@ -337,18 +344,23 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
     return;
   }
   // the group is complete: rows 0..63 enter S and z.  Their keys get the feature map in place first.
-  __syncthreads();                                       // every wave is done with the raw rows
+  __syncthreads();                                       // every wave is done with the raw rows, the queries and the weights
   for (int e = tid; e < GC * (D / 8); e += G::NT) {
     const int r = e / (D / 8), i0 = 8 * (e % (D / 8));
     u32x4* p8 = reinterpret_cast<u32x4*>(sm.kr + r * G::KS + i0);
-    *p8 = phi_pack8(*p8, a.relu);
+    u32x4 fh, fl;
+    phi_split8(*p8, a.relu, fh, fl);
+    *p8 = fh;
+    *reinterpret_cast<u32x4*>(sm.klo() + r * G::KS + i0) = fl;
   }
   __syncthreads();
 #pragma unroll
   for (int ib = 0; ib < G::IB; ++ib) {
 #pragma unroll
-    for (int ks = 0; ks < GC / 16; ++ks)
+    for (int ks = 0; ks < GC / 16; ++ks) {
+      Sacc[ib] = mfma(tr_operand(sm.klo(), G::KS, 16 * ks, 32 * ib, lane), vf[ks], Sacc[ib]);
       Sacc[ib] = mfma(tr_operand(sm.kr, G::KS, 16 * ks, 32 * ib, lane), vf[ks], Sacc[ib]);
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(Sacc[ib][r]), Srs, so,
@@ -356,7 +368,7 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
   }
   if (!upper) {
     float zs = zreg;
-    for (int r = 0; r < GC; ++r) zs += bf16_bits_to_f32(sm.kr[r * G::KS + cc]);
+    for (int r = 0; r < GC; ++r) zs += bf16_bits_to_f32(sm.kr[r * G::KS + cc]) + bf16_bits_to_f32(sm.klo()[r * G::KS + cc]);
     a.z[(size_t)bh * D + cc] = zs;
   }
   // the next group opens with the kept drafts beyond the completed one: rows 64 .. n+m-1 -> rows 0 ..

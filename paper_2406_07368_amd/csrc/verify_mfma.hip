@@ -7,8 +7,12 @@
 //   O^T  = S0^T phi(Q)^T + V^T P^T        P^T = causal(phi(K) phi(Q)^T)  (select mask)
 //   S   += phi(K_acc)^T V                 K_acc: rows of the accepted drafts, the others zero
 //
-// exactly as in the prefill kernel and with its arithmetic (bf16 operands, fp32
-// accumulation; S is rounded to bf16 for the read-out only, the stored state stays fp32).
+// exactly as in the prefill kernel, with bf16 operands and fp32 accumulation; S is rounded to
+// bf16 for the read-out only, the stored state stays fp32.  Unlike the prefill, the state update
+// takes phi(k) as the sum of two bf16 terms (two MFMAs per tile): the state lives on through
+// thousands of such steps, the matrix cores are idle most of the step, and this way every
+// product that enters S carries sixteen significant bits of phi(k) -- the same state, to 1e-5,
+// as the streaming kernel's fp32 products.
 // The work on the vector ALUs no longer grows with the number of drafts, which is what
 // held the streaming form back at k = 4 and k = 8.
 //
@@ -17,9 +21,9 @@
 // feature).  Every lane requests its 4 D/32 state words first thing (a half wave reads one
 // whole 128-byte row segment per request), then the drafts are prepared and scored while
 // the state is on its way; the updated tiles go straight back.  n_commit == 0 writes nothing.
-#include "common.cuh"
+#include "common.h"
 #include "kernels.h"
-#include "mfma_util.cuh"
+#include "mfma_util.h"
 
 namespace linattn {
 
@@ -42,7 +46,8 @@ template <int D>
 struct VmSmem {
   using G = VmCfg<D>;
   __attribute__((aligned(16))) uint16_t q[G::KT * G::QS];
-  __attribute__((aligned(16))) uint16_t k[G::KT * G::KS];
+  __attribute__((aligned(16))) uint16_t k[G::KT * G::KS];            // phi(K) rounded to bf16
+  __attribute__((aligned(16))) uint16_t klo[G::KT * G::KS];          // what the rounding dropped, as bf16
   __attribute__((aligned(16))) uint16_t v[(HALO + G::KT) * G::VS];   // row r = draft r - HALO
   __attribute__((aligned(16))) uint16_t p[G::NW][G::KT * G::PS];     // each wave's own copy of the scores
   __attribute__((aligned(16))) float w[8 * D];                       // conv taps, tap-major
@@ -109,12 +114,14 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
 
   // ---- drafts -> LDS: phi(Q), phi(K) as bf16 rows (rows >= kk are zero rows), V, history, z, taps --
   {
-    u32x4 qp = phi_pack8(rq, a.relu), kp = phi_pack8(rk, a.relu);
-    if (dj >= kk) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; }
+    u32x4 qp = phi_pack8(rq, a.relu), kp, kl;
+    phi_split8(rk, a.relu, kp, kl);
+    if (dj >= kk) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; kl = u32x4{0, 0, 0, 0}; }
     u32x2* qrow = reinterpret_cast<u32x2*>(sm.q + dj * G::QS + di0);
     qrow[0] = u32x2{qp[0], qp[1]};
     qrow[1] = u32x2{qp[2], qp[3]};
     *reinterpret_cast<u32x4*>(sm.k + dj * G::KS + di0) = kp;
+    *reinterpret_cast<u32x4*>(sm.klo + dj * G::KS + di0) = kl;
     u32x2* vrow = reinterpret_cast<u32x2*>(sm.v + (HALO + dj) * G::VS + di0);
     vrow[0] = u32x2{rv[0], rv[1]};
     vrow[1] = u32x2{rv[2], rv[3]};
@@ -214,6 +221,8 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
     }
     if (n > 0) {   // uniform per workgroup; n == 0 leaves the state untouched
       const u32x4 kt = __builtin_bit_cast(u32x4, tr_operand(sm.k, G::KS, 0, 32 * ib, lane)) & keep;
+      const u32x4 ktl = __builtin_bit_cast(u32x4, tr_operand(sm.klo, G::KS, 0, 32 * ib, lane)) & keep;
+      Sacc[ib] = mfma(__builtin_bit_cast(bf16x8, ktl), vf, Sacc[ib]);
       Sacc[ib] = mfma(__builtin_bit_cast(bf16x8, kt), vf, Sacc[ib]);
 #pragma unroll
       for (int r = 0; r < 16; ++r)
@@ -249,7 +258,7 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
   if (n == 0) return;   // uniform per workgroup: nothing accepted, state untouched
   if (tid < D) {
     float zs = zreg;
-    for (int j = 0; j < n; ++j) zs += bf16_bits_to_f32(sm.k[j * G::KS + tid]);
+    for (int j = 0; j < n; ++j) zs += bf16_bits_to_f32(sm.k[j * G::KS + tid]) + bf16_bits_to_f32(sm.klo[j * G::KS + tid]);
     a.z[(size_t)bh * D + tid] = zs;
     // the last Kc-1 rows of (history ++ accepted drafts); all of them are rows of the LDS copy
     for (int r = 0; r < Kc - 1; ++r)

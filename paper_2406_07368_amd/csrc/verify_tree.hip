@@ -16,11 +16,13 @@
 // One workgroup per (b, h), D/32 waves; wave w owns value channels 32w..32w+31, i.e. the
 // column block S[:, 32w:32w+32] as D/32 MFMA accumulator tiles, requested first thing and
 // written straight back (nontemporal, buffer addressing), as in the chain kernel.  The
-// score tiles are shared through LDS.  Arithmetic as in the prefill: bf16 operands, fp32
-// accumulation; the stored state stays fp32.  Nothing accepted = nothing written.
-#include "common.cuh"
+// score tiles are shared through LDS.  Arithmetic: bf16 operands, fp32 accumulation; the
+// stored state stays fp32, and the state update takes phi(k) as the sum of two bf16 terms (two
+// MFMAs per tile), so that every product entering S carries sixteen significant bits of phi(k).
+// Nothing accepted = nothing written.
+#include "common.h"
 #include "kernels.h"
-#include "mfma_util.cuh"
+#include "mfma_util.h"
 
 namespace linattn {
 
@@ -46,10 +48,12 @@ struct VtCfg {
 template <int D>
 struct VtSmem {
   using G = VtCfg<D>;
+  // q and p are only read until the outputs' accumulators are complete; after that their memory holds the
+  // low-order term of phi(K) for the state update (klo() below)
   __attribute__((aligned(16))) uint16_t q[G::KT * G::QS];
-  __attribute__((aligned(16))) uint16_t k[G::KT * G::KS];
-  __attribute__((aligned(16))) uint16_t v[(HALO + G::KT) * G::VS];   // row r = candidate r - HALO
   __attribute__((aligned(16))) uint16_t p[G::KT * G::PS];
+  __attribute__((aligned(16))) uint16_t k[G::KT * G::KS];            // phi(K) rounded to bf16
+  __attribute__((aligned(16))) uint16_t v[(HALO + G::KT) * G::VS];   // row r = candidate r - HALO
   __attribute__((aligned(16))) float w[8 * D];                       // conv taps, tap-major
   __attribute__((aligned(16))) float z[D];
   __attribute__((aligned(16))) float denq[4][G::KT];                 // phi(q).z, one part per quarter of the features
@@ -57,7 +61,12 @@ struct VtSmem {
   __attribute__((aligned(16))) unsigned long long onpath[G::KT];     // bit a of row i: candidate a is on the root path of i
   __attribute__((aligned(16))) uint8_t taprow[G::KT][8];             // row of sm.v that tap t of candidate i reads
   int parent[G::KT];
+  __device__ uint16_t* klo() { return q; }                           // [KT][KS], over q and p
 };
+static_assert(sizeof(VtSmem<128>::q) + sizeof(VtSmem<128>::p) >= sizeof(VtSmem<128>::k) &&
+              sizeof(VtSmem<64>::q) + sizeof(VtSmem<64>::p) >= sizeof(VtSmem<64>::k) &&
+              offsetof(VtSmem<128>, p) == sizeof(VtSmem<128>::q) && offsetof(VtSmem<64>, p) == sizeof(VtSmem<64>::q),
+              "the low-order term of phi(K) takes the place of q and p");
 
 }  // namespace
 
@@ -123,12 +132,14 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
           float, __builtin_amdgcn_raw_buffer_load_b32(Srs, so, (32 * ib + 8 * (r >> 2) + (r & 3)) * (D * 4), 2));
 
   // ---- candidates -> LDS: phi(Q), phi(K) as bf16 rows (rows >= n are zero rows), V, history, z, taps --
+  u32x4 kl[G::QP];                                       // phi(K) - bf16(phi(K)): stays in registers until q and p are free
 #pragma unroll
   for (int m = 0; m < G::QP; ++m) {
     const int piece = tid + G::NT * m;
     const int dj = piece / (D / 8), di0 = 8 * (piece % (D / 8));
-    u32x4 qp = phi_pack8(rq[m], a.relu), kp = phi_pack8(rk[m], a.relu);
-    if (dj >= n) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; }
+    u32x4 qp = phi_pack8(rq[m], a.relu), kp;
+    phi_split8(rk[m], a.relu, kp, kl[m]);
+    if (dj >= n) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; kl[m] = u32x4{0, 0, 0, 0}; }
     u32x2* qrow = reinterpret_cast<u32x2*>(sm.q + dj * G::QS + di0);
     qrow[0] = u32x2{qp[0], qp[1]};
     qrow[1] = u32x2{qp[2], qp[3]};
@@ -272,6 +283,13 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   // ---- the state moves along the accepted root path (rows off the path are masked out of phi(K)^T) ---
   const unsigned long long commit = acc_node >= 0 ? sm.onpath[acc_node] : 0ull;
   if (acc_node >= 0) {   // uniform per workgroup; nothing accepted leaves the state untouched
+    __syncthreads();     // every wave has read q and p for the last time
+#pragma unroll
+    for (int m = 0; m < G::QP; ++m) {
+      const int piece = tid + G::NT * m;
+      *reinterpret_cast<u32x4*>(sm.klo() + (piece / (D / 8)) * G::KS + 8 * (piece % (D / 8))) = kl[m];
+    }
+    __syncthreads();
 #pragma unroll
     for (int ib = 0; ib < G::IB; ++ib) {
 #pragma unroll
@@ -284,6 +302,8 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
             keep[i] = (((commit >> c0) & 1ull) ? 0x0000ffffu : 0u) | (((commit >> (c0 + 1)) & 1ull) ? 0xffff0000u : 0u);
           }
           const u32x4 kt = __builtin_bit_cast(u32x4, tr_operand(sm.k, G::KS, 16 * ks, 32 * ib, lane)) & keep;
+          const u32x4 ktl = __builtin_bit_cast(u32x4, tr_operand(sm.klo(), G::KS, 16 * ks, 32 * ib, lane)) & keep;
+          Sacc[ib] = mfma(__builtin_bit_cast(bf16x8, ktl), vf[ks], Sacc[ib]);
           Sacc[ib] = mfma(__builtin_bit_cast(bf16x8, kt), vf[ks], Sacc[ib]);
         }
       }
@@ -334,7 +354,7 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   if (!upper) {
     float zs = zreg;
     for (int c = 0; c < n; ++c)
-      if ((commit >> c) & 1ull) zs += bf16_bits_to_f32(sm.k[c * G::KS + cc]);
+      if ((commit >> c) & 1ull) zs += bf16_bits_to_f32(sm.k[c * G::KS + cc]) + bf16_bits_to_f32(sm.klo()[c * G::KS + cc]);
     a.z[(size_t)bh * D + cc] = zs;
   } else {
     // the last Kc-1 rows of (history ++ accepted path) are what the taps 0..Kc-2 of the accepted candidate read

@@ -6,6 +6,11 @@ import torch
 
 # Bars from the benchmark spec: max relative error, fp32 inputs / bf16 inputs with fp32 accumulation.
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+# S and z after a verify / decode / tree-verify / generation step that was handed its state in fp32: the state
+# is fp32 on both sides of the call, and every kernel adds phi(k) v^T with at least sixteen significant bits of
+# phi(k) (fp32 products, or phi(k) as the sum of two bf16 terms on the matrix cores): each product is off by at
+# most 2^-17 of itself, a few 1e-6 of the head's rms after up to 64 tokens.
+STATE_TOL = 2e-5
 
 
 def rel_err(got, want) -> float:
@@ -36,6 +41,18 @@ def err_stats(got, want):
     diff = np.abs(got - want)
     unfloored = diff / np.maximum(np.abs(want), 1e-30)
     return rel_err(got, want), float(diff.max()), float(np.percentile(unfloored, 99.9))
+
+
+def check_unfloored(got, want, tol, what, percentile=99.0):
+    """The plain elementwise relative error |got - want| / |want| has no finite maximum where an output crosses
+    zero, so it is held to the bar at a percentile instead: at most 1 % of the elements may exceed it."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return 0.0
+    p = float(np.percentile(np.abs(got - want) / np.maximum(np.abs(want), 1e-30), percentile))
+    assert p <= tol, f"{what}: {percentile}th percentile of the un-floored relative error {p:.3e} > {tol:.1e}"
+    return p
 
 
 def check(got, want, tol, what):

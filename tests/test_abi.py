@@ -36,6 +36,14 @@ def test_version_and_status_strings():
     assert binding.status_string(99) == "unknown status"
 
 
+def test_wait_limit_setting_round_trips():
+    lib = binding.load()
+    assert lib.linattn_set_wait_limit(5) == 1 << 20
+    assert lib.linattn_set_wait_limit(-1) == 5
+    assert lib.linattn_set_wait_limit(0) == -1          # 0 restores the default
+    assert lib.linattn_set_wait_limit(0) == 1 << 20
+
+
 def good_desc(**kw):
     d = binding.make_desc(2, 4, 128, 3, 64, L=256)
     for k, v in kw.items():

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import oracle
-from parity import TOL, check, dev, host
+from parity import STATE_TOL, TOL, check, dev, host
 from paper_2406_07368_amd import binding, workloads
 
 pytestmark = pytest.mark.gpu
@@ -98,8 +98,8 @@ def test_verify_random_case(seed):
     out = binding.verify(dev(q, dt), dev(k, dt), dev(v, dt), dev(w), state, nc, eps, phi=phi)
     torch.cuda.synchronize()
     check(host(out), want[0], TOL[io], what + " out")
-    check(host(state[0]), want[1], TOL[io], what + " S")
-    check(host(state[1]), want[2], TOL[io], what + " z")
+    check(host(state[0]), want[1], STATE_TOL, what + " S")
+    check(host(state[1]), want[2], STATE_TOL, what + " z")
     assert np.array_equal(host(state[2]), workloads.round_to_io(want[3], io).astype(np.float64)), what + " hist"
 
 
@@ -127,8 +127,8 @@ def test_verify_tree_random_case(seed):
     out = binding.verify_tree(dev(q, dt), dev(k, dt), dev(v, dt), torch.from_numpy(parent).cuda(), dev(w), state, acc, eps, phi=phi)
     torch.cuda.synchronize()
     check(host(out), want[0], TOL["bf16"], what + " out")
-    check(host(state[0]), want[1], TOL["bf16"], what + " S")
-    check(host(state[1]), want[2], TOL["bf16"], what + " z")
+    check(host(state[0]), want[1], STATE_TOL, what + " S")
+    check(host(state[1]), want[2], STATE_TOL, what + " z")
     assert np.array_equal(host(state[2]), workloads.round_to_io(want[3], "bf16").astype(np.float64)), what + " hist"
 
 
@@ -159,8 +159,8 @@ def test_verify_grouped_random_case(seed):
     out = binding.verify_grouped(dev(q, dt), dev(k, dt), dev(v, dt), dev(w), gs, alpha, nc, eps, phi=phi)
     torch.cuda.synchronize()
     check(host(out), want[0], TOL[io], what + " out")
-    check(host(gs[0]), want[1], TOL[io], what + " S")
-    check(host(gs[1]), want[2], TOL[io], what + " z")
+    check(host(gs[0]), want[1], STATE_TOL, what + " S")
+    check(host(gs[1]), want[2], STATE_TOL, what + " z")
     assert np.array_equal(host(gs[2]), workloads.round_to_io(want[3], io).astype(np.float64)), what + " hist"
     assert np.array_equal(gs[5].cpu().numpy(), np.repeat(want[6][:, None], H, axis=1)), what + " rows in use"
     for b, n in enumerate(want[6]):

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import oracle
-from parity import TOL, check, dev, host
+from parity import STATE_TOL, TOL, check, dev, host
 from paper_2406_07368_amd import binding, workloads
 from test_gpu_prefill import small_case
 from test_gpu_verify import make_case
@@ -50,10 +50,10 @@ def test_relu_verify_and_decode(io, B, H):
     torch.cuda.synchronize()
     tol = TOL[io]
     check(host(out), want[0], tol, "verify out")
-    check(host(state[0]), want[1], tol, "verify S")
-    check(host(state[1]), want[2], tol, "verify z")
+    check(host(state[0]), want[1], STATE_TOL, "verify S")
+    check(host(state[1]), want[2], STATE_TOL, "verify z")
     check(host(out1)[:, :, None], want1[0], tol, "decode out")
-    check(host(state1[0]), want1[1], tol, "decode S")
+    check(host(state1[0]), want1[1], STATE_TOL, "decode S")
 
 
 def test_relu_tree_verify():
@@ -70,6 +70,6 @@ def test_relu_tree_verify():
                               torch.from_numpy(accept).cuda(), EPS, phi="relu")
     torch.cuda.synchronize()
     check(host(out), want[0], TOL["bf16"], "out")
-    check(host(state[0]), want[1], TOL["bf16"], "S")
-    check(host(state[1]), want[2], TOL["bf16"], "z")
+    check(host(state[0]), want[1], STATE_TOL, "S")
+    check(host(state[1]), want[2], STATE_TOL, "z")
     assert np.array_equal(host(state[2]), workloads.round_to_io(want[3], "bf16").astype(np.float64))
