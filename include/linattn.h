@@ -125,6 +125,27 @@ linattn_status linattn_prefill(const linattn_desc *desc, int32_t L,
                                void *workspace, size_t workspace_bytes,
                                void *hip_stream);
 
+/* linattn_prefill for callers that cannot allocate or pass device scratch (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments minus the workspace, same kernels, same
+ * results bit for bit.  The scratch of a segmented prefill lives in a static device array inside the library,
+ * linattn_noalloc_scratch_bytes() = 17 432 576 bytes, which every GPU the library runs on holds until the
+ * process ends; that is enough for every descriptor linattn_prefill accepts (LINATTN_ERR_WORKSPACE if a request
+ * ever needed more).  The call allocates and frees nothing; its first use on a device asks the runtime once for the
+ * array's address there (with that device current, which is also the device `hip_stream` must belong to).
+ * All calls on one GPU share the one array: two such calls that overlap in time on the same GPU (different
+ * streams, or a captured graph replayed concurrently with itself) race; calls in stream order are safe, and
+ * nothing in the array needs to be cleared between calls. */
+linattn_status linattn_prefill_noalloc(const linattn_desc *desc, int32_t L,
+                                       const void *q, const void *k, const void *v,
+                                       const float *conv_w,
+                                       const float *S_in, const float *z_in, const void *hist_in,
+                                       void *out,
+                                       float *S_out, float *z_out, void *hist_out,
+                                       void *hip_stream);
+
+/* Size in bytes of the static device scratch behind linattn_prefill_noalloc. */
+size_t linattn_noalloc_scratch_bytes(void);
+
 /* Prefill in the three-branch form of Sec. 4.1 (the text around the figure of the
  * augmented attention): the sequence is cut into consecutive groups of `chunk`
  * tokens, counted from the first token of the call, and every token gets

@@ -21,7 +21,7 @@ LINATTN_F32, LINATTN_BF16 = 0, 1
 LINATTN_PHI_ELU1, LINATTN_PHI_RELU = 0, 1
 PHI = {"elu1": LINATTN_PHI_ELU1, "relu": LINATTN_PHI_RELU}
 MAX_CONV_K, MAX_DRAFT, MAX_TREE = 8, 16, 64
-SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_grouped", "linattn_verify", "linattn_verify_grouped", "linattn_verify_tree", "linattn_decode",
+SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_noalloc", "linattn_noalloc_scratch_bytes", "linattn_prefill_grouped", "linattn_verify", "linattn_verify_grouped", "linattn_verify_tree", "linattn_decode",
            "linattn_set_wait_limit", "linattn_status_string", "linattn_version")
 
 
@@ -53,6 +53,10 @@ def load():
     lib.linattn_workspace_bytes.argtypes = [dp, i32]
     lib.linattn_prefill.restype = ctypes.c_int
     lib.linattn_prefill.argtypes = [dp, i32] + [vp] * 11 + [vp, sz, vp]
+    lib.linattn_prefill_noalloc.restype = ctypes.c_int
+    lib.linattn_prefill_noalloc.argtypes = [dp, i32] + [vp] * 11 + [vp]
+    lib.linattn_noalloc_scratch_bytes.restype = sz
+    lib.linattn_noalloc_scratch_bytes.argtypes = []
     lib.linattn_prefill_grouped.restype = ctypes.c_int
     lib.linattn_prefill_grouped.argtypes = [dp, i32, ctypes.c_float] + [vp] * 11 + [vp, sz, vp]
     lib.linattn_verify.restype = ctypes.c_int
@@ -122,6 +126,17 @@ def linattn_prefill(desc: Desc, L, q, k, v, conv_w, S_in, z_in, hist_in, out, S_
                                 _ptr(S_in), _ptr(z_in), _ptr(hist_in), _ptr(out), _ptr(S_out), _ptr(z_out),
                                 _ptr(hist_out), _ptr(workspace), int(workspace_bytes), _stream(stream))
     _check(st, "linattn_prefill")
+
+
+def linattn_prefill_noalloc(desc: Desc, L, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, stream=None) -> None:
+    st = load().linattn_prefill_noalloc(ctypes.byref(desc), int(L), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
+                                        _ptr(S_in), _ptr(z_in), _ptr(hist_in), _ptr(out), _ptr(S_out), _ptr(z_out),
+                                        _ptr(hist_out), _stream(stream))
+    _check(st, "linattn_prefill_noalloc")
+
+
+def linattn_noalloc_scratch_bytes() -> int:
+    return int(load().linattn_noalloc_scratch_bytes())
 
 
 def linattn_prefill_grouped(desc: Desc, L, alpha, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out,

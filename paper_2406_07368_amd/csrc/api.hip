@@ -8,6 +8,7 @@
 #include <atomic>
 
 #include "kernels.h"
+#include "mfma_util.h"
 
 using namespace linattn;
 
@@ -16,6 +17,34 @@ namespace {
 // Polls before a wait between the waves of a prefill workgroup gives up (linattn_set_wait_limit).
 constexpr int32_t kDefaultWaitSpins = 1 << 20;
 std::atomic<int32_t> g_wait_spins{kDefaultWaitSpins};
+
+// Scratch of linattn_prefill_noalloc: the workspace of a segmented prefill, held by every GPU the library runs
+// on until the process ends.  Sized for the largest workspace any descriptor can ask for: the launch plan never
+// puts more than 256 (b, h, segment) slots of d*d + d floats on the chip, plus 8 staged history rows per (b, h)
+// for fewer than 256 of those.
+constexpr size_t kScratchBytes = 256 * (128 * 128 + 128) * sizeof(float) + 256 * HALO * 128 * sizeof(uint16_t);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// In host code `scratch` is only a handle for the symbol: the array's device address is asked for once per device
+// (each GPU has its own copy at its own address) and kept here.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+hipError_t scratch_for_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the same answer from every thread that gets here first
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return hipSuccess;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -146,6 +175,22 @@ linattn_status linattn_prefill(const linattn_desc* desc, int32_t L, const void* 
   return prefill_any(desc, L, false, 0.f, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, workspace,
                      workspace_bytes, hip_stream);
 }
+
+linattn_status linattn_prefill_noalloc(const linattn_desc* desc, int32_t L, const void* q, const void* k, const void* v,
+                                       const float* conv_w, const float* S_in, const float* z_in, const void* hist_in,
+                                       void* out, float* S_out, float* z_out, void* hist_out, void* hip_stream) {
+  linattn_status st = check_desc(desc, true, true);
+  if (st != LINATTN_OK) return st;
+  if (L < 0) return LINATTN_ERR_SHAPE;
+  const size_t need = plan_prefill(desc, L).ws_bytes;
+  if (need > kScratchBytes) return LINATTN_ERR_WORKSPACE;     // beyond what the static scratch holds
+  void* ws = nullptr;
+  if (need > 0 && scratch_for_current_device(&ws) != hipSuccess) return LINATTN_ERR_HIP;
+  return prefill_any(desc, L, false, 0.f, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, ws, need,
+                     hip_stream);
+}
+
+size_t linattn_noalloc_scratch_bytes(void) { return kScratchBytes; }
 
 linattn_status linattn_prefill_grouped(const linattn_desc* desc, int32_t L, float alpha, const void* q, const void* k,
                                        const void* v, const float* conv_w, const float* S_in, const float* z_in,
