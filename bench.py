@@ -18,7 +18,8 @@ prefill launches, measured with events on the launch stream inside the timed
 region); the verify/decode step times are reported beside it in microseconds with
 their own HBM roofline; the tree-structured verify (64 candidates) and the three-branch form of
 the prefill with its one-token generation step are timed after the steps and reported as ``tree_verify``,
-``prefill_grouped`` and ``verify_grouped`` (one token = decode, and eight drafts).  Between steps the verify state rotates over 32 separate
+``prefill_grouped`` and ``verify_grouped`` (one token = decode, and eight drafts); the prefill workloads of
+configs 1, 2 and 5 likewise, as ``other_configs``.  Between steps the verify state rotates over 32 separate
 state sets (2.1 GB) and the prefill inputs over 2 sets (2.1 GB) so that nothing is
 served from the 256 MB last-level cache.
 
@@ -282,6 +283,91 @@ def main():
         other_layout_ms = {"layout": other, "mean": sum(a.elapsed_time(b) for a, b in ev2) / len(ev2),
                            "min": min(a.elapsed_time(b) for a, b in ev2)}
 
+    side = None
+    if args.only == "all" and not args.length:
+        # the other prefill workloads (not part of the step): configs 1, 2 and 5, head-major as the parity tests
+        # run them, two input sets each (config 2's 25 MB would otherwise be served from the last-level cache)
+        side = {}
+        for name in ("cfg1_fp32_tiny", "cfg2_gpt2_small", "cfg5_long_context"):
+            wl = workloads.CONFIGS[name]
+            sdt = workloads.torch_dtype(wl.io_dtype)
+            gs = torch.Generator(device=dev).manual_seed(wl.seed)
+            sets = []
+            for _ in range(2 if name != "cfg2_gpt2_small" else 16):
+                q, k, v = ((torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev) * wl.scale).to(sdt) for _ in range(3))
+                sets.append((q, k, v, torch.empty_like(q)))
+            swts = torch.from_numpy(workloads.conv_weights(np.random.default_rng(wl.seed), wl.H, wl.d, wl.conv_k)).to(dev)
+            sdesc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, sdt, L=wl.L)
+            sws_bytes = binding.linattn_workspace_bytes(sdesc, wl.L)
+            sws = torch.empty(max(sws_bytes, 16), dtype=torch.uint8, device=dev)
+            sS = torch.empty((wl.B, wl.H, wl.d, wl.d), device=dev)
+            sz = torch.empty((wl.B, wl.H, wl.d), device=dev)
+            sh = torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d), device=dev, dtype=sdt)
+            evs = []
+            n_warm, n_timed = 20, min(max(args.steps, 20), 50)
+            for i in range(n_warm + n_timed):
+                q, k, v, out = sets[i % len(sets)]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                binding.linattn_prefill(sdesc, wl.L, q, k, v, swts, None, None, None, out, sS, sz, sh, sws, sws_bytes, stream)
+                e1.record(stream)
+                if i >= n_warm:
+                    evs.append((e0, e1))
+            stream.synchronize()
+            t_ms = [a.elapsed_time(b) for a, b in evs]
+            t_mean = sum(t_ms) / len(t_ms)
+            esz = 4 if wl.io_dtype == "f32" else 2
+            nb = 4 * wl.B * wl.H * wl.L * wl.d * esz
+            side[name] = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d{wl.d} {wl.io_dtype} chunk{wl.chunk} Kc{wl.conv_k}, head-major",
+                          "ms": {"mean": t_mean, "median": float(np.median(t_ms)), "min": min(t_ms)},
+                          "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3), "workspace_bytes": sws_bytes,
+                          "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
+            del sets, sws, sS, sz, sh
+        torch.cuda.empty_cache()
+
+    flash = None
+    if args.only == "all" and not args.length:
+        # next row of the scope (not part of the step): the sizes of the paper's FLASH experiment -- 63-tap masked
+        # DWConv, groups of 256 tokens, batch 1, 1K / 4K / 8K tokens, as eight heads of 128.  Token-level form
+        # (matrix-core attention kernel + the long-convolution pass) and the three-branch form in groups of 256
+        # (the plain fp32 kernel: one workgroup per head, token by token -- correct, not fast).
+        flash = {}
+        for name in ("flash_L1024", "flash_L4096", "flash_L8192"):
+            wl = workloads.CONFIGS[name]
+            gs = torch.Generator(device=dev).manual_seed(wl.seed)
+            q, k, v = ((torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev) * wl.scale).to(torch.bfloat16) for _ in range(3))
+            out = torch.empty_like(q)
+            fw = torch.from_numpy(workloads.conv_weights(np.random.default_rng(wl.seed), wl.H, wl.d, wl.conv_k)).to(dev)
+            fdesc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, torch.bfloat16, L=wl.L)
+            fws_bytes = binding.linattn_workspace_bytes(fdesc, wl.L)
+            fws = torch.empty(max(fws_bytes, 16), dtype=torch.uint8, device=dev)
+            fS = torch.empty((wl.B, wl.H, wl.d, wl.d), device=dev)
+            fz = torch.empty((wl.B, wl.H, wl.d), device=dev)
+            fh = torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d), device=dev, dtype=torch.bfloat16)
+            nb = 4 * wl.B * wl.H * wl.L * wl.d * 2
+            row = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d{wl.d} bf16, groups of {wl.chunk}, Kc{wl.conv_k}, head-major"}
+            for key, n_warm, n_timed, call in (
+                    ("token_level", 10, 30, lambda: binding.linattn_prefill(fdesc, wl.L, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream)),
+                    ("three_branch", 1, 3, lambda: binding.linattn_prefill_grouped(fdesc, wl.L, 1.0, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream))):
+                evs = []
+                for i in range(n_warm + n_timed):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    call()
+                    e1.record(stream)
+                    if i >= n_warm:
+                        evs.append((e0, e1))
+                stream.synchronize()
+                t_ms = [a.elapsed_time(b) for a, b in evs]
+                t_mean = sum(t_ms) / len(t_ms)
+                row[key] = {"ms": {"mean": t_mean, "min": min(t_ms)}, "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3),
+                            "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
+            flash[name] = row
+            del q, k, v, out, fws
+        torch.cuda.empty_cache()
+
     grouped = None
     if do_prefill and args.only == "all" and pw.chunk == 64:
         # next row of the scope (not part of the step): the three-branch form of the same prefill (grouped linear
@@ -443,6 +529,10 @@ def main():
             result["value"] = us["k8"]["mean"]
             result["unit"] = "us/step (verify k=8)"
             result["higher_is_better"] = False
+    if side:
+        result["other_configs"] = side
+    if flash:
+        result["flash_shape"] = flash
     if not args.no_cpu_baseline and do_prefill:
         result["cpu_baseline"] = cpu_baseline(pw, args.cpu_seconds)
     print(json.dumps(result))

@@ -79,16 +79,21 @@ typedef enum { LINATTN_F32 = 0, LINATTN_BF16 = 1 } linattn_dtype;
  * existing ones (Sec. 3, "Comprehensive Evaluation"); its denominator can vanish, so pass eps > 0. */
 typedef enum { LINATTN_PHI_ELU1 = 0, LINATTN_PHI_RELU = 1 } linattn_phi;
 
-#define LINATTN_MAX_CONV_K 8   /* taps t, t-1, ..., t-Kc+1                              */
+#define LINATTN_MAX_CONV_K 8   /* taps t, t-1, ..., t-Kc+1: verify, decode, tree            */
+#define LINATTN_MAX_CONV_K_PREFILL 63  /* ... and of the prefill entry points (Sec. 4.1: the
+                                  FLASH experiment uses a masked DWConv of kernel size 63) */
 #define LINATTN_MAX_DRAFT 16   /* draft tokens per verify call                          */
 #define LINATTN_MAX_TREE 64    /* candidate tokens per tree-verify call                 */
 
 typedef struct {
   int32_t B, H;            /* batch rows, heads                                        */
   int32_t d;               /* head dimension d_k = d_v: 64 or 128                       */
-  int32_t conv_k;          /* Kc, 1..LINATTN_MAX_CONV_K                                 */
-  int32_t chunk;           /* tokens per group in prefill: 64 or 128 (ignored by
-                              verify/decode).  The result does not depend on it.       */
+  int32_t conv_k;          /* Kc, 1..LINATTN_MAX_CONV_K; the prefill entry points take
+                              up to LINATTN_MAX_CONV_K_PREFILL (kernels of more than 8
+                              taps run as a pass of their own behind the attention)     */
+  int32_t chunk;           /* tokens per group in prefill: 64, 128 or 256 (ignored by
+                              verify/decode).  The result of linattn_prefill does not
+                              depend on it; that of the three-branch form does.         */
   int32_t io_dtype;        /* linattn_dtype of q, k, v, out, hist                       */
   int32_t phi;             /* linattn_phi                                               */
   float eps;               /* added to every denominator; >= 0                          */
@@ -161,9 +166,12 @@ size_t linattn_noalloc_scratch_bytes(void);
  * linattn_workspace_bytes); the state handed back is the same running sum.  To
  * continue a sequence with the same grouping, cut it at multiples of `chunk`.
  *   alpha        finite (LINATTN_ERR_SHAPE otherwise)
- * chunk must be 64 (LINATTN_ERR_UNSUPPORTED otherwise).  bf16 rows run on the
- * matrix cores; fp32 rows on a plain fp32 kernel that is exact to fp32 rounding
- * but not built for speed. */
+ * chunk must be 64 (the paper's group size for LLaMA) or 256 (its group size for
+ * FLASH, Sec. 5 "Settings"); LINATTN_ERR_UNSUPPORTED otherwise, and for fp32 rows
+ * of 128 elements in groups of 256.  bf16 rows in groups of 64 run on the matrix
+ * cores; fp32 rows, and all rows in groups of 256, on a plain fp32 kernel that is
+ * exact to fp32 rounding but not built for speed (one workgroup per (b, h), no
+ * workspace). */
 linattn_status linattn_prefill_grouped(const linattn_desc *desc, int32_t L, float alpha,
                                        const void *q, const void *k, const void *v,
                                        const float *conv_w,

@@ -20,7 +20,7 @@ _lib = None
 LINATTN_F32, LINATTN_BF16 = 0, 1
 LINATTN_PHI_ELU1, LINATTN_PHI_RELU = 0, 1
 PHI = {"elu1": LINATTN_PHI_ELU1, "relu": LINATTN_PHI_RELU}
-MAX_CONV_K, MAX_DRAFT, MAX_TREE = 8, 16, 64
+MAX_CONV_K, MAX_CONV_K_PREFILL, MAX_DRAFT, MAX_TREE = 8, 63, 16, 64
 SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_noalloc", "linattn_noalloc_scratch_bytes", "linattn_prefill_grouped", "linattn_verify", "linattn_verify_grouped", "linattn_verify_tree", "linattn_decode",
            "linattn_set_wait_limit", "linattn_status_string", "linattn_version")
 
@@ -207,10 +207,10 @@ def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, str
     return out, (S, z, h)
 
 
-def prefill_grouped(q, k, v, conv_w, alpha=1.0, state=None, eps=0.0, want_state=True, stream=None, phi="elu1"):
+def prefill_grouped(q, k, v, conv_w, alpha=1.0, state=None, eps=0.0, want_state=True, stream=None, phi="elu1", group=64):
     """The three-branch form (grouped linear attention, weight alpha + local softmax attention + masked conv)
-    with groups of 64 tokens; arguments as for ``prefill``."""
-    return prefill(q, k, v, conv_w, state, 64, eps, want_state, stream, phi, grouped_alpha=alpha)
+    with groups of 64 or 256 tokens; arguments as for ``prefill``."""
+    return prefill(q, k, v, conv_w, state, group, eps, want_state, stream, phi, grouped_alpha=alpha)
 
 
 def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None, phi="elu1"):

@@ -50,16 +50,16 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 // chunk: the group size takes part in the call; strides: q, k, v, out are addressed by the descriptor's strides
 // (the verify entry points take dense tensors and ignore them).
-linattn_status check_desc(const linattn_desc* d, bool chunk, bool strides) {
+linattn_status check_desc(const linattn_desc* d, bool chunk, bool strides, int max_conv_k = LINATTN_MAX_CONV_K) {
   if (!d) return LINATTN_ERR_NULL;
   if (d->io_dtype != LINATTN_F32 && d->io_dtype != LINATTN_BF16) return LINATTN_ERR_DTYPE;
   if (d->phi != LINATTN_PHI_ELU1 && d->phi != LINATTN_PHI_RELU) return LINATTN_ERR_DTYPE;
   if (d->B < 1 || d->H < 1) return LINATTN_ERR_SHAPE;
   if ((int64_t)d->B * d->H > (int64_t)1 << 24) return LINATTN_ERR_SHAPE;
   if (d->d != 64 && d->d != 128) return LINATTN_ERR_SHAPE;
-  if (d->conv_k < 1 || d->conv_k > LINATTN_MAX_CONV_K) return LINATTN_ERR_SHAPE;
+  if (d->conv_k < 1 || d->conv_k > max_conv_k) return LINATTN_ERR_SHAPE;
   if (!(d->eps >= 0.f)) return LINATTN_ERR_SHAPE;
-  if (chunk && d->chunk != 64 && d->chunk != 128) return LINATTN_ERR_SHAPE;
+  if (chunk && d->chunk != 64 && d->chunk != 128 && d->chunk != 256) return LINATTN_ERR_SHAPE;
   if (strides) {
     if (d->stride_t < d->d || d->stride_h < 0 || d->stride_b < 0) return LINATTN_ERR_SHAPE;
     if ((d->stride_t | d->stride_h | d->stride_b) & 7) return LINATTN_ERR_SHAPE;
@@ -78,9 +78,10 @@ struct PrefillPlan {
 // kernel (exact fp32 products).  bf16 inputs go to the matrix-core kernel; when
 // B*H alone cannot fill the 256 compute units the sequence axis is cut into
 // segments whose start states come from a first pass over K, V and a scan.
-PrefillPlan plan_prefill(const linattn_desc* d, int32_t L) {
+PrefillPlan plan_prefill(const linattn_desc* d, int32_t L, bool grouped = false) {
   PrefillPlan p{};
-  p.mfma = d->io_dtype == LINATTN_BF16;
+  // the matrix-core kernel's three-branch form has groups of 64 tokens; groups of 256 take the vector-ALU kernel
+  p.mfma = d->io_dtype == LINATTN_BF16 && !(grouped && d->chunk != 64);
   p.nseg = 1;
   p.seg_len = L;
   if (p.mfma && L > 0) {
@@ -98,13 +99,13 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
                            const void* v, const float* conv_w, const float* S_in, const float* z_in, const void* hist_in,
                            void* out, float* S_out, float* z_out, void* hist_out, void* workspace,
                            size_t workspace_bytes, void* hip_stream) {
-  linattn_status st = check_desc(desc, true, true);
+  linattn_status st = check_desc(desc, true, true, LINATTN_MAX_CONV_K_PREFILL);
   if (st != LINATTN_OK) return st;
   if (L < 0) return LINATTN_ERR_SHAPE;
   if (grouped) {
     if (!(alpha == alpha) || alpha - alpha != 0.f) return LINATTN_ERR_SHAPE;   // NaN, infinity
-    // the groups are part of the result here: only the kernels' own group of 64 tokens
-    if (desc->chunk != 64) return LINATTN_ERR_UNSUPPORTED;
+    // the groups are part of the result here: 64 tokens (the paper's size for LLaMA) or 256 (its size for FLASH)
+    if (!prefill_grouped_simt_available(desc->io_dtype == LINATTN_BF16, desc->d, desc->chunk)) return LINATTN_ERR_UNSUPPORTED;
   }
   if (!conv_w) return LINATTN_ERR_NULL;
   if (L > 0 && (!q || !k || !v || !out)) return LINATTN_ERR_NULL;
@@ -118,24 +119,37 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
   // the last token of the last (b, h) must be addressable with 64-bit offsets
   if ((double)desc->stride_b * desc->B + (double)desc->stride_h * desc->H + (double)desc->stride_t * L > 9.0e18)
     return LINATTN_ERR_SHAPE;
-  const PrefillPlan plan = plan_prefill(desc, L);
+  const PrefillPlan plan = plan_prefill(desc, L, grouped);
   if (plan.ws_bytes > 0 && (!workspace || workspace_bytes < plan.ws_bytes)) return LINATTN_ERR_WORKSPACE;
 
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   PrefillArgs a{};
+  // More than 8 taps: the attention kernels run without the convolution (one tap, taken as zero, no history) and
+  // a pass of its own adds it to the outputs and hands the history on.
+  const bool long_conv = desc->conv_k > LINATTN_MAX_CONV_K;
+  const bool kernel_hist = has_hist && !long_conv;
   a.q = q; a.k = k; a.v = v; a.conv_w = conv_w;
-  a.S_in = S_in; a.z_in = z_in; a.hist_in = has_hist ? hist_in : nullptr;
-  a.out = out; a.S_out = S_out; a.z_out = z_out; a.hist_out = has_hist ? hist_out : nullptr;
+  a.S_in = S_in; a.z_in = z_in; a.hist_in = kernel_hist ? hist_in : nullptr;
+  a.out = out; a.S_out = S_out; a.z_out = z_out; a.hist_out = kernel_hist ? hist_out : nullptr;
   a.ws = static_cast<float*>(workspace);
-  a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
+  a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = long_conv ? 1 : desc->conv_k; a.no_conv = long_conv;
+  a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU; a.group = desc->chunk;
   a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
   a.nseg = plan.nseg; a.seg_len = plan.seg_len;
   a.alpha = alpha;
   a.wait_spins = g_wait_spins.load(std::memory_order_relaxed);
   hipError_t e;
+  const bool bf16 = desc->io_dtype == LINATTN_BF16;
   if (plan.mfma && L > 0) e = launch_prefill_mfma(a, desc->d, desc->chunk, grouped, stream);
-  else if (grouped && L > 0) e = launch_prefill_grouped_simt(a, desc->d, stream);      // fp32 rows
-  else e = launch_prefill_simt(a, desc->io_dtype == LINATTN_BF16, desc->d, stream);   // L = 0: the state is handed through
+  else if (grouped && L > 0) e = launch_prefill_grouped_simt(a, bf16, desc->d, stream);   // fp32 rows; groups of 256
+  else e = launch_prefill_simt(a, bf16, desc->d, stream);                                 // L = 0: the state is handed through
+  if (e == hipSuccess && long_conv) {
+    ConvLongArgs c{};
+    c.v = v; c.conv_w = conv_w; c.hist_in = hist_in; c.out = out; c.hist_out = hist_out;
+    c.B = desc->B; c.H = desc->H; c.L = L; c.Kc = desc->conv_k;
+    c.sb = desc->stride_b; c.sh = desc->stride_h; c.st = desc->stride_t;
+    e = launch_conv_long(c, bf16, desc->d, stream);
+  }
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 
@@ -164,7 +178,7 @@ int32_t linattn_set_wait_limit(int32_t spins) {
 }
 
 size_t linattn_workspace_bytes(const linattn_desc* desc, int32_t L) {
-  if (check_desc(desc, true, true) != LINATTN_OK || L < 0) return 0;
+  if (check_desc(desc, true, true, LINATTN_MAX_CONV_K_PREFILL) != LINATTN_OK || L < 0) return 0;
   return plan_prefill(desc, L).ws_bytes;
 }
 
@@ -179,7 +193,7 @@ linattn_status linattn_prefill(const linattn_desc* desc, int32_t L, const void* 
 linattn_status linattn_prefill_noalloc(const linattn_desc* desc, int32_t L, const void* q, const void* k, const void* v,
                                        const float* conv_w, const float* S_in, const float* z_in, const void* hist_in,
                                        void* out, float* S_out, float* z_out, void* hist_out, void* hip_stream) {
-  linattn_status st = check_desc(desc, true, true);
+  linattn_status st = check_desc(desc, true, true, LINATTN_MAX_CONV_K_PREFILL);
   if (st != LINATTN_OK) return st;
   if (L < 0) return LINATTN_ERR_SHAPE;
   const size_t need = plan_prefill(desc, L).ws_bytes;

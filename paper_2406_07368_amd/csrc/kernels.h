@@ -76,6 +76,18 @@ struct PrefillArgs {
   int nseg;                 // workgroups along the sequence axis per (b, h)
   int seg_len;              // tokens per segment (multiple of the chunk size)
   int wait_spins;           // polls before a wait between the waves of a workgroup gives up; < 0: give up at once
+  int no_conv;              // the taps are taken as zero: a convolution with more than 8 taps runs as a pass of its own
+  int group;                // three-branch form: tokens per group (64 or 256)
+};
+
+struct ConvLongArgs {
+  const void* v;            // [B,H,L,d] by strides
+  const float* conv_w;      // [H,d,Kc]
+  const void* hist_in;      // [B,H,Kc-1,d] or null
+  void* out;                // [B,H,L,d] by strides: out += conv
+  void* hist_out;           // [B,H,Kc-1,d] or null; may be hist_in
+  int B, H, L, Kc;
+  int64_t sb, sh, st;
 };
 
 // verify.hip
@@ -98,8 +110,12 @@ hipError_t launch_verify_tree(const VerifyTreeArgs& a, int d, hipStream_t st);
 
 // prefill_simt.hip : fp32 arithmetic on the vector ALUs, one workgroup per (b, h)
 hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st);
-// ... and the three-branch form for fp32 rows (groups of 64 tokens, a.alpha)
-hipError_t launch_prefill_grouped_simt(const PrefillArgs& a, int d, hipStream_t st);
+// ... and the three-branch form (a.group tokens per group, a.alpha): fp32 rows, and any rows in groups of 256
+bool prefill_grouped_simt_available(bool bf16, int d, int group);
+hipError_t launch_prefill_grouped_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st);
+
+// conv_long.hip : out += causal depthwise conv with 9..63 taps, and the history that goes with it
+hipError_t launch_conv_long(const ConvLongArgs& a, bool bf16, int d, hipStream_t st);
 
 // prefill_mfma.hip : launch plan of the bf16 prefill (segments, prefix sum over segment states)
 int prefill_mfma_pick_segments(int BH, int L, int chunk);

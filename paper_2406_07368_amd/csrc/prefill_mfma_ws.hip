@@ -553,7 +553,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 #pragma unroll
       for (int mth = 0; mth < TAP_IT; ++mth) {
         const int e = lt + G::NLT * mth;
-        if (e < KCM * D) wl[e] = e / D < a.Kc ? tap_reg[mth] : 0.f;
+        if (e < KCM * D) wl[e] = (e / D < a.Kc && !a.no_conv) ? tap_reg[mth] : 0.f;
       }
 #pragma unroll
       for (int mth = 0; mth < HALO_IT; ++mth) {

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
 
   float wreg[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) wreg[j] = j < Kc ? a.conv_w[((size_t)h * D + c) * Kc + j] : 0.f;
+  for (int j = 0; j < 8; ++j) wreg[j] = (j < Kc && !a.no_conv) ? a.conv_w[((size_t)h * D + c) * Kc + j] : 0.f;
 
   for (int e = tid; e < D * D; e += 256) S[e] = a.S_in ? a.S_in[(size_t)bh * D * D + e] : 0.f;
   if (tid < D) zz[tid] = a.z_in ? a.z_in[(size_t)bh * D + tid] : 0.f;
@@ -144,42 +144,52 @@ __global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
 }
 
 // The three-branch form (grouped linear attention over the groups before a token's own, weight alpha + causal
-// softmax attention inside its group of 64 + masked conv) with fp32 arithmetic: the path for fp32 rows.  One
-// workgroup walks one (b, h) group by group and, inside a group, token by token; S and z are only advanced at
-// the end of a group, which is exactly what the linear branch is defined on.  Not tuned for throughput.
+// softmax attention inside its group + masked conv) with fp32 arithmetic: the path for fp32 rows, and for
+// groups of 256 tokens (the group size of the paper's FLASH experiment, Sec. 5 "Settings") whatever the rows.
+// One workgroup walks one (b, h) group by group and, inside a group, token by token; S and z are only advanced
+// at the end of a group, which is exactly what the linear branch is defined on.  The state sits in registers
+// (thread (c, tg) holds S[i][c] for i = tg, tg + NG, ...), the group's raw key rows and value rows in LDS in
+// the i/o dtype.  Exact to fp32 rounding; not built for speed.
 namespace {
-constexpr int GC = 64;     // tokens per group
-template <int D>
+template <typename Io, int D, int GCT>
 struct GroupedSimtLayout {
-  static constexpr int S = 0;                         // [D][D]
-  static constexpr int KR = S + D * D;                // [GC][D+1] raw key rows of the group
-  static constexpr int VV = KR + GC * (D + 1);        // [HMAX+GC][D]: history rows, then the group's value rows
-  static constexpr int QR = VV + (HMAX + GC) * D;     // [D] raw q_t
+  typedef typename Io::elem elem;
+  static constexpr int KSTR = D + 4 / (int)sizeof(elem);                  // key row stride: one 4-byte word of padding
+  static constexpr int KR = 0;                                             // [GCT][KSTR] raw key rows of the group (elem)
+  static constexpr int VV = KR + GCT * KSTR * (int)sizeof(elem);           // [HMAX+GCT][D]: history rows, then the group's value rows (elem)
+  static constexpr int F0 = (VV + (HMAX + GCT) * D * (int)sizeof(elem) + 15) / 16 * 16;   // floats from here
+  static constexpr int QR = 0;                        // [D] raw q_t
   static constexpr int FQ = QR + D;                   // [D] phi(q_t)
-  static constexpr int LG = FQ + D;                   // [GC] logits, then weights
-  static constexpr int PART = LG + GC;                // [256 / D][D] partial outputs
+  static constexpr int LG = FQ + D;                   // [GCT] logits, then weights
+  static constexpr int PART = LG + GCT;               // [256 / D][D] partial outputs
   static constexpr int ZZ = PART + 256;               // [D]
-  static constexpr int SCAL = ZZ + D;                 // [4]
-  static constexpr int TOTAL = SCAL + 4;
+  static constexpr int SCAL = ZZ + D;                 // [16]: alpha / denominator; per-wave maxima and sums
+  static constexpr int NFLOAT = SCAL + 16;
+  static constexpr int TOTAL = F0 + NFLOAT * (int)sizeof(float);
 };
+__device__ __forceinline__ float elem_to_f32(float x) { return x; }
+__device__ __forceinline__ float elem_to_f32(uint16_t x) { return bf16_bits_to_f32(x); }
 }  // namespace
 
-template <typename Io, int D>
+template <typename Io, int D, int GCT>
 __global__ __launch_bounds__(256) void prefill_grouped_simt_kernel(PrefillArgs a) {
-  using Lay = GroupedSimtLayout<D>;
+  using Lay = GroupedSimtLayout<Io, D, GCT>;
+  typedef typename Io::elem elem;
   constexpr int NG = 256 / D;
-  extern __shared__ float sm[];
-  float* S = sm + Lay::S;
-  float* kr = sm + Lay::KR;
-  float* vv = sm + Lay::VV;
-  float* qr = sm + Lay::QR;
-  float* fq = sm + Lay::FQ;
-  float* lg = sm + Lay::LG;
-  float* part = sm + Lay::PART;
-  float* zz = sm + Lay::ZZ;
-  float* scal = sm + Lay::SCAL;
+  constexpr int NS = D / NG;                           // state rows per thread
+  constexpr int KSTR = Lay::KSTR;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  elem* kr = reinterpret_cast<elem*>(smem + Lay::KR);
+  elem* vv = reinterpret_cast<elem*>(smem + Lay::VV);
+  float* fl = reinterpret_cast<float*>(smem + Lay::F0);
+  float* qr = fl + Lay::QR;
+  float* fq = fl + Lay::FQ;
+  float* lg = fl + Lay::LG;
+  float* part = fl + Lay::PART;
+  float* zz = fl + Lay::ZZ;
+  float* scal = fl + Lay::SCAL;
 
-  const int tid = threadIdx.x, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
   const int Kc = a.Kc, L = a.L;
   const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
@@ -189,30 +199,27 @@ __global__ __launch_bounds__(256) void prefill_grouped_simt_kernel(PrefillArgs a
 
   float wreg[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) wreg[j] = j < Kc ? a.conv_w[((size_t)h * D + c) * Kc + j] : 0.f;
-  for (int e = tid; e < D * D; e += 256) S[e] = a.S_in ? a.S_in[(size_t)bh * D * D + e] : 0.f;
+  for (int j = 0; j < 8; ++j) wreg[j] = (j < Kc && !a.no_conv) ? a.conv_w[((size_t)h * D + c) * Kc + j] : 0.f;
+  float Sreg[NS];                                      // S[tg + NG m][c]
+#pragma unroll
+  for (int m = 0; m < NS; ++m) Sreg[m] = a.S_in ? a.S_in[(size_t)bh * D * D + (size_t)(tg + NG * m) * D + c] : 0.f;
   if (tid < D) zz[tid] = a.z_in ? a.z_in[(size_t)bh * D + tid] : 0.f;
   for (int e = tid; e < HMAX * D; e += 256) {
     const int row = e / D, cc = e % D;
     const int r = row - (HMAX - (Kc - 1));   // row of the incoming history, oldest first
-    vv[e] = (r >= 0 && a.hist_in) ? Io::load1(a.hist_in, ((int64_t)bh * (Kc - 1) + r) * D + cc) : 0.f;
+    if (r >= 0 && a.hist_in) vv[e] = static_cast<const elem*>(a.hist_in)[((int64_t)bh * (Kc - 1) + r) * D + cc];
+    else vv[e] = (elem)0;
   }
   __syncthreads();
 
-  for (int t0 = 0; t0 < L; t0 += GC) {
-    const int nt = (L - t0) < GC ? (L - t0) : GC;
-    // a. the group's raw key and value rows
-    for (int c8 = tid; c8 < nt * (D / 8); c8 += 256) {
-      const int t = c8 / (D / 8), i0 = (c8 % (D / 8)) * 8;
-      float xk[8], xv[8];
-      const int64_t off = base + (int64_t)(t0 + t) * a.st + i0;
-      Io::load8(a.k, off, xk);
-      Io::load8(a.v, off, xv);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        kr[t * (D + 1) + i0 + e] = xk[e];
-        vv[(HMAX + t) * D + i0 + e] = xv[e];
-      }
+  for (int t0 = 0; t0 < L; t0 += GCT) {
+    const int nt = (L - t0) < GCT ? (L - t0) : GCT;
+    // a. the group's raw key and value rows, as they are
+    for (int e = tid; e < nt * D; e += 256) {
+      const int t = e / D, i = e % D;
+      const int64_t off = base + (int64_t)(t0 + t) * a.st + i;
+      kr[t * KSTR + i] = static_cast<const elem*>(a.k)[off];
+      vv[(HMAX + t) * D + i] = static_cast<const elem*>(a.v)[off];
     }
     __syncthreads();
     for (int t = 0; t < nt; ++t) {
@@ -224,48 +231,56 @@ __global__ __launch_bounds__(256) void prefill_grouped_simt_kernel(PrefillArgs a
       }
       __syncthreads();
       // c. logits against the group's rows up to the token (four lanes per row); the linear normaliser
-      {
-        const int i = tid / 4, sub = tid % 4;
+      for (int i0 = 0; i0 <= t; i0 += 64) {
+        const int i = i0 + tid / 4, sub = tid % 4;
         float acc = 0.f;
         if (i <= t) {
-          const float* y = kr + i * (D + 1) + sub * (D / 4);
+          const elem* y = kr + i * KSTR + sub * (D / 4);
           const float* x = qr + sub * (D / 4);
 #pragma unroll 8
-          for (int f = 0; f < D / 4; ++f) acc = fmaf(x[f], y[f], acc);
+          for (int f = 0; f < D / 4; ++f) acc = fmaf(x[f], elem_to_f32(y[f]), acc);
         }
         acc += __shfl_xor(acc, 1);
         acc += __shfl_xor(acc, 2);
-        if (sub == 0) lg[i] = acc * inv_sqrt_d;
-        if (tid >= 192) {                       // the last wave: phi(q_t).z
-          float dz = 0.f;
-          for (int f = lane; f < D; f += 64) dz = fmaf(fq[f], zz[f], dz);
+        if (sub == 0 && i < GCT) lg[i] = acc * inv_sqrt_d;
+      }
+      if (wave == 3) {                          // the last wave: phi(q_t).z
+        float dz = 0.f;
+        for (int f = lane; f < D; f += 64) dz = fmaf(fq[f], zz[f], dz);
 #pragma unroll
-          for (int off = 32; off >= 1; off >>= 1) dz += __shfl_xor(dz, off);
-          if (lane == 0) {
-            const float gden = dz + a.eps;
-            scal[0] = gden != 0.f ? a.alpha / gden : 0.f;
-          }
+        for (int off = 32; off >= 1; off >>= 1) dz += __shfl_xor(dz, off);
+        if (lane == 0) {
+          const float gden = dz + a.eps;
+          scal[0] = gden != 0.f ? a.alpha / gden : 0.f;
         }
       }
       __syncthreads();
-      // d. softmax over rows 0..t (one wave, one row per lane)
-      if (tid < 64) {
-        const float x = tid <= t ? lg[tid] : -INFINITY;
+      // d. softmax over rows 0..t, one row per thread: largest logit and mass over the workgroup
+      {
+        const bool seen = tid < GCT && tid <= t;
+        const float x = seen ? lg[tid] : -INFINITY;
         float top = x;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) top = fmaxf(top, __shfl_xor(top, off));
-        const float p = tid <= t ? __expf(x - top) : 0.f;
+        if (lane == 0) scal[4 + wave] = top;
+        __syncthreads();
+        top = fmaxf(fmaxf(scal[4], scal[5]), fmaxf(scal[6], scal[7]));   // row 0 is always seen: finite
+        const float p = seen ? __expf(x - top) : 0.f;
         float mass = p;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) mass += __shfl_xor(mass, off);
-        lg[tid] = p / mass;
+        if (lane == 0) scal[8 + wave] = mass;
+        __syncthreads();
+        mass = (scal[8] + scal[9]) + (scal[10] + scal[11]);
+        if (tid < GCT) lg[tid] = p / mass;
       }
       __syncthreads();
       // e. both branches for channel c, the features / rows dealt out over the NG thread groups
       {
         float lin = 0.f, loc = 0.f;
-        for (int i = tg; i < D; i += NG) lin = fmaf(fq[i], S[i * D + c], lin);
-        for (int s2 = tg; s2 <= t; s2 += NG) loc = fmaf(lg[s2], vv[(HMAX + s2) * D + c], loc);
+#pragma unroll
+        for (int m = 0; m < NS; ++m) lin = fmaf(fq[tg + NG * m], Sreg[m], lin);
+        for (int s2 = tg; s2 <= t; s2 += NG) loc = fmaf(lg[s2], elem_to_f32(vv[(HMAX + s2) * D + c]), loc);
         part[tg * D + c] = fmaf(scal[0], lin, loc);
       }
       __syncthreads();
@@ -276,52 +291,65 @@ __global__ __launch_bounds__(256) void prefill_grouped_simt_kernel(PrefillArgs a
         float u = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-          if (j < Kc) u = fmaf(wreg[j], vv[(HMAX + t - j) * D + tid], u);
+          if (j < Kc) u = fmaf(wreg[j], elem_to_f32(vv[(HMAX + t - j) * D + tid]), u);
         Io::store1(a.out, base + (int64_t)(t0 + t) * a.st + tid, y + u);
       }
-      // the next token's step b writes qr, fq (read in c, e: both behind barriers by then) -- no barrier needed here
-      // except for lg and part, which the next token's c and e write after their own barriers
+      // the next token's step b writes qr, fq (read in c, e: both behind barriers by then); lg, part and scal are
+      // written by the next token's c, d, e after barriers of their own
     }
     __syncthreads();
     // f. the group enters the sums: S += phi(K)^T V, z += colsum phi(K); the history slides forward by nt rows
-    for (int i = tg; i < D; i += NG) {
-      float acc = S[i * D + c];
-      for (int s2 = 0; s2 < nt; ++s2) acc = fmaf(phi_any(kr[s2 * (D + 1) + i], a.relu), vv[(HMAX + s2) * D + c], acc);
-      S[i * D + c] = acc;
+    for (int s2 = 0; s2 < nt; ++s2) {
+      const float x = elem_to_f32(vv[(HMAX + s2) * D + c]);
+#pragma unroll
+      for (int m = 0; m < NS; ++m) Sreg[m] = fmaf(phi_any(elem_to_f32(kr[s2 * KSTR + tg + NG * m]), a.relu), x, Sreg[m]);
     }
     if (tid < D) {
       float zs = zz[tid];
-      for (int s2 = 0; s2 < nt; ++s2) zs += phi_any(kr[s2 * (D + 1) + tid], a.relu);
+      for (int s2 = 0; s2 < nt; ++s2) zs += phi_any(elem_to_f32(kr[s2 * KSTR + tid]), a.relu);
       zz[tid] = zs;
       for (int r = 0; r < HMAX; ++r) vv[r * D + tid] = vv[(r + nt) * D + tid];
     }
     __syncthreads();
   }
 
-  if (a.S_out)
-    for (int e = tid; e < D * D; e += 256) a.S_out[(size_t)bh * D * D + e] = S[e];
+  if (a.S_out) {
+#pragma unroll
+    for (int m = 0; m < NS; ++m) a.S_out[(size_t)bh * D * D + (size_t)(tg + NG * m) * D + c] = Sreg[m];
+  }
   if (a.z_out && tid < D) a.z_out[(size_t)bh * D + tid] = zz[tid];
   if (a.hist_out)
     for (int e = tid; e < (Kc - 1) * D; e += 256) {
       const int r = e / D, cc = e % D;
-      Io::store1(a.hist_out, ((int64_t)bh * (Kc - 1) + r) * D + cc, vv[(HMAX - (Kc - 1) + r) * D + cc]);
+      static_cast<elem*>(a.hist_out)[((int64_t)bh * (Kc - 1) + r) * D + cc] = vv[(HMAX - (Kc - 1) + r) * D + cc];
     }
 }
 
-template <typename Io, int D>
+template <typename Io, int D, int GCT>
 static hipError_t launch_grouped_one(const PrefillArgs& a, hipStream_t st) {
-  constexpr size_t bytes = sizeof(float) * GroupedSimtLayout<D>::TOTAL;
+  constexpr int bytes = GroupedSimtLayout<Io, D, GCT>::TOTAL;
   static_assert(bytes <= 160 * 1024, "LDS");
-  auto kern = prefill_grouped_simt_kernel<Io, D>;
+  auto kern = prefill_grouped_simt_kernel<Io, D, GCT>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H)), dim3(256), bytes, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_prefill_grouped_simt(const PrefillArgs& a, int d, hipStream_t st) {
-  return d == 128 ? launch_grouped_one<IoF32, 128>(a, st) : launch_grouped_one<IoF32, 64>(a, st);
+// fp32 rows of 128 elements in groups of 256 would need 266 KB of LDS for the group's rows: no kernel.
+bool prefill_grouped_simt_available(bool bf16, int d, int group) {
+  return (group == 64 || group == 256) && (d == 64 || d == 128) && (bf16 || d == 64 || group == 64);
+}
+
+hipError_t launch_prefill_grouped_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st) {
+  if (a.group == 256) {
+    if (bf16) return d == 128 ? launch_grouped_one<IoBf16, 128, 256>(a, st) : launch_grouped_one<IoBf16, 64, 256>(a, st);
+    if (d == 64) return launch_grouped_one<IoF32, 64, 256>(a, st);
+    return hipErrorInvalidValue;
+  }
+  if (bf16) return d == 128 ? launch_grouped_one<IoBf16, 128, 64>(a, st) : launch_grouped_one<IoBf16, 64, 64>(a, st);
+  return d == 128 ? launch_grouped_one<IoF32, 128, 64>(a, st) : launch_grouped_one<IoF32, 64, 64>(a, st);
 }
 
 template <typename Io, int D>

@@ -57,6 +57,11 @@ CONFIGS = {
     # (root-to-leaf paths), the shape of the paper's single-batch comparison (Sec. 5.3, Tab. 9)
     "tree_verify_64x42": Workload("tree_verify_64x42", "verify_tree", 32, 32, 2048, 128, "bf16", 64, 3, 1.0,
                                   1006, (64, 42)),
+    # the shape of the paper's FLASH experiment (Sec. 4.1: masked DWConv of kernel size 63; Sec. 5 "Settings" and
+    # Sec. 5.3: groups of 256 tokens, batch 1, sequences of 1K / 4K / 8K tokens), as eight heads of 128
+    "flash_L1024": Workload("flash_L1024", "prefill", 1, 8, 1024, 128, "bf16", 256, 63, 128 ** -0.5, 1011),
+    "flash_L4096": Workload("flash_L4096", "prefill", 1, 8, 4096, 128, "bf16", 256, 63, 128 ** -0.5, 1012),
+    "flash_L8192": Workload("flash_L8192", "prefill", 1, 8, 8192, 128, "bf16", 256, 63, 128 ** -0.5, 1013),
     # config 5: long-context prefill
     "cfg5_long_context": Workload("cfg5_long_context", "prefill", 1, 32, 65536, 128, "bf16", 128, 5, 1.0, 1005),
 }

@@ -804,4 +804,56 @@ def pin_grouped_verify_ignores_rows_beyond_fill_and_later_drafts(lib=None):
     assert np.max(np.abs(later[0][:, :, 3] - base[0][:, :, 3])) > 1e-3
 
 
+# ---- the sizes of the paper's FLASH experiment (Sec. 4.1: masked DWConv of kernel size 63; Sec. 5 "Settings": groups of 256) --
+def pin_conv_of_63_taps_matches_library_grouped_conv(lib=None):
+    """Kernel size 63: sequences shorter and longer than the window, with and without a 62-row history; in both
+    prefill forms and in the three-branch form the conv is what is added on top of the attention output."""
+    B, H, d, Kc = 1, 2, 3, 63
+    r = _rng(901)
+    w = r.standard_normal((H, d, Kc))
+    for L in (5, 62, 63, 150):
+        v = r.standard_normal((B, H, L, d))
+        for hist in (None, r.standard_normal((B, H, Kc - 1, d))):
+            left = np.zeros((B, H, Kc - 1, d)) if hist is None else hist
+            x = np.concatenate([left, v], axis=2)
+            x = torch.from_numpy(x).permute(0, 1, 3, 2).reshape(B, H * d, L + Kc - 1)
+            wt = torch.from_numpy(w[:, :, ::-1].copy()).reshape(H * d, 1, Kc)
+            want = torch.nn.functional.conv1d(x, wt, groups=H * d).reshape(B, H, d, L).permute(0, 1, 3, 2).numpy()
+            _close(oracle.causal_conv(v, w, hist, lib=lib), want, 1e-12, f"63 taps vs conv1d, L={L}")
+            q, k = r.standard_normal(v.shape), r.standard_normal(v.shape)
+            for f in FORMS:
+                fn = getattr(oracle, f)
+                res = fn(q, k, v, w, hist0=hist, lib=lib)
+                without = fn(q, k, v, np.zeros_like(w), hist0=hist, lib=lib)
+                _close(res[0] - without[0], want, 1e-11, f"{f}: 63-tap conv added to the attention output, L={L}")
+                _close(res[3], np.concatenate([left, v], axis=2)[:, :, -(Kc - 1):], 0.0, f"{f}: history after L={L}")
+            g = oracle.prefill_grouped(q, k, v, w, 256, hist0=hist, lib=lib)
+            g0 = oracle.prefill_grouped(q, k, v, np.zeros_like(w), 256, hist0=hist, lib=lib)
+            _close(g[0] - g0[0], want, 1e-11, f"three-branch form: 63-tap conv added, L={L}")
+
+
+def pin_grouped_256_token_groups(lib=None):
+    """Groups of 256 tokens.  A sequence of at most 256 tokens is one group: library causal softmax attention plus
+    the conv.  A longer one: its first 256 outputs are that again; the tokens after the boundary see the first
+    group only through (S, z, hist), so they equal a fresh call started from the token-level state of the first
+    256 tokens; and the state handed back is the token-level running sum."""
+    q, k, v, w = _rand(902, B=1, H=2, L=300, d=4, Kc=5)
+    tq, tk, tv = (torch.from_numpy(a[:, :, :256]) for a in (q, k, v))
+    first = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True).numpy()
+    conv = oracle.causal_conv(v, w)
+    whole = oracle.prefill_grouped(q, k, v, w, 256, alpha=0.6, eps=1e-3, lib=lib)
+    _close(whole[0][:, :, :256], first + conv[:, :, :256], 1e-11, "first group of 256 vs library softmax attention")
+    st = oracle.prefill_recurrent(q[:, :, :256], k[:, :, :256], v[:, :, :256], w, lib=lib)
+    tail = oracle.prefill_grouped(q[:, :, 256:], k[:, :, 256:], v[:, :, 256:], w, 256, alpha=0.6, S0=st[1], z0=st[2],
+                                  hist0=st[3], eps=1e-3, lib=lib)
+    _close(whole[0][:, :, 256:], tail[0], 1e-11, "tokens after the boundary")
+    full = oracle.prefill_recurrent(q, k, v, w, lib=lib)
+    for i, name in ((1, "S"), (2, "z"), (3, "hist")):
+        _close(whole[i], full[i], 1e-11, name)
+    # the group size is part of the result: 64-token groups give something else from token 64 on
+    other = oracle.prefill_grouped(q, k, v, w, 64, alpha=0.6, eps=1e-3, lib=lib)[0]
+    _close(other[:, :, :64], whole[0][:, :, :64], 1e-11, "before the first 64-token boundary")
+    assert np.max(np.abs(other[:, :, 64:] - whole[0][:, :, 64:])) > 1e-3
+
+
 ALL_PINS = [obj for name, obj in sorted(globals().items()) if name.startswith("pin_") and callable(obj)]

@@ -62,7 +62,7 @@ def prefill_status(desc, L=256, **over):
 
 
 @pytest.mark.parametrize("field,value,status", [
-    ("d", 96, 2), ("d", 0, 2), ("B", 0, 2), ("H", -1, 2), ("conv_k", 0, 2), ("conv_k", 9, 2),
+    ("d", 96, 2), ("d", 0, 2), ("B", 0, 2), ("H", -1, 2), ("conv_k", 0, 2), ("conv_k", 64, 2),
     ("chunk", 32, 2), ("stride_t", (1 << 22) + 8, 2), ("io_dtype", 7, 3), ("phi", 2, 3), ("eps", -1.0, 2), ("eps", float("nan"), 2),
     ("stride_t", 64, 2), ("stride_t", 132, 2), ("stride_h", 12, 2),
 ])
@@ -118,7 +118,9 @@ def test_prefill_grouped_rejects_bad_arguments():
     assert grouped_status(d, k=None) == 1
     assert grouped_status(d, out=P + 8) == 4
     assert grouped_status(d, S_in=P) == 1
-    assert grouped_status(good_desc(chunk=128)) == 5                        # the group is part of the result: 64 only
+    assert grouped_status(good_desc(chunk=128)) == 5                        # the group is part of the result: 64 or 256
+    assert grouped_status(good_desc(chunk=256, io_dtype=binding.LINATTN_F32)) == 5   # fp32 rows of 128 in groups of 256: no kernel
+    assert grouped_status(good_desc(conv_k=64)) == 2
     assert grouped_status(good_desc(chunk=32)) == 2
     few = binding.make_desc(1, 2, 128, 3, 64, L=4096)                       # segmented: needs the workspace
     assert binding.linattn_workspace_bytes(few, 4096) > 0
@@ -148,6 +150,7 @@ def test_verify_grouped_rejects_bad_arguments():
     assert vgrouped_status(d, n_commit=P + 1) == 4
     assert vgrouped_status(good_desc(chunk=128)) == 5           # the window is one group of 64 rows
     assert vgrouped_status(good_desc(d=96)) == 2
+    assert vgrouped_status(good_desc(conv_k=9)) == 2
 
 
 def verify_status(desc, kk=4, **over):
@@ -168,6 +171,7 @@ def test_verify_rejects_bad_arguments():
     assert verify_status(d, z=P + 4) == 4
     assert verify_status(d, n_commit=P + 2) == 4
     assert verify_status(good_desc(d=32)) == 2
+    assert verify_status(good_desc(conv_k=9)) == 2              # kernels of more than 8 taps: prefill entry points only
     lib = binding.load()
     assert lib.linattn_decode(ctypes.byref(d), P, None, P, P, P, P, P, P, None) == 1
 
@@ -192,6 +196,7 @@ def test_verify_tree_rejects_bad_arguments():
     assert tree_status(d, accept=P + 1) == 4
     assert tree_status(good_desc(io_dtype=binding.LINATTN_F32)) == 5      # bf16 candidates only
     assert tree_status(good_desc(d=96)) == 2
+    assert tree_status(good_desc(conv_k=63)) == 2
 
 
 def test_binding_raises_on_refusal():
