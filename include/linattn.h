@@ -49,7 +49,9 @@
  *     every stride is a multiple of 8 elements).  The same strides apply to all
  *     four.  State tensors are dense: S [B,H,d,d] float (row = key feature i,
  *     column = value channel c, c contiguous), z [B,H,d] float,
- *     hist [B,H,Kc-1,d] in the i/o dtype, conv_w [H,d,Kc] float.
+ *     hist [B,H,Kc-1,d] in the i/o dtype, conv_w [H,d,Kc] float.  (With value
+ *     rows wider than key rows -- linattn_desc.d_v -- every "d" that counts
+ *     value channels reads d_v, and v, out take strides of their own.)
  *   - Buffers must not overlap except where an alias is explicitly allowed.
  */
 #ifndef LINATTN_H
@@ -84,6 +86,7 @@ typedef enum { LINATTN_PHI_ELU1 = 0, LINATTN_PHI_RELU = 1 } linattn_phi;
                                   FLASH experiment uses a masked DWConv of kernel size 63) */
 #define LINATTN_MAX_DRAFT 16   /* draft tokens per verify call                          */
 #define LINATTN_MAX_TREE 64    /* candidate tokens per tree-verify call                 */
+#define LINATTN_MAX_DV 2048    /* widest value row (a multiple of d)                       */
 
 typedef struct {
   int32_t B, H;            /* batch rows, heads                                        */
@@ -99,6 +102,17 @@ typedef struct {
   float eps;               /* added to every denominator; >= 0                          */
   int64_t stride_b, stride_h, stride_t; /* element strides of q, k, v, out: multiples of
                               8, stride_t >= d and <= 2^22                           */
+  /* Value rows wider than key rows (Sec. 3, Eq. 1: Q, K of width d_k, V of width d_v).  */
+  int32_t d_v;             /* 0 or d: d_v = d_k = d.  Otherwise a multiple of d, at most
+                              LINATTN_MAX_DV: v, out and hist rows have d_v elements,
+                              S is [B,H,d,d_v], conv_w [H,d_v,Kc]; q, k, z keep d.
+                              linattn_prefill, _noalloc, linattn_verify and
+                              linattn_decode only (LINATTN_ERR_UNSUPPORTED elsewhere);
+                              z_out must then not be z_in in the prefill calls.        */
+  int32_t reserved;        /* 0                                                        */
+  int64_t stride_b_v, stride_h_v, stride_t_v; /* element strides of v and out when
+                              d_v differs from d (q and k keep stride_b/h/t); all 0
+                              when d_v is 0 or d: v and out then share q's strides     */
 } linattn_desc;
 
 /* Bytes of device scratch `linattn_prefill` needs for this descriptor and L

@@ -154,14 +154,45 @@ def _prefill(fname, q, k, v, w, S0, z0, hist0, eps, lib):
     return out, S1, z1, h1
 
 
+def _value_blocks(d, v):
+    """Value rows wider than key rows (Sec. 3, Eq. 1: Q, K of width d_k, V of width d_v).  Column c of the output
+    -- of the attention part and of the depthwise conv alike -- is a function of Q, K and column c of V only, and
+    so are column c of S and of the history; z does not involve V at all.  A V of width d_v = m d_k is therefore
+    m problems of width d_k that share Q and K: the slices of the last axis of v, w, S, hist, one per problem."""
+    dv = np.shape(v)[-1]
+    if dv == d:
+        return None
+    if dv % d != 0:
+        raise ValueError(f"value width {dv} is not a multiple of the key width {d}")
+    return [slice(i, i + d) for i in range(0, dv, d)]
+
+
+def _cut(a, sl, axis=-1):
+    if a is None:
+        return None
+    idx = [slice(None)] * np.ndim(a)
+    idx[axis] = sl
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64)[tuple(idx)])
+
+
+def _prefill_any_width(fname, q, k, v, w, S0, z0, hist0, eps, lib):
+    blocks = _value_blocks(np.shape(q)[-1], v)
+    if blocks is None:
+        return _prefill(fname, q, k, v, w, S0, z0, hist0, eps, lib)
+    parts = [_prefill(fname, q, k, _cut(v, sl), _cut(w, sl, axis=1), _cut(S0, sl), z0, _cut(hist0, sl), eps, lib)
+             for sl in blocks]
+    return (np.concatenate([p[0] for p in parts], axis=-1), np.concatenate([p[1] for p in parts], axis=-1), parts[0][2],
+            np.concatenate([p[3] for p in parts], axis=-1))
+
+
 def prefill_quadratic(q, k, v, w, S0=None, z0=None, hist0=None, eps=0.0, lib=None):
-    """Brute-force masked quadratic form.  Returns (out, S, z, hist)."""
-    return _prefill("oracle_prefill_quadratic", q, k, v, w, S0, z0, hist0, eps, lib)
+    """Brute-force masked quadratic form.  Returns (out, S, z, hist).  v may be wider than q, k (see _value_blocks)."""
+    return _prefill_any_width("oracle_prefill_quadratic", q, k, v, w, S0, z0, hist0, eps, lib)
 
 
 def prefill_recurrent(q, k, v, w, S0=None, z0=None, hist0=None, eps=0.0, lib=None):
-    """Token-by-token recurrence.  Returns (out, S, z, hist)."""
-    return _prefill("oracle_prefill_recurrent", q, k, v, w, S0, z0, hist0, eps, lib)
+    """Token-by-token recurrence.  Returns (out, S, z, hist).  v may be wider than q, k (see _value_blocks)."""
+    return _prefill_any_width("oracle_prefill_recurrent", q, k, v, w, S0, z0, hist0, eps, lib)
 
 
 def prefill_grouped(q, k, v, w, group, alpha=1.0, S0=None, z0=None, hist0=None, eps=0.0, lib=None):
@@ -197,6 +228,12 @@ def verify(q, k, v, w, S, z, hist, n_commit=None, eps=0.0, lib=None):
     The incoming state arrays are not modified.
     """
     lib = lib or _load()
+    blocks = _value_blocks(np.shape(q)[-1], v)
+    if blocks is not None:                     # v wider than q, k: one problem per block of value channels
+        parts = [verify(q, k, _cut(v, sl), _cut(w, sl, axis=1), _cut(S, sl), z, _cut(hist, sl), n_commit, eps, lib)
+                 for sl in blocks]
+        return (np.concatenate([p[0] for p in parts], axis=-1), np.concatenate([p[1] for p in parts], axis=-1),
+                parts[0][2], np.concatenate([p[3] for p in parts], axis=-1))
     q = _c(q)
     B, H, kk, d = q.shape
     k = _c(k, q.shape)
@@ -293,6 +330,11 @@ def verify_tree(q, k, v, parent, w, S, z, hist, accept=None, eps=0.0, lib=None):
 def decode(q, k, v, w, S, z, hist, eps=0.0, lib=None):
     """One generated token per head: q, k, v [B,H,1,d]; the state always advances."""
     lib = lib or _load()
+    blocks = _value_blocks(np.shape(q)[-1], v)
+    if blocks is not None:                     # v wider than q, k: one problem per block of value channels
+        parts = [decode(q, k, _cut(v, sl), _cut(w, sl, axis=1), _cut(S, sl), z, _cut(hist, sl), eps, lib) for sl in blocks]
+        return (np.concatenate([p[0] for p in parts], axis=-1), np.concatenate([p[1] for p in parts], axis=-1),
+                parts[0][2], np.concatenate([p[3] for p in parts], axis=-1))
     q = _c(q)
     B, H, one, d = q.shape
     if one != 1:

@@ -35,7 +35,9 @@ class Desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("conv_k", ctypes.c_int32), ("chunk", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
                 ("phi", ctypes.c_int32), ("eps", ctypes.c_float),
-                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_t", ctypes.c_int64)]
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_t", ctypes.c_int64),
+                ("d_v", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("stride_b_v", ctypes.c_int64), ("stride_h_v", ctypes.c_int64), ("stride_t_v", ctypes.c_int64)]
 
 
 def load():
@@ -101,13 +103,21 @@ def _check(status: int, where: str):
         raise LinattnError(status, where)
 
 
-def make_desc(B, H, d, conv_k, chunk=64, io_dtype=torch.bfloat16, eps=0.0, strides=None, L=None, phi="elu1") -> Desc:
-    """Descriptor for dense [B,H,L,d] tensors unless ``strides`` (b, h, t) is given.  phi: "elu1" or "relu"."""
+def make_desc(B, H, d, conv_k, chunk=64, io_dtype=torch.bfloat16, eps=0.0, strides=None, L=None, phi="elu1",
+              d_v=None, strides_v=None) -> Desc:
+    """Descriptor for dense [B,H,L,d] tensors unless ``strides`` (b, h, t) is given.  phi: "elu1" or "relu".
+    d_v: width of the value rows when it differs from d (a multiple of d); v and out are then dense [B,H,L,d_v]
+    unless ``strides_v`` is given."""
     code = {torch.float32: LINATTN_F32, torch.bfloat16: LINATTN_BF16}[io_dtype]
+    Lx = 0 if L is None else int(L)
     if strides is None:
-        Lx = 0 if L is None else int(L)
         strides = (H * Lx * d, Lx * d, d)
-    return Desc(B, H, d, conv_k, chunk, code, PHI[phi], float(eps), *[int(s) for s in strides])
+    if d_v is None or d_v == d:
+        return Desc(B, H, d, conv_k, chunk, code, PHI[phi], float(eps), *[int(s) for s in strides], 0, 0, 0, 0, 0)
+    if strides_v is None:
+        strides_v = (H * Lx * d_v, Lx * d_v, d_v)
+    return Desc(B, H, d, conv_k, chunk, code, PHI[phi], float(eps), *[int(s) for s in strides], int(d_v), 0,
+                *[int(s) for s in strides_v])
 
 
 def linattn_set_wait_limit(spins: int) -> int:
@@ -176,26 +186,29 @@ def linattn_decode(desc: Desc, q, k, v, conv_w, S, z, hist, out, stream=None) ->
 
 # ---- conveniences that only allocate with torch and forward to the calls above ---------------
 def prefill(q, k, v, conv_w, state=None, chunk=64, eps=0.0, want_state=True, stream=None, phi="elu1", grouped_alpha=None):
-    """q, k, v: [B,H,L,d] CUDA tensors (fp32 or bf16), dense or any view with unit stride along d
-    and equal strides for the three (e.g. ``x.transpose(1, 2)`` of a token-major [B,L,H,d] tensor);
-    ``out`` gets the same strides.  Returns out, (S, z, hist).  grouped_alpha: None, or the weight of the
-    grouped branch of the three-branch form (``linattn_prefill_grouped``; bf16, groups of 64)."""
+    """q, k: [B,H,L,d], v: [B,H,L,d_v] CUDA tensors (fp32 or bf16; d_v = d or a multiple of d), dense or any view
+    with unit stride along the last axis (e.g. ``x.transpose(1, 2)`` of a token-major [B,L,H,d] tensor); q and k
+    share their strides, and so does v when d_v = d; ``out`` gets v's shape and strides.  Returns out, (S, z, hist).
+    grouped_alpha: None, or the weight of the grouped branch of the three-branch form (``linattn_prefill_grouped``)."""
     B, H, L, d = q.shape
+    d_v = v.shape[3]
     Kc = conv_w.shape[2]
-    if q.is_contiguous() and k.is_contiguous() and v.is_contiguous():
-        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, L=L, phi=phi)
-        out = torch.empty_like(q)
+    dense = q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    if not dense and (q.stride(3) != 1 or v.stride(3) != 1 or k.stride() != q.stride() or (d_v == d and v.stride() != q.stride())):
+        raise ValueError("q, k (and v, when it has their width) must share their strides and be contiguous along d")
+    sq = None if dense else q.stride()[:3]
+    sv = None if dense else v.stride()[:3]
+    if d_v == d:
+        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, strides=sq, L=L, phi=phi)
     else:
-        if q.stride(3) != 1 or k.stride() != q.stride() or v.stride() != q.stride():
-            raise ValueError("q, k, v must share their strides and be contiguous along d")
-        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, strides=q.stride()[:3], phi=phi)
-        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+        desc = make_desc(B, H, d, Kc, chunk, q.dtype, eps, strides=sq, L=L, phi=phi, d_v=d_v, strides_v=sv)
+    out = torch.empty_like(v) if dense else torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
     S_in, z_in, h_in = state if state is not None else (None, None, None)
     S = z = h = None
     if want_state:
-        S = torch.empty((B, H, d, d), dtype=torch.float32, device=q.device)
+        S = torch.empty((B, H, d, d_v), dtype=torch.float32, device=q.device)
         z = torch.empty((B, H, d), dtype=torch.float32, device=q.device)
-        h = torch.empty((B, H, max(Kc - 1, 0), d), dtype=q.dtype, device=q.device)
+        h = torch.empty((B, H, max(Kc - 1, 0), d_v), dtype=q.dtype, device=q.device)
     nbytes = linattn_workspace_bytes(desc, L)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device) if nbytes else None
     if ws is not None and stream is not None and not isinstance(stream, int):
@@ -214,10 +227,10 @@ def prefill_grouped(q, k, v, conv_w, alpha=1.0, state=None, eps=0.0, want_state=
 
 
 def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None, phi="elu1"):
-    """q, k, v: dense [B,H,kk,d].  ``state`` = (S, z, hist) is updated in place.  Returns out."""
+    """q, k: dense [B,H,kk,d]; v: dense [B,H,kk,d_v].  ``state`` = (S, z, hist) is updated in place.  Returns out."""
     B, H, kk, d = q.shape
-    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=kk, phi=phi)
-    out = torch.empty_like(q)
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=kk, phi=phi, d_v=v.shape[-1])
+    out = torch.empty_like(v)
     S, z, h = state
     linattn_verify(desc, kk, q, k, v, conv_w, S, z, h, n_commit, out, stream)
     return out
@@ -261,10 +274,10 @@ def verify_tree(q, k, v, parent, conv_w, state, accept=None, eps=0.0, stream=Non
 
 
 def decode(q, k, v, conv_w, state, eps=0.0, stream=None, phi="elu1"):
-    """q, k, v: dense [B,H,d] (or [B,H,1,d]).  ``state`` is updated in place.  Returns out."""
+    """q, k: dense [B,H,d] (or [B,H,1,d]); v: dense [B,H,d_v].  ``state`` is updated in place.  Returns out."""
     B, H, d = q.shape[0], q.shape[1], q.shape[-1]
-    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=1, phi=phi)
-    out = torch.empty_like(q)
+    desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=1, phi=phi, d_v=v.shape[-1])
+    out = torch.empty_like(v)
     S, z, h = state
     linattn_decode(desc, q, k, v, conv_w, S, z, h, out, stream)
     return out

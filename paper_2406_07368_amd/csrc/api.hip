@@ -50,6 +50,9 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 // chunk: the group size takes part in the call; strides: q, k, v, out are addressed by the descriptor's strides
 // (the verify entry points take dense tensors and ignore them).
+// Value blocks of d channels per head: d_v = m d (m = 1 when d_v is 0 or d).
+int value_blocks(const linattn_desc* d) { return d->d_v == 0 ? 1 : d->d_v / d->d; }
+
 linattn_status check_desc(const linattn_desc* d, bool chunk, bool strides, int max_conv_k = LINATTN_MAX_CONV_K) {
   if (!d) return LINATTN_ERR_NULL;
   if (d->io_dtype != LINATTN_F32 && d->io_dtype != LINATTN_BF16) return LINATTN_ERR_DTYPE;
@@ -60,10 +63,19 @@ linattn_status check_desc(const linattn_desc* d, bool chunk, bool strides, int m
   if (d->conv_k < 1 || d->conv_k > max_conv_k) return LINATTN_ERR_SHAPE;
   if (!(d->eps >= 0.f)) return LINATTN_ERR_SHAPE;
   if (chunk && d->chunk != 64 && d->chunk != 128 && d->chunk != 256) return LINATTN_ERR_SHAPE;
+  if (d->d_v < 0 || d->d_v > LINATTN_MAX_DV || d->d_v % d->d != 0 || d->reserved != 0) return LINATTN_ERR_SHAPE;
+  const bool wide = d->d_v != 0 && d->d_v != d->d;
   if (strides) {
     if (d->stride_t < d->d || d->stride_h < 0 || d->stride_b < 0) return LINATTN_ERR_SHAPE;
     if ((d->stride_t | d->stride_h | d->stride_b) & 7) return LINATTN_ERR_SHAPE;
     if (d->stride_t > (int64_t)1 << 22) return LINATTN_ERR_SHAPE;   // the kernels index inside a group with 32 bits
+    if (wide) {
+      if (d->stride_t_v < d->d_v || d->stride_h_v < 0 || d->stride_b_v < 0) return LINATTN_ERR_SHAPE;
+      if ((d->stride_t_v | d->stride_h_v | d->stride_b_v) & 7) return LINATTN_ERR_SHAPE;
+      if (d->stride_t_v > (int64_t)1 << 22) return LINATTN_ERR_SHAPE;
+    } else if (d->stride_t_v != 0 || d->stride_h_v != 0 || d->stride_b_v != 0) {
+      return LINATTN_ERR_SHAPE;                                     // v and out share q's strides when d_v = d
+    }
   }
   return LINATTN_OK;
 }
@@ -84,14 +96,15 @@ PrefillPlan plan_prefill(const linattn_desc* d, int32_t L, bool grouped = false)
   p.mfma = d->io_dtype == LINATTN_BF16 && !(grouped && d->chunk != 64);
   p.nseg = 1;
   p.seg_len = L;
+  const int heads = d->B * d->H * value_blocks(d);      // what the kernels see as heads: one per value block
   if (p.mfma && L > 0) {
-    p.nseg = prefill_mfma_pick_segments(d->B * d->H, L, d->chunk);
+    p.nseg = prefill_mfma_pick_segments(heads, L, d->chunk);
     const int chunks = (L + d->chunk - 1) / d->chunk;
     const int cps = (chunks + p.nseg - 1) / p.nseg;
     p.seg_len = cps * d->chunk;
     p.nseg = (L + p.seg_len - 1) / p.seg_len;
   }
-  p.ws_bytes = p.mfma ? prefill_mfma_workspace_bytes(d->B * d->H, d->d, p.nseg) : 0;
+  p.ws_bytes = p.mfma ? prefill_mfma_workspace_bytes(heads, d->d, p.nseg) : 0;
   return p;
 }
 
@@ -102,6 +115,12 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
   linattn_status st = check_desc(desc, true, true, LINATTN_MAX_CONV_K_PREFILL);
   if (st != LINATTN_OK) return st;
   if (L < 0) return LINATTN_ERR_SHAPE;
+  const int m = value_blocks(desc);
+  if (m > 1) {
+    if (grouped) return LINATTN_ERR_UNSUPPORTED;                      // the three-branch kernels take d_v = d only
+    // the value blocks of a head all read z_in and the first of them writes z_out
+    if (z_in != nullptr && z_out == z_in) return LINATTN_ERR_UNSUPPORTED;
+  }
   if (grouped) {
     if (!(alpha == alpha) || alpha - alpha != 0.f) return LINATTN_ERR_SHAPE;   // NaN, infinity
     // the groups are part of the result here: 64 tokens (the paper's size for LLaMA) or 256 (its size for FLASH)
@@ -117,7 +136,8 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
   for (const void* p : ptrs)
     if (!aligned16(p)) return LINATTN_ERR_ALIGN;
   // the last token of the last (b, h) must be addressable with 64-bit offsets
-  if ((double)desc->stride_b * desc->B + (double)desc->stride_h * desc->H + (double)desc->stride_t * L > 9.0e18)
+  if ((double)desc->stride_b * desc->B + (double)desc->stride_h * desc->H + (double)desc->stride_t * L > 9.0e18 ||
+      (double)desc->stride_b_v * desc->B + (double)desc->stride_h_v * desc->H + (double)desc->stride_t_v * L > 9.0e18)
     return LINATTN_ERR_SHAPE;
   const PrefillPlan plan = plan_prefill(desc, L, grouped);
   if (plan.ws_bytes > 0 && (!workspace || workspace_bytes < plan.ws_bytes)) return LINATTN_ERR_WORKSPACE;
@@ -135,6 +155,10 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
   a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = long_conv ? 1 : desc->conv_k; a.no_conv = long_conv;
   a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU; a.group = desc->chunk;
   a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
+  a.m = m;
+  a.sb_v = m > 1 ? desc->stride_b_v : desc->stride_b;
+  a.sh_v = m > 1 ? desc->stride_h_v : desc->stride_h;
+  a.st_v = m > 1 ? desc->stride_t_v : desc->stride_t;
   a.nseg = plan.nseg; a.seg_len = plan.seg_len;
   a.alpha = alpha;
   a.wait_spins = g_wait_spins.load(std::memory_order_relaxed);
@@ -147,7 +171,7 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
     ConvLongArgs c{};
     c.v = v; c.conv_w = conv_w; c.hist_in = hist_in; c.out = out; c.hist_out = hist_out;
     c.B = desc->B; c.H = desc->H; c.L = L; c.Kc = desc->conv_k;
-    c.sb = desc->stride_b; c.sh = desc->stride_h; c.st = desc->stride_t;
+    c.sb = a.sb_v; c.sh = a.sh_v; c.st = a.st_v; c.m = m;
     e = launch_conv_long(c, bf16, desc->d, stream);
   }
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
@@ -231,11 +255,14 @@ linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* 
   a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;
   a.n_commit = n_commit; a.out = out;
   a.B = desc->B; a.H = desc->H; a.kk = kk; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
-  const int nsplit = verify_pick_split(desc->B * desc->H);
+  const int m = value_blocks(desc);
+  a.dv = m * desc->d;
+  const int nsplit = verify_pick_split(desc->B * desc->H * m);
   const bool bf16 = desc->io_dtype == LINATTN_BF16;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const hipError_t e = verify_mfma_available(bf16, desc->d, nsplit, kk) ? launch_verify_mfma(a, desc->d, stream)
-                                                                        : launch_verify(a, bf16, desc->d, nsplit, stream);
+  // value rows wider than key rows: the streaming kernel, whose workgroups own column slices of a head's state
+  const hipError_t e = (m == 1 && verify_mfma_available(bf16, desc->d, nsplit, kk)) ? launch_verify_mfma(a, desc->d, stream)
+                                                                                    : launch_verify(a, bf16, desc->d, nsplit, stream);
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 
@@ -253,6 +280,7 @@ linattn_status linattn_verify_grouped(const linattn_desc* desc, int32_t kk, floa
     if (!aligned16(p)) return LINATTN_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(fill) & 3u) || (reinterpret_cast<uintptr_t>(n_commit) & 3u)) return LINATTN_ERR_ALIGN;
   if (desc->chunk != 64) return LINATTN_ERR_UNSUPPORTED;
+  if (value_blocks(desc) > 1) return LINATTN_ERR_UNSUPPORTED;
 
   VerifyGroupedArgs a{};
   a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;
@@ -279,6 +307,7 @@ linattn_status linattn_verify_tree(const linattn_desc* desc, int32_t n, const vo
     if (!aligned16(p)) return LINATTN_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(parent) & 3u) || (reinterpret_cast<uintptr_t>(accept) & 3u)) return LINATTN_ERR_ALIGN;
   if (desc->io_dtype != LINATTN_BF16) return LINATTN_ERR_UNSUPPORTED;   // the tree kernel exists for bf16 candidates only
+  if (value_blocks(desc) > 1) return LINATTN_ERR_UNSUPPORTED;
 
   VerifyTreeArgs a{};
   a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;

@@ -26,16 +26,19 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   constexpr int NG = 256 / D;                 // token groups of threads
   constexpr int TPT = CL_TOK / NG;            // tokens per thread
   const int tid = threadIdx.x;
-  const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  // one (b, h, value block of D channels); d_v = D: one block per head
+  const int bh = blockIdx.y / a.m, blk = blockIdx.y % a.m, b = bh / a.H, h = bh % a.H;
+  const int DVT = a.m * D;
   const int t0 = blockIdx.x * CL_TOK;
   const int Kc = a.Kc, L = a.L;
-  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh + (int64_t)blk * D;
+  const int64_t hist_base = (int64_t)bh * (Kc - 1) * DVT + (int64_t)blk * D;
   const int c = tid % D, tg = tid / D;
 
   // this channel's taps; beyond Kc they are zero, so the unrolled loop below needs no tap count
   float wreg[CL_MAXK];
 #pragma unroll
-  for (int j = 0; j < CL_MAXK; ++j) wreg[j] = j < Kc ? a.conv_w[((size_t)h * D + c) * Kc + j] : 0.f;
+  for (int j = 0; j < CL_MAXK; ++j) wreg[j] = j < Kc ? a.conv_w[((size_t)h * DVT + blk * D + c) * Kc + j] : 0.f;
 
   // rows t0 - 62 .. t0 + 63: the sequence, before it the incoming history, before that (and past the end) zeros
   for (int e = tid; e < (CL_HALO + CL_TOK) * (D / 8); e += 256) {
@@ -43,7 +46,7 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
     const int tok = t0 - CL_HALO + row;
     float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (tok >= 0 && tok < L) Io::load8(a.v, base + (int64_t)tok * a.st + i0, x);
-    else if (tok < 0 && a.hist_in && Kc - 1 + tok >= 0) Io::load8(a.hist_in, ((int64_t)bh * (Kc - 1) + (Kc - 1 + tok)) * D + i0, x);
+    else if (tok < 0 && a.hist_in && Kc - 1 + tok >= 0) Io::load8(a.hist_in, hist_base + (int64_t)(Kc - 1 + tok) * DVT + i0, x);
 #pragma unroll
     for (int i = 0; i < 8; ++i) xs[row * D + i0 + i] = x[i];
   }
@@ -82,17 +85,18 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
 // the extended sequence for row r, so hist_out may be hist_in.
 template <typename Io>
 __global__ void conv_long_hist_kernel(ConvLongArgs a, int D) {
-  const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
+  const int bh = blockIdx.x / a.m, blk = blockIdx.x % a.m, b = bh / a.H, h = bh % a.H;
   const int c = threadIdx.x;
   if (c >= D) return;
-  const int R = a.Kc - 1;
-  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const int R = a.Kc - 1, DVT = a.m * D;
+  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh + (int64_t)blk * D;
+  const int64_t hist_base = (int64_t)bh * R * DVT + (int64_t)blk * D;
   for (int r = 0; r < R; ++r) {
     const int e = a.L + r;                    // row of (history ++ sequence), the history being rows 0 .. R-1
     float x = 0.f;
     if (e >= R) x = Io::load1(a.v, base + (int64_t)(e - R) * a.st + c);
-    else if (a.hist_in) x = Io::load1(a.hist_in, ((int64_t)bh * R + e) * D + c);
-    Io::store1(a.hist_out, ((int64_t)bh * R + r) * D + c, x);
+    else if (a.hist_in) x = Io::load1(a.hist_in, hist_base + (int64_t)e * DVT + c);
+    Io::store1(a.hist_out, hist_base + (int64_t)r * DVT + c, x);
   }
 }
 
@@ -104,11 +108,11 @@ static hipError_t launch_cl(const ConvLongArgs& a, hipStream_t st) {
     auto kern = conv_long_kernel<Io, D>;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((a.L + CL_TOK - 1) / CL_TOK), (unsigned)(a.B * a.H)), dim3(256), LDS, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)((a.L + CL_TOK - 1) / CL_TOK), (unsigned)(a.B * a.H * a.m)), dim3(256), LDS, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (a.hist_out) {
-    hipLaunchKernelGGL((conv_long_hist_kernel<Io>), dim3((unsigned)(a.B * a.H)), dim3(D), 0, st, a, D);
+    hipLaunchKernelGGL((conv_long_hist_kernel<Io>), dim3((unsigned)(a.B * a.H * a.m)), dim3(D), 0, st, a, D);
     e = hipGetLastError();
   }
   return e;

@@ -19,6 +19,7 @@ struct VerifyArgs {
   int B, H, kk, Kc;
   float eps;
   int relu;                 // feature map: 0 = elu + 1, 1 = max(x, 0)
+  int dv;                   // width of the value rows (v, out, hist, the rows of S, conv_w): a multiple of d
 };
 
 struct VerifyTreeArgs {
@@ -78,7 +79,27 @@ struct PrefillArgs {
   int wait_spins;           // polls before a wait between the waves of a workgroup gives up; < 0: give up at once
   int no_conv;              // the taps are taken as zero: a convolution with more than 8 taps runs as a pass of its own
   int group;                // three-branch form: tokens per group (64 or 256)
+  // Value rows wider than key rows: d_v = m d.  The kernels then see B*H*m heads of d value channels each, head
+  // (b, h, block) sharing q, k, z with its siblings and owning channels block*d .. block*d + d - 1 of v, out, hist,
+  // conv_w and of the rows of S.  m = 1: nothing changes.
+  int m;
+  int64_t sb_v, sh_v, st_v; // element strides of v and out
 };
+
+// (b, h, value block) of a prefill workgroup and what follows from it
+struct HeadIndex {
+  int bhs;                  // index over B*H*m: workspace slots
+  int bh;                   // index over B*H: q, k, z
+  int b, h, blk;
+  int dvt;                  // m * d: row length of v, out, hist, S
+};
+__device__ __forceinline__ HeadIndex head_index(const PrefillArgs& a, int bhs, int d) {
+  HeadIndex x;
+  x.bhs = bhs; x.bh = bhs / a.m; x.blk = bhs % a.m;
+  x.b = x.bh / a.H; x.h = x.bh % a.H; x.dvt = a.m * d;
+  return x;
+}
+
 
 struct ConvLongArgs {
   const void* v;            // [B,H,L,d] by strides
@@ -87,7 +108,8 @@ struct ConvLongArgs {
   void* out;                // [B,H,L,d] by strides: out += conv
   void* hist_out;           // [B,H,Kc-1,d] or null; may be hist_in
   int B, H, L, Kc;
-  int64_t sb, sh, st;
+  int64_t sb, sh, st;       // strides of v and out
+  int m;                    // value blocks of d channels per head (d_v = m d)
 };
 
 // verify.hip

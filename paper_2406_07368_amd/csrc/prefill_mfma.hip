@@ -18,12 +18,14 @@ namespace linattn {
 template <int D>
 __global__ __launch_bounds__(256) void segment_scan_kernel(PrefillArgs a) {
   constexpr int SLOT = D * D + D;
-  const int bh = blockIdx.y;
+  const HeadIndex hx = head_index(a, blockIdx.y, D);      // one (b, h, value block)
+  const int bh = hx.bh;
   const int e = blockIdx.x * 256 + threadIdx.x;
-  float* ws_bh = a.ws + (size_t)bh * a.nseg * SLOT;
+  float* ws_bh = a.ws + (size_t)hx.bhs * a.nseg * SLOT;
   if (e < SLOT) {
     float run = 0.f;
-    if (a.S_in) run = e < D * D ? a.S_in[(size_t)bh * D * D + e] : a.z_in[(size_t)bh * D + (e - D * D)];
+    if (a.S_in) run = e < D * D ? a.S_in[(size_t)bh * D * hx.dvt + (size_t)(e / D) * hx.dvt + hx.blk * D + e % D]
+                                : a.z_in[(size_t)bh * D + (e - D * D)];
     ws_bh[e] = run;
     for (int g = 1; g < a.nseg; ++g) {
       run += ws_bh[(size_t)g * SLOT + e];
@@ -31,10 +33,10 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(PrefillArgs a) {
     }
   }
   if (a.hist_in && e < HALO * D) {
-    uint16_t* staged = reinterpret_cast<uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
+    uint16_t* staged = reinterpret_cast<uint16_t*>(a.ws + (size_t)a.B * a.H * a.m * a.nseg * SLOT) + (size_t)hx.bhs * HALO * D;
     const int r = e / D, cc = e % D;           // staged row r holds token r - HALO
     const int hr = (a.Kc - 1) - HALO + r;      // row of the incoming history
-    staged[e] = hr >= 0 ? static_cast<const uint16_t*>(a.hist_in)[((size_t)bh * (a.Kc - 1) + hr) * D + cc] : (uint16_t)0;
+    staged[e] = hr >= 0 ? static_cast<const uint16_t*>(a.hist_in)[((size_t)bh * (a.Kc - 1) + hr) * hx.dvt + hx.blk * D + cc] : (uint16_t)0;
   }
 }
 
@@ -63,7 +65,7 @@ size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg) {
 // boundaries, so the first pass and the prefix sum are the same for both forms).
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st) {
   (void)chunk;
-  const int BH = a.B * a.H;
+  const int BH = a.B * a.H * a.m;             // heads the kernels see: one per value block
   hipError_t e;
   if (a.nseg > 1) {
     if ((e = launch_prefill_mfma_ws(a, d, true, false, st)) != hipSuccess) return e;

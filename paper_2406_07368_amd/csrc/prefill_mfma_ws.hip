@@ -135,20 +135,26 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   auto bufO = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + G::OFF_OST + (GROUPED ? 0 : bi) * G::OST); };
 
   const int nseg_grid = STATE_ONLY ? a.nseg - 1 : a.nseg;
-  const int bh = blockIdx.x / nseg_grid, seg = blockIdx.x % nseg_grid;
-  const int b = bh / a.H, h = bh % a.H;
+  // a workgroup is one (b, h, value block) -- or one segment of it; with d_v = d there is one block per head
+  const HeadIndex hx = head_index(a, blockIdx.x / nseg_grid, D);
+  const int seg = blockIdx.x % nseg_grid;
+  const int bh = hx.bh, h = hx.h, DVT = hx.dvt;
   const int t_begin = seg * a.seg_len;
   const int t_end = (t_begin + a.seg_len) < a.L ? (t_begin + a.seg_len) : a.L;
   const int nchunks = (t_end - t_begin + C - 1) / C;
-  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const int64_t base = (int64_t)hx.b * a.sb + (int64_t)h * a.sh;
+  const int64_t base_v = (int64_t)hx.b * a.sb_v + (int64_t)h * a.sh_v + (int64_t)hx.blk * D;
   const uint16_t* gq = static_cast<const uint16_t*>(a.q) + base;
   const uint16_t* gk = static_cast<const uint16_t*>(a.k) + base;
-  const uint16_t* gv = static_cast<const uint16_t*>(a.v) + base;
-  uint16_t* gout = static_cast<uint16_t*>(a.out) + base;
+  const uint16_t* gv = static_cast<const uint16_t*>(a.v) + base_v;
+  uint16_t* gout = static_cast<uint16_t*>(a.out) + base_v;
   constexpr int SLOT = D * D + D;
-  float* ws_bh = a.ws + (size_t)bh * a.nseg * SLOT;
+  float* ws_bh = a.ws + (size_t)hx.bhs * a.nseg * SLOT;
   const uint16_t* staged_hist =
-      reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
+      reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.m * a.nseg * SLOT) + (size_t)hx.bhs * HALO * D;
+  // this block's corner of the tensors whose rows count value channels
+  const int64_t hist_base = (int64_t)bh * (a.Kc - 1) * DVT + (int64_t)hx.blk * D;   // + r * DVT + c
+  const int64_t S_base = (int64_t)bh * D * DVT + (int64_t)hx.blk * D;               // + i * DVT + c
 
   if (tid == 0) { *sync_q = 0u; *sync_s = 0u; *sync_m = 0u; *gave_up = 0u; }
   __syncthreads();                                     // the counters are used before the next barrier
@@ -163,7 +169,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
     const int r16 = (64 / LPR) * lw + lane / LPR;      // token within a 16-token pass
     const int c0 = 8 * (lane % LPR);                   // first of the 8 columns this thread carries
 
-    const uint32_t loff_b = (uint32_t)(r16 * (int)a.st + c0) * 2u;   // this thread's byte offset inside a pass
+    const uint32_t loff_b = (uint32_t)(r16 * (int)a.st + c0) * 2u;   // this thread's byte offset inside a pass: q, k
+    const uint32_t loff_v = (uint32_t)(r16 * (int)a.st_v + c0) * 2u; // ... v, out
 
     // Two register sets: group g lives in set g & 1 from the moment it is requested (two groups
     // ahead of its use) until it has been written to LDS.
@@ -189,21 +196,23 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       const int tok = t_begin + gc * C + 16 * p;       // uniform
       const int64_t off = (int64_t)tok * a.st;
       const char* bk = reinterpret_cast<const char*>(gk + off);
-      const char* bv = reinterpret_cast<const char*>(gv + off);
+      const char* bv = reinterpret_cast<const char*>(gv + (int64_t)tok * a.st_v);
       const char* bq = reinterpret_cast<const char*>(gq + off);
       // past the last group every lane of a row group re-reads row 0 of the last group: one cache line
       // per request instead of 16 fresh rows
       uint32_t lo = g < nchunks ? loff_b : (uint32_t)c0 * 2u;
+      uint32_t lv = g < nchunks ? loff_v : (uint32_t)c0 * 2u;
       if (PARTIAL) {
         const int last = t_end - 1 - tok;              // last row of the segment, relative to this pass
         const int r = (g < nchunks && r16 <= last) ? r16 : (last < 0 ? last : 0);   // a row that exists
         lo = (uint32_t)(r * (int)a.st + c0) * 2u;      // byte offset, may be negative: wraps with the base
+        lv = (uint32_t)(r * (int)a.st_v + c0) * 2u;
         if (LK) rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + (int32_t)lo));
-        if (LV) rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + (int32_t)lo));
+        if (LV) rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + (int32_t)lv));
         if (LQ) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + (int32_t)lo));
       } else {
         if (LK) rk[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bk + lo));
-        if (LV) rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + lo));
+        if (LV) rv[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bv + lv));
         if (LQ) rq[SET][p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(bq + lo));
       }
     };
@@ -271,7 +280,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       const int tok0 = t_begin + g * C;
       const int nt = (t_end - tok0) < C ? (t_end - tok0) : C;
       const uint16_t* ost = bufO(g & 1);
-      char* bo = reinterpret_cast<char*>(gout + (int64_t)tok0 * a.st);
+      char* bo = reinterpret_cast<char*>(gout + (int64_t)tok0 * a.st_v);
       // a wait of this workgroup gave up (the word was written before the barrier that precedes this store):
       // the rows become NaN.  One uniform branch per group; the path is never taken in a correct run.
       if (__builtin_amdgcn_readfirstlane(*gave_up)) {
@@ -280,7 +289,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           const int t = 16 * p + r16;
           if (!PARTIAL || t < nt)
             __builtin_nontemporal_store(u32x4{0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u, 0x7fc07fc0u},
-                                        reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st * 2u + loff_b));
+                                        reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st_v * 2u + loff_v));
         }
         return;
       }
@@ -290,7 +299,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
         const u32x2* src = reinterpret_cast<const u32x2*>(ost + t * G::OS + c0);
         const u32x2 lo = src[0], hi2 = src[1];
         if (!PARTIAL || t < nt)
-          __builtin_nontemporal_store(u32x4{lo[0], lo[1], hi2[0], hi2[1]}, reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st * 2u + loff_b));
+          __builtin_nontemporal_store(u32x4{lo[0], lo[1], hi2[0], hi2[1]}, reinterpret_cast<u32x4*>(bo + (uint32_t)(16 * p) * (uint32_t)a.st_v * 2u + loff_v));
       }
     };
     // Group g (held in set g & 1) -> buffer g & 1; as each pass leaves the registers, the same pass
@@ -530,19 +539,19 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       for (int mth = 0; mth < TAP_IT; ++mth) {
         const int e = lt + G::NLT * mth;
         const int j = e / D, cc = e % D;
-        tap_reg[mth] = a.conv_w[((size_t)h * D + cc) * a.Kc + (j < a.Kc ? j : 0)];
+        tap_reg[mth] = a.conv_w[((size_t)h * DVT + hx.blk * D + cc) * a.Kc + (j < a.Kc ? j : 0)];
       }
 #pragma unroll
       for (int mth = 0; mth < HALO_IT; ++mth) {
         const int e = lt + G::NLT * mth;
         const int r = e / D, cc = e % D;
         const int tok = t_begin - HALO + r;
-        const uint16_t* src = gv + (int64_t)t_begin * a.st + cc;   // exists: the segment is not empty
+        const uint16_t* src = gv + (int64_t)t_begin * a.st_v + cc;   // exists: the segment is not empty
         bool ok = false;
-        if (tok >= 0) { src = gv + (int64_t)tok * a.st + cc; ok = true; }
+        if (tok >= 0) { src = gv + (int64_t)tok * a.st_v + cc; ok = true; }
         else if (a.hist_in && a.nseg > 1) { src = staged_hist + (size_t)(HALO + tok) * D + cc; ok = true; }
         else if (a.hist_in && a.Kc - 1 + tok >= 0) {
-          src = static_cast<const uint16_t*>(a.hist_in) + ((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + cc;
+          src = static_cast<const uint16_t*>(a.hist_in) + hist_base + (int64_t)(a.Kc - 1 + tok) * DVT + cc;
           ok = true;
         }
         halo_reg[mth] = *src;
@@ -651,15 +660,16 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   {
     const float* Ssrc = nullptr;
     const float* zsrc = nullptr;
+    int srow = D;                                      // row length of the source: a workspace slot, or the caller's S
     if (STATE_ONLY) {}
     else if (a.nseg > 1) { Ssrc = ws_bh + (size_t)seg * SLOT; zsrc = Ssrc + D * D; }
-    else if (a.S_in) { Ssrc = a.S_in + (size_t)bh * D * D; zsrc = a.z_in + (size_t)bh * D; }
+    else if (a.S_in) { Ssrc = a.S_in + S_base; zsrc = a.z_in + (size_t)bh * D; srow = DVT; }
 #pragma unroll
     for (int ib = 0; ib < G::IB; ++ib)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int i = 32 * ib + 8 * (r >> 2) + 4 * hi + (r & 3);
-        Sacc[ib][r] = Ssrc ? Ssrc[(size_t)i * D + cw] : 0.f;
+        Sacc[ib][r] = Ssrc ? Ssrc[(size_t)i * srow + cw] : 0.f;
       }
 #pragma unroll
     for (int r = 0; r < 16; ++r) Zacc[r] = zsrc ? zsrc[32 * w + 8 * (r >> 2) + 4 * hi + (r & 3)] : 0.f;
@@ -861,16 +871,16 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       for (int r = 0; r < 16; ++r) Zacc[r] = __builtin_nanf("");
     }
     if (a.S_out) {
-      float* Sdst = a.S_out + (size_t)bh * D * D;
+      float* Sdst = a.S_out + S_base;
 #pragma unroll
       for (int ib = 0; ib < G::IB; ++ib)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int i = 32 * ib + 8 * (r >> 2) + 4 * hi + (r & 3);
-          Sdst[(size_t)i * D + cw] = Sacc[ib][r];
+          Sdst[(size_t)i * DVT + cw] = Sacc[ib][r];
         }
     }
-    if (a.z_out && l32 == 0) {
+    if (a.z_out && l32 == 0 && hx.blk == 0) {           // z is the same in every value block: the first one hands it back
 #pragma unroll
       for (int r = 0; r < 16; ++r) a.z_out[(size_t)bh * D + 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3)] = Zacc[r];
     }
@@ -878,14 +888,14 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       // last Kc-1 value rows of (history ++ sequence); one thread per channel, rows in ascending order,
       // so an aliased hist_in is read before it is overwritten (with segments the staged copy is read)
       const uint16_t* hin = static_cast<const uint16_t*>(a.hist_in);
-      uint16_t* hout = static_cast<uint16_t*>(a.hist_out) + (size_t)bh * (a.Kc - 1) * D;
+      uint16_t* hout = static_cast<uint16_t*>(a.hist_out) + hist_base;
       for (int r = 0; r < a.Kc - 1; ++r) {
         const int tok = a.L - (a.Kc - 1) + r;
         uint16_t x = 0;
-        if (tok >= 0) x = gv[(int64_t)tok * a.st + tid];
+        if (tok >= 0) x = gv[(int64_t)tok * a.st_v + tid];
         else if (hin) x = a.nseg > 1 ? staged_hist[(size_t)(HALO + tok) * D + tid]
-                                     : hin[((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + tid];
-        hout[(size_t)r * D + tid] = x;
+                                     : hin[hist_base + (int64_t)(a.Kc - 1 + tok) * DVT + tid];
+        hout[(size_t)r * DVT + tid] = x;
       }
     }
   }
@@ -899,7 +909,7 @@ static hipError_t launch_ws(const PrefillArgs& a, hipStream_t st) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
   if (e != hipSuccess) return e;
   const int segs = STATE_ONLY ? a.nseg - 1 : a.nseg;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * segs)), dim3(G::NT), G::TOTAL, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * a.m * segs)), dim3(G::NT), G::TOTAL, st, a);
   return hipGetLastError();
 }
 

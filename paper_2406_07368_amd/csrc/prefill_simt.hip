@@ -39,21 +39,25 @@ __global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
   float* zz = sm + Lay::ZZ;
 
   const int tid = threadIdx.x;
-  const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
+  const HeadIndex hx = head_index(a, blockIdx.x, D);      // one (b, h, value block)
+  const int bh = hx.bh, h = hx.h, DVT = hx.dvt;
   const int Kc = a.Kc, L = a.L;
-  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const int64_t base = (int64_t)hx.b * a.sb + (int64_t)h * a.sh;
+  const int64_t base_v = (int64_t)hx.b * a.sb_v + (int64_t)h * a.sh_v + (int64_t)hx.blk * D;
+  const int64_t hist_base = (int64_t)bh * (Kc - 1) * DVT + (int64_t)hx.blk * D;
+  const int64_t S_base = (int64_t)bh * D * DVT + (int64_t)hx.blk * D;
   const int c = tid % D, tg = tid / D;
 
   float wreg[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) wreg[j] = (j < Kc && !a.no_conv) ? a.conv_w[((size_t)h * D + c) * Kc + j] : 0.f;
+  for (int j = 0; j < 8; ++j) wreg[j] = (j < Kc && !a.no_conv) ? a.conv_w[((size_t)h * DVT + hx.blk * D + c) * Kc + j] : 0.f;
 
-  for (int e = tid; e < D * D; e += 256) S[e] = a.S_in ? a.S_in[(size_t)bh * D * D + e] : 0.f;
+  for (int e = tid; e < D * D; e += 256) S[e] = a.S_in ? a.S_in[S_base + (int64_t)(e / D) * DVT + e % D] : 0.f;
   if (tid < D) zz[tid] = a.z_in ? a.z_in[(size_t)bh * D + tid] : 0.f;
   for (int e = tid; e < HMAX * D; e += 256) {
     const int row = e / D, cc = e % D;
     const int r = row - (HMAX - (Kc - 1));   // row of the incoming history, oldest first
-    vv[e] = (r >= 0 && a.hist_in) ? Io::load1(a.hist_in, ((int64_t)bh * (Kc - 1) + r) * D + cc) : 0.f;
+    vv[e] = (r >= 0 && a.hist_in) ? Io::load1(a.hist_in, hist_base + (int64_t)r * DVT + cc) : 0.f;
   }
   __syncthreads();
 
@@ -67,7 +71,7 @@ __global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
         const int64_t off = base + (int64_t)(t0 + t) * a.st + i0;
         Io::load8(a.q, off, xq);
         Io::load8(a.k, off, xk);
-        Io::load8(a.v, off, xv);
+        Io::load8(a.v, base_v + (int64_t)(t0 + t) * a.st_v + i0, xv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) { xq[e] = phi_any(xq[e], a.relu); xk[e] = phi_any(xk[e], a.relu); }
       } else {
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         if (j < Kc) u = fmaf(wreg[j], vv[(HMAX + t - j) * D + c], u);
-      Io::store1(a.out, base + (int64_t)(t0 + t) * a.st + c, num / den[t] + u);
+      Io::store1(a.out, base_v + (int64_t)(t0 + t) * a.st_v + c, num / den[t] + u);
     }
     __syncthreads();
     // d. carry: S += phi(K)^T V, z += colsum phi(K); history slides forward by nt rows
@@ -134,12 +138,12 @@ __global__ __launch_bounds__(256) void prefill_simt_kernel(PrefillArgs a) {
   }
 
   if (a.S_out)
-    for (int e = tid; e < D * D; e += 256) a.S_out[(size_t)bh * D * D + e] = S[e];
-  if (a.z_out && tid < D) a.z_out[(size_t)bh * D + tid] = zz[tid];
+    for (int e = tid; e < D * D; e += 256) a.S_out[S_base + (int64_t)(e / D) * DVT + e % D] = S[e];
+  if (a.z_out && tid < D && hx.blk == 0) a.z_out[(size_t)bh * D + tid] = zz[tid];   // the same in every value block
   if (a.hist_out)
     for (int e = tid; e < (Kc - 1) * D; e += 256) {
       const int r = e / D, cc = e % D;
-      Io::store1(a.hist_out, ((int64_t)bh * (Kc - 1) + r) * D + cc, vv[(HMAX - (Kc - 1) + r) * D + cc]);
+      Io::store1(a.hist_out, hist_base + (int64_t)r * DVT + cc, vv[(HMAX - (Kc - 1) + r) * D + cc]);
     }
 }
 
@@ -359,7 +363,7 @@ static hipError_t launch_one(const PrefillArgs& a, hipStream_t st) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H)), dim3(256), bytes, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * a.m)), dim3(256), bytes, st, a);
   return hipGetLastError();
 }
 

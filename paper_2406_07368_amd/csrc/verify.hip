@@ -48,7 +48,6 @@ __device__ __forceinline__ void load_row(const float* row, float (&f)[KP]) {
 // the bandwidth).
 template <typename Io, int D, int CW, int KP>
 __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyArgs a) {
-  constexpr int NSPLIT = D / CW;
   constexpr int CG = CW / 4;          // float4 column groups per row slice
   constexpr int RPP = 256 / CG;       // rows covered per pass
   constexpr int NPASS = D / RPP;
@@ -56,16 +55,20 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
   __shared__ VerifySmem<D, CW, KP> sm;
 
   const int tid = threadIdx.x;
-  const int bh = blockIdx.x / NSPLIT;
-  const int c0 = (blockIdx.x % NSPLIT) * CW;
+  // value rows of DV = a.dv elements (a multiple of D; DV == D: d_v = d_k): DV / CW column slices per head, and
+  // DV is the row length of v, out, hist, conv_w and S
+  const int DV = a.dv, nslice = DV / CW;
+  const int bh = blockIdx.x / nslice;
+  const int c0 = (blockIdx.x % nslice) * CW;
   const int b = bh / a.H, h = bh % a.H;
   const int kk = a.kk, Kc = a.Kc;
   const int cg = tid % CG, r0 = tid / CG;
 
   // ---- 0. the small inputs are requested FIRST: every workgroup of the launch is about to ask for
   //         its state at the same moment, and anything requested after that waits behind it ------
-  const int64_t tok0 = (int64_t)bh * kk * D;
-  const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
+  const int64_t tok0 = (int64_t)bh * kk * D;              // q, k
+  const int64_t vtok0 = (int64_t)bh * kk * DV;            // v, out
+  const int64_t hist0 = (int64_t)bh * (Kc - 1) * DV;
   constexpr int QK_IT = (KP * (D / 8) + 255) / 256;   // 8-element pieces of q and k per thread
   constexpr int V_IT = (KP * (CW / 8) + 255) / 256;
   float xq[QK_IT][8], xk[QK_IT][8], xv[V_IT][8];
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
   for (int m = 0; m < V_IT; ++m) {
     const int c8 = tid + 256 * m;
     const int j = c8 / (CW / 8), cc = (c8 % (CW / 8)) * 8;
-    if (c8 < KP * (CW / 8) && j < kk) Io::load8(a.v, tok0 + (int64_t)j * D + c0 + cc, xv[m]);
+    if (c8 < KP * (CW / 8) && j < kk) Io::load8(a.v, vtok0 + (int64_t)j * DV + c0 + cc, xv[m]);
     else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) xv[m][e] = 0.f;
@@ -98,8 +101,8 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
     const int e = tid + 256 * m;          // rows 0..7: taps, rows 8..15: history
     const int t = (e / CW) & 7, cc = e % CW;
     float x = 0.f;
-    if (e < 8 * CW) { if (t < Kc) x = a.conv_w[((size_t)h * D + c0 + cc) * Kc + t]; }
-    else if (e < 16 * CW) { if (t < Kc - 1) x = Io::load1(a.hist, hist0 + (int64_t)(Kc - 2 - t) * D + c0 + cc); }
+    if (e < 8 * CW) { if (t < Kc) x = a.conv_w[((size_t)h * DV + c0 + cc) * Kc + t]; }
+    else if (e < 16 * CW) { if (t < Kc - 1) x = Io::load1(a.hist, hist0 + (int64_t)(Kc - 2 - t) * DV + c0 + cc); }
     wh[m] = x;
   }
   int n = kk;
@@ -109,10 +112,10 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
   //         in flight before anything else, each later one is issued when its slot frees up ----
   constexpr int PDW = KP >= 8 ? 2 : 4;        // fewer passes in flight when the read-outs need the registers
   constexpr int PD = NPASS < PDW ? NPASS : PDW;
-  float* Sg = a.S + (size_t)bh * D * D + c0 + 4 * cg;
+  float* Sg = a.S + (size_t)bh * D * DV + c0 + 4 * cg;
   f32x4 s[PD];
 #pragma unroll
-  for (int p = 0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D));
+  for (int p = 0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * DV));
 
   // ---- 1. drafts -> LDS (phi applied), normaliser, taps and history -> LDS -----------------------
 #pragma unroll
@@ -204,9 +207,9 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
         for (int j = 0; j < KP; ++j)
 #pragma unroll
           for (int e = 0; e < 4; ++e) cur[e] = fmaf(g[j], vr[j][e], cur[e]);
-        __builtin_nontemporal_store(cur, reinterpret_cast<f32x4*>(Sg + (size_t)i * D));
+        __builtin_nontemporal_store(cur, reinterpret_cast<f32x4*>(Sg + (size_t)i * DV));
       }
-      if (p + PD < NPASS) s[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)((p + PD) * RPP + r0) * D));
+      if (p + PD < NPASS) s[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)((p + PD) * RPP + r0) * DV));
     }
   }
   // threads that share a column group sit CG lanes apart inside a wave
@@ -241,12 +244,12 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
       const float x = t <= j ? sm.vv[j - t][c] : sm.hh[t - j - 1][c];
       u = fmaf(sm.wt[t][c], x, u);
     }
-    Io::store1(a.out, tok0 + (int64_t)j * D + c0 + c, num / sm.den[j] + u);
+    Io::store1(a.out, vtok0 + (int64_t)j * DV + c0 + c, num / sm.den[j] + u);
   }
 
   // ---- 5. the rest of the state: normaliser and history ----------------------------------
   if (n == 0) return;   // uniform per workgroup: nothing accepted, state untouched
-  if (NSPLIT == 1 && tid < D) {   // with several slices per head a separate launch updates z
+  if (nslice == 1 && tid < D) {   // with several slices per head a separate launch updates z
     float zs = sm.zz[tid];
     for (int j = 0; j < n; ++j) zs += sm.fk[tid][j];
     a.z[(size_t)bh * D + tid] = zs;
@@ -256,7 +259,7 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
     for (int c = tid; c < CW; c += 256) {
       for (int r = 0; r < Kc - 1; ++r) {
         const int sidx = n - (Kc - 1) + r;   // position in (history ++ accepted drafts)
-        const int64_t dst = hist0 + (int64_t)r * D + c0 + c;
+        const int64_t dst = hist0 + (int64_t)r * DV + c0 + c;
         if (sidx >= 0) Io::store1(a.hist, dst, sm.vv[sidx][c]);
         else Io::store1(a.hist, dst, sm.hh[-sidx - 1][c]);   // an old history row, -sidx positions back
       }
@@ -282,14 +285,14 @@ __global__ __launch_bounds__(256) void verify_z_kernel(VerifyArgs a) {
 
 template <typename Io, int D, int CW>
 static hipError_t launch_kp(const VerifyArgs& a, hipStream_t st) {
-  const dim3 grid((unsigned)(a.B * a.H * (D / CW))), block(256);
+  const dim3 grid((unsigned)(a.B * a.H * (a.dv / CW))), block(256);
   if (a.kk <= 1) hipLaunchKernelGGL((verify_kernel<Io, D, CW, 1>), grid, block, 0, st, a);
   else if (a.kk <= 4) hipLaunchKernelGGL((verify_kernel<Io, D, CW, 4>), grid, block, 0, st, a);
   else if (a.kk <= 8) hipLaunchKernelGGL((verify_kernel<Io, D, CW, 8>), grid, block, 0, st, a);
   else hipLaunchKernelGGL((verify_kernel<Io, D, CW, 16>), grid, block, 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (D / CW > 1) {
+  if (a.dv / CW > 1) {
     const int total = a.B * a.H * D;
     hipLaunchKernelGGL((verify_z_kernel<Io, D>), dim3((total + 255) / 256), block, 0, st, a);
     e = hipGetLastError();

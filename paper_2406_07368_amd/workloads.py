@@ -37,6 +37,7 @@ class Workload:
     scale: float
     seed: int
     draft_k: tuple = ()
+    d_v: int = 0       # width of the value rows when it differs from d (a multiple of d); 0: d
 
     def small(self, **kw) -> "Workload":
         return replace(self, **kw)
@@ -62,6 +63,10 @@ CONFIGS = {
     "flash_L1024": Workload("flash_L1024", "prefill", 1, 8, 1024, 128, "bf16", 256, 63, 128 ** -0.5, 1011),
     "flash_L4096": Workload("flash_L4096", "prefill", 1, 8, 4096, 128, "bf16", 256, 63, 128 ** -0.5, 1012),
     "flash_L8192": Workload("flash_L8192", "prefill", 1, 8, 8192, 128, "bf16", 256, 63, 128 ** -0.5, 1013),
+    # value rows wider than key rows (Sec. 3, Eq. 1: d_k and d_v are separate): the LLaMA-2-7B layer shape with the
+    # query/key width halved, prefill and verify
+    "wide_values_prefill": Workload("wide_values_prefill", "prefill", 8, 32, 4096, 64, "bf16", 64, 3, 64 ** -0.5, 1021, (), 128),
+    "wide_values_verify": Workload("wide_values_verify", "verify", 32, 32, 2048, 64, "bf16", 64, 3, 1.0, 1022, (1, 4, 8), 128),
     # config 5: long-context prefill
     "cfg5_long_context": Workload("cfg5_long_context", "prefill", 1, 32, 65536, 128, "bf16", 128, 5, 1.0, 1005),
 }
@@ -98,8 +103,8 @@ def draft_block(wl: Workload, kk: int, step: int = 0, seed: int | None = None):
     """q, k, v [B,H,kk,d] for one verify/decode step (seed + 100*(step+1))."""
     base = wl.seed if seed is None else seed
     rng = np.random.default_rng(base + 100 * (step + 1))
-    shape = (wl.B, wl.H, kk, wl.d)
-    return tuple(round_to_io(rng.standard_normal(shape) * wl.scale, wl.io_dtype) for _ in range(3))
+    return tuple(round_to_io(rng.standard_normal((wl.B, wl.H, kk, width)) * wl.scale, wl.io_dtype)
+                 for width in (wl.d, wl.d, wl.d_v or wl.d))
 
 
 def candidate_tree(n: int, leaves: int, seed: int) -> np.ndarray:
@@ -154,8 +159,8 @@ def prefill_tensors(wl: Workload, seed: int | None = None):
     """
     s = wl.seed if seed is None else seed
     g = torch.Generator(device="cpu").manual_seed(s)
-    shape = (wl.B, wl.H, wl.L, wl.d)
     dt = torch_dtype(wl.io_dtype)
-    q, k, v = ((torch.randn(shape, generator=g, dtype=torch.float32) * wl.scale).to(dt) for _ in range(3))
-    w = torch.from_numpy(conv_weights(np.random.default_rng(s), wl.H, wl.d, wl.conv_k))
+    q, k, v = ((torch.randn((wl.B, wl.H, wl.L, width), generator=g, dtype=torch.float32) * wl.scale).to(dt)
+               for width in (wl.d, wl.d, wl.d_v or wl.d))
+    w = torch.from_numpy(conv_weights(np.random.default_rng(s), wl.H, wl.d_v or wl.d, wl.conv_k))
     return q, k, v, w

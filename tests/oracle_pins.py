@@ -856,4 +856,86 @@ def pin_grouped_256_token_groups(lib=None):
     assert np.max(np.abs(other[:, :, 64:] - whole[0][:, :, 64:])) > 1e-3
 
 
+# ---- value rows wider than key rows (Sec. 3, Eq. 1: Q, K in R^{n x d_k}, V in R^{n x d_v}) ----------------------------
+def _wide_case(seed, B=2, H=2, L=9, d=3, m=2, Kc=3):
+    r = _rng(seed)
+    q, k = r.standard_normal((B, H, L, d)), r.standard_normal((B, H, L, d))
+    v = r.standard_normal((B, H, L, m * d))
+    w = r.standard_normal((H, m * d, Kc))
+    S0 = r.standard_normal((B, H, d, m * d))
+    z0 = np.abs(r.standard_normal((B, H, d))) + 1.0
+    h0 = r.standard_normal((B, H, Kc - 1, m * d))
+    return q, k, v, w, S0, z0, h0
+
+
+def pin_wide_values_exact_rational_brute_force(lib=None):
+    """d_k = 2, d_v = 4, one head, four tokens, an incoming state and history: every output, S, z and the history
+    from the definition in exact rational arithmetic (inputs are small integers or logs of 1/2 and 1/4, whose
+    feature-map values are rationals), in both prefill forms and token by token."""
+    ln2, ln4 = math.log(0.5), math.log(0.25)
+    q = np.array([[0.0, 1.0], [ln2, 2.0], [1.0, ln4], [0.0, 0.0]])
+    k = np.array([[1.0, 0.0], [ln4, 1.0], [0.0, ln2], [2.0, 1.0]])
+    v = np.array([[1.0, -2.0, 3.0, 0.0], [0.0, 1.0, -1.0, 2.0], [2.0, 2.0, 0.0, -3.0], [-1.0, 0.0, 1.0, 1.0]])
+    w = np.array([[1.0, -1.0], [2.0, 0.5], [0.0, 3.0], [-2.0, 1.0]])          # [d_v][Kc = 2]
+    S0 = np.array([[1.0, 0.0, -1.0, 2.0], [0.5, 1.0, 0.0, -0.5]])               # [d_k][d_v]
+    z0 = np.array([2.0, 1.0])
+    h0 = np.array([[3.0, -1.0, 0.5, 2.0]])                                       # [Kc - 1][d_v]
+    F = Fraction
+    phi = lambda x: F(x) + 1 if x > 0 else _phi_frac(x) if x < 0 else F(1)
+    fq = [[phi(x) for x in row] for row in q]
+    fk = [[phi(x) for x in row] for row in k]
+    S = [[F(x) for x in row] for row in S0]
+    z = [F(x) for x in z0]
+    want = []
+    for t in range(4):
+        for i in range(2):
+            z[i] += fk[t][i]
+            for c in range(4):
+                S[i][c] += fk[t][i] * F(v[t][c])
+        den = sum(fq[t][i] * z[i] for i in range(2))
+        row = []
+        for c in range(4):
+            prev = F(v[t - 1][c]) if t > 0 else F(h0[0][c])
+            row.append(sum(fq[t][i] * S[i][c] for i in range(2)) / den + F(w[c][0]) * F(v[t][c]) + F(w[c][1]) * prev)
+        want.append(row)
+    want = np.array([[float(x) for x in row] for row in want])
+    args = (q[None, None], k[None, None], v[None, None], w[None], S0[None, None], z0[None, None], h0[None, None])
+    for f in FORMS:
+        got = getattr(oracle, f)(*args, lib=lib)
+        _close(got[0][0, 0], want, 1e-13, f + " wide values: outputs")
+        _close(got[1][0, 0], np.array([[float(x) for x in row] for row in S]), 1e-13, f + " wide values: S")
+        _close(got[2][0, 0], np.array([float(x) for x in z]), 1e-13, f + " wide values: z")
+        _close(got[3][0, 0], v[3:4], 0.0, f + " wide values: history")
+    got = oracle.verify(*args, lib=lib)
+    _close(got[0][0, 0], want, 1e-13, "verify, wide values: outputs")
+
+
+def pin_wide_values_zero_keys_give_running_mean(lib=None):
+    """K == 0 makes every weight equal: the attention part is the running mean of the d_v-wide value rows."""
+    q, k, v, w, _, _, _ = _wide_case(911, L=12, d=3, m=3)
+    k = np.zeros_like(k)
+    want = np.cumsum(v, axis=2) / np.arange(1, v.shape[2] + 1)[None, None, :, None]
+    for f in FORMS:
+        _close(getattr(oracle, f)(q, k, v, np.zeros_like(w), lib=lib)[0], want, 1e-12, f + " running mean, wide values")
+
+
+def pin_wide_values_verify_is_sequential_decode_and_prefill(lib=None):
+    """With d_v = 2 d_k as with d_v = d_k: k drafts at once = k decode steps = the same tokens through the prefill;
+    commit counts move the state over the kept drafts only."""
+    q, k, v, w, S0, z0, h0 = _wide_case(912, L=5, d=4, m=2, Kc=4)
+    ver = oracle.verify(q, k, v, w, S0, z0, h0, lib=lib)
+    pre = oracle.prefill_recurrent(q, k, v, w, S0, z0, h0, lib=lib)
+    for x, y, n in zip(ver, pre, ("out", "S", "z", "hist")):
+        _close(x, y, 1e-12, "verify vs prefill, wide values: " + n)
+    S, z, h = S0, z0, h0
+    for j in range(5):
+        o, S, z, h = oracle.decode(q[:, :, j:j + 1], k[:, :, j:j + 1], v[:, :, j:j + 1], w, S, z, h, lib=lib)
+        _close(o, ver[0][:, :, j:j + 1], 1e-12, f"decode step {j}, wide values")
+    part = oracle.verify(q, k, v, w, S0, z0, h0, np.array([2, 0], dtype=np.int32), lib=lib)
+    two = oracle.prefill_recurrent(q[:1, :, :2], k[:1, :, :2], v[:1, :, :2], w, S0[:1], z0[:1], h0[:1], lib=lib)
+    _close(part[1][:1], two[1], 1e-12, "two kept drafts: S")
+    _close(part[3][:1], two[3], 0.0, "two kept drafts: history")
+    _close(part[1][1:], S0[1:], 0.0, "nothing kept: S untouched")
+
+
 ALL_PINS = [obj for name, obj in sorted(globals().items()) if name.startswith("pin_") and callable(obj)]
