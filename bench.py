@@ -283,91 +283,6 @@ def main():
         other_layout_ms = {"layout": other, "mean": sum(a.elapsed_time(b) for a, b in ev2) / len(ev2),
                            "min": min(a.elapsed_time(b) for a, b in ev2)}
 
-    side = None
-    if args.only == "all" and not args.length:
-        # the other prefill workloads (not part of the step): configs 1, 2 and 5, head-major as the parity tests
-        # run them, two input sets each (config 2's 25 MB would otherwise be served from the last-level cache)
-        side = {}
-        for name in ("cfg1_fp32_tiny", "cfg2_gpt2_small", "cfg5_long_context"):
-            wl = workloads.CONFIGS[name]
-            sdt = workloads.torch_dtype(wl.io_dtype)
-            gs = torch.Generator(device=dev).manual_seed(wl.seed)
-            sets = []
-            for _ in range(2 if name != "cfg2_gpt2_small" else 16):
-                q, k, v = ((torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev) * wl.scale).to(sdt) for _ in range(3))
-                sets.append((q, k, v, torch.empty_like(q)))
-            swts = torch.from_numpy(workloads.conv_weights(np.random.default_rng(wl.seed), wl.H, wl.d, wl.conv_k)).to(dev)
-            sdesc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, sdt, L=wl.L)
-            sws_bytes = binding.linattn_workspace_bytes(sdesc, wl.L)
-            sws = torch.empty(max(sws_bytes, 16), dtype=torch.uint8, device=dev)
-            sS = torch.empty((wl.B, wl.H, wl.d, wl.d), device=dev)
-            sz = torch.empty((wl.B, wl.H, wl.d), device=dev)
-            sh = torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d), device=dev, dtype=sdt)
-            evs = []
-            n_warm, n_timed = 20, min(max(args.steps, 20), 50)
-            for i in range(n_warm + n_timed):
-                q, k, v, out = sets[i % len(sets)]
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                binding.linattn_prefill(sdesc, wl.L, q, k, v, swts, None, None, None, out, sS, sz, sh, sws, sws_bytes, stream)
-                e1.record(stream)
-                if i >= n_warm:
-                    evs.append((e0, e1))
-            stream.synchronize()
-            t_ms = [a.elapsed_time(b) for a, b in evs]
-            t_mean = sum(t_ms) / len(t_ms)
-            esz = 4 if wl.io_dtype == "f32" else 2
-            nb = 4 * wl.B * wl.H * wl.L * wl.d * esz
-            side[name] = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d{wl.d} {wl.io_dtype} chunk{wl.chunk} Kc{wl.conv_k}, head-major",
-                          "ms": {"mean": t_mean, "median": float(np.median(t_ms)), "min": min(t_ms)},
-                          "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3), "workspace_bytes": sws_bytes,
-                          "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                       "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
-            del sets, sws, sS, sz, sh
-        torch.cuda.empty_cache()
-
-    flash = None
-    if args.only == "all" and not args.length:
-        # next row of the scope (not part of the step): the sizes of the paper's FLASH experiment -- 63-tap masked
-        # DWConv, groups of 256 tokens, batch 1, 1K / 4K / 8K tokens, as eight heads of 128.  Token-level form
-        # (matrix-core attention kernel + the long-convolution pass) and the three-branch form in groups of 256
-        # (the plain fp32 kernel: one workgroup per head, token by token -- correct, not fast).
-        flash = {}
-        for name in ("flash_L1024", "flash_L4096", "flash_L8192"):
-            wl = workloads.CONFIGS[name]
-            gs = torch.Generator(device=dev).manual_seed(wl.seed)
-            q, k, v = ((torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev) * wl.scale).to(torch.bfloat16) for _ in range(3))
-            out = torch.empty_like(q)
-            fw = torch.from_numpy(workloads.conv_weights(np.random.default_rng(wl.seed), wl.H, wl.d, wl.conv_k)).to(dev)
-            fdesc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, torch.bfloat16, L=wl.L)
-            fws_bytes = binding.linattn_workspace_bytes(fdesc, wl.L)
-            fws = torch.empty(max(fws_bytes, 16), dtype=torch.uint8, device=dev)
-            fS = torch.empty((wl.B, wl.H, wl.d, wl.d), device=dev)
-            fz = torch.empty((wl.B, wl.H, wl.d), device=dev)
-            fh = torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d), device=dev, dtype=torch.bfloat16)
-            nb = 4 * wl.B * wl.H * wl.L * wl.d * 2
-            row = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d{wl.d} bf16, groups of {wl.chunk}, Kc{wl.conv_k}, head-major"}
-            for key, n_warm, n_timed, call in (
-                    ("token_level", 10, 30, lambda: binding.linattn_prefill(fdesc, wl.L, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream)),
-                    ("three_branch", 1, 3, lambda: binding.linattn_prefill_grouped(fdesc, wl.L, 1.0, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream))):
-                evs = []
-                for i in range(n_warm + n_timed):
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record(stream)
-                    call()
-                    e1.record(stream)
-                    if i >= n_warm:
-                        evs.append((e0, e1))
-                stream.synchronize()
-                t_ms = [a.elapsed_time(b) for a, b in evs]
-                t_mean = sum(t_ms) / len(t_ms)
-                row[key] = {"ms": {"mean": t_mean, "min": min(t_ms)}, "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3),
-                            "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                         "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
-            flash[name] = row
-            del q, k, v, out, fws
-        torch.cuda.empty_cache()
-
     grouped = None
     if do_prefill and args.only == "all" and pw.chunk == 64:
         # next row of the scope (not part of the step): the three-branch form of the same prefill (grouped linear
@@ -468,6 +383,161 @@ def main():
                                          "frac": nb / t_mean / 1e3 / HBM_PEAK_GBS, "algorithmic_bytes": nb,
                                          "traffic_from_profiles": read_traffic(f"verify_grouped_cfg4_{key}_pmc.txt")}}
 
+    side = None
+    if args.only == "all" and not args.length:
+        # the other prefill workloads (not part of the step): configs 1, 2 and 5, head-major as the parity tests
+        # run them, two input sets each (config 2's 25 MB would otherwise be served from the last-level cache)
+        side = {}
+        for name in ("cfg1_fp32_tiny", "cfg2_gpt2_small", "cfg5_long_context"):
+            wl = workloads.CONFIGS[name]
+            sdt = workloads.torch_dtype(wl.io_dtype)
+            gs = torch.Generator(device=dev).manual_seed(wl.seed)
+            sets = []
+            for _ in range(2 if name != "cfg2_gpt2_small" else 16):
+                q, k, v = ((torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev) * wl.scale).to(sdt) for _ in range(3))
+                sets.append((q, k, v, torch.empty_like(q)))
+            swts = torch.from_numpy(workloads.conv_weights(np.random.default_rng(wl.seed), wl.H, wl.d, wl.conv_k)).to(dev)
+            sdesc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, sdt, L=wl.L)
+            sws_bytes = binding.linattn_workspace_bytes(sdesc, wl.L)
+            sws = torch.empty(max(sws_bytes, 16), dtype=torch.uint8, device=dev)
+            sS = torch.empty((wl.B, wl.H, wl.d, wl.d), device=dev)
+            sz = torch.empty((wl.B, wl.H, wl.d), device=dev)
+            sh = torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d), device=dev, dtype=sdt)
+            evs = []
+            n_warm, n_timed = 20, min(max(args.steps, 20), 50)
+            for i in range(n_warm + n_timed):
+                q, k, v, out = sets[i % len(sets)]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                binding.linattn_prefill(sdesc, wl.L, q, k, v, swts, None, None, None, out, sS, sz, sh, sws, sws_bytes, stream)
+                e1.record(stream)
+                if i >= n_warm:
+                    evs.append((e0, e1))
+            stream.synchronize()
+            t_ms = [a.elapsed_time(b) for a, b in evs]
+            t_mean = sum(t_ms) / len(t_ms)
+            esz = 4 if wl.io_dtype == "f32" else 2
+            nb = 4 * wl.B * wl.H * wl.L * wl.d * esz
+            side[name] = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d{wl.d} {wl.io_dtype} chunk{wl.chunk} Kc{wl.conv_k}, head-major",
+                          "ms": {"mean": t_mean, "median": float(np.median(t_ms)), "min": min(t_ms)},
+                          "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3), "workspace_bytes": sws_bytes,
+                          "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
+            del sets, sws, sS, sz, sh
+        torch.cuda.empty_cache()
+
+    flash = None
+    if args.only == "all" and not args.length:
+        # next row of the scope (not part of the step): the sizes of the paper's FLASH experiment -- 63-tap masked
+        # DWConv, groups of 256 tokens, batch 1, 1K / 4K / 8K tokens, as eight heads of 128.  Token-level form
+        # (matrix-core attention kernel + the long-convolution pass) and the three-branch form in groups of 256
+        # (the plain fp32 kernel: one workgroup per head, token by token -- correct, not fast).
+        flash = {}
+        for name in ("flash_L1024", "flash_L4096", "flash_L8192"):
+            wl = workloads.CONFIGS[name]
+            gs = torch.Generator(device=dev).manual_seed(wl.seed)
+            q, k, v = ((torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev) * wl.scale).to(torch.bfloat16) for _ in range(3))
+            out = torch.empty_like(q)
+            fw = torch.from_numpy(workloads.conv_weights(np.random.default_rng(wl.seed), wl.H, wl.d, wl.conv_k)).to(dev)
+            fdesc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, torch.bfloat16, L=wl.L)
+            fws_bytes = binding.linattn_workspace_bytes(fdesc, wl.L)
+            fws = torch.empty(max(fws_bytes, 16), dtype=torch.uint8, device=dev)
+            fS = torch.empty((wl.B, wl.H, wl.d, wl.d), device=dev)
+            fz = torch.empty((wl.B, wl.H, wl.d), device=dev)
+            fh = torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d), device=dev, dtype=torch.bfloat16)
+            nb = 4 * wl.B * wl.H * wl.L * wl.d * 2
+            row = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d{wl.d} bf16, groups of {wl.chunk}, Kc{wl.conv_k}, head-major"}
+            for key, n_warm, n_timed, call in (
+                    ("token_level", 10, 30, lambda: binding.linattn_prefill(fdesc, wl.L, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream)),
+                    ("three_branch", 1, 3, lambda: binding.linattn_prefill_grouped(fdesc, wl.L, 1.0, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream))):
+                evs = []
+                for i in range(n_warm + n_timed):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    call()
+                    e1.record(stream)
+                    if i >= n_warm:
+                        evs.append((e0, e1))
+                stream.synchronize()
+                t_ms = [a.elapsed_time(b) for a, b in evs]
+                t_mean = sum(t_ms) / len(t_ms)
+                row[key] = {"ms": {"mean": t_mean, "min": min(t_ms)}, "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3),
+                            "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
+            flash[name] = row
+            del q, k, v, out, fws
+        torch.cuda.empty_cache()
+
+    wide = None
+    if args.only == "all" and not args.length:
+        # next row of the scope (not part of the step): value rows wider than key rows, d_k 64 / d_v 128 on the
+        # LLaMA layer shape -- prefill (two value blocks per head on the matrix-core kernel, q and k read by both)
+        # and an 8-draft verify step (streaming kernel: column slices of the 64 x 128 state)
+        wide = {}
+        wl = workloads.CONFIGS["wide_values_prefill"]
+        gs = torch.Generator(device=dev).manual_seed(wl.seed)
+        sets = []
+        for _ in range(2):
+            q, k = ((torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev) * wl.scale).to(torch.bfloat16) for _ in range(2))
+            v = (torch.randn((wl.B, wl.H, wl.L, wl.d_v), generator=gs, device=dev) * wl.scale).to(torch.bfloat16)
+            sets.append((q, k, v, torch.empty_like(v)))
+        ww = torch.from_numpy(workloads.conv_weights(np.random.default_rng(wl.seed), wl.H, wl.d_v, wl.conv_k)).to(dev)
+        wdesc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, torch.bfloat16, L=wl.L, d_v=wl.d_v)
+        wS = torch.empty((wl.B, wl.H, wl.d, wl.d_v), device=dev)
+        wz = torch.empty((wl.B, wl.H, wl.d), device=dev)
+        wh = torch.empty((wl.B, wl.H, wl.conv_k - 1, wl.d_v), device=dev, dtype=torch.bfloat16)
+        evs = []
+        for i in range(20 + 30):
+            q, k, v, out = sets[i % 2]
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            binding.linattn_prefill(wdesc, wl.L, q, k, v, ww, None, None, None, out, wS, wz, wh, None, 0, stream)
+            e1.record(stream)
+            if i >= 20:
+                evs.append((e0, e1))
+        stream.synchronize()
+        t_ms = [a.elapsed_time(b) for a, b in evs]
+        t_mean = sum(t_ms) / len(t_ms)
+        nb = wl.B * wl.H * wl.L * (2 * wl.d + 2 * wl.d_v) * 2
+        wide["prefill"] = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d_k{wl.d} d_v{wl.d_v} bf16 chunk{wl.chunk} Kc{wl.conv_k}, head-major",
+                           "ms": {"mean": t_mean, "median": float(np.median(t_ms)), "min": min(t_ms)},
+                           "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3),
+                           "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                        "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
+        del sets
+        if do_verify:
+            vwl = workloads.CONFIGS["wide_values_verify"]
+            kk = 8
+            wstates = [(torch.randn((vwl.B, vwl.H, vwl.d, vwl.d_v), generator=gs, device=dev) * 50.0,
+                        torch.rand((vwl.B, vwl.H, vwl.d), generator=gs, device=dev) * 100.0 + 1900.0,
+                        torch.randn((vwl.B, vwl.H, vwl.conv_k - 1, vwl.d_v), generator=gs, device=dev).to(torch.bfloat16))
+                       for _ in range(args.state_sets)]
+            dq, dk = (torch.randn((vwl.B, vwl.H, kk, vwl.d), generator=gs, device=dev).to(torch.bfloat16) for _ in range(2))
+            dv = torch.randn((vwl.B, vwl.H, kk, vwl.d_v), generator=gs, device=dev).to(torch.bfloat16)
+            do = torch.empty_like(dv)
+            vdesc2 = binding.make_desc(vwl.B, vwl.H, vwl.d, vwl.conv_k, 64, torch.bfloat16, L=kk, d_v=vwl.d_v)
+            evs = []
+            for i in range(10 + 40):
+                S, z, h = wstates[i % len(wstates)]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                binding.linattn_verify(vdesc2, kk, dq, dk, dv, ww, S, z, h, None, do, stream)
+                e1.record(stream)
+                if i >= 10:
+                    evs.append((e0, e1))
+            stream.synchronize()
+            t_us = [a.elapsed_time(b) * 1e3 for a, b in evs]
+            t_mean = sum(t_us) / len(t_us)
+            heads = vwl.B * vwl.H
+            nb = heads * ((vwl.d * vwl.d_v + vwl.d) * 8 + kk * (2 * vwl.d + 2 * vwl.d_v) * 2 + (vwl.conv_k - 1) * vwl.d_v * 4)
+            wide["verify_k8"] = {"workload": f"B{vwl.B} H{vwl.H} d_k{vwl.d} d_v{vwl.d_v} bf16, 8 drafts, all kept, synthetic state of the "
+                                             "magnitude a 2048-token prefix leaves",
+                                 "us": {"mean": t_mean, "median": float(np.median(t_us)), "min": min(t_us)},
+                                 "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                              "frac": nb / t_mean / 1e3 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
+            del wstates
+        torch.cuda.empty_cache()
+
     timed_ms = {n: [a.elapsed_time(b) for a, b in lst[n_settled[n]:]] for n, lst in ev.items() if len(lst) > n_settled[n]}
     mean_ms = {n: sum(t) / len(t) for n, t in timed_ms.items()}
     min_ms = {n: min(t) for n, t in timed_ms.items()}
@@ -533,6 +603,8 @@ def main():
         result["other_configs"] = side
     if flash:
         result["flash_shape"] = flash
+    if wide:
+        result["wide_values"] = wide
     if not args.no_cpu_baseline and do_prefill:
         result["cpu_baseline"] = cpu_baseline(pw, args.cpu_seconds)
     print(json.dumps(result))

@@ -59,14 +59,17 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
     for (int e = 0; e < CL_BLK; ++e) acc[e] = 0.f;
     // value rows from the newest output's own row backwards: row m feeds output e through tap e - 7 + m
     const float* newest = xs + (CL_HALO + tb0 + CL_BLK - 1) * D + c;
+    // (fully unrolled, so that every tap index is a constant and the taps stay in registers)
 #pragma unroll
     for (int m = 0; m < CL_MAXK + CL_BLK - 1; ++m) {
-      if (m - (CL_BLK - 1) >= Kc) break;      // uniform: no output of the block reaches this far back
-      const float x = newest[-m * D];
+      if (m - (CL_BLK - 1) < Kc) {            // uniform: beyond that no output of the block reaches this far back
+        const float x = newest[-m * D];
 #pragma unroll
-      for (int e = 0; e < CL_BLK; ++e) {
-        const int j = e - (CL_BLK - 1) + m;
-        if (j >= 0 && j < CL_MAXK) acc[e] = fmaf(wreg[j], x, acc[e]);
+        for (int e = 0; e < CL_BLK; ++e) {
+          constexpr int J0 = -(CL_BLK - 1);
+          const int j = e + J0 + m;
+          if (j >= 0 && j < CL_MAXK) acc[e] = fmaf(wreg[j], x, acc[e]);
+        }
       }
     }
 #pragma unroll
