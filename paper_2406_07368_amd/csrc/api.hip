@@ -92,19 +92,20 @@ struct PrefillPlan {
 // segments whose start states come from a first pass over K, V and a scan.
 PrefillPlan plan_prefill(const linattn_desc* d, int32_t L, bool grouped = false) {
   PrefillPlan p{};
-  // the matrix-core kernel's three-branch form has groups of 64 tokens; groups of 256 take the vector-ALU kernel
-  p.mfma = d->io_dtype == LINATTN_BF16 && !(grouped && d->chunk != 64);
+  p.mfma = d->io_dtype == LINATTN_BF16;
+  const bool g256 = p.mfma && grouped && d->chunk == 256;   // three-branch form in groups of 256: its own full pass
   p.nseg = 1;
   p.seg_len = L;
   const int heads = d->B * d->H * value_blocks(d);      // what the kernels see as heads: one per value block
   if (p.mfma && L > 0) {
-    p.nseg = prefill_mfma_pick_segments(heads, L, d->chunk);
+    p.nseg = g256 ? prefill_grouped256_pick_segments(heads, L) : prefill_mfma_pick_segments(heads, L, d->chunk);
     const int chunks = (L + d->chunk - 1) / d->chunk;
     const int cps = (chunks + p.nseg - 1) / p.nseg;
     p.seg_len = cps * d->chunk;
     p.nseg = (L + p.seg_len - 1) / p.seg_len;
   }
-  p.ws_bytes = p.mfma ? prefill_mfma_workspace_bytes(heads, d->d, p.nseg) : 0;
+  p.ws_bytes = !p.mfma ? 0 : g256 ? prefill_grouped256_workspace_bytes(heads, d->d, p.nseg)
+                                  : prefill_mfma_workspace_bytes(heads, d->d, p.nseg);
   return p;
 }
 
@@ -203,7 +204,10 @@ int32_t linattn_set_wait_limit(int32_t spins) {
 
 size_t linattn_workspace_bytes(const linattn_desc* desc, int32_t L) {
   if (check_desc(desc, true, true, LINATTN_MAX_CONV_K_PREFILL) != LINATTN_OK || L < 0) return 0;
-  return plan_prefill(desc, L).ws_bytes;
+  // the descriptor does not say which prefill form will be called: enough for either
+  const size_t a = plan_prefill(desc, L, false).ws_bytes;
+  const size_t b = desc->chunk == 256 && value_blocks(desc) == 1 ? plan_prefill(desc, L, true).ws_bytes : 0;
+  return a > b ? a : b;
 }
 
 linattn_status linattn_prefill(const linattn_desc* desc, int32_t L, const void* q, const void* k, const void* v,

@@ -20,7 +20,10 @@ constexpr int CL_MAXK = 63;
 constexpr int CL_BLK = 8;         // outputs a thread carries at once
 }  // namespace
 
-template <typename Io, int D>
+// KMAX: tap capacity of the instantiation (taps beyond Kc are zeros; the loops below are straight-line code for
+// exactly KMAX taps: a branch per tap would put every LDS read into a basic block of its own, with a full wait
+// behind it).
+template <typename Io, int D, int KMAX>
 __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   extern __shared__ float xs[];   // [CL_HALO + CL_TOK][D]
   constexpr int NG = 256 / D;                 // token groups of threads
@@ -35,87 +38,149 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   const int64_t hist_base = (int64_t)bh * (Kc - 1) * DVT + (int64_t)blk * D;
   const int c = tid % D, tg = tid / D;
 
-  // this channel's taps; beyond Kc they are zero, so the unrolled loop below needs no tap count
-  float wreg[CL_MAXK];
+  // this channel's taps; beyond Kc they are zero, so the unrolled loop below needs no tap count.  The D * Kc taps of
+  // the block are contiguous in memory: they come in through LDS with whole-row requests (a thread reading its own
+  // Kc consecutive floats would touch 64 cache lines per request), then each thread picks its own (stride Kc floats
+  // between lanes; Kc odd or not, at most a 2-way bank conflict, once per workgroup).
+  float wreg[KMAX];
+  {
+    // (16 bytes per request, every request of the thread issued before the first value is stored)
+    const f32x4* wsrc = reinterpret_cast<const f32x4*>(a.conv_w + ((size_t)h * DVT + blk * D) * Kc);
+    constexpr int WIT = (D * KMAX / 4 + 255) / 256;
+    f32x4 wt[WIT];
 #pragma unroll
-  for (int j = 0; j < CL_MAXK; ++j) wreg[j] = j < Kc ? a.conv_w[((size_t)h * DVT + blk * D + c) * Kc + j] : 0.f;
+    for (int i = 0; i < WIT; ++i) {
+      const int e = tid + 256 * i;
+      wt[i] = wsrc[e < D * Kc / 4 ? e : D * Kc / 4 - 1];   // unconditional: a branch would end in a full wait
+    }
+#pragma unroll
+    for (int i = 0; i < WIT; ++i) {
+      const int e = tid + 256 * i;
+      if (e < D * Kc / 4) *reinterpret_cast<f32x4*>(xs + 4 * e) = wt[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) wreg[j] = j < Kc ? xs[c * Kc + j] : 0.f;
+    __syncthreads();                          // the staging area is about to take the value rows
+  }
 
   // rows t0 - 62 .. t0 + 63: the sequence, before it the incoming history, before that (and past the end) zeros
-  for (int e = tid; e < (CL_HALO + CL_TOK) * (D / 8); e += 256) {
-    const int row = e / (D / 8), i0 = 8 * (e % (D / 8));
-    const int tok = t0 - CL_HALO + row;
-    float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (tok >= 0 && tok < L) Io::load8(a.v, base + (int64_t)tok * a.st + i0, x);
-    else if (tok < 0 && a.hist_in && Kc - 1 + tok >= 0) Io::load8(a.hist_in, hist_base + (int64_t)(Kc - 1 + tok) * DVT + i0, x);
+  // (again every request first, then the stores)
+  {
+    constexpr int RIT = ((CL_HALO + CL_TOK) * (D / 8) + 255) / 256;
+    typename Io::raw8 raw[RIT];
+    bool have[RIT];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) xs[row * D + i0 + i] = x[i];
+    for (int i = 0; i < RIT; ++i) {
+      const int e = tid + 256 * i;
+      const int row = e / (D / 8), i0 = 8 * (e % (D / 8));
+      const int tok = t0 - CL_HALO + row;
+      // unconditional requests (a row that does not exist reads row 0 of the sequence instead and is dropped):
+      // every branch around a request would end in a full wait
+      const bool in_seq = tok >= 0 && tok < L;
+      const bool in_hist = tok < 0 && a.hist_in != nullptr && Kc - 1 + tok >= 0;
+      const void* src = in_hist ? a.hist_in : a.v;
+      const int64_t idx = in_hist ? hist_base + (int64_t)(Kc - 1 + tok) * DVT + i0 : base + (int64_t)(in_seq ? tok : 0) * a.st + i0;
+      raw[i] = Io::load_raw8(src, idx);
+      have[i] = in_seq || in_hist;
+    }
+#pragma unroll
+    for (int i = 0; i < RIT; ++i) {
+      const int e = tid + 256 * i;
+      const int row = e / (D / 8), i0 = 8 * (e % (D / 8));
+      if (e < (CL_HALO + CL_TOK) * (D / 8)) {
+        float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (have[i]) Io::unpack8(raw[i], x);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) xs[row * D + i0 + j] = x[j];
+      }
+    }
   }
   __syncthreads();
 
   for (int tb0 = tg * TPT; tb0 < (tg + 1) * TPT; tb0 += CL_BLK) {
     if (t0 + tb0 >= L) break;                 // uniform per wave: D >= 64 channels share tb0
-    float acc[CL_BLK];
+    // what the attention kernels left in out for these 8 tokens: requested now, needed after the 500 multiply-adds
+    // (read and written back one by one, each token would pay a round trip to memory of its own)
+    float acc[CL_BLK], prev[CL_BLK];
 #pragma unroll
-    for (int e = 0; e < CL_BLK; ++e) acc[e] = 0.f;
+    for (int e = 0; e < CL_BLK; ++e) {
+      acc[e] = 0.f;
+      const int tok = t0 + tb0 + e;                       // past the end: the last token's element, never stored
+      prev[e] = Io::load1(a.out, base + (int64_t)(tok < L ? tok : L - 1) * a.st + c);
+    }
     // value rows from the newest output's own row backwards: row m feeds output e through tap e - 7 + m
     const float* newest = xs + (CL_HALO + tb0 + CL_BLK - 1) * D + c;
     // (fully unrolled, so that every tap index is a constant and the taps stay in registers)
 #pragma unroll
-    for (int m = 0; m < CL_MAXK + CL_BLK - 1; ++m) {
-      if (m - (CL_BLK - 1) < Kc) {            // uniform: beyond that no output of the block reaches this far back
-        const float x = newest[-m * D];
+    for (int m = 0; m < KMAX + CL_BLK - 1; ++m) {
+      const float x = newest[-m * D];
 #pragma unroll
-        for (int e = 0; e < CL_BLK; ++e) {
-          constexpr int J0 = -(CL_BLK - 1);
-          const int j = e + J0 + m;
-          if (j >= 0 && j < CL_MAXK) acc[e] = fmaf(wreg[j], x, acc[e]);
-        }
+      for (int e = 0; e < CL_BLK; ++e) {
+        constexpr int J0 = -(CL_BLK - 1);
+        const int j = e + J0 + m;
+        if (j >= 0 && j < KMAX) acc[e] = fmaf(wreg[j], x, acc[e]);
       }
     }
 #pragma unroll
     for (int e = 0; e < CL_BLK; ++e) {
       const int tok = t0 + tb0 + e;
-      if (tok < L) {
-        const int64_t o = base + (int64_t)tok * a.st + c;
-        Io::store1(a.out, o, Io::load1(a.out, o) + acc[e]);
-      }
+      if (tok < L) Io::store1(a.out, base + (int64_t)tok * a.st + c, prev[e] + acc[e]);
     }
   }
 }
 
 // New history = the last Kc-1 rows of (incoming history ++ sequence).  Runs behind conv_long_kernel, which is the
-// last reader of hist_in; one thread per channel writes its rows in ascending order and reads row L + r >= r of
-// the extended sequence for row r, so hist_out may be hist_in.
-template <typename Io>
-__global__ void conv_long_hist_kernel(ConvLongArgs a, int D) {
+// last reader of hist_in before this.  One workgroup per (b, h, value block): every element is read (all requests in
+// flight at once) before, behind a barrier, any is written, so hist_out may be hist_in.
+template <typename Io, int D>
+__global__ __launch_bounds__(256) void conv_long_hist_kernel(ConvLongArgs a) {
   const int bh = blockIdx.x / a.m, blk = blockIdx.x % a.m, b = bh / a.H, h = bh % a.H;
-  const int c = threadIdx.x;
-  if (c >= D) return;
+  const int tid = threadIdx.x;
   const int R = a.Kc - 1, DVT = a.m * D;
   const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh + (int64_t)blk * D;
   const int64_t hist_base = (int64_t)bh * R * DVT + (int64_t)blk * D;
-  for (int r = 0; r < R; ++r) {
+  constexpr int EIT = (CL_HALO * D + 255) / 256;
+  float x[EIT];
+#pragma unroll
+  for (int i = 0; i < EIT; ++i) {
+    const int el = tid + 256 * i;
+    const int r = el / D, c = el % D;
     const int e = a.L + r;                    // row of (history ++ sequence), the history being rows 0 .. R-1
-    float x = 0.f;
-    if (e >= R) x = Io::load1(a.v, base + (int64_t)(e - R) * a.st + c);
-    else if (a.hist_in) x = Io::load1(a.hist_in, hist_base + (int64_t)e * DVT + c);
-    Io::store1(a.hist_out, hist_base + (int64_t)r * DVT + c, x);
+    x[i] = 0.f;
+    if (r < R) {
+      if (e >= R) x[i] = Io::load1(a.v, base + (int64_t)(e - R) * a.st + c);
+      else if (a.hist_in) x[i] = Io::load1(a.hist_in, hist_base + (int64_t)e * DVT + c);
+    }
   }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < EIT; ++i) {
+    const int el = tid + 256 * i;
+    const int r = el / D, c = el % D;
+    if (r < R) Io::store1(a.hist_out, hist_base + (int64_t)r * DVT + c, x[i]);
+  }
+}
+
+template <typename Io, int D, int KMAX>
+static hipError_t launch_cl_k(const ConvLongArgs& a, hipStream_t st) {
+  constexpr int LDS = (CL_HALO + CL_TOK) * D * (int)sizeof(float);
+  auto kern = conv_long_kernel<Io, D, KMAX>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3((unsigned)((a.L + CL_TOK - 1) / CL_TOK), (unsigned)(a.B * a.H * a.m)), dim3(256), LDS, st, a);
+  return hipGetLastError();
 }
 
 template <typename Io, int D>
 static hipError_t launch_cl(const ConvLongArgs& a, hipStream_t st) {
-  constexpr int LDS = (CL_HALO + CL_TOK) * D * (int)sizeof(float);
   hipError_t e = hipSuccess;
   if (a.L > 0) {
-    auto kern = conv_long_kernel<Io, D>;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    e = a.Kc <= 16 ? launch_cl_k<Io, D, 16>(a, st) : a.Kc <= 32 ? launch_cl_k<Io, D, 32>(a, st) : launch_cl_k<Io, D, CL_MAXK>(a, st);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((a.L + CL_TOK - 1) / CL_TOK), (unsigned)(a.B * a.H * a.m)), dim3(256), LDS, st, a);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (a.hist_out) {
-    hipLaunchKernelGGL((conv_long_hist_kernel<Io>), dim3((unsigned)(a.B * a.H * a.m)), dim3(D), 0, st, a, D);
+    hipLaunchKernelGGL((conv_long_hist_kernel<Io, D>), dim3((unsigned)(a.B * a.H * a.m)), dim3(256), 0, st, a);
     e = hipGetLastError();
   }
   return e;

@@ -144,6 +144,12 @@ int prefill_mfma_pick_segments(int BH, int L, int chunk);
 size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg);
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st);
 
+// prefill_grouped256.hip : the three-branch form in groups of 256 tokens on the matrix cores (bf16 rows); one
+// workspace slot per (b, h, segment) also without segments
+int prefill_grouped256_pick_segments(int BH, int L);
+size_t prefill_grouped256_workspace_bytes(int BH, int d, int nseg);
+hipError_t launch_prefill_grouped256(const PrefillArgs& a, int d, hipStream_t st);
+
 // prefill_mfma_ws.hip : the matrix-core kernel, with front-end waves (HBM traffic, feature map, scores)
 // and state waves (everything that touches S and z) working side by side
 hipError_t launch_prefill_mfma_ws(const PrefillArgs& a, int d, bool state_only, bool grouped, hipStream_t st);

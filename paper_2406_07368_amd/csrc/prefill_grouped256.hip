@@ -1,0 +1,437 @@
+// The three-branch form of Sec. 4.1 in groups of 256 tokens on the matrix cores (bf16 rows): the group size of the
+// paper's FLASH experiment (Sec. 5 "Settings", Sec. 5.3).  Per token t of a group g
+//
+//   out_t = alpha * phi(q_t)^T S_g / (phi(q_t).z_g + eps)            S_g, z_g: the sums over everything before the group
+//         + sum_{i in g, i <= t} softmax_i(q_t.k_i / sqrt(d)) v_i     causal softmax attention inside the group (Eq. 1)
+//         + causal depthwise conv of V
+//
+// A group of 256 tokens is four times what the 64-token kernel keeps in LDS, and its running state cannot both stay
+// frozen for the group and take the group's own products in the same registers.  So this kernel is built the other
+// way round: one workgroup of eight waves per (b, h, segment) walks its groups with the whole group's raw key and
+// value rows in LDS (139 KB at d = 128) and the running state in its workspace slot in global memory (fp32; it stays
+// in the L2 cache between the group's read-out and its update).  Wave w owns the 32 queries 32w .. 32w+31 of the
+// group and all value channels:
+//
+//   local branch    for each 32-key tile up to the diagonal: S^T tile = K Q^T (keys in registers, queries in lanes),
+//                   online softmax per lane (running maximum, running sum), and O^T += V^T P^T with P taken
+//                   straight from the score accumulators as the MFMA operand -- the accumulator layout is the
+//                   operand layout up to a permutation of the key index, which is applied to the transposed reads
+//                   of V instead, so the weights never touch LDS;
+//   linear branch   O_lin^T = S_g^T phi(Q)^T, one 32-channel tile at a time, the state read from the workspace slot as
+//                   the MFMA operand (bf16, rounded for the read-out only, as in the other matrix-core kernels);
+//   epilogue        O / l + alpha O_lin / (phi(q).z_g + eps), staged through LDS in fp32 (the key rows' memory); the
+//                   store loop adds the causal conv over V and writes whole rows.
+//
+// Then, unless nothing after the group needs it, the group enters the state: phi is applied to the key rows in
+// place and every wave adds two 32 x 32 tiles of phi(K)^T V to the slot.  Segments along the sequence start on group
+// boundaries; their start states come from the same first pass and prefix sum as in the 64-token kernels.
+#include "common.h"
+#include "kernels.h"
+#include "mfma_util.h"
+
+namespace linattn {
+
+namespace {
+
+template <int D>
+struct G256Cfg {
+  static constexpr int GT = 256;             // tokens per group
+  static constexpr int NW = 8;               // waves: one 32-query tile each
+  static constexpr int NT = NW * 64;
+  static constexpr int KSD = D / 16;         // feature steps of a 32 x 32 x 16 MFMA
+  static constexpr int CT = D / 32;          // 32-channel tiles
+  static constexpr int KS = D + 8;           // key rows: 16-byte row reads, transpose reads
+  static constexpr int VS = D + 4;           // value rows: transpose reads, 8-byte row reads
+  static constexpr int OS = D + 4;           // staged output rows, fp32, 128 at a time (in the key rows' memory)
+  static constexpr int OFF_K = 0;
+  static constexpr int OFF_V = OFF_K + GT * KS * 2;                   // row r = token r - HALO
+  static constexpr int OFF_W = (OFF_V + (HALO + GT) * VS * 2 + 15) / 16 * 16;   // [8][D] float conv taps, tap-major
+  static constexpr int OFF_Z = OFF_W + 8 * D * 4;                     // [D] float: z before the group
+  static constexpr int TOTAL = OFF_Z + D * 4;
+  static_assert(128 * OS * 4 <= GT * KS * 2, "the staged outputs take the place of the key rows");
+  static_assert(TOTAL <= 160 * 1024, "LDS");
+};
+
+// Transposed MFMA operand of a row-major bf16 array with lanes <-> 32 columns col0 + lane % 32 and registers <-> the
+// rows in the order in which a 32 x 32 score accumulator holds its keys: registers 0..3 <-> rows row0 + 4 (lane / 32)
+// + 0..3, registers 4..7 <-> rows row0 + 8 + 4 (lane / 32) + 0..3.
+__device__ __forceinline__ bf16x8 tr_operand_acc_order(const uint16_t* base, int stride, int row0, int col0, int lane) {
+  const int j = lane & 15;
+  const uint16_t* p = base + (row0 + 4 * (lane >> 5) + (j >> 2)) * stride + col0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
+  return cat4(lds_tr4(p), lds_tr4(p + 8 * stride));
+}
+
+}  // namespace
+
+// Keeps the compiler from moving memory operations across this point: the unrolled epilogue would otherwise
+// request every tap, value row and state word of a group at once and spill hundreds of registers.
+#define LINATTN_ORDER() __asm__ volatile("" ::: "memory")
+
+template <int D, int KCM>
+__global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) {
+  using G = G256Cfg<D>;
+  constexpr int GT = G::GT;
+  constexpr int SLOT = D * D + D;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* Kl = reinterpret_cast<uint16_t*>(smem + G::OFF_K);
+  uint16_t* Vl = reinterpret_cast<uint16_t*>(smem + G::OFF_V);
+  float* wl = reinterpret_cast<float*>(smem + G::OFF_W);
+  float* zl = reinterpret_cast<float*>(smem + G::OFF_Z);
+  float* Ol = reinterpret_cast<float*>(smem + G::OFF_K);   // staged output rows, once the key rows are done with
+
+  const int tid = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+  const int bh = blockIdx.x / a.nseg, seg = blockIdx.x % a.nseg;
+  const int b = bh / a.H, h = bh % a.H;
+  const int t_begin = seg * a.seg_len;
+  const int t_end = (t_begin + a.seg_len) < a.L ? (t_begin + a.seg_len) : a.L;
+  const int ngroups = (t_end - t_begin + GT - 1) / GT;
+  const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
+  const uint16_t* gq = static_cast<const uint16_t*>(a.q) + base;
+  const uint16_t* gk = static_cast<const uint16_t*>(a.k) + base;
+  const uint16_t* gv = static_cast<const uint16_t*>(a.v) + base;
+  uint16_t* gout = static_cast<uint16_t*>(a.out) + base;
+  // this workgroup's slot: the state before its current group, S [D][D] then z [D], fp32
+  float* slot = a.ws + ((size_t)bh * a.nseg + seg) * SLOT;
+  const uint16_t* staged_hist =
+      reinterpret_cast<const uint16_t*>(a.ws + (size_t)a.B * a.H * a.nseg * SLOT) + (size_t)bh * HALO * D;
+  const bool last_seg = seg == a.nseg - 1;
+  // The slot through buffer addressing (descriptor in scalar registers + one lane offset + a constant per request):
+  // the several hundred requests of a group then need no address registers of their own.
+  const __amdgpu_buffer_rsrc_t slot_rs = __builtin_amdgcn_make_buffer_rsrc(slot, 0, SLOT * 4, 0x00020000);
+  static_assert(D == 64 || D == 128, "1 / sqrt(d) below");
+  constexpr float to_log2 = 1.44269504088896340736f * (D == 64 ? 0.125f : 0.08838834764831845f);
+
+  // ---- once: the conv taps; without segments nobody has written the slot yet -----------------------------------
+  for (int e = tid; e < 8 * D; e += G::NT) {
+    const int j = e / D, cc = e % D;
+    wl[e] = (j < a.Kc && !a.no_conv) ? a.conv_w[((size_t)h * D + cc) * a.Kc + j] : 0.f;
+  }
+  if (a.nseg == 1) {
+    for (int e = tid; e < SLOT; e += G::NT) {
+      float x = 0.f;
+      if (a.S_in) x = e < D * D ? a.S_in[(size_t)bh * D * D + e] : a.z_in[(size_t)bh * D + (e - D * D)];
+      slot[e] = x;
+    }
+  }
+  // The slot is written and read by this workgroup only, but by different waves: a fence of workgroup scope (the
+  // waves of a workgroup share their compute unit's vector cache, so completed stores are seen by all of them; a
+  // fence of device scope would write back and invalidate the whole L2 of the chiplet, tens of microseconds) and
+  // the barrier.
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __syncthreads();
+
+  for (int gi = 0; gi < ngroups; ++gi) {
+    const int tok0 = t_begin + gi * GT;
+    const int nt = (t_end - tok0) < GT ? (t_end - tok0) : GT;
+    // ---- 1. this wave's queries, straight into MFMA operand registers: lane = query 32w + l32, registers =
+    //         features 16ks + 8hi + 0..7.  A query past the end reads the last row that exists; it is never stored.
+    const int qt = 32 * w + l32;
+    const int qrow = qt < nt ? qt : nt - 1;
+    u32x4 qraw[G::KSD];
+    {
+      const uint16_t* qp = gq + (int64_t)(tok0 + qrow) * a.st + 8 * hi;
+#pragma unroll
+      for (int ks = 0; ks < G::KSD; ++ks) qraw[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+    }
+    constexpr int SIT = D * D / 4 / G::NT;                 // 16-byte pieces of S per thread
+    u32x2 spk[SIT];                                        // ... rounded to bf16 once they have arrived
+    // ---- 2. the group's raw key rows and value rows -> LDS (rows past the end are zero rows), the 8 value rows
+    //         before the group (earlier tokens, else the incoming history, else zeros), z before the group
+    //         (every request of the group is issued before the first one is waited for)
+    {
+      constexpr int NPC = GT * (D / 8) / G::NT;            // 16-byte pieces of K (and of V) per thread
+      constexpr int NHL = HALO * D / G::NT;                // elements of the 8 rows before the group per thread
+      u32x4 kx[NPC], vx[NPC];
+      uint16_t hx[NHL];
+      // the state before the group, for the linear branch: requested first (requests return in order, so it has
+      // arrived -- ahead of any update of the slot -- by the time the rows below are stored), kept in registers
+      // while the local branch runs
+      f32x4 sreg[SIT];
+#pragma unroll
+      for (int i = 0; i < SIT; ++i) sreg[i] = reinterpret_cast<const f32x4*>(slot)[tid + G::NT * i];
+#pragma unroll
+      for (int i = 0; i < NPC; ++i) {
+        const int e = tid + G::NT * i;
+        const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
+        kx[i] = vx[i] = u32x4{0, 0, 0, 0};
+        if (r < nt) {
+          kx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gk + (int64_t)(tok0 + r) * a.st + c0));
+          vx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gv + (int64_t)(tok0 + r) * a.st + c0));
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < NHL; ++i) {
+        const int e = tid + G::NT * i;
+        const int r = e / D, cc = e % D;
+        const int tok = tok0 - HALO + r;
+        hx[i] = 0;
+        if (tok >= 0) hx[i] = gv[(int64_t)tok * a.st + cc];
+        else if (a.hist_in && a.nseg > 1) hx[i] = staged_hist[(size_t)(HALO + tok) * D + cc];
+        else if (a.hist_in && a.Kc - 1 + tok >= 0)
+          hx[i] = static_cast<const uint16_t*>(a.hist_in)[((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + cc];
+      }
+      const float zx = tid < D ? slot[D * D + tid] : 0.f;
+#pragma unroll
+      for (int i = 0; i < NPC; ++i) {
+        const int e = tid + G::NT * i;
+        const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
+        *reinterpret_cast<u32x4*>(Kl + r * G::KS + c0) = kx[i];
+        u32x2* vrow = reinterpret_cast<u32x2*>(Vl + (HALO + r) * G::VS + c0);
+        vrow[0] = u32x2{vx[i][0], vx[i][1]};
+        vrow[1] = u32x2{vx[i][2], vx[i][3]};
+      }
+#pragma unroll
+      for (int i = 0; i < NHL; ++i) {
+        const int e = tid + G::NT * i;
+        Vl[(e / D) * G::VS + e % D] = hx[i];
+      }
+      if (tid < D) zl[tid] = zx;
+#pragma unroll
+      for (int i = 0; i < SIT; ++i) spk[i] = u32x2{pack_bf16x2(sreg[i][0], sreg[i][1]), pack_bf16x2(sreg[i][2], sreg[i][3])};
+    }
+    __syncthreads();                                       // A: the group is in LDS
+
+    // ---- 3. local branch: key tiles 0 .. w, online softmax per lane, O^T += V^T P^T ---------------------------
+    // o[ct][r] = O[query 32w + l32][channel 32ct + 8(r/4) + 4hi + r%4]
+    f32x16 o[G::CT];
+#pragma unroll
+    for (int ct = 0; ct < G::CT; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[ct][r] = 0.f;
+    float mtop = -INFINITY, mass = 0.f;                    // largest raw product so far; this lane's share of the sum
+    for (int kt = 0; kt <= w; ++kt) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      const uint16_t* ka = Kl + (32 * kt + l32) * G::KS + 8 * hi;
+#pragma unroll
+      for (int ks = 0; ks < G::KSD; ++ks) acc = mfma(lds_row8(ka + 16 * ks), __builtin_bit_cast(bf16x8, qraw[ks]), acc);
+      // acc[r]: key 32kt + 8(r/4) + 4hi + r%4, query 32w + l32.  Keys later than the query (diagonal tile only)
+      // become -inf: their weight is an exact zero, nothing of a later token leaks.
+      float top = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int kl = 8 * (r >> 2) + 4 * hi + (r & 3);
+        acc[r] = (kt < w || kl <= l32) ? acc[r] : -INFINITY;
+        top = fmaxf(top, acc[r]);
+      }
+      top = fmaxf(top, __shfl_xor(top, 32));               // lanes l and l + 32 hold the same query
+      const float mnew = fmaxf(mtop, top);                 // finite from the first tile on: key 0 is seen by every query
+      const float corr = __builtin_amdgcn_exp2f((mtop - mnew) * to_log2);   // exp2(-inf) = 0 the first time
+      const float shift = -mnew * to_log2;
+      float rs = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        acc[r] = __builtin_amdgcn_exp2f(fmaf(acc[r], to_log2, shift));
+        rs += acc[r];
+      }
+      mass = fmaf(mass, corr, rs);
+      mtop = mnew;
+#pragma unroll
+      for (int ct = 0; ct < G::CT; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[ct][r] *= corr;
+      const bf16x8 p0 = pack8(acc, 0), p1 = pack8(acc, 8);
+#pragma unroll
+      for (int ct = 0; ct < G::CT; ++ct) {
+        o[ct] = mfma(tr_operand_acc_order(Vl + HALO * G::VS, G::VS, 32 * kt, 32 * ct, lane), p0, o[ct]);
+        o[ct] = mfma(tr_operand_acc_order(Vl + HALO * G::VS, G::VS, 32 * kt + 16, 32 * ct, lane), p1, o[ct]);
+      }
+    }
+    mass += __shfl_xor(mass, 32);
+    const float inv_mass = __builtin_amdgcn_rcpf(mass);    // the token itself is always seen: mass >= 1
+#pragma unroll
+    for (int ct = 0; ct < G::CT; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[ct][r] *= inv_mass;
+
+    // ---- 4. for the linear branch: phi(Q) as the MFMA operand (in place of the raw rows) and phi(q).z -----------
+    bf16x8 fq[G::KSD];
+    float dz = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < G::KSD; ++ks) {
+      const u32x4 f = phi_pack8(qraw[ks], a.relu);
+      fq[ks] = __builtin_bit_cast(bf16x8, f);
+      const float* zp = zl + 16 * ks + 8 * hi;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        dz = fmaf(bf16_lo_to_f32(f[i]), zp[2 * i], dz);
+        dz = fmaf(bf16_hi_to_f32(f[i]), zp[2 * i + 1], dz);
+      }
+    }
+    dz += __shfl_xor(dz, 32);
+    const float gden = dz + a.eps;
+    const float fscale = gden != 0.f ? a.alpha * __builtin_amdgcn_rcpf(gden) : 0.f;   // nothing before the group: no branch
+
+    // ---- 6. the group enters the state, if anything after it needs that -----------------------------------------
+    const bool more = gi + 1 < ngroups;
+    const bool update = more || (last_seg && (a.S_out != nullptr || a.z_out != nullptr));   // uniform
+    __syncthreads();                                       // B: every wave is done with the raw key rows
+    if (update) {
+      for (int e = tid; e < GT * (D / 8); e += G::NT) {
+        const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
+        u32x4* p8 = reinterpret_cast<u32x4*>(Kl + r * G::KS + c0);
+        u32x4 f = phi_pack8(*p8, a.relu);
+        if (r >= nt) f = u32x4{0, 0, 0, 0};                // phi(0) = 1: rows that do not exist stay zero rows
+        *p8 = f;
+      }
+      __syncthreads();
+      // 16 tiles (feature block ib, channel block cb) of S over 8 waves; lanes = channels, registers = features
+#pragma unroll
+      for (int s2 = 0; s2 < (G::CT * G::CT + G::NW - 1) / G::NW; ++s2) {
+        const int tile = w + G::NW * s2;
+        if (tile < G::CT * G::CT) {                        // uniform
+          const int ib = tile / G::CT, cb = tile % G::CT;
+          const int so = ((32 * ib + 4 * hi) * D + 32 * cb + l32) * 4;
+          f32x16 sacc;
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            sacc[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(slot_rs, so, (8 * (r >> 2) + (r & 3)) * (D * 4), 0));
+          for (int ks = 0; ks < GT / 16; ++ks)
+            sacc = mfma(tr_operand(Kl, G::KS, 16 * ks, 32 * ib, lane), tr_operand(Vl + HALO * G::VS, G::VS, 16 * ks, 32 * cb, lane), sacc);
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sacc[r]), slot_rs, so, (8 * (r >> 2) + (r & 3)) * (D * 4), 0);
+        }
+      }
+      if (tid < D) {
+        float zs = zl[tid];
+        for (int r = 0; r < nt; ++r) zs += bf16_bits_to_f32(Kl[r * G::KS + tid]);
+        slot[D * D + tid] = zs;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // the next group's read-out loads what other waves stored
+      __syncthreads();                                     // the key rows' memory is free; the slot is complete
+    }
+
+    // ---- 6b. linear branch: S_g (still the state before the group: it was read ahead of the update) goes to the
+    //          key rows' memory as bf16 [feature][channel]; O^T += (alpha / (phi(q).z + eps)) S_g^T phi(Q)^T with the
+    //          state operand from transposed LDS reads (lanes = channels, registers = features 16ks + 8hi + 0..7)
+    {
+      uint16_t* Sl = Kl;
+      constexpr int SS = D + 4;
+#pragma unroll
+      for (int i = 0; i < SIT; ++i) {
+        const int e = 4 * (tid + G::NT * i);
+        *reinterpret_cast<u32x2*>(Sl + (e / D) * SS + e % D) = spk[i];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int ct = 0; ct < G::CT; ++ct) {
+        f32x16 lin;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) lin[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < G::KSD; ++ks) lin = mfma(tr_operand(Sl, SS, 16 * ks, 32 * ct, lane), fq[ks], lin);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[ct][r] = fmaf(lin[r], fscale, o[ct][r]);
+      }
+      __syncthreads();                                     // every wave is done with the state operand
+    }
+
+    // ---- 7. outputs: staged as fp32 rows in the key rows' memory, 128 tokens at a time (waves 0..3, then 4..7);
+    //         the store loop adds the causal conv over V (taps and value rows from LDS), rounds once and writes
+    //         whole rows
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+      if ((w >> 2) == half) {                              // uniform per wave
+        float* orow = Ol + (qt - 128 * half) * G::OS + 4 * hi;
+#pragma unroll
+        for (int ct = 0; ct < G::CT; ++ct)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            *reinterpret_cast<f32x4*>(orow + 32 * ct + 8 * g) = f32x4{o[ct][4 * g], o[ct][4 * g + 1], o[ct][4 * g + 2], o[ct][4 * g + 3]};
+      }
+      __syncthreads();
+      for (int e = tid; e < 128 * (D / 8); e += G::NT) {
+        const int r = 128 * half + e / (D / 8), c0 = 8 * (e % (D / 8));
+        if (r < nt) {
+          const float* src = Ol + (r - 128 * half) * G::OS + c0;
+          const f32x4 y0 = *reinterpret_cast<const f32x4*>(src), y1 = *reinterpret_cast<const f32x4*>(src + 4);
+          float y[8] = {y0[0], y0[1], y0[2], y0[3], y1[0], y1[1], y1[2], y1[3]};
+#pragma unroll
+          for (int j = 0; j < KCM; ++j) {
+            const f32x4 w0 = *reinterpret_cast<const f32x4*>(wl + j * D + c0), w1 = *reinterpret_cast<const f32x4*>(wl + j * D + c0 + 4);
+            const u32x2* vp = reinterpret_cast<const u32x2*>(Vl + (HALO + r - j) * G::VS + c0);
+            const u32x2 x0 = vp[0], x1 = vp[1];
+            y[0] = fmaf(w0[0], bf16_lo_to_f32(x0[0]), y[0]);
+            y[1] = fmaf(w0[1], bf16_hi_to_f32(x0[0]), y[1]);
+            y[2] = fmaf(w0[2], bf16_lo_to_f32(x0[1]), y[2]);
+            y[3] = fmaf(w0[3], bf16_hi_to_f32(x0[1]), y[3]);
+            y[4] = fmaf(w1[0], bf16_lo_to_f32(x1[0]), y[4]);
+            y[5] = fmaf(w1[1], bf16_hi_to_f32(x1[0]), y[5]);
+            y[6] = fmaf(w1[2], bf16_lo_to_f32(x1[1]), y[6]);
+            y[7] = fmaf(w1[3], bf16_hi_to_f32(x1[1]), y[7]);
+          }
+          __builtin_nontemporal_store(u32x4{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])},
+                                      reinterpret_cast<u32x4*>(gout + (int64_t)(tok0 + r) * a.st + c0));
+        }
+      }
+      __syncthreads();                                     // the staging rows are free again; after the second half, all of LDS
+    }
+  }
+
+  // ---- the state after the last token, handed over by the last segment ----------------------------------------------
+  if (!last_seg) return;
+  if (ngroups > 0 && (a.S_out || a.z_out)) {
+    if (a.S_out) {
+      // (every request of the thread in flight before the first store: a loop of load, wait, store would pay one
+      // round trip to memory per iteration)
+      constexpr int SIT = D * D / 4 / G::NT;
+      f32x4 sx[SIT];
+#pragma unroll
+      for (int i = 0; i < SIT; ++i) sx[i] = reinterpret_cast<const f32x4*>(slot)[tid + G::NT * i];
+#pragma unroll
+      for (int i = 0; i < SIT; ++i) reinterpret_cast<f32x4*>(a.S_out + (size_t)bh * D * D)[tid + G::NT * i] = sx[i];
+    }
+    if (a.z_out && tid < D) a.z_out[(size_t)bh * D + tid] = slot[D * D + tid];
+  }
+  if (a.hist_out && tid < D) {
+    // last Kc-1 value rows of (history ++ sequence); one thread per channel reads all its rows before it writes
+    // any, so an aliased hist_in is read before it is overwritten (with segments the staged copy is read)
+    const uint16_t* hin = static_cast<const uint16_t*>(a.hist_in);
+    uint16_t* hout = static_cast<uint16_t*>(a.hist_out) + (size_t)bh * (a.Kc - 1) * D;
+    uint16_t hx[HALO];
+#pragma unroll
+    for (int r = 0; r < HALO; ++r) {
+      const int tok = a.L - (a.Kc - 1) + r;
+      hx[r] = 0;
+      if (r < a.Kc - 1) {
+        if (tok >= 0) hx[r] = gv[(int64_t)tok * a.st + tid];
+        else if (hin) hx[r] = a.nseg > 1 ? staged_hist[(size_t)(HALO + tok) * D + tid]
+                                         : hin[((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + tid];
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < HALO; ++r)
+      if (r < a.Kc - 1) hout[(size_t)r * D + tid] = hx[r];
+  }
+}
+
+#undef LINATTN_ORDER
+
+template <int D, int KCM>
+static hipError_t launch_g256(const PrefillArgs& a, hipStream_t st) {
+  using G = G256Cfg<D>;
+  auto kern = prefill_grouped256_kernel<D, KCM>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * a.nseg)), dim3(G::NT), G::TOTAL, st, a);
+  return hipGetLastError();
+}
+
+// The full pass of the three-branch form in groups of 256 tokens.  a.ws holds one slot per (b, h, segment) -- with
+// segments, filled by the first pass and the prefix sum; without, initialised here -- and the staged history rows.
+hipError_t launch_prefill_grouped256(const PrefillArgs& a, int d, hipStream_t st) {
+  if (d == 128) {
+    if (a.Kc <= 3) return launch_g256<128, 3>(a, st);
+    if (a.Kc <= 5) return launch_g256<128, 5>(a, st);
+    return launch_g256<128, 8>(a, st);
+  }
+  if (a.Kc <= 3) return launch_g256<64, 3>(a, st);
+  if (a.Kc <= 5) return launch_g256<64, 5>(a, st);
+  return launch_g256<64, 8>(a, st);
+}
+
+}  // namespace linattn

@@ -44,9 +44,11 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(PrefillArgs a) {
 // a workgroup takes most of a unit's LDS, so the 257th would wait for a whole segment), with at least 2 groups per
 // segment, and no segments at all for sequences of fewer than 8 groups, where a second launch costs more than it saves.
 int prefill_mfma_pick_segments(int BH, int L, int chunk) {
-  const int chunks = (L + chunk - 1) / chunk;
+  const int groups = (L + 63) / 64;            // the kernel walks groups of 64 tokens whatever `chunk` says
+  const int chunks = (L + chunk - 1) / chunk;  // segments start on multiples of `chunk`
   int want = 256 / BH;
-  int most = chunks >= 8 ? chunks / 2 : 1;
+  int most = groups >= 8 ? groups / 2 : 1;
+  if (most > chunks) most = chunks;
   if (want > most) want = most;
   if (want > 64) want = 64;
   return want < 1 ? 1 : want;
@@ -57,14 +59,29 @@ size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg) {
   return (size_t)BH * nseg * ((size_t)d * d + d) * sizeof(float) + (size_t)BH * HALO * d * sizeof(uint16_t);
 }
 
+// Segments of the 256-token three-branch kernel: a workgroup takes all of a compute unit, so as many as fill the
+// chip, down to one group per segment (the groups of a segment are walked one after the other).
+int prefill_grouped256_pick_segments(int BH, int L) {
+  const int groups = (L + 255) / 256;
+  int want = 256 / BH;
+  if (want > groups) want = groups;
+  if (want > 64) want = 64;
+  return want < 1 ? 1 : want;
+}
+
+// ... whose running state lives in its workspace slot: one slot per (b, h, segment) even without segments
+size_t prefill_grouped256_workspace_bytes(int BH, int d, int nseg) {
+  return (size_t)BH * nseg * ((size_t)d * d + d) * sizeof(float) + (size_t)BH * HALO * d * sizeof(uint16_t);
+}
+
 // The group size only blocks the computation; the result does not depend on it (the in-group
 // part is the exact masked product).  A requested group of 128 tokens is walked as two steps of
 // 64: two 128-token row buffers do not fit in LDS, and larger groups only add in-group MFMA work
 // per token on this design.  Segment boundaries stay multiples of the requested size.
-// grouped: the three-branch form, whose groups are exactly 64 tokens (segments start on group
-// boundaries, so the first pass and the prefix sum are the same for both forms).
+// grouped: the three-branch form, whose groups are exactly `chunk` tokens, 64 or 256 (segments start on
+// group boundaries, so the first pass and the prefix sum are the same for both forms; groups of 256 have a
+// kernel of their own for the full pass).
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st) {
-  (void)chunk;
   const int BH = a.B * a.H * a.m;             // heads the kernels see: one per value block
   hipError_t e;
   if (a.nseg > 1) {
@@ -75,6 +92,7 @@ hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grou
     else hipLaunchKernelGGL((segment_scan_kernel<64>), grid, dim3(256), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
+  if (grouped && chunk == 256) return launch_prefill_grouped256(a, d, st);
   return launch_prefill_mfma_ws(a, d, false, grouped, st);
 }
 

@@ -885,18 +885,24 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       for (int r = 0; r < 16; ++r) a.z_out[(size_t)bh * D + 32 * w + 8 * (r >> 2) + 4 * hi + (r & 3)] = Zacc[r];
     }
     if (a.hist_out && tid < D) {
-      // last Kc-1 value rows of (history ++ sequence); one thread per channel, rows in ascending order,
-      // so an aliased hist_in is read before it is overwritten (with segments the staged copy is read)
+      // last Kc-1 value rows of (history ++ sequence); one thread per channel reads all its rows before it
+      // writes any, so an aliased hist_in is read before it is overwritten (with segments the staged copy is read)
       const uint16_t* hin = static_cast<const uint16_t*>(a.hist_in);
       uint16_t* hout = static_cast<uint16_t*>(a.hist_out) + hist_base;
-      for (int r = 0; r < a.Kc - 1; ++r) {
+      uint16_t hrow[HALO];                                 // all rows requested before the first one is stored
+#pragma unroll
+      for (int r = 0; r < HALO; ++r) {
         const int tok = a.L - (a.Kc - 1) + r;
-        uint16_t x = 0;
-        if (tok >= 0) x = gv[(int64_t)tok * a.st_v + tid];
-        else if (hin) x = a.nseg > 1 ? staged_hist[(size_t)(HALO + tok) * D + tid]
-                                     : hin[hist_base + (int64_t)(a.Kc - 1 + tok) * DVT + tid];
-        hout[(size_t)r * DVT + tid] = x;
+        hrow[r] = 0;
+        if (r < a.Kc - 1) {
+          if (tok >= 0) hrow[r] = gv[(int64_t)tok * a.st_v + tid];
+          else if (hin) hrow[r] = a.nseg > 1 ? staged_hist[(size_t)(HALO + tok) * D + tid]
+                                             : hin[hist_base + (int64_t)(a.Kc - 1 + tok) * DVT + tid];
+        }
       }
+#pragma unroll
+      for (int r = 0; r < HALO; ++r)
+        if (r < a.Kc - 1) hout[(size_t)r * DVT + tid] = hrow[r];
     }
   }
 }

@@ -101,6 +101,48 @@ def test_three_branch_form_in_groups_of_256(io, d, L, Kc, with_state):
     compare(run(q, k, v, w, state, io, 256, 1e-3, alpha=0.7), want, io, f"groups of 256, L={L} Kc={Kc}")
 
 
+@pytest.mark.parametrize("B,H,L,d,Kc,with_state", [(10, 10, 1100, 128, 5, True),     # 100 heads: two segments of 3 and 2 groups
+                                                    (8, 32, 600, 128, 3, True),      # 256 heads: no segments, 3 groups each
+                                                    (8, 32, 300, 64, 8, False),
+                                                    (1, 3, 2100, 64, 2, True)])      # 9 segments of one group
+def test_three_branch_form_in_groups_of_256_launch_plans(B, H, L, d, Kc, with_state):
+    """bf16 rows on the matrix cores: every way the sequence can be laid out on the chip (segments of several groups,
+    of one group, none at all), with the state handed back after the last token."""
+    q, k, v, w, state = small_case(7450 + B + L, B, H, L, d, Kc, "bf16", with_state)
+    args = {} if state is None else dict(S0=state[0], z0=state[1], hist0=state[2])
+    want = oracle.prefill_grouped(q, k, v, w, 256, alpha=1.0, eps=1e-3, **args)
+    compare(run(q, k, v, w, state, "bf16", 256, 1e-3, alpha=1.0), want, "bf16", f"B{B} H{H} L{L} d{d}")
+
+
+def test_three_branch_form_in_groups_of_256_details():
+    """Nothing before the first group and eps = 0 (the linear branch is absent there, no division by zero reaches
+    the output); the other feature map; token-major tensors; peaked softmax weights; no leak from later tokens."""
+    io, dt, d = "bf16", torch.bfloat16, 128
+    q, k, v, w, _ = small_case(7460, 1, 4, 700, d, 3, io, False)
+    want = oracle.prefill_grouped(q, k, v, w, 256, alpha=1.0, eps=0.0)
+    base = run(q, k, v, w, None, io, 256, 0.0, alpha=1.0)
+    compare(base, want, io, "eps = 0")
+    with oracle.feature_map("relu"):
+        want = oracle.prefill_grouped(q, k, v, w, 256, alpha=0.5, eps=0.05)
+    out, (S, z, h) = binding.prefill(dev(q, dt), dev(k, dt), dev(v, dt), dev(w), None, 256, 0.05, phi="relu", grouped_alpha=0.5)
+    torch.cuda.synchronize()
+    compare((host(out), host(S), host(z), host(h)), want, io, "relu")
+    tq, tk, tv = (dev(np.ascontiguousarray(a.transpose(0, 2, 1, 3)), dt).transpose(1, 2) for a in (q, k, v))
+    out, (S, z, h) = binding.prefill(tq, tk, tv, dev(w), None, 256, 0.0, grouped_alpha=1.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out), base[0]), "token-major layout"
+    q3, k3, v3, w3, _ = small_case(7461, 2, 2, 500, d, 3, io, False, scale=2.5)        # logits in the tens
+    want = oracle.prefill_grouped(q3, k3, v3, w3, 256, alpha=0.0)
+    compare(run(q3, k3, v3, w3, None, io, 256, alpha=0.0), want, io, "peaked weights")
+    rng = np.random.default_rng(7462)
+    for t in (0, 100, 255, 256, 600):
+        q2, k2, v2 = q.copy(), k.copy(), v.copy()
+        for a in (q2, k2, v2):
+            a[:, :, t + 1:] = workloads.round_to_io(a[:, :, t + 1:] + 4.0 * rng.standard_normal(a[:, :, t + 1:].shape), io)
+        got = run(q2, k2, v2, w, None, io, 256, 0.0, alpha=1.0)[0]
+        assert np.array_equal(got[:, :, :t + 1], base[0][:, :, :t + 1]), f"leak into tokens <= {t}"
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_three_branch_form_in_groups_of_64_with_63_taps(d):
     """The matrix-core kernel of the three-branch form followed by the long convolution."""
