@@ -264,9 +264,10 @@ linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* 
   const int nsplit = verify_pick_split(desc->B * desc->H * m);
   const bool bf16 = desc->io_dtype == LINATTN_BF16;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  // value rows wider than key rows: the streaming kernel, whose workgroups own column slices of a head's state
-  const hipError_t e = (m == 1 && verify_mfma_available(bf16, desc->d, nsplit, kk)) ? launch_verify_mfma(a, desc->d, stream)
-                                                                                    : launch_verify(a, bf16, desc->d, nsplit, stream);
+  // whole blocks of d value channels per workgroup on the matrix cores when there are enough of them to fill the
+  // chip (B H m >= 768), column slices of a head's state on the streaming kernel otherwise
+  const hipError_t e = verify_mfma_available(bf16, desc->d, nsplit, kk) ? launch_verify_mfma(a, desc->d, stream)
+                                                                        : launch_verify(a, bf16, desc->d, nsplit, stream);
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 

@@ -115,6 +115,7 @@ struct ConvLongArgs {
 // verify.hip
 int verify_pick_split(int BH);
 hipError_t launch_verify(const VerifyArgs& a, bool bf16, int d, int nsplit, hipStream_t st);
+hipError_t launch_verify_z(const VerifyArgs& a, bool bf16, int d, hipStream_t st);   // z += accepted phi(k), all heads
 
 // verify_mfma.hip : the same step as one 16-token group on the matrix cores (bf16 drafts, whole heads)
 bool verify_mfma_available(bool bf16, int d, int nsplit, int kk);

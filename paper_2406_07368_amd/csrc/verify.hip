@@ -283,6 +283,20 @@ __global__ __launch_bounds__(256) void verify_z_kernel(VerifyArgs a) {
   a.z[gid] = zs;
 }
 
+// z += sum of the accepted phi(k_j) for every head, as a launch of its own (fp32 sums of fp32 feature maps).
+hipError_t launch_verify_z(const VerifyArgs& a, bool bf16, int d, hipStream_t st) {
+  const int total = a.B * a.H * d;
+  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (bf16) {
+    if (d == 128) hipLaunchKernelGGL((verify_z_kernel<IoBf16, 128>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((verify_z_kernel<IoBf16, 64>), grid, block, 0, st, a);
+  } else {
+    if (d == 128) hipLaunchKernelGGL((verify_z_kernel<IoF32, 128>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((verify_z_kernel<IoF32, 64>), grid, block, 0, st, a);
+  }
+  return hipGetLastError();
+}
+
 template <typename Io, int D, int CW>
 static hipError_t launch_kp(const VerifyArgs& a, hipStream_t st) {
   const dim3 grid((unsigned)(a.B * a.H * (a.dv / CW))), block(256);

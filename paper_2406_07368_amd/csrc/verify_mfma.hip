@@ -63,20 +63,25 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
-  const int bh = blockIdx.x;
+  // Value rows of DV = a.dv = m D elements: one workgroup per (b, h, block of D value channels).  The blocks of a head
+  // share q, k and z (each computes the feature maps and scores for itself: the matrix cores are idle most of the
+  // step) and own their channels of v, out, hist, conv_w and of the rows of S.  DV == D: one block per head.
+  const int DV = a.dv, nblk = DV / D;
+  const int bh = blockIdx.x / nblk, blk = blockIdx.x % nblk;
   const int b = bh / a.H, h = bh % a.H;
   const int kk = a.kk, Kc = a.Kc;
   const int cw = 32 * w + l32;               // the channel this lane owns in the state tiles
 
   // ---- the drafts and the other small inputs are requested first, then the state ---------------
-  const int64_t tok0 = (int64_t)bh * kk * D;
-  const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
+  const int64_t tok0 = (int64_t)bh * kk * D;                                    // q, k
+  const int64_t vtok0 = (int64_t)bh * kk * DV + (int64_t)blk * D;               // v, out: rows of DV elements
+  const int64_t hist0 = (int64_t)bh * (Kc - 1) * DV + (int64_t)blk * D;
   const int dj = tid / (D / 8), di0 = 8 * (tid % (D / 8));   // one 8-element piece of q, k, v per thread
   u32x4 rq = {0, 0, 0, 0}, rk = {0, 0, 0, 0}, rv = {0, 0, 0, 0};
   if (dj < kk) {
     rq = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.q) + tok0 + (int64_t)dj * D + di0);
     rk = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.k) + tok0 + (int64_t)dj * D + di0);
-    rv = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.v) + tok0 + (int64_t)dj * D + di0);
+    rv = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.v) + vtok0 + (int64_t)dj * DV + di0);
   }
   // taps, history and z: channel tid % D; the lower D threads take the taps and z, the upper D the history
   const int cc = tid % D, upper = tid / D;
@@ -85,12 +90,12 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
   if (!upper) {
     zreg = a.z[(size_t)bh * D + cc];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) aux[t] = t < Kc ? __float_as_uint(a.conv_w[((size_t)h * D + cc) * Kc + t]) : 0u;
+    for (int t = 0; t < 8; ++t) aux[t] = t < Kc ? __float_as_uint(a.conv_w[((size_t)h * DV + blk * D + cc) * Kc + t]) : 0u;
   } else {
 #pragma unroll
     for (int r = 0; r < HALO; ++r) {          // LDS row r holds the value row HALO - r positions before the drafts
       const int back = HALO - r;              // 1 .. HALO
-      aux[r] = back <= Kc - 1 ? static_cast<const uint16_t*>(a.hist)[hist0 + (int64_t)(Kc - 1 - back) * D + cc] : 0u;
+      aux[r] = back <= Kc - 1 ? static_cast<const uint16_t*>(a.hist)[hist0 + (int64_t)(Kc - 1 - back) * DV + cc] : 0u;
     }
   }
   int n = kk;
@@ -102,15 +107,16 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
   // The state is touched once per step: the requests carry the nontemporal policy (last argument 2),
   // which on this chip is worth 13 % of the step time.
   const __amdgpu_buffer_rsrc_t Srs =
-      __builtin_amdgcn_make_buffer_rsrc(a.S + (size_t)bh * D * D, 0, D * D * 4, 0x00020000);
-  const int so = (4 * hi * D + cw) * 4;
+      __builtin_amdgcn_make_buffer_rsrc(a.S + (size_t)bh * D * DV + (size_t)blk * D, 0, (D * DV - blk * D) * 4, 0x00020000);
+  const int row_bytes = DV * 4;              // D * 4 when the value rows are as wide as the key rows: a constant then
+  const int so = 4 * hi * row_bytes + cw * 4;
   f32x16 Sacc[G::IB];
 #pragma unroll
   for (int ib = 0; ib < G::IB; ++ib)
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       Sacc[ib][r] = __builtin_bit_cast(
-          float, __builtin_amdgcn_raw_buffer_load_b32(Srs, so, (32 * ib + 8 * (r >> 2) + (r & 3)) * (D * 4), 2));
+          float, __builtin_amdgcn_raw_buffer_load_b32(Srs, so, (32 * ib + 8 * (r >> 2) + (r & 3)) * row_bytes, 2));
 
   // ---- drafts -> LDS: phi(Q), phi(K) as bf16 rows (rows >= kk are zero rows), V, history, z, taps --
   {
@@ -227,7 +233,7 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(Sacc[ib][r]), Srs, so,
-                                              (32 * ib + 8 * (r >> 2) + (r & 3)) * (D * 4), 2);
+                                              (32 * ib + 8 * (r >> 2) + (r & 3)) * row_bytes, 2);
     }
   }
 
@@ -236,7 +242,7 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
     const float inv = __builtin_amdgcn_rcpf(a.eps + dq + rs);
     const uint16_t* vrow = sm.v + (HALO + l32) * G::VS + 32 * w + 4 * hi;
     const float* wrow = sm.w + 32 * w + 4 * hi;
-    uint16_t* orow = static_cast<uint16_t*>(a.out) + tok0 + (int64_t)l32 * D + 32 * w + 4 * hi;
+    uint16_t* orow = static_cast<uint16_t*>(a.out) + vtok0 + (int64_t)l32 * DV + 32 * w + 4 * hi;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       float u[4] = {0.f, 0.f, 0.f, 0.f};
@@ -257,12 +263,14 @@ __global__ __launch_bounds__(D * 2, 4) void verify_mfma_kernel(VerifyArgs a) {
   // ---- the rest of the state: normaliser and history ----------------------------------------------
   if (n == 0) return;   // uniform per workgroup: nothing accepted, state untouched
   if (tid < D) {
-    float zs = zreg;
-    for (int j = 0; j < n; ++j) zs += bf16_bits_to_f32(sm.k[j * G::KS + tid]) + bf16_bits_to_f32(sm.klo[j * G::KS + tid]);
-    a.z[(size_t)bh * D + tid] = zs;
+    if (nblk == 1) {                         // several blocks per head all read the old z: a launch of its own updates it
+      float zs = zreg;
+      for (int j = 0; j < n; ++j) zs += bf16_bits_to_f32(sm.k[j * G::KS + tid]) + bf16_bits_to_f32(sm.klo[j * G::KS + tid]);
+      a.z[(size_t)bh * D + tid] = zs;
+    }
     // the last Kc-1 rows of (history ++ accepted drafts); all of them are rows of the LDS copy
     for (int r = 0; r < Kc - 1; ++r)
-      static_cast<uint16_t*>(a.hist)[hist0 + (int64_t)r * D + tid] = sm.v[(HALO + n - (Kc - 1) + r) * G::VS + tid];
+      static_cast<uint16_t*>(a.hist)[hist0 + (int64_t)r * DV + tid] = sm.v[(HALO + n - (Kc - 1) + r) * G::VS + tid];
   }
 }
 
@@ -271,10 +279,12 @@ bool verify_mfma_available(bool bf16, int d, int nsplit, int kk) {
 }
 
 hipError_t launch_verify_mfma(const VerifyArgs& a, int d, hipStream_t st) {
-  const dim3 grid((unsigned)(a.B * a.H));
+  const dim3 grid((unsigned)(a.B * a.H * (a.dv / d)));
   if (d == 128) hipLaunchKernelGGL((verify_mfma_kernel<128>), grid, dim3(256), 0, st, a);
   else hipLaunchKernelGGL((verify_mfma_kernel<64>), grid, dim3(128), 0, st, a);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && a.dv != d) e = launch_verify_z(a, true, d, st);   // z of a head with several value blocks
+  return e;
 }
 
 }  // namespace linattn
