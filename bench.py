@@ -102,8 +102,15 @@ def layouts(wl):
             "bhld": ((B, H, L, d), (H * L * d, L * d, d))}
 
 
+# rocprofv3 counter summaries of the prefill workloads (all launches of one call summed)
+TRAFFIC_FILES = {"cfg3_llama7b_prefill": "prefill_mfma_cfg3_pmc.txt", "cfg5_long_context": "prefill_cfg5_pmc.txt",
+                 "cfg2_gpt2_small": "prefill_cfg2_pmc.txt"}
+
+
 def read_traffic(name):
     """HBM bytes per launch measured with rocprofv3 counters, if a summary is committed under profiles/."""
+    if not name:
+        return None
     path = os.path.join(ROOT, "profiles", name)
     try:
         m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
@@ -422,7 +429,8 @@ def main():
                           "ms": {"mean": t_mean, "median": float(np.median(t_ms)), "min": min(t_ms)},
                           "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3), "workspace_bytes": sws_bytes,
                           "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                       "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
+                                       "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb,
+                                       "traffic_from_profiles": read_traffic(TRAFFIC_FILES.get(name, ""))}}
             del sets, sws, sS, sz, sh
         torch.cuda.empty_cache()
 
@@ -431,7 +439,8 @@ def main():
         # next row of the scope (not part of the step): the sizes of the paper's FLASH experiment -- 63-tap masked
         # DWConv, groups of 256 tokens, batch 1, 1K / 4K / 8K tokens, as eight heads of 128.  Token-level form
         # (matrix-core attention kernel + the long-convolution pass) and the three-branch form in groups of 256
-        # (the plain fp32 kernel: one workgroup per head, token by token -- correct, not fast).
+        # (its own matrix-core kernel + the same long-convolution pass).  Eight heads cannot fill the chip: these
+        # are latency figures, a few launches of some tens of microseconds each.
         flash = {}
         for name in ("flash_L1024", "flash_L4096", "flash_L8192"):
             wl = workloads.CONFIGS[name]
@@ -449,7 +458,7 @@ def main():
             row = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d{wl.d} bf16, groups of {wl.chunk}, Kc{wl.conv_k}, head-major"}
             for key, n_warm, n_timed, call in (
                     ("token_level", 10, 30, lambda: binding.linattn_prefill(fdesc, wl.L, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream)),
-                    ("three_branch", 1, 3, lambda: binding.linattn_prefill_grouped(fdesc, wl.L, 1.0, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream))):
+                    ("three_branch", 10, 30, lambda: binding.linattn_prefill_grouped(fdesc, wl.L, 1.0, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream))):
                 evs = []
                 for i in range(n_warm + n_timed):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -571,7 +580,7 @@ def main():
             result["prefill_grouped"] = grouped
         result["roofline"] = {"bound": "hbm", "achieved": nbytes / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": nbytes / t / 1e9 / HBM_PEAK_GBS,
-                              "traffic_from_profiles": read_traffic("prefill_mfma_cfg3_pmc.txt") if pw.name.startswith("cfg3") and not args.length else None,
+                              "traffic_from_profiles": read_traffic(TRAFFIC_FILES.get(pw.name, "")) if not args.length else None,
                               "kernel": "prefill_mfma_ws_kernel (+ state-only pass and scan when the sequence is segmented)",
                               "algorithmic_bytes": nbytes, "workspace_bytes": ws_bytes}
         result["mfma"] = {"tflops_causal": fc / t / 1e12, "tflops_dense_tiles": fd / t / 1e12,

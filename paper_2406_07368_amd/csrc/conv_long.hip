@@ -23,6 +23,9 @@ constexpr int CL_BLK = 8;         // outputs a thread carries at once
 // KMAX: tap capacity of the instantiation (taps beyond Kc are zeros; the loops below are straight-line code for
 // exactly KMAX taps: a branch per tap would put every LDS read into a basic block of its own, with a full wait
 // behind it).
+static __device__ __forceinline__ float elem_to_f32(float x) { return x; }
+static __device__ __forceinline__ float elem_to_f32(uint16_t x) { return bf16_bits_to_f32(x); }
+
 template <typename Io, int D, int KMAX>
 __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   extern __shared__ float xs[];   // [CL_HALO + CL_TOK][D]
@@ -42,34 +45,13 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   // the block are contiguous in memory: they come in through LDS with whole-row requests (a thread reading its own
   // Kc consecutive floats would touch 64 cache lines per request), then each thread picks its own (stride Kc floats
   // between lanes; Kc odd or not, at most a 2-way bank conflict, once per workgroup).
-  float wreg[KMAX];
-  {
-    // (16 bytes per request, every request of the thread issued before the first value is stored)
-    const f32x4* wsrc = reinterpret_cast<const f32x4*>(a.conv_w + ((size_t)h * DVT + blk * D) * Kc);
-    constexpr int WIT = (D * KMAX / 4 + 255) / 256;
-    f32x4 wt[WIT];
-#pragma unroll
-    for (int i = 0; i < WIT; ++i) {
-      const int e = tid + 256 * i;
-      wt[i] = wsrc[e < D * Kc / 4 ? e : D * Kc / 4 - 1];   // unconditional: a branch would end in a full wait
-    }
-#pragma unroll
-    for (int i = 0; i < WIT; ++i) {
-      const int e = tid + 256 * i;
-      if (e < D * Kc / 4) *reinterpret_cast<f32x4*>(xs + 4 * e) = wt[i];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < KMAX; ++j) wreg[j] = j < Kc ? xs[c * Kc + j] : 0.f;
-    __syncthreads();                          // the staging area is about to take the value rows
-  }
-
-  // rows t0 - 62 .. t0 + 63: the sequence, before it the incoming history, before that (and past the end) zeros
-  // (again every request first, then the stores)
-  {
-    constexpr int RIT = ((CL_HALO + CL_TOK) * (D / 8) + 255) / 256;
-    typename Io::raw8 raw[RIT];
-    bool have[RIT];
+  // Every request of the workgroup -- taps, value rows, the 32 elements of out that the thread adds to -- is issued
+  // before the first wait: one trip to memory per workgroup instead of one per stage.
+  constexpr int RIT = ((CL_HALO + CL_TOK) * (D / 8) + 255) / 256;
+  typename Io::raw8 raw[RIT];
+  bool have[RIT];
+  auto issue_rows = [&]() __attribute__((always_inline)) {
+    // rows t0 - 62 .. t0 + 63: the sequence, before it the incoming history, before that (and past the end) zeros
 #pragma unroll
     for (int i = 0; i < RIT; ++i) {
       const int e = tid + 256 * i;
@@ -84,6 +66,42 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       raw[i] = Io::load_raw8(src, idx);
       have[i] = in_seq || in_hist;
     }
+  };
+  // what the attention kernels left in out for this thread's tokens, as it lies in memory (converted where it is
+  // added to); past the end: the last token's element, never stored
+  typename Io::elem prev[TPT];
+  auto issue_prev = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int e = 0; e < TPT; ++e) {
+      const int tok = t0 + tg * TPT + e;
+      prev[e] = static_cast<const typename Io::elem*>(a.out)[base + (int64_t)(tok < L ? tok : L - 1) * a.st + c];
+    }
+  };
+  float wreg[KMAX];
+  {
+    // (16 bytes per request, every request of the thread issued before the first value is stored)
+    const f32x4* wsrc = reinterpret_cast<const f32x4*>(a.conv_w + ((size_t)h * DVT + blk * D) * Kc);
+    constexpr int WIT = (D * KMAX / 4 + 255) / 256;
+    f32x4 wt[WIT];
+#pragma unroll
+    for (int i = 0; i < WIT; ++i) {
+      const int e = tid + 256 * i;
+      wt[i] = wsrc[e < D * Kc / 4 ? e : D * Kc / 4 - 1];   // unconditional: a branch would end in a full wait
+    }
+    issue_rows();                             // the value rows and what is already in out are on their way
+    issue_prev();                             // while the taps make their trip through LDS
+#pragma unroll
+    for (int i = 0; i < WIT; ++i) {
+      const int e = tid + 256 * i;
+      if (e < D * Kc / 4) *reinterpret_cast<f32x4*>(xs + 4 * e) = wt[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) wreg[j] = j < Kc ? xs[c * Kc + j] : 0.f;
+    __syncthreads();                          // the staging area is about to take the value rows
+  }
+
+  {
 #pragma unroll
     for (int i = 0; i < RIT; ++i) {
       const int e = tid + 256 * i;
@@ -98,17 +116,13 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   }
   __syncthreads();
 
-  for (int tb0 = tg * TPT; tb0 < (tg + 1) * TPT; tb0 += CL_BLK) {
-    if (t0 + tb0 >= L) break;                 // uniform per wave: D >= 64 channels share tb0
-    // what the attention kernels left in out for these 8 tokens: requested now, needed after the 500 multiply-adds
-    // (read and written back one by one, each token would pay a round trip to memory of its own)
-    float acc[CL_BLK], prev[CL_BLK];
+  // (one copy of the 500 multiply-adds in the instruction stream: the loop over the thread's blocks stays a loop)
+#pragma unroll 1
+  for (int blk8 = 0; blk8 < TPT / CL_BLK; ++blk8) {
+    const int tb0 = tg * TPT + blk8 * CL_BLK;
+    float acc[CL_BLK];
 #pragma unroll
-    for (int e = 0; e < CL_BLK; ++e) {
-      acc[e] = 0.f;
-      const int tok = t0 + tb0 + e;                       // past the end: the last token's element, never stored
-      prev[e] = Io::load1(a.out, base + (int64_t)(tok < L ? tok : L - 1) * a.st + c);
-    }
+    for (int e = 0; e < CL_BLK; ++e) acc[e] = 0.f;
     // value rows from the newest output's own row backwards: row m feeds output e through tap e - 7 + m
     const float* newest = xs + (CL_HALO + tb0 + CL_BLK - 1) * D + c;
     // (fully unrolled, so that every tap index is a constant and the taps stay in registers)
@@ -125,8 +139,11 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
 #pragma unroll
     for (int e = 0; e < CL_BLK; ++e) {
       const int tok = t0 + tb0 + e;
-      if (tok < L) Io::store1(a.out, base + (int64_t)tok * a.st + c, prev[e] + acc[e]);
+      if (tok < L) Io::store1(a.out, base + (int64_t)tok * a.st + c, elem_to_f32(prev[e]) + acc[e]);
     }
+    // the next block's elements move to the front (constant register indices in a loop that is not unrolled)
+#pragma unroll
+    for (int e = 0; e + CL_BLK < TPT; ++e) prev[e] = prev[e + CL_BLK];
   }
 }
 
@@ -140,25 +157,37 @@ __global__ __launch_bounds__(256) void conv_long_hist_kernel(ConvLongArgs a) {
   const int R = a.Kc - 1, DVT = a.m * D;
   const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh + (int64_t)blk * D;
   const int64_t hist_base = (int64_t)bh * R * DVT + (int64_t)blk * D;
-  constexpr int EIT = (CL_HALO * D + 255) / 256;
-  float x[EIT];
+  // whole vectors of 8 channels, as they lie in memory (history and value rows share their element type); every
+  // request is unconditional -- a vector that does not exist reads the first one of hist_out instead and is
+  // replaced by zeros -- so that all of them are in flight together
+  using raw8 = typename Io::raw8;
+  using elem = typename Io::elem;
+  constexpr int VPR = D / 8;
+  constexpr int EIT = (CL_HALO * VPR + 255) / 256;
+  raw8 x[EIT];
+  bool have[EIT];
 #pragma unroll
   for (int i = 0; i < EIT; ++i) {
     const int el = tid + 256 * i;
-    const int r = el / D, c = el % D;
+    const int r = el / VPR, c = 8 * (el % VPR);
     const int e = a.L + r;                    // row of (history ++ sequence), the history being rows 0 .. R-1
-    x[i] = 0.f;
-    if (r < R) {
-      if (e >= R) x[i] = Io::load1(a.v, base + (int64_t)(e - R) * a.st + c);
-      else if (a.hist_in) x[i] = Io::load1(a.hist_in, hist_base + (int64_t)e * DVT + c);
-    }
+    const bool from_v = r < R && e >= R;
+    const bool from_h = r < R && e < R && a.hist_in != nullptr;
+    const void* src = from_v ? a.v : from_h ? a.hist_in : a.hist_out;
+    const int64_t idx = from_v ? base + (int64_t)(e - R) * a.st + c : from_h ? hist_base + (int64_t)e * DVT + c : hist_base;
+    x[i] = Io::load_raw8(src, idx);
+    have[i] = from_v || from_h;
   }
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < EIT; ++i) {
     const int el = tid + 256 * i;
-    const int r = el / D, c = el % D;
-    if (r < R) Io::store1(a.hist_out, hist_base + (int64_t)r * DVT + c, x[i]);
+    const int r = el / VPR, c = 8 * (el % VPR);
+    if (r < R) {
+      raw8 y = x[i];
+      if (!have[i]) y = raw8{};
+      *reinterpret_cast<raw8*>(static_cast<elem*>(a.hist_out) + hist_base + (int64_t)r * DVT + c) = y;
+    }
   }
 }
 
