@@ -547,6 +547,29 @@ def main():
             del wstates
         torch.cuda.empty_cache()
 
+    copy_ref = None
+    if args.only == "all":
+        # for reference (not a kernel of the library): what a plain elementwise kernel reaches on this GPU, reading
+        # 1 GiB and writing 1 GiB per launch over rotating buffers -- the practical ceiling under the published peak
+        with torch.cuda.stream(stream):
+            bufs = [torch.zeros(1 << 28, dtype=torch.float32, device=dev) for _ in range(4)]
+            evs = []
+            for i in range(5 + 20):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                torch.add(bufs[i % 4], 1.0, out=bufs[(i + 1) % 4])
+                e1.record(stream)
+                if i >= 5:
+                    evs.append((e0, e1))
+        stream.synchronize()
+        t_ms = [a.elapsed_time(b) for a, b in evs]
+        t_mean = sum(t_ms) / len(t_ms)
+        copy_ref = {"kernel": "torch.add(x, 1, out=y), 1 GiB read + 1 GiB written per launch", "ms": {"mean": t_mean, "min": min(t_ms)},
+                    "achieved": 2 * (1 << 30) / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": 2 * (1 << 30) / t_mean / 1e6 / HBM_PEAK_GBS}
+        del bufs
+        torch.cuda.empty_cache()
+
     timed_ms = {n: [a.elapsed_time(b) for a, b in lst[n_settled[n]:]] for n, lst in ev.items() if len(lst) > n_settled[n]}
     mean_ms = {n: sum(t) / len(t) for n, t in timed_ms.items()}
     min_ms = {n: min(t) for n, t in timed_ms.items()}
@@ -614,6 +637,8 @@ def main():
         result["flash_shape"] = flash
     if wide:
         result["wide_values"] = wide
+    if copy_ref:
+        result["hbm_copy_reference"] = copy_ref
     if not args.no_cpu_baseline and do_prefill:
         result["cpu_baseline"] = cpu_baseline(pw, args.cpu_seconds)
     print(json.dumps(result))

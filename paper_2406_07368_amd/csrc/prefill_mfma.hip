@@ -27,9 +27,21 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(PrefillArgs a) {
     if (a.S_in) run = e < D * D ? a.S_in[(size_t)bh * D * hx.dvt + (size_t)(e / D) * hx.dvt + hx.blk * D + e % D]
                                 : a.z_in[(size_t)bh * D + (e - D * D)];
     ws_bh[e] = run;
-    for (int g = 1; g < a.nseg; ++g) {
-      run += ws_bh[(size_t)g * SLOT + e];
-      ws_bh[(size_t)g * SLOT + e] = run;
+    // sixteen segments at a time: all their increments are requested before the first is added (read, add and
+    // write back one by one, every segment would pay a trip to memory of its own: the compiler may not move a
+    // load across the store before it)
+    for (int g0 = 1; g0 < a.nseg; g0 += 16) {
+      float inc[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int g = g0 + i < a.nseg ? g0 + i : a.nseg - 1;   // past the end: the last one again, not used
+        inc[i] = ws_bh[(size_t)g * SLOT + e];
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        run += inc[i];
+        if (g0 + i < a.nseg) ws_bh[(size_t)(g0 + i) * SLOT + e] = run;
+      }
     }
   }
   if (a.hist_in && e < HALO * D) {
