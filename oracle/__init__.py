@@ -57,6 +57,8 @@ def _declare(lib):
         fn.argtypes = [i, i, i, i, i, f] + [_dp] * 11
     lib.oracle_prefill_grouped.restype = i
     lib.oracle_prefill_grouped.argtypes = [i, i, i, i, i, i, f, f] + [_dp] * 11
+    lib.oracle_prefill_grouped_backward.restype = i
+    lib.oracle_prefill_grouped_backward.argtypes = [i, i, i, i, i, i, f, f] + [_dp] * 17
     lib.oracle_verify_grouped.restype = i
     lib.oracle_verify_grouped.argtypes = [i, i, i, i, i, i, f, f] + [_dp] * 9 + [_ip, _ip, _dp]
     lib.oracle_verify.restype = i
@@ -219,6 +221,37 @@ def prefill_grouped(q, k, v, w, group, alpha=1.0, S0=None, z0=None, hist0=None, 
     if rc != 0:
         raise ValueError(f"oracle_prefill_grouped rejected its arguments (code {rc})")
     return out, S1, z1, h1
+
+
+def prefill_grouped_backward(q, k, v, w, dout, group, alpha=1.0, S0=None, z0=None, hist0=None, dS1=None, dz1=None,
+                             eps=0.0, lib=None):
+    """Gradient of the three-branch form (the training direction of Sec. 5.3): for the loss
+    sum(dout * out) + sum(dS1 * S1) + sum(dz1 * z1) of ``prefill_grouped`` with the same arguments, the derivatives with
+    respect to q, k, v, the conv weights (summed over the batch), the incoming state and the incoming history.
+    Returns a dict with dq, dk, dv, dw, dS0, dz0, dhist0."""
+    lib = lib or _load()
+    q = _c(q)
+    B, H, L, d = q.shape
+    k = _c(k, q.shape)
+    v = _c(v, q.shape)
+    dout = _c(dout, q.shape)
+    w = _c(w)
+    Kc = w.shape[2]
+    w = _c(w, (H, d, Kc))
+    S0 = _c(S0, (B, H, d, d)) if S0 is not None else None
+    z0 = _c(z0, (B, H, d)) if z0 is not None else None
+    hist0 = _c(hist0, (B, H, Kc - 1, d)) if hist0 is not None else None
+    dS1 = _c(dS1, (B, H, d, d)) if dS1 is not None else None
+    dz1 = _c(dz1, (B, H, d)) if dz1 is not None else None
+    r = {"dq": np.empty_like(q), "dk": np.empty_like(q), "dv": np.empty_like(q), "dw": np.empty((H, d, Kc)),
+         "dS0": np.empty((B, H, d, d)), "dz0": np.empty((B, H, d)), "dhist0": np.empty((B, H, Kc - 1, d))}
+    rc = lib.oracle_prefill_grouped_backward(B, H, L, d, Kc, int(group), float(eps), float(alpha), _p(q), _p(k), _p(v),
+                                             _p(w), _p(S0), _p(z0), _p(hist0), _p(dout), _p(dS1), _p(dz1), _p(r["dq"]),
+                                             _p(r["dk"]), _p(r["dv"]), _p(r["dw"]), _p(r["dS0"]), _p(r["dz0"]),
+                                             _p(r["dhist0"]))
+    if rc != 0:
+        raise ValueError(f"oracle_prefill_grouped_backward rejected its arguments (code {rc})")
+    return r
 
 
 def verify(q, k, v, w, S, z, hist, n_commit=None, eps=0.0, lib=None):

@@ -361,6 +361,192 @@ int oracle_prefill_grouped(int B, int H, int L, int d, int Kc, int C, double eps
   return 0;
 }
 
+/* ---- gradient of the three-branch form, one head (training: Sec. 5.3 times a training
+ * step, forward and backward, of FLASH with this block in groups of 256) ----
+ * For a loss  Lo = sum_{t,c} dout[t][c] * out[t][c] + sum dS1 * S1 + sum dz1 * z1  the
+ * derivatives with respect to every input of grouped_head, by the chain rule through
+ * that function's own steps taken in reverse.  With P_g = (S, z) before group g:
+ *   P_{g+1} = P_g + sum_{t in g} (phi(k_t) v_t^T, phi(k_t)), so the gradient D_g with respect
+ *   to P_g is D_{g+1} plus what the queries of group g contribute;
+ *   grouped branch of token t (group g):  G = alpha * N / D,  N = S^T phi(q_t),  D = phi(q_t).z + eps
+ *       dN = alpha * dout_t / D,   dD = -alpha * (N . dout_t) / D^2,
+ *       d phi(q_t) = S dN + z dD,   dS += phi(q_t) dN^T,   dz += phi(q_t) dD;
+ *   local branch:  A = sum_i p_i v_i,  p = softmax(l),  l_i = q_t.k_i / sqrt(d):
+ *       dv_i += p_i dout_t,   dp_i = dout_t . v_i,   dl_i = p_i (dp_i - sum_j p_j dp_j),
+ *       dq_t += sum_i dl_i k_i / sqrt(d),   dk_i += dl_i q_t / sqrt(d);
+ *   a token i of group g entered P_{g+1}:  d phi(k_i) = D_{g+1}.S v_i + D_{g+1}.z,
+ *       dv_i += D_{g+1}.S^T phi(k_i);
+ *   phi'(x) = 1 for x > 0, else exp(x)  (ReLU map: 1 for x > 0, else 0);
+ *   conv:  out[t][c] has the term w[c][j] * vext[t-j][c].
+ * dq, dk, dv are written; dw (this head's [d][Kc]) is ADDED to (the weights are shared
+ * by the batch rows); dS0, dz0, dhist0 may be NULL (not wanted). */
+static double dphi(double x) {
+  if (g_feature_map == 1) return x > 0.0 ? 1.0 : 0.0;
+  return x > 0.0 ? 1.0 : exp(x);
+}
+
+static void grouped_backward_head(int L, int d, int Kc, int C, double eps, double alpha,
+                                  const double *q, const double *k, const double *v,
+                                  const double *w, const double *S0, const double *z0,
+                                  const double *hist0, const double *dout,
+                                  const double *dS1, const double *dz1, double *dq,
+                                  double *dk, double *dv, double *dw, double *dS0,
+                                  double *dz0, double *dhist0) {
+  size_t nS = (size_t)d * d;
+  int ng = (L + C - 1) / C;
+  /* the sums as they stood before every group (and after the last one) */
+  double *Sg = (double *)calloc((size_t)(ng + 1) * nS, sizeof(double));
+  double *zg = (double *)calloc((size_t)(ng + 1) * d, sizeof(double));
+  if (S0) memcpy(Sg, S0, sizeof(double) * nS);
+  if (z0) memcpy(zg, z0, sizeof(double) * (size_t)d);
+  for (int g = 0; g < ng; ++g) {
+    double *Sn = Sg + (size_t)(g + 1) * nS, *zn = zg + (size_t)(g + 1) * d;
+    memcpy(Sn, Sg + (size_t)g * nS, sizeof(double) * nS);
+    memcpy(zn, zg + (size_t)g * d, sizeof(double) * (size_t)d);
+    int g0 = g * C, g1 = g0 + C < L ? g0 + C : L;
+    for (int t = g0; t < g1; ++t)
+      for (int i = 0; i < d; ++i) {
+        double fk = oracle_phi(k[(size_t)t * d + i]);
+        zn[i] += fk;
+        for (int c = 0; c < d; ++c) Sn[(size_t)i * d + c] += fk * v[(size_t)t * d + c];
+      }
+  }
+  double *DS = (double *)calloc(nS, sizeof(double));   /* gradient w.r.t. the sums after the current group */
+  double *DZ = (double *)calloc((size_t)d, sizeof(double));
+  double *gS = (double *)malloc(sizeof(double) * nS);  /* what the current group's queries add to it */
+  double *gz = (double *)malloc(sizeof(double) * (size_t)d);
+  double *fq = (double *)malloc(sizeof(double) * (size_t)d);
+  double *gnum = (double *)malloc(sizeof(double) * (size_t)d);
+  double *dnum = (double *)malloc(sizeof(double) * (size_t)d);
+  double *p = (double *)malloc(sizeof(double) * (size_t)(C > 0 ? C : 1));
+  double *dp = (double *)malloc(sizeof(double) * (size_t)(C > 0 ? C : 1));
+  if (dS1) memcpy(DS, dS1, sizeof(double) * nS);
+  if (dz1) memcpy(DZ, dz1, sizeof(double) * (size_t)d);
+  memset(dq, 0, sizeof(double) * (size_t)L * d);
+  memset(dk, 0, sizeof(double) * (size_t)L * d);
+  memset(dv, 0, sizeof(double) * (size_t)L * d);
+  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  for (int g = ng - 1; g >= 0; --g) {
+    int g0 = g * C, g1 = g0 + C < L ? g0 + C : L;
+    const double *S = Sg + (size_t)g * nS, *z = zg + (size_t)g * d;
+    /* the group's keys and values entered the sums that every later group read */
+    for (int t = g0; t < g1; ++t)
+      for (int i = 0; i < d; ++i) {
+        double kti = k[(size_t)t * d + i], fk = oracle_phi(kti);
+        double dfk = DZ[i];
+        for (int c = 0; c < d; ++c) {
+          dfk += DS[(size_t)i * d + c] * v[(size_t)t * d + c];
+          dv[(size_t)t * d + c] += fk * DS[(size_t)i * d + c];
+        }
+        dk[(size_t)t * d + i] += dfk * dphi(kti);
+      }
+    memset(gS, 0, sizeof(double) * nS);
+    memset(gz, 0, sizeof(double) * (size_t)d);
+    for (int t = g0; t < g1; ++t) {
+      const double *qt = q + (size_t)t * d, *dot_ = dout + (size_t)t * d;
+      /* grouped branch */
+      for (int i = 0; i < d; ++i) fq[i] = oracle_phi(qt[i]);
+      double gden = dot(fq, z, d) + eps;
+      if (gden != 0.0) {
+        double nd = 0.0;
+        for (int c = 0; c < d; ++c) {
+          double a = 0.0;
+          for (int i = 0; i < d; ++i) a += fq[i] * S[(size_t)i * d + c];
+          gnum[c] = a;
+          dnum[c] = alpha * dot_[c] / gden;
+          nd += a * dot_[c];
+        }
+        double dden = -alpha * nd / (gden * gden);
+        for (int i = 0; i < d; ++i) {
+          double dfq = z[i] * dden;
+          for (int c = 0; c < d; ++c) {
+            dfq += S[(size_t)i * d + c] * dnum[c];
+            gS[(size_t)i * d + c] += fq[i] * dnum[c];
+          }
+          gz[i] += fq[i] * dden;
+          dq[(size_t)t * d + i] += dfq * dphi(qt[i]);
+        }
+      }
+      /* local branch: the softmax weights of the group's tokens up to t, as in the forward */
+      double top = -INFINITY, mass = 0.0;
+      for (int i = g0; i <= t; ++i) {
+        p[i - g0] = dot(qt, k + (size_t)i * d, d) * inv_sqrt_d;
+        if (p[i - g0] > top) top = p[i - g0];
+      }
+      for (int i = g0; i <= t; ++i) {
+        p[i - g0] = exp(p[i - g0] - top);
+        mass += p[i - g0];
+      }
+      double pbar = 0.0;
+      for (int i = g0; i <= t; ++i) {
+        p[i - g0] /= mass;
+        dp[i - g0] = dot(dot_, v + (size_t)i * d, d);
+        pbar += p[i - g0] * dp[i - g0];
+      }
+      for (int i = g0; i <= t; ++i) {
+        double dl = p[i - g0] * (dp[i - g0] - pbar);
+        for (int f = 0; f < d; ++f) {
+          dq[(size_t)t * d + f] += dl * k[(size_t)i * d + f] * inv_sqrt_d;
+          dk[(size_t)i * d + f] += dl * qt[f] * inv_sqrt_d;
+          dv[(size_t)i * d + f] += p[i - g0] * dot_[f];
+        }
+      }
+    }
+    for (size_t e = 0; e < nS; ++e) DS[e] += gS[e];
+    for (int i = 0; i < d; ++i) DZ[i] += gz[i];
+  }
+  if (dS0) memcpy(dS0, DS, sizeof(double) * nS);
+  if (dz0) memcpy(dz0, DZ, sizeof(double) * (size_t)d);
+  /* masked DWConv: out[t][c] += w[c][j] * vext[t-j][c] */
+  if (dhist0) memset(dhist0, 0, sizeof(double) * (size_t)(Kc - 1) * d);
+  for (int t = 0; t < L; ++t)
+    for (int c = 0; c < d; ++c)
+      for (int j = 0; j < Kc; ++j) {
+        int s2 = t - j;
+        double go = dout[(size_t)t * d + c];
+        if (s2 >= 0) {
+          dv[(size_t)s2 * d + c] += w[(size_t)c * Kc + j] * go;
+          dw[(size_t)c * Kc + j] += go * v[(size_t)s2 * d + c];
+        } else if (hist0 && s2 >= -(Kc - 1)) {
+          if (dhist0) dhist0[(size_t)(Kc - 1 + s2) * d + c] += w[(size_t)c * Kc + j] * go;
+          dw[(size_t)c * Kc + j] += go * hist0[(size_t)(Kc - 1 + s2) * d + c];
+        }
+      }
+  free(Sg); free(zg); free(DS); free(DZ); free(gS); free(gz); free(fq); free(gnum);
+  free(dnum); free(p); free(dp);
+}
+
+/* dw: [H, d, Kc], summed over the batch rows.  dS1, dz1 (gradient flowing into the state
+ * handed back) and S0, z0, hist0 may be NULL (zeros); dS0, dz0, dhist0 may be NULL. */
+int oracle_prefill_grouped_backward(int B, int H, int L, int d, int Kc, int C, double eps,
+                                    double alpha, const double *q, const double *k,
+                                    const double *v, const double *w, const double *S0,
+                                    const double *z0, const double *hist0,
+                                    const double *dout, const double *dS1,
+                                    const double *dz1, double *dq, double *dk, double *dv,
+                                    double *dw, double *dS0, double *dz0, double *dhist0) {
+  if (B < 0 || H < 1 || L < 0 || d < 1 || Kc < 1 || C < 1) return 1;
+  size_t nS = (size_t)d * d, nh = (size_t)(Kc - 1) * d, nw = (size_t)d * Kc;
+  double *dw_bh = (double *)calloc((size_t)(B * H > 0 ? B * H : 1) * nw, sizeof(double));
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < B * H; ++bh) {
+    int h = bh % H;
+    size_t o = (size_t)bh * L * d;
+    grouped_backward_head(L, d, Kc, C, eps, alpha, q + o, k + o, v + o, w + (size_t)h * nw,
+                          S0 ? S0 + bh * nS : NULL, z0 ? z0 + (size_t)bh * d : NULL,
+                          hist0 ? hist0 + bh * nh : NULL, dout + o,
+                          dS1 ? dS1 + bh * nS : NULL, dz1 ? dz1 + (size_t)bh * d : NULL,
+                          dq + o, dk + o, dv + o, dw_bh + (size_t)bh * nw,
+                          dS0 ? dS0 + bh * nS : NULL, dz0 ? dz0 + (size_t)bh * d : NULL,
+                          dhist0 ? dhist0 + bh * nh : NULL);
+  }
+  memset(dw, 0, sizeof(double) * (size_t)H * nw);
+  for (int bh = 0; bh < B * H; ++bh)
+    for (size_t e = 0; e < nw; ++e) dw[(size_t)(bh % H) * nw + e] += dw_bh[(size_t)bh * nw + e];
+  free(dw_bh);
+  return 0;
+}
+
 /* Verification of kk draft tokens (Sec. 4.2): defined as kk recurrent steps
  * taken one after the other from the SAME incoming state; all kk outputs are
  * produced; the state handed back is the one reached after the first

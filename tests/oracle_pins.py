@@ -938,4 +938,199 @@ def pin_wide_values_verify_is_sequential_decode_and_prefill(lib=None):
     _close(part[1][1:], S0[1:], 0.0, "nothing kept: S untouched")
 
 
+# --- gradient of the three-branch form (training direction) --------------------------------------------------
+def _fd_gradients(loss, arrays, h=1e-6):
+    """Central differences of a scalar function of several arrays, element by element (the arrays are changed in place
+    and restored)."""
+    grads = []
+    for a in arrays:
+        g = np.zeros_like(a)
+        it = np.nditer(a, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = a[idx]
+            a[idx] = old + h
+            up = loss()
+            a[idx] = old - h
+            dn = loss()
+            a[idx] = old
+            g[idx] = (up - dn) / (2 * h)
+        grads.append(g)
+    return grads
+
+
+def _backward_case(seed, B=2, H=2, L=11, d=3, Kc=3):
+    r = _rng(seed)
+    q, k, v = (r.standard_normal((B, H, L, d)) for _ in range(3))
+    w = r.standard_normal((H, d, Kc))
+    S0 = 0.3 * r.standard_normal((B, H, d, d)) + 0.5
+    z0 = r.random((B, H, d)) + 0.5
+    h0 = r.standard_normal((B, H, Kc - 1, d))
+    dout = r.standard_normal((B, H, L, d))
+    dS1 = r.standard_normal((B, H, d, d))
+    dz1 = r.standard_normal((B, H, d))
+    return q, k, v, w, S0, z0, h0, dout, dS1, dz1
+
+
+_GRAD_NAMES = ("dq", "dk", "dv", "dw", "dS0", "dz0", "dhist0")
+
+
+def pin_grouped_backward_matches_finite_differences_of_the_forward(lib=None):
+    """The gradient is by definition the derivative of the (pinned) forward function: central differences of
+    sum(dout*out) + sum(dS1*S1) + sum(dz1*z1) in fp64, every element of every input, short last group included."""
+    for seed, group, alpha, eps in ((501, 4, 0.7, 0.1), (502, 3, 1.0, 0.0), (503, 16, 1.9, 0.0)):
+        q, k, v, w, S0, z0, h0, dout, dS1, dz1 = _backward_case(seed)
+        args = [q, k, v, w, S0, z0, h0]
+
+        def loss():
+            o, S1, z1, _ = oracle.prefill_grouped(q, k, v, w, group, alpha, S0, z0, h0, eps, lib=lib)
+            return float((o * dout).sum() + (S1 * dS1).sum() + (z1 * dz1).sum())
+
+        got = oracle.prefill_grouped_backward(q, k, v, w, dout, group, alpha, S0, z0, h0, dS1, dz1, eps, lib=lib)
+        for name, fd in zip(_GRAD_NAMES, _fd_gradients(loss, args)):
+            _close(got[name], fd, 2e-7, f"{name} (group {group})")
+
+
+def pin_grouped_backward_from_an_empty_state(lib=None):
+    """No incoming state, eps = 0: the first group has no grouped branch at all (its denominator is exactly zero), and the
+    gradient must say the same; this is the training case."""
+    q, k, v, w, _, _, _, dout, _, _ = _backward_case(504, L=10)
+    for group in (4, 5):
+        def loss():
+            return float((oracle.prefill_grouped(q, k, v, w, group, 1.3, lib=lib)[0] * dout).sum())
+
+        got = oracle.prefill_grouped_backward(q, k, v, w, dout, group, 1.3, lib=lib)
+        for name, fd in zip(_GRAD_NAMES[:4], _fd_gradients(loss, [q, k, v, w])):
+            _close(got[name], fd, 2e-7, f"{name} (group {group}, empty state)")
+        assert np.all(np.isfinite(got["dq"]))
+
+
+def pin_grouped_backward_single_group_is_the_library_attention_gradient(lib=None):
+    """One group, no state, zero conv weights: the function is the library's causal softmax attention, and its gradient
+    is what the library's own differentiation gives."""
+    r = _rng(505)
+    B, H, L, d = 2, 2, 9, 4
+    q, k, v, dout = (r.standard_normal((B, H, L, d)) for _ in range(4))
+    w = np.zeros((H, d, 2))
+    got = oracle.prefill_grouped_backward(q, k, v, w, dout, 16, alpha=0.4, lib=lib)
+    tq, tk, tv = (torch.from_numpy(a).requires_grad_(True) for a in (q, k, v))
+    out = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+    out.backward(torch.from_numpy(dout))
+    for name, t in (("dq", tq), ("dk", tk), ("dv", tv)):
+        _close(got[name], t.grad.numpy(), 1e-12, f"{name} vs library attention gradient")
+
+
+def pin_grouped_backward_conv_part_is_the_library_conv_gradient(lib=None):
+    """The conv branch adds to the output, so it adds to dv, and it alone feeds dw and dhist0: the difference to a run
+    with zero weights, and dw / dhist0 themselves, against the library's differentiation of its grouped conv1d."""
+    q, k, v, w, S0, z0, h0, dout, _, _ = _backward_case(506, L=12, d=4, Kc=5)
+    B, H, L, d = q.shape
+    Kc = w.shape[2]
+    got = oracle.prefill_grouped_backward(q, k, v, w, dout, 4, 1.0, S0, z0, h0, lib=lib)
+    base = oracle.prefill_grouped_backward(q, k, v, np.zeros_like(w), dout, 4, 1.0, S0, z0, h0, lib=lib)
+    ext = torch.from_numpy(np.concatenate([h0, v], axis=2)).requires_grad_(True)      # [B, H, Kc-1+L, d]
+    tw = torch.from_numpy(w).requires_grad_(True)
+    x = ext.permute(0, 1, 3, 2).reshape(B, H * d, Kc - 1 + L)                          # channels = (h, c)
+    ker = torch.flip(tw, dims=[2]).reshape(H * d, 1, Kc)                               # tap j meets v[t-j]
+    u = torch.nn.functional.conv1d(x, ker, groups=H * d).reshape(B, H, d, L).permute(0, 1, 3, 2)
+    u.backward(torch.from_numpy(dout))
+    g_ext = ext.grad.numpy()
+    _close(got["dv"] - base["dv"], g_ext[:, :, Kc - 1:], 1e-12, "conv part of dv")
+    _close(got["dhist0"], g_ext[:, :, :Kc - 1], 1e-12, "dhist0")
+    _close(got["dw"], tw.grad.numpy(), 1e-12, "dw")
+    for name in ("dq", "dk", "dS0", "dz0"):
+        assert np.array_equal(got[name], base[name]), f"{name} must not depend on the conv weights"
+
+
+def pin_grouped_backward_is_linear_in_dout(lib=None):
+    q, k, v, w, S0, z0, h0, d1, dS1, dz1 = _backward_case(507)
+    d2 = _rng(508).standard_normal(d1.shape)
+    a = oracle.prefill_grouped_backward(q, k, v, w, d1, 4, 0.8, S0, z0, h0, eps=0.05, lib=lib)
+    b = oracle.prefill_grouped_backward(q, k, v, w, d2, 4, 0.8, S0, z0, h0, eps=0.05, lib=lib)
+    c = oracle.prefill_grouped_backward(q, k, v, w, 2.0 * d1 - 0.5 * d2, 4, 0.8, S0, z0, h0, eps=0.05, lib=lib)
+    for name in _GRAD_NAMES:
+        _close(c[name], 2.0 * a[name] - 0.5 * b[name], 1e-12, name)
+
+
+def pin_grouped_backward_is_causal(lib=None):
+    """A loss that looks at token t alone cannot move because of a later token: dk, dv are exactly zero after t, dq is
+    exactly zero everywhere but at t; and it does depend on the first token (through the sums) and on its own group."""
+    q, k, v, w, S0, z0, h0, dout, _, _ = _backward_case(509, L=13)
+    t = 9                                                # the second token of the group 8..11
+    only = np.zeros_like(dout)
+    only[:, :, t] = dout[:, :, t]
+    g = oracle.prefill_grouped_backward(q, k, v, w, only, 4, 1.0, S0, z0, h0, lib=lib)
+    assert np.all(g["dk"][:, :, t + 1:] == 0.0) and np.all(g["dv"][:, :, t + 1:] == 0.0)
+    assert np.all(g["dq"][:, :, :t] == 0.0) and np.all(g["dq"][:, :, t + 1:] == 0.0)
+    assert np.all(np.abs(g["dq"][:, :, t]).max(axis=-1) > 0)
+    assert np.all(np.abs(g["dk"][:, :, 0]).max(axis=-1) > 0) and np.all(np.abs(g["dv"][:, :, 0]).max(axis=-1) > 0)
+    assert np.all(np.abs(g["dk"][:, :, t]).max(axis=-1) > 0)        # its own key: the local branch
+    # token 8 of t's own group reaches it through the local branch only, tokens 4..7 of the group before through the sums
+    # only: both kinds must be there
+    assert np.all(np.abs(g["dv"][:, :, 8]).max(axis=-1) > 0) and np.all(np.abs(g["dk"][:, :, 8]).max(axis=-1) > 0)
+    assert np.all(np.abs(g["dv"][:, :, 5]).max(axis=-1) > 0) and np.all(np.abs(g["dk"][:, :, 5]).max(axis=-1) > 0)
+
+
+def pin_grouped_backward_chains_across_a_split(lib=None):
+    """A sequence cut at a group boundary is two calls chained through (S, z, hist); the gradient chains the other way
+    round through (dS0, dz0, dhist0) of the second call."""
+    q, k, v, w, S0, z0, h0, dout, dS1, dz1 = _backward_case(510, L=14, d=4, Kc=3)
+    Kc = w.shape[2]
+    G, cut = 3, 6
+    whole = oracle.prefill_grouped_backward(q, k, v, w, dout, G, 1.3, S0, z0, h0, dS1, dz1, eps=1e-3, lib=lib)
+    fa = oracle.prefill_grouped(q[:, :, :cut], k[:, :, :cut], v[:, :, :cut], w, G, 1.3, S0, z0, h0, eps=1e-3, lib=lib)
+    gb = oracle.prefill_grouped_backward(q[:, :, cut:], k[:, :, cut:], v[:, :, cut:], w, dout[:, :, cut:], G, 1.3,
+                                         fa[1], fa[2], fa[3], dS1, dz1, eps=1e-3, lib=lib)
+    ga = oracle.prefill_grouped_backward(q[:, :, :cut], k[:, :, :cut], v[:, :, :cut], w, dout[:, :, :cut], G, 1.3,
+                                         S0, z0, h0, gb["dS0"], gb["dz0"], eps=1e-3, lib=lib)
+    dv_a = ga["dv"].copy()
+    dv_a[:, :, cut - (Kc - 1):] += gb["dhist0"]          # the second call's history is the first call's last rows
+    _close(np.concatenate([ga["dq"], gb["dq"]], axis=2), whole["dq"], 1e-12, "dq")
+    _close(np.concatenate([ga["dk"], gb["dk"]], axis=2), whole["dk"], 1e-12, "dk")
+    _close(np.concatenate([dv_a, gb["dv"]], axis=2), whole["dv"], 1e-12, "dv")
+    _close(ga["dw"] + gb["dw"], whole["dw"], 1e-12, "dw")
+    for name in ("dS0", "dz0", "dhist0"):
+        _close(ga[name], whole[name], 1e-12, name)
+
+
+def pin_grouped_backward_closed_form_for_zero_queries_and_keys(lib=None):
+    """Q = K = 0: every feature is 1 and every logit 0, so out_t = alpha * mean(v before t's group) + mean(v of the group up
+    to t) + conv, and dv follows by hand: token i receives alpha * dout_t / (tokens before t's group) from every t of a
+    later group and dout_t / (t - g0 + 1) from every t >= i of its own group (plus the conv part, zero here)."""
+    r = _rng(511)
+    B, H, L, d, G, alpha = 1, 2, 10, 3, 4, 0.6
+    v, dout = r.standard_normal((B, H, L, d)), r.standard_normal((B, H, L, d))
+    zero = np.zeros((B, H, L, d))
+    got = oracle.prefill_grouped_backward(zero, zero, v, np.zeros((H, d, 2)), dout, G, alpha, lib=lib)
+    want = np.zeros_like(v)
+    for t in range(L):
+        g0 = (t // G) * G
+        for i in range(g0):
+            want[:, :, i] += alpha * dout[:, :, t] / g0
+        for i in range(g0, t + 1):
+            want[:, :, i] += dout[:, :, t] / (t - g0 + 1)
+    _close(got["dv"], want, 1e-12, "dv, closed form")
+
+
+def pin_grouped_backward_relu_map_matches_finite_differences(lib=None):
+    """The other feature map (derivative 1 above zero, 0 below); inputs kept away from the kink."""
+    q, k, v, w, S0, z0, h0, dout, dS1, dz1 = _backward_case(512, L=9)
+    q[np.abs(q) < 0.05] = 0.3
+    k[np.abs(k) < 0.05] = -0.3
+    with oracle.feature_map("relu", lib):
+        def loss():
+            o, S1, z1, _ = oracle.prefill_grouped(q, k, v, w, 4, 0.9, S0, z0, h0, 0.5, lib=lib)
+            return float((o * dout).sum() + (S1 * dS1).sum() + (z1 * dz1).sum())
+
+        got = oracle.prefill_grouped_backward(q, k, v, w, dout, 4, 0.9, S0, z0, h0, dS1, dz1, 0.5, lib=lib)
+        fds = _fd_gradients(loss, [q, k, v, w, S0, z0, h0])
+    for name, fd in zip(_GRAD_NAMES, fds):
+        _close(got[name], fd, 2e-7, f"{name} (relu map)")
+    # a negative key entry is invisible to the sums: its derivative comes from the local branch alone, which does not
+    # know alpha, dS1 or dz1
+    with oracle.feature_map("relu", lib):
+        other = oracle.prefill_grouped_backward(q, k, v, w, dout, 4, 0.0, S0, z0, h0, None, None, 0.5, lib=lib)
+    _close(got["dk"][k < 0], other["dk"][k < 0], 1e-12, "dk of negative key entries")
+
+
 ALL_PINS = [obj for name, obj in sorted(globals().items()) if name.startswith("pin_") and callable(obj)]

@@ -92,6 +92,32 @@ MUTANTS = [
     ("gverify_commits_everything", "int n = n_commit ? n_commit[b] : kk;\n    size_t o = (size_t)bh * kk * d;\n    double *Sw = (double *)malloc(sizeof(double) * nS);\n    double *zw = (double *)malloc(sizeof(double) * (size_t)d);\n    double *hw = (double *)malloc(sizeof(double) * (nh ? nh : 1));\n    double *kw",
      "int n = kk;\n    size_t o = (size_t)bh * kk * d;\n    double *Sw = (double *)malloc(sizeof(double) * nS);\n    double *zw = (double *)malloc(sizeof(double) * (size_t)d);\n    double *hw = (double *)malloc(sizeof(double) * (nh ? nh : 1));\n    double *kw"),
     ("recurrent_ignores_incoming_S", "load_state(d, Kc, S0 ? S0 + bh * nS : NULL, z0", "load_state(d, Kc, NULL, z0"),
+    # the gradient of the three-branch form
+    ("gbwd_denominator_gradient_sign", "double dden = -alpha * nd / (gden * gden);", "double dden = alpha * nd / (gden * gden);"),
+    ("gbwd_denominator_not_squared", "double dden = -alpha * nd / (gden * gden);", "double dden = -alpha * nd / gden;"),
+    ("gbwd_numerator_gradient_drops_alpha", "dnum[c] = alpha * dot_[c] / gden;", "dnum[c] = dot_[c] / gden;"),
+    ("gbwd_query_gradient_drops_the_z_term", "double dfq = z[i] * dden;", "double dfq = 0.0;"),
+    ("gbwd_dz_dropped", "gz[i] += fq[i] * dden;", ""),
+    ("gbwd_dS_transposed", "gS[(size_t)i * d + c] += fq[i] * dnum[c];", "gS[(size_t)c * d + i] += fq[i] * dnum[c];"),
+    ("gbwd_dq_drops_the_maps_derivative", "dq[(size_t)t * d + i] += dfq * dphi(qt[i]);", "dq[(size_t)t * d + i] += dfq;"),
+    ("gbwd_dk_drops_the_maps_derivative", "dk[(size_t)t * d + i] += dfk * dphi(kti);", "dk[(size_t)t * d + i] += dfk;"),
+    ("gbwd_derivative_of_elu_is_one", "return x > 0.0 ? 1.0 : exp(x);", "return 1.0;"),
+    ("gbwd_derivative_of_relu_is_one", "if (g_feature_map == 1) return x > 0.0 ? 1.0 : 0.0;", "if (g_feature_map == 1) return 1.0;"),
+    ("gbwd_later_groups_gradient_dropped", "for (size_t e = 0; e < nS; ++e) DS[e] += gS[e];", "for (size_t e = 0; e < nS; ++e) DS[e] = gS[e];"),
+    ("gbwd_key_gradient_drops_dz", "double dfk = DZ[i];", "double dfk = 0.0;"),
+    ("gbwd_value_gradient_from_sums_transposed", "dv[(size_t)t * d + c] += fk * DS[(size_t)i * d + c];", "dv[(size_t)t * d + c] += fk * DS[(size_t)c * d + i];"),
+    ("gbwd_softmax_drops_the_mean_term", "double dl = p[i - g0] * (dp[i - g0] - pbar);", "double dl = p[i - g0] * dp[i - g0];"),
+    ("gbwd_local_dq_drops_the_logit_scale", "dq[(size_t)t * d + f] += dl * k[(size_t)i * d + f] * inv_sqrt_d;", "dq[(size_t)t * d + f] += dl * k[(size_t)i * d + f];"),
+    ("gbwd_local_dk_uses_the_key", "dk[(size_t)i * d + f] += dl * qt[f] * inv_sqrt_d;", "dk[(size_t)i * d + f] += dl * k[(size_t)i * d + f] * inv_sqrt_d;"),
+    ("gbwd_local_weights_not_normalised", "p[i - g0] /= mass;", ""),
+    ("gbwd_conv_taps_reversed", "dv[(size_t)s2 * d + c] += w[(size_t)c * Kc + j] * go;", "dv[(size_t)s2 * d + c] += w[(size_t)c * Kc + (Kc - 1 - j)] * go;"),
+    ("gbwd_dw_of_one_batch_row_only", "dw[(size_t)(bh % H) * nw + e] += dw_bh[(size_t)bh * nw + e];", "dw[(size_t)(bh % H) * nw + e] = dw_bh[(size_t)bh * nw + e];"),
+    ("gbwd_dw_misses_the_history", "dw[(size_t)c * Kc + j] += go * hist0[(size_t)(Kc - 1 + s2) * d + c];", ""),
+    ("gbwd_dhist_reversed", "dhist0[(size_t)(Kc - 1 + s2) * d + c] += w", "dhist0[(size_t)(-s2 - 1) * d + c] += w"),
+    ("gbwd_gradient_into_the_final_state_ignored", "if (dS1) memcpy(DS, dS1, sizeof(double) * nS);", ""),
+    ("gbwd_queries_read_their_own_groups_sums", "const double *S = Sg + (size_t)g * nS, *z = zg + (size_t)g * d;",
+     "const double *S = Sg + (size_t)(g + 1) * nS, *z = zg + (size_t)(g + 1) * d;"),
+    ("gbwd_empty_denominator_not_skipped", "      if (gden != 0.0) {\n        double nd = 0.0;", "      {\n        double nd = 0.0;"),
 ]
 
 
