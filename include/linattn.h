@@ -182,10 +182,10 @@ size_t linattn_noalloc_scratch_bytes(void);
  *   alpha        finite (LINATTN_ERR_SHAPE otherwise)
  * chunk must be 64 (the paper's group size for LLaMA) or 256 (its group size for
  * FLASH, Sec. 5 "Settings"); LINATTN_ERR_UNSUPPORTED otherwise, and for fp32 rows
- * of 128 elements in groups of 256.  bf16 rows in groups of 64 run on the matrix
- * cores; fp32 rows, and all rows in groups of 256, on a plain fp32 kernel that is
- * exact to fp32 rounding but not built for speed (one workgroup per (b, h), no
- * workspace). */
+ * of 128 elements in groups of 256.  bf16 rows run on the matrix cores (groups of
+ * 256 keep their running state in the workspace, which they need for every L > 0);
+ * fp32 rows on a plain fp32 kernel that is exact to fp32 rounding but not built
+ * for speed (one workgroup per (b, h), no workspace). */
 linattn_status linattn_prefill_grouped(const linattn_desc *desc, int32_t L, float alpha,
                                        const void *q, const void *k, const void *v,
                                        const float *conv_w,
@@ -194,6 +194,45 @@ linattn_status linattn_prefill_grouped(const linattn_desc *desc, int32_t L, floa
                                        float *S_out, float *z_out, void *hist_out,
                                        void *workspace, size_t workspace_bytes,
                                        void *hip_stream);
+
+/* Gradient of linattn_prefill_grouped (Sec. 5.3: the paper times a training step,
+ * forward and backward, of FLASH with this block in groups of 256 tokens), for a
+ * sequence that starts from nothing (no incoming state or history: training).
+ * With out = linattn_prefill_grouped(q, k, v, conv_w) and dout = d loss / d out, it
+ * writes the derivatives of the loss with respect to q, k, v and the conv weights:
+ *   grouped branch   through phi(q)^T S / (phi(q).z + eps) into the queries, and
+ *                    through the group-level sums S, z into every key and value
+ *                    of the earlier groups (phi'(x) = 1 for x > 0, else exp(x); for
+ *                    the map max(x, 0): 1 for x > 0, else 0);
+ *   local branch     the gradient of causal softmax attention inside each group;
+ *   conv             dv[s] += sum_j conv_w[h][c][j] dout[s+j], and
+ *                    dconv_w[h][c][j] = sum over batch rows and tokens of
+ *                    dout[b,h,t,c] * v[b,h,t-j,c].
+ *   desc         in      as for the forward call; bf16 rows, d_v = d, chunk 64 or
+ *                        256 (LINATTN_ERR_UNSUPPORTED otherwise); conv_k <= 63
+ *   L            in      tokens per sequence, any L >= 0
+ *   q, k, v, dout in     device, bf16, addressed by the descriptor's strides
+ *   conv_w       in      device float [H,d,Kc]
+ *   dq, dk, dv   out     device, bf16, same strides; must not alias the inputs
+ *   dconv_w      out     device float [H,d,Kc], written (not added to); NULL = not wanted
+ *   workspace    scratch device, >= linattn_backward_workspace_bytes(desc, L), 16-byte
+ *                        aligned: the sums before every group and the gradients with
+ *                        respect to them ((d*d+d) floats per group and head, twice),
+ *                        five floats per token and head, and the partial conv-weight
+ *                        sums.  Contents on entry are ignored.
+ * Arithmetic: bf16 operands on the matrix cores, fp32 accumulation; dv is rounded
+ * to bf16 before the conv's share is added (a second rounding).  The result does not
+ * depend on the launch configuration (no atomics: fixed summation order).
+ * Asynchronous on hip_stream; every argument is validated before anything is
+ * enqueued. */
+size_t linattn_backward_workspace_bytes(const linattn_desc *desc, int32_t L);
+
+linattn_status linattn_prefill_grouped_backward(const linattn_desc *desc, int32_t L, float alpha,
+                                                const void *q, const void *k, const void *v,
+                                                const float *conv_w, const void *dout,
+                                                void *dq, void *dk, void *dv, float *dconv_w,
+                                                void *workspace, size_t workspace_bytes,
+                                                void *hip_stream);
 
 /* Speculative verification (Sec. 4.2): scores kk draft tokens per (b, h) from
  * one running state.  Output j equals what kk single decode steps would give

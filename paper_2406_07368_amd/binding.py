@@ -21,7 +21,7 @@ LINATTN_F32, LINATTN_BF16 = 0, 1
 LINATTN_PHI_ELU1, LINATTN_PHI_RELU = 0, 1
 PHI = {"elu1": LINATTN_PHI_ELU1, "relu": LINATTN_PHI_RELU}
 MAX_CONV_K, MAX_CONV_K_PREFILL, MAX_DRAFT, MAX_TREE = 8, 63, 16, 64
-SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_noalloc", "linattn_noalloc_scratch_bytes", "linattn_prefill_grouped", "linattn_verify", "linattn_verify_grouped", "linattn_verify_tree", "linattn_decode",
+SYMBOLS = ("linattn_workspace_bytes", "linattn_prefill", "linattn_prefill_noalloc", "linattn_noalloc_scratch_bytes", "linattn_prefill_grouped", "linattn_backward_workspace_bytes", "linattn_prefill_grouped_backward", "linattn_verify", "linattn_verify_grouped", "linattn_verify_tree", "linattn_decode",
            "linattn_set_wait_limit", "linattn_status_string", "linattn_version")
 
 
@@ -61,6 +61,10 @@ def load():
     lib.linattn_noalloc_scratch_bytes.argtypes = []
     lib.linattn_prefill_grouped.restype = ctypes.c_int
     lib.linattn_prefill_grouped.argtypes = [dp, i32, ctypes.c_float] + [vp] * 11 + [vp, sz, vp]
+    lib.linattn_backward_workspace_bytes.restype = sz
+    lib.linattn_backward_workspace_bytes.argtypes = [dp, i32]
+    lib.linattn_prefill_grouped_backward.restype = ctypes.c_int
+    lib.linattn_prefill_grouped_backward.argtypes = [dp, i32, ctypes.c_float] + [vp] * 9 + [vp, sz, vp]
     lib.linattn_verify.restype = ctypes.c_int
     lib.linattn_verify.argtypes = [dp, i32] + [vp] * 9 + [vp]
     lib.linattn_verify_grouped.restype = ctypes.c_int
@@ -159,6 +163,20 @@ def linattn_prefill_grouped(desc: Desc, L, alpha, q, k, v, conv_w, S_in, z_in, h
     _check(st, "linattn_prefill_grouped")
 
 
+def linattn_backward_workspace_bytes(desc: Desc, L) -> int:
+    return int(load().linattn_backward_workspace_bytes(ctypes.byref(desc), int(L)))
+
+
+def linattn_prefill_grouped_backward(desc: Desc, L, alpha, q, k, v, conv_w, dout, dq, dk, dv, dconv_w, workspace,
+                                     workspace_bytes=None, stream=None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    st = load().linattn_prefill_grouped_backward(ctypes.byref(desc), int(L), float(alpha), _ptr(q), _ptr(k), _ptr(v),
+                                                 _ptr(conv_w), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dconv_w),
+                                                 _ptr(workspace), int(workspace_bytes), _stream(stream))
+    _check(st, "linattn_prefill_grouped_backward")
+
+
 def linattn_verify(desc: Desc, kk, q, k, v, conv_w, S, z, hist, n_commit, out, stream=None) -> None:
     st = load().linattn_verify(ctypes.byref(desc), int(kk), _ptr(q), _ptr(k), _ptr(v), _ptr(conv_w),
                                _ptr(S), _ptr(z), _ptr(hist), _ptr(n_commit), _ptr(out), _stream(stream))
@@ -224,6 +242,28 @@ def prefill_grouped(q, k, v, conv_w, alpha=1.0, state=None, eps=0.0, want_state=
     """The three-branch form (grouped linear attention, weight alpha + local softmax attention + masked conv)
     with groups of 64 or 256 tokens; arguments as for ``prefill``."""
     return prefill(q, k, v, conv_w, state, group, eps, want_state, stream, phi, grouped_alpha=alpha)
+
+
+def prefill_grouped_backward(q, k, v, conv_w, dout, alpha=1.0, eps=0.0, stream=None, phi="elu1", group=256,
+                             want_dw=True):
+    """Gradient of ``prefill_grouped`` for a sequence that starts from nothing: q, k, v, dout bf16 [B,H,L,d] CUDA
+    tensors, dense or views that share their strides and are contiguous along d.  Returns dq, dk, dv (same layout)
+    and the gradient of the conv weights (fp32 [H,d,Kc], summed over the batch; None if not wanted)."""
+    B, H, L, d = q.shape
+    Kc = conv_w.shape[2]
+    dense = all(t.is_contiguous() for t in (q, k, v, dout))
+    if not dense and (q.stride(3) != 1 or any(t.stride() != q.stride() for t in (k, v, dout))):
+        raise ValueError("q, k, v and dout must share their strides and be contiguous along d")
+    desc = make_desc(B, H, d, Kc, group, q.dtype, eps, strides=None if dense else q.stride()[:3], L=L, phi=phi)
+    new = (lambda: torch.empty_like(q)) if dense else (lambda: torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device))
+    dq, dk, dv = new(), new(), new()
+    dw = torch.empty((H, d, Kc), dtype=torch.float32, device=q.device) if want_dw else None
+    nbytes = linattn_backward_workspace_bytes(desc, L)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=q.device)
+    if stream is not None and not isinstance(stream, int):
+        ws.record_stream(stream)
+    linattn_prefill_grouped_backward(desc, L, alpha, q, k, v, conv_w, dout, dq, dk, dv, dw, ws, nbytes, stream)
+    return dq, dk, dv, dw
 
 
 def verify(q, k, v, conv_w, state, n_commit=None, eps=0.0, stream=None, phi="elu1"):

@@ -196,7 +196,7 @@ const char* linattn_status_string(linattn_status s) {
   return "unknown status";
 }
 
-int32_t linattn_version(void) { return 200; }
+int32_t linattn_version(void) { return 210; }
 
 int32_t linattn_set_wait_limit(int32_t spins) {
   return g_wait_spins.exchange(spins == 0 ? kDefaultWaitSpins : spins, std::memory_order_relaxed);
@@ -240,6 +240,85 @@ linattn_status linattn_prefill_grouped(const linattn_desc* desc, int32_t L, floa
                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
   return prefill_any(desc, L, true, alpha, q, k, v, conv_w, S_in, z_in, hist_in, out, S_out, z_out, hist_out, workspace,
                      workspace_bytes, hip_stream);
+}
+
+namespace {
+struct BackwardPlan {
+  int ng, nwb;
+  size_t off_P, off_D, off_stats, off_dw, bytes;   // byte offsets of the pieces of the workspace
+};
+size_t round256(size_t x) { return (x + 255) / 256 * 256; }
+BackwardPlan plan_backward(const linattn_desc* d, int32_t L) {
+  BackwardPlan p{};
+  const size_t BH = (size_t)d->B * d->H, slot = (size_t)d->d * d->d + d->d;
+  p.ng = L > 0 ? (L + d->chunk - 1) / d->chunk : 0;
+  p.nwb = grouped_bwd_dw_blocks(L);
+  p.off_P = 0;
+  p.off_D = round256(BH * (p.ng > 0 ? p.ng : 1) * slot * sizeof(float));
+  p.off_stats = p.off_D + round256(BH * (p.ng > 0 ? p.ng : 1) * slot * sizeof(float));
+  p.off_dw = p.off_stats + round256(5 * BH * (size_t)(L > 0 ? L : 1) * sizeof(float));
+  p.bytes = p.off_dw + round256(BH * (size_t)(p.nwb > 0 ? p.nwb : 1) * d->d * d->conv_k * sizeof(float));
+  return p;
+}
+linattn_status check_backward(const linattn_desc* desc, int32_t L) {
+  linattn_status st = check_desc(desc, true, true, LINATTN_MAX_CONV_K_PREFILL);
+  if (st != LINATTN_OK) return st;
+  if (L < 0) return LINATTN_ERR_SHAPE;
+  if (desc->io_dtype != LINATTN_BF16 || value_blocks(desc) > 1) return LINATTN_ERR_UNSUPPORTED;
+  if (desc->chunk != 64 && desc->chunk != 256) return LINATTN_ERR_UNSUPPORTED;
+  return LINATTN_OK;
+}
+}  // namespace
+
+size_t linattn_backward_workspace_bytes(const linattn_desc* desc, int32_t L) {
+  if (check_backward(desc, L) != LINATTN_OK) return 0;
+  return plan_backward(desc, L).bytes;
+}
+
+linattn_status linattn_prefill_grouped_backward(const linattn_desc* desc, int32_t L, float alpha, const void* q,
+                                                const void* k, const void* v, const float* conv_w, const void* dout,
+                                                void* dq, void* dk, void* dv, float* dconv_w, void* workspace,
+                                                size_t workspace_bytes, void* hip_stream) {
+  linattn_status st = check_backward(desc, L);
+  if (st != LINATTN_OK) return st;
+  if (!(alpha == alpha) || alpha - alpha != 0.f) return LINATTN_ERR_SHAPE;   // NaN, infinity
+  if (!conv_w) return LINATTN_ERR_NULL;
+  if (L > 0 && (!q || !k || !v || !dout || !dq || !dk || !dv)) return LINATTN_ERR_NULL;
+  const void* ptrs[] = {q, k, v, conv_w, dout, dq, dk, dv, dconv_w, workspace};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return LINATTN_ERR_ALIGN;
+  if ((double)desc->stride_b * desc->B + (double)desc->stride_h * desc->H + (double)desc->stride_t * L > 9.0e18)
+    return LINATTN_ERR_SHAPE;
+  const BackwardPlan plan = plan_backward(desc, L);
+  if (!workspace || workspace_bytes < plan.bytes) return LINATTN_ERR_WORKSPACE;
+  if ((int64_t)desc->B * desc->H > 65535 || (int64_t)2 * plan.ng > 0x7fffffff) return LINATTN_ERR_SHAPE;   // grid limits
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  GroupedBwdArgs a{};
+  a.q = q; a.k = k; a.v = v; a.dout = dout; a.dq = dq; a.dk = dk; a.dv = dv; a.conv_w = conv_w; a.dconv_w = dconv_w;
+  a.P = reinterpret_cast<float*>(ws + plan.off_P);
+  a.Dg = reinterpret_cast<float*>(ws + plan.off_D);
+  a.stats = reinterpret_cast<float*>(ws + plan.off_stats);
+  a.dw_part = reinterpret_cast<float*>(ws + plan.off_dw);
+  a.B = desc->B; a.H = desc->H; a.L = L; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
+  a.alpha = alpha;
+  a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
+  a.group = desc->chunk; a.ng = plan.ng; a.nwb = plan.nwb;
+  hipError_t e = hipSuccess;
+  if (L > 0) {
+    if (e == hipSuccess) e = launch_grouped_bwd(a, desc->d, stream);
+    // the conv's share of dv: the same taps met from the other side, dv[s] += sum_j w[j] dout[s + j]
+    if (e == hipSuccess) {
+      ConvLongArgs c{};
+      c.v = dout; c.conv_w = conv_w; c.out = dv;
+      c.B = a.B; c.H = a.H; c.L = L; c.Kc = a.Kc; c.sb = a.sb; c.sh = a.sh; c.st = a.st; c.m = 1; c.rev = 1;
+      e = launch_conv_long(c, true, desc->d, stream);
+    }
+  } else if (dconv_w) {
+    e = launch_grouped_bwd(a, desc->d, stream);            // no tokens: the sums over nothing
+  }
+  return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 
 linattn_status linattn_verify(const linattn_desc* desc, int32_t kk, const void* q, const void* k, const void* v,

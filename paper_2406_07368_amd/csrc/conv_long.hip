@@ -62,7 +62,8 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       const bool in_seq = tok >= 0 && tok < L;
       const bool in_hist = tok < 0 && a.hist_in != nullptr && Kc - 1 + tok >= 0;
       const void* src = in_hist ? a.hist_in : a.v;
-      const int64_t idx = in_hist ? hist_base + (int64_t)(Kc - 1 + tok) * DVT + i0 : base + (int64_t)(in_seq ? tok : 0) * a.st + i0;
+      const int mt = in_seq ? (a.rev ? L - 1 - tok : tok) : 0;     // where the token lies in memory
+      const int64_t idx = in_hist ? hist_base + (int64_t)(Kc - 1 + tok) * DVT + i0 : base + (int64_t)mt * a.st + i0;
       raw[i] = Io::load_raw8(src, idx);
       have[i] = in_seq || in_hist;
     }
@@ -74,7 +75,8 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
 #pragma unroll
     for (int e = 0; e < TPT; ++e) {
       const int tok = t0 + tg * TPT + e;
-      prev[e] = static_cast<const typename Io::elem*>(a.out)[base + (int64_t)(tok < L ? tok : L - 1) * a.st + c];
+      const int mt = tok < L ? (a.rev ? L - 1 - tok : tok) : 0;
+      prev[e] = static_cast<const typename Io::elem*>(a.out)[base + (int64_t)mt * a.st + c];
     }
   };
   float wreg[KMAX];
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
 #pragma unroll
     for (int e = 0; e < CL_BLK; ++e) {
       const int tok = t0 + tb0 + e;
-      if (tok < L) Io::store1(a.out, base + (int64_t)tok * a.st + c, elem_to_f32(prev[e]) + acc[e]);
+      if (tok < L) Io::store1(a.out, base + (int64_t)(a.rev ? L - 1 - tok : tok) * a.st + c, elem_to_f32(prev[e]) + acc[e]);
     }
     // the next block's elements move to the front (constant register indices in a loop that is not unrolled)
 #pragma unroll

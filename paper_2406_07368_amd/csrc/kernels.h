@@ -110,6 +110,29 @@ struct ConvLongArgs {
   int B, H, L, Kc;
   int64_t sb, sh, st;       // strides of v and out
   int m;                    // value blocks of d channels per head (d_v = m d)
+  int rev;                  // the token axis runs backwards (out[t] += sum_j w[j] v[t + j]): the conv's share of the
+                            // gradient with respect to its input; no history then
+};
+
+// Gradient of the three-branch form for a sequence that starts from nothing (training): bf16 rows, one set of strides
+struct GroupedBwdArgs {
+  const void* q; const void* k; const void* v;   // [B,H,L,d] by strides
+  const void* dout;         // gradient with respect to the outputs, same layout
+  void* dq; void* dk; void* dv;                  // same layout
+  const float* conv_w;      // [H,d,Kc]
+  float* dconv_w;           // [H,d,Kc], summed over the batch rows; null = not wanted
+  float* P;                 // [B*H][ng][d*d + d]: the sums before every group
+  float* Dg;                // [B*H][ng][d*d + d]: what a group's queries add to the gradient of the sums before it; after
+                            // the suffix sum: the gradient with respect to the sums after the group
+  float* stats;             // [5][B*H*L]: per token, largest logit (log2 units), 1 / sum of weights, pbar, alpha / den, d den
+  float* dw_part;           // [B*H][nwb][d*Kc]: conv-weight gradient of one block of tokens
+  int B, H, L, Kc;
+  float eps;
+  int relu;
+  float alpha;
+  int64_t sb, sh, st;
+  int group, ng;            // tokens per group (64 or 256), groups per sequence
+  int nwb;                  // token blocks of the conv-weight pass per sequence
 };
 
 // verify.hip
@@ -140,7 +163,12 @@ hipError_t launch_prefill_grouped_simt(const PrefillArgs& a, bool bf16, int d, h
 // conv_long.hip : out += causal depthwise conv with 9..63 taps, and the history that goes with it
 hipError_t launch_conv_long(const ConvLongArgs& a, bool bf16, int d, hipStream_t st);
 
+// prefill_grouped_bwd.hip : gradient of the three-branch form (bf16 rows, groups of 64 or 256)
+int grouped_bwd_dw_blocks(int L);
+hipError_t launch_grouped_bwd(const GroupedBwdArgs& a, int d, hipStream_t st);
+
 // prefill_mfma.hip : launch plan of the bf16 prefill (segments, prefix sum over segment states)
+hipError_t launch_segment_scan(const PrefillArgs& a, int d, hipStream_t st);   // the prefix sum alone
 int prefill_mfma_pick_segments(int BH, int L, int chunk);
 size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg);
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st);

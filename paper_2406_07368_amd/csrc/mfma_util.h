@@ -33,6 +33,16 @@ __device__ __forceinline__ bf16x8 tr_operand(const uint16_t* base, int stride, i
   return cat4(lds_tr4(p), lds_tr4(p + 4 * stride));
 }
 
+// The same with registers <-> the rows in the order in which a 32 x 32 accumulator holds its row index: registers
+// 0..3 <-> rows row0 + 4 (lane / 32) + 0..3, registers 4..7 <-> rows row0 + 8 + 4 (lane / 32) + 0..3.  An accumulator
+// packed with pack8(acc, 0) / pack8(acc, 8) is then the other operand of a product over rows row0 .. row0 + 15 /
+// row0 + 16 .. row0 + 31 without its values ever passing through LDS.
+__device__ __forceinline__ bf16x8 tr_operand_acc_order(const uint16_t* base, int stride, int row0, int col0, int lane) {
+  const int j = lane & 15;
+  const uint16_t* p = base + (row0 + 4 * (lane >> 5) + (j >> 2)) * stride + col0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
+  return cat4(lds_tr4(p), lds_tr4(p + 8 * stride));
+}
+
 __device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -42,6 +52,19 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int o) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) r[i] = pack_bf16x2(x[o + 2 * i], x[o + 2 * i + 1]);
   return __builtin_bit_cast(bf16x8, r);
+}
+
+// Eight accumulator values as the sum of two bf16 operands: hi = bf16(x), lo = bf16(x - hi).  A product with hi and
+// one with lo carries sixteen significant bits of x where one operand carries eight.
+__device__ __forceinline__ void split8(const f32x16& x, int o, bf16x8& hi, bf16x8& lo) {
+  u32x4 h, l;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    h[i] = pack_bf16x2(x[o + 2 * i], x[o + 2 * i + 1]);
+    l[i] = pack_bf16x2(x[o + 2 * i] - bf16_lo_to_f32(h[i]), x[o + 2 * i + 1] - bf16_hi_to_f32(h[i]));
+  }
+  hi = __builtin_bit_cast(bf16x8, h);
+  lo = __builtin_bit_cast(bf16x8, l);
 }
 
 

@@ -52,15 +52,6 @@ struct G256Cfg {
   static_assert(TOTAL <= 160 * 1024, "LDS");
 };
 
-// Transposed MFMA operand of a row-major bf16 array with lanes <-> 32 columns col0 + lane % 32 and registers <-> the
-// rows in the order in which a 32 x 32 score accumulator holds its keys: registers 0..3 <-> rows row0 + 4 (lane / 32)
-// + 0..3, registers 4..7 <-> rows row0 + 8 + 4 (lane / 32) + 0..3.
-__device__ __forceinline__ bf16x8 tr_operand_acc_order(const uint16_t* base, int stride, int row0, int col0, int lane) {
-  const int j = lane & 15;
-  const uint16_t* p = base + (row0 + 4 * (lane >> 5) + (j >> 2)) * stride + col0 + 16 * ((lane >> 4) & 1) + 4 * (j & 3);
-  return cat4(lds_tr4(p), lds_tr4(p + 8 * stride));
-}
-
 }  // namespace
 
 // Keeps the compiler from moving memory operations across this point: the unrolled epilogue would otherwise

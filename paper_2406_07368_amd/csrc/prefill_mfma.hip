@@ -93,16 +93,20 @@ size_t prefill_grouped256_workspace_bytes(int BH, int d, int nseg) {
 // grouped: the three-branch form, whose groups are exactly `chunk` tokens, 64 or 256 (segments start on
 // group boundaries, so the first pass and the prefix sum are the same for both forms; groups of 256 have a
 // kernel of their own for the full pass).
-hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st) {
+hipError_t launch_segment_scan(const PrefillArgs& a, int d, hipStream_t st) {
   const int BH = a.B * a.H * a.m;             // heads the kernels see: one per value block
+  const int slot = d * d + d;
+  const dim3 grid((unsigned)((slot + 255) / 256), (unsigned)BH);
+  if (d == 128) hipLaunchKernelGGL((segment_scan_kernel<128>), grid, dim3(256), 0, st, a);
+  else hipLaunchKernelGGL((segment_scan_kernel<64>), grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st) {
   hipError_t e;
   if (a.nseg > 1) {
     if ((e = launch_prefill_mfma_ws(a, d, true, false, st)) != hipSuccess) return e;
-    const int slot = d * d + d;
-    const dim3 grid((unsigned)((slot + 255) / 256), (unsigned)BH);
-    if (d == 128) hipLaunchKernelGGL((segment_scan_kernel<128>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((segment_scan_kernel<64>), grid, dim3(256), 0, st, a);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = launch_segment_scan(a, d, st)) != hipSuccess) return e;
   }
   if (grouped && chunk == 256) return launch_prefill_grouped256(a, d, st);
   return launch_prefill_mfma_ws(a, d, false, grouped, st);

@@ -150,6 +150,17 @@ def random_state(wl: Workload, tokens: int, seed: int | None = None):
     return S, z, hist
 
 
+def upstream_gradient(shape, io_dtype: str, seed: int) -> np.ndarray:
+    """Seeded stand-in for d loss / d out of a training step: N(0, 1), exactly representable in ``io_dtype``."""
+    return round_to_io(np.random.default_rng(seed).standard_normal(shape), io_dtype)
+
+
+def upstream_gradient_tensor(wl: Workload, seed: int | None = None):
+    """Full-size variant (torch CPU tensor in the i/o dtype, ``torch.Generator``), shape of the outputs of ``wl``."""
+    g = torch.Generator(device="cpu").manual_seed((wl.seed if seed is None else seed) + 7919)
+    return torch.randn((wl.B, wl.H, wl.L, wl.d_v or wl.d), generator=g, dtype=torch.float32).to(torch_dtype(wl.io_dtype))
+
+
 def prefill_tensors(wl: Workload, seed: int | None = None):
     """Full-size variant of ``prefill_inputs``: torch CPU tensors already in the i/o dtype.
 

@@ -127,6 +127,38 @@ def test_prefill_grouped_rejects_bad_arguments():
     assert grouped_status(few, L=4096, ws=None, ws_bytes=0) == 6
 
 
+def backward_status(desc, L=256, alpha=1.0, **over):
+    lib = binding.load()
+    a = dict(q=P, k=P, v=P, conv_w=P, dout=P, dq=P, dk=P, dv=P, dw=P, ws=P, ws_bytes=1 << 40)
+    a.update(over)
+    return lib.linattn_prefill_grouped_backward(ctypes.byref(desc) if desc is not None else None, L, alpha, a["q"], a["k"],
+                                                a["v"], a["conv_w"], a["dout"], a["dq"], a["dk"], a["dv"], a["dw"], a["ws"],
+                                                a["ws_bytes"], None)
+
+
+def test_prefill_grouped_backward_rejects_bad_arguments():
+    d = good_desc(chunk=256)
+    assert backward_status(None) == 1
+    assert backward_status(d, L=-1) == 2
+    assert backward_status(d, alpha=float("nan")) == 2
+    assert backward_status(d, dout=None) == 1
+    assert backward_status(d, dk=None) == 1
+    assert backward_status(d, conv_w=None) == 1
+    assert backward_status(d, dq=P + 8) == 4
+    assert backward_status(d, dw=P + 4) == 4
+    assert backward_status(good_desc(chunk=128)) == 5                       # groups of 64 or 256
+    assert backward_status(good_desc(io_dtype=binding.LINATTN_F32)) == 5    # bf16 rows only
+    assert backward_status(binding.make_desc(2, 4, 64, 3, 64, L=256, d_v=128)) == 5   # d_v = d only
+    assert backward_status(good_desc(conv_k=64)) == 2
+    need = binding.linattn_backward_workspace_bytes(d, 256)
+    assert need > 2 * 2 * 4 * (128 * 128 + 128) * 4                         # two slots per group and head, and more
+    assert backward_status(d, ws=None, ws_bytes=0) == 6
+    assert backward_status(d, ws_bytes=need - 1) == 6
+    assert binding.linattn_backward_workspace_bytes(good_desc(io_dtype=binding.LINATTN_F32), 256) == 0
+    # the size grows with the number of groups, not faster
+    assert binding.linattn_backward_workspace_bytes(d, 2560) < 11 * need
+
+
 def vgrouped_status(desc, kk=4, alpha=1.0, **over):
     lib = binding.load()
     a = dict(q=P, k=P, v=P, conv_w=P, S=P, z=P, hist=P, kwin=P, vwin=P, fill=P, n_commit=None, out=P)
