@@ -473,8 +473,32 @@ def main():
                 row[key] = {"ms": {"mean": t_mean, "min": min(t_ms)}, "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3),
                             "roofline": {"bound": "hbm", "achieved": nb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                          "frac": nb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nb}}
+            # the training direction of the same shape (Sec. 5.3 times forward + backward): gradient of the three-branch
+            # form, dout seeded; algorithmic bytes = q, k, v, dout read, dq, dk, dv written
+            dout = torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev).to(torch.bfloat16)
+            dq, dk, dv = (torch.empty_like(q) for _ in range(3))
+            dw = torch.empty_like(fw)
+            bws_bytes = binding.linattn_backward_workspace_bytes(fdesc, wl.L)
+            bws = torch.empty(max(bws_bytes, 16), dtype=torch.uint8, device=dev)
+            evs = []
+            for i in range(10 + 30):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                binding.linattn_prefill_grouped_backward(fdesc, wl.L, 1.0, q, k, v, fw, dout, dq, dk, dv, dw, bws, bws_bytes, stream)
+                e1.record(stream)
+                if i >= 10:
+                    evs.append((e0, e1))
+            stream.synchronize()
+            t_ms = [a.elapsed_time(b) for a, b in evs]
+            t_mean = sum(t_ms) / len(t_ms)
+            nbb = 7 * wl.B * wl.H * wl.L * wl.d * 2
+            row["three_branch_backward"] = {"ms": {"mean": t_mean, "min": min(t_ms)}, "tokens_per_s": wl.B * wl.L / (t_mean * 1e-3),
+                                            "workspace_bytes": bws_bytes,
+                                            "roofline": {"bound": "hbm", "achieved": nbb / t_mean / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                                         "frac": nbb / t_mean / 1e6 / HBM_PEAK_GBS, "algorithmic_bytes": nbb}}
+            row["training_step_ms"] = row["three_branch"]["ms"]["mean"] + t_mean
             flash[name] = row
-            del q, k, v, out, fws
+            del q, k, v, out, fws, dout, dq, dk, dv, bws
         torch.cuda.empty_cache()
 
     wide = None

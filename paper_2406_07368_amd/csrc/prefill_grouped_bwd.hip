@@ -48,7 +48,8 @@ struct BwdCfg {
   static constexpr int REGION = ((ROWS > SREG ? (ROWS > STG ? ROWS : STG) : (SREG > STG ? SREG : STG)) + 15) / 16 * 16;
   static constexpr int OFF_Z = REGION;             // [D] float
   static constexpr int OFF_ST = OFF_Z + D * 4;     // [3][GT] float: per-token scalars
-  static constexpr int TOTAL = OFF_ST + 3 * GT * 4;
+  static constexpr int OFF_RED = OFF_ST + 3 * GT * 4;   // [NT] float: partial sums of the z passes
+  static constexpr int TOTAL = OFF_RED + NT * 4;
   static constexpr int SLOT = D * D + D;
   static_assert(TOTAL <= 160 * 1024, "LDS");
   static_assert(NT >= D, "one thread per feature in the z passes");
@@ -377,21 +378,42 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_gs_kernel(GroupedBwdArgs a
   load_rows2<D, GT>(gq, gdo, a.st, tok0, nt, Ql, Dl, tid);
   if (tid < GT) { fs[tid] = f3; dd[tid] = d4; }
   __syncthreads();
-  // gz[f] = sum_t phi(q_t[f]) dden_t
-  if (tid < D) {
+  // gz[f] = sum_t phi(q_t[f]) dden_t: thread = (feature, one of NT / D runs of tokens), eight independent terms in
+  // flight (one by one, every term would wait for its own LDS reads and exponential), the runs added up through LDS
+  {
+    constexpr int NP = G::NT / D, TPP = GT / NP;           // runs per feature, tokens per run
+    float* zp = reinterpret_cast<float*>(smem + G::OFF_RED);   // [NP][D]
+    const int f = tid % D, part = tid / D;
     float gz = 0.f;
-    for (int t = 0; t < nt; ++t) gz = fmaf(phi_f(bf16_bits_to_f32(Ql[t * G::KS + tid]), a.relu), dd[t], gz);
+#pragma unroll 8
+    for (int i = 0; i < TPP; ++i) {
+      const int t = part * TPP + i;                        // rows past the end are zero rows with weight 0
+      gz = fmaf(phi_f(bf16_bits_to_f32(Ql[t * G::KS + f]), a.relu), dd[t], gz);
+    }
+    zp[part * D + f] = gz;
+  }
+  __syncthreads();
+  if (tid < D) {
+    const float* zp = reinterpret_cast<const float*>(smem + G::OFF_RED);
+    float gz = 0.f;
+#pragma unroll
+    for (int p = 0; p < G::NT / D; ++p) gz += zp[p * D + tid];
     slot[D * D + tid] = gz;
   }
   // the tiles (feature block ib, channel block cb) over the waves; lanes = channels, registers = features.  The
   // operand (alpha / den_t) phi(q_t) is made from the raw rows as they are read (lane = feature, registers = tokens
   // 16ks + 8hi + 0..7) and enters as hi + lo: D.S v + D.z is again a difference of nearly equal parts.
+  // A wave takes a feature block and CBG channel blocks at a time, so that the operand made above serves several tiles.
+  constexpr int CBG = (G::CT * G::CT / G::NW) < 1 ? 1 : ((G::CT * G::CT / G::NW) > G::CT ? G::CT : (G::CT * G::CT / G::NW));
+  constexpr int UPB = G::CT / CBG;                         // units per feature block
 #pragma unroll 1
-  for (int tile = w; tile < G::CT * G::CT; tile += G::NW) {
-    const int ib = tile / G::CT, cb = tile % G::CT;
-    f32x16 sacc;
+  for (int unit = w; unit < G::CT * UPB; unit += G::NW) {
+    const int ib = unit / UPB, cb0 = (unit % UPB) * CBG;
+    f32x16 sacc[CBG];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+    for (int j = 0; j < CBG; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[j][r] = 0.f;
     for (int ks = 0; ks < GT / 16; ++ks) {
       const u32x4 raw = __builtin_bit_cast(u32x4, tr_operand(Ql, G::KS, 16 * ks, 32 * ib, lane));
       const float* fsp = fs + 16 * ks + 8 * hi;            // 0 for rows past the end
@@ -403,13 +425,19 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_gs_kernel(GroupedBwdArgs a
         ah[i] = pack_bf16x2(x0, x1);
         al[i] = pack_bf16x2(x0 - bf16_lo_to_f32(ah[i]), x1 - bf16_hi_to_f32(ah[i]));
       }
-      const bf16x8 dop = tr_operand(Dl, G::KS, 16 * ks, 32 * cb, lane);
-      sacc = mfma(__builtin_bit_cast(bf16x8, ah), dop, sacc);
-      sacc = mfma(__builtin_bit_cast(bf16x8, al), dop, sacc);
-    }
-    float* so = slot + (32 * ib + 4 * hi) * D + 32 * cb + l32;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) so[(8 * (r >> 2) + (r & 3)) * D] = sacc[r];
+      for (int j = 0; j < CBG; ++j) {
+        const bf16x8 dop = tr_operand(Dl, G::KS, 16 * ks, 32 * (cb0 + j), lane);
+        sacc[j] = mfma(__builtin_bit_cast(bf16x8, ah), dop, sacc[j]);
+        sacc[j] = mfma(__builtin_bit_cast(bf16x8, al), dop, sacc[j]);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < CBG; ++j) {
+      float* so = slot + (32 * ib + 4 * hi) * D + 32 * (cb0 + j) + l32;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) so[(8 * (r >> 2) + (r & 3)) * D] = sacc[j][r];
+    }
   }
 }
 
