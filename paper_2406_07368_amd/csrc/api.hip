@@ -257,7 +257,8 @@ BackwardPlan plan_backward(const linattn_desc* d, int32_t L) {
   p.off_D = round256(BH * (p.ng > 0 ? p.ng : 1) * slot * sizeof(float));
   p.off_stats = p.off_D + round256(BH * (p.ng > 0 ? p.ng : 1) * slot * sizeof(float));
   p.off_dw = p.off_stats + round256(5 * BH * (size_t)(L > 0 ? L : 1) * sizeof(float));
-  p.bytes = p.off_dw + round256(BH * (size_t)(p.nwb > 0 ? p.nwb : 1) * d->d * d->conv_k * sizeof(float));
+  // partial conv-weight sums, and as much again for the stages of their reduction
+  p.bytes = p.off_dw + 2 * round256(BH * (size_t)(p.nwb > 0 ? p.nwb : 1) * d->d * d->conv_k * sizeof(float));
   return p;
 }
 linattn_status check_backward(const linattn_desc* desc, int32_t L) {

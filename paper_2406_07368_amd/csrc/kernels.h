@@ -125,7 +125,8 @@ struct GroupedBwdArgs {
   float* Dg;                // [B*H][ng][d*d + d]: what a group's queries add to the gradient of the sums before it; after
                             // the suffix sum: the gradient with respect to the sums after the group
   float* stats;             // [5][B*H*L]: per token, largest logit (log2 units), 1 / sum of weights, pbar, alpha / den, d den
-  float* dw_part;           // [B*H][nwb][d*Kc]: conv-weight gradient of one block of tokens
+  float* dw_part;           // [H][B*nwb][d*Kc]: conv-weight gradient of one block of tokens; as much again behind it
+                            // for the stages of the sum over them
   int B, H, L, Kc;
   float eps;
   int relu;

@@ -709,7 +709,8 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_kernel(GroupedBwdArgs a) {
 #pragma unroll
   for (int j = 0; j < KMAX; ++j) red[(tg * D + c) * KMAX + j] = acc[j];
   __syncthreads();
-  float* part = a.dw_part + ((size_t)bh * a.nwb + blockIdx.x) * D * Kc;
+  // partial sums of a head lie together: [H][B * nwb][D * Kc]
+  float* part = a.dw_part + (((size_t)h * a.B + b) * a.nwb + blockIdx.x) * D * Kc;
   for (int e = tid; e < D * Kc; e += 256) {
     const int cc = e / Kc, j = e % Kc;
     float s = 0.f;
@@ -719,16 +720,19 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_kernel(GroupedBwdArgs a) {
   }
 }
 
-// dw[h][e] = sum over batch rows and token blocks, in a fixed order
-__global__ __launch_bounds__(256) void grouped_bwd_dw_reduce_kernel(GroupedBwdArgs a, int per_head) {
-  const int e = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y;
+// Sums over batch rows and token blocks in a fixed order, DW_RED partial sums at a time: in [H][n][per_head] ->
+// out [H][ceil(n / DW_RED)][per_head]; the last stage writes dconv_w (n = 0: zeros).
+namespace { constexpr int DW_RED = 32; }
+__global__ __launch_bounds__(256) void grouped_bwd_dw_reduce_kernel(const float* in, float* out, int n, int per_head) {
+  const int e = blockIdx.x * 256 + threadIdx.x, h = blockIdx.y, c = blockIdx.z;
   if (e >= per_head) return;
+  const int nout = (n + DW_RED - 1) / DW_RED;
+  const int i0 = c * DW_RED, i1 = (i0 + DW_RED) < n ? (i0 + DW_RED) : n;
+  const float* p = in + ((size_t)h * n + i0) * per_head + e;
   float s = 0.f;
-  for (int b = 0; b < a.B; ++b) {
-    const float* p = a.dw_part + ((size_t)(b * a.H + h) * a.nwb) * per_head + e;
-    for (int i = 0; i < a.nwb; ++i) s += p[(size_t)i * per_head];
-  }
-  a.dconv_w[(size_t)h * per_head + e] = s;
+#pragma unroll 8
+  for (int i = i0; i < i1; ++i, p += per_head) s += *p;
+  out[((size_t)h * (nout > 0 ? nout : 1) + c) * per_head + e] = s;
 }
 
 int grouped_bwd_dw_blocks(int L) { return (L + DW_TOK - 1) / DW_TOK; }
@@ -779,8 +783,22 @@ static hipError_t launch_bwd_dw(const GroupedBwdArgs& a, hipStream_t st) {
   if (a.nwb > 0) hipLaunchKernelGGL(kern, dim3((unsigned)a.nwb, (unsigned)(a.B * a.H)), dim3(256), LDS, st, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const int per_head = D * a.Kc;
-  hipLaunchKernelGGL(grouped_bwd_dw_reduce_kernel, dim3((unsigned)((per_head + 255) / 256), (unsigned)a.H), dim3(256), 0, st, a, per_head);
-  return hipGetLastError();
+  // stages of 32: the partial sums ping-pong between the two halves of the buffer until one row per head is left
+  const float* in = a.dw_part;
+  float* other = a.dw_part + (size_t)a.B * a.H * (a.nwb > 0 ? a.nwb : 1) * per_head;
+  int n = a.B * a.nwb;
+  for (;;) {
+    const int nout = (n + DW_RED - 1) / DW_RED;
+    float* out = nout <= 1 ? a.dconv_w : other;
+    hipLaunchKernelGGL(grouped_bwd_dw_reduce_kernel, dim3((unsigned)((per_head + 255) / 256), (unsigned)a.H, (unsigned)(nout > 0 ? nout : 1)),
+                       dim3(256), 0, st, in, out, n, per_head);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (nout <= 1) break;
+    other = const_cast<float*>(in);
+    in = out;
+    n = nout;
+  }
+  return hipSuccess;
 }
 
 // The kernels of this file, in order.
