@@ -55,11 +55,17 @@ struct BwdCfg {
   static_assert(NT >= D, "one thread per feature in the z passes");
 };
 
-__device__ __forceinline__ float phi_f(float x, int relu) { return relu ? fmaxf(x, 0.f) : phi_elu1_max(x); }
-// phi'(x): 1 above zero; below, exp(x) for elu + 1 and 0 for max(x, 0)
+// phi(x) and phi'(x) without a branch on the feature map (a branch per element would cut the unrolled loops into
+// pieces): with one = 1 for elu + 1 and 0 for max(x, 0), phi = max(x + one, one * min(exp(x), 1)) and
+// phi' = 1 above zero, one * exp(x) below.
+__device__ __forceinline__ float phi_f(float x, int relu) {
+  const float one = relu ? 0.f : 1.f;
+  const float e = __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(x * 1.44269504088896340736f), 0.f, 1.f);
+  return fmaxf(x + one, one * e);
+}
 __device__ __forceinline__ float dphi_f(float x, int relu) {
-  const float e = relu ? 0.f : __builtin_amdgcn_exp2f(x * 1.44269504088896340736f);
-  return x > 0.f ? 1.f : e;
+  const float one = relu ? 0.f : 1.f;
+  return x > 0.f ? 1.f : one * __builtin_amdgcn_exp2f(x * 1.44269504088896340736f);
 }
 
 // rows tok0 .. tok0 + GT - 1 of two tensors -> LDS (rows past the end are zero rows); every request before the first store
@@ -262,7 +268,9 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int kl = 8 * (r >> 2) + 4 * hi + (r & 3);
-      const float p = (kt < w || kl <= l32) ? __builtin_amdgcn_exp2f(fmaf(acc[r], to_log2, -mlog2)) * inv_mass : 0.f;
+      // (the mask as a select on the exponent, exp2(-inf) = 0: a branch per element would cut the loop into pieces)
+      const float arg = (kt < w || kl <= l32) ? fmaf(acc[r], to_log2, -mlog2) : -INFINITY;
+      const float p = __builtin_amdgcn_exp2f(arg) * inv_mass;
       acc[r] = p * (dpa[r] - pbar) * inv_sqrt_d;
     }
     // ds enters as hi + lo (two bf16 terms): with one term its rounding, met by cancelling products, is the largest
@@ -535,7 +543,8 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
     for (int r = 0; r < 16; ++r) {
       const int tl = 8 * (r >> 2) + 4 * hi + (r & 3);
       const int t = 32 * qt + tl;
-      sc[r] = (qt > w || tl >= l32) ? __builtin_amdgcn_exp2f(fmaf(sc[r], to_log2, -ml[t])) * il[t] : 0.f;
+      const float arg = (qt > w || tl >= l32) ? fmaf(sc[r], to_log2, -ml[t]) : -INFINITY;   // a select, not a branch
+      sc[r] = __builtin_amdgcn_exp2f(arg) * il[t];
     }
     if (role == 0) {                                       // dV^T += dO^T P
       bf16x8 p0, p0l, p1, p1l;                             // the weights as hi + lo too
@@ -583,6 +592,9 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
     load_slot<D, GT>(slot, Sl, zl, tid);
     __syncthreads();
     if (role == 0) {                                       // dV^T += D.S^T phi(K)^T
+      bf16x8 fko[G::KSD];
+#pragma unroll
+      for (int ks = 0; ks < G::KSD; ++ks) fko[ks] = __builtin_bit_cast(bf16x8, phi_pack8(kop[ks], a.relu));
 #pragma unroll
       for (int ct = 0; ct < G::CT; ++ct) {
         f32x16 lin;
@@ -590,9 +602,8 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
         for (int r = 0; r < 16; ++r) lin[r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < G::KSD; ++ks) {
-          const bf16x8 fk = __builtin_bit_cast(bf16x8, phi_pack8(kop[ks], a.relu));
-          lin = mfma(tr_operand(Sl, G::SS, 16 * ks, 32 * ct, lane), fk, lin);
-          lin = mfma(tr_operand(Sl + D * G::SS, G::SS, 16 * ks, 32 * ct, lane), fk, lin);
+          lin = mfma(tr_operand(Sl, G::SS, 16 * ks, 32 * ct, lane), fko[ks], lin);
+          lin = mfma(tr_operand(Sl + D * G::SS, G::SS, 16 * ks, 32 * ct, lane), fko[ks], lin);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc4[ct][r] += lin[r];
