@@ -89,6 +89,27 @@ __device__ __forceinline__ u32x4 phi_pack8(u32x4 x, int relu) {
   return y;
 }
 
+// The same without a branch on the feature map: with one = 1 for elu + 1 and 0 for max(x, 0), phi(x) =
+// max(x + one, one * min(exp(x), 1)).  For callers inside unrolled loops, where a branch per call would cut the loop
+// into basic blocks with a full wait at the end of each.
+__device__ __forceinline__ float phi_nb(float x, float one) {
+  return fmaxf(x + one, one * __builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(x * 1.44269504088896340736f), 0.f, 1.f));
+}
+__device__ __forceinline__ u32x4 phi_pack8_nb(u32x4 x, float one) {
+  u32x4 y;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) y[i] = pack_bf16x2(phi_nb(bf16_lo_to_f32(x[i]), one), phi_nb(bf16_hi_to_f32(x[i]), one));
+  return y;
+}
+__device__ __forceinline__ void phi_split8_nb(u32x4 x, float one, u32x4& hi, u32x4& lo) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float f0 = phi_nb(bf16_lo_to_f32(x[i]), one), f1 = phi_nb(bf16_hi_to_f32(x[i]), one);
+    hi[i] = pack_bf16x2(f0, f1);
+    lo[i] = pack_bf16x2(f0 - bf16_lo_to_f32(hi[i]), f1 - bf16_hi_to_f32(hi[i]));
+  }
+}
+
 // phi on four packed bf16 pairs as the sum of two bf16 terms: hi = bf16(phi(x)), lo = bf16(phi(x) - hi).
 // phi(x) = x + 1 of a bf16 x needs more significant bits than one bf16 has; hi + lo carries sixteen, so a
 // product (hi + lo) * v that enters the fp32 state is off by 2^-17 of itself instead of 2^-9.  max(x, 0)

@@ -243,7 +243,7 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
     float dz = 0.f;
 #pragma unroll
     for (int ks = 0; ks < G::KSD; ++ks) {
-      const u32x4 f = phi_pack8(qraw[ks], a.relu);
+      const u32x4 f = phi_pack8_nb(qraw[ks], a.relu ? 0.f : 1.f);
       fq[ks] = __builtin_bit_cast(bf16x8, f);
       const float* zp = zl + 16 * ks + 8 * hi;
 #pragma unroll
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
       for (int e = tid; e < GT * (D / 8); e += G::NT) {
         const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
         u32x4* p8 = reinterpret_cast<u32x4*>(Kl + r * G::KS + c0);
-        u32x4 f = phi_pack8(*p8, a.relu);
+        u32x4 f = phi_pack8_nb(*p8, a.relu ? 0.f : 1.f);
         if (r >= nt) f = u32x4{0, 0, 0, 0};                // phi(0) = 1: rows that do not exist stay zero rows
         *p8 = f;
       }

@@ -137,8 +137,8 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   for (int m = 0; m < G::QP; ++m) {
     const int piece = tid + G::NT * m;
     const int dj = piece / (D / 8), di0 = 8 * (piece % (D / 8));
-    u32x4 qp = phi_pack8(rq[m], a.relu), kp;
-    phi_split8(rk[m], a.relu, kp, kl[m]);
+    u32x4 qp = phi_pack8_nb(rq[m], a.relu ? 0.f : 1.f), kp;
+    phi_split8_nb(rk[m], a.relu ? 0.f : 1.f, kp, kl[m]);
     if (dj >= n) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; kl[m] = u32x4{0, 0, 0, 0}; }
     u32x2* qrow = reinterpret_cast<u32x2*>(sm.q + dj * G::QS + di0);
     qrow[0] = u32x2{qp[0], qp[1]};
