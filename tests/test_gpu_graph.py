@@ -145,3 +145,37 @@ def test_three_branch_generation_replays_as_a_graph():
         for a, b in zip(graph_state, eager_state):
             assert torch.equal(a, b), f"replay {replay}: state differs from the eager calls"
     assert int(graph_state[5].min()) < 40                 # some groups were completed and re-opened
+
+
+def test_training_step_replays_as_a_graph():
+    """Forward and gradient of the three-branch form (groups of 256, 63 taps: a dozen launches and two workspaces)
+    captured once and replayed, outputs and workspaces cleared between the replays."""
+    wl = workloads.CONFIGS["flash_L1024"]
+    q, k, v, w = workloads.prefill_tensors(wl)
+    gq, gk, gv, gw = q.cuda(), k.cuda(), v.cuda(), w.cuda()
+    gdo = workloads.upstream_gradient_tensor(wl).cuda()
+    desc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, BF, L=wl.L)
+    nf, nb = binding.linattn_workspace_bytes(desc, wl.L), binding.linattn_backward_workspace_bytes(desc, wl.L)
+    wsf, wsb = torch.empty(nf, dtype=torch.uint8, device="cuda"), torch.empty(nb, dtype=torch.uint8, device="cuda")
+    mk = lambda: [torch.empty_like(gq) for _ in range(4)] + [torch.empty_like(gw)]
+    want, got = mk(), mk()
+
+    def call(dst):
+        out, dq, dk, dv, dw = dst
+        binding.linattn_prefill_grouped(desc, wl.L, 1.0, gq, gk, gv, gw, None, None, None, out, None, None, None, wsf, nf)
+        binding.linattn_prefill_grouped_backward(desc, wl.L, 1.0, gq, gk, gv, gw, gdo, dq, dk, dv, dw, wsb, nb)
+    call(want)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        call(got)
+    for replay in range(3):
+        for t in got:
+            t.zero_()
+        wsf.zero_()
+        wsb.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), f"replay {replay} differs from the eager call"

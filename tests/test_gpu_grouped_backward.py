@@ -88,6 +88,19 @@ def test_gradient_is_reproducible_bit_for_bit():
         assert np.array_equal(a[name], b[name]), name
 
 
+def test_conv_weight_gradient_not_wanted():
+    """dconv_w = NULL: the other three gradients are the same bits, and the conv-weight pass does not run."""
+    q, k, v, w, dout = case(9500, 2, 2, 300, 64, 5)
+    bf = torch.bfloat16
+    args = (dev(q, bf), dev(k, bf), dev(v, bf), dev(w), dev(dout, bf))
+    with_dw = binding.prefill_grouped_backward(*args, group=64)
+    without = binding.prefill_grouped_backward(*args, group=64, want_dw=False)
+    torch.cuda.synchronize()
+    assert without[3] is None
+    for a, b in zip(with_dw[:3], without[:3]):
+        assert torch.equal(a, b)
+
+
 def test_no_tokens():
     bf = torch.bfloat16
     empty = torch.empty((2, 3, 0, 128), dtype=bf, device="cuda")
