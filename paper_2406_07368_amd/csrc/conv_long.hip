@@ -7,7 +7,7 @@
 // fit next to their row buffers, and 63 taps per output are a vector-ALU workload of the size of the attention
 // itself.  So long kernels are register-blocked here instead: a thread owns one channel, holds its taps in
 // registers and slides over 8 outputs at a time, every value row read from LDS feeding up to 8 multiply-adds.
-// One workgroup = 64 tokens of one (b, h); rows t0-62 .. t0+63 of V are staged in LDS as fp32.
+// One workgroup = 64 tokens of one (b, h); rows t0-62 .. t0+63 of V are staged in LDS as they lie in memory.
 #include "common.h"
 #include "kernels.h"
 
@@ -28,7 +28,11 @@ static __device__ __forceinline__ float elem_to_f32(uint16_t x) { return bf16_bi
 
 template <typename Io, int D, int KMAX>
 __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
-  extern __shared__ float xs[];   // [CL_HALO + CL_TOK][D]
+  // the value rows [CL_HALO + CL_TOK][D] as they lie in memory (bf16 rows stay bf16: half the LDS of fp32 rows, so
+  // twice the workgroups per compute unit); before them, for a moment, the taps as fp32
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_cl[];
+  float* xs = reinterpret_cast<float*>(smem_cl);
+  typename Io::elem* xe = reinterpret_cast<typename Io::elem*>(smem_cl);
   constexpr int NG = 256 / D;                 // token groups of threads
   constexpr int TPT = CL_TOK / NG;            // tokens per thread
   const int tid = threadIdx.x;
@@ -68,15 +72,17 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       have[i] = in_seq || in_hist;
     }
   };
-  // what the attention kernels left in out for this thread's tokens, as it lies in memory (converted where it is
-  // added to); past the end: the last token's element, never stored
-  typename Io::elem prev[TPT];
-  auto issue_prev = [&]() __attribute__((always_inline)) {
+  // what the attention kernels left in out, as it lies in memory (converted where it is added to), eight tokens at a
+  // time: the first eight with the first requests, the next eight while the current ones are being computed (all 32
+  // at once would cost the registers that let a second and third workgroup share the compute unit).  Past the end: the
+  // first token's element, never stored.
+  typename Io::elem prev[CL_BLK];
+  auto issue_prev = [&](int blk8, typename Io::elem (&dst)[CL_BLK]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int e = 0; e < TPT; ++e) {
-      const int tok = t0 + tg * TPT + e;
+    for (int e = 0; e < CL_BLK; ++e) {
+      const int tok = t0 + tg * TPT + blk8 * CL_BLK + e;
       const int mt = tok < L ? (a.rev ? L - 1 - tok : tok) : 0;
-      prev[e] = static_cast<const typename Io::elem*>(a.out)[base + (int64_t)mt * a.st + c];
+      dst[e] = static_cast<const typename Io::elem*>(a.out)[base + (int64_t)mt * a.st + c];
     }
   };
   float wreg[KMAX];
@@ -90,13 +96,13 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       const int e = tid + 256 * i;
       wt[i] = wsrc[e < D * Kc / 4 ? e : D * Kc / 4 - 1];   // unconditional: a branch would end in a full wait
     }
-    issue_rows();                             // the value rows and what is already in out are on their way
-    issue_prev();                             // while the taps make their trip through LDS
+    issue_rows();                             // the value rows are on their way while the taps make their trip through LDS
 #pragma unroll
     for (int i = 0; i < WIT; ++i) {
       const int e = tid + 256 * i;
       if (e < D * Kc / 4) *reinterpret_cast<f32x4*>(xs + 4 * e) = wt[i];
     }
+    issue_prev(0, prev);                      // ... and the first of what is already in out
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) wreg[j] = j < Kc ? xs[c * Kc + j] : 0.f;
@@ -109,10 +115,9 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       const int e = tid + 256 * i;
       const int row = e / (D / 8), i0 = 8 * (e % (D / 8));
       if (e < (CL_HALO + CL_TOK) * (D / 8)) {
-        float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (have[i]) Io::unpack8(raw[i], x);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) xs[row * D + i0 + j] = x[j];
+        typename Io::raw8 y = raw[i];
+        if (!have[i]) y = typename Io::raw8{};
+        *reinterpret_cast<typename Io::raw8*>(xe + row * D + i0) = y;
       }
     }
   }
@@ -123,14 +128,16 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   for (int blk8 = 0; blk8 < TPT / CL_BLK; ++blk8) {
     const int tb0 = tg * TPT + blk8 * CL_BLK;
     float acc[CL_BLK];
+    typename Io::elem next[CL_BLK];
+    issue_prev(blk8 + 1 < TPT / CL_BLK ? blk8 + 1 : blk8, next);
 #pragma unroll
     for (int e = 0; e < CL_BLK; ++e) acc[e] = 0.f;
     // value rows from the newest output's own row backwards: row m feeds output e through tap e - 7 + m
-    const float* newest = xs + (CL_HALO + tb0 + CL_BLK - 1) * D + c;
+    const typename Io::elem* newest = xe + (CL_HALO + tb0 + CL_BLK - 1) * D + c;
     // (fully unrolled, so that every tap index is a constant and the taps stay in registers)
 #pragma unroll
     for (int m = 0; m < KMAX + CL_BLK - 1; ++m) {
-      const float x = newest[-m * D];
+      const float x = elem_to_f32(newest[-m * D]);
 #pragma unroll
       for (int e = 0; e < CL_BLK; ++e) {
         constexpr int J0 = -(CL_BLK - 1);
@@ -143,9 +150,8 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       const int tok = t0 + tb0 + e;
       if (tok < L) Io::store1(a.out, base + (int64_t)(a.rev ? L - 1 - tok : tok) * a.st + c, elem_to_f32(prev[e]) + acc[e]);
     }
-    // the next block's elements move to the front (constant register indices in a loop that is not unrolled)
 #pragma unroll
-    for (int e = 0; e + CL_BLK < TPT; ++e) prev[e] = prev[e + CL_BLK];
+    for (int e = 0; e < CL_BLK; ++e) prev[e] = next[e];
   }
 }
 
@@ -195,7 +201,8 @@ __global__ __launch_bounds__(256) void conv_long_hist_kernel(ConvLongArgs a) {
 
 template <typename Io, int D, int KMAX>
 static hipError_t launch_cl_k(const ConvLongArgs& a, hipStream_t st) {
-  constexpr int LDS = (CL_HALO + CL_TOK) * D * (int)sizeof(float);
+  constexpr int LDS_ROWS = (CL_HALO + CL_TOK) * D * (int)sizeof(typename Io::elem), LDS_TAPS = D * KMAX * (int)sizeof(float);
+  constexpr int LDS = LDS_ROWS > LDS_TAPS ? LDS_ROWS : LDS_TAPS;
   auto kern = conv_long_kernel<Io, D, KMAX>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (e != hipSuccess) return e;
