@@ -232,11 +232,11 @@ def main():
     # Whatever --warmup says, untimed steps go on until the duration of the dominant launch has settled:
     # a GPU that was idle runs its first launches at boost clock, is then pulled down hard by the power
     # management and recovers over some tens of launches.  Settled = every duration of the last window lies
-    # within +-5 % of the window's median, and that median differs by at most 2 % from the median of the window
-    # before (the recovery is a slow drift that a single window does not show).  The unsettled figures are
-    # reported beside the settled ones.
+    # within +-5 % of the window's median, and the medians of the last three windows differ by at most 1 % from
+    # one to the next (the recovery is a slow drift, about 1 % per window towards its end, that two windows do
+    # not show).  The unsettled figures are reported beside the settled ones.
     settle_name = "prefill" if do_prefill else "verify8"
-    settle_steps, settle_hist, prev_med = 0, [], None
+    settle_steps, settle_hist, meds = 0, [], []
     while settle_steps < SETTLE_CAP:
         n0 = len(ev[settle_name])
         for i in range(SETTLE_WINDOW):
@@ -246,9 +246,10 @@ def main():
         last = [a.elapsed_time(b) for a, b in ev[settle_name][n0:]]
         settle_hist.extend(last)
         med = float(np.median(last))
-        if prev_med is not None and abs(med - prev_med) <= 0.02 * med and max(abs(t - med) for t in last) <= 0.05 * med:
+        meds.append(med)
+        if (len(meds) >= 3 and abs(meds[-1] - meds[-2]) <= 0.01 * med and abs(meds[-2] - meds[-3]) <= 0.01 * med
+                and max(abs(t - med) for t in last) <= 0.05 * med):
             break
-        prev_med = med
     # the timed region follows at once (an idle gap of a few milliseconds would send the clock through its hump
     # again): the settling records stay in the lists and are skipped when the durations are read
     n_settled = {name: len(lst) for name, lst in ev.items()}
@@ -604,7 +605,7 @@ def main():
         "value": None, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "settle_steps": settle_steps,
         "settle": {"kernel": settle_name, "rule": f"untimed steps in windows of {SETTLE_WINDOW} until every duration of a window lies within 5 % "
-                                                  f"of its median and the median within 2 % of the previous window's (at most {SETTLE_CAP})",
+                                                  f"of its median and the medians of three windows in a row within 1 % of each other (at most {SETTLE_CAP})",
                    "unsettled_ms": {"first": settle_hist[0], "max": max(settle_hist), "mean_first_window": float(np.mean(settle_hist[:SETTLE_WINDOW]))},
                    "settled_window_ms": float(np.median(settle_hist[-SETTLE_WINDOW:])),
                    "window_medians_ms": [float(np.median(settle_hist[i:i + SETTLE_WINDOW])) for i in range(0, len(settle_hist), SETTLE_WINDOW)]},
