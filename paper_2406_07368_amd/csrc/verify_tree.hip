@@ -70,7 +70,10 @@ static_assert(sizeof(VtSmem<128>::q) + sizeof(VtSmem<128>::p) >= sizeof(VtSmem<1
 
 }  // namespace
 
-template <int D>
+// KCM: tap capacity of the instantiation (3, 5 or 8; taps beyond Kc are zeros in LDS and their rows are valid rows):
+// the epilogue's loops over the taps are straight-line code -- a test of the tap count per tap and channel group cut
+// them into sixty basic blocks, each with a full wait at its end.
+template <int D, int KCM>
 __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a) {
   using G = VtCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -294,7 +297,7 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
     for (int ib = 0; ib < G::IB; ++ib) {
 #pragma unroll
       for (int ks = 0; ks < G::KSC; ++ks) {
-        if (16 * ks < n) {                               // uniform
+        {                                                // (candidates that do not exist are not on the path: masked)
           u32x4 keep;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
@@ -332,15 +335,13 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
       for (int g = 0; g < 4; ++g) {
         float u[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          if (t < Kc) {
-            const f32x4 wv4 = *reinterpret_cast<const f32x4*>(wrow + t * D + 8 * g);
-            const u32x2 x = *reinterpret_cast<const u32x2*>(sm.v + rows[t] * G::VS + 32 * w + 4 * hi + 8 * g);
-            u[0] = fmaf(wv4[0], bf16_lo_to_f32(x[0]), u[0]);
-            u[1] = fmaf(wv4[1], bf16_hi_to_f32(x[0]), u[1]);
-            u[2] = fmaf(wv4[2], bf16_lo_to_f32(x[1]), u[2]);
-            u[3] = fmaf(wv4[3], bf16_hi_to_f32(x[1]), u[3]);
-          }
+        for (int t = 0; t < KCM; ++t) {
+          const f32x4 wv4 = *reinterpret_cast<const f32x4*>(wrow + t * D + 8 * g);
+          const u32x2 x = *reinterpret_cast<const u32x2*>(sm.v + rows[t] * G::VS + 32 * w + 4 * hi + 8 * g);
+          u[0] = fmaf(wv4[0], bf16_lo_to_f32(x[0]), u[0]);
+          u[1] = fmaf(wv4[1], bf16_hi_to_f32(x[0]), u[1]);
+          u[2] = fmaf(wv4[2], bf16_lo_to_f32(x[1]), u[2]);
+          u[3] = fmaf(wv4[3], bf16_hi_to_f32(x[1]), u[3]);
         }
         *reinterpret_cast<u32x2*>(orow + 8 * g) =
             u32x2{pack_bf16x2(fmaf(o[tb][4 * g], inv, u[0]), fmaf(o[tb][4 * g + 1], inv, u[1])),
@@ -363,9 +364,9 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   }
 }
 
-template <int D>
+template <int D, int KCM>
 static hipError_t launch_vt(const VerifyTreeArgs& a, hipStream_t st) {
-  auto kern = verify_tree_kernel<D>;
+  auto kern = verify_tree_kernel<D, KCM>;
   constexpr int LDS = (int)sizeof(VtSmem<D>);
   static_assert(LDS <= 80 * 1024, "two workgroups per compute unit");
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -375,7 +376,8 @@ static hipError_t launch_vt(const VerifyTreeArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_verify_tree(const VerifyTreeArgs& a, int d, hipStream_t st) {
-  return d == 128 ? launch_vt<128>(a, st) : launch_vt<64>(a, st);
+  if (d == 128) return a.Kc <= 3 ? launch_vt<128, 3>(a, st) : a.Kc <= 5 ? launch_vt<128, 5>(a, st) : launch_vt<128, 8>(a, st);
+  return a.Kc <= 3 ? launch_vt<64, 3>(a, st) : a.Kc <= 5 ? launch_vt<64, 5>(a, st) : launch_vt<64, 8>(a, st);
 }
 
 }  // namespace linattn
