@@ -297,7 +297,7 @@ linattn_status linattn_verify_grouped(const linattn_desc *desc, int32_t kk, floa
  * of several candidates is computed once and the state is read once for all
  * of them.  Afterwards the state of batch row b has advanced over the root
  * path of candidate accept[b], oldest token first.
- *   q, k, v      in      [B,H,n,d] dense, bf16 (desc strides are ignored)
+ *   q, k, v      in      [B,H,n,d] dense, i/o dtype (desc strides are ignored)
  *   parent       in      device int32 [n], shared by all (b, h); an entry outside
  *                        -1..i-1 is read as -1
  *   conv_w       in      [H,d,Kc] float
@@ -305,9 +305,10 @@ linattn_status linattn_verify_grouped(const linattn_desc *desc, int32_t kk, floa
  *   accept       in      device int32 [B] or NULL; -1, NULL or an entry outside
  *                        0..n-1 accepts nothing and leaves that row's state
  *                        bit-unchanged
- *   out          out     [B,H,n,d] dense, bf16
- * 1 <= n <= LINATTN_MAX_TREE.  io_dtype must be LINATTN_BF16
- * (LINATTN_ERR_UNSUPPORTED otherwise). */
+ *   out          out     [B,H,n,d] dense, i/o dtype
+ * 1 <= n <= LINATTN_MAX_TREE.  bf16 candidates run on the matrix cores (bf16
+ * operands, fp32 accumulation), fp32 candidates in exact fp32 multiply-adds on the
+ * vector ALUs; d_v = d only (LINATTN_ERR_UNSUPPORTED otherwise). */
 linattn_status linattn_verify_tree(const linattn_desc *desc, int32_t n,
                                    const void *q, const void *k, const void *v,
                                    const int32_t *parent,

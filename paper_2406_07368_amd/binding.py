@@ -303,7 +303,7 @@ def verify_grouped(q, k, v, conv_w, state, alpha=1.0, n_commit=None, eps=0.0, st
 
 
 def verify_tree(q, k, v, parent, conv_w, state, accept=None, eps=0.0, stream=None, phi="elu1"):
-    """q, k, v: dense bf16 [B,H,n,d]; parent: int32 [n] on the GPU.  ``state`` is updated in place along the
+    """q, k, v: dense [B,H,n,d], bf16 or fp32; parent: int32 [n] on the GPU.  ``state`` is updated in place along the
     root path of candidate ``accept[b]`` (int32 [B] on the GPU; None accepts nothing).  Returns out."""
     B, H, n, d = q.shape
     desc = make_desc(B, H, d, conv_w.shape[2], 64, q.dtype, eps, L=n, phi=phi)

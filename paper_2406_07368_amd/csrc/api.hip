@@ -391,14 +391,15 @@ linattn_status linattn_verify_tree(const linattn_desc* desc, int32_t n, const vo
   for (const void* p : ptrs)
     if (!aligned16(p)) return LINATTN_ERR_ALIGN;
   if ((reinterpret_cast<uintptr_t>(parent) & 3u) || (reinterpret_cast<uintptr_t>(accept) & 3u)) return LINATTN_ERR_ALIGN;
-  if (desc->io_dtype != LINATTN_BF16) return LINATTN_ERR_UNSUPPORTED;   // the tree kernel exists for bf16 candidates only
   if (value_blocks(desc) > 1) return LINATTN_ERR_UNSUPPORTED;
 
   VerifyTreeArgs a{};
   a.q = q; a.k = k; a.v = v; a.conv_w = conv_w; a.S = S; a.z = z; a.hist = hist;
   a.parent = parent; a.accept = accept; a.out = out;
   a.B = desc->B; a.H = desc->H; a.n = n; a.Kc = desc->conv_k; a.eps = desc->eps; a.relu = desc->phi == LINATTN_PHI_RELU;
-  const hipError_t e = launch_verify_tree(a, desc->d, static_cast<hipStream_t>(hip_stream));
+  // bf16 candidates on the matrix cores; fp32 candidates in exact fp32 on the vector ALUs
+  const hipError_t e = desc->io_dtype == LINATTN_BF16 ? launch_verify_tree(a, desc->d, static_cast<hipStream_t>(hip_stream))
+                                                      : launch_verify_tree_simt(a, desc->d, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }
 

@@ -25,11 +25,11 @@ struct VerifyArgs {
 struct VerifyTreeArgs {
   const void* q;
   const void* k;
-  const void* v;            // [B,H,n,d] dense, bf16
+  const void* v;            // [B,H,n,d] dense, i/o dtype
   const float* conv_w;      // [H,d,Kc]
   float* S;                 // [B,H,d,d] in/out
   float* z;                 // [B,H,d]   in/out
-  void* hist;               // [B,H,Kc-1,d] in/out, bf16
+  void* hist;               // [B,H,Kc-1,d] in/out, i/o dtype
   const int32_t* parent;    // device [n]
   const int32_t* accept;    // device [B] or null
   void* out;                // [B,H,n,d]
@@ -154,6 +154,8 @@ hipError_t launch_verify_grouped_mfma(const VerifyGroupedArgs& a, int d, hipStre
 
 // verify_tree.hip : candidates arranged as a tree, scored from one read of the state
 hipError_t launch_verify_tree(const VerifyTreeArgs& a, int d, hipStream_t st);
+// verify_tree_simt.hip : the same for fp32 candidates, exact fp32 multiply-adds on the vector ALUs
+hipError_t launch_verify_tree_simt(const VerifyTreeArgs& a, int d, hipStream_t st);
 
 // prefill_simt.hip : fp32 arithmetic on the vector ALUs, one workgroup per (b, h)
 hipError_t launch_prefill_simt(const PrefillArgs& a, bool bf16, int d, hipStream_t st);

@@ -226,7 +226,7 @@ def test_verify_tree_rejects_bad_arguments():
     assert tree_status(d, S=P + 8) == 4
     assert tree_status(d, parent=P + 2) == 4
     assert tree_status(d, accept=P + 1) == 4
-    assert tree_status(good_desc(io_dtype=binding.LINATTN_F32)) == 5      # bf16 candidates only
+    assert tree_status(binding.make_desc(2, 4, 64, 3, 64, L=8, d_v=128)) == 5   # d_v = d only
     assert tree_status(good_desc(d=96)) == 2
     assert tree_status(good_desc(conv_k=63)) == 2
 

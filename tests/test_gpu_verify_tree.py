@@ -46,6 +46,44 @@ def test_tree_matches_oracle(d, n, Kc):
     assert np.array_equal(got[3][1], hist[1].astype(np.float64))
 
 
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("n,Kc", [(1, 3), (2, 1), (5, 2), (17, 3), (33, 5), (47, 8), (64, 3), (64, 8)])
+def test_tree_of_fp32_candidates_matches_oracle(d, n, Kc):
+    """fp32 candidates: exact fp32 multiply-adds on the vector ALUs, held to the fp32 bar."""
+    B, H = 3, 4
+    rng = np.random.default_rng(520 + n + d + Kc)
+    q, k, v, w, S, z, hist = make_case(620 + n + d, B, H, d, Kc, n, "f32", prefix=24)
+    parent = random_tree(rng, n)
+    accept = np.array([n - 1, -1, int(rng.integers(0, n))], dtype=np.int32)
+    want = oracle.verify_tree(q, k, v, parent, w, S, z, hist, accept, eps=1e-3)
+    state = (dev(S), dev(z), dev(hist))
+    out = binding.verify_tree(dev(q), dev(k), dev(v), torch.from_numpy(parent).cuda(), dev(w), state,
+                              torch.from_numpy(accept).cuda(), 1e-3)
+    torch.cuda.synchronize()
+    check(host(out), want[0], TOL["f32"], "out")
+    check(host(state[0]), want[1], STATE_TOL, "S")
+    check(host(state[1]), want[2], STATE_TOL, "z")
+    assert np.array_equal(host(state[2]), want[3]), "hist"
+    assert np.array_equal(host(state[0])[1], S[1].astype(np.float64))      # nothing accepted: bit-unchanged
+    assert np.array_equal(host(state[1])[1], z[1].astype(np.float64))
+
+
+def test_fp32_tree_that_is_a_chain_equals_plain_verify():
+    B, H, d, Kc, n = 4, 6, 128, 3, 11
+    q, k, v, w, S, z, hist = make_case(43, B, H, d, Kc, n, "f32", prefix=12)
+    chain = np.arange(n, dtype=np.int32) - 1
+    n_commit = (np.arange(B) * 3 % (n + 1)).astype(np.int32)
+    ts = (dev(S), dev(z), dev(hist))
+    tout = binding.verify_tree(dev(q), dev(k), dev(v), torch.from_numpy(chain).cuda(), dev(w), ts, torch.from_numpy(n_commit - 1).cuda())
+    vs = (dev(S), dev(z), dev(hist))
+    vout = binding.verify(dev(q), dev(k), dev(v), dev(w), vs, torch.from_numpy(n_commit).cuda())
+    torch.cuda.synchronize()
+    check(host(tout), host(vout), 1e-5, "out")
+    check(host(ts[0]), host(vs[0]), 1e-5, "S")
+    check(host(ts[1]), host(vs[1]), 1e-5, "z")
+    assert torch.equal(ts[2], vs[2])
+
+
 def test_chain_shaped_tree_equals_plain_verify_on_the_gpu():
     """parent[i] = i - 1: the same outputs and state as linattn_verify with n_commit = accept + 1."""
     B, H, d, Kc, n = 24, 32, 128, 3, 13           # whole heads: both calls run on the matrix cores
