@@ -88,6 +88,15 @@ def test_gradient_is_reproducible_bit_for_bit():
         assert np.array_equal(a[name], b[name]), name
 
 
+@pytest.mark.parametrize("group,L", [(64, 1536), (256, 3000)])
+def test_gradient_with_more_workgroups_than_the_chip_holds(group, L):
+    """48 heads x dozens of groups: every kernel of the call runs in several rounds, and the sums over the batch
+    rows that share a head's conv weights have six terms."""
+    q, k, v, w, dout = case(9600 + group, 6, 8, L, 128, 3, scale=0.5)
+    want = oracle.prefill_grouped_backward(q, k, v, w, dout, group, alpha=1.0, eps=0.0)
+    compare(run(q, k, v, w, dout, group, 1.0, 0.0), want, f"group={group} L={L}")
+
+
 def test_conv_weight_gradient_not_wanted():
     """dconv_w = NULL: the other three gradients are the same bits, and the conv-weight pass does not run."""
     q, k, v, w, dout = case(9500, 2, 2, 300, 64, 5)
