@@ -98,7 +98,7 @@ PrefillPlan plan_prefill(const linattn_desc* d, int32_t L, bool grouped = false)
   p.seg_len = L;
   const int heads = d->B * d->H * value_blocks(d);      // what the kernels see as heads: one per value block
   if (p.mfma && L > 0) {
-    p.nseg = g256 ? prefill_grouped256_pick_segments(heads, L) : prefill_mfma_pick_segments(heads, L, d->chunk);
+    p.nseg = g256 ? prefill_grouped256_pick_segments(heads, L) : prefill_mfma_pick_segments(heads, L, d->chunk, d->d);
     const int chunks = (L + d->chunk - 1) / d->chunk;
     const int cps = (chunks + p.nseg - 1) / p.nseg;
     p.seg_len = cps * d->chunk;

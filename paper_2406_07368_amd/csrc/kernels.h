@@ -172,7 +172,7 @@ hipError_t launch_grouped_bwd(const GroupedBwdArgs& a, int d, hipStream_t st);
 
 // prefill_mfma.hip : launch plan of the bf16 prefill (segments, prefix sum over segment states)
 hipError_t launch_segment_scan(const PrefillArgs& a, int d, hipStream_t st);   // the prefix sum alone
-int prefill_mfma_pick_segments(int BH, int L, int chunk);
+int prefill_mfma_pick_segments(int BH, int L, int chunk, int d);
 size_t prefill_mfma_workspace_bytes(int BH, int d, int nseg);
 hipError_t launch_prefill_mfma(const PrefillArgs& a, int d, int chunk, bool grouped, hipStream_t st);
 

@@ -52,13 +52,14 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(PrefillArgs a) {
   }
 }
 
-// Segments per (b, h): as many as keep all workgroups of the second pass resident at once (one per compute unit:
-// a workgroup takes most of a unit's LDS, so the 257th would wait for a whole segment), with at least 2 groups per
-// segment, and no segments at all for sequences of fewer than 8 groups, where a second launch costs more than it saves.
-int prefill_mfma_pick_segments(int BH, int L, int chunk) {
+// Segments per (b, h): as many as keep all workgroups of the second pass resident at once (at d = 128 one per compute
+// unit: a workgroup takes most of a unit's LDS, so the 257th would wait for a whole segment; at d = 64 two), with at
+// least 2 groups per segment, and no segments at all for sequences of fewer than 8 groups, where a second launch costs
+// more than it saves.
+int prefill_mfma_pick_segments(int BH, int L, int chunk, int d) {
   const int groups = (L + 63) / 64;            // the kernel walks groups of 64 tokens whatever `chunk` says
   const int chunks = (L + chunk - 1) / chunk;  // segments start on multiples of `chunk`
-  int want = 256 / BH;
+  int want = (d == 64 ? 512 : 256) / BH;
   int most = groups >= 8 ? groups / 2 : 1;
   if (most > chunks) most = chunks;
   if (want > most) want = most;

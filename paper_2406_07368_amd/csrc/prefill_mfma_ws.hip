@@ -74,7 +74,11 @@ struct WsCfg {
   static constexpr int OS = D + 4;           // output staging rows: 8-byte writes, one row per lane
   static constexpr int OFF_OST = OFF_WL + KCMAX * D * 4;   // [2][C][OS] bf16: finished output rows of a group
   static constexpr int OST = C * OS * 2;
-  static constexpr int NOST = GROUPED ? 1 : 2;             // staging buffers
+  // One staging buffer (emptied at the start of a step, before the signal the state waves wait for) or two (emptied
+  // half-way through the fill).  The three-branch form has no room for two; at d = 64 one buffer brings the
+  // workgroup under half of a compute unit's LDS, and two workgroups per unit are worth more than the later store.
+  static constexpr bool ONE_STAGE = GROUPED || D == 64;
+  static constexpr int NOST = ONE_STAGE ? 1 : 2;           // staging buffers
   static constexpr int OFF_ZOP = OFF_OST + NOST * OST;     // [NW][2][16] bf16: z as the MFMA operand of each feature block
   static constexpr int OFF_SYNC = OFF_ZOP + NW * 64;       // the counters of the front-end waves' and the state waves' signals
   static constexpr int TOTAL = OFF_SYNC + 16;
@@ -132,7 +136,7 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
   uint16_t* rawK = reinterpret_cast<uint16_t*>(smem + G::OFF_RK);
   auto bufK = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BK); };
   auto bufV = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + bi * G::BUF + G::BV); };   // row r = token r - HALO
-  auto bufO = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + G::OFF_OST + (GROUPED ? 0 : bi) * G::OST); };
+  auto bufO = [&](int bi) { return reinterpret_cast<uint16_t*>(smem + G::OFF_OST + (G::ONE_STAGE ? 0 : bi) * G::OST); };
 
   const int nseg_grid = STATE_ONLY ? a.nseg - 1 : a.nseg;
   // a workgroup is one (b, h, value block) -- or one segment of it; with d_v = d there is one block per head
@@ -590,14 +594,13 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       // ci - 1 stored.
       auto step = [&](int ci, auto set_tag, auto store_tag) __attribute__((always_inline)) {
         if (!STATE_ONLY) {
-          if constexpr (GROUPED) {
-            // the one staging buffer: group ci - 1 leaves before the state waves may write group ci
-            // (they wait for this step's signal first)
+          // the one staging buffer: group ci - 1 leaves before the state waves may write group ci
+          // (they wait for this step's signal first)
+          if constexpr (G::ONE_STAGE) {
             if (decltype(store_tag)::value) store_group(ci - 1, Full{});
-            scores_local(ci);
-          } else {
-            scores(ci);
           }
+          if constexpr (GROUPED) scores_local(ci);
+          else scores(ci);
           q_dot_z(ci);
           signal(sync_q);
           // the last HALO value rows of group ci become the rows before group ci + 1
@@ -613,6 +616,8 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
           // phi(Q), raw Q and raw K exist once: group ci + 1 may replace them when every front-end wave
           // has its scores of group ci and every state wave its products with phi(Q) (the fill waits)
           fill_group(ci + 1, set_tag, std::true_type{}, relu_tag);
+        } else if constexpr (G::ONE_STAGE) {
+          fill_group(ci + 1, set_tag, std::false_type{}, relu_tag);   // the store has happened already
         } else {
           fill_group(ci + 1, set_tag, store_tag, relu_tag);
         }
@@ -629,15 +634,14 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
       if (ci >= 1 && ci + 1 < nchunks) { step(ci, Set0{}, std::true_type{}); ++ci; }
       if (nchunks > 0) {                                 // ci == nchunks - 1: nothing left to fill
         if (!STATE_ONLY) {
-          if constexpr (GROUPED) {
+          if constexpr (G::ONE_STAGE) {
             if (ci > 0) store_group(ci - 1, Full{});
-            scores_local(ci);
-          } else {
-            scores(ci);
           }
+          if constexpr (GROUPED) scores_local(ci);
+          else scores(ci);
           q_dot_z(ci);
           signal(sync_q);
-          if (!GROUPED && ci > 0) store_group(ci - 1, Full{});
+          if (!G::ONE_STAGE && ci > 0) store_group(ci - 1, Full{});
         }
         __syncthreads();                                 // barrier C
       }
