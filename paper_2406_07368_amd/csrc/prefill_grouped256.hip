@@ -9,7 +9,7 @@
 // frozen for the group and take the group's own products in the same registers.  So this kernel is built the other
 // way round: one workgroup of eight waves per (b, h, segment) walks its groups with the whole group's raw key and
 // value rows in LDS (139 KB at d = 128) and the running state in its workspace slot in global memory (fp32; it stays
-// in the L2 cache between the group's read-out and its update).  Wave w owns the 32 queries 32w .. 32w+31 of the
+// in the L2 cache between the group's read-out and its update).  Every wave owns one 32-query tile of the
 // group and all value channels:
 //
 //   local branch    for each 32-key tile up to the diagonal: S^T tile = K Q^T (keys in registers, queries in lanes),
@@ -17,13 +17,14 @@
 //                   straight from the score accumulators as the MFMA operand -- the accumulator layout is the
 //                   operand layout up to a permutation of the key index, which is applied to the transposed reads
 //                   of V instead, so the weights never touch LDS;
-//   linear branch   O_lin^T = S_g^T phi(Q)^T, one 32-channel tile at a time, the state read from the workspace slot as
-//                   the MFMA operand (bf16, rounded for the read-out only, as in the other matrix-core kernels);
+//   linear branch   O_lin^T = S_g^T phi(Q)^T, one 32-channel tile at a time, the state before the group as the MFMA
+//                   operand (bf16 in LDS, rounded for the read-out only, as in the other matrix-core kernels);
 //   epilogue        O / l + alpha O_lin / (phi(q).z_g + eps), staged through LDS in fp32 (the key rows' memory); the
 //                   store loop adds the causal conv over V and writes whole rows.
 //
 // Then, unless nothing after the group needs it, the group enters the state: phi is applied to the key rows in
-// place and every wave adds two 32 x 32 tiles of phi(K)^T V to the slot.  Segments along the sequence start on group
+// place and every wave adds phi(K)^T V to its two 32 x 32 tiles of the state -- the tiles it read for the linear
+// branch -- and writes them back to the slot.  Segments along the sequence start on group
 // boundaries; their start states come from the same first pass and prefix sum as in the 64-token kernels.
 #include "common.h"
 #include "kernels.h"
@@ -47,8 +48,11 @@ struct G256Cfg {
   static constexpr int OFF_V = OFF_K + GT * KS * 2;                   // row r = token r - HALO
   static constexpr int OFF_W = (OFF_V + (HALO + GT) * VS * 2 + 15) / 16 * 16;   // [8][D] float conv taps, tap-major
   static constexpr int OFF_Z = OFF_W + 8 * D * 4;                     // [D] float: z before the group
-  static constexpr int TOTAL = OFF_Z + D * 4;
+  static constexpr int OFF_R = OFF_Z + D * 4;                         // [NW][D] float: per-wave column sums of phi(K)
+  static constexpr int TOTAL = OFF_R + NW * D * 4;
+  static constexpr int OB = D + 8;           // staged output rows, bf16, the whole group at once (no conv in the kernel)
   static_assert(128 * OS * 4 <= GT * KS * 2, "the staged outputs take the place of the key rows");
+  static_assert(GT * OB * 2 <= GT * KS * 2, "the staged bf16 outputs take the place of the key rows");
   static_assert(TOTAL <= 160 * 1024, "LDS");
 };
 
@@ -68,11 +72,14 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
   uint16_t* Vl = reinterpret_cast<uint16_t*>(smem + G::OFF_V);
   float* wl = reinterpret_cast<float*>(smem + G::OFF_W);
   float* zl = reinterpret_cast<float*>(smem + G::OFF_Z);
+  float* redl = reinterpret_cast<float*>(smem + G::OFF_R);
   float* Ol = reinterpret_cast<float*>(smem + G::OFF_K);   // staged output rows, once the key rows are done with
 
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
+  // Query tile j meets j + 1 key tiles.  Waves w and w + 4 share a SIMD: tiles (w, 7 - w) give every SIMD nine.
+  const int qtile = w < 4 ? w : 11 - w;
   const int bh = blockIdx.x / a.nseg, seg = blockIdx.x % a.nseg;
   const int b = bh / a.H, h = bh % a.H;
   const int t_begin = seg * a.seg_len;
@@ -116,9 +123,9 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
   for (int gi = 0; gi < ngroups; ++gi) {
     const int tok0 = t_begin + gi * GT;
     const int nt = (t_end - tok0) < GT ? (t_end - tok0) : GT;
-    // ---- 1. this wave's queries, straight into MFMA operand registers: lane = query 32w + l32, registers =
+    // ---- 1. this wave's queries, straight into MFMA operand registers: lane = query 32 qtile + l32, registers =
     //         features 16ks + 8hi + 0..7.  A query past the end reads the last row that exists; it is never stored.
-    const int qt = 32 * w + l32;
+    const int qt = 32 * qtile + l32;
     const int qrow = qt < nt ? qt : nt - 1;
     u32x4 qraw[G::KSD];
     {
@@ -126,86 +133,99 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
 #pragma unroll
       for (int ks = 0; ks < G::KSD; ++ks) qraw[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
     }
-    constexpr int SIT = D * D / 4 / G::NT;                 // 16-byte pieces of S per thread
-    u32x2 spk[SIT];                                        // ... rounded to bf16 once they have arrived
     // ---- 2. the group's raw key rows and value rows -> LDS (rows past the end are zero rows), the 8 value rows
-    //         before the group (earlier tokens, else the incoming history, else zeros), z before the group
-    //         (every request of the group is issued before the first one is waited for)
+    //         before the group (earlier tokens, else the incoming history, else zeros), z before the group.
+    //         Every request is issued without a condition -- a row past the end re-reads the last row that exists,
+    //         a history row that does not exist re-reads a row that does; the values are dropped afterwards --
+    //         because a load under a lane-dependent branch makes the compiler wait for all earlier ones first, and
+    //         the rows then arrive one round trip after the other.
     {
       constexpr int NPC = GT * (D / 8) / G::NT;            // 16-byte pieces of K (and of V) per thread
       constexpr int NHL = HALO * D / G::NT;                // elements of the 8 rows before the group per thread
       u32x4 kx[NPC], vx[NPC];
       uint16_t hx[NHL];
-      // the state before the group, for the linear branch: requested first (requests return in order, so it has
-      // arrived -- ahead of any update of the slot -- by the time the rows below are stored), kept in registers
-      // while the local branch runs
-      f32x4 sreg[SIT];
-#pragma unroll
-      for (int i = 0; i < SIT; ++i) sreg[i] = reinterpret_cast<const f32x4*>(slot)[tid + G::NT * i];
 #pragma unroll
       for (int i = 0; i < NPC; ++i) {
         const int e = tid + G::NT * i;
         const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
-        kx[i] = vx[i] = u32x4{0, 0, 0, 0};
-        if (r < nt) {
-          kx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gk + (int64_t)(tok0 + r) * a.st + c0));
-          vx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gv + (int64_t)(tok0 + r) * a.st + c0));
+        const int64_t off = (int64_t)(tok0 + (r < nt ? r : nt - 1)) * a.st + c0;
+        kx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gk + off));
+        vx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gv + off));
+      }
+      if constexpr (KCM > 0) {
+        const uint16_t* hin = static_cast<const uint16_t*>(a.hist_in);
+#pragma unroll
+        for (int i = 0; i < NHL; ++i) {
+          const int e = tid + G::NT * i;
+          const int r = e / D, cc = e % D;
+          const int tok = tok0 - HALO + r;
+          // (selects only: the load below has no condition)
+          const bool staged = tok < 0 && hin != nullptr && a.nseg > 1;
+          const bool given = tok < 0 && hin != nullptr && a.nseg <= 1 && a.Kc - 1 + tok >= 0;
+          const uint16_t* base_p = staged ? staged_hist : given ? hin : gv;
+          const int64_t off = staged ? (int64_t)(HALO + tok) * D + cc
+                              : given ? ((int64_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + cc
+                                      : (int64_t)(tok >= 0 ? tok : 0) * a.st + cc;
+          const uint16_t* src = base_p + off;
+          const bool have = tok >= 0 || staged || given;
+          const uint16_t x = *src;
+          hx[i] = have ? x : (uint16_t)0;
         }
       }
-#pragma unroll
-      for (int i = 0; i < NHL; ++i) {
-        const int e = tid + G::NT * i;
-        const int r = e / D, cc = e % D;
-        const int tok = tok0 - HALO + r;
-        hx[i] = 0;
-        if (tok >= 0) hx[i] = gv[(int64_t)tok * a.st + cc];
-        else if (a.hist_in && a.nseg > 1) hx[i] = staged_hist[(size_t)(HALO + tok) * D + cc];
-        else if (a.hist_in && a.Kc - 1 + tok >= 0)
-          hx[i] = static_cast<const uint16_t*>(a.hist_in)[((size_t)bh * (a.Kc - 1) + (a.Kc - 1 + tok)) * D + cc];
-      }
-      const float zx = tid < D ? slot[D * D + tid] : 0.f;
+      const float zx = slot[D * D + (tid < D ? tid : 0)];
+      const bool ragged = nt < GT;                         // uniform
 #pragma unroll
       for (int i = 0; i < NPC; ++i) {
         const int e = tid + G::NT * i;
         const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
+        if (ragged && r >= nt) kx[i] = vx[i] = u32x4{0, 0, 0, 0};
         *reinterpret_cast<u32x4*>(Kl + r * G::KS + c0) = kx[i];
         u32x2* vrow = reinterpret_cast<u32x2*>(Vl + (HALO + r) * G::VS + c0);
         vrow[0] = u32x2{vx[i][0], vx[i][1]};
         vrow[1] = u32x2{vx[i][2], vx[i][3]};
       }
+      if constexpr (KCM > 0) {
 #pragma unroll
-      for (int i = 0; i < NHL; ++i) {
-        const int e = tid + G::NT * i;
-        Vl[(e / D) * G::VS + e % D] = hx[i];
+        for (int i = 0; i < NHL; ++i) {
+          const int e = tid + G::NT * i;
+          Vl[(e / D) * G::VS + e % D] = hx[i];
+        }
       }
       if (tid < D) zl[tid] = zx;
-#pragma unroll
-      for (int i = 0; i < SIT; ++i) spk[i] = u32x2{pack_bf16x2(sreg[i][0], sreg[i][1]), pack_bf16x2(sreg[i][2], sreg[i][3])};
     }
     __syncthreads();                                       // A: the group is in LDS
 
-    // ---- 3. local branch: key tiles 0 .. w, online softmax per lane, O^T += V^T P^T ---------------------------
-    // o[ct][r] = O[query 32w + l32][channel 32ct + 8(r/4) + 4hi + r%4]
+    // ---- 3. local branch: key tiles 0 .. qtile, online softmax per lane, O^T += V^T P^T -----------------------
+    // o[ct][r] = O[query 32 qtile + l32][channel 32ct + 8(r/4) + 4hi + r%4]
+    // The products of key tile kt + 1 are issued before the softmax of tile kt, so that the matrix cores work while
+    // the vector ALUs do: a wave alone is a chain of LDS read -> MFMA -> exp -> MFMA that nothing else fills (two
+    // waves per SIMD).  After the last tile the look-ahead repeats that tile; its result is dropped.
     f32x16 o[G::CT];
 #pragma unroll
     for (int ct = 0; ct < G::CT; ++ct)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[ct][r] = 0.f;
     float mtop = -INFINITY, mass = 0.f;                    // largest raw product so far; this lane's share of the sum
-    for (int kt = 0; kt <= w; ++kt) {
-      f32x16 acc;
+    auto scores = [&](int kt) {
+      f32x16 s;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
       const uint16_t* ka = Kl + (32 * kt + l32) * G::KS + 8 * hi;
 #pragma unroll
-      for (int ks = 0; ks < G::KSD; ++ks) acc = mfma(lds_row8(ka + 16 * ks), __builtin_bit_cast(bf16x8, qraw[ks]), acc);
-      // acc[r]: key 32kt + 8(r/4) + 4hi + r%4, query 32w + l32.  Keys later than the query (diagonal tile only)
-      // become -inf: their weight is an exact zero, nothing of a later token leaks.
+      for (int ks = 0; ks < G::KSD; ++ks) s = mfma(lds_row8(ka + 16 * ks), __builtin_bit_cast(bf16x8, qraw[ks]), s);
+      return s;
+    };
+    f32x16 ahead = scores(0);
+    for (int kt = 0; kt <= qtile; ++kt) {
+      f32x16 acc = ahead;
+      ahead = scores(kt < qtile ? kt + 1 : qtile);
+      // acc[r]: key 32kt + 8(r/4) + 4hi + r%4, query 32 qtile + l32.  Keys later than the query (diagonal tile
+      // only) become -inf: their weight is an exact zero, nothing of a later token leaks.
       float top = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int kl = 8 * (r >> 2) + 4 * hi + (r & 3);
-        acc[r] = (kt < w || kl <= l32) ? acc[r] : -INFINITY;
+        acc[r] = (kt < qtile || kl <= l32) ? acc[r] : -INFINITY;
         top = fmaxf(top, acc[r]);
       }
       top = fmaxf(top, __shfl_xor(top, 32));               // lanes l and l + 32 hold the same query
@@ -231,6 +251,22 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
         o[ct] = mfma(tr_operand_acc_order(Vl + HALO * G::VS, G::VS, 32 * kt + 16, 32 * ct, lane), p1, o[ct]);
       }
     }
+    // ---- 4. this wave's tiles of the state before the group (feature block ib, channel block cb; lanes = channels,
+    //         registers = features): requested here, so that they travel while the feature map runs.  They are the
+    //         linear branch's operand and, with the group's own products added, the state after the group -- the slot
+    //         is read once.
+    constexpr int TPW = (G::CT * G::CT + G::NW - 1) / G::NW;
+    f32x16 sold[TPW];
+#pragma unroll
+    for (int s2 = 0; s2 < TPW; ++s2) {
+      const int tile = w + G::NW * s2;
+      if (tile < G::CT * G::CT) {                          // uniform
+        const int so = ((32 * (tile / G::CT) + 4 * hi) * D + 32 * (tile % G::CT) + l32) * 4;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          sold[s2][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(slot_rs, so, (8 * (r >> 2) + (r & 3)) * (D * 4), 0));
+      }
+    }
     mass += __shfl_xor(mass, 32);
     const float inv_mass = __builtin_amdgcn_rcpf(mass);    // the token itself is always seen: mass >= 1
 #pragma unroll
@@ -238,7 +274,7 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[ct][r] *= inv_mass;
 
-    // ---- 4. for the linear branch: phi(Q) as the MFMA operand (in place of the raw rows) and phi(q).z -----------
+    // ---- 5. for the linear branch: phi(Q) as the MFMA operand (in place of the raw rows) and phi(q).z -----------
     bf16x8 fq[G::KSD];
     float dz = 0.f;
 #pragma unroll
@@ -261,51 +297,89 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
     const bool update = more || (last_seg && (a.S_out != nullptr || a.z_out != nullptr));   // uniform
     __syncthreads();                                       // B: every wave is done with the raw key rows
     if (update) {
-      for (int e = tid; e < GT * (D / 8); e += G::NT) {
+      // phi in place on the key rows (a thread meets the same eight features in every row it maps: their sums over
+      // the rows, for z, on the way)
+      static_assert(G::NT % (D / 8) == 0 && 64 % (D / 8) == 0, "a thread's feature block is fixed");
+      float zp[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < GT * (D / 8) / G::NT; ++i) {
+        const int e = tid + G::NT * i;
         const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
         u32x4* p8 = reinterpret_cast<u32x4*>(Kl + r * G::KS + c0);
         u32x4 f = phi_pack8_nb(*p8, a.relu ? 0.f : 1.f);
         if (r >= nt) f = u32x4{0, 0, 0, 0};                // phi(0) = 1: rows that do not exist stay zero rows
         *p8 = f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          zp[2 * j] += bf16_lo_to_f32(f[j]);
+          zp[2 * j + 1] += bf16_hi_to_f32(f[j]);
+        }
+      }
+      // the lanes of a wave that share a feature block (lane % (D/8) equal) add up; one row of sums per wave
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+#pragma unroll
+        for (int m = D / 8; m < 64; m *= 2) zp[j] += __shfl_xor(zp[j], m);
+      }
+      if (lane < D / 8) {
+        *reinterpret_cast<f32x4*>(redl + w * D + 8 * lane) = f32x4{zp[0], zp[1], zp[2], zp[3]};
+        *reinterpret_cast<f32x4*>(redl + w * D + 8 * lane + 4) = f32x4{zp[4], zp[5], zp[6], zp[7]};
       }
       __syncthreads();
-      // 16 tiles (feature block ib, channel block cb) of S over 8 waves; lanes = channels, registers = features
+      // S += phi(K)^T V on this wave's tiles: they share their channel block, so one value operand serves both
+      static_assert(G::NW % G::CT == 0, "a wave's tiles lie in one channel block");
+      if (w < G::CT * G::CT) {                             // uniform
+        const int cb = w % G::CT;
+        f32x16 snew[TPW];
 #pragma unroll
-      for (int s2 = 0; s2 < (G::CT * G::CT + G::NW - 1) / G::NW; ++s2) {
-        const int tile = w + G::NW * s2;
-        if (tile < G::CT * G::CT) {                        // uniform
-          const int ib = tile / G::CT, cb = tile % G::CT;
-          const int so = ((32 * ib + 4 * hi) * D + 32 * cb + l32) * 4;
-          f32x16 sacc;
+        for (int s2 = 0; s2 < TPW; ++s2) snew[s2] = sold[s2];
+#pragma unroll 8
+        for (int ks = 0; ks < GT / 16; ++ks) {
+          const bf16x8 vb = tr_operand(Vl + HALO * G::VS, G::VS, 16 * ks, 32 * cb, lane);
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            sacc[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(slot_rs, so, (8 * (r >> 2) + (r & 3)) * (D * 4), 0));
-          for (int ks = 0; ks < GT / 16; ++ks)
-            sacc = mfma(tr_operand(Kl, G::KS, 16 * ks, 32 * ib, lane), tr_operand(Vl + HALO * G::VS, G::VS, 16 * ks, 32 * cb, lane), sacc);
+          for (int s2 = 0; s2 < TPW; ++s2)
+            if (w + G::NW * s2 < G::CT * G::CT)
+              snew[s2] = mfma(tr_operand(Kl, G::KS, 16 * ks, 32 * ((w + G::NW * s2) / G::CT), lane), vb, snew[s2]);
+        }
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sacc[r]), slot_rs, so, (8 * (r >> 2) + (r & 3)) * (D * 4), 0);
+        for (int s2 = 0; s2 < TPW; ++s2) {
+          const int tile = w + G::NW * s2;
+          if (tile < G::CT * G::CT) {
+            const int so = ((32 * (tile / G::CT) + 4 * hi) * D + 32 * cb + l32) * 4;
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(snew[s2][r]), slot_rs, so, (8 * (r >> 2) + (r & 3)) * (D * 4), 0);
+          }
         }
       }
       if (tid < D) {
         float zs = zl[tid];
-        for (int r = 0; r < nt; ++r) zs += bf16_bits_to_f32(Kl[r * G::KS + tid]);
+#pragma unroll
+        for (int i = 0; i < G::NW; ++i) zs += redl[i * D + tid];
         slot[D * D + tid] = zs;
       }
-      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");   // the next group's read-out loads what other waves stored
-      __syncthreads();                                     // the key rows' memory is free; the slot is complete
+      // (No fence: from here to the end of the walk every lane re-reads from the slot only what it stored itself --
+      // the tile layout and the tile-to-wave map are the same in every group, and z is one thread per feature.)
+      __syncthreads();                                     // the key rows' memory is free
     }
 
-    // ---- 6b. linear branch: S_g (still the state before the group: it was read ahead of the update) goes to the
-    //          key rows' memory as bf16 [feature][channel]; O^T += (alpha / (phi(q).z + eps)) S_g^T phi(Q)^T with the
-    //          state operand from transposed LDS reads (lanes = channels, registers = features 16ks + 8hi + 0..7)
+    // ---- 6b. linear branch: the state before the group goes to the key rows' memory as bf16 [channel][feature]
+    //          (rounded for the read-out only), every wave its own tiles; O^T += (alpha / (phi(q).z + eps))
+    //          S_g^T phi(Q)^T with the state operand read row-wise (lanes = channels, registers = features
+    //          16ks + 8hi + 0..7)
     {
       uint16_t* Sl = Kl;
-      constexpr int SS = D + 4;
+      constexpr int SS = D + 8;
 #pragma unroll
-      for (int i = 0; i < SIT; ++i) {
-        const int e = 4 * (tid + G::NT * i);
-        *reinterpret_cast<u32x2*>(Sl + (e / D) * SS + e % D) = spk[i];
+      for (int s2 = 0; s2 < TPW; ++s2) {
+        const int tile = w + G::NW * s2;
+        if (tile < G::CT * G::CT) {                        // uniform
+          uint16_t* srow = Sl + (32 * (tile % G::CT) + l32) * SS + 32 * (tile / G::CT) + 4 * hi;
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            *reinterpret_cast<u32x2*>(srow + 8 * g) =
+                u32x2{pack_bf16x2(sold[s2][4 * g], sold[s2][4 * g + 1]), pack_bf16x2(sold[s2][4 * g + 2], sold[s2][4 * g + 3])};
+        }
       }
       __syncthreads();
 #pragma unroll
@@ -313,8 +387,9 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
         f32x16 lin;
 #pragma unroll
         for (int r = 0; r < 16; ++r) lin[r] = 0.f;
+        const uint16_t* sa = Sl + (32 * ct + l32) * SS + 8 * hi;
 #pragma unroll
-        for (int ks = 0; ks < G::KSD; ++ks) lin = mfma(tr_operand(Sl, SS, 16 * ks, 32 * ct, lane), fq[ks], lin);
+        for (int ks = 0; ks < G::KSD; ++ks) lin = mfma(lds_row8(sa + 16 * ks), fq[ks], lin);
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[ct][r] = fmaf(lin[r], fscale, o[ct][r]);
       }
@@ -324,6 +399,28 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
     // ---- 7. outputs: staged as fp32 rows in the key rows' memory, 128 tokens at a time (waves 0..3, then 4..7);
     //         the store loop adds the causal conv over V (taps and value rows from LDS), rounds once and writes
     //         whole rows
+    if constexpr (KCM == 0) {
+      // no conv in this kernel (more than 8 taps: a pass of its own adds it): the rows are rounded here and staged
+      // as bf16, the whole group at once
+      uint16_t* Ob = Kl;
+      uint16_t* orow = Ob + qt * G::OB + 4 * hi;
+#pragma unroll
+      for (int ct = 0; ct < G::CT; ++ct)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<u32x2*>(orow + 32 * ct + 8 * g) =
+              u32x2{pack_bf16x2(o[ct][4 * g], o[ct][4 * g + 1]), pack_bf16x2(o[ct][4 * g + 2], o[ct][4 * g + 3])};
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < GT * (D / 8) / G::NT; ++i) {
+        const int e = tid + G::NT * i;
+        const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
+        if (r < nt)
+          __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(Ob + r * G::OB + c0),
+                                      reinterpret_cast<u32x4*>(gout + (int64_t)(tok0 + r) * a.st + c0));
+      }
+      __syncthreads();                                     // all of LDS is free again
+    } else
 #pragma unroll 1
     for (int half = 0; half < 2; ++half) {
       if ((w >> 2) == half) {                              // uniform per wave
@@ -365,6 +462,9 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
 
   // ---- the state after the last token, handed over by the last segment ----------------------------------------------
   if (!last_seg) return;
+  // other lanes than the ones that stored it read the slot from here on
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __syncthreads();
   if (ngroups > 0 && (a.S_out || a.z_out)) {
     if (a.S_out) {
       // (every request of the thread in flight before the first store: a loop of load, wait, store would pay one
@@ -416,10 +516,12 @@ static hipError_t launch_g256(const PrefillArgs& a, hipStream_t st) {
 // segments, filled by the first pass and the prefix sum; without, initialised here -- and the staged history rows.
 hipError_t launch_prefill_grouped256(const PrefillArgs& a, int d, hipStream_t st) {
   if (d == 128) {
+    if (a.no_conv) return launch_g256<128, 0>(a, st);
     if (a.Kc <= 3) return launch_g256<128, 3>(a, st);
     if (a.Kc <= 5) return launch_g256<128, 5>(a, st);
     return launch_g256<128, 8>(a, st);
   }
+  if (a.no_conv) return launch_g256<64, 0>(a, st);
   if (a.Kc <= 3) return launch_g256<64, 3>(a, st);
   if (a.Kc <= 5) return launch_g256<64, 5>(a, st);
   return launch_g256<64, 8>(a, st);
