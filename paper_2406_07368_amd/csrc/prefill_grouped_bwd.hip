@@ -117,7 +117,7 @@ __device__ __forceinline__ void load_slot(const float* slot, uint16_t* Sl, float
   if (tid < D) zl[tid] = zx;
 }
 
-// acc[ct][r] = X[row 32w + l32][column 32ct + 8(r/4) + 4hi + r%4] -> global bf16 rows, staged through LDS in fp32,
+// acc[ct][r] = X[row 32w + l32][column 32ct + 8(r/4) + 4hi + r%4] (w: the wave's row tile) -> global bf16 rows, staged through LDS in fp32,
 // RP rows at a time (the waves of one pass write, all threads store whole rows).  Ends with a barrier.
 template <int D, int GT>
 __device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], float* Ol, uint16_t* gout, int64_t st, int tok0,
@@ -192,9 +192,13 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
   constexpr float inv_sqrt_d = D == 64 ? 0.125f : 0.08838834764831845f;
   constexpr float to_log2 = 1.44269504088896340736f * inv_sqrt_d;
 
-  // this wave's queries and their incoming gradients, straight into MFMA operand registers: lane = query 32w + l32,
-  // registers = features / channels 16ks + 8hi + 0..7.  A query past the end reads the last row; it is never stored.
-  const int qt = 32 * w + l32;
+  // Query tile j meets j + 1 key tiles.  Waves w and w + NW/2 share a SIMD: the tiles (w, NW - 1 - w) give every SIMD
+  // the same number of key tiles.
+  const int qtile = w < G::NW / 2 ? w : G::NW + G::NW / 2 - 1 - w;
+  // this wave's queries and their incoming gradients, straight into MFMA operand registers: lane = query
+  // 32 qtile + l32, registers = features / channels 16ks + 8hi + 0..7.  A query past the end reads the last row; it is
+  // never stored.
+  const int qt = 32 * qtile + l32;
   const int qrow = qt < nt ? qt : nt - 1;
   u32x4 qraw[G::KSD], draw[G::KSD];
   {
@@ -223,15 +227,15 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
 
   // ---- pass 1: largest logit, sum of the weights and sum of e_i dp_i per query ---------------------------------
   float mtop = -INFINITY, mass = 0.f, racc = 0.f;
-  for (int kt = 0; kt <= w; ++kt) {
+  for (int kt = 0; kt <= qtile; ++kt) {
     f32x16 acc, dpa;
     scores(kt, acc, dpa);
-    // acc[r], dpa[r]: key 32kt + 8(r/4) + 4hi + r%4, query 32w + l32; keys later than the query do not exist for it
+    // acc[r], dpa[r]: key 32kt + 8(r/4) + 4hi + r%4, query 32 qtile + l32; keys later than the query do not exist for it
     float top = -INFINITY;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int kl = 8 * (r >> 2) + 4 * hi + (r & 3);
-      acc[r] = (kt < w || kl <= l32) ? acc[r] : -INFINITY;
+      acc[r] = (kt < qtile || kl <= l32) ? acc[r] : -INFINITY;
       top = fmaxf(top, acc[r]);
     }
     top = fmaxf(top, __shfl_xor(top, 32));
@@ -256,20 +260,20 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
   const float mlog2 = mtop * to_log2;
 
   // ---- pass 2: ds = p (dp - pbar) / sqrt(d), dQ^T += K^T ds^T --------------------------------------------------
-  // dqa[ft][r] = dQ[query 32w + l32][feature 32ft + 8(r/4) + 4hi + r%4]
+  // dqa[ft][r] = dQ[query 32 qtile + l32][feature 32ft + 8(r/4) + 4hi + r%4]
   f32x16 dqa[G::CT];
 #pragma unroll
   for (int ft = 0; ft < G::CT; ++ft)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dqa[ft][r] = 0.f;
-  for (int kt = 0; kt <= w; ++kt) {
+  for (int kt = 0; kt <= qtile; ++kt) {
     f32x16 acc, dpa;
     scores(kt, acc, dpa);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int kl = 8 * (r >> 2) + 4 * hi + (r & 3);
       // (the mask as a select on the exponent, exp2(-inf) = 0: a branch per element would cut the loop into pieces)
-      const float arg = (kt < w || kl <= l32) ? fmaf(acc[r], to_log2, -mlog2) : -INFINITY;
+      const float arg = (kt < qtile || kl <= l32) ? fmaf(acc[r], to_log2, -mlog2) : -INFINITY;
       const float p = __builtin_amdgcn_exp2f(arg) * inv_mass;
       acc[r] = p * (dpa[r] - pbar) * inv_sqrt_d;
     }
@@ -348,7 +352,7 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
     a.stats[4 * n + e] = dden;
   }
   __syncthreads();                                         // every wave is done with the state operand
-  store_rows<D, GT>(dqa, Ol, gdq, a.st, tok0, nt, tid, w, l32, hi);
+  store_rows<D, GT>(dqa, Ol, gdq, a.st, tok0, nt, tid, qtile, l32, hi);
 }
 
 // ---- what the queries of a group add to the gradient of the sums before it; and those sums themselves -----------------
@@ -505,8 +509,10 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
   constexpr float inv_sqrt_d = D == 64 ? 0.125f : 0.08838834764831845f;
   constexpr float to_log2 = 1.44269504088896340736f * inv_sqrt_d;
 
-  // this wave's keys (and their values) as MFMA operands: lane = key 32w + l32, registers = features 16ks + 8hi + 0..7
-  const int kt_own = 32 * w + l32;
+  // this wave's keys (and their values) as MFMA operands: lane = key 32 ktile + l32, registers = features 16ks + 8hi + 0..7
+  // key tile j meets the query tiles j .. NW - 1: mirrored over the waves as in the query-side kernel
+  const int ktile = w < G::NW / 2 ? w : G::NW + G::NW / 2 - 1 - w;
+  const int kt_own = 32 * ktile + l32;
   const int krow = kt_own < nt ? kt_own : nt - 1;
   u32x4 kop[G::KSD], vop[G::KSD];
   {
@@ -524,15 +530,15 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
   if (tid < GT) { ml[tid] = s0; il[tid] = s1; pl[tid] = s2; }
   __syncthreads();
 
-  // acc4[ct][r] = dV or dK [key 32w + l32][column 32ct + 8(r/4) + 4hi + r%4]
+  // acc4[ct][r] = dV or dK [key 32 ktile + l32][column 32ct + 8(r/4) + 4hi + r%4]
   f32x16 acc4[G::CT];
 #pragma unroll
   for (int ct = 0; ct < G::CT; ++ct)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc4[ct][r] = 0.f;
   const int nqt = (nt + 31) / 32;
-  for (int qt = w; qt < nqt; ++qt) {
-    // sc[r]: query 32qt + 8(r/4) + 4hi + r%4 (registers), key 32w + l32 (lane)
+  for (int qt = ktile; qt < nqt; ++qt) {
+    // sc[r]: query 32qt + 8(r/4) + 4hi + r%4 (registers), key 32 ktile + l32 (lane)
     f32x16 sc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sc[r] = 0.f;
@@ -543,7 +549,7 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
     for (int r = 0; r < 16; ++r) {
       const int tl = 8 * (r >> 2) + 4 * hi + (r & 3);
       const int t = 32 * qt + tl;
-      const float arg = (qt > w || tl >= l32) ? fmaf(sc[r], to_log2, -ml[t]) : -INFINITY;   // a select, not a branch
+      const float arg = (qt > ktile || tl >= l32) ? fmaf(sc[r], to_log2, -ml[t]) : -INFINITY;   // a select, not a branch
       sc[r] = __builtin_amdgcn_exp2f(arg) * il[t];
     }
     if (role == 0) {                                       // dV^T += dO^T P
@@ -632,24 +638,34 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
     }
     __syncthreads();                                       // every wave is done with the d x d operand
   }
-  store_rows<D, GT>(acc4, Ol, gout, a.st, tok0, nt, tid, w, l32, hi);
+  store_rows<D, GT>(acc4, Ol, gout, a.st, tok0, nt, tid, ktile, l32, hi);
 }
 
 // ---- dw: per workgroup the products of its tokens, then one sum over batch rows and token blocks --------------------
 // dw[h][c][j] = sum_b sum_t dO[b,h,t,c] v[b,h,t-j,c].  One workgroup = DW_TOK tokens of one (b, h); a thread owns one
 // channel and a quarter (d = 64) or half (d = 128) of the tokens, holds the sums of all taps in registers and walks its
-// tokens eight at a time: every value row read from LDS meets up to eight gradients (the loops are straight-line
-// code for the tap capacity of the instantiation, as in the forward long conv).
+// tokens sixteen at a time.  Both factors are bf16, so two products per instruction come for free: the gradients of
+// tokens (t, t+1) and the values of tokens (s, s+1), each pair in one register, meet in one v_dot2 (exact products,
+// fp32 sum) and both products belong to tap t - s.  The value pairs of all alignments are made on the way: every
+// value read from LDS joins the one read before it.  (The loops are straight-line code for the tap capacity of the
+// instantiation, as in the forward long conv.)
 namespace {
-constexpr int DW_TOK = 64;
+constexpr int DW_TOK = 128;
 constexpr int DW_HALO = 62;
-constexpr int DW_BLK = 8;
+constexpr int DW_BLK = 16;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
 }  // namespace
 
 template <int D, int KMAX>
 __global__ __launch_bounds__(256) void grouped_bwd_dw_kernel(GroupedBwdArgs a) {
-  extern __shared__ float xs[];                            // [DW_HALO + DW_TOK][D] value rows, then [256][KMAX] sums
+  extern __shared__ __attribute__((aligned(16))) unsigned char dw_smem[];
+  uint16_t* xs = reinterpret_cast<uint16_t*>(dw_smem);     // [DW_HALO + DW_TOK][D] value rows (bf16) ...
+  float* red = reinterpret_cast<float*>(dw_smem);          // ... then [NG - 1][D][KMAX] sums
   constexpr int NG = 256 / D, TPT = DW_TOK / NG;
+  static_assert(TPT % DW_BLK == 0, "whole blocks of gradients per thread");
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int t0 = blockIdx.x * DW_TOK;
@@ -658,14 +674,16 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_kernel(GroupedBwdArgs a) {
   const uint16_t* gv = static_cast<const uint16_t*>(a.v) + base;
   const uint16_t* gdo = static_cast<const uint16_t*>(a.dout) + base;
   const int c = tid % D, tg = tid / D;
-  // this thread's gradients (a token past the end: zero) and the value rows t0 - 62 .. t0 + 63, all requested first
-  uint16_t go_raw[TPT];
-#pragma unroll
-  for (int e = 0; e < TPT; ++e) {
-    const int tok = t0 + tg * TPT + e;
-    go_raw[e] = gdo[(int64_t)(tok < L ? tok : L - 1) * a.st + c];
-  }
+  // this thread's gradients (a token past the end: zero), two tokens per register, and the value rows
+  // t0 - 62 .. t0 + DW_TOK - 1, all requested first
+  uint32_t gp[TPT / 2];
   {
+    uint16_t go_raw[TPT];
+#pragma unroll
+    for (int e = 0; e < TPT; ++e) {
+      const int tok = t0 + tg * TPT + e;
+      go_raw[e] = gdo[(int64_t)(tok < L ? tok : L - 1) * a.st + c];
+    }
     constexpr int RIT = ((DW_HALO + DW_TOK) * (D / 8) + 255) / 256;
     u32x4 raw[RIT];
 #pragma unroll
@@ -680,14 +698,14 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_kernel(GroupedBwdArgs a) {
       const int e = tid + 256 * i;
       const int row = e / (D / 8), i0 = 8 * (e % (D / 8));
       const int tok = t0 - DW_HALO + row;
-      if (e < (DW_HALO + DW_TOK) * (D / 8)) {
-        const bool have = tok >= 0 && tok < L;
+      if (e < (DW_HALO + DW_TOK) * (D / 8))
+        *reinterpret_cast<u32x4*>(xs + row * D + i0) = (tok >= 0 && tok < L) ? raw[i] : u32x4{0, 0, 0, 0};
+    }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          xs[row * D + i0 + 2 * j] = have ? bf16_lo_to_f32(raw[i][j]) : 0.f;
-          xs[row * D + i0 + 2 * j + 1] = have ? bf16_hi_to_f32(raw[i][j]) : 0.f;
-        }
-      }
+    for (int e = 0; e < TPT; e += 2) {
+      const int tok = t0 + tg * TPT + e;
+      const uint32_t lo = tok < L ? go_raw[e] : 0u, hi = tok + 1 < L ? go_raw[e + 1] : 0u;
+      gp[e / 2] = lo | (hi << 16);
     }
   }
   __syncthreads();
@@ -695,40 +713,48 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_kernel(GroupedBwdArgs a) {
 #pragma unroll
   for (int j = 0; j < KMAX; ++j) acc[j] = 0.f;
 #pragma unroll 1
-  for (int blk8 = 0; blk8 < TPT / DW_BLK; ++blk8) {
-    const int tb0 = tg * TPT + blk8 * DW_BLK;
-    float go[DW_BLK];
+  for (int blk = 0; blk < TPT / DW_BLK; ++blk) {
+    const int tb0 = tg * TPT + blk * DW_BLK;
+    // value rows from the block's newest token backwards: x(m) = v[newest - m].  The pair (x(m), x(m-1)) = tokens
+    // (s, s+1) meets the gradients of tokens (tb0 + e, tb0 + e + 1), e even, through tap e - (DW_BLK - 1) + m.
+    const uint16_t* newest = xs + (DW_HALO + tb0 + DW_BLK - 1) * D + c;
+    uint32_t newer = newest[0];
 #pragma unroll
-    for (int e = 0; e < DW_BLK; ++e) go[e] = (t0 + tb0 + e) < L ? bf16_bits_to_f32(go_raw[e]) : 0.f;
-    // value rows from the newest token's own row backwards: row m meets gradient e through tap e - 7 + m
-    const float* newest = xs + (DW_HALO + tb0 + DW_BLK - 1) * D + c;
+    for (int m = 1; m < KMAX + DW_BLK - 1; ++m) {
+      const uint32_t x = newest[-m * D];
+      const uint32_t pair = x | (newer << 16);
+      newer = x;
 #pragma unroll
-    for (int m = 0; m < KMAX + DW_BLK - 1; ++m) {
-      const float x = newest[-m * D];
-#pragma unroll
-      for (int e = 0; e < DW_BLK; ++e) {
+      for (int e = 0; e < DW_BLK; e += 2) {
         const int j = e - (DW_BLK - 1) + m;
-        if (j >= 0 && j < KMAX) acc[j] = fmaf(go[e], x, acc[j]);
+        if (j >= 0 && j < KMAX) acc[j] = dot2_bf16(gp[e / 2], pair, acc[j]);
       }
     }
 #pragma unroll
-    for (int e = 0; e + DW_BLK < TPT; ++e) go_raw[e] = go_raw[e + DW_BLK];
+    for (int e = 0; e + DW_BLK / 2 < TPT / 2; ++e) gp[e] = gp[e + DW_BLK / 2];
   }
   // the token groups of threads add up through LDS (fixed order), then one row of partial sums per workgroup
   __syncthreads();
-  float* red = xs;                                         // [NG][D][KMAX]
+  if (tg > 0) {
 #pragma unroll
-  for (int j = 0; j < KMAX; ++j) red[(tg * D + c) * KMAX + j] = acc[j];
+    for (int j = 0; j < KMAX; ++j) red[((tg - 1) * D + c) * KMAX + j] = acc[j];
+  }
+  __syncthreads();
+  if (tg == 0) {
+#pragma unroll
+    for (int q = 0; q < NG - 1; ++q)
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j) acc[j] += red[(q * D + c) * KMAX + j];
+  }
+  __syncthreads();
+  if (tg == 0) {
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) red[c * KMAX + j] = acc[j];
+  }
   __syncthreads();
   // partial sums of a head lie together: [H][B * nwb][D * Kc]
   float* part = a.dw_part + (((size_t)h * a.B + b) * a.nwb + blockIdx.x) * D * Kc;
-  for (int e = tid; e < D * Kc; e += 256) {
-    const int cc = e / Kc, j = e % Kc;
-    float s = 0.f;
-#pragma unroll
-    for (int q = 0; q < NG; ++q) s += red[(q * D + cc) * KMAX + j];
-    part[e] = s;
-  }
+  for (int e = tid; e < D * Kc; e += 256) part[e] = red[(e / Kc) * KMAX + e % Kc];
 }
 
 // Sums over batch rows and token blocks in a fixed order, DW_RED partial sums at a time: in [H][n][per_head] ->
@@ -785,8 +811,8 @@ static hipError_t launch_bwd_core(const GroupedBwdArgs& a, hipStream_t st) {
 
 template <int D, int KMAX>
 static hipError_t launch_bwd_dw(const GroupedBwdArgs& a, hipStream_t st) {
-  constexpr int LDS_ROWS = (DW_HALO + DW_TOK) * D * (int)sizeof(float);
-  constexpr int LDS_RED = 256 * KMAX * (int)sizeof(float);
+  constexpr int LDS_ROWS = (DW_HALO + DW_TOK) * D * (int)sizeof(uint16_t);
+  constexpr int LDS_RED = (256 / D > 2 ? 256 / D - 1 : 1) * D * KMAX * (int)sizeof(float);
   constexpr int LDS = LDS_ROWS > LDS_RED ? LDS_ROWS : LDS_RED;
   auto kern = grouped_bwd_dw_kernel<D, KMAX>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
