@@ -109,6 +109,55 @@ PrefillPlan plan_prefill(const linattn_desc* d, int32_t L, bool grouped = false)
   return p;
 }
 
+// A second stream of the library's own for work that needs nothing from the kernels beside it (the conv's share of dv
+// and the conv-weight sums next to the gradient kernels): forked from the caller's
+// stream and joined back into it with events, so that for the caller everything still happens on its stream --
+// also under graph capture, where the side stream becomes part of the capture.  One per host thread and device,
+// made at the first call that wants it (never while the caller's stream is being captured: then, and if anything
+// cannot be made, the work simply stays on the caller's stream, in the same order).  Default priority.
+struct SideLane {
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, mid = nullptr, join = nullptr;
+  bool ok = false;
+};
+SideLane* side_lane(hipStream_t caller) {
+  static thread_local SideLane lanes[16];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+  SideLane& l = lanes[dev];
+  if (l.ok) return &l;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(caller, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  bool made = hipStreamCreateWithFlags(&l.s, hipStreamNonBlocking) == hipSuccess &&
+              hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) == hipSuccess &&
+              hipEventCreateWithFlags(&l.mid, hipEventDisableTiming) == hipSuccess &&
+              hipEventCreateWithFlags(&l.join, hipEventDisableTiming) == hipSuccess;
+  if (!made) {
+    (void)hipGetLastError();
+    if (l.join) (void)hipEventDestroy(l.join);
+    if (l.mid) (void)hipEventDestroy(l.mid);
+    if (l.fork) (void)hipEventDestroy(l.fork);
+    if (l.s) (void)hipStreamDestroy(l.s);
+    l = SideLane{};
+    return nullptr;
+  }
+  l.ok = true;
+  return &l;
+}
+// the side stream starts behind everything the caller's stream holds so far
+hipError_t fork_side(SideLane* l, hipStream_t caller) {
+  hipError_t e = hipEventRecord(l->fork, caller);
+  return e != hipSuccess ? e : hipStreamWaitEvent(l->s, l->fork, 0);
+}
+// the caller's stream goes on behind everything the side stream holds so far
+hipError_t join_side(SideLane* l, hipStream_t caller) {
+  hipError_t e = hipEventRecord(l->join, l->s);
+  return e != hipSuccess ? e : hipStreamWaitEvent(caller, l->join, 0);
+}
+
 linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, float alpha, const void* q, const void* k,
                            const void* v, const float* conv_w, const float* S_in, const float* z_in, const void* hist_in,
                            void* out, float* S_out, float* z_out, void* hist_out, void* workspace,
@@ -165,6 +214,25 @@ linattn_status prefill_any(const linattn_desc* desc, int32_t L, bool grouped, fl
   a.wait_spins = g_wait_spins.load(std::memory_order_relaxed);
   hipError_t e;
   const bool bf16 = desc->io_dtype == LINATTN_BF16;
+  if (plan.mfma && L > 0 && grouped && desc->chunk == 256 && long_conv) {
+    // Groups of 256 with a long conv: the conv pass writes out first and the full pass adds the rest to it (one
+    // rounding of the sum, and the conv pass reads only V).  On the caller's stream: beside the first pass on the
+    // side stream the call took 9 to 14 us longer -- the fork and the join cost more than the two short kernels
+    // they would overlap.
+    {
+      ConvLongArgs c{};
+      c.v = v; c.conv_w = conv_w; c.hist_in = hist_in; c.out = out; c.hist_out = hist_out;
+      c.B = desc->B; c.H = desc->H; c.L = L; c.Kc = desc->conv_k;
+      c.sb = a.sb_v; c.sh = a.sh_v; c.st = a.st_v; c.m = m; c.assign = 1;
+      e = launch_conv_long(c, true, desc->d, stream);
+    }
+    if (e == hipSuccess && a.nseg > 1) {
+      e = launch_prefill_mfma_ws(a, desc->d, true, false, stream);
+      if (e == hipSuccess) e = launch_segment_scan(a, desc->d, stream);
+    }
+    if (e == hipSuccess) e = launch_prefill_grouped256(a, desc->d, stream);
+    return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
+  }
   if (plan.mfma && L > 0) e = launch_prefill_mfma(a, desc->d, desc->chunk, grouped, stream);
   else if (grouped && L > 0) e = launch_prefill_grouped_simt(a, bf16, desc->d, stream);   // fp32 rows; groups of 256
   else e = launch_prefill_simt(a, bf16, desc->d, stream);                                 // L = 0: the state is handed through
@@ -306,18 +374,25 @@ linattn_status linattn_prefill_grouped_backward(const linattn_desc* desc, int32_
   a.alpha = alpha;
   a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
   a.group = desc->chunk; a.ng = plan.ng; a.nwb = plan.nwb;
+  // The conv's share of dv (the same taps met from the other side, dv[s] = sum_j w[j] dout[s + j]) is written first
+  // and the conv-weight sums need nothing from the other kernels: both run on the side stream; the kernel that adds
+  // the rest of dv waits for the first, the end of the call for the second.
   hipError_t e = hipSuccess;
-  if (L > 0) {
-    if (e == hipSuccess) e = launch_grouped_bwd(a, desc->d, stream);
-    // the conv's share of dv: the same taps met from the other side, dv[s] += sum_j w[j] dout[s + j]
-    if (e == hipSuccess) {
-      ConvLongArgs c{};
-      c.v = dout; c.conv_w = conv_w; c.out = dv;
-      c.B = a.B; c.H = a.H; c.L = L; c.Kc = a.Kc; c.sb = a.sb; c.sh = a.sh; c.st = a.st; c.m = 1; c.rev = 1;
-      e = launch_conv_long(c, true, desc->d, stream);
-    }
-  } else if (dconv_w) {
-    e = launch_grouped_bwd(a, desc->d, stream);            // no tokens: the sums over nothing
+  SideLane* lane = (L > 0) ? side_lane(stream) : nullptr;
+  hipStream_t cs = lane ? lane->s : stream;
+  if (lane) e = fork_side(lane, stream);
+  if (e == hipSuccess && L > 0) {
+    ConvLongArgs c{};
+    c.v = dout; c.conv_w = conv_w; c.out = dv;
+    c.B = a.B; c.H = a.H; c.L = L; c.Kc = a.Kc; c.sb = a.sb; c.sh = a.sh; c.st = a.st; c.m = 1; c.rev = 1; c.assign = 1;
+    e = launch_conv_long(c, true, desc->d, cs);
+    if (e == hipSuccess && lane) e = hipEventRecord(lane->mid, cs);
+  }
+  if (e == hipSuccess) e = launch_grouped_bwd_dw(a, desc->d, cs);            // no tokens: the sums over nothing
+  if (e == hipSuccess) e = launch_grouped_bwd_core(a, desc->d, stream, lane ? lane->mid : nullptr);
+  if (lane) {                                              // joined whatever happened, so that nothing stays forked
+    const hipError_t ej = join_side(lane, stream);
+    if (e == hipSuccess) e = ej;
   }
   return e == hipSuccess ? LINATTN_OK : LINATTN_ERR_HIP;
 }

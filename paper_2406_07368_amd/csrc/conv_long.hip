@@ -2,6 +2,7 @@
 // DWConv with kernel size 63), as a pass of its own behind the attention kernels:
 //
 //   out[t][c] += sum_{j < Kc} w[h][c][j] * Vext[t - j][c]        Vext = hist_in ++ V, zeros before that
+//   (or out = ..., when the pass runs ahead of the kernel that adds the rest)
 //
 // The attention kernels keep an 8-row halo of V in LDS and gather the taps per token; a 62-row halo does not
 // fit next to their row buffers, and 63 taps per output are a vector-ALU workload of the size of the attention
@@ -26,7 +27,7 @@ constexpr int CL_BLK = 8;         // outputs a thread carries at once
 static __device__ __forceinline__ float elem_to_f32(float x) { return x; }
 static __device__ __forceinline__ float elem_to_f32(uint16_t x) { return bf16_bits_to_f32(x); }
 
-template <typename Io, int D, int KMAX>
+template <typename Io, int D, int KMAX, bool ASSIGN>
 __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   // the value rows [CL_HALO + CL_TOK][D] as they lie in memory (bf16 rows stay bf16: half the LDS of fp32 rows, so
   // twice the workgroups per compute unit); before them, for a moment, the taps as fp32
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   // time: the first eight with the first requests, the next eight while the current ones are being computed (all 32
   // at once would cost the registers that let a second and third workgroup share the compute unit).  Past the end: the
   // first token's element, never stored.
-  typename Io::elem prev[CL_BLK];
+  [[maybe_unused]] typename Io::elem prev[CL_BLK];
   auto issue_prev = [&](int blk8, typename Io::elem (&dst)[CL_BLK]) __attribute__((always_inline)) {
 #pragma unroll
     for (int e = 0; e < CL_BLK; ++e) {
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       const int e = tid + 256 * i;
       if (e < D * Kc / 4) *reinterpret_cast<f32x4*>(xs + 4 * e) = wt[i];
     }
-    issue_prev(0, prev);                      // ... and the first of what is already in out
+    if constexpr (!ASSIGN) issue_prev(0, prev);   // ... and the first of what is already in out
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < KMAX; ++j) wreg[j] = j < Kc ? xs[c * Kc + j] : 0.f;
@@ -128,8 +129,8 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   for (int blk8 = 0; blk8 < TPT / CL_BLK; ++blk8) {
     const int tb0 = tg * TPT + blk8 * CL_BLK;
     float acc[CL_BLK];
-    typename Io::elem next[CL_BLK];
-    issue_prev(blk8 + 1 < TPT / CL_BLK ? blk8 + 1 : blk8, next);
+    [[maybe_unused]] typename Io::elem next[CL_BLK];
+    if constexpr (!ASSIGN) issue_prev(blk8 + 1 < TPT / CL_BLK ? blk8 + 1 : blk8, next);
 #pragma unroll
     for (int e = 0; e < CL_BLK; ++e) acc[e] = 0.f;
     // value rows from the newest output's own row backwards: row m feeds output e through tap e - 7 + m
@@ -148,10 +149,13 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
 #pragma unroll
     for (int e = 0; e < CL_BLK; ++e) {
       const int tok = t0 + tb0 + e;
-      if (tok < L) Io::store1(a.out, base + (int64_t)(a.rev ? L - 1 - tok : tok) * a.st + c, elem_to_f32(prev[e]) + acc[e]);
+      if (tok < L)
+        Io::store1(a.out, base + (int64_t)(a.rev ? L - 1 - tok : tok) * a.st + c, ASSIGN ? acc[e] : elem_to_f32(prev[e]) + acc[e]);
     }
+    if constexpr (!ASSIGN) {
 #pragma unroll
-    for (int e = 0; e < CL_BLK; ++e) prev[e] = next[e];
+      for (int e = 0; e < CL_BLK; ++e) prev[e] = next[e];
+    }
   }
 }
 
@@ -199,22 +203,24 @@ __global__ __launch_bounds__(256) void conv_long_hist_kernel(ConvLongArgs a) {
   }
 }
 
-template <typename Io, int D, int KMAX>
+template <typename Io, int D, int KMAX, bool ASSIGN>
 static hipError_t launch_cl_k(const ConvLongArgs& a, hipStream_t st) {
   constexpr int LDS_ROWS = (CL_HALO + CL_TOK) * D * (int)sizeof(typename Io::elem), LDS_TAPS = D * KMAX * (int)sizeof(float);
   constexpr int LDS = LDS_ROWS > LDS_TAPS ? LDS_ROWS : LDS_TAPS;
-  auto kern = conv_long_kernel<Io, D, KMAX>;
+  auto kern = conv_long_kernel<Io, D, KMAX, ASSIGN>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)((a.L + CL_TOK - 1) / CL_TOK), (unsigned)(a.B * a.H * a.m)), dim3(256), LDS, st, a);
   return hipGetLastError();
 }
 
-template <typename Io, int D>
+template <typename Io, int D, bool ASSIGN>
 static hipError_t launch_cl(const ConvLongArgs& a, hipStream_t st) {
   hipError_t e = hipSuccess;
   if (a.L > 0) {
-    e = a.Kc <= 16 ? launch_cl_k<Io, D, 16>(a, st) : a.Kc <= 32 ? launch_cl_k<Io, D, 32>(a, st) : launch_cl_k<Io, D, CL_MAXK>(a, st);
+    e = a.Kc <= 16   ? launch_cl_k<Io, D, 16, ASSIGN>(a, st)
+        : a.Kc <= 32 ? launch_cl_k<Io, D, 32, ASSIGN>(a, st)
+                     : launch_cl_k<Io, D, CL_MAXK, ASSIGN>(a, st);
     if (e != hipSuccess) return e;
   }
   if (a.hist_out) {
@@ -225,8 +231,12 @@ static hipError_t launch_cl(const ConvLongArgs& a, hipStream_t st) {
 }
 
 hipError_t launch_conv_long(const ConvLongArgs& a, bool bf16, int d, hipStream_t st) {
-  if (bf16) return d == 128 ? launch_cl<IoBf16, 128>(a, st) : launch_cl<IoBf16, 64>(a, st);
-  return d == 128 ? launch_cl<IoF32, 128>(a, st) : launch_cl<IoF32, 64>(a, st);
+  if (a.assign) {
+    if (!bf16) return hipErrorInvalidValue;
+    return d == 128 ? launch_cl<IoBf16, 128, true>(a, st) : launch_cl<IoBf16, 64, true>(a, st);
+  }
+  if (bf16) return d == 128 ? launch_cl<IoBf16, 128, false>(a, st) : launch_cl<IoBf16, 64, false>(a, st);
+  return d == 128 ? launch_cl<IoF32, 128, false>(a, st) : launch_cl<IoF32, 64, false>(a, st);
 }
 
 }  // namespace linattn

@@ -112,6 +112,8 @@ struct ConvLongArgs {
   int m;                    // value blocks of d channels per head (d_v = m d)
   int rev;                  // the token axis runs backwards (out[t] += sum_j w[j] v[t + j]): the conv's share of the
                             // gradient with respect to its input; no history then
+  int assign;               // out = conv instead of out += conv (bf16 rows only): the pass then runs ahead of the
+                            // kernel that adds the rest, and needs nothing from it
 };
 
 // Gradient of the three-branch form for a sequence that starts from nothing (training): bf16 rows, one set of strides
@@ -168,7 +170,11 @@ hipError_t launch_conv_long(const ConvLongArgs& a, bool bf16, int d, hipStream_t
 
 // prefill_grouped_bwd.hip : gradient of the three-branch form (bf16 rows, groups of 64 or 256)
 int grouped_bwd_dw_blocks(int L);
-hipError_t launch_grouped_bwd(const GroupedBwdArgs& a, int d, hipStream_t st);
+// ... in two parts that need nothing from each other: everything but the conv-weight sums (dv is added to what it
+// holds: the conv's share is written first; `before_dkdv`, if not null, is waited for ahead of the kernel that does
+// so), and the conv-weight sums
+hipError_t launch_grouped_bwd_core(const GroupedBwdArgs& a, int d, hipStream_t st, hipEvent_t before_dkdv);
+hipError_t launch_grouped_bwd_dw(const GroupedBwdArgs& a, int d, hipStream_t st);
 
 // prefill_mfma.hip : launch plan of the bf16 prefill (segments, prefix sum over segment states)
 hipError_t launch_segment_scan(const PrefillArgs& a, int d, hipStream_t st);   // the prefix sum alone

@@ -20,7 +20,8 @@
 //   linear branch   O_lin^T = S_g^T phi(Q)^T, one 32-channel tile at a time, the state before the group as the MFMA
 //                   operand (bf16 in LDS, rounded for the read-out only, as in the other matrix-core kernels);
 //   epilogue        O / l + alpha O_lin / (phi(q).z_g + eps), staged through LDS in fp32 (the key rows' memory); the
-//                   store loop adds the causal conv over V and writes whole rows.
+//                   store loop adds the causal conv over V (up to 8 taps; with more, what the long-conv pass left in
+//                   out) and writes whole rows.
 //
 // Then, unless nothing after the group needs it, the group enters the state: phi is applied to the key rows in
 // place and every wave adds phi(K)^T V to its two 32 x 32 tiles of the state -- the tiles it read for the linear
@@ -50,9 +51,7 @@ struct G256Cfg {
   static constexpr int OFF_Z = OFF_W + 8 * D * 4;                     // [D] float: z before the group
   static constexpr int OFF_R = OFF_Z + D * 4;                         // [NW][D] float: per-wave column sums of phi(K)
   static constexpr int TOTAL = OFF_R + NW * D * 4;
-  static constexpr int OB = D + 8;           // staged output rows, bf16, the whole group at once (no conv in the kernel)
   static_assert(128 * OS * 4 <= GT * KS * 2, "the staged outputs take the place of the key rows");
-  static_assert(GT * OB * 2 <= GT * KS * 2, "the staged bf16 outputs take the place of the key rows");
   static_assert(TOTAL <= 160 * 1024, "LDS");
 };
 
@@ -400,26 +399,45 @@ __global__ __launch_bounds__(512) void prefill_grouped256_kernel(PrefillArgs a) 
     //         the store loop adds the causal conv over V (taps and value rows from LDS), rounds once and writes
     //         whole rows
     if constexpr (KCM == 0) {
-      // no conv in this kernel (more than 8 taps: a pass of its own adds it): the rows are rounded here and staged
-      // as bf16, the whole group at once
-      uint16_t* Ob = Kl;
-      uint16_t* orow = Ob + qt * G::OB + 4 * hi;
+      // No conv in this kernel (more than 8 taps): the pass that computes it ran first and left it in out, which is
+      // added to here -- the requests for this thread's pieces of out go ahead of the staging, the sum is formed in
+      // fp32 and rounded once.  128 tokens at a time (waves 0..3, then 4..7), as below.
+      constexpr int PPT = 128 * (D / 8) / G::NT;
+#pragma unroll 1
+      for (int half = 0; half < 2; ++half) {
+        u32x4 held[PPT];
 #pragma unroll
-      for (int ct = 0; ct < G::CT; ++ct)
+        for (int i = 0; i < PPT; ++i) {
+          const int e = tid + G::NT * i;
+          const int r = 128 * half + e / (D / 8), c0 = 8 * (e % (D / 8));
+          held[i] = *reinterpret_cast<const u32x4*>(gout + (int64_t)(tok0 + (r < nt ? r : nt - 1)) * a.st + c0);
+        }
+        if ((w >> 2) == half) {                            // uniform per wave
+          float* orow = Ol + (qt - 128 * half) * G::OS + 4 * hi;
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<u32x2*>(orow + 32 * ct + 8 * g) =
-              u32x2{pack_bf16x2(o[ct][4 * g], o[ct][4 * g + 1]), pack_bf16x2(o[ct][4 * g + 2], o[ct][4 * g + 3])};
-      __syncthreads();
+          for (int ct = 0; ct < G::CT; ++ct)
 #pragma unroll
-      for (int i = 0; i < GT * (D / 8) / G::NT; ++i) {
-        const int e = tid + G::NT * i;
-        const int r = e / (D / 8), c0 = 8 * (e % (D / 8));
-        if (r < nt)
-          __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(Ob + r * G::OB + c0),
-                                      reinterpret_cast<u32x4*>(gout + (int64_t)(tok0 + r) * a.st + c0));
+            for (int g = 0; g < 4; ++g)
+              *reinterpret_cast<f32x4*>(orow + 32 * ct + 8 * g) = f32x4{o[ct][4 * g], o[ct][4 * g + 1], o[ct][4 * g + 2], o[ct][4 * g + 3]};
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+          const int e = tid + G::NT * i;
+          const int r = 128 * half + e / (D / 8), c0 = 8 * (e % (D / 8));
+          if (r < nt) {
+            const float* src = Ol + (r - 128 * half) * G::OS + c0;
+            const f32x4 y0 = *reinterpret_cast<const f32x4*>(src), y1 = *reinterpret_cast<const f32x4*>(src + 4);
+            const u32x4 h4 = held[i];
+            __builtin_nontemporal_store(u32x4{pack_bf16x2(y0[0] + bf16_lo_to_f32(h4[0]), y0[1] + bf16_hi_to_f32(h4[0])),
+                                              pack_bf16x2(y0[2] + bf16_lo_to_f32(h4[1]), y0[3] + bf16_hi_to_f32(h4[1])),
+                                              pack_bf16x2(y1[0] + bf16_lo_to_f32(h4[2]), y1[1] + bf16_hi_to_f32(h4[2])),
+                                              pack_bf16x2(y1[2] + bf16_lo_to_f32(h4[3]), y1[3] + bf16_hi_to_f32(h4[3]))},
+                                        reinterpret_cast<u32x4*>(gout + (int64_t)(tok0 + r) * a.st + c0));
+          }
+        }
+        __syncthreads();                                   // the staging rows are free again; after the second half, all of LDS
       }
-      __syncthreads();                                     // all of LDS is free again
     } else
 #pragma unroll 1
     for (int half = 0; half < 2; ++half) {

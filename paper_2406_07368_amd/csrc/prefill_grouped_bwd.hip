@@ -117,14 +117,28 @@ __device__ __forceinline__ void load_slot(const float* slot, uint16_t* Sl, float
   if (tid < D) zl[tid] = zx;
 }
 
-// acc[ct][r] = X[row 32w + l32][column 32ct + 8(r/4) + 4hi + r%4] (w: the wave's row tile) -> global bf16 rows, staged through LDS in fp32,
-// RP rows at a time (the waves of one pass write, all threads store whole rows).  Ends with a barrier.
+// acc[ct][r] = X[row 32w + l32][column 32ct + 8(r/4) + 4hi + r%4] (w: the wave's row tile) -> global bf16 rows, staged
+// through LDS in fp32, RP rows at a time (the waves of one pass write, all threads store whole rows).  add (uniform):
+// the rows are added to what gout holds (requested ahead of the staging; one rounding).  Ends with a barrier.
 template <int D, int GT>
 __device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], float* Ol, uint16_t* gout, int64_t st, int tok0,
-                                           int nt, int tid, int w, int l32, int hi) {
+                                           int nt, int tid, int w, int l32, int hi, bool add = false) {
   using G = BwdCfg<D, GT>;
+  constexpr int PPT = G::RP * (D / 8) / G::NT;
+  static_assert(PPT * G::NT == G::RP * (D / 8), "whole pieces per thread");
 #pragma unroll 1
   for (int pass = 0; pass < GT / G::RP; ++pass) {
+    u32x4 held[PPT];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) held[i] = u32x4{0, 0, 0, 0};
+    if (add) {
+#pragma unroll
+      for (int i = 0; i < PPT; ++i) {
+        const int e = tid + G::NT * i;
+        const int r = G::RP * pass + e / (D / 8), c0 = 8 * (e % (D / 8));
+        held[i] = *reinterpret_cast<const u32x4*>(gout + (int64_t)(tok0 + (r < nt ? r : nt - 1)) * st + c0);
+      }
+    }
     if ((32 * w) / G::RP == pass) {                          // uniform per wave
       float* orow = Ol + (32 * w + l32 - G::RP * pass) * G::OS + 4 * hi;
 #pragma unroll
@@ -134,13 +148,19 @@ __device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], float* O
           *reinterpret_cast<f32x4*>(orow + 32 * ct + 8 * g) = f32x4{acc[ct][4 * g], acc[ct][4 * g + 1], acc[ct][4 * g + 2], acc[ct][4 * g + 3]};
     }
     __syncthreads();
-    for (int e = tid; e < G::RP * (D / 8); e += G::NT) {
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) {
+      const int e = tid + G::NT * i;
       const int r = G::RP * pass + e / (D / 8), c0 = 8 * (e % (D / 8));
       if (r < nt) {
         const float* src = Ol + (r - G::RP * pass) * G::OS + c0;
         const f32x4 y0 = *reinterpret_cast<const f32x4*>(src), y1 = *reinterpret_cast<const f32x4*>(src + 4);
+        const u32x4 h4 = held[i];
         *reinterpret_cast<u32x4*>(gout + (int64_t)(tok0 + r) * st + c0) =
-            u32x4{pack_bf16x2(y0[0], y0[1]), pack_bf16x2(y0[2], y0[3]), pack_bf16x2(y1[0], y1[1]), pack_bf16x2(y1[2], y1[3])};
+            u32x4{pack_bf16x2(y0[0] + bf16_lo_to_f32(h4[0]), y0[1] + bf16_hi_to_f32(h4[0])),
+                  pack_bf16x2(y0[2] + bf16_lo_to_f32(h4[1]), y0[3] + bf16_hi_to_f32(h4[1])),
+                  pack_bf16x2(y1[0] + bf16_lo_to_f32(h4[2]), y1[1] + bf16_hi_to_f32(h4[2])),
+                  pack_bf16x2(y1[2] + bf16_lo_to_f32(h4[3]), y1[3] + bf16_hi_to_f32(h4[3]))};
       }
     }
     __syncthreads();
@@ -638,7 +658,8 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
     }
     __syncthreads();                                       // every wave is done with the d x d operand
   }
-  store_rows<D, GT>(acc4, Ol, gout, a.st, tok0, nt, tid, ktile, l32, hi);
+  // dv is added to what the conv's share left there (written ahead of this kernel); dk is written
+  store_rows<D, GT>(acc4, Ol, gout, a.st, tok0, nt, tid, ktile, l32, hi, role == 0);
 }
 
 // ---- dw: per workgroup the products of its tokens, then one sum over batch rows and token blocks --------------------
@@ -775,7 +796,7 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_reduce_kernel(const float*
 int grouped_bwd_dw_blocks(int L) { return (L + DW_TOK - 1) / DW_TOK; }
 
 template <int D, int GT>
-static hipError_t launch_bwd_core(const GroupedBwdArgs& a, hipStream_t st) {
+static hipError_t launch_bwd_core(const GroupedBwdArgs& a, hipStream_t st, hipEvent_t before_dkdv) {
   using G = BwdCfg<D, GT>;
   const int BH = a.B * a.H;
   hipError_t e;
@@ -805,6 +826,7 @@ static hipError_t launch_bwd_core(const GroupedBwdArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(grouped_bwd_suffix_kernel, dim3((unsigned)((G::SLOT + 255) / 256), (unsigned)BH), dim3(256), 0, st, a, (int)G::SLOT);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
+  if (before_dkdv && (e = hipStreamWaitEvent(st, before_dkdv, 0)) != hipSuccess) return e;
   hipLaunchKernelGGL(kk, dim3((unsigned)(2 * a.ng), (unsigned)BH), dim3(G::NT), G::TOTAL, st, a);
   return hipGetLastError();
 }
@@ -838,13 +860,16 @@ static hipError_t launch_bwd_dw(const GroupedBwdArgs& a, hipStream_t st) {
   return hipSuccess;
 }
 
-// The kernels of this file, in order.
-hipError_t launch_grouped_bwd(const GroupedBwdArgs& a, int d, hipStream_t st) {
-  hipError_t e = hipSuccess;
-  if (a.L <= 0) {}                                         // no tokens: only the conv-weight sums (zeros) are written
-  else if (d == 128) e = a.group == 256 ? launch_bwd_core<128, 256>(a, st) : launch_bwd_core<128, 64>(a, st);
-  else e = a.group == 256 ? launch_bwd_core<64, 256>(a, st) : launch_bwd_core<64, 64>(a, st);
-  if (e != hipSuccess || !a.dconv_w) return e;
+// Everything but the conv-weight sums, in order.
+hipError_t launch_grouped_bwd_core(const GroupedBwdArgs& a, int d, hipStream_t st, hipEvent_t before_dkdv) {
+  if (a.L <= 0) return hipSuccess;
+  if (d == 128) return a.group == 256 ? launch_bwd_core<128, 256>(a, st, before_dkdv) : launch_bwd_core<128, 64>(a, st, before_dkdv);
+  return a.group == 256 ? launch_bwd_core<64, 256>(a, st, before_dkdv) : launch_bwd_core<64, 64>(a, st, before_dkdv);
+}
+
+// The conv-weight sums (no tokens: zeros).
+hipError_t launch_grouped_bwd_dw(const GroupedBwdArgs& a, int d, hipStream_t st) {
+  if (!a.dconv_w) return hipSuccess;
   if (d == 128) return a.Kc <= 16 ? launch_bwd_dw<128, 16>(a, st) : a.Kc <= 32 ? launch_bwd_dw<128, 32>(a, st) : launch_bwd_dw<128, 63>(a, st);
   return a.Kc <= 16 ? launch_bwd_dw<64, 16>(a, st) : a.Kc <= 32 ? launch_bwd_dw<64, 32>(a, st) : launch_bwd_dw<64, 63>(a, st);
 }
