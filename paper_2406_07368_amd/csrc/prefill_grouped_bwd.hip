@@ -569,8 +569,10 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
     for (int r = 0; r < 16; ++r) {
       const int tl = 8 * (r >> 2) + 4 * hi + (r & 3);
       const int t = 32 * qt + tl;
-      const float arg = (qt > ktile || tl >= l32) ? fmaf(sc[r], to_log2, -ml[t]) : -INFINITY;   // a select, not a branch
-      sc[r] = __builtin_amdgcn_exp2f(arg) * il[t];
+      // (the scalars are read whatever the mask says: a read under the condition would make it a branch per element)
+      const float mt = ml[t], it = il[t];
+      const float x = fmaf(sc[r], to_log2, -mt);
+      sc[r] = __builtin_amdgcn_exp2f((qt > ktile || tl >= l32) ? x : -INFINITY) * it;
     }
     if (role == 0) {                                       // dV^T += dO^T P
       bf16x8 p0, p0l, p1, p1l;                             // the weights as hi + lo too
