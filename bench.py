@@ -441,10 +441,12 @@ def main():
         # DWConv, groups of 256 tokens, batch 1, 1K / 4K / 8K tokens, as eight heads of 128.  Token-level form
         # (matrix-core attention kernel + the long-convolution pass) and the three-branch form in groups of 256
         # (its own matrix-core kernel + the same long-convolution pass).  Eight heads cannot fill the chip: these
-        # are latency figures, a few launches of some tens of microseconds each.
+        # are latency figures, a few launches of some tens of microseconds each.  The last row is the same layer on a
+        # batch of eight sequences (2048 groups): the size at which the chip, not the launch chain, is the bound.
         flash = {}
-        for name in ("flash_L1024", "flash_L4096", "flash_L8192"):
+        for name in ("flash_L1024", "flash_L4096", "flash_L8192", "flash_B8_L8192"):
             wl = workloads.CONFIGS[name]
+            few = wl.B > 1                                  # the batch row: milliseconds per call, fewer of them
             gs = torch.Generator(device=dev).manual_seed(wl.seed)
             q, k, v = ((torch.randn((wl.B, wl.H, wl.L, wl.d), generator=gs, device=dev) * wl.scale).to(torch.bfloat16) for _ in range(3))
             out = torch.empty_like(q)
@@ -458,8 +460,8 @@ def main():
             nb = 4 * wl.B * wl.H * wl.L * wl.d * 2
             row = {"workload": f"B{wl.B} H{wl.H} L{wl.L} d{wl.d} bf16, groups of {wl.chunk}, Kc{wl.conv_k}, head-major"}
             for key, n_warm, n_timed, call in (
-                    ("token_level", 10, 30, lambda: binding.linattn_prefill(fdesc, wl.L, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream)),
-                    ("three_branch", 10, 30, lambda: binding.linattn_prefill_grouped(fdesc, wl.L, 1.0, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream))):
+                    ("token_level", 5 if few else 10, 10 if few else 30, lambda: binding.linattn_prefill(fdesc, wl.L, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream)),
+                    ("three_branch", 5 if few else 10, 10 if few else 30, lambda: binding.linattn_prefill_grouped(fdesc, wl.L, 1.0, q, k, v, fw, None, None, None, out, fS, fz, fh, fws, fws_bytes, stream))):
                 evs = []
                 for i in range(n_warm + n_timed):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -482,12 +484,13 @@ def main():
             bws_bytes = binding.linattn_backward_workspace_bytes(fdesc, wl.L)
             bws = torch.empty(max(bws_bytes, 16), dtype=torch.uint8, device=dev)
             evs = []
-            for i in range(10 + 30):
+            bwarm, btimed = (5, 10) if few else (10, 30)
+            for i in range(bwarm + btimed):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
                 binding.linattn_prefill_grouped_backward(fdesc, wl.L, 1.0, q, k, v, fw, dout, dq, dk, dv, dw, bws, bws_bytes, stream)
                 e1.record(stream)
-                if i >= 10:
+                if i >= bwarm:
                     evs.append((e0, e1))
             stream.synchronize()
             t_ms = [a.elapsed_time(b) for a, b in evs]

@@ -63,6 +63,9 @@ CONFIGS = {
     "flash_L1024": Workload("flash_L1024", "prefill", 1, 8, 1024, 128, "bf16", 256, 63, 128 ** -0.5, 1011),
     "flash_L4096": Workload("flash_L4096", "prefill", 1, 8, 4096, 128, "bf16", 256, 63, 128 ** -0.5, 1012),
     "flash_L8192": Workload("flash_L8192", "prefill", 1, 8, 8192, 128, "bf16", 256, 63, 128 ** -0.5, 1013),
+    # the same layer on a batch of eight sequences: 2048 groups of 256 tokens, several per compute unit -- the size
+    # at which the kernels of the FLASH shape are bound by the chip and not by the latency of a few launches
+    "flash_B8_L8192": Workload("flash_B8_L8192", "prefill", 8, 8, 8192, 128, "bf16", 256, 63, 128 ** -0.5, 1014),
     # value rows wider than key rows (Sec. 3, Eq. 1: d_k and d_v are separate): the LLaMA-2-7B layer shape with the
     # query/key width halved, prefill and verify
     "wide_values_prefill": Workload("wide_values_prefill", "prefill", 8, 32, 4096, 64, "bf16", 64, 3, 64 ** -0.5, 1021, (), 128),

@@ -133,3 +133,28 @@ def test_flash_shapes_every_head(name):
     compare(got, want, name)
     for n in ("dq", "dk", "dv"):
         check_unfloored(got[n], want[n], TOL["bf16"], f"{name} {n}")
+
+
+def test_flash_shape_on_a_batch_one_head_of_every_batch_row():
+    """B8 H8 L8192: 2048 groups, several rounds of every kernel.  The oracle follows one head through all eight batch
+    rows: dq, dk, dv of those rows and the conv-weight gradient of that head (a sum over the batch), forward and back."""
+    wl = workloads.CONFIGS["flash_B8_L8192"]
+    hsel = 5
+    q, k, v, w = workloads.prefill_tensors(wl)
+    dout = workloads.upstream_gradient_tensor(wl)
+    gq, gk, gv, gw, gd = q.cuda(), k.cuda(), v.cuda(), w.cuda(), dout.cuda()
+    out, (S, z, hist) = binding.prefill_grouped(gq, gk, gv, gw, 1.0, group=wl.chunk)
+    dq, dk, dv, dw = binding.prefill_grouped_backward(gq, gk, gv, gw, gd, 1.0, group=wl.chunk)
+    torch.cuda.synchronize()
+    sl = slice(hsel, hsel + 1)
+    hq, hk, hv, hd = (t[:, sl].double().numpy() for t in (q, k, v, dout))
+    hw = w[sl].double().numpy()
+    fwant = oracle.prefill_grouped(hq, hk, hv, hw, wl.chunk, alpha=1.0)
+    check(host(out[:, sl]), fwant[0], TOL["bf16"], "forward out")
+    check(host(S[:, sl]), fwant[1], TOL["bf16"], "forward S")
+    check(host(z[:, sl]), fwant[2], TOL["bf16"], "forward z")
+    want = oracle.prefill_grouped_backward(hq, hk, hv, hw, hd, wl.chunk, alpha=1.0)
+    got = {"dq": host(dq[:, sl]), "dk": host(dk[:, sl]), "dv": host(dv[:, sl]), "dw": host(dw[sl])}
+    compare(got, want, f"{wl.name} head {hsel}")
+    for n in ("dq", "dk", "dv"):
+        check_unfloored(got[n], want[n], TOL["bf16"], f"{wl.name} head {hsel} {n}")
