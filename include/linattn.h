@@ -220,11 +220,18 @@ linattn_status linattn_prefill_grouped(const linattn_desc *desc, int32_t L, floa
  *                        respect to them ((d*d+d) floats per group and head, twice),
  *                        five floats per token and head, and the partial conv-weight
  *                        sums.  Contents on entry are ignored.
- * Arithmetic: bf16 operands on the matrix cores, fp32 accumulation; dv is rounded
- * to bf16 before the conv's share is added (a second rounding).  The result does not
- * depend on the launch configuration (no atomics: fixed summation order).
+ * Arithmetic: bf16 operands on the matrix cores, fp32 accumulation; the conv's
+ * share of dv is rounded to bf16 before the rest is added to it (a second rounding).
+ * The result does not depend on the launch configuration (no atomics: fixed
+ * summation order).
  * Asynchronous on hip_stream; every argument is validated before anything is
- * enqueued. */
+ * enqueued.  Part of the work (the conv's share of dv, the conv-weight sums) runs on
+ * a second stream that the library creates at the first such call of a host thread
+ * on a device (default priority; it is forked from hip_stream and joined back into
+ * it with events inside the call, so work enqueued on hip_stream after the call
+ * sees all of the call's results, and a graph capture of hip_stream captures all of
+ * it).  If hip_stream is being captured at that first call, or the stream cannot be
+ * made, everything runs on hip_stream. */
 size_t linattn_backward_workspace_bytes(const linattn_desc *desc, int32_t L);
 
 linattn_status linattn_prefill_grouped_backward(const linattn_desc *desc, int32_t L, float alpha,
