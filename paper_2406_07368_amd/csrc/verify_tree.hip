@@ -353,9 +353,14 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   // ---- the rest of the state: normaliser and history ----------------------------------------------------
   if (acc_node < 0) return;   // uniform per workgroup
   if (!upper) {
+    // (every row is read whatever the path says and weighed by 0 or 1: reads under the condition, one after the
+    // other, were 2 x 64 dependent trips to LDS on two of the four waves at the very end of the kernel)
     float zs = zreg;
-    for (int c = 0; c < n; ++c)
-      if ((commit >> c) & 1ull) zs += bf16_bits_to_f32(sm.k[c * G::KS + cc]) + bf16_bits_to_f32(sm.klo()[c * G::KS + cc]);
+#pragma unroll 8
+    for (int c = 0; c < G::KT; ++c) {
+      const float on = ((commit >> c) & 1ull) ? 1.f : 0.f;   // rows >= n are zero rows and never on the path
+      zs = fmaf(on, bf16_bits_to_f32(sm.k[c * G::KS + cc]) + bf16_bits_to_f32(sm.klo()[c * G::KS + cc]), zs);
+    }
     a.z[(size_t)bh * D + cc] = zs;
   } else {
     // the last Kc-1 rows of (history ++ accepted path) are what the taps 0..Kc-2 of the accepted candidate read
