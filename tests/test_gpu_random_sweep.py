@@ -75,6 +75,49 @@ def test_prefill_random_case(seed):
 
 
 @pytest.mark.parametrize("seed", range(16))
+def test_groups_of_256_random_case(seed):
+    """The three-branch form in groups of 256 (bf16 rows): forward with and without an incoming state, any tap count up
+    to 63 (up to 8 taps the attention kernel adds the conv itself, beyond that it adds to what the conv pass wrote),
+    and its gradient, for which the conv pass always runs first and beside the other kernels."""
+    rng = np.random.default_rng(9500 + seed)
+    d = int(rng.choice([64, 128]))
+    Kc = int(rng.choice([1, 2, 3, 5, 8, 9, 16, 17, 33, 63]))
+    B, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    L = int(rng.choice([1, 31, 255, 256, 257, 300, 511, 513, 777, 1025, 1300]))
+    layout = str(rng.choice(["bhld", "blhd", "padded"]))
+    phi = "relu" if rng.random() < 0.25 else "elu1"
+    eps = 0.05 if phi == "relu" else float(rng.choice([0.0, 1e-3]))
+    alpha = float(rng.choice([1.0, 0.5, 2.0]))
+    scale = float(rng.choice([1.0, 0.5, d ** -0.5]))
+    q, k, v = (workloads.round_to_io(rng.standard_normal((B, H, L, d)) * scale, "bf16") for _ in range(3))
+    w = workloads.conv_weights(rng, H, d, Kc)
+    dout = workloads.upstream_gradient((B, H, L, d), "bf16", 9600 + seed)
+    state = random_state(rng, B, H, d, Kc, "bf16") if rng.random() < 0.5 else None
+    what = f"seed {seed}: d{d} Kc{Kc} B{B} H{H} L{L} {layout} {phi} alpha {alpha} scale {scale:.3f} state={state is not None}"
+    print(what, flush=True)
+    dt = torch.bfloat16
+    args = (None, None, None) if state is None else state
+    with oracle.feature_map(phi):
+        want = oracle.prefill_grouped(q, k, v, w, 256, alpha, *args, eps=eps)
+        want_b = oracle.prefill_grouped_backward(q, k, v, w, dout, 256, alpha=alpha, eps=eps)
+    gq, gk, gv, gd = (in_layout(x, dt, layout) for x in (q, k, v, dout))
+    gw = dev(w)
+    gstate = None if state is None else (dev(state[0]), dev(state[1]), dev(state[2], dt))
+    out, (S, z, h) = binding.prefill_grouped(gq, gk, gv, gw, alpha, gstate, eps, phi=phi, group=256)
+    dq, dk, dv, dw = binding.prefill_grouped_backward(gq, gk, gv, gw, gd, alpha, eps, phi=phi, group=256)
+    torch.cuda.synchronize()
+    check(host(out), want[0], TOL["bf16"], f"{what} out")
+    check(host(S), want[1], TOL["bf16"], f"{what} S")
+    check(host(z), want[2], TOL["bf16"], f"{what} z")
+    assert np.array_equal(host(h), workloads.round_to_io(want[3], "bf16").astype(np.float64)), f"{what} hist"
+    for name, got in (("dq", dq), ("dk", dk), ("dv", dv)):
+        check(host(got), want_b[name], TOL["bf16"], f"{what} {name}")
+    rms = max(float(np.sqrt(np.mean(want_b["dw"] ** 2))), 1e-30)
+    err = float(np.max(np.abs(host(dw) - want_b["dw"]))) / rms
+    assert err <= TOL["f32"], f"{what} dw: max abs err / rms {err:.3e}"
+
+
+@pytest.mark.parametrize("seed", range(16))
 def test_verify_random_case(seed):
     """Chain verify with random commit counts; whole heads (matrix cores) and split heads (streaming kernel)."""
     rng = np.random.default_rng(9100 + seed)
