@@ -179,3 +179,46 @@ def test_training_step_replays_as_a_graph():
         torch.cuda.synchronize()
         for a, b in zip(got, want):
             assert torch.equal(a, b), f"replay {replay} differs from the eager call"
+
+
+FIRST_CALL_UNDER_CAPTURE = r"""
+import sys, torch
+sys.path.insert(0, sys.argv[1])
+from paper_2406_07368_amd import binding, workloads
+wl = workloads.CONFIGS["flash_L1024"]
+q, k, v, w = (t.cuda() for t in workloads.prefill_tensors(wl))
+do = workloads.upstream_gradient_tensor(wl).cuda()
+desc = binding.make_desc(wl.B, wl.H, wl.d, wl.conv_k, wl.chunk, torch.bfloat16, L=wl.L)
+nb = binding.linattn_backward_workspace_bytes(desc, wl.L)
+ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+mk = lambda: [torch.empty_like(q) for _ in range(3)] + [torch.empty_like(w)]
+got, want = mk(), mk()
+side = torch.cuda.Stream()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g, stream=side):          # the library's very first call in this process
+    binding.linattn_prefill_grouped_backward(desc, wl.L, 1.0, q, k, v, w, do, *got, ws, nb)
+g.replay()
+torch.cuda.synchronize()
+binding.linattn_prefill_grouped_backward(desc, wl.L, 1.0, q, k, v, w, do, *want, ws, nb)   # eager: makes the side stream
+torch.cuda.synchronize()
+assert all(torch.equal(a, b) for a, b in zip(got, want)), "captured first call differs from the eager call"
+for t in got:
+    t.zero_()
+g.replay()
+torch.cuda.synchronize()
+assert all(torch.equal(a, b) for a, b in zip(got, want)), "replay after the eager call differs"
+print("ok")
+"""
+
+
+def test_gradient_captured_as_the_first_call_of_a_process():
+    """The gradient forks part of its work onto a stream the library makes at its first such call -- unless that call
+    is being captured: then everything stays on the caller's stream.  A fresh process captures the gradient before any
+    eager call, replays it, and compares with the eager call (which then does make the side stream)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-c", FIRST_CALL_UNDER_CAPTURE, root], capture_output=True, text=True, timeout=280)
+    assert res.returncode == 0 and res.stdout.strip().endswith("ok"), res.stdout[-2000:] + res.stderr[-4000:]
+
