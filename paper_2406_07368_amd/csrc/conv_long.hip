@@ -124,6 +124,22 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   }
   __syncthreads();
 
+  // The history handed on (the last Kc - 1 rows of history ++ sequence), when the launcher asked for it here: every
+  // workgroup writes the rows whose tokens it owns (t0 <= token < t0 + 64; the first one also the rows that stay
+  // history rows), straight from its LDS copy.  Asked for only when no other workgroup can still have hist_in to read.
+  if (a.hist_fused) {
+    const int R = Kc - 1;
+    for (int e = tid; e < R * (D / 8); e += 256) {
+      const int r = e / (D / 8), i0 = 8 * (e % (D / 8));
+      const int tok = L - R + r;                           // the token (negative: a row of the old history) that becomes row r
+      const bool mine = tok < L && ((tok >= t0 && tok < t0 + CL_TOK) || (tok < 0 && t0 == 0));
+      const int row = tok - t0 + CL_HALO;                  // its row in the LDS copy
+      if (mine && row >= 0)
+        *reinterpret_cast<typename Io::raw8*>(static_cast<typename Io::elem*>(a.hist_out) + hist_base + (int64_t)r * DVT + i0) =
+            *reinterpret_cast<const typename Io::raw8*>(xe + row * D + i0);
+    }
+  }
+
   // (one copy of the 500 multiply-adds in the instruction stream: the loop over the thread's blocks stays a loop)
 #pragma unroll 1
   for (int blk8 = 0; blk8 < TPT / CL_BLK; ++blk8) {
@@ -159,7 +175,8 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   }
 }
 
-// New history = the last Kc-1 rows of (incoming history ++ sequence).  Runs behind conv_long_kernel, which is the
+// New history = the last Kc-1 rows of (incoming history ++ sequence), for the cases the conv kernel cannot do on the
+// way (hist_out is hist_in on a sequence of several workgroups; no tokens).  Runs behind conv_long_kernel, which is the
 // last reader of hist_in before this.  One workgroup per (b, h, value block): every element is read (all requests in
 // flight at once) before, behind a barrier, any is written, so hist_out may be hist_in.
 template <typename Io, int D>
@@ -215,15 +232,19 @@ static hipError_t launch_cl_k(const ConvLongArgs& a, hipStream_t st) {
 }
 
 template <typename Io, int D, bool ASSIGN>
-static hipError_t launch_cl(const ConvLongArgs& a, hipStream_t st) {
+static hipError_t launch_cl(const ConvLongArgs& a_in, hipStream_t st) {
   hipError_t e = hipSuccess;
+  // The history can be handed on by the conv kernel itself unless hist_out is hist_in and several workgroups share a
+  // head: the first of them reads the old rows, the last would overwrite them, and nothing orders the two.
+  ConvLongArgs a = a_in;
+  a.hist_fused = a.hist_out != nullptr && !a.rev && a.L > 0 && (a.hist_out != a.hist_in || a.L <= CL_TOK);
   if (a.L > 0) {
     e = a.Kc <= 16   ? launch_cl_k<Io, D, 16, ASSIGN>(a, st)
         : a.Kc <= 32 ? launch_cl_k<Io, D, 32, ASSIGN>(a, st)
                      : launch_cl_k<Io, D, CL_MAXK, ASSIGN>(a, st);
     if (e != hipSuccess) return e;
   }
-  if (a.hist_out) {
+  if (a.hist_out && !a.hist_fused) {
     hipLaunchKernelGGL((conv_long_hist_kernel<Io, D>), dim3((unsigned)(a.B * a.H * a.m)), dim3(256), 0, st, a);
     e = hipGetLastError();
   }

@@ -112,6 +112,7 @@ struct ConvLongArgs {
   int m;                    // value blocks of d channels per head (d_v = m d)
   int rev;                  // the token axis runs backwards (out[t] += sum_j w[j] v[t + j]): the conv's share of the
                             // gradient with respect to its input; no history then
+  int hist_fused;           // set by the launcher: the conv kernel writes hist_out itself (no launch of its own)
   int assign;               // out = conv instead of out += conv (bf16 rows only): the pass then runs ahead of the
                             // kernel that adds the rest, and needs nothing from it
 };
