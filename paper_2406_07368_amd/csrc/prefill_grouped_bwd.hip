@@ -318,7 +318,7 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
   load_slot<D, GT>(slot, Sl, zl, tid);
   __syncthreads();
   const uint16_t* qrow_p = gq + (int64_t)(tok0 + qrow) * a.st;
-  // W[f][t] = sum_c S_g[f][c] dO[t][c], one 32-feature tile at a time; nd = phi(q).W first, then the tiles again
+  // W[f][t] = sum_c S_g[f][c] dO[t][c], one 32-feature tile at a time; nd = phi(q).W first, then the tiles' own use
   auto w_tile = [&](int ft, f32x16& wt) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) wt[r] = 0.f;
@@ -332,16 +332,16 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
   // den = phi(q).z + eps and nd = phi(q).W, both with phi(q) in fp32: f W and z dden nearly cancel, so neither may
   // carry the rounding of a bf16 phi(q)
   float nd = 0.f, dz = 0.f;
+  f32x16 wt[G::CT];                                        // kept for the second use below (the raw q rows' registers are free)
 #pragma unroll
   for (int ft = 0; ft < G::CT; ++ft) {
-    f32x16 wt;
-    w_tile(ft, wt);
+    w_tile(ft, wt[ft]);
     float qv[16];
     row_in_acc_order(qrow_p, ft, hi, qv);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float fqv = phi_f(qv[r], a.relu);
-      nd = fmaf(fqv, wt[r], nd);
+      nd = fmaf(fqv, wt[ft][r], nd);
       dz = fmaf(fqv, zl[32 * ft + 8 * (r >> 2) + 4 * hi + (r & 3)], dz);
     }
   }
@@ -352,14 +352,12 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
   const float dden = gden != 0.f ? -fscale * nd / gden : 0.f;
 #pragma unroll
   for (int ft = 0; ft < G::CT; ++ft) {
-    f32x16 wt;
-    w_tile(ft, wt);
     float qv[16];
     row_in_acc_order(qrow_p, ft, hi, qv);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int f = 32 * ft + 8 * (r >> 2) + 4 * hi + (r & 3);
-      dqa[ft][r] = fmaf(fmaf(fscale, wt[r], zl[f] * dden), dphi_f(qv[r], a.relu), dqa[ft][r]);
+      dqa[ft][r] = fmaf(fmaf(fscale, wt[ft][r], zl[f] * dden), dphi_f(qv[r], a.relu), dqa[ft][r]);
     }
   }
   // the per-token scalars for the kernels that follow
