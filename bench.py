@@ -34,7 +34,9 @@ import argparse
 import json
 import os
 import re
+import glob
 import sys
+import threading
 import time
 
 import numpy as np
@@ -44,6 +46,64 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 from paper_2406_07368_amd import binding, workloads  # noqa: E402
+
+
+class BoardTelemetry:
+    """The board's own sensors (sysfs: socket power in microwatts, the core clock level marked with '*'), read from a
+    thread every 20 ms between start() and stop().  Not a profiler and not part of any timing: it says whether the
+    timed steps ran at the power limit and at which core clock.  Sensors that cannot be read are left out."""
+
+    def __init__(self):
+        self.power = next(iter(sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                                      glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))), None)
+        self.sclk = next(iter(sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))), None)
+        cap = self.power and os.path.join(os.path.dirname(self.power), "power1_cap")
+        self.cap_w = self._read_float(cap, 1e-6) if cap and os.path.exists(cap) else None
+        self.watts, self.mhz, self._stop, self._thread = [], [], threading.Event(), None
+
+    @staticmethod
+    def _read_float(path, scale):
+        try:
+            with open(path) as f:
+                return float(f.read().split()[0]) * scale
+        except (OSError, ValueError, IndexError):
+            return None
+
+    def _sample(self):
+        if self.power:
+            w = self._read_float(self.power, 1e-6)
+            if w is not None:
+                self.watts.append(w)
+        if self.sclk:
+            try:
+                with open(self.sclk) as f:
+                    m = re.search(r"(\d+)\s*Mhz\s*\*", f.read(), re.I)
+                if m:
+                    self.mhz.append(float(m.group(1)))
+            except OSError:
+                pass
+
+    def start(self):
+        if not (self.power or self.sclk):
+            return
+
+        def loop():
+            while not self._stop.wait(0.02):
+                self._sample()
+        self._thread = threading.Thread(target=loop, daemon=True)
+        self._thread.start()
+
+    def stop(self):
+        self._stop.set()
+        if self._thread:
+            self._thread.join()
+        out = {"what": "board sensors sampled every 20 ms over the settling and the timed steps (not a measurement of any kernel)"}
+        if self.watts:
+            out["socket_power_w"] = {"mean": sum(self.watts) / len(self.watts), "max": max(self.watts), "samples": len(self.watts),
+                                     "limit": self.cap_w}
+        if self.mhz:
+            out["core_clock_mhz"] = {"mean": sum(self.mhz) / len(self.mhz), "min": min(self.mhz), "samples": len(self.mhz)}
+        return out if len(out) > 1 else None
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix throughput
@@ -237,6 +297,8 @@ def main():
     # not show).  The unsettled figures are reported beside the settled ones.
     settle_name = "prefill" if do_prefill else "verify8"
     settle_steps, settle_hist, meds = 0, [], []
+    sensors = BoardTelemetry()
+    sensors.start()
     while settle_steps < SETTLE_CAP:
         n0 = len(ev[settle_name])
         for i in range(SETTLE_WINDOW):
@@ -269,6 +331,7 @@ def main():
     stream.synchronize()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
+    telemetry = sensors.stop()
 
     other_layout_ms = None
     if do_prefill and args.only == "all":
@@ -612,6 +675,7 @@ def main():
                    "unsettled_ms": {"first": settle_hist[0], "max": max(settle_hist), "mean_first_window": float(np.mean(settle_hist[:SETTLE_WINDOW]))},
                    "settled_window_ms": float(np.median(settle_hist[-SETTLE_WINDOW:])),
                    "window_medians_ms": [float(np.median(settle_hist[i:i + SETTLE_WINDOW])) for i in range(0, len(settle_hist), SETTLE_WINDOW)]},
+        "telemetry": telemetry,
         "ms_per_step": wall_ms / args.steps, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{pw.name} B{pw.B} H{pw.H} L{pw.L} d{pw.d} bf16 chunk{pw.chunk} Kc{pw.conv_k} (prefill) + "
