@@ -122,6 +122,7 @@ def parse_args():
     ap.add_argument("--only", choices=["all", "prefill", "verify"], default="all",
                     help="restrict the step to one stage (for profiling runs)")
     ap.add_argument("--state-sets", type=int, default=32)
+    ap.add_argument("--no-telemetry", action="store_true", help="do not sample the board's power and clock sensors")
     ap.add_argument("--prefill-workload", default="cfg3_llama7b_prefill",
                     choices=["cfg2_gpt2_small", "cfg3_llama7b_prefill", "cfg5_long_context"],
                     help="prefill workload of the step (the headline is cfg3; the others are for side measurements)")
@@ -292,13 +293,15 @@ def main():
     # Whatever --warmup says, untimed steps go on until the duration of the dominant launch has settled:
     # a GPU that was idle runs its first launches at boost clock, is then pulled down hard by the power
     # management and recovers over some tens of launches.  Settled = every duration of the last window lies
-    # within +-5 % of the window's median, and the medians of the last three windows differ by at most 1 % from
-    # one to the next (the recovery is a slow drift, about 1 % per window towards its end, that two windows do
-    # not show).  The unsettled figures are reported beside the settled ones.
+    # within +-5 % of the window's median, and the medians of the last four windows lie within 1 % of each other
+    # (the recovery is a slow drift, about 1 % per window towards its end: three windows each within 1 % of the one
+    # before it still let a run start 8 % above the level it reached 100 steps later, on a GPU that another job
+    # had just left warm).  The unsettled figures are reported beside the settled ones.
     settle_name = "prefill" if do_prefill else "verify8"
     settle_steps, settle_hist, meds = 0, [], []
     sensors = BoardTelemetry()
-    sensors.start()
+    if not args.no_telemetry:
+        sensors.start()
     while settle_steps < SETTLE_CAP:
         n0 = len(ev[settle_name])
         for i in range(SETTLE_WINDOW):
@@ -309,7 +312,7 @@ def main():
         settle_hist.extend(last)
         med = float(np.median(last))
         meds.append(med)
-        if (len(meds) >= 3 and abs(meds[-1] - meds[-2]) <= 0.01 * med and abs(meds[-2] - meds[-3]) <= 0.01 * med
+        if (len(meds) >= 4 and max(meds[-4:]) - min(meds[-4:]) <= 0.01 * med
                 and max(abs(t - med) for t in last) <= 0.05 * med):
             break
     # the timed region follows at once (an idle gap of a few milliseconds would send the clock through its hump
@@ -671,7 +674,7 @@ def main():
         "value": None, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "settle_steps": settle_steps,
         "settle": {"kernel": settle_name, "rule": f"untimed steps in windows of {SETTLE_WINDOW} until every duration of a window lies within 5 % "
-                                                  f"of its median and the medians of three windows in a row within 1 % of each other (at most {SETTLE_CAP})",
+                                                  f"of its median and the medians of four windows in a row within 1 % of each other (at most {SETTLE_CAP})",
                    "unsettled_ms": {"first": settle_hist[0], "max": max(settle_hist), "mean_first_window": float(np.mean(settle_hist[:SETTLE_WINDOW]))},
                    "settled_window_ms": float(np.median(settle_hist[-SETTLE_WINDOW:])),
                    "window_medians_ms": [float(np.median(settle_hist[i:i + SETTLE_WINDOW])) for i in range(0, len(settle_hist), SETTLE_WINDOW)]},
