@@ -511,8 +511,13 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dkdv_kernel(GroupedBwdArgs
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
-  const int role = blockIdx.x & 1;                         // 0: dv, 1: dk
-  const int g = blockIdx.x >> 1, bh = blockIdx.y;
+  // The two workgroups of a group (0: dv, 1: dk) read the same Q and dO rows: they get block indices 8 apart, which
+  // the dispatcher places on the same chiplet, so that the second of them finds the rows in that chiplet's L2 (blocks
+  // 0..7 = groups 0..7 for dv, 8..15 = the same groups for dk, and so on; a remainder of fewer than 8 groups alternates).
+  const int full = (a.ng >> 3) << 3, bx = blockIdx.x;
+  const int role = bx < 2 * full ? (bx >> 3) & 1 : (bx - 2 * full) & 1;
+  const int g = bx < 2 * full ? ((bx >> 4) << 3) | (bx & 7) : full + ((bx - 2 * full) >> 1);
+  const int bh = blockIdx.y;
   const int b = bh / a.H, h = bh % a.H;
   const int tok0 = g * GT;
   const int nt = (a.L - tok0) < GT ? (a.L - tok0) : GT;
