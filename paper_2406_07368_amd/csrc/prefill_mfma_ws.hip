@@ -140,7 +140,15 @@ __global__ __launch_bounds__(D * 4) void prefill_mfma_ws_kernel(PrefillArgs a) {
 
   const int nseg_grid = STATE_ONLY ? a.nseg - 1 : a.nseg;
   // a workgroup is one (b, h, value block) -- or one segment of it; with d_v = d there is one block per head
-  const HeadIndex hx = head_index(a, blockIdx.x / nseg_grid, D);
+  // The value blocks of a head read the same q and k rows: without segments they get block indices 8 apart, which
+  // the dispatcher places on the same chiplet, so that all but the first of them find the rows in that chiplet's L2
+  // (blocks 0..7 = heads 0..7, value block 0; 8..15 = the same heads, value block 1; ...).
+  int bhs_idx = blockIdx.x / nseg_grid;
+  if (a.m > 1 && nseg_grid == 1 && (a.B * a.H) % 8 == 0) {
+    const int bx = blockIdx.x;
+    bhs_idx = ((bx / (8 * a.m)) * 8 + (bx & 7)) * a.m + (bx >> 3) % a.m;
+  }
+  const HeadIndex hx = head_index(a, bhs_idx, D);
   const int seg = blockIdx.x % nseg_grid;
   const int bh = hx.bh, h = hx.h, DVT = hx.dvt;
   const int t_begin = seg * a.seg_len;
