@@ -40,7 +40,11 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   // one (b, h, value block of D channels); d_v = D: one block per head
   const int bh = blockIdx.y / a.m, blk = blockIdx.y % a.m, b = bh / a.H, h = bh % a.H;
   const int DVT = a.m * D;
-  const int t0 = blockIdx.x * CL_TOK;
+  // Neighbouring token blocks share 62 of their rows: block indices 8 apart land on the same chiplet, so they get
+  // neighbouring token blocks, and the shared rows come from that chiplet's L2 (when the count is a multiple of 8).
+  const int nblk = gridDim.x;
+  const int tblk = nblk % 8 == 0 ? (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3) : (int)blockIdx.x;
+  const int t0 = tblk * CL_TOK;
   const int Kc = a.Kc, L = a.L;
   const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh + (int64_t)blk * D;
   const int64_t hist_base = (int64_t)bh * (Kc - 1) * DVT + (int64_t)blk * D;

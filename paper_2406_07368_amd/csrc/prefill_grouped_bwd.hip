@@ -694,7 +694,11 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_kernel(GroupedBwdArgs a) {
   static_assert(TPT % DW_BLK == 0, "whole blocks of gradients per thread");
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
-  const int t0 = blockIdx.x * DW_TOK;
+  // (neighbouring token blocks share 62 value rows: block indices 8 apart, which land on the same chiplet, get
+  // neighbouring token blocks when the count is a multiple of 8)
+  const int nblk = gridDim.x;
+  const int tblk = nblk % 8 == 0 ? (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3) : (int)blockIdx.x;
+  const int t0 = tblk * DW_TOK;
   const int L = a.L, Kc = a.Kc;
   const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh;
   const uint16_t* gv = static_cast<const uint16_t*>(a.v) + base;
@@ -779,7 +783,7 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_kernel(GroupedBwdArgs a) {
   }
   __syncthreads();
   // partial sums of a head lie together: [H][B * nwb][D * Kc]
-  float* part = a.dw_part + (((size_t)h * a.B + b) * a.nwb + blockIdx.x) * D * Kc;
+  float* part = a.dw_part + (((size_t)h * a.B + b) * a.nwb + tblk) * D * Kc;
   for (int e = tid; e < D * Kc; e += 256) part[e] = red[(e / Kc) * KMAX + e % Kc];
 }
 
