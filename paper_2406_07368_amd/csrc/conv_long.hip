@@ -7,7 +7,7 @@
 // The attention kernels keep an 8-row halo of V in LDS and gather the taps per token; a 62-row halo does not
 // fit next to their row buffers, and 63 taps per output are a vector-ALU workload of the size of the attention
 // itself.  So long kernels are register-blocked here instead: a thread owns one channel, holds its taps in
-// registers and slides over 8 outputs at a time, every value row read from LDS feeding up to 8 multiply-adds.
+// registers and slides over 16 outputs at a time, every value row read from LDS feeding up to 16 multiply-adds.
 // One workgroup = 64 tokens of one (b, h); rows t0-62 .. t0+63 of V are staged in LDS as they lie in memory.
 #include "common.h"
 #include "kernels.h"
@@ -18,7 +18,7 @@ namespace {
 constexpr int CL_TOK = 64;        // tokens per workgroup
 constexpr int CL_HALO = 62;       // rows before them that the longest kernel reaches
 constexpr int CL_MAXK = 63;
-constexpr int CL_BLK = 8;         // outputs a thread carries at once
+constexpr int CL_BLK = 16;        // outputs a thread carries at once
 }  // namespace
 
 // KMAX: tap capacity of the instantiation (taps beyond Kc are zeros; the loops below are straight-line code for
@@ -77,8 +77,8 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       have[i] = in_seq || in_hist;
     }
   };
-  // what the attention kernels left in out, as it lies in memory (converted where it is added to), eight tokens at a
-  // time: the first eight with the first requests, the next eight while the current ones are being computed (all 32
+  // what the attention kernels left in out, as it lies in memory (converted where it is added to), sixteen tokens at a
+  // time: the first sixteen with the first requests, the next while the current ones are being computed (all 32
   // at once would cost the registers that let a second and third workgroup share the compute unit).  Past the end: the
   // first token's element, never stored.
   [[maybe_unused]] typename Io::elem prev[CL_BLK];
