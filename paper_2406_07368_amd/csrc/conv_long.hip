@@ -8,17 +8,19 @@
 // fit next to their row buffers, and 63 taps per output are a vector-ALU workload of the size of the attention
 // itself.  So long kernels are register-blocked here instead: a thread owns one channel, holds its taps in
 // registers and slides over 16 outputs at a time, every value row read from LDS feeding up to 16 multiply-adds.
-// One workgroup = 64 tokens of one (b, h); rows t0-62 .. t0+63 of V are staged in LDS as they lie in memory.
+// One workgroup = 64 (or 32) tokens of one (b, h); rows t0-62 .. t0+63 of V are staged in LDS as they lie in memory.
 #include "common.h"
 #include "kernels.h"
 
 namespace linattn {
 
 namespace {
-constexpr int CL_TOK = 64;        // tokens per workgroup
+constexpr int CL_TOK = 64;        // tokens per workgroup (32 when that still leaves compute units without one: a
+                                  // workgroup's time is one thread's chain over its tokens, and half the chain is
+                                  // worth more then than the halo rows it reads twice)
 constexpr int CL_HALO = 62;       // rows before them that the longest kernel reaches
 constexpr int CL_MAXK = 63;
-constexpr int CL_BLK = 16;        // outputs a thread carries at once
+constexpr int CL_BLK = 16;        // outputs a thread carries at once (fewer if it has fewer tokens)
 }  // namespace
 
 // KMAX: tap capacity of the instantiation (taps beyond Kc are zeros; the loops below are straight-line code for
@@ -27,15 +29,16 @@ constexpr int CL_BLK = 16;        // outputs a thread carries at once
 static __device__ __forceinline__ float elem_to_f32(float x) { return x; }
 static __device__ __forceinline__ float elem_to_f32(uint16_t x) { return bf16_bits_to_f32(x); }
 
-template <typename Io, int D, int KMAX, bool ASSIGN>
+template <typename Io, int D, int KMAX, bool ASSIGN, int TOK>
 __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
-  // the value rows [CL_HALO + CL_TOK][D] as they lie in memory (bf16 rows stay bf16: half the LDS of fp32 rows, so
+  // the value rows [CL_HALO + TOK][D] as they lie in memory (bf16 rows stay bf16: half the LDS of fp32 rows, so
   // twice the workgroups per compute unit); before them, for a moment, the taps as fp32
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_cl[];
   float* xs = reinterpret_cast<float*>(smem_cl);
   typename Io::elem* xe = reinterpret_cast<typename Io::elem*>(smem_cl);
   constexpr int NG = 256 / D;                 // token groups of threads
-  constexpr int TPT = CL_TOK / NG;            // tokens per thread
+  constexpr int TPT = TOK / NG;            // tokens per thread
+  constexpr int BLK = TPT < CL_BLK ? TPT : CL_BLK;
   const int tid = threadIdx.x;
   // one (b, h, value block of D channels); d_v = D: one block per head
   const int bh = blockIdx.y / a.m, blk = blockIdx.y % a.m, b = bh / a.H, h = bh % a.H;
@@ -44,7 +47,7 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   // neighbouring token blocks, and the shared rows come from that chiplet's L2 (when the count is a multiple of 8).
   const int nblk = gridDim.x;
   const int tblk = nblk % 8 == 0 ? (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3) : (int)blockIdx.x;
-  const int t0 = tblk * CL_TOK;
+  const int t0 = tblk * TOK;
   const int Kc = a.Kc, L = a.L;
   const int64_t base = (int64_t)b * a.sb + (int64_t)h * a.sh + (int64_t)blk * D;
   const int64_t hist_base = (int64_t)bh * (Kc - 1) * DVT + (int64_t)blk * D;
@@ -56,7 +59,7 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   // between lanes; Kc odd or not, at most a 2-way bank conflict, once per workgroup).
   // Every request of the workgroup -- taps, value rows, the 32 elements of out that the thread adds to -- is issued
   // before the first wait: one trip to memory per workgroup instead of one per stage.
-  constexpr int RIT = ((CL_HALO + CL_TOK) * (D / 8) + 255) / 256;
+  constexpr int RIT = ((CL_HALO + TOK) * (D / 8) + 255) / 256;
   typename Io::raw8 raw[RIT];
   bool have[RIT];
   auto issue_rows = [&]() __attribute__((always_inline)) {
@@ -81,11 +84,11 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   // time: the first sixteen with the first requests, the next while the current ones are being computed (all 32
   // at once would cost the registers that let a second and third workgroup share the compute unit).  Past the end: the
   // first token's element, never stored.
-  [[maybe_unused]] typename Io::elem prev[CL_BLK];
-  auto issue_prev = [&](int blk8, typename Io::elem (&dst)[CL_BLK]) __attribute__((always_inline)) {
+  [[maybe_unused]] typename Io::elem prev[BLK];
+  auto issue_prev = [&](int blk8, typename Io::elem (&dst)[BLK]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int e = 0; e < CL_BLK; ++e) {
-      const int tok = t0 + tg * TPT + blk8 * CL_BLK + e;
+    for (int e = 0; e < BLK; ++e) {
+      const int tok = t0 + tg * TPT + blk8 * BLK + e;
       const int mt = tok < L ? (a.rev ? L - 1 - tok : tok) : 0;
       dst[e] = static_cast<const typename Io::elem*>(a.out)[base + (int64_t)mt * a.st + c];
     }
@@ -119,7 +122,7 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
     for (int i = 0; i < RIT; ++i) {
       const int e = tid + 256 * i;
       const int row = e / (D / 8), i0 = 8 * (e % (D / 8));
-      if (e < (CL_HALO + CL_TOK) * (D / 8)) {
+      if (e < (CL_HALO + TOK) * (D / 8)) {
         typename Io::raw8 y = raw[i];
         if (!have[i]) y = typename Io::raw8{};
         *reinterpret_cast<typename Io::raw8*>(xe + row * D + i0) = y;
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
     for (int e = tid; e < R * (D / 8); e += 256) {
       const int r = e / (D / 8), i0 = 8 * (e % (D / 8));
       const int tok = L - R + r;                           // the token (negative: a row of the old history) that becomes row r
-      const bool mine = tok < L && ((tok >= t0 && tok < t0 + CL_TOK) || (tok < 0 && t0 == 0));
+      const bool mine = tok < L && ((tok >= t0 && tok < t0 + TOK) || (tok < 0 && t0 == 0));
       const int row = tok - t0 + CL_HALO;                  // its row in the LDS copy
       if (mine && row >= 0)
         *reinterpret_cast<typename Io::raw8*>(static_cast<typename Io::elem*>(a.hist_out) + hist_base + (int64_t)r * DVT + i0) =
@@ -146,35 +149,35 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
 
   // (one copy of the 500 multiply-adds in the instruction stream: the loop over the thread's blocks stays a loop)
 #pragma unroll 1
-  for (int blk8 = 0; blk8 < TPT / CL_BLK; ++blk8) {
-    const int tb0 = tg * TPT + blk8 * CL_BLK;
-    float acc[CL_BLK];
-    [[maybe_unused]] typename Io::elem next[CL_BLK];
-    if constexpr (!ASSIGN) issue_prev(blk8 + 1 < TPT / CL_BLK ? blk8 + 1 : blk8, next);
+  for (int blk8 = 0; blk8 < TPT / BLK; ++blk8) {
+    const int tb0 = tg * TPT + blk8 * BLK;
+    float acc[BLK];
+    [[maybe_unused]] typename Io::elem next[BLK];
+    if constexpr (!ASSIGN) issue_prev(blk8 + 1 < TPT / BLK ? blk8 + 1 : blk8, next);
 #pragma unroll
-    for (int e = 0; e < CL_BLK; ++e) acc[e] = 0.f;
+    for (int e = 0; e < BLK; ++e) acc[e] = 0.f;
     // value rows from the newest output's own row backwards: row m feeds output e through tap e - 7 + m
-    const typename Io::elem* newest = xe + (CL_HALO + tb0 + CL_BLK - 1) * D + c;
+    const typename Io::elem* newest = xe + (CL_HALO + tb0 + BLK - 1) * D + c;
     // (fully unrolled, so that every tap index is a constant and the taps stay in registers)
 #pragma unroll
-    for (int m = 0; m < KMAX + CL_BLK - 1; ++m) {
+    for (int m = 0; m < KMAX + BLK - 1; ++m) {
       const float x = elem_to_f32(newest[-m * D]);
 #pragma unroll
-      for (int e = 0; e < CL_BLK; ++e) {
-        constexpr int J0 = -(CL_BLK - 1);
+      for (int e = 0; e < BLK; ++e) {
+        constexpr int J0 = -(BLK - 1);
         const int j = e + J0 + m;
         if (j >= 0 && j < KMAX) acc[e] = fmaf(wreg[j], x, acc[e]);
       }
     }
 #pragma unroll
-    for (int e = 0; e < CL_BLK; ++e) {
+    for (int e = 0; e < BLK; ++e) {
       const int tok = t0 + tb0 + e;
       if (tok < L)
         Io::store1(a.out, base + (int64_t)(a.rev ? L - 1 - tok : tok) * a.st + c, ASSIGN ? acc[e] : elem_to_f32(prev[e]) + acc[e]);
     }
     if constexpr (!ASSIGN) {
 #pragma unroll
-      for (int e = 0; e < CL_BLK; ++e) prev[e] = next[e];
+      for (int e = 0; e < BLK; ++e) prev[e] = next[e];
     }
   }
 }
@@ -224,15 +227,22 @@ __global__ __launch_bounds__(256) void conv_long_hist_kernel(ConvLongArgs a) {
   }
 }
 
-template <typename Io, int D, int KMAX, bool ASSIGN>
-static hipError_t launch_cl_k(const ConvLongArgs& a, hipStream_t st) {
-  constexpr int LDS_ROWS = (CL_HALO + CL_TOK) * D * (int)sizeof(typename Io::elem), LDS_TAPS = D * KMAX * (int)sizeof(float);
+template <typename Io, int D, int KMAX, bool ASSIGN, int TOK>
+static hipError_t launch_cl_t(const ConvLongArgs& a, hipStream_t st) {
+  constexpr int LDS_ROWS = (CL_HALO + TOK) * D * (int)sizeof(typename Io::elem), LDS_TAPS = D * KMAX * (int)sizeof(float);
   constexpr int LDS = LDS_ROWS > LDS_TAPS ? LDS_ROWS : LDS_TAPS;
-  auto kern = conv_long_kernel<Io, D, KMAX, ASSIGN>;
+  auto kern = conv_long_kernel<Io, D, KMAX, ASSIGN, TOK>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kern, dim3((unsigned)((a.L + CL_TOK - 1) / CL_TOK), (unsigned)(a.B * a.H * a.m)), dim3(256), LDS, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)((a.L + TOK - 1) / TOK), (unsigned)(a.B * a.H * a.m)), dim3(256), LDS, st, a);
   return hipGetLastError();
+}
+
+template <typename Io, int D, int KMAX, bool ASSIGN>
+static hipError_t launch_cl_k(const ConvLongArgs& a, hipStream_t st) {
+  // fewer 64-token workgroups than compute units: 32 tokens each
+  const int64_t wgs = (int64_t)((a.L + CL_TOK - 1) / CL_TOK) * a.B * a.H * a.m;
+  return wgs < 256 ? launch_cl_t<Io, D, KMAX, ASSIGN, CL_TOK / 2>(a, st) : launch_cl_t<Io, D, KMAX, ASSIGN, CL_TOK>(a, st);
 }
 
 template <typename Io, int D, bool ASSIGN>
@@ -241,7 +251,7 @@ static hipError_t launch_cl(const ConvLongArgs& a_in, hipStream_t st) {
   // The history can be handed on by the conv kernel itself unless hist_out is hist_in and several workgroups share a
   // head: the first of them reads the old rows, the last would overwrite them, and nothing orders the two.
   ConvLongArgs a = a_in;
-  a.hist_fused = a.hist_out != nullptr && !a.rev && a.L > 0 && (a.hist_out != a.hist_in || a.L <= CL_TOK);
+  a.hist_fused = a.hist_out != nullptr && !a.rev && a.L > 0 && (a.hist_out != a.hist_in || a.L <= CL_TOK / 2);
   if (a.L > 0) {
     e = a.Kc <= 16   ? launch_cl_k<Io, D, 16, ASSIGN>(a, st)
         : a.Kc <= 32 ? launch_cl_k<Io, D, 32, ASSIGN>(a, st)
