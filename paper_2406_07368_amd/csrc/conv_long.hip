@@ -7,7 +7,8 @@
 // The attention kernels keep an 8-row halo of V in LDS and gather the taps per token; a 62-row halo does not
 // fit next to their row buffers, and 63 taps per output are a vector-ALU workload of the size of the attention
 // itself.  So long kernels are register-blocked here instead: a thread owns one channel, holds its taps in
-// registers and slides over 16 outputs at a time, every value row read from LDS feeding up to 16 multiply-adds.
+// registers and slides over 16 (adding to out: 8) outputs at a time, every value row read from LDS feeding that many
+// multiply-adds.
 // One workgroup = 64 (or 32) tokens of one (b, h); rows t0-62 .. t0+63 of V are staged in LDS as they lie in memory.
 #include "common.h"
 #include "kernels.h"
@@ -20,7 +21,7 @@ constexpr int CL_TOK = 64;        // tokens per workgroup (32 when that still le
                                   // worth more then than the halo rows it reads twice)
 constexpr int CL_HALO = 62;       // rows before them that the longest kernel reaches
 constexpr int CL_MAXK = 63;
-constexpr int CL_BLK = 16;        // outputs a thread carries at once (fewer if it has fewer tokens)
+constexpr int CL_BLK = 16;        // outputs a thread carries at once (fewer if it has fewer tokens; half when adding to out)
 }  // namespace
 
 // KMAX: tap capacity of the instantiation (taps beyond Kc are zeros; the loops below are straight-line code for
@@ -38,7 +39,10 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
   typename Io::elem* xe = reinterpret_cast<typename Io::elem*>(smem_cl);
   constexpr int NG = 256 / D;                 // token groups of threads
   constexpr int TPT = TOK / NG;            // tokens per thread
-  constexpr int BLK = TPT < CL_BLK ? TPT : CL_BLK;
+  // (adding to out, a block also holds its own and the next block's elements of out: with sixteen the registers allow
+  // two workgroups per compute unit instead of three, which costs 13 % at a chip-filling size)
+  constexpr int BLK_MAX = ASSIGN ? CL_BLK : CL_BLK / 2;
+  constexpr int BLK = TPT < BLK_MAX ? TPT : BLK_MAX;
   const int tid = threadIdx.x;
   // one (b, h, value block of D channels); d_v = D: one block per head
   const int bh = blockIdx.y / a.m, blk = blockIdx.y % a.m, b = bh / a.H, h = bh % a.H;
@@ -80,8 +84,8 @@ __global__ __launch_bounds__(256) void conv_long_kernel(ConvLongArgs a) {
       have[i] = in_seq || in_hist;
     }
   };
-  // what the attention kernels left in out, as it lies in memory (converted where it is added to), sixteen tokens at a
-  // time: the first sixteen with the first requests, the next while the current ones are being computed (all 32
+  // what the attention kernels left in out, as it lies in memory (converted where it is added to), a block of tokens at a
+  // time: the first block with the first requests, the next while the current ones are being computed (all 32
   // at once would cost the registers that let a second and third workgroup share the compute unit).  Past the end: the
   // first token's element, never stored.
   [[maybe_unused]] typename Io::elem prev[BLK];
