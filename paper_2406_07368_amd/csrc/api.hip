@@ -1,6 +1,7 @@
 // C ABI (include/linattn.h): argument validation, launch planning, dispatch.
-// No device memory is allocated here and nothing is kept between calls (one setting apart:
-// linattn_set_wait_limit).
+// No device memory is allocated here.  What is kept between calls: the wait limit (linattn_set_wait_limit), the
+// device address of the static scratch of linattn_prefill_noalloc, and the gradient's side stream with its events
+// (one per host thread and device); no results, no buffers.
 #include "../../include/linattn.h"
 
 #include <hip/hip_runtime.h>

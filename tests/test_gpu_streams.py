@@ -46,3 +46,42 @@ def test_calls_on_four_streams_overlap_without_interfering():
         for a_list, b_list in zip(got, want):
             for a, b in zip(a_list, b_list):
                 assert torch.equal(a, b)
+
+
+def test_gradient_calls_from_two_streams_and_two_host_threads():
+    """The gradient forks part of its work to a stream of the library's own (one per host thread and device) and joins it
+    before it returns: calls of one thread on two streams share that stream, calls of two threads do not, and all give
+    the bits that one call after the other gives."""
+    import threading
+    B, H, d, Kc, L = 2, 4, 128, 63, 1100
+    rng = np.random.default_rng(82)
+    gw = dev(workloads.conv_weights(rng, H, d, Kc))
+    jobs = [tuple(dev(workloads.round_to_io(rng.standard_normal((B, H, L, d)), "bf16"), BF) for _ in range(4)) for _ in range(4)]
+
+    def grad(job, stream):
+        q, k, v, dout = job
+        return binding.prefill_grouped_backward(q, k, v, gw, dout, 0.9, 1e-3, stream=stream, group=256)
+
+    torch.cuda.synchronize()
+    want = [grad(job, torch.cuda.current_stream()) for job in jobs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in jobs]
+    got = [None] * len(jobs)
+
+    def worker(idx):                       # two jobs per thread, each on a stream of its own, three rounds
+        for _ in range(3):
+            for i in idx:
+                with torch.cuda.stream(streams[i]):
+                    got[i] = grad(jobs[i], streams[i])
+            for i in idx:
+                streams[i].synchronize()
+
+    threads = [threading.Thread(target=worker, args=(idx,)) for idx in ((0, 1), (2, 3))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for a_list, b_list in zip(got, want):
+        for a, b in zip(a_list, b_list):
+            assert torch.equal(a, b)
