@@ -86,7 +86,10 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   const int n = a.n, Kc = a.Kc;
   const int cw = 32 * w + l32;               // the channel this lane owns in the state tiles
 
-  // ---- the candidates and the other small inputs are requested first, then the state -------------
+  // ---- every request of the call is issued before anything waits: the candidates and the small inputs first (they
+  //      are needed first), then the state.  All of them unconditional -- a request under a condition that depends on
+  //      the lane ends in a wait for everything before it, and three of those in a row kept the state requests back
+  //      for three trips to memory --: indices past the end are clamped and what they bring is dropped. ------------
   const int64_t tok0 = (int64_t)bh * n * D;
   const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
   u32x4 rq[G::QP], rk[G::QP], rv[G::QP];
@@ -94,45 +97,45 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   for (int m = 0; m < G::QP; ++m) {
     const int piece = tid + G::NT * m;
     const int dj = piece / (D / 8), di0 = 8 * (piece % (D / 8));
-    rq[m] = rk[m] = rv[m] = u32x4{0, 0, 0, 0};
-    if (dj < n) {
-      rq[m] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.q) + tok0 + (int64_t)dj * D + di0);
-      rk[m] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.k) + tok0 + (int64_t)dj * D + di0);
-      rv[m] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.v) + tok0 + (int64_t)dj * D + di0);
-    }
+    const int64_t off = tok0 + (int64_t)(dj < n ? dj : n - 1) * D + di0;
+    rq[m] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.q) + off);
+    rk[m] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.k) + off);
+    rv[m] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(a.v) + off);
   }
-  // taps, history and z: channel tid % D; the lower D threads take the taps and z, the upper D the history
+  // taps and history rows: element e = tid + NT m of the [8][D] arrays in LDS; z and parent: one element per thread
+  constexpr int TAP_IT = 8 * D / G::NT;
+  uint32_t tap_reg[TAP_IT], hist_reg[TAP_IT];
+  // (one tap: no history, and any address that can be read serves)
+  const uint16_t* hsrc = Kc > 1 ? static_cast<const uint16_t*>(a.hist) + hist0 : static_cast<const uint16_t*>(a.v) + tok0;
+#pragma unroll
+  for (int mth = 0; mth < TAP_IT; ++mth) {
+    const int e = tid + G::NT * mth;
+    const int t = e / D, c = e % D;
+    tap_reg[mth] = __float_as_uint(a.conv_w[((size_t)h * D + c) * Kc + (t < Kc ? t : 0)]);
+    const int back = HALO - t;                // LDS row t holds the value row HALO - t positions before the candidates
+    hist_reg[mth] = hsrc[(size_t)(back <= Kc - 1 ? Kc - 1 - back : 0) * D + c];
+  }
   const int cc = tid % D, upper = tid / D;
-  float zreg = 0.f;
-  uint32_t aux[8];
-  if (!upper) {
-    zreg = a.z[(size_t)bh * D + cc];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) aux[t] = t < Kc ? __float_as_uint(a.conv_w[((size_t)h * D + cc) * Kc + t]) : 0u;
-  } else {
-#pragma unroll
-    for (int r = 0; r < HALO; ++r) {          // LDS row r holds the value row HALO - r positions before the candidates
-      const int back = HALO - r;              // 1 .. HALO
-      aux[r] = back <= Kc - 1 ? static_cast<const uint16_t*>(a.hist)[hist0 + (int64_t)(Kc - 1 - back) * D + cc] : 0u;
-    }
-  }
-  int par = -1;
-  if (tid < n) { par = a.parent[tid]; par = (par < -1 || par >= tid) ? -1 : par; }   // a malformed entry starts a new root
+  const float zreg = a.z[(size_t)bh * D + cc];
+  const int par_raw = a.parent[tid < n ? tid : 0];
   int acc_node = -1;
   if (a.accept) { acc_node = a.accept[b]; acc_node = (acc_node < 0 || acc_node >= n) ? -1 : acc_node; }
 
   // Sacc[ib][r] = S[32ib + 8(r/4) + 4hi + r%4][cw]; nontemporal buffer requests (descriptor in scalar
-  // registers + one lane offset + a constant each)
+  // registers + one lane offset + a constant each).  A wave can have 63 requests under way: the first half of the
+  // tiles goes out here, the second when the candidates have arrived, so that no request has to wait for a free slot.
   const __amdgpu_buffer_rsrc_t Srs =
       __builtin_amdgcn_make_buffer_rsrc(a.S + (size_t)bh * D * D, 0, D * D * 4, 0x00020000);
   const int so = (4 * hi * D + cw) * 4;
   f32x16 Sacc[G::IB];
+  constexpr int IB0 = G::IB > 2 ? G::IB / 2 : G::IB;
 #pragma unroll
-  for (int ib = 0; ib < G::IB; ++ib)
+  for (int ib = 0; ib < IB0; ++ib)
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       Sacc[ib][r] = __builtin_bit_cast(
           float, __builtin_amdgcn_raw_buffer_load_b32(Srs, so, (32 * ib + 8 * (r >> 2) + (r & 3)) * (D * 4), 2));
+  __builtin_amdgcn_sched_barrier(0);
 
   // ---- candidates -> LDS: phi(Q), phi(K) as bf16 rows (rows >= n are zero rows), V, history, z, taps --
   u32x4 kl[G::QP];                                       // phi(K) - bf16(phi(K)): stays in registers until q and p are free
@@ -140,26 +143,34 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
   for (int m = 0; m < G::QP; ++m) {
     const int piece = tid + G::NT * m;
     const int dj = piece / (D / 8), di0 = 8 * (piece % (D / 8));
-    u32x4 qp = phi_pack8_nb(rq[m], a.relu ? 0.f : 1.f), kp;
+    u32x4 qp = phi_pack8_nb(rq[m], a.relu ? 0.f : 1.f), kp, vp = rv[m];
     phi_split8_nb(rk[m], a.relu ? 0.f : 1.f, kp, kl[m]);
-    if (dj >= n) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; kl[m] = u32x4{0, 0, 0, 0}; }
+    if (dj >= n) { qp = u32x4{0, 0, 0, 0}; kp = u32x4{0, 0, 0, 0}; kl[m] = u32x4{0, 0, 0, 0}; vp = u32x4{0, 0, 0, 0}; }
     u32x2* qrow = reinterpret_cast<u32x2*>(sm.q + dj * G::QS + di0);
     qrow[0] = u32x2{qp[0], qp[1]};
     qrow[1] = u32x2{qp[2], qp[3]};
     *reinterpret_cast<u32x4*>(sm.k + dj * G::KS + di0) = kp;
     u32x2* vrow = reinterpret_cast<u32x2*>(sm.v + (HALO + dj) * G::VS + di0);
-    vrow[0] = u32x2{rv[m][0], rv[m][1]};
-    vrow[1] = u32x2{rv[m][2], rv[m][3]};
+    vrow[0] = u32x2{vp[0], vp[1]};
+    vrow[1] = u32x2{vp[2], vp[3]};
   }
-  if (!upper) {
-    sm.z[cc] = zreg;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) sm.w[t * D + cc] = __uint_as_float(aux[t]);
-  } else {
-#pragma unroll
-    for (int r = 0; r < HALO; ++r) sm.v[r * G::VS + cc] = (uint16_t)aux[r];
+  for (int mth = 0; mth < TAP_IT; ++mth) {
+    const int e = tid + G::NT * mth;
+    const int t = e / D, c = e % D;
+    sm.w[t * D + c] = t < Kc ? __uint_as_float(tap_reg[mth]) : 0.f;
+    sm.v[t * G::VS + c] = HALO - t <= Kc - 1 ? (uint16_t)hist_reg[mth] : (uint16_t)0;
   }
-  if (tid < G::KT) sm.parent[tid] = par;
+  if (!upper) sm.z[cc] = zreg;
+  if (tid < G::KT) sm.parent[tid] = (tid < n && par_raw >= -1 && par_raw < tid) ? par_raw : -1;   // a malformed entry starts a new root
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int ib = IB0; ib < G::IB; ++ib)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      Sacc[ib][r] = __builtin_bit_cast(
+          float, __builtin_amdgcn_raw_buffer_load_b32(Srs, so, (32 * ib + 8 * (r >> 2) + (r & 3)) * (D * 4), 2));
+  __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
 
   // ---- the tree: for every candidate the set of candidates on its root path and, tap by tap, the
@@ -352,17 +363,36 @@ __global__ __launch_bounds__(D * 2, 2) void verify_tree_kernel(VerifyTreeArgs a)
 
   // ---- the rest of the state: normaliser and history ----------------------------------------------------
   if (acc_node < 0) return;   // uniform per workgroup
-  if (!upper) {
-    // (every row is read whatever the path says and weighed by 0 or 1: reads under the condition, one after the
-    // other, were 2 x 64 dependent trips to LDS on two of the four waves at the very end of the kernel)
-    float zs = zreg;
-#pragma unroll 8
-    for (int c = 0; c < G::KT; ++c) {
-      const float on = ((commit >> c) & 1ull) ? 1.f : 0.f;   // rows >= n are zero rows and never on the path
-      zs = fmaf(on, bf16_bits_to_f32(sm.k[c * G::KS + cc]) + bf16_bits_to_f32(sm.klo()[c * G::KS + cc]), zs);
+  {
+    // z += the sum of phi(k) over the accepted path, both terms: this wave's 32 features as one more tile against an
+    // all-ones operand (as a loop over the rows it was 64 dependent trips to LDS on half of the waves, at the very end
+    // of the workgroup).  Zacc[r] = the increment of z[32w + 8(r/4) + 4hi + r%4], the same in every lane of a half wave.
+    f32x16 Zacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Zacc[r] = 0.f;
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+#pragma unroll
+    for (int ks = 0; ks < G::KSC; ++ks) {
+      u32x4 keep;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int c0 = 16 * ks + 8 * hi + 2 * i;
+        keep[i] = (((commit >> c0) & 1ull) ? 0x0000ffffu : 0u) | (((commit >> (c0 + 1)) & 1ull) ? 0xffff0000u : 0u);
+      }
+      const u32x4 kt = __builtin_bit_cast(u32x4, tr_operand(sm.k, G::KS, 16 * ks, 32 * w, lane)) & keep;
+      const u32x4 ktl = __builtin_bit_cast(u32x4, tr_operand(sm.klo(), G::KS, 16 * ks, 32 * w, lane)) & keep;
+      Zacc = mfma(__builtin_bit_cast(bf16x8, ktl), ones, Zacc);
+      Zacc = mfma(__builtin_bit_cast(bf16x8, kt), ones, Zacc);
     }
-    a.z[(size_t)bh * D + cc] = zs;
-  } else {
+    float inc = Zacc[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) inc = l32 == r ? Zacc[r] : inc;
+    if (l32 < 16) {
+      const int f = 32 * w + 8 * (l32 >> 2) + 4 * hi + (l32 & 3);
+      a.z[(size_t)bh * D + f] = sm.z[f] + inc;
+    }
+  }
+  if (upper) {
     // the last Kc-1 rows of (history ++ accepted path) are what the taps 0..Kc-2 of the accepted candidate read
     for (int r = 0; r < Kc - 1; ++r)
       static_cast<uint16_t*>(a.hist)[hist0 + (int64_t)r * D + cc] = sm.v[sm.taprow[acc_node][Kc - 2 - r] * G::VS + cc];
