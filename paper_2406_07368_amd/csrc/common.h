@@ -48,6 +48,9 @@ struct IoF32 {
     const f32x4* p = reinterpret_cast<const f32x4*>(static_cast<const float*>(base) + idx);
     return raw8{p[0], p[1]};
   }
+  // The value has to be in its registers here: a request whose only uses sit under a condition is otherwise moved
+  // down to them by the compiler, behind every request issued in between, with a wait for all of those.
+  static __device__ __forceinline__ void needed_here(const raw8& r) { asm volatile("" ::"v"(r.lo[0]), "v"(r.hi[0])); }
   static __device__ __forceinline__ void unpack8(const raw8& r, float (&x)[8]) {
     x[0] = r.lo[0]; x[1] = r.lo[1]; x[2] = r.lo[2]; x[3] = r.lo[3];
     x[4] = r.hi[0]; x[5] = r.hi[1]; x[6] = r.hi[2]; x[7] = r.hi[3];
@@ -77,6 +80,7 @@ struct IoBf16 {
   static __device__ __forceinline__ raw8 load_raw8(const void* base, int64_t idx) {
     return *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(base) + idx);
   }
+  static __device__ __forceinline__ void needed_here(const raw8& r) { asm volatile("" ::"v"(r[0])); }
   static __device__ __forceinline__ void unpack8(const raw8& r, float (&x)[8]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {

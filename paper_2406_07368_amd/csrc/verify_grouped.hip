@@ -144,12 +144,17 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
   const float z_reg = a.z[(size_t)bh * D + (tid < D ? tid : 0)];
   constexpr int TAP_IT = 8 * D / 256;
   float tap_reg[TAP_IT], hist_reg[TAP_IT];
+  // (one tap: no history; the request then reads a draft's value row, which is dropped.  As `Kc > 1 ? load : 0` every
+  // one of these requests sat in a branch of its own with a full wait behind it: four trips to memory in a row ahead
+  // of the state's requests)
+  const void* hsrc = Kc > 1 ? a.hist : a.v;
+  const int64_t hbase = Kc > 1 ? hist0 : tok0;
 #pragma unroll
   for (int mth = 0; mth < TAP_IT; ++mth) {
     const int e = tid + 256 * mth;
     const int t = e / D, cc = e % D;
     tap_reg[mth] = a.conv_w[((size_t)h * D + cc) * Kc + (t < Kc ? t : 0)];
-    hist_reg[mth] = Kc > 1 ? Io::load1(a.hist, hist0 + (int64_t)(t < Kc - 1 ? Kc - 2 - t : 0) * D + cc) : 0.f;
+    hist_reg[mth] = Io::load1(hsrc, hbase + (int64_t)(t < Kc - 1 ? Kc - 2 - t : 0) * D + cc);
   }
   typename Io::raw8 rk[RT];
 #pragma unroll
@@ -165,6 +170,8 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
   f32x4 s[PD];
 #pragma unroll
   for (int p = 0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D));
+  Io::needed_here(q_raw);                          // (used by a few threads only: kept ahead of the state's requests)
+  Io::needed_here(v_raw);
 
   if (pj < KP) {
     float xq[8], xv[8];
