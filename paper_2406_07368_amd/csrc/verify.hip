@@ -64,46 +64,44 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
   const int kk = a.kk, Kc = a.Kc;
   const int cg = tid % CG, r0 = tid / CG;
 
-  // ---- 0. the small inputs are requested FIRST: every workgroup of the launch is about to ask for
-  //         its state at the same moment, and anything requested after that waits behind it ------
+  // ---- 0. every request of the step is issued before anything waits, the small inputs FIRST: every workgroup of
+  //         the launch is about to ask for its state at the same moment, and anything requested after that waits
+  //         behind it.  All requests unconditional -- indices past the end are clamped, what they bring is dropped --:
+  //         under conditions on the thread index every one of them sat in a block of its own with a full wait at its
+  //         end, a dozen trips to memory in a row before the state was asked for. ------------------------------------
   const int64_t tok0 = (int64_t)bh * kk * D;              // q, k
   const int64_t vtok0 = (int64_t)bh * kk * DV;            // v, out
   const int64_t hist0 = (int64_t)bh * (Kc - 1) * DV;
   constexpr int QK_IT = (KP * (D / 8) + 255) / 256;   // 8-element pieces of q and k per thread
   constexpr int V_IT = (KP * (CW / 8) + 255) / 256;
-  float xq[QK_IT][8], xk[QK_IT][8], xv[V_IT][8];
+  typename Io::raw8 rq[QK_IT], rk[QK_IT], rv[V_IT];
 #pragma unroll
   for (int m = 0; m < QK_IT; ++m) {
     const int c8 = tid + 256 * m;
     const int j = c8 / (D / 8), i0 = (c8 % (D / 8)) * 8;
-    if (c8 < KP * (D / 8) && j < kk) {
-      Io::load8(a.q, tok0 + (int64_t)j * D + i0, xq[m]);
-      Io::load8(a.k, tok0 + (int64_t)j * D + i0, xk[m]);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { xq[m][e] = -1e30f; xk[m][e] = -1e30f; }   // phi -> 0
-    }
+    const int64_t off = tok0 + (int64_t)(j < kk ? j : kk - 1) * D + i0;
+    rq[m] = Io::load_raw8(a.q, off);
+    rk[m] = Io::load_raw8(a.k, off);
   }
 #pragma unroll
   for (int m = 0; m < V_IT; ++m) {
     const int c8 = tid + 256 * m;
     const int j = c8 / (CW / 8), cc = (c8 % (CW / 8)) * 8;
-    if (c8 < KP * (CW / 8) && j < kk) Io::load8(a.v, vtok0 + (int64_t)j * DV + c0 + cc, xv[m]);
-    else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) xv[m][e] = 0.f;
-    }
+    rv[m] = Io::load_raw8(a.v, vtok0 + (int64_t)(j < kk ? j : kk - 1) * DV + c0 + cc);
   }
-  const float zreg = tid < D ? a.z[(size_t)bh * D + tid] : 0.f;
-  float wh[(16 * CW + 255) / 256];
+  const float zreg = a.z[(size_t)bh * D + tid % D];
+  // taps and history rows of the slice's channels: element e = tid + 256 m of the [8][CW] arrays in LDS
+  constexpr int TAP_IT = (8 * CW + 255) / 256;
+  float tap_reg[TAP_IT], hist_reg[TAP_IT];
+  // (one tap: no history; the request then reads a draft's value row, which is dropped)
+  const void* hsrc = Kc > 1 ? a.hist : a.v;
+  const int64_t hbase = (Kc > 1 ? hist0 : vtok0) + c0;
 #pragma unroll
-  for (int m = 0; m < (16 * CW + 255) / 256; ++m) {
-    const int e = tid + 256 * m;          // rows 0..7: taps, rows 8..15: history
-    const int t = (e / CW) & 7, cc = e % CW;
-    float x = 0.f;
-    if (e < 8 * CW) { if (t < Kc) x = a.conv_w[((size_t)h * DV + c0 + cc) * Kc + t]; }
-    else if (e < 16 * CW) { if (t < Kc - 1) x = Io::load1(a.hist, hist0 + (int64_t)(Kc - 2 - t) * DV + c0 + cc); }
-    wh[m] = x;
+  for (int m = 0; m < TAP_IT; ++m) {
+    const int e = (tid + 256 * m) % (8 * CW);
+    const int t = e / CW, cc = e % CW;
+    tap_reg[m] = a.conv_w[((size_t)h * DV + c0 + cc) * Kc + (t < Kc ? t : 0)];
+    hist_reg[m] = Io::load1(hsrc, hbase + (int64_t)(t < Kc - 1 ? Kc - 2 - t : 0) * DV + cc);
   }
   int n = kk;
   if (a.n_commit) { n = a.n_commit[b]; n = n < 0 ? 0 : (n > kk ? kk : n); }
@@ -116,6 +114,12 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
   f32x4 s[PD];
 #pragma unroll
   for (int p = 0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * DV));
+  // (values that only some threads use: kept ahead of the state's requests, or the compiler moves their requests down
+  // to the uses, behind the state's)
+#pragma unroll
+  for (int m = 0; m < QK_IT; ++m) { Io::needed_here(rq[m]); Io::needed_here(rk[m]); }
+#pragma unroll
+  for (int m = 0; m < V_IT; ++m) Io::needed_here(rv[m]);
 
   // ---- 1. drafts -> LDS (phi applied), normaliser, taps and history -> LDS -----------------------
 #pragma unroll
@@ -123,10 +127,13 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
     const int c8 = tid + 256 * m;
     const int j = c8 / (D / 8), i0 = (c8 % (D / 8)) * 8;
     if (c8 < KP * (D / 8)) {
+      float xq[8], xk[8];
+      Io::unpack8(rq[m], xq);
+      Io::unpack8(rk[m], xk);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        sm.fq[i0 + e][j] = j < kk ? phi_any(xq[m][e], a.relu) : 0.f;
-        sm.fk[i0 + e][j] = j < kk ? phi_any(xk[m][e], a.relu) : 0.f;
+        sm.fq[i0 + e][j] = j < kk ? phi_any(xq[e], a.relu) : 0.f;
+        sm.fk[i0 + e][j] = j < kk ? phi_any(xk[e], a.relu) : 0.f;
       }
     }
   }
@@ -135,16 +142,21 @@ __global__ __launch_bounds__(256, (KP <= 8 ? 4 : 2)) void verify_kernel(VerifyAr
     const int c8 = tid + 256 * m;
     const int j = c8 / (CW / 8), cc = (c8 % (CW / 8)) * 8;
     if (c8 < KP * (CW / 8)) {
+      float xv[8];
+      Io::unpack8(rv[m], xv);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sm.vv[j][cc + e] = xv[m][e];
+      for (int e = 0; e < 8; ++e) sm.vv[j][cc + e] = j < kk ? xv[e] : 0.f;
     }
   }
   if (tid < D) sm.zz[tid] = zreg;
 #pragma unroll
-  for (int m = 0; m < (16 * CW + 255) / 256; ++m) {
+  for (int m = 0; m < TAP_IT; ++m) {
     const int e = tid + 256 * m;
-    if (e < 8 * CW) sm.wt[e / CW][e % CW] = wh[m];
-    else if (e < 16 * CW) sm.hh[(e / CW) & 7][e % CW] = wh[m];
+    if (e < 8 * CW) {
+      const int t = e / CW, cc = e % CW;
+      sm.wt[t][cc] = t < Kc ? tap_reg[m] : 0.f;
+      sm.hh[t][cc] = t < Kc - 1 ? hist_reg[m] : 0.f;
+    }
   }
   __syncthreads();
 
