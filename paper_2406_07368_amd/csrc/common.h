@@ -110,4 +110,33 @@ struct IoBf16 {
   }
 };
 
+// Sums across lanes without the LDS crossbar (hundreds of them per step: as ds_bpermute they were the
+// bottleneck).  Within a row of 16 lanes: DPP modifiers on the add; across rows: the lane-swap instructions.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, false));
+}
+// every lane gets the sum over its group of N consecutive lanes (N = 8 or 16, groups aligned)
+template <int N>
+__device__ __forceinline__ float sum_lanes(float x) {
+  x = dpp_add<0xB1>(x);                 // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                 // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);                // row_half_mirror: the other quad of each 8
+  if (N == 16) x = dpp_add<0x140>(x);   // row_mirror: the other half of each 16
+  return x;
+}
+// the same for the largest value
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float x) {
+  return fmaxf(x, __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, false)));
+}
+template <int N>
+__device__ __forceinline__ float max_lanes(float x) {
+  x = dpp_max<0xB1>(x);
+  x = dpp_max<0x4E>(x);
+  x = dpp_max<0x141>(x);
+  if (N == 16) x = dpp_max<0x140>(x);
+  return x;
+}
+
 }  // namespace linattn

@@ -56,21 +56,6 @@ struct VgSmem {
   float hh[8][D];             // hh[t]: the value row t+1 positions before the first draft
 };
 
-// Sums across lanes without the LDS crossbar (hundreds of them per step: as ds_bpermute they were the
-// bottleneck).  Within a row of 16 lanes: DPP modifiers on the add; across rows: the lane-swap instructions.
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  return x + __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xf, 0xf, false));
-}
-// every lane gets the sum over its group of N consecutive lanes (N = 8 or 16, groups aligned)
-template <int N>
-__device__ __forceinline__ float sum_lanes(float x) {
-  x = dpp_add<0xB1>(x);                 // quad_perm [1,0,3,2]
-  x = dpp_add<0x4E>(x);                 // quad_perm [2,3,0,1]
-  x = dpp_add<0x141>(x);                // row_half_mirror: the other quad of each 8
-  if (N == 16) x = dpp_add<0x140>(x);   // row_mirror: the other half of each 16
-  return x;
-}
 // x[l] + x[l ^ 8] (rotation by 8 inside a row of 16)
 __device__ __forceinline__ float add_xor8(float x) { return dpp_add<0x128>(x); }
 // x[l] + x[l ^ 16]: rows 0,1 and rows 2,3 of the wave are swapped against each other
@@ -257,46 +242,58 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
   for (int e = tid; e < KP * D; e += 256) sm.sc.loc[e / D][e % D] = 0.f;   // step 1 is done with its copy of phi(q)
   static_assert(D == 64 || D == 128, "1 / sqrt(d) below");
   constexpr float to_log2 = 1.44269504088896340736f * (D == 64 ? 0.125f : 0.08838834764831845f);
-  for (int j = wv; j < kk; j += 4) {
-    const int P = n + j;                                            // position of the draft
+  {
+    // Sixteen lanes per draft, four drafts per wave, every sum and maximum inside a row of sixteen lanes with DPP
+    // modifiers (a wave per draft with sums across its 64 lanes through the LDS crossbar was 18 dependent shuffles).
+    constexpr int RPL = GROWS / 16;                                 // rows per lane
+    static_assert(KP <= 16, "one pass of four waves");
+    const int j = 4 * wv + (lane >> 4), sub = lane & 15;
+    const bool live = j < kk;
+    const int jj = live ? j : 0;                                    // lanes without a draft follow the first and write nothing
+    const int P = n + jj;                                           // position of the draft
     const int g0 = P < GC ? 0 : GC;                                 // first row of its group
-    float xr[2];                                                    // rows lane and lane + 64
+    float xr[RPL];
     float top = -INFINITY;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int r = lane + 64 * t;
-      const bool seen = r >= g0 && r <= P;
-      xr[t] = seen ? sm.W[j][r < GROWS ? r : GROWS - 1] : -INFINITY;
+    for (int t = 0; t < RPL; ++t) {
+      const int r = sub + 16 * t;
+      const float x = sm.W[jj][r];
+      xr[t] = (r >= g0 && r <= P) ? x : -INFINITY;
       top = fmaxf(top, xr[t]);
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) top = fmaxf(top, __shfl_xor(top, off));
+    top = max_lanes<16>(top);                                       // the draft itself is always seen: finite
     float mass = 0.f;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < RPL; ++t) {
       xr[t] = __builtin_amdgcn_exp2f((xr[t] - top) * to_log2);      // exp2(-inf) = 0: rows that are not seen
       mass += xr[t];
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mass += __shfl_xor(mass, off);
     // phi(q_j).z, plus the completed group for a draft of the next group
     float dz = 0.f;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) dz = fmaf(sm.sc.fq[lane + 64 * e][j], sm.zz[lane + 64 * e], dz);
-    if (g0 > 0) dz += sm.lin[j][lane];                              // GC == 64 rows, one per lane
+    for (int e = 0; e < D / 16; ++e) dz = fmaf(sm.sc.fq[sub + 16 * e][jj], sm.zz[sub + 16 * e], dz);
+    float lin[GC / 16];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) dz += __shfl_xor(dz, off);
+    for (int t = 0; t < GC / 16; ++t) lin[t] = sm.lin[jj][sub + 16 * t];
+    if (g0 > 0) {
+#pragma unroll
+      for (int t = 0; t < GC / 16; ++t) dz += lin[t];
+    }
+    mass = sum_lanes<16>(mass);
+    dz = sum_lanes<16>(dz);
     const float gden = dz + a.eps;
     const float f = gden != 0.f ? a.alpha / gden : 0.f;
     const float inv_mass = 1.f / mass;                              // the draft itself is always seen: mass >= 1
+    if (live) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int r = lane + 64 * t;
-      float wgt = xr[t] * inv_mass;
-      if (g0 > 0 && r < GC) wgt = f * sm.lin[j][r];                 // the completed group, through the linear branch
-      if (r < GROWS) sm.W[j][r] = wgt;
+      for (int t = 0; t < RPL; ++t) {
+        const int r = sub + 16 * t;
+        float wgt = xr[t] * inv_mass;
+        if (t < GC / 16) wgt = g0 > 0 ? f * lin[t] : wgt;           // the completed group, through the linear branch
+        sm.W[j][r] = wgt;
+      }
+      if (sub == 0) sm.fscale[j] = f;
     }
-    if (lane == 0) sm.fscale[j] = f;
   }
   __syncthreads();
 

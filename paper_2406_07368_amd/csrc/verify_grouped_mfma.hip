@@ -219,50 +219,56 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
   // ---- 2. per draft: softmax over its rows, the linear normaliser, the weights of the value rows (bf16) ----
   static_assert(D == 64 || D == 128, "1 / sqrt(d) below");
   constexpr float to_log2 = 1.44269504088896340736f * (D == 64 ? 0.125f : 0.08838834764831845f);
-  for (int j = w; j < G::NQ; j += G::NW) {
-    if (j >= kk) {                                       // uniform: a draft that does not exist has no weights
-      if (lane < G::RK / 2) reinterpret_cast<uint32_t*>(sm.p + j * G::PS)[lane] = 0u;
-      if (lane == 0) sm.fscale[j] = 0.f;
-      continue;
-    }
+  // Sixteen lanes per draft, four drafts per wave at once, every sum and maximum inside a row of sixteen lanes with
+  // DPP modifiers (a wave per draft with the sums across 64 lanes through the LDS crossbar was 18 dependent shuffles
+  // per draft: 2.5 us of a workgroup's 10).
+  constexpr int RPL = G::RK / 16;                        // rows per lane
+#pragma unroll
+  for (int j0 = 0; j0 < G::NQ; j0 += 4 * G::NW) {
+    const int j = j0 + 4 * w + (lane >> 4), sub = lane & 15;
+    const bool live = j < kk;                            // a draft that does not exist has no weights
     const int P = n + j;                                 // position of the draft
     const int g0 = P < GC ? 0 : GC;                      // first row of its group
-    float xr[2];                                         // rows lane and lane + 64
+    float xr[RPL];
     float top = -INFINITY;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int r = lane + 64 * t;
-      const bool seen = r >= g0 && r <= P;
-      xr[t] = seen ? sm.W[j][r < G::RK ? r : G::RK - 1] : -INFINITY;
+    for (int t = 0; t < RPL; ++t) {
+      const int r = sub + 16 * t;
+      const float x = sm.W[j][r];
+      xr[t] = (live && r >= g0 && r <= P) ? x : -INFINITY;
       top = fmaxf(top, xr[t]);
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) top = fmaxf(top, __shfl_xor(top, off));
+    top = max_lanes<16>(top);
+    top = live ? top : 0.f;                              // (the draft itself is always seen: finite for a live draft)
     float mass = 0.f;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < RPL; ++t) {
       xr[t] = __builtin_amdgcn_exp2f((xr[t] - top) * to_log2);   // exp2(-inf) = 0: rows that are not seen
       mass += xr[t];
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mass += __shfl_xor(mass, off);
     float dz = 0.f;
 #pragma unroll
-    for (int e = 0; e < D / 64; ++e) dz = fmaf(bf16_bits_to_f32(sm.q[j * G::QS + lane + 64 * e]), sm.z[lane + 64 * e], dz);
-    if (g0 > 0) dz += sm.lin[j][lane];                   // GC == 64 rows, one per lane
+    for (int e = 0; e < D / 16; ++e) dz = fmaf(bf16_bits_to_f32(sm.q[j * G::QS + sub + 16 * e]), sm.z[sub + 16 * e], dz);
+    float lin[GC / 16];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) dz += __shfl_xor(dz, off);
-    const float gden = dz + a.eps;
-    const float f = gden != 0.f ? a.alpha / gden : 0.f;
-    const float inv_mass = 1.f / mass;                   // the draft itself is always seen: mass >= 1
+    for (int t = 0; t < GC / 16; ++t) lin[t] = sm.lin[j][sub + 16 * t];
+    if (g0 > 0) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int r = lane + 64 * t;
-      float wgt = xr[t] * inv_mass;
-      if (g0 > 0 && r < GC) wgt = f * sm.lin[j][r];      // the completed group, through the linear branch
-      if (r < G::RK) sm.p[j * G::PS + r] = f32_to_bf16_bits(wgt);
+      for (int t = 0; t < GC / 16; ++t) dz += lin[t];
     }
-    if (lane == 0) sm.fscale[j] = f;
+    mass = sum_lanes<16>(mass);
+    dz = sum_lanes<16>(dz);
+    const float gden = dz + a.eps;
+    const float f = (live && gden != 0.f) ? a.alpha / gden : 0.f;
+    const float inv_mass = live ? 1.f / mass : 0.f;      // the draft itself is always seen: mass >= 1
+#pragma unroll
+    for (int t = 0; t < RPL; ++t) {
+      const int r = sub + 16 * t;
+      float wgt = xr[t] * inv_mass;
+      if (t < GC / 16) wgt = g0 > 0 ? f * lin[t] : wgt;  // the completed group, through the linear branch
+      sm.p[j * G::PS + r] = f32_to_bf16_bits(wgt);
+    }
+    if (sub == 0) sm.fscale[j] = f;
   }
   __syncthreads();
 
