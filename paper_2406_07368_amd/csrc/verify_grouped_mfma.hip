@@ -63,7 +63,9 @@ static_assert(offsetof(VgmSmem<128>, w) - offsetof(VgmSmem<128>, qr) >= VgmCfg<1
 
 }  // namespace
 
-template <int D>
+// KCM: tap capacity of the instantiation (3, 5 or 8; taps beyond Kc are zeros in LDS and their rows are valid rows), so
+// that the output loop over the taps is straight-line code.
+template <int D, int KCM>
 __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGroupedArgs a) {
   using G = VgmCfg<D>;
   constexpr int GC = G::GC;
@@ -109,21 +111,26 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
   // q: NQ * D / 8 pieces, at most one per thread
   const int qj = tid / (D / 8), qi0 = 8 * (tid % (D / 8));
   const u32x4 rq = *reinterpret_cast<const u32x4*>(gq + (size_t)(qj < kk ? qj : kk - 1) * D + qi0);
-  // taps, history and z: channel tid % D; the lower D threads take the taps and z, the upper D the history
+  // taps and history rows: element e = tid + NT m of the [8][D] arrays in LDS; z: one element per thread.  Unconditional,
+  // like every request here: a request under a condition that depends on the lane ends in a wait for the requests
+  // before it.
   const int cc = tid % D, upper = tid / D;
-  float zreg = 0.f;
-  uint32_t aux[8];
-  if (!upper) {
-    zreg = a.z[(size_t)bh * D + cc];
+  constexpr int TAP_IT = 8 * D / G::NT;
+  uint32_t tap_reg[TAP_IT], hist_reg[TAP_IT];
+  // (one tap: no history, and any address that can be read serves)
+  const uint16_t* hsrc = Kc > 1 ? static_cast<const uint16_t*>(a.hist) + hist0 : gq;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) aux[t] = t < Kc ? __float_as_uint(a.conv_w[((size_t)h * D + cc) * Kc + t]) : 0u;
-  } else {
-#pragma unroll
-    for (int r = 0; r < HALO; ++r) {          // LDS row r holds the value row HALO - r positions before the first draft
-      const int back = HALO - r;              // 1 .. HALO
-      aux[r] = back <= Kc - 1 ? static_cast<const uint16_t*>(a.hist)[hist0 + (int64_t)(Kc - 1 - back) * D + cc] : 0u;
-    }
+  for (int mth = 0; mth < TAP_IT; ++mth) {
+    const int e = tid + G::NT * mth;
+    const int t = e / D, c = e % D;
+    tap_reg[mth] = __float_as_uint(a.conv_w[((size_t)h * D + c) * Kc + (t < Kc ? t : 0)]);
+    const int back = HALO - t;                // LDS row t holds the value row HALO - t positions before the first draft
+    hist_reg[mth] = hsrc[(size_t)(back <= Kc - 1 ? Kc - 1 - back : 0) * D + c];
   }
+  const float zreg = a.z[(size_t)bh * D + cc];
+  // (the fences keep the small requests ahead of the state's and every use behind all requests: a use scheduled
+  // between two requests is a wait between them)
+  __builtin_amdgcn_sched_barrier(0);
   // Sacc[ib][r] = S[32ib + 8(r/4) + 4hi + r%4][cw]
   const __amdgpu_buffer_rsrc_t Srs =
       __builtin_amdgcn_make_buffer_rsrc(a.S + (size_t)bh * D * D, 0, D * D * 4, 0x00020000);
@@ -135,6 +142,7 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
     for (int r = 0; r < 16; ++r)
       Sacc[ib][r] = __builtin_bit_cast(
           float, __builtin_amdgcn_raw_buffer_load_b32(Srs, so, (32 * ib + 8 * (r >> 2) + (r & 3)) * (D * 4), 2));
+  __builtin_amdgcn_sched_barrier(0);
 
   // ---- rows -> LDS (rows past the end are zero rows), q raw and phi(q), history, z, taps -------------
 #pragma unroll
@@ -148,7 +156,8 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
     vrow[0] = u32x2{vp[0], vp[1]};
     vrow[1] = u32x2{vp[2], vp[3]};
   }
-  if (qj < G::NQ) {
+  static_assert(G::NT / (D / 8) == G::NQ, "every thread has a piece of a query row");
+  {
     u32x4 raw = rq, fq = phi_pack8(rq, a.relu);
     if (qj >= kk) { raw = u32x4{0, 0, 0, 0}; fq = u32x4{0, 0, 0, 0}; }
     u32x2* r0 = reinterpret_cast<u32x2*>(sm.qr + qj * G::QS + qi0);
@@ -158,14 +167,14 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
     f0[0] = u32x2{fq[0], fq[1]};
     f0[1] = u32x2{fq[2], fq[3]};
   }
-  if (!upper) {
-    sm.z[cc] = zreg;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) sm.w[t * D + cc] = __uint_as_float(aux[t]);
-  } else {
-#pragma unroll
-    for (int r = 0; r < HALO; ++r) sm.v[r * G::VS + cc] = (uint16_t)aux[r];
+  for (int mth = 0; mth < TAP_IT; ++mth) {
+    const int e = tid + G::NT * mth;
+    const int t = e / D, c = e % D;
+    sm.w[t * D + c] = t < Kc ? __uint_as_float(tap_reg[mth]) : 0.f;
+    sm.v[t * G::VS + c] = HALO - t <= Kc - 1 ? (uint16_t)hist_reg[mth] : (uint16_t)0;
   }
+  if (!upper) sm.z[cc] = zreg;
   __syncthreads();
 
   // ---- 1. logits: the 32-key tiles of K Q^T (and, for a group being completed, phi(K) phi(Q)^T), dealt out
@@ -310,17 +319,15 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
     for (int g = 0; g < 4; ++g) {
       float u[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        if (t < Kc) {
-          // tap t looks t rows back from draft j: another draft if t <= j, else history row (t - j) back
-          const int row = t <= j ? HALO + n + j - t : HALO - (t - j);
-          const f32x4 wv4 = *reinterpret_cast<const f32x4*>(wrow + t * D + 8 * g);
-          const u32x2 x = *reinterpret_cast<const u32x2*>(sm.v + row * G::VS + 32 * w + 4 * hi + 8 * g);
-          u[0] = fmaf(wv4[0], bf16_lo_to_f32(x[0]), u[0]);
-          u[1] = fmaf(wv4[1], bf16_hi_to_f32(x[0]), u[1]);
-          u[2] = fmaf(wv4[2], bf16_lo_to_f32(x[1]), u[2]);
-          u[3] = fmaf(wv4[3], bf16_hi_to_f32(x[1]), u[3]);
-        }
+      for (int t = 0; t < KCM; ++t) {
+        // tap t looks t rows back from draft j: another draft if t <= j, else history row (t - j) back
+        const int row = t <= j ? HALO + n + j - t : HALO - (t - j);
+        const f32x4 wv4 = *reinterpret_cast<const f32x4*>(wrow + t * D + 8 * g);
+        const u32x2 x = *reinterpret_cast<const u32x2*>(sm.v + row * G::VS + 32 * w + 4 * hi + 8 * g);
+        u[0] = fmaf(wv4[0], bf16_lo_to_f32(x[0]), u[0]);
+        u[1] = fmaf(wv4[1], bf16_hi_to_f32(x[0]), u[1]);
+        u[2] = fmaf(wv4[2], bf16_lo_to_f32(x[1]), u[2]);
+        u[3] = fmaf(wv4[3], bf16_hi_to_f32(x[1]), u[3]);
       }
       *reinterpret_cast<u32x2*>(orow + 8 * g) =
           u32x2{pack_bf16x2(o[4 * g] + u[0], o[4 * g + 1] + u[1]), pack_bf16x2(o[4 * g + 2] + u[2], o[4 * g + 3] + u[3])};
@@ -387,9 +394,9 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
   }
 }
 
-template <int D>
+template <int D, int KCM>
 static hipError_t launch_vgm(const VerifyGroupedArgs& a, hipStream_t st) {
-  auto kern = verify_grouped_mfma_kernel<D>;
+  auto kern = verify_grouped_mfma_kernel<D, KCM>;
   constexpr int LDS = (int)sizeof(VgmSmem<D>);
   static_assert(LDS <= 80 * 1024, "two workgroups per compute unit");
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -403,7 +410,8 @@ static hipError_t launch_vgm(const VerifyGroupedArgs& a, hipStream_t st) {
 bool verify_grouped_mfma_available(bool bf16, int d, int kk) { return bf16 && kk >= 4 && kk <= 16 && (d == 64 || d == 128); }
 
 hipError_t launch_verify_grouped_mfma(const VerifyGroupedArgs& a, int d, hipStream_t st) {
-  return d == 128 ? launch_vgm<128>(a, st) : launch_vgm<64>(a, st);
+  if (d == 128) return a.Kc <= 3 ? launch_vgm<128, 3>(a, st) : a.Kc <= 5 ? launch_vgm<128, 5>(a, st) : launch_vgm<128, 8>(a, st);
+  return a.Kc <= 3 ? launch_vgm<64, 3>(a, st) : a.Kc <= 5 ? launch_vgm<64, 5>(a, st) : launch_vgm<64, 8>(a, st);
 }
 
 }  // namespace linattn
