@@ -103,12 +103,6 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
   const int kk = a.kk, Kc = a.Kc;
   const int cg = tid % CG, r0 = tid / CG;
 
-  int n = a.fill[bh];                                               // every head carries its own copy of the count
-  n = n < 0 ? 0 : (n > GC - 1 ? GC - 1 : n);                       // rows of the open group
-  int m = kk;
-  if (a.n_commit) { m = a.n_commit[b]; m = m < 0 ? 0 : (m > kk ? kk : m); }
-  const int rows = n + kk;                                          // rows of (window ++ drafts)
-  const bool crossing = rows > GC;                                  // some draft belongs to the next group
   const int64_t tok0 = (int64_t)bh * kk * D;
   const int64_t win0 = (int64_t)bh * GC * D;
   const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
@@ -116,7 +110,10 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
   // ---- 0. every request of the step is issued before anything waits: the small inputs first (they are
   //         needed first), then this thread's rows of the open group and of the drafts, then the first passes
   //         of the state.  All of them unconditional (indices past the end are clamped, the data not used),
-  //         so that nothing serialises on a round trip to memory. ----
+  //         so that nothing serialises on a round trip to memory.  The count of rows in use is itself a trip to
+  //         memory that the rows' addresses have to wait for: whatever does not need it -- the small inputs and the
+  //         first passes of the state -- is requested ahead of that wait (behind it, every workgroup of the launch
+  //         spent its first microseconds with nothing requested). ----
   constexpr int CG8 = D / 8;                       // 8-feature pieces per row
   constexpr int NPART = 256 / CG8;                 // row partitions
   constexpr int RT = (GROWS + NPART - 1) / NPART;  // rows per thread
@@ -141,6 +138,20 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
     tap_reg[mth] = a.conv_w[((size_t)h * D + cc) * Kc + (t < Kc ? t : 0)];
     hist_reg[mth] = Io::load1(hsrc, hbase + (int64_t)(t < Kc - 1 ? Kc - 2 - t : 0) * D + cc);
   }
+  constexpr int PDW = KP <= 1 ? 8 : 4;             // row passes in flight (more when the read-outs leave registers free)
+  constexpr int PD = NPASS < PDW ? NPASS : PDW;
+  const float* Sg = a.S + (size_t)bh * D * D + 4 * cg;
+  f32x4 s[PD];
+  constexpr int PD0 = PD < 2 ? PD : 2;            // passes requested ahead of the rows (which are needed first and come in behind them)
+#pragma unroll
+  for (int p = 0; p < PD0; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D));
+  __builtin_amdgcn_sched_barrier(0);
+  int n = a.fill[bh];                                               // every head carries its own copy of the count
+  n = n < 0 ? 0 : (n > GC - 1 ? GC - 1 : n);                       // rows of the open group
+  int m = kk;
+  if (a.n_commit) { m = a.n_commit[b]; m = m < 0 ? 0 : (m > kk ? kk : m); }
+  const int rows = n + kk;                                          // rows of (window ++ drafts)
+  const bool crossing = rows > GC;                                  // some draft belongs to the next group
   typename Io::raw8 rk[RT];
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
@@ -149,12 +160,8 @@ __global__ __launch_bounds__(256, (sizeof(typename Io::elem) != 2 ? 2 : KP <= 8 
     const void* src = row_of(a.kwin, a.k, win0, tok0, D, n, r < rows ? r : rows - 1, &idx);
     rk[t] = Io::load_raw8(src, idx + 8 * c8);
   }
-  constexpr int PDW = KP <= 1 ? 8 : 4;             // row passes in flight (more when the read-outs leave registers free)
-  constexpr int PD = NPASS < PDW ? NPASS : PDW;
-  const float* Sg = a.S + (size_t)bh * D * D + 4 * cg;
-  f32x4 s[PD];
 #pragma unroll
-  for (int p = 0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D));
+  for (int p = PD0; p < PD; ++p) s[p] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Sg + (size_t)(p * RPP + r0) * D));
   Io::needed_here(q_raw);                          // (used by a few threads only: kept ahead of the state's requests)
   Io::needed_here(v_raw);
 

@@ -79,12 +79,6 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
   const int kk = a.kk, Kc = a.Kc;
   const int cw = 32 * w + l32;               // the channel this lane owns in the state tiles
 
-  int n = a.fill[bh];                        // every head carries its own copy of the count
-  n = n < 0 ? 0 : (n > GC - 1 ? GC - 1 : n);
-  int m = kk;
-  if (a.n_commit) { m = a.n_commit[b]; m = m < 0 ? 0 : (m > kk ? kk : m); }
-  const int rows = n + kk;                   // rows of (open group ++ drafts)
-  const bool crossing = rows > GC;           // some draft belongs to the next group
   const int64_t tok0 = (int64_t)bh * kk * D;
   const int64_t win0 = (int64_t)bh * GC * D;
   const int64_t hist0 = (int64_t)bh * (Kc - 1) * D;
@@ -94,20 +88,10 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
   uint16_t* wk = static_cast<uint16_t*>(a.kwin) + win0;
   uint16_t* wvp = static_cast<uint16_t*>(a.vwin) + win0;
 
-  // ---- every request first: the rows (clamped past the end, the data then not used), the drafts' q,
-  //      the small inputs, the state ---------------------------------------------------------------
-  u32x4 rk[G::RP], rv[G::RP];
-#pragma unroll
-  for (int mth = 0; mth < G::RP; ++mth) {
-    const int piece = tid + G::NT * mth;
-    int r = piece / (D / 8);
-    const int i0 = 8 * (piece % (D / 8));
-    r = r < rows ? r : rows - 1;
-    const uint16_t* ks = r < n ? wk + (size_t)r * D : gk + (size_t)(r - n) * D;
-    const uint16_t* vs = r < n ? wvp + (size_t)r * D : gv + (size_t)(r - n) * D;
-    rk[mth] = *reinterpret_cast<const u32x4*>(ks + i0);
-    rv[mth] = *reinterpret_cast<const u32x4*>(vs + i0);
-  }
+  // ---- every request first.  The count of rows in use is itself a trip to memory that the rows' addresses have to
+  //      wait for: whatever does not need it -- the drafts' q, the small inputs, the first tile of the state -- is
+  //      requested ahead of that wait, then the rows (clamped past the end, the data then not used), then the rest
+  //      of the state. -------------------------------------------------------------------------------------------
   // q: NQ * D / 8 pieces, at most one per thread
   const int qj = tid / (D / 8), qi0 = 8 * (tid % (D / 8));
   const u32x4 rq = *reinterpret_cast<const u32x4*>(gq + (size_t)(qj < kk ? qj : kk - 1) * D + qi0);
@@ -137,7 +121,29 @@ __global__ __launch_bounds__(D * 2, 2) void verify_grouped_mfma_kernel(VerifyGro
   const int so = (4 * hi * D + cw) * 4;
   f32x16 Sacc[G::IB];
 #pragma unroll
-  for (int ib = 0; ib < G::IB; ++ib)
+  for (int r = 0; r < 16; ++r)
+    Sacc[0][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(Srs, so, (8 * (r >> 2) + (r & 3)) * (D * 4), 2));
+  __builtin_amdgcn_sched_barrier(0);
+  int n = a.fill[bh];                        // every head carries its own copy of the count
+  n = n < 0 ? 0 : (n > GC - 1 ? GC - 1 : n);
+  int m = kk;
+  if (a.n_commit) { m = a.n_commit[b]; m = m < 0 ? 0 : (m > kk ? kk : m); }
+  const int rows = n + kk;                   // rows of (open group ++ drafts)
+  const bool crossing = rows > GC;           // some draft belongs to the next group
+  u32x4 rk[G::RP], rv[G::RP];
+#pragma unroll
+  for (int mth = 0; mth < G::RP; ++mth) {
+    const int piece = tid + G::NT * mth;
+    int r = piece / (D / 8);
+    const int i0 = 8 * (piece % (D / 8));
+    r = r < rows ? r : rows - 1;
+    const uint16_t* ks = r < n ? wk + (size_t)r * D : gk + (size_t)(r - n) * D;
+    const uint16_t* vs = r < n ? wvp + (size_t)r * D : gv + (size_t)(r - n) * D;
+    rk[mth] = *reinterpret_cast<const u32x4*>(ks + i0);
+    rv[mth] = *reinterpret_cast<const u32x4*>(vs + i0);
+  }
+#pragma unroll
+  for (int ib = 1; ib < G::IB; ++ib)
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       Sacc[ib][r] = __builtin_bit_cast(
