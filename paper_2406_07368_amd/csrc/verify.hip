@@ -287,11 +287,18 @@ __global__ __launch_bounds__(256) void verify_z_kernel(VerifyArgs a) {
   if (gid >= a.B * a.H * D) return;
   const int bh = gid / D, i = gid % D;
   const int b = bh / a.H;
+  // every draft's element requested at once, whatever the count says (a loop up to the count was one trip to memory
+  // per draft, one after the other); kept or dropped by select
+  constexpr int KMAX = 16;   // drafts per call at most (the entry point refuses more)
+  float x[KMAX];
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) x[j] = Io::load1(a.k, ((int64_t)bh * a.kk + (j < a.kk ? j : a.kk - 1)) * D + i);
+  float zs = a.z[gid];
   int n = a.kk;
   if (a.n_commit) { n = a.n_commit[b]; n = n < 0 ? 0 : (n > a.kk ? a.kk : n); }
   if (n == 0) return;
-  float zs = a.z[gid];
-  for (int j = 0; j < n; ++j) zs += phi_any(Io::load1(a.k, ((int64_t)bh * a.kk + j) * D + i), a.relu);
+#pragma unroll
+  for (int j = 0; j < KMAX; ++j) zs += j < n ? phi_any(x[j], a.relu) : 0.f;
   a.z[gid] = zs;
 }
 
