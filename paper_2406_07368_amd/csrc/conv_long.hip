@@ -236,7 +236,7 @@ static hipError_t launch_cl_t(const ConvLongArgs& a, hipStream_t st) {
   constexpr int LDS_ROWS = (CL_HALO + TOK) * D * (int)sizeof(typename Io::elem), LDS_TAPS = D * KMAX * (int)sizeof(float);
   constexpr int LDS = LDS_ROWS > LDS_TAPS ? LDS_ROWS : LDS_TAPS;
   auto kern = conv_long_kernel<Io, D, KMAX, ASSIGN, TOK>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, LDS);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)((a.L + TOK - 1) / TOK), (unsigned)(a.B * a.H * a.m)), dim3(256), LDS, st, a);
   return hipGetLastError();

@@ -4,7 +4,28 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace linattn {
+
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) once per kernel and device instead of once per launch: the call
+// costs host time that a call made of a dozen short launches cannot hide.  `done` is the call site's own mask of the
+// devices that have been served (a site names one kernel instantiation).
+inline hipError_t set_max_lds_once(const void* kern, int bytes, std::atomic<uint64_t>& done) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = dev >= 0 && dev < 64 ? uint64_t(1) << dev : 0;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
+#define LINATTN_MAX_LDS_ONCE(kern, bytes)                                             \
+  ([&]() -> hipError_t {                                                              \
+    static std::atomic<uint64_t> done_{0};                                            \
+    return ::linattn::set_max_lds_once(reinterpret_cast<const void*>(kern), (bytes), done_); \
+  }())
 
 struct VerifyArgs {
   const void* q;

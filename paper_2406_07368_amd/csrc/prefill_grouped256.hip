@@ -524,7 +524,7 @@ template <int D, int KCM>
 static hipError_t launch_g256(const PrefillArgs& a, hipStream_t st) {
   using G = G256Cfg<D>;
   auto kern = prefill_grouped256_kernel<D, KCM>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, G::TOTAL);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * a.nseg)), dim3(G::NT), G::TOTAL, st, a);
   return hipGetLastError();

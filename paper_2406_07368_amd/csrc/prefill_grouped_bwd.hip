@@ -825,17 +825,13 @@ int grouped_bwd_dw_blocks(int L) { return (L + DW_TOK - 1) / DW_TOK; }
 //          and then nothing from dq;
 //   dkdv   needs dq (the local branch's scalars per token), dsums, and the conv's share in dv.
 template <int D, int GT>
-static hipError_t set_lds(const void* kern) {
-  return hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, BwdCfg<D, GT>::TOTAL);
-}
-template <int D, int GT>
 static hipError_t launch_bwd_part(const GroupedBwdArgs& a, int part, hipStream_t st) {
   using G = BwdCfg<D, GT>;
   const unsigned BH = (unsigned)(a.B * a.H);
   hipError_t e;
   if (part == 0) {
     auto ks = grouped_bwd_gs_kernel<D, GT, true>;
-    if ((e = set_lds<D, GT>(reinterpret_cast<const void*>(ks))) != hipSuccess) return e;
+    if ((e = LINATTN_MAX_LDS_ONCE(ks, G::TOTAL)) != hipSuccess) return e;
     if (a.ng > 1) {
       hipLaunchKernelGGL(ks, dim3((unsigned)(a.ng - 1), BH), dim3(G::NT), G::TOTAL, st, a);
       if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -846,7 +842,7 @@ static hipError_t launch_bwd_part(const GroupedBwdArgs& a, int part, hipStream_t
   }
   if (part == 1) {
     auto kq = grouped_bwd_dq_kernel<D, GT, false>;
-    if ((e = set_lds<D, GT>(reinterpret_cast<const void*>(kq))) != hipSuccess) return e;
+    if ((e = LINATTN_MAX_LDS_ONCE(kq, G::TOTAL)) != hipSuccess) return e;
     hipLaunchKernelGGL(kq, dim3((unsigned)a.ng, BH), dim3(G::NT), G::TOTAL, st, a);
     return hipGetLastError();
   }
@@ -854,8 +850,8 @@ static hipError_t launch_bwd_part(const GroupedBwdArgs& a, int part, hipStream_t
     if (a.ng <= 1) return hipSuccess;                      // one group: nothing before it, nothing to sum
     auto kd = grouped_bwd_dq_kernel<D, GT, true>;
     auto kg = grouped_bwd_gs_kernel<D, GT, false>;
-    if ((e = set_lds<D, GT>(reinterpret_cast<const void*>(kd))) != hipSuccess) return e;
-    if ((e = set_lds<D, GT>(reinterpret_cast<const void*>(kg))) != hipSuccess) return e;
+    if ((e = LINATTN_MAX_LDS_ONCE(kd, G::TOTAL)) != hipSuccess) return e;
+    if ((e = LINATTN_MAX_LDS_ONCE(kg, G::TOTAL)) != hipSuccess) return e;
     if (a.dsums_beside_dq) {
       hipLaunchKernelGGL(kd, dim3((unsigned)(a.ng - 1), BH), dim3(G::NT), G::TOTAL, st, a);
       if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -866,7 +862,7 @@ static hipError_t launch_bwd_part(const GroupedBwdArgs& a, int part, hipStream_t
     return hipGetLastError();
   }
   auto kk = grouped_bwd_dkdv_kernel<D, GT>;
-  if ((e = set_lds<D, GT>(reinterpret_cast<const void*>(kk))) != hipSuccess) return e;
+  if ((e = LINATTN_MAX_LDS_ONCE(kk, G::TOTAL)) != hipSuccess) return e;
   hipLaunchKernelGGL(kk, dim3((unsigned)(2 * a.ng), BH), dim3(G::NT), G::TOTAL, st, a);
   return hipGetLastError();
 }
@@ -877,7 +873,7 @@ static hipError_t launch_bwd_dw(const GroupedBwdArgs& a, hipStream_t st) {
   constexpr int LDS_RED = (256 / D > 2 ? 256 / D - 1 : 1) * D * KMAX * (int)sizeof(float);
   constexpr int LDS = LDS_ROWS > LDS_RED ? LDS_ROWS : LDS_RED;
   auto kern = grouped_bwd_dw_kernel<D, KMAX>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, LDS);
   if (e != hipSuccess) return e;
   if (a.nwb > 0) hipLaunchKernelGGL(kern, dim3((unsigned)a.nwb, (unsigned)(a.B * a.H)), dim3(256), LDS, st, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -924,7 +924,7 @@ static hipError_t launch_ws(const PrefillArgs& a, hipStream_t st) {
   using G = WsCfg<D, C, GROUPED>;
   static_assert(G::FITS, "two row buffers must fit in the 160 KB of LDS");
   auto kern = prefill_mfma_ws_kernel<D, C, KCM, STATE_ONLY, GROUPED>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::TOTAL);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, G::TOTAL);
   if (e != hipSuccess) return e;
   const int segs = STATE_ONLY ? a.nseg - 1 : a.nseg;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * a.m * segs)), dim3(G::NT), G::TOTAL, st, a);

@@ -334,8 +334,7 @@ static hipError_t launch_grouped_one(const PrefillArgs& a, hipStream_t st) {
   constexpr int bytes = GroupedSimtLayout<Io, D, GCT>::TOTAL;
   static_assert(bytes <= 160 * 1024, "LDS");
   auto kern = prefill_grouped_simt_kernel<Io, D, GCT>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, bytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H)), dim3(256), bytes, st, a);
   return hipGetLastError();
@@ -360,8 +359,7 @@ template <typename Io, int D>
 static hipError_t launch_one(const PrefillArgs& a, hipStream_t st) {
   constexpr size_t bytes = sizeof(float) * SimtLayout<D>::TOTAL;
   auto kern = prefill_simt_kernel<Io, D>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, (int)bytes);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H * a.m)), dim3(256), bytes, st, a);
   return hipGetLastError();

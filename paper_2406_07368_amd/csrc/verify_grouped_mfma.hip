@@ -405,7 +405,7 @@ static hipError_t launch_vgm(const VerifyGroupedArgs& a, hipStream_t st) {
   auto kern = verify_grouped_mfma_kernel<D, KCM>;
   constexpr int LDS = (int)sizeof(VgmSmem<D>);
   static_assert(LDS <= 80 * 1024, "two workgroups per compute unit");
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, LDS);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H)), dim3(VgmCfg<D>::NT), LDS, st, a);
   return hipGetLastError();

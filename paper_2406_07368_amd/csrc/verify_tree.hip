@@ -404,7 +404,7 @@ static hipError_t launch_vt(const VerifyTreeArgs& a, hipStream_t st) {
   auto kern = verify_tree_kernel<D, KCM>;
   constexpr int LDS = (int)sizeof(VtSmem<D>);
   static_assert(LDS <= 80 * 1024, "two workgroups per compute unit");
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, LDS);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H)), dim3(VtCfg<D>::NT), LDS, st, a);
   return hipGetLastError();

@@ -225,7 +225,7 @@ static hipError_t launch_vts(const VerifyTreeArgs& a, hipStream_t st) {
   auto kern = verify_tree_simt_kernel<Io, D>;
   constexpr int LDS = (int)sizeof(VtsSmem<D>);
   static_assert(LDS <= 160 * 1024, "LDS");
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  hipError_t e = LINATTN_MAX_LDS_ONCE(kern, LDS);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3((unsigned)(a.B * a.H)), dim3(256), LDS, st, a);
   return hipGetLastError();
