@@ -405,8 +405,7 @@ linattn_status linattn_prefill_grouped_backward(const linattn_desc* desc, int32_
     c.v = dout; c.conv_w = conv_w; c.out = dv;
     c.B = a.B; c.H = a.H; c.L = L; c.Kc = a.Kc; c.sb = a.sb; c.sh = a.sh; c.st = a.st; c.m = 1; c.rev = 1; c.assign = 1;
     e = launch_conv_long(c, true, desc->d, cs);
-    // (with the gradient of the sums behind it on the same stream, that one's event covers the conv as well)
-    if (e == hipSuccess && lane && !a.dsums_beside_dq) e = hipEventRecord(lane->mid, cs);
+    if (e == hipSuccess && lane) e = hipEventRecord(lane->mid, cs);
   }
   if (a.dsums_beside_dq) {
     if (e == hipSuccess) e = hipStreamWaitEvent(cs, lane->sums, 0);
@@ -416,7 +415,8 @@ linattn_status linattn_prefill_grouped_backward(const linattn_desc* desc, int32_
   if (e == hipSuccess) e = launch_grouped_bwd_dw(a, desc->d, cs);            // no tokens: the sums over nothing
   if (e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Dq, stream);
   if (!a.dsums_beside_dq && e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Dsums, ds);
-  if (e == hipSuccess && lane) e = hipStreamWaitEvent(stream, a.dsums_beside_dq ? lane->dsums : lane->mid, 0);
+  if (e == hipSuccess && lane) e = hipStreamWaitEvent(stream, lane->mid, 0);
+  if (e == hipSuccess && a.dsums_beside_dq) e = hipStreamWaitEvent(stream, lane->dsums, 0);
   if (e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Dkdv, stream);
   if (lane) {                                              // joined whatever happened, so that nothing stays forked
     const hipError_t ej = join_side(lane, stream);
