@@ -391,11 +391,6 @@ linattn_status linattn_prefill_grouped_backward(const linattn_desc* desc, int32_
   SideLane* lane = (L > 0) ? side_lane(stream) : nullptr;
   hipStream_t cs = lane ? lane->s : stream;
   a.dsums_beside_dq = lane != nullptr && (int64_t)plan.ng * a.B * a.H <= 64;
-  if (a.dsums_beside_dq) {                                // (not in a captured graph: replays of the wider graph were slower)
-    hipStreamCaptureStatus cstat = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(stream, &cstat) != hipSuccess) { (void)hipGetLastError(); cstat = hipStreamCaptureStatusNone; }
-    if (cstat != hipStreamCaptureStatusNone) a.dsums_beside_dq = 0;
-  }
   hipStream_t ds = a.dsums_beside_dq ? cs : stream;       // where the gradient of the sums goes
   if (lane) e = fork_side(lane, stream);
   if (e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Sums, stream);
