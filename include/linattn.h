@@ -225,8 +225,7 @@ linattn_status linattn_prefill_grouped(const linattn_desc *desc, int32_t L, floa
  * The result does not depend on the launch configuration (no atomics: fixed
  * summation order).
  * Asynchronous on hip_stream; every argument is validated before anything is
- * enqueued.  Part of the work (the conv's share of dv, the conv-weight sums, in small
- * calls also the gradient of the group sums) runs on
+ * enqueued.  Part of the work (the conv's share of dv, the conv-weight sums) runs on
  * a second stream that the library creates at the first such call of a host thread
  * on a device (default priority; it is forked from hip_stream and joined back into
  * it with events inside the call, so work enqueued on hip_stream after the call

@@ -118,7 +118,7 @@ PrefillPlan plan_prefill(const linattn_desc* d, int32_t L, bool grouped = false)
 // cannot be made, the work simply stays on the caller's stream, in the same order).  Default priority.
 struct SideLane {
   hipStream_t s = nullptr;
-  hipEvent_t fork = nullptr, mid = nullptr, sums = nullptr, dsums = nullptr, join = nullptr;
+  hipEvent_t fork = nullptr, mid = nullptr, join = nullptr;
   bool ok = false;
 };
 SideLane* side_lane(hipStream_t caller) {
@@ -135,14 +135,10 @@ SideLane* side_lane(hipStream_t caller) {
   bool made = hipStreamCreateWithFlags(&l.s, hipStreamNonBlocking) == hipSuccess &&
               hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) == hipSuccess &&
               hipEventCreateWithFlags(&l.mid, hipEventDisableTiming) == hipSuccess &&
-              hipEventCreateWithFlags(&l.sums, hipEventDisableTiming) == hipSuccess &&
-              hipEventCreateWithFlags(&l.dsums, hipEventDisableTiming) == hipSuccess &&
               hipEventCreateWithFlags(&l.join, hipEventDisableTiming) == hipSuccess;
   if (!made) {
     (void)hipGetLastError();
     if (l.join) (void)hipEventDestroy(l.join);
-    if (l.dsums) (void)hipEventDestroy(l.dsums);
-    if (l.sums) (void)hipEventDestroy(l.sums);
     if (l.mid) (void)hipEventDestroy(l.mid);
     if (l.fork) (void)hipEventDestroy(l.fork);
     if (l.s) (void)hipStreamDestroy(l.s);
@@ -379,22 +375,13 @@ linattn_status linattn_prefill_grouped_backward(const linattn_desc* desc, int32_
   a.alpha = alpha;
   a.sb = desc->stride_b; a.sh = desc->stride_h; a.st = desc->stride_t;
   a.group = desc->chunk; a.ng = plan.ng; a.nwb = plan.nwb;
-  // Two streams.  The library's own takes the conv's share of dv (the same taps met from the other side,
-  // dv[s] = sum_j w[j] dout[s + j]; written first, the last kernel adds the rest to it) and the conv-weight sums, which
-  // need nothing from the other kernels; the last kernel waits for the first, the end of the call for the second.
-  // When the kernels of the call are too small to fill the chip (at most 64 workgroups each), the gradient of the sums
-  // goes there as well, between the two: with its own short launch for the grouped branch's scalars it needs only the
-  // sums and runs beside dq instead of behind it (with kernels that fill the chip the two would only take turns, and
-  // the conv-weight sums behind them would end later: measured 10 % slower).  Without a second stream the same
-  // launches go to the caller's stream in an order that respects all of that.
+  // The conv's share of dv (the same taps met from the other side, dv[s] = sum_j w[j] dout[s + j]) is written first
+  // and the conv-weight sums need nothing from the other kernels: both run on the side stream; the kernel that adds
+  // the rest of dv waits for the first, the end of the call for the second.
   hipError_t e = hipSuccess;
   SideLane* lane = (L > 0) ? side_lane(stream) : nullptr;
   hipStream_t cs = lane ? lane->s : stream;
-  a.dsums_beside_dq = lane != nullptr && (int64_t)plan.ng * a.B * a.H <= 64;
-  hipStream_t ds = a.dsums_beside_dq ? cs : stream;       // where the gradient of the sums goes
   if (lane) e = fork_side(lane, stream);
-  if (e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Sums, stream);
-  if (e == hipSuccess && a.dsums_beside_dq) e = hipEventRecord(lane->sums, stream);
   if (e == hipSuccess && L > 0) {
     ConvLongArgs c{};
     c.v = dout; c.conv_w = conv_w; c.out = dv;
@@ -402,17 +389,8 @@ linattn_status linattn_prefill_grouped_backward(const linattn_desc* desc, int32_
     e = launch_conv_long(c, true, desc->d, cs);
     if (e == hipSuccess && lane) e = hipEventRecord(lane->mid, cs);
   }
-  if (a.dsums_beside_dq) {
-    if (e == hipSuccess) e = hipStreamWaitEvent(cs, lane->sums, 0);
-    if (e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Dsums, ds);
-    if (e == hipSuccess) e = hipEventRecord(lane->dsums, cs);
-  }
   if (e == hipSuccess) e = launch_grouped_bwd_dw(a, desc->d, cs);            // no tokens: the sums over nothing
-  if (e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Dq, stream);
-  if (!a.dsums_beside_dq && e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Dsums, ds);
-  if (e == hipSuccess && lane) e = hipStreamWaitEvent(stream, lane->mid, 0);
-  if (e == hipSuccess && a.dsums_beside_dq) e = hipStreamWaitEvent(stream, lane->dsums, 0);
-  if (e == hipSuccess) e = launch_grouped_bwd_part(a, desc->d, GroupedBwdPart::Dkdv, stream);
+  if (e == hipSuccess) e = launch_grouped_bwd_core(a, desc->d, stream, lane ? lane->mid : nullptr);
   if (lane) {                                              // joined whatever happened, so that nothing stays forked
     const hipError_t ej = join_side(lane, stream);
     if (e == hipSuccess) e = ej;

@@ -158,8 +158,6 @@ struct GroupedBwdArgs {
   int64_t sb, sh, st;
   int group, ng;            // tokens per group (64 or 256), groups per sequence
   int nwb;                  // token blocks of the conv-weight pass per sequence
-  int dsums_beside_dq;      // the gradient of the sums runs beside dq (on a stream of its own): the grouped branch's two
-                            // scalars per token then come from a short launch ahead of it, else from dq itself
 };
 
 // verify.hip
@@ -194,12 +192,10 @@ hipError_t launch_conv_long(const ConvLongArgs& a, bool bf16, int d, hipStream_t
 
 // prefill_grouped_bwd.hip : gradient of the three-branch form (bf16 rows, groups of 64 or 256)
 int grouped_bwd_dw_blocks(int L);
-// ... in parts, so that the caller can spread them over two streams.  Sums: every group's own sums and their prefix.
-// Dq: needs the sums.  Dsums: the grouped branch's scalars per token, the gradient of the sums and its suffix sum;
-// needs the sums, nothing from dq.  Dkdv: needs dq and dsums, and adds dv to what dv holds (the conv's share is written
-// first).  And the conv-weight sums, which need nothing from the others.
-enum class GroupedBwdPart { Sums = 0, Dq = 1, Dsums = 2, Dkdv = 3 };
-hipError_t launch_grouped_bwd_part(const GroupedBwdArgs& a, int d, GroupedBwdPart part, hipStream_t st);
+// ... in two parts that need nothing from each other: everything but the conv-weight sums (dv is added to what it
+// holds: the conv's share is written first; `before_dkdv`, if not null, is waited for ahead of the kernel that does
+// so), and the conv-weight sums
+hipError_t launch_grouped_bwd_core(const GroupedBwdArgs& a, int d, hipStream_t st, hipEvent_t before_dkdv);
 hipError_t launch_grouped_bwd_dw(const GroupedBwdArgs& a, int d, hipStream_t st);
 
 // prefill_mfma.hip : launch plan of the bf16 prefill (segments, prefix sum over segment states)

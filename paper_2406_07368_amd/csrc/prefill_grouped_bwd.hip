@@ -184,10 +184,7 @@ __device__ __forceinline__ void row_in_acc_order(const uint16_t* row, int ft, in
 }  // namespace
 
 // ---- dq and the per-token scalars ---------------------------------------------------------------------------------
-// SCALARS: only the two per-token scalars that the gradient of the sums needs (alpha / den and d den), for the groups
-// that have one before them, by the grouped branch's own code: a short launch whose result lets that gradient be
-// summed beside the full launch instead of behind it.
-template <int D, int GT, bool SCALARS = false>
+template <int D, int GT>
 __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a) {
   using G = BwdCfg<D, GT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -200,7 +197,7 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
   const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, l32 = lane & 31, hi = lane >> 5;
-  const int g = SCALARS ? blockIdx.x + 1 : blockIdx.x, bh = blockIdx.y;
+  const int g = blockIdx.x, bh = blockIdx.y;
   const int b = bh / a.H, h = bh % a.H;
   const int tok0 = g * GT;
   const int nt = (a.L - tok0) < GT ? (a.L - tok0) : GT;
@@ -229,14 +226,10 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
     const uint16_t* dp = gdo + (int64_t)(tok0 + qrow) * a.st + 8 * hi;
 #pragma unroll
     for (int ks = 0; ks < G::KSD; ++ks) {
-      if (!SCALARS) qraw[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
+      qraw[ks] = *reinterpret_cast<const u32x4*>(qp + 16 * ks);
       draw[ks] = *reinterpret_cast<const u32x4*>(dp + 16 * ks);
     }
   }
-  float inv_mass = 0.f, pbar = 0.f, mlog2 = 0.f;
-  // dqa[ft][r] = dQ[query 32 qtile + l32][feature 32ft + 8(r/4) + 4hi + r%4]
-  f32x16 dqa[G::CT];
-  if constexpr (!SCALARS) {
   load_rows2<D, GT>(gk, gv, a.st, tok0, nt, Kl, Vl, tid);
   __syncthreads();
 
@@ -282,11 +275,13 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
   }
   mass += __shfl_xor(mass, 32);
   racc += __shfl_xor(racc, 32);
-  inv_mass = 1.f / mass;                                   // the token itself is always seen: mass >= 1
-  pbar = racc * inv_mass;
-  mlog2 = mtop * to_log2;
+  const float inv_mass = 1.f / mass;                       // the token itself is always seen: mass >= 1
+  const float pbar = racc * inv_mass;
+  const float mlog2 = mtop * to_log2;
 
   // ---- pass 2: ds = p (dp - pbar) / sqrt(d), dQ^T += K^T ds^T --------------------------------------------------
+  // dqa[ft][r] = dQ[query 32 qtile + l32][feature 32ft + 8(r/4) + 4hi + r%4]
+  f32x16 dqa[G::CT];
 #pragma unroll
   for (int ft = 0; ft < G::CT; ++ft)
 #pragma unroll
@@ -318,7 +313,6 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
     }
   }
   __syncthreads();                                         // every wave is done with the key and value rows
-  }  // !SCALARS
 
   // ---- the grouped branch: S_g -> LDS as bf16 [feature][channel], z_g -> LDS ------------------------------------
   load_slot<D, GT>(slot, Sl, zl, tid);
@@ -356,21 +350,6 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
   const float gden = dz + a.eps;
   const float fscale = gden != 0.f ? a.alpha / gden : 0.f; // nothing before the group: no branch
   const float dden = gden != 0.f ? -fscale * nd / gden : 0.f;
-  // the per-token scalars for the kernels that follow: the local branch's from the full launch, the grouped branch's
-  // from the short one
-  if (hi == 0 && qt < nt) {
-    const size_t n = (size_t)a.B * a.H * a.L, e = (size_t)bh * a.L + tok0 + qt;
-    if (SCALARS || !a.dsums_beside_dq) {
-      a.stats[3 * n + e] = fscale;
-      a.stats[4 * n + e] = dden;
-    }
-    if (!SCALARS) {
-      a.stats[e] = mlog2;
-      a.stats[n + e] = inv_mass;
-      a.stats[2 * n + e] = pbar;
-    }
-  }
-  if constexpr (SCALARS) return;
 #pragma unroll
   for (int ft = 0; ft < G::CT; ++ft) {
     float qv[16];
@@ -380,6 +359,15 @@ __global__ __launch_bounds__(GT * 2) void grouped_bwd_dq_kernel(GroupedBwdArgs a
       const int f = 32 * ft + 8 * (r >> 2) + 4 * hi + (r & 3);
       dqa[ft][r] = fmaf(fmaf(fscale, wt[ft][r], zl[f] * dden), dphi_f(qv[r], a.relu), dqa[ft][r]);
     }
+  }
+  // the per-token scalars for the kernels that follow
+  if (hi == 0 && qt < nt) {
+    const size_t n = (size_t)a.B * a.H * a.L, e = (size_t)bh * a.L + tok0 + qt;
+    a.stats[e] = mlog2;
+    a.stats[n + e] = inv_mass;
+    a.stats[2 * n + e] = pbar;
+    a.stats[3 * n + e] = fscale;
+    a.stats[4 * n + e] = dden;
   }
   __syncthreads();                                         // every wave is done with the state operand
   store_rows<D, GT>(dqa, Ol, gdq, a.st, tok0, nt, tid, qtile, l32, hi);
@@ -816,54 +804,39 @@ __global__ __launch_bounds__(256) void grouped_bwd_dw_reduce_kernel(const float*
 
 int grouped_bwd_dw_blocks(int L) { return (L + DW_TOK - 1) / DW_TOK; }
 
-// The launches of the gradient in four parts, so that the caller can put them on two streams:
-//   sums   every group's own sums of phi(K)^T V and phi(K), then the prefix sum (which also writes the zeros before
-//          group 0): what dq and dsums read;
-//   dq     needs sums;
-//   dsums  what the queries of every group add to the gradient of the sums before it, and the suffix sum; needs sums
-//          and the grouped branch's two scalars per token: from dq, or (dsums_beside_dq) from a short launch of its own,
-//          and then nothing from dq;
-//   dkdv   needs dq (the local branch's scalars per token), dsums, and the conv's share in dv.
 template <int D, int GT>
-static hipError_t launch_bwd_part(const GroupedBwdArgs& a, int part, hipStream_t st) {
+static hipError_t launch_bwd_core(const GroupedBwdArgs& a, hipStream_t st, hipEvent_t before_dkdv) {
   using G = BwdCfg<D, GT>;
-  const unsigned BH = (unsigned)(a.B * a.H);
+  const int BH = a.B * a.H;
   hipError_t e;
-  if (part == 0) {
-    auto ks = grouped_bwd_gs_kernel<D, GT, true>;
-    if ((e = LINATTN_MAX_LDS_ONCE(ks, G::TOTAL)) != hipSuccess) return e;
-    if (a.ng > 1) {
-      hipLaunchKernelGGL(ks, dim3((unsigned)(a.ng - 1), BH), dim3(G::NT), G::TOTAL, st, a);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
+  auto kq = grouped_bwd_dq_kernel<D, GT>;
+  auto kg = grouped_bwd_gs_kernel<D, GT, false>;
+  auto ks = grouped_bwd_gs_kernel<D, GT, true>;
+  auto kk = grouped_bwd_dkdv_kernel<D, GT>;
+  if ((e = LINATTN_MAX_LDS_ONCE(kq, G::TOTAL)) != hipSuccess) return e;
+  if ((e = LINATTN_MAX_LDS_ONCE(kg, G::TOTAL)) != hipSuccess) return e;
+  if ((e = LINATTN_MAX_LDS_ONCE(kk, G::TOTAL)) != hipSuccess) return e;
+  if ((e = LINATTN_MAX_LDS_ONCE(ks, G::TOTAL)) != hipSuccess) return e;
+  // the sums before every group: every group's own sums, then the prefix sum (which also writes the zeros before group 0)
+  if (a.ng > 1) {
+    hipLaunchKernelGGL(ks, dim3((unsigned)(a.ng - 1), (unsigned)BH), dim3(G::NT), G::TOTAL, st, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {
     PrefillArgs f{};
     f.ws = a.P; f.B = a.B; f.H = a.H; f.m = 1; f.nseg = a.ng;
-    return launch_segment_scan(f, D, st);
+    if ((e = launch_segment_scan(f, D, st)) != hipSuccess) return e;
   }
-  if (part == 1) {
-    auto kq = grouped_bwd_dq_kernel<D, GT, false>;
-    if ((e = LINATTN_MAX_LDS_ONCE(kq, G::TOTAL)) != hipSuccess) return e;
-    hipLaunchKernelGGL(kq, dim3((unsigned)a.ng, BH), dim3(G::NT), G::TOTAL, st, a);
-    return hipGetLastError();
-  }
-  if (part == 2) {
-    if (a.ng <= 1) return hipSuccess;                      // one group: nothing before it, nothing to sum
-    auto kd = grouped_bwd_dq_kernel<D, GT, true>;
-    auto kg = grouped_bwd_gs_kernel<D, GT, false>;
-    if ((e = LINATTN_MAX_LDS_ONCE(kd, G::TOTAL)) != hipSuccess) return e;
-    if ((e = LINATTN_MAX_LDS_ONCE(kg, G::TOTAL)) != hipSuccess) return e;
-    if (a.dsums_beside_dq) {
-      hipLaunchKernelGGL(kd, dim3((unsigned)(a.ng - 1), BH), dim3(G::NT), G::TOTAL, st, a);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(kg, dim3((unsigned)(a.ng - 1), BH), dim3(G::NT), G::TOTAL, st, a);
+  hipLaunchKernelGGL(kq, dim3((unsigned)a.ng, (unsigned)BH), dim3(G::NT), G::TOTAL, st, a);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (a.ng > 1) {
+    hipLaunchKernelGGL(kg, dim3((unsigned)(a.ng - 1), (unsigned)BH), dim3(G::NT), G::TOTAL, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(grouped_bwd_suffix_kernel, dim3((unsigned)((G::SLOT + 255) / 256), BH), dim3(256), 0, st, a, (int)G::SLOT);
-    return hipGetLastError();
+    hipLaunchKernelGGL(grouped_bwd_suffix_kernel, dim3((unsigned)((G::SLOT + 255) / 256), (unsigned)BH), dim3(256), 0, st, a, (int)G::SLOT);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  auto kk = grouped_bwd_dkdv_kernel<D, GT>;
-  if ((e = LINATTN_MAX_LDS_ONCE(kk, G::TOTAL)) != hipSuccess) return e;
-  hipLaunchKernelGGL(kk, dim3((unsigned)(2 * a.ng), BH), dim3(G::NT), G::TOTAL, st, a);
+  if (before_dkdv && (e = hipStreamWaitEvent(st, before_dkdv, 0)) != hipSuccess) return e;
+  hipLaunchKernelGGL(kk, dim3((unsigned)(2 * a.ng), (unsigned)BH), dim3(G::NT), G::TOTAL, st, a);
   return hipGetLastError();
 }
 
@@ -897,11 +870,10 @@ static hipError_t launch_bwd_dw(const GroupedBwdArgs& a, hipStream_t st) {
 }
 
 // Everything but the conv-weight sums, in order.
-hipError_t launch_grouped_bwd_part(const GroupedBwdArgs& a, int d, GroupedBwdPart part, hipStream_t st) {
+hipError_t launch_grouped_bwd_core(const GroupedBwdArgs& a, int d, hipStream_t st, hipEvent_t before_dkdv) {
   if (a.L <= 0) return hipSuccess;
-  const int p = (int)part;
-  if (d == 128) return a.group == 256 ? launch_bwd_part<128, 256>(a, p, st) : launch_bwd_part<128, 64>(a, p, st);
-  return a.group == 256 ? launch_bwd_part<64, 256>(a, p, st) : launch_bwd_part<64, 64>(a, p, st);
+  if (d == 128) return a.group == 256 ? launch_bwd_core<128, 256>(a, st, before_dkdv) : launch_bwd_core<128, 64>(a, st, before_dkdv);
+  return a.group == 256 ? launch_bwd_core<64, 256>(a, st, before_dkdv) : launch_bwd_core<64, 64>(a, st, before_dkdv);
 }
 
 // The conv-weight sums (no tokens: zeros).
