@@ -46,7 +46,7 @@ def compare_state(got, want, io, what, fill_in):
 @pytest.mark.parametrize("io", ["bf16", "f32"])
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("kk,Kc,fill", [(1, 3, (0, 17)), (1, 1, (63, 62)), (2, 3, (62, 10)), (3, 2, (63, 40)), (4, 3, (30, 61)), (5, 5, (59, 60)), (8, 2, (0, 63)),
-                                        (13, 8, (50, 55)), (16, 3, (47, 48)), (16, 4, (63, 5))])
+                                        (13, 8, (50, 55)), (16, 3, (47, 48)), (16, 4, (63, 5)), (6, 1, (20, 63))])
 def test_verify_grouped_matches_oracle(io, d, kk, Kc, fill):
     """Groups that stay open, groups that are completed by the kept drafts, drafts beyond the end of the group.
     bf16 with four or more drafts runs on the matrix cores, everything else on the vector ALUs."""
